@@ -1,0 +1,222 @@
+"""ctypes access to the CPU oracle (oracle/rk_oracle.cpp).
+
+TEST INFRASTRUCTURE ONLY.  May be imported by tests/, by the smoke check and
+by the CPU-baseline leg of the benchmark; never by the GPU library or its
+Python binding.  Imports nothing from the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rk_oracle.cpp")
+_HDR = os.path.join(_HERE, "rk_oracle.h")
+_LIB = os.path.join(_HERE, "librk_oracle.so")
+
+NO_PLAN = 0xFFFFFFFF
+N_TERMS = 24
+TERMS = ("n", "m", "a", "Tf_mb", "T_fwd", "T_bwd", "V_dp", "V_tp", "V_pp", "T_dp", "T_tp",
+         "T_pp", "T_cc", "Psi", "T_opt", "T_off", "T_oo", "T_iter", "thr", "M_gpu", "H_host",
+         "B_dp", "B_tp", "B_pp")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (strict IEEE: no contraction, no fast-math)."""
+    stale = (not os.path.exists(_LIB)
+             or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_HDR)))
+    if force or stale:
+        cmd = ["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
+               "-shared", "-pthread", "-Wall", "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True, cwd=_HERE)
+    return _LIB
+
+
+class _Env(C.Structure):
+    _fields_ = [("B_intra", C.c_float), ("B_inter", C.c_float), ("B_pcie", C.c_float),
+                ("gpu_mem_cap", C.c_float), ("gpus_per_node", C.c_uint32)]
+
+
+class _Grid(C.Structure):
+    _fields_ = [("n_cpu", C.c_uint32), ("cpu_levels", C.c_void_p), ("cpu_mode", C.c_uint32),
+                ("n_mem", C.c_uint32), ("mem_levels_gb", C.c_void_p), ("mem_mode", C.c_uint32)]
+
+
+class _Bounds(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("g_max", "tp_max", "pp_max", "zero_mask", "gc_mask", "off_mask")]
+
+
+class _Table(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("triple_off", "triples", "seg_off", "seg_g", "seg_first")]
+
+
+ASSIGN_DTYPE = np.dtype([("g", np.uint32), ("c", np.uint32), ("mem_gb", np.float32),
+                         ("plan", np.uint32), ("thr", np.float32)])
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.ork_f_overlap.restype = C.c_double
+        _lib.ork_f_overlap.argtypes = [C.c_double] * 3
+        _lib.ork_eval_one.restype = C.c_uint32
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _env(env):
+    return _Env(env.B_intra, env.B_inter, env.B_pcie, env.gpu_mem_cap, env.gpus_per_node)
+
+
+def _bounds(b):
+    return _Bounds(b.g_max, b.tp_max, b.pp_max, b.zero_mask, b.gc_mask, b.off_mask)
+
+
+class _GridHolder:
+    def __init__(self, grid):
+        self.cpu = np.ascontiguousarray(grid.cpu_levels, dtype=np.uint32)
+        self.mem = np.ascontiguousarray(grid.mem_levels_gb, dtype=np.float32)
+        self.c = _Grid(len(self.cpu), _p(self.cpu), grid.cpu_mode, len(self.mem), _p(self.mem), grid.mem_mode)
+        self.rows = len(self.cpu) * len(self.mem)
+
+
+class Table:
+    """Plan table produced by enumerate(); numpy arrays."""
+
+    def __init__(self, triple_off, triples, seg_off, seg_g, seg_first):
+        self.triple_off, self.triples = triple_off, triples
+        self.seg_off, self.seg_g, self.seg_first = seg_off, seg_g, seg_first
+        self.c = _Table(_p(triple_off), _p(triples), _p(seg_off), _p(seg_g), _p(seg_first))
+
+    @property
+    def n_jobs(self):
+        return len(self.triple_off) - 1
+
+    def n_candidates(self, rows, jb=0, je=None):
+        je = self.n_jobs if je is None else je
+        return 16 * rows * int(self.triple_off[je] - self.triple_off[jb])
+
+    def n_segments(self, rows, jb=0, je=None):
+        je = self.n_jobs if je is None else je
+        return rows * int(self.seg_off[je] - self.seg_off[jb])
+
+
+def f_overlap(k, x, y):
+    return lib().ork_f_overlap(float(k), float(x), float(y))
+
+
+def enumerate_plans(ints, bounds) -> Table:
+    ints = np.ascontiguousarray(ints, dtype=np.uint32)
+    J = ints.shape[0]
+    nt, ns = C.c_uint64(0), C.c_uint64(0)
+    b = _bounds(bounds)
+    lib().ork_enumerate(C.c_uint32(J), _p(ints), C.byref(b), None, None, C.c_uint64(0), None, None, None,
+                        C.c_uint64(0), C.byref(nt), C.byref(ns))
+    triple_off = np.zeros(J + 1, np.uint32)
+    triples = np.zeros((max(nt.value, 1), 3), np.uint32)
+    seg_off = np.zeros(J + 1, np.uint32)
+    seg_g = np.zeros(max(ns.value, 1), np.uint32)
+    seg_first = np.zeros(max(ns.value, 1), np.uint32)
+    rc = lib().ork_enumerate(C.c_uint32(J), _p(ints), C.byref(b), _p(triple_off), _p(triples),
+                             C.c_uint64(nt.value), _p(seg_off), _p(seg_g), _p(seg_first),
+                             C.c_uint64(ns.value), C.byref(nt), C.byref(ns))
+    assert rc == 0
+    return Table(triple_off, triples[:nt.value], seg_off, seg_g[:ns.value], seg_first[:ns.value])
+
+
+def eval_one(coef_row, ints_row, bounds, env, d, t, p, z, gc, off, c, host_bytes):
+    """One candidate -> (reason bits, dict of every intermediate term)."""
+    cf = np.ascontiguousarray(coef_row, dtype=np.float32)
+    it = np.ascontiguousarray(ints_row, dtype=np.uint32)
+    terms = np.zeros(N_TERMS, np.float64)
+    b, e = _bounds(bounds), _env(env)
+    reason = lib().ork_eval_one(_p(cf), _p(it), C.byref(b), C.byref(e), C.c_uint32(d), C.c_uint32(t),
+                                C.c_uint32(p), C.c_uint32(z), C.c_uint32(gc), C.c_uint32(off),
+                                C.c_uint32(c), C.c_float(host_bytes), _p(terms))
+    return int(reason), dict(zip(TERMS, terms.tolist()))
+
+
+def eval_jobs(coef, ints, bounds, table, grid, env, jb=0, je=None, want_reason=True, n_threads=1):
+    coef = np.ascontiguousarray(coef, dtype=np.float32)
+    ints = np.ascontiguousarray(ints, dtype=np.uint32)
+    J = coef.shape[0]
+    je = J if je is None else je
+    gh = _GridHolder(grid)
+    n = table.n_candidates(gh.rows, jb, je)
+    thr = np.zeros(n, np.float64)
+    reason = np.zeros(n, np.uint8) if want_reason else None
+    b, e = _bounds(bounds), _env(env)
+    rc = lib().ork_eval_jobs(C.c_uint32(J), _p(coef), _p(ints), C.byref(b), C.byref(table.c), C.byref(gh.c),
+                             C.byref(e), C.c_uint32(jb), C.c_uint32(je), _p(thr), _p(reason),
+                             C.c_uint32(n_threads))
+    assert rc == 0
+    return thr, reason
+
+
+def best_plan(table, grid, thr, jb=0, je=None):
+    """Segmented argmax; dtype of thr (float64 or float32) selects the precision."""
+    je = table.n_jobs if je is None else je
+    gh = _GridHolder(grid)
+    n = table.n_segments(gh.rows, jb, je)
+    thr = np.ascontiguousarray(thr)
+    assert thr.dtype in (np.float32, np.float64)
+    assert thr.size == table.n_candidates(gh.rows, jb, je)
+    best_thr = np.zeros(n, thr.dtype)
+    best_idx = np.zeros(n, np.uint32)
+    fn = lib().ork_best_plan_f64 if thr.dtype == np.float64 else lib().ork_best_plan_f32
+    rc = fn(C.byref(table.c), C.byref(gh.c), C.c_uint32(jb), C.c_uint32(je), _p(thr), _p(best_thr), _p(best_idx))
+    assert rc == 0
+    return best_thr, best_idx
+
+
+def curves(table, grid, best_thr, best_idx, jb=0, je=None):
+    je = table.n_jobs if je is None else je
+    gh = _GridHolder(grid)
+    best_thr = np.ascontiguousarray(best_thr, dtype=np.float32)
+    best_idx = np.ascontiguousarray(best_idx, dtype=np.uint32)
+    n = table.n_segments(gh.rows, jb, je)
+    assert best_thr.size == n and best_idx.size == n
+    ct, cp, cg = np.zeros(n, np.float32), np.zeros(n, np.uint32), np.zeros(n, np.uint32)
+    rc = lib().ork_curves_f32(C.byref(table.c), C.byref(gh.c), C.c_uint32(jb), C.c_uint32(je),
+                              _p(best_thr), _p(best_idx), _p(ct), _p(cp), _p(cg))
+    assert rc == 0
+    return ct, cp, cg
+
+
+def greedy(ref_thr, table, grid, cluster, best_thr, best_idx, curve_thr):
+    gh = _GridHolder(grid)
+    J = table.n_jobs
+    ref_thr = np.ascontiguousarray(ref_thr, dtype=np.float32)
+    best_thr = np.ascontiguousarray(best_thr, dtype=np.float32)
+    best_idx = np.ascontiguousarray(best_idx, dtype=np.uint32)
+    curve_thr = np.ascontiguousarray(curve_thr, dtype=np.float32)
+    assign = np.zeros(J, ASSIGN_DTYPE)
+    total, gap = C.c_double(0), C.c_double(0)
+    rc = lib().ork_greedy_f32(C.c_uint32(J), _p(ref_thr), C.byref(table.c), C.byref(gh.c),
+                              C.c_uint32(cluster.G), C.c_uint32(cluster.C), C.c_float(cluster.host_mem_gb),
+                              _p(best_thr), _p(best_idx), _p(curve_thr), _p(assign),
+                              C.byref(total), C.byref(gap))
+    assert rc == 0
+    return assign, total.value, gap.value
+
+
+def schedule_round(wl, n_threads=1):
+    """The whole path on a workload: enumerate -> evaluate (float64) -> argmax
+    (float64) -> round to float32 -> curves -> greedy.  Returns a dict."""
+    table = enumerate_plans(wl.ints, wl.bounds)
+    thr, reason = eval_jobs(wl.coef, wl.ints, wl.bounds, table, wl.grid, wl.env, n_threads=n_threads)
+    bt64, bp = best_plan(table, wl.grid, thr)
+    bt = bt64.astype(np.float32)
+    ct, cp, cg = curves(table, wl.grid, bt, bp)
+    assign, total, gap = greedy(wl.coef[:, 16], table, wl.grid, wl.cluster, bt, bp, ct)
+    return dict(table=table, thr=thr, reason=reason, best_thr64=bt64, best_thr=bt, best_plan=bp,
+                curve_thr=ct, curve_plan=cp, curve_g=cg, assign=assign, total=total, min_gap=gap)

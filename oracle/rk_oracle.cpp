@@ -1,0 +1,487 @@
+/*
+ * CPU oracle (test infrastructure, see rk_oracle.h).  Written from the
+ * paper's Sec. 4 (performance model) and Sec. 5.2 (resource sensitivity
+ * curves, best-plan search, slope-ordered greedy).  Every function states the
+ * passage it follows and how it is pinned by the CPU test-suite.
+ *
+ * Build: g++ -O2 -std=c++17 -ffp-contract=off -fPIC -shared -pthread
+ */
+#include "rk_oracle.h"
+
+#include <cmath>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+namespace {
+
+enum { P_BYTES, SEQ, HIDDEN, ELEM_BYTES, T_FWD_SAMPLE, K_BWD, K_SYNC, K_OPT, K_OPT_OFF,
+       K_OFF, K_SWAP, K_CONST, MEM_STATE, MEM_ACT, MEM_ACT_GC, MEM_CONST, REF_THR, N_COEF };
+enum { LAYERS, GBATCH, MBATCH, N_INT };
+
+/* order of the terms[] array returned by ork_eval_one */
+enum { X_N, X_M, X_A, X_TF_MB, X_T_FWD, X_T_BWD, X_V_DP, X_V_TP, X_V_PP, X_T_DP, X_T_TP,
+       X_T_PP, X_T_CC, X_PSI, X_T_OPT, X_T_OFF, X_T_OO, X_T_ITER, X_THR, X_M_GPU, X_H_HOST,
+       X_B_DP, X_B_TP, X_B_PP };
+
+const float GIB = 1073741824.0f;
+
+/* Structural validity of a plan on top of the (d,t,p) partitioning rules:
+ * the option must be allowed by the bounds, and offloading needs partitioned
+ * gradients (Sec. 4.2 "Modeling T_off": ZeRO-Offload moves *partitioned*
+ * gradients), i.e. ZeRO stage >= 2. */
+bool option_valid(const ork_bounds *b, uint32_t z, uint32_t gc, uint32_t off) {
+    if (!((b->zero_mask >> z) & 1u)) return false;
+    if (!((b->gc_mask >> gc) & 1u)) return false;
+    if (!((b->off_mask >> off) & 1u)) return false;
+    if (off && z < 2) return false;
+    return true;
+}
+
+/* Bottleneck-bandwidth rule of Sec. 4.1 "Modeling T_comm" under a packed
+ * placement with tensor-parallel ranks adjacent, then data-parallel, then
+ * pipeline stages.  A job inside one node uses the intra-node links for
+ * everything.  A job over several nodes keeps a communication group on the
+ * intra-node links only when whole groups tile a node. */
+void bandwidths(const ork_env *env, uint32_t d, uint32_t t, uint32_t p,
+                double *B_dp, double *B_tp, double *B_pp) {
+    const uint32_t N = env->gpus_per_node;
+    const uint64_t g = (uint64_t)d * t * p;
+    const double bi = env->B_intra, bx = env->B_inter;
+    if (g <= N) { *B_dp = bi; *B_tp = bi; *B_pp = bi; return; }
+    *B_tp = (N % t == 0) ? bi : bx;
+    *B_dp = (N % ((uint64_t)t * d) == 0) ? bi : bx;
+    *B_pp = bx;
+}
+
+/* GPU and host memory of a plan, float32, one rounding per operation, in
+ * exactly this order.  The paper leaves the estimate to the training
+ * frameworks (Sec. 6); this is the mixed-precision Adam accounting of the
+ * ZeRO paper it cites: 16 bytes of state per 2-byte parameter, partitioned
+ * by stage, plus activations and a constant.
+ *   Psi   = P_bytes / (t*p)
+ *   kappa = 8 | 2+6/d | 1+7/d | 8/d   for ZeRO 0..3 without offload
+ *           1 | 1/d                   for ZeRO 2,3 with offload
+ *   S     = (mem_state*kappa)*Psi
+ *   tok   = (mu*seq)*hidden ; lay = layers/p ; w = min(p, b/(d*mu))
+ *   base  = ((tok*lay)/t)*w
+ *   A     = mem_act*base                              without checkpointing
+ *           mem_act_gc*base + (mem_act*tok)/t         with checkpointing
+ *   M_gpu = (S + A) + mem_const
+ *   H_host= ((mem_state*(7/d))*Psi)*g  with offload, else 0
+ */
+void memory_f32(const float *cf, const uint32_t *in, uint32_t d, uint32_t t, uint32_t p,
+                uint32_t z, uint32_t gc, uint32_t off, float *M_gpu, float *H_host) {
+    const float fd = (float)d, ft = (float)t;
+    const float tp = (float)(t * p);
+    const float Psi = cf[P_BYTES] / tp;
+    float kappa;
+    if (off) {
+        kappa = (z == 2) ? 1.0f : 1.0f / fd;
+    } else if (z == 0) {
+        kappa = 8.0f;
+    } else if (z == 1) {
+        float q = 6.0f / fd; kappa = 2.0f + q;
+    } else if (z == 2) {
+        float q = 7.0f / fd; kappa = 1.0f + q;
+    } else {
+        kappa = 8.0f / fd;
+    }
+    float sk = cf[MEM_STATE] * kappa;
+    const float S = sk * Psi;
+    const uint32_t mu = in[MBATCH];
+    const uint32_t n = in[GBATCH] / (d * mu);
+    const uint32_t w = (p < n) ? p : n;
+    float tok = (float)mu * cf[SEQ];
+    tok = tok * cf[HIDDEN];
+    const float lay = (float)(in[LAYERS] / p);
+    float base = tok * lay;
+    base = base / ft;
+    base = base * (float)w;
+    float A;
+    if (gc) {
+        float a1 = cf[MEM_ACT_GC] * base;
+        float a2 = cf[MEM_ACT] * tok;
+        a2 = a2 / ft;
+        A = a1 + a2;
+    } else {
+        A = cf[MEM_ACT] * base;
+    }
+    float M = S + A;
+    M = M + cf[MEM_CONST];
+    *M_gpu = M;
+    if (off) {
+        float q = 7.0f / fd;
+        float h = cf[MEM_STATE] * q;
+        h = h * Psi;
+        h = h * (float)(d * t * p);
+        *H_host = h;
+    } else {
+        *H_host = 0.0f;
+    }
+}
+
+/* Sec. 4, Eq. (1) and the paragraphs before it, for one candidate.
+ * Pinned by tests/test_oracle_model.py: hand-computed sums with all overlap
+ * exponents 1, the single-GPU closed form, volume special cases, V = 0 at
+ * size 1, monotonicity in c for offload plans. */
+uint32_t eval_candidate(const float *cf, const uint32_t *in, const ork_bounds *bounds,
+                        const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t z,
+                        uint32_t gc, uint32_t off, uint32_t c, float host_bytes, double *x) {
+    for (int i = 0; i < ORK_N_TERMS; ++i) x[i] = 0.0;
+    if (!option_valid(bounds, z, gc, off)) return 1u;
+
+    const double b = in[GBATCH], mu = in[MBATCH], l = in[LAYERS];
+    const double P = cf[P_BYTES], s = cf[SEQ], h = cf[HIDDEN], eb = cf[ELEM_BYTES];
+
+    /* micro-batches per replica; pipeline plans run them as 1F1B
+     * micro-batches, the others as gradient-accumulation steps */
+    const double n = (double)(in[GBATCH] / (d * in[MBATCH]));
+    const double m = (p > 1) ? n : 1.0;
+    const double a = (p > 1) ? 1.0 : n;
+
+    /* T_fwd: linear in per-GPU batch, tensor shard and layers per stage;
+     * pipeline fill plus steady state (m + p - 1) */
+    const double Tf_mb = (double)cf[T_FWD_SAMPLE] * mu / ((double)t * p);
+    const double T_fwd = Tf_mb * (m + p - 1.0);
+    /* T_bwd proportional to T_fwd; checkpointing recomputes one forward */
+    const double T_bwd = (double)cf[K_BWD] * T_fwd + (gc ? T_fwd : 0.0);
+
+    /* communication volumes, zero when the corresponding size is 1 */
+    const double V_dp = (d > 1) ? P * 2.0 * (d - 1.0) / ((double)d * t * p) : 0.0;
+    const double V_tp = (t > 1) ? eb * 4.0 * 2.0 * (t - 1.0) * b * s * h * l / ((double)d * t) : 0.0;
+    const double V_pp = (p > 1) ? eb * 2.0 * p * b * s * h / ((double)d * t) : 0.0;
+    double B_dp, B_tp, B_pp;
+    bandwidths(env, d, t, p, &B_dp, &B_tp, &B_pp);
+    const double T_dp = V_dp / B_dp, T_tp = V_tp / B_tp, T_pp = V_pp / B_pp;
+
+    /* computation + communication; the accumulation form reduces to the 3D
+     * form at a = 1 */
+    const double sync = ork_f_overlap(cf[K_SYNC], T_bwd, T_dp);
+    double T_cc;
+    if (p > 1) T_cc = T_fwd + sync + T_tp + T_pp;
+    else       T_cc = a * T_fwd + (a - 1.0) * T_bwd + sync + T_tp;
+
+    /* optimizer and offloading */
+    const double Psi = P / ((double)t * p);
+    double T_opt, T_off = 0.0, T_oo;
+    if (off) {
+        T_opt = (double)cf[K_OPT_OFF] * Psi / ((double)d * c);
+        T_off = Psi / ((double)d * env->B_pcie);
+        T_oo = ork_f_overlap(cf[K_OFF], T_dp, T_off) + ork_f_overlap(cf[K_SWAP], T_opt, T_off);
+    } else {
+        T_opt = (double)cf[K_OPT] * Psi / ((z >= 1) ? (double)d : 1.0);
+        T_oo = T_opt;
+    }
+    const double T_iter = T_cc + T_oo + (double)cf[K_CONST];
+    const double thr = b / T_iter;
+
+    float M_gpu, H_host;
+    memory_f32(cf, in, d, t, p, z, gc, off, &M_gpu, &H_host);
+    uint32_t reason = 0;
+    if (!(M_gpu <= env->gpu_mem_cap)) reason |= 2u;
+    if (!(H_host <= host_bytes)) reason |= 4u;
+
+    x[X_N] = n; x[X_M] = m; x[X_A] = a; x[X_TF_MB] = Tf_mb; x[X_T_FWD] = T_fwd; x[X_T_BWD] = T_bwd;
+    x[X_V_DP] = V_dp; x[X_V_TP] = V_tp; x[X_V_PP] = V_pp; x[X_T_DP] = T_dp; x[X_T_TP] = T_tp;
+    x[X_T_PP] = T_pp; x[X_T_CC] = T_cc; x[X_PSI] = Psi; x[X_T_OPT] = T_opt; x[X_T_OFF] = T_off;
+    x[X_T_OO] = T_oo; x[X_T_ITER] = T_iter; x[X_THR] = thr; x[X_M_GPU] = M_gpu; x[X_H_HOST] = H_host;
+    x[X_B_DP] = B_dp; x[X_B_TP] = B_tp; x[X_B_PP] = B_pp;
+    return reason;
+}
+
+uint32_t cpus_of(const ork_grid *grid, uint32_t ci, uint32_t g) {
+    return grid->cpu_mode ? grid->cpu_levels[ci] * g : grid->cpu_levels[ci];
+}
+
+/* host-memory tier in bytes (float32): GB * 2^30, times g in per-GPU mode */
+float tier_bytes(const ork_grid *grid, uint32_t mi, uint32_t g) {
+    float v = grid->mem_levels_gb[mi] * GIB;
+    if (grid->mem_mode) v = v * (float)g;
+    return v;
+}
+
+float tier_gb(const ork_grid *grid, uint32_t mi, uint32_t g) {
+    float v = grid->mem_levels_gb[mi];
+    if (grid->mem_mode) v = v * (float)g;
+    return v;
+}
+
+template <typename T>
+int best_plan_impl(const ork_table *tb, const ork_grid *grid, uint32_t job_begin, uint32_t job_end,
+                   const T *thr, T *best_thr, uint32_t *best_plan) {
+    const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    for (uint32_t j = job_begin; j < job_end; ++j) {
+        const uint64_t nt = tb->triple_off[j + 1] - tb->triple_off[j];
+        const uint64_t ns = tb->seg_off[j + 1] - tb->seg_off[j];
+        const uint64_t cbase = 16ull * rows * (tb->triple_off[j] - tb->triple_off[job_begin]);
+        const uint64_t sbase = rows * (tb->seg_off[j] - tb->seg_off[job_begin]);
+        for (uint64_t r = 0; r < rows; ++r) {
+            for (uint64_t sg = 0; sg < ns; ++sg) {
+                const uint64_t first = tb->seg_first[tb->seg_off[j] + sg];
+                const uint64_t last = (sg + 1 < ns) ? tb->seg_first[tb->seg_off[j] + sg + 1] : nt;
+                T bv = 0; uint32_t bp = ORK_NO_PLAN;
+                for (uint64_t plan = first * 16; plan < last * 16; ++plan) {
+                    const T v = thr[cbase + r * nt * 16 + plan];
+                    if (v > bv) { bv = v; bp = (uint32_t)plan; }   /* strict: lowest index wins ties */
+                }
+                best_thr[sbase + r * ns + sg] = bv;
+                best_plan[sbase + r * ns + sg] = bp;
+            }
+        }
+    }
+    return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+/* Sec. 4.3 "Modeling overlapping": the definition, written out.
+ * Pinned: k=1 gives x+y, large k approaches max, f(k;x,0)=x, f(k;x,x)=x*2^(1/k). */
+double ork_f_overlap(double k, double x, double y) {
+    return std::pow(std::pow(x, k) + std::pow(y, k), 1.0 / k);
+}
+
+/* Plan space of Sec. 3 (3D parallel sizes with d*t*p = g, Table 1) under the
+ * partitioning constraints Fig. 6 alludes to: t a power of two up to tp_max,
+ * p divides the layer count, d*mu divides the global batch.
+ * Pinned: brute force over [1..g]^3 in the tests; with constraints lifted the
+ * count per g is the number of ordered factorisations into three factors. */
+int ork_enumerate(uint32_t n_jobs, const uint32_t *ints, const ork_bounds *bounds,
+                  uint32_t *triple_off, uint32_t *triples, uint64_t cap_triples,
+                  uint32_t *seg_off, uint32_t *seg_g, uint32_t *seg_first, uint64_t cap_segs,
+                  uint64_t *n_triples, uint64_t *n_segs) {
+    uint64_t nt = 0, ns = 0;
+    const bool write = triple_off && triples && seg_off && seg_g && seg_first;
+    bool overflow = false;
+    for (uint32_t j = 0; j < n_jobs; ++j) {
+        const uint32_t l = ints[j * 3 + LAYERS], b = ints[j * 3 + GBATCH], mu = ints[j * 3 + MBATCH];
+        if (write) { triple_off[j] = (uint32_t)nt; seg_off[j] = (uint32_t)ns; }
+        const uint64_t job_first = nt;
+        for (uint32_t g = 1; g <= bounds->g_max; ++g) {
+            bool any = false;
+            for (uint32_t t = 1; t <= 8 && t <= bounds->tp_max; t *= 2) {
+                for (uint32_t p = 1; p <= bounds->pp_max && p <= l; ++p) {
+                    if (l % p != 0) continue;
+                    if (g % (t * p) != 0) continue;
+                    const uint32_t d = g / (t * p);
+                    if (b % (d * mu) != 0) continue;
+                    if (!any) {
+                        any = true;
+                        if (write) {
+                            if (ns < cap_segs) { seg_g[ns] = g; seg_first[ns] = (uint32_t)(nt - job_first); }
+                            else overflow = true;
+                        }
+                        ++ns;
+                    }
+                    if (write) {
+                        if (nt < cap_triples) {
+                            triples[nt * 3 + 0] = d; triples[nt * 3 + 1] = t; triples[nt * 3 + 2] = p;
+                        } else overflow = true;
+                    }
+                    ++nt;
+                }
+            }
+        }
+    }
+    if (write) { triple_off[n_jobs] = (uint32_t)nt; seg_off[n_jobs] = (uint32_t)ns; }
+    if (n_triples) *n_triples = nt;
+    if (n_segs) *n_segs = ns;
+    return overflow ? -1 : 0;
+}
+
+uint32_t ork_eval_one(const float *coef17, const uint32_t *ints3, const ork_bounds *bounds,
+                      const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t z,
+                      uint32_t gc, uint32_t off, uint32_t c, float host_bytes, double *terms) {
+    return eval_candidate(coef17, ints3, bounds, env, d, t, p, z, gc, off, c, host_bytes, terms);
+}
+
+/* The plain definition: every candidate evaluated from scratch. */
+int ork_eval_jobs(uint32_t n_jobs, const float *coef, const uint32_t *ints,
+                  const ork_bounds *bounds, const ork_table *tb, const ork_grid *grid,
+                  const ork_env *env, uint32_t job_begin, uint32_t job_end,
+                  double *thr, uint8_t *reason_out, uint32_t n_threads) {
+    if (job_end > n_jobs || job_begin > job_end) return -1;
+    if (n_threads == 0) n_threads = 1;
+    const uint64_t rows_m = grid->n_mem;
+    auto work = [&](uint32_t tid) {
+        double x[ORK_N_TERMS];
+        for (uint32_t j = job_begin + tid; j < job_end; j += n_threads) {
+            const float *cf = coef + (uint64_t)j * N_COEF;
+            const uint32_t *in = ints + (uint64_t)j * N_INT;
+            const uint64_t nt = tb->triple_off[j + 1] - tb->triple_off[j];
+            const uint64_t cbase = 16ull * grid->n_cpu * grid->n_mem *
+                                   (tb->triple_off[j] - tb->triple_off[job_begin]);
+            for (uint32_t ci = 0; ci < grid->n_cpu; ++ci)
+            for (uint32_t mi = 0; mi < grid->n_mem; ++mi)
+            for (uint64_t tl = 0; tl < nt; ++tl) {
+                const uint32_t *tr = tb->triples + (tb->triple_off[j] + tl) * 3;
+                const uint32_t d = tr[0], t = tr[1], p = tr[2], g = d * t * p;
+                for (uint32_t o = 0; o < 16; ++o) {
+                    const uint32_t z = o >> 2, gc = (o >> 1) & 1u, off = o & 1u;
+                    const uint32_t c = cpus_of(grid, ci, g);
+                    const float hb = tier_bytes(grid, mi, g);
+                    const uint32_t reason = eval_candidate(cf, in, bounds, env, d, t, p, z, gc, off, c, hb, x);
+                    const uint64_t idx = cbase + ((ci * rows_m + mi) * nt + tl) * 16 + o;
+                    thr[idx] = reason ? 0.0 : x[X_THR];
+                    if (reason_out) reason_out[idx] = (uint8_t)reason;
+                }
+            }
+        }
+    };
+    if (n_threads == 1) { work(0); return 0; }
+    std::vector<std::thread> pool;
+    for (uint32_t i = 0; i < n_threads; ++i) pool.emplace_back(work, i);
+    for (auto &th : pool) th.join();
+    return 0;
+}
+
+/* GetBestPlan of Sec. 5.2 / Algorithm 1: the best predicted throughput among
+ * the feasible plans for a given resource amount; lowest plan index on exact
+ * ties; no feasible plan gives (0, ORK_NO_PLAN).
+ * Pinned: numpy argmax over a flat list in the tests. */
+int ork_best_plan_f64(const ork_table *tb, const ork_grid *grid, uint32_t jb, uint32_t je,
+                      const double *thr, double *best_thr, uint32_t *best_plan) {
+    return best_plan_impl<double>(tb, grid, jb, je, thr, best_thr, best_plan);
+}
+int ork_best_plan_f32(const ork_table *tb, const ork_grid *grid, uint32_t jb, uint32_t je,
+                      const float *thr, float *best_thr, uint32_t *best_plan) {
+    return best_plan_impl<float>(tb, grid, jb, je, thr, best_thr, best_plan);
+}
+
+/* Resource sensitivity curve (Sec. 5.2, Fig. 6): for each GPU count the
+ * maximum throughput achievable within that many GPUs, so the curve is flat
+ * over counts that bring nothing; keeps the smallest count reaching the
+ * maximum and its plan.  Pinned: numpy maximum.accumulate in the tests. */
+int ork_curves_f32(const ork_table *tb, const ork_grid *grid, uint32_t jb, uint32_t je,
+                   const float *best_thr, const uint32_t *best_plan,
+                   float *curve_thr, uint32_t *curve_plan, uint32_t *curve_g) {
+    const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    for (uint32_t j = jb; j < je; ++j) {
+        const uint64_t ns = tb->seg_off[j + 1] - tb->seg_off[j];
+        const uint64_t sbase = rows * (tb->seg_off[j] - tb->seg_off[jb]);
+        for (uint64_t r = 0; r < rows; ++r) {
+            float cur = 0.0f; uint32_t plan = ORK_NO_PLAN, gg = 0;
+            for (uint64_t sg = 0; sg < ns; ++sg) {
+                const uint64_t i = sbase + r * ns + sg;
+                if (best_thr[i] > cur) { cur = best_thr[i]; plan = best_plan[i]; gg = tb->seg_g[tb->seg_off[j] + sg]; }
+                curve_thr[i] = cur; curve_plan[i] = plan; curve_g[i] = gg;
+            }
+        }
+    }
+    return 0;
+}
+
+/* Greedy marginal-gain allocation: a reading of Sec. 5.2 (slopes of the
+ * curves, "slopes of GPUs and then CPUs", memory allocated last from the
+ * chosen plan's estimate) with every job best-effort and the cluster as
+ * totals.  Slopes are float32: ((v1 - v0) / ref_thr) / delta.
+ *  GPU pass : repeatedly give the (job, larger GPU count) with the highest
+ *             normalised throughput gain per GPU, at the lowest CPU level and
+ *             the highest memory tier; ties -> smaller count, lower job index.
+ *  CPU pass : same over CPU levels at the granted GPU count.
+ *  Memory   : in job order, among the tiers that still fit, the one with the
+ *             highest throughput (smallest such tier); none feasible -> the
+ *             job is dropped and its GPUs/CPUs stay unused this round.
+ * PARITY UNPINNED as a heuristic reading; the tests pin capacity invariants,
+ * optimality on concave curves against exhaustive search, and hand cases. */
+int ork_greedy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb,
+                   const ork_grid *grid, uint32_t G, uint32_t C, float host_mem_gb,
+                   const float *best_thr, const uint32_t *best_plan,
+                   const float *curve_thr, ork_assign *assign, double *total, double *min_gap) {
+    const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    const uint32_t m_top = grid->n_mem - 1;
+    std::vector<int64_t> gi(n_jobs, -1);
+    std::vector<uint32_t> ci(n_jobs, 0);
+    uint64_t freeG = G, freeC = C;
+    double gap_min = INFINITY;
+
+    auto ns_of = [&](uint32_t j) { return (uint64_t)(tb->seg_off[j + 1] - tb->seg_off[j]); };
+    auto g_of = [&](uint32_t j, int64_t s) -> uint64_t { return s < 0 ? 0 : tb->seg_g[tb->seg_off[j] + s]; };
+    auto at = [&](const float *arr, uint32_t j, uint32_t c, uint32_t m, uint64_t s) {
+        return arr[rows * tb->seg_off[j] + ((uint64_t)c * grid->n_mem + m) * ns_of(j) + s];
+    };
+    auto cpu_cost = [&](uint32_t j, uint32_t c, int64_t s) -> uint64_t {
+        return s < 0 ? 0 : cpus_of(grid, c, (uint32_t)g_of(j, s));
+    };
+    auto note_gap = [&](float win, float second) {
+        if (second > 0.0f) { double gp = ((double)win - second) / win; if (gp < gap_min) gap_min = gp; }
+    };
+
+    /* GPU pass */
+    for (;;) {
+        float top = 0.0f, second = 0.0f; uint32_t tj = 0; int64_t ts = -1;
+        for (uint32_t j = 0; j < n_jobs; ++j) {
+            const float cur = gi[j] < 0 ? 0.0f : at(curve_thr, j, 0, m_top, gi[j]);
+            for (int64_t s = gi[j] + 1; s < (int64_t)ns_of(j); ++s) {
+                const uint64_t dg = g_of(j, s) - g_of(j, gi[j]);
+                if (dg > freeG) break;
+                const float v = at(curve_thr, j, 0, m_top, s);
+                if (!(v > cur)) continue;
+                const uint64_t dc = cpu_cost(j, 0, s) - cpu_cost(j, 0, gi[j]);
+                if (dc > freeC) continue;
+                float sl = (v - cur) / ref_thr[j];
+                sl = sl / (float)dg;
+                if (sl > top) { second = top; top = sl; tj = j; ts = s; }
+                else if (sl > second) second = sl;
+            }
+        }
+        if (ts < 0) break;
+        note_gap(top, second);
+        freeG -= g_of(tj, ts) - g_of(tj, gi[tj]);
+        freeC -= cpu_cost(tj, 0, ts) - cpu_cost(tj, 0, gi[tj]);
+        gi[tj] = ts;
+    }
+    /* CPU pass */
+    for (;;) {
+        float top = 0.0f, second = 0.0f; uint32_t tj = 0; int64_t tc = -1;
+        for (uint32_t j = 0; j < n_jobs; ++j) {
+            if (gi[j] < 0) continue;
+            const float cur = at(best_thr, j, ci[j], m_top, gi[j]);
+            for (uint32_t c = ci[j] + 1; c < grid->n_cpu; ++c) {
+                const uint64_t dc = cpu_cost(j, c, gi[j]) - cpu_cost(j, ci[j], gi[j]);
+                if (dc > freeC) break;
+                const float v = at(best_thr, j, c, m_top, gi[j]);
+                if (!(v > cur)) continue;
+                float sl = (v - cur) / ref_thr[j];
+                sl = sl / (float)dc;
+                if (sl > top) { second = top; top = sl; tj = j; tc = c; }
+                else if (sl > second) second = sl;
+            }
+        }
+        if (tc < 0) break;
+        note_gap(top, second);
+        freeC -= cpu_cost(tj, (uint32_t)tc, gi[tj]) - cpu_cost(tj, ci[tj], gi[tj]);
+        ci[tj] = (uint32_t)tc;
+    }
+    /* memory, then output */
+    float freeM = host_mem_gb;
+    double sum = 0.0;
+    for (uint32_t j = 0; j < n_jobs; ++j) {
+        ork_assign out = {0, 0, 0.0f, ORK_NO_PLAN, 0.0f};
+        if (gi[j] >= 0) {
+            const uint32_t g = (uint32_t)g_of(j, gi[j]);
+            float bv = 0.0f; int64_t bm = -1;
+            for (uint32_t m = 0; m < grid->n_mem; ++m) {
+                if (!(tier_gb(grid, m, g) <= freeM)) continue;
+                const float v = at(best_thr, j, ci[j], m, gi[j]);
+                if (v > bv) { bv = v; bm = m; }
+            }
+            if (bm >= 0) {
+                const float cost = tier_gb(grid, (uint32_t)bm, g);
+                freeM = freeM - cost;
+                out.g = g; out.c = (uint32_t)cpu_cost(j, ci[j], gi[j]); out.mem_gb = cost;
+                out.plan = best_plan[rows * tb->seg_off[j] + ((uint64_t)ci[j] * grid->n_mem + bm) * ns_of(j) + gi[j]];
+                out.thr = bv;
+                sum += (double)bv / (double)ref_thr[j];
+            }
+        }
+        assign[j] = out;
+    }
+    if (total) *total = sum;
+    if (min_gap) *min_gap = gap_min;
+    return 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,112 @@
+/*
+ * CPU oracle for the plan-evaluation path of the Rubick scheduler
+ * (arxiv 2408.08586).  TEST INFRASTRUCTURE ONLY: a plain, slow, obviously
+ * correct implementation used to check the GPU library and to serve as the
+ * reported CPU baseline.  It shares no code with the GPU library and nothing
+ * in the product path may call it.
+ *
+ * All pointers are host pointers.  Times are double precision; the memory
+ * feasibility test and the greedy slopes are float32 with one rounding per
+ * written operation (build with -ffp-contract=off), because those values
+ * decide integers that the GPU library must reproduce bit for bit.
+ *
+ * Job descriptor: coef[j*17 + k] (float32) with k =
+ *   0 P_bytes  1 seq  2 hidden  3 elem_bytes  4 t_fwd_sample  5 k_bwd  6 k_sync
+ *   7 k_opt  8 k_opt_off  9 k_off  10 k_swap  11 k_const  12 mem_state
+ *   13 mem_act  14 mem_act_gc  15 mem_const  16 ref_thr
+ * and ints[j*3 + k] (uint32) with k = 0 layers, 1 global batch, 2 micro-batch size.
+ * Symbols follow Table 1 of the paper.
+ *
+ * Parity status of each function is stated at its definition in rk_oracle.cpp.
+ */
+#ifndef RK_ORACLE_H
+#define RK_ORACLE_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ORK_NO_PLAN 0xFFFFFFFFu
+#define ORK_N_TERMS 24
+
+typedef struct {
+    float B_intra, B_inter, B_pcie;   /* bytes/s */
+    float gpu_mem_cap;                /* bytes */
+    uint32_t gpus_per_node;
+} ork_env;
+
+typedef struct {
+    uint32_t n_cpu;
+    const uint32_t *cpu_levels;       /* ascending, >= 1 */
+    uint32_t cpu_mode;                /* 0: CPUs of the job, 1: CPUs per GPU */
+    uint32_t n_mem;
+    const float *mem_levels_gb;       /* ascending */
+    uint32_t mem_mode;                /* 0: GB of the job, 1: GB per GPU */
+} ork_grid;
+
+typedef struct {
+    uint32_t g_max, tp_max, pp_max;
+    uint32_t zero_mask, gc_mask, off_mask;
+} ork_bounds;
+
+typedef struct {                      /* plan table, filled by ork_enumerate */
+    const uint32_t *triple_off;       /* [n_jobs+1] */
+    const uint32_t *triples;          /* [n_triples][3] = d,t,p */
+    const uint32_t *seg_off;          /* [n_jobs+1] */
+    const uint32_t *seg_g;            /* [n_segs] GPU count of the segment */
+    const uint32_t *seg_first;        /* [n_segs] first triple (job-local) */
+} ork_table;
+
+typedef struct { uint32_t g, c; float mem_gb; uint32_t plan; float thr; } ork_assign;
+
+/* (x^k + y^k)^(1/k), Sec. 4.3 "Modeling overlapping". */
+double ork_f_overlap(double k, double x, double y);
+
+/* Enumerate (d,t,p) triples per job in canonical order (g, then t, then p
+ * ascending).  Null output buffers: only the counts are produced. Returns 0,
+ * or -1 if a capacity is too small (counts still written). */
+int ork_enumerate(uint32_t n_jobs, const uint32_t *ints, const ork_bounds *bounds,
+                  uint32_t *triple_off, uint32_t *triples, uint64_t cap_triples,
+                  uint32_t *seg_off, uint32_t *seg_g, uint32_t *seg_first, uint64_t cap_segs,
+                  uint64_t *n_triples, uint64_t *n_segs);
+
+/* One candidate; terms[ORK_N_TERMS] receives every intermediate quantity
+ * (order documented in rk_oracle.cpp).  Returns the reason bits
+ * (0 = feasible; 1 structural, 2 GPU memory, 4 host memory). */
+uint32_t ork_eval_one(const float *coef17, const uint32_t *ints3, const ork_bounds *bounds,
+                      const ork_env *env, uint32_t d, uint32_t t, uint32_t p,
+                      uint32_t z, uint32_t gc, uint32_t off, uint32_t c, float host_bytes,
+                      double *terms);
+
+/* Every candidate of jobs [job_begin, job_end): thr (0 when infeasible) and
+ * optional reason bits, candidate order [job][cpu level][mem tier][plan],
+ * plan = triple*16 + (z*4 + gc*2 + off). */
+int ork_eval_jobs(uint32_t n_jobs, const float *coef, const uint32_t *ints,
+                  const ork_bounds *bounds, const ork_table *table, const ork_grid *grid,
+                  const ork_env *env, uint32_t job_begin, uint32_t job_end,
+                  double *thr, uint8_t *reason_or_null, uint32_t n_threads);
+
+/* Per segment x cpu level x mem tier: maximum and lowest-index argmax. */
+int ork_best_plan_f64(const ork_table *table, const ork_grid *grid, uint32_t job_begin,
+                      uint32_t job_end, const double *thr, double *best_thr, uint32_t *best_plan);
+int ork_best_plan_f32(const ork_table *table, const ork_grid *grid, uint32_t job_begin,
+                      uint32_t job_end, const float *thr, float *best_thr, uint32_t *best_plan);
+
+/* Prefix maximum over a job's GPU counts (resource sensitivity curve). */
+int ork_curves_f32(const ork_table *table, const ork_grid *grid, uint32_t job_begin,
+                   uint32_t job_end, const float *best_thr, const uint32_t *best_plan,
+                   float *curve_thr, uint32_t *curve_plan, uint32_t *curve_g);
+
+/* Greedy marginal-gain allocation over all n_jobs jobs of the table.
+ * min_gap (optional) receives the smallest relative gap between a winning
+ * slope and its runner-up over all decisions taken. */
+int ork_greedy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *table,
+                   const ork_grid *grid, uint32_t G, uint32_t C, float host_mem_gb,
+                   const float *best_thr, const uint32_t *best_plan,
+                   const float *curve_thr, ork_assign *assign, double *total, double *min_gap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,264 @@
+"""Seeded synthetic scheduling workloads (job descriptors, allocation grids, clusters).
+
+This module is the only code shared by the CPU oracle and the HIP path: it
+draws numbers and fills arrays, and contains none of the performance model's
+arithmetic.  Every draw is a pure function of (seed, config, round, job, field)
+through a counter-based generator (splitmix64 finaliser), so any job of any
+configuration can be regenerated in isolation.
+
+The five configurations stand in for the workload shapes of the paper's
+evaluation (Sec. 7: seven Transformer models of 86M-30B parameters, a cluster
+of 8 servers x 8 GPUs, a 406-job trace): only the shapes are used; no fitted
+coefficient, trace record or dataset item is reproduced.
+
+Job descriptor layout (Table 1 of the paper defines the symbols):
+  coef  float32 [n_jobs, 17], columns COEF_FIELDS
+  ints  uint32  [n_jobs, 3],  columns INT_FIELDS
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+BASE_SEED = 0x52554249
+
+COEF_FIELDS = (
+    "P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample",
+    "k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_const",
+    "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr",
+)
+INT_FIELDS = ("layers", "gbatch", "mbatch")
+N_COEF = len(COEF_FIELDS)
+N_INT = len(INT_FIELDS)
+
+_MASK = np.uint64(0xFFFFFFFFFFFFFFFF)
+_GOLDEN = np.uint64(0x9E3779B97F4A7C15)
+
+
+def _mix(x: np.ndarray) -> np.ndarray:
+    """splitmix64 output function on a uint64 array."""
+    with np.errstate(over="ignore"):
+        x = (x ^ (x >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        x = (x ^ (x >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        x = x ^ (x >> np.uint64(31))
+    return x
+
+
+def _key(seed: int, *parts) -> np.ndarray:
+    """Chain (seed, part0, part1, ...) into one uint64 per broadcast element."""
+    x = np.asarray(np.uint64(seed & 0xFFFFFFFFFFFFFFFF))
+    with np.errstate(over="ignore"):
+        for v in parts:
+            v = np.asarray(v).astype(np.uint64)
+            x = _mix(x + _GOLDEN * (v + np.uint64(1)))
+    return x
+
+
+def uniform(seed: int, *parts) -> np.ndarray:
+    """U[0,1) double, one per broadcast element of `parts`."""
+    return (_key(seed, *parts) >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
+
+
+@dataclass
+class Grid:
+    """Allocation grid: CPU levels and host-memory tiers (per job or per GPU)."""
+    cpu_levels: np.ndarray           # uint32 [n_cpu], ascending, >= 1
+    cpu_mode: int                    # 0: CPUs of the whole job; 1: CPUs per GPU
+    mem_levels_gb: np.ndarray        # float32 [n_mem], ascending
+    mem_mode: int                    # 0: GB for the whole job; 1: GB per GPU
+
+
+@dataclass
+class Env:
+    B_intra: float = 400e9           # bytes/s, links inside a node
+    B_inter: float = 100e9           # bytes/s, links between nodes
+    B_pcie: float = 32e9             # bytes/s, GPU <-> host
+    gpu_mem_cap: float = 80e9        # bytes
+    gpus_per_node: int = 8
+
+
+@dataclass
+class Bounds:
+    g_max: int
+    tp_max: int = 8
+    pp_max: int = 255
+    zero_mask: int = 0xF             # bit z set: ZeRO stage z allowed
+    gc_mask: int = 0x3               # bit v set: gradient checkpointing == v allowed
+    off_mask: int = 0x3              # bit v set: offload == v allowed
+
+
+@dataclass
+class Cluster:
+    G: int
+    C: int
+    host_mem_gb: float
+
+
+@dataclass
+class Workload:
+    name: str
+    coef: np.ndarray                 # float32 [J, 17]
+    ints: np.ndarray                 # uint32 [J, 3]
+    bounds: Bounds
+    grid: Grid
+    env: Env
+    cluster: Cluster
+    meta: dict = field(default_factory=dict)
+
+    @property
+    def n_jobs(self) -> int:
+        return int(self.coef.shape[0])
+
+    def subset(self, idx) -> "Workload":
+        idx = np.asarray(idx)
+        return Workload(self.name + "[subset]", np.ascontiguousarray(self.coef[idx]),
+                        np.ascontiguousarray(self.ints[idx]), self.bounds, self.grid,
+                        self.env, self.cluster, dict(self.meta))
+
+
+# field ids for the counter-based generator
+_F_PARAMS, _F_BUCKET, _F_LAYERS, _F_BATCH, _F_MBATCH = 0, 1, 2, 3, 4
+_F_COEF0 = 16                         # + column index of COEF_FIELDS
+
+
+def _log_uniform(u, lo, hi):
+    return np.exp(np.log(lo) + u * (np.log(hi) - np.log(lo)))
+
+
+def draw_jobs(seed: int, config: int, rnd, job_ids, *, param_buckets, layer_choices,
+              batch_choices=(32, 64, 128), mbatch_choices=(1, 2, 4), seq=2048):
+    """Draw job descriptors.
+
+    param_buckets: list of (probability, lo, hi) for the parameter count N
+    (log-uniform inside a bucket).  `rnd` may be a scalar or an array aligned
+    with job_ids (the round whose stream a job is drawn from).
+    """
+    job_ids = np.asarray(job_ids, dtype=np.uint64)
+    rnd = np.broadcast_to(np.asarray(rnd, dtype=np.uint64), job_ids.shape)
+    J = job_ids.shape[0]
+
+    def u(fld):
+        return uniform(seed, config, rnd, job_ids, fld)
+
+    # parameter count
+    ub = u(_F_BUCKET)
+    un = u(_F_PARAMS)
+    N = np.zeros(J)
+    acc = 0.0
+    chosen = np.zeros(J, dtype=bool)
+    for prob, lo, hi in param_buckets:
+        acc += prob
+        sel = (~chosen) & (ub < acc + 1e-12)
+        N[sel] = _log_uniform(un[sel], lo, hi)
+        chosen |= sel
+    lo, hi = param_buckets[-1][1], param_buckets[-1][2]
+    N[~chosen] = _log_uniform(un[~chosen], lo, hi)
+
+    def pick(fld, choices):
+        c = np.asarray(choices)
+        return c[np.minimum((u(fld) * len(c)).astype(np.int64), len(c) - 1)]
+
+    layers = pick(_F_LAYERS, layer_choices).astype(np.uint32)
+    gbatch = pick(_F_BATCH, batch_choices).astype(np.uint32)
+    mbatch = pick(_F_MBATCH, mbatch_choices).astype(np.uint32)
+    # hidden size from the usual transformer size relation N ~ 12 l h^2
+    hidden = 128.0 * np.maximum(1.0, np.round(np.sqrt(N / (12.0 * layers)) / 128.0))
+
+    nominal = {
+        "P_bytes": 2.0 * N,
+        "seq": np.full(J, float(seq)),
+        "hidden": hidden,
+        "elem_bytes": np.full(J, 2.0),
+        "t_fwd_sample": 2.0 * N * seq / 1.5e14,
+        "k_bwd": np.full(J, 2.0),
+        "k_sync": np.full(J, 2.0),
+        "k_opt": np.full(J, 5e-12),
+        "k_opt_off": np.full(J, 5e-9),
+        "k_off": np.full(J, 2.0),
+        "k_swap": np.full(J, 2.0),
+        "k_const": np.full(J, 0.05),
+        "mem_state": np.full(J, 1.0),
+        "mem_act": np.full(J, 34.0),
+        "mem_act_gc": np.full(J, 2.0),
+        "mem_const": np.full(J, float(2 ** 30)),
+        # reference throughput used to normalise speedups: a nominal
+        # samples/s figure for the model size (an input, not a prediction)
+        "ref_thr": 1.5e14 / (6.0 * N * seq),
+    }
+    fixed = {"P_bytes", "seq", "hidden", "elem_bytes"}      # model constants, not fitted
+    coef = np.zeros((J, N_COEF), dtype=np.float32)
+    for col, name in enumerate(COEF_FIELDS):
+        v = nominal[name]
+        if name not in fixed:
+            v = v * (0.5 + 1.5 * u(_F_COEF0 + col))
+        coef[:, col] = v.astype(np.float32)
+    ints = np.stack([layers, gbatch, mbatch], axis=1).astype(np.uint32)
+    return np.ascontiguousarray(coef), np.ascontiguousarray(ints)
+
+
+def _abs_levels(n):
+    return np.arange(1, n + 1, dtype=np.uint32)
+
+
+def tiny(seed: int = BASE_SEED) -> Workload:
+    """8 jobs on one 8-GPU node; about 1e4 candidates."""
+    coef, ints = draw_jobs(seed, 1, 0, np.arange(8), param_buckets=[(1.0, 0.1e9, 13e9)],
+                           layer_choices=(12, 24, 32, 40))
+    return Workload("tiny", coef, ints, Bounds(g_max=8),
+                    Grid(_abs_levels(8), 0, np.array([64.0], np.float32), 0),
+                    Env(), Cluster(8, 32, 512.0))
+
+
+def paper_scale(seed: int = BASE_SEED) -> Workload:
+    """64 jobs on 8 nodes x 8 GPUs (the size of the paper's testbed); about 1e6 candidates."""
+    coef, ints = draw_jobs(seed, 2, 0, np.arange(64),
+                           param_buckets=[(0.4, 0.1e9, 1.3e9), (0.4, 1.3e9, 13e9), (0.2, 13e9, 70e9)],
+                           layer_choices=(12, 24, 32, 40))
+    return Workload("paper_scale", coef, ints, Bounds(g_max=64),
+                    Grid(_abs_levels(32), 0, np.array([64.0], np.float32), 0),
+                    Env(), Cluster(64, 256, 4096.0))
+
+
+_BIG = dict(param_buckets=[(1.0, 0.1e9, 175e9)], layer_choices=(24, 32, 48, 80, 96))
+_RATIOS = np.array([1, 2, 4, 8, 16], dtype=np.uint32)
+
+
+def large(seed: int = BASE_SEED) -> Workload:
+    """1,000 jobs, 128 nodes x (8 GPUs, 128 CPUs, 2 TB); CPU levels are per-GPU ratios."""
+    coef, ints = draw_jobs(seed, 3, 0, np.arange(1000), **_BIG)
+    return Workload("large", coef, ints, Bounds(g_max=1024),
+                    Grid(_RATIOS.copy(), 1, np.array([2048.0], np.float32), 0),
+                    Env(), Cluster(1024, 128 * 128, 128 * 2048.0))
+
+
+def stress(seed: int = BASE_SEED, n_jobs: int = 10000) -> Workload:
+    """10,000 jobs, 4096 GPUs, full (g, CPU ratio, host-memory tier) grid."""
+    coef, ints = draw_jobs(seed, 4, 0, np.arange(n_jobs), **_BIG)
+    return Workload("stress", coef, ints, Bounds(g_max=4096),
+                    Grid(_RATIOS.copy(), 1, np.array([0.0, 64.0, 256.0, 1024.0], np.float32), 0),
+                    Env(), Cluster(4096, 512 * 128, 512 * 2048.0))
+
+
+def what_if(round_index: int, seed: int = BASE_SEED, n_jobs: int = 500) -> Workload:
+    """One of 256 independent what-if rounds: 500 jobs on about 512 GPUs.
+
+    Capacity is perturbed by a uniform +-25 % and one job in ten is redrawn,
+    both keyed by (seed, round)."""
+    r = int(round_index)
+    ids = np.arange(n_jobs)
+    n_redraw = n_jobs // 10
+    order = np.argsort(uniform(seed, 5, r, ids, 1000), kind="stable")
+    rnd = np.zeros(n_jobs, dtype=np.uint64)
+    rnd[order[:n_redraw]] = r + 1                      # stream 0 is the base job set
+    coef, ints = draw_jobs(seed, 5, rnd, ids, **_BIG)
+    ug = float(uniform(seed, 5, r, 0, 1001))
+    uc = float(uniform(seed, 5, r, 0, 1002))
+    G = int(round(512 * (1.0 + (ug - 0.5) * 0.5)))
+    C = int(round(8192 * (1.0 + (uc - 0.5) * 0.5)))
+    return Workload(f"what_if[{r}]", coef, ints, Bounds(g_max=512),
+                    Grid(_RATIOS.copy(), 1, np.array([2048.0], np.float32), 0),
+                    Env(), Cluster(G, C, 64 * 2048.0), {"round": r})
+
+
+CONFIGS = {"tiny": tiny, "paper_scale": paper_scale, "large": large, "stress": stress}
