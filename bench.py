@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the plan-evaluation path on one MI355X.
+
+A step is one pass of the whole path over one synthetic scheduling problem:
+enumerate plans -> (per job chunk) evaluate candidates, best plan per segment,
+curves -> greedy allocation.  Inputs are resident in HBM before the timed
+region.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def build_workload(name):
+    import workloads
+    if name == "stress":
+        return workloads.stress(), ("stress: 10,000 jobs, G=4096 (512 nodes x 8 GPUs), CPU ratios {1,2,4,8,16} per GPU, "
+                                    "host-memory tiers {0,64,256,1024} GiB")
+    if name == "large":
+        return workloads.large(), "large: 1,000 jobs, G=1024, CPU ratios {1,2,4,8,16} per GPU, one 2048 GiB tier"
+    if name == "paper_scale":
+        return workloads.paper_scale(), "paper_scale: 64 jobs, G=64, 1..32 CPUs, one 64 GiB tier"
+    if name == "tiny":
+        return workloads.tiny(), "tiny: 8 jobs, G=8"
+    raise SystemExit(f"unknown workload {name}")
+
+
+def cpu_baseline(wl, sample_jobs, threads):
+    """The oracle, as it stands, on the first `sample_jobs` jobs of the workload."""
+    import oracle
+    import workloads
+    sub = wl.subset(np.arange(min(sample_jobs, wl.n_jobs)))
+    frac = sub.n_jobs / wl.n_jobs
+    sub.cluster = workloads.Cluster(max(1, int(wl.cluster.G * frac)), max(1, int(wl.cluster.C * frac)),
+                                    wl.cluster.host_mem_gb * frac)
+    t0 = time.perf_counter()
+    tb = oracle.enumerate_plans(sub.ints, sub.bounds)
+    t1 = time.perf_counter()
+    thr, _ = oracle.eval_jobs(sub.coef, sub.ints, sub.bounds, tb, sub.grid, sub.env, want_reason=False,
+                              n_threads=threads)
+    t2 = time.perf_counter()
+    bt64, bp = oracle.best_plan(tb, sub.grid, thr)
+    bt = bt64.astype(np.float32)
+    ct, cp, cg = oracle.curves(tb, sub.grid, bt, bp)
+    t3 = time.perf_counter()
+    oracle.greedy(sub.coef[:, 16], tb, sub.grid, sub.cluster, bt, bp, ct)
+    t4 = time.perf_counter()
+    n = thr.size
+    return {"value": n / (t4 - t0), "unit": "candidates/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {sub.n_jobs} jobs of the workload ({n} candidates), capacities scaled by {frac:g}; "
+                      f"evaluation on {threads} threads, the other stages on 1",
+            "seconds": {"enumerate": t1 - t0, "evaluate": t2 - t1, "best_plan+curves": t3 - t2, "greedy": t4 - t3},
+            "eval_only_candidates_per_s": n / (t2 - t1)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="stress")
+    ap.add_argument("--chunks", type=int, default=3, help="job chunks streamed through one candidate buffer")
+    ap.add_argument("--cpu-sample-jobs", type=int, default=1500)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("this benchmark measures one GPU; the path runs on a single device (use --gpus 1)")
+
+    import torch
+    import paper_2408_08586_amd as rk
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    rk.load_library()
+    wl, desc = build_workload(args.workload)
+    dev = "cuda:0"
+    ctx = rk.rk_create(0)
+    jobs = rk.Jobs(wl.coef, wl.ints, dev)
+    bounds, grid, env = rk.make_bounds(wl.bounds), rk.make_grid(wl.grid), rk.make_env(wl.env)
+    cluster = rk.make_cluster(wl.cluster)
+    n_rows = len(wl.grid.cpu_levels) * len(wl.grid.mem_levels_gb)
+
+    table = rk.enumerate_to_table(ctx, jobs, bounds, dev)      # sizes the buffers; enumeration is re-run per step
+    J = wl.n_jobs
+    n_chunks = max(1, min(args.chunks, J))
+    edges = np.linspace(0, J, n_chunks + 1).astype(int)
+    chunk_cands = [table.n_candidates(n_rows, int(a), int(b)) for a, b in zip(edges[:-1], edges[1:])]
+    n_cand = table.n_candidates(n_rows)
+    n_seg = table.n_segments(n_rows)
+    thr = torch.empty(max(chunk_cands) + 4, dtype=torch.float32, device=dev)
+    f32 = lambda n: torch.empty(n + 4, dtype=torch.float32, device=dev)
+    i32 = lambda n: torch.empty(n + 4, dtype=torch.int32, device=dev)
+    best_thr, best_plan = f32(n_seg), i32(n_seg)
+    curve_thr, curve_plan, curve_g = f32(n_seg), i32(n_seg), i32(n_seg)
+    assign = rk.new_assign(J, dev)
+    total = torch.zeros(1, dtype=torch.float32, device=dev)
+    seg_start = [n_rows * int(table.h_seg_off[a]) for a in edges[:-1]]
+    seg_count = [table.n_segments(n_rows, int(a), int(b)) for a, b in zip(edges[:-1], edges[1:])]
+
+    kernel_ms = {"enumerate": [], "eval": [], "best_plan": [], "curves": [], "allocate": []}
+
+    def timed(name, fn, record):
+        if not record:
+            fn()
+            return
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        kernel_ms[name].append((a, b))
+
+    def step(record):
+        timed("enumerate", lambda: rk.rk_enumerate_plans(ctx, jobs, bounds, table.c), record)
+        for k in range(n_chunks):
+            jb, je = int(edges[k]), int(edges[k + 1])
+            s0, sn = seg_start[k], seg_count[k]
+            timed("eval", lambda: rk.rk_eval_candidates(ctx, jobs, table.c, grid, env, jb, je, thr, None), record)
+            timed("best_plan", lambda: rk.rk_best_plan(ctx, table.c, grid, jb, je, thr, best_thr[s0:], best_plan[s0:]), record)
+            timed("curves", lambda: rk.rk_curves(ctx, table.c, grid, jb, je, best_thr[s0:], best_plan[s0:],
+                                                 curve_thr[s0:], curve_plan[s0:], curve_g[s0:]), record)
+        timed("allocate", lambda: rk.rk_allocate(ctx, jobs.ref_thr, table.c, grid, cluster, 0, J, best_thr, best_plan,
+                                                 curve_thr, assign, total), record)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    avg_ms = {k: (sum(a.elapsed_time(b) for a, b in v) / len(v) if v else 0.0) for k, v in kernel_ms.items()}
+    per_step_ms = {k: avg_ms[k] * (len(v) / args.steps) for k, v in kernel_ms.items()}
+
+    # fused round (the path a scheduler would call): latency of rk_schedule_round
+    for _ in range(2):
+        rk.rk_schedule_round(ctx, jobs, bounds, grid, env, cluster, assign, total)
+    torch.cuda.synchronize()
+    lat = []
+    for _ in range(max(5, args.steps)):
+        a = time.perf_counter()
+        rk.rk_schedule_round(ctx, jobs, bounds, grid, env, cluster, assign, total)
+        torch.cuda.synchronize()
+        lat.append((time.perf_counter() - a) * 1e3)
+    lat = np.array(lat)
+
+    # roofline of the dominant kernel (algorithmic bytes per launch / average launch duration)
+    cand_per_launch = n_cand / n_chunks
+    seg_per_launch = n_seg / n_chunks
+    bytes_eval = 4.0 * cand_per_launch + 4.0 * table.n_triples / n_chunks
+    bytes_best = 4.0 * cand_per_launch + 8.0 * seg_per_launch
+    gbs_eval = bytes_eval / (avg_ms["eval"] * 1e-3) / 1e9
+    gbs_best = bytes_best / (avg_ms["best_plan"] * 1e-3) / 1e9
+    dom = "eval" if per_step_ms["eval"] >= per_step_ms["best_plan"] else "best_plan"
+    achieved = gbs_eval if dom == "eval" else gbs_best
+    pair_gbs = (bytes_eval + bytes_best) / ((avg_ms["eval"] + avg_ms["best_plan"]) * 1e-3) / 1e9
+
+    out = {
+        "metric": "candidate plan evaluations/sec (whole path: enumerate + evaluate + best plan + curves + greedy), 1 GPU",
+        "value": n_cand / (ms_per_step * 1e-3),
+        "unit": "candidates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": desc, "n_jobs": J, "n_candidates": n_cand, "n_segment_rows": n_seg,
+                   "n_triples": table.n_triples, "job_chunks": n_chunks},
+        "roofline": {"bound": "hbm", "kernel": "k_eval" if dom == "eval" else "k_best_plan",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None},
+        "kernels": {"avg_launch_ms": avg_ms, "per_step_ms": per_step_ms,
+                    "eval_GBps": gbs_eval, "best_plan_GBps": gbs_best,
+                    "eval_plus_best_plan_GBps": pair_gbs, "eval_plus_best_plan_frac_of_hbm": pair_gbs / HBM_PEAK_GBS,
+                    "eval_plus_best_plan_candidates_per_s": n_cand / ((per_step_ms["eval"] + per_step_ms["best_plan"]) * 1e-3)},
+        "round_latency_ms": {"entry": "rk_schedule_round (fused evaluation, host-synchronous)",
+                             "min": float(lat.min()), "median": float(np.median(lat)), "max": float(lat.max())},
+    }
+    if not args.no_cpu_baseline:
+        threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_jobs, threads)
+    rk.rk_destroy(ctx)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

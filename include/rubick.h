@@ -1,0 +1,251 @@
+/*
+ * rubick.h - C ABI of the GPU plan-evaluation library (gfx950 / MI355X).
+ *
+ * The library evaluates the performance model of the Rubick scheduler
+ * (arxiv 2408.08586, Sec. 4) for every (job x execution plan x resource
+ * allocation) candidate, masks plans that do not fit in memory, takes the
+ * best plan per (job, allocation) (GetBestPlan, Sec. 5.2 / Algorithm 1),
+ * builds the per-job resource sensitivity curves (Sec. 5.2, Fig. 6) and runs a
+ * slope-ordered greedy allocation over them (Sec. 5.2).
+ *
+ * Conventions
+ *  - Every function returns RK_OK (0) or a negative error code; the text of
+ *    the last error of a context is available from rk_last_error().  Nothing
+ *    throws, aborts or allocates memory the caller must free.
+ *  - Pointers marked [device] are device pointers on the context's GPU and
+ *    must be 16-byte aligned; pointers marked [host] are ordinary host
+ *    pointers.  Structs are host structs passed by pointer and are read
+ *    before the call returns.  The caller owns every input and output buffer;
+ *    the context owns only its scratch memory.  Inputs are never modified.
+ *  - Work is enqueued on the context's HIP stream and calls return without
+ *    waiting, except where a count has to come back to the host (stated per
+ *    function).  rk_sync() waits for everything enqueued so far.
+ *  - A context is not thread-safe; use one per host thread.
+ *
+ * Vocabulary (symbols as in Table 1 of the paper)
+ *  triple    (d, t, p): data / tensor / pipeline parallel sizes, g = d*t*p GPUs
+ *  option    o = z*4 + gc*2 + off: ZeRO stage z in 0..3, gradient
+ *            checkpointing gc, offload off (ZeRO-Offload needs z >= 2)
+ *  plan      (triple, option); plan index inside a job = triple_index*16 + o
+ *  row       (cpu level ci, memory tier mi) of the allocation grid,
+ *            r = ci*n_mem + mi
+ *  candidate (job, row, plan)
+ *  segment   all plans of one job with the same GPU count g
+ *
+ * Array layouts (jb = first job of the range a call works on)
+ *  candidates: 16*n_rows*(triple_off[j]-triple_off[jb]) + (r*nt_j + tl)*16 + o
+ *  segments  : n_rows*(seg_off[j]-seg_off[jb]) + r*ns_j + s
+ *  with nt_j / ns_j the number of triples / segments of job j.
+ */
+#ifndef RUBICK_H
+#define RUBICK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RK_OK                 0
+#define RK_ERR_INVALID_ARG   (-1)   /* null pointer, bad size, bad level order ... */
+#define RK_ERR_CAPACITY      (-2)   /* an output buffer is too small; needed size reported */
+#define RK_ERR_DEVICE        (-3)   /* a HIP call failed; see rk_last_error() */
+#define RK_ERR_UNSUPPORTED   (-4)   /* input outside the documented limits */
+
+#define RK_NO_PLAN            0xFFFFFFFFu
+#define RK_MAX_CPU_LEVELS     64
+#define RK_MAX_MEM_LEVELS     16
+#define RK_MAX_G              65535u   /* largest g_max */
+#define RK_MAX_PP             16383u   /* largest pp_max */
+#define RK_MAX_TRIPLES_PER_JOB 2048u
+#define RK_MAX_JOBS_PER_ROUND 12288u   /* limit of the greedy allocation kernel */
+
+/* reason bits of the optional feasibility output (0 = feasible) */
+#define RK_INFEASIBLE_STRUCT  1u   /* option not allowed, or offload with z < 2 */
+#define RK_INFEASIBLE_GPU_MEM 2u   /* estimated GPU memory above env.gpu_mem_cap */
+#define RK_INFEASIBLE_HOST_MEM 4u  /* offloaded state above the memory tier */
+
+/* packed triple: d in bits 0..15, log2(t) in bits 16..17, p in bits 18..31 */
+#define RK_TRIPLE_D(x)  ((x) & 0xFFFFu)
+#define RK_TRIPLE_T(x)  (1u << (((x) >> 16) & 3u))
+#define RK_TRIPLE_P(x)  ((x) >> 18)
+
+typedef struct rk_ctx rk_ctx;
+
+/* Job descriptors, struct of arrays of length n_jobs, all [device].
+ * Model constants and fitted coefficients of Table 1 plus the coefficients of
+ * the memory estimate (the paper delegates that estimate to the training
+ * frameworks, Sec. 6; the form used here is documented with
+ * rk_eval_candidates). */
+typedef struct {
+    uint32_t n_jobs;
+    const float *P_bytes;       /* parameter size in bytes */
+    const float *seq;           /* s */
+    const float *hidden;        /* h */
+    const float *elem_bytes;    /* bytes per activation element */
+    const float *t_fwd_sample;  /* forward seconds of one sample, whole model, one GPU */
+    const float *k_bwd, *k_sync, *k_opt, *k_opt_off, *k_off, *k_swap, *k_const;
+    const float *mem_state;     /* scale of the model-state bytes */
+    const float *mem_act;       /* activation bytes per token*hidden*layer */
+    const float *mem_act_gc;    /* same, kept with gradient checkpointing */
+    const float *mem_const;     /* constant bytes per GPU */
+    const float *ref_thr;       /* reference throughput that normalises gains */
+    const uint32_t *layers;     /* l */
+    const uint32_t *gbatch;     /* b, global batch (kept fixed, Sec. 3) */
+    const uint32_t *mbatch;     /* micro-batch size mu; b/(d*mu) micro-batches per replica */
+} rk_jobs;
+
+/* Plan space bounds: d*t*p <= g_max, t in {1,2,4,8} and <= tp_max, p <= pp_max
+ * and p | layers, (d*mu) | b.  Option masks: bit v set = value v allowed. */
+typedef struct {
+    uint32_t g_max, tp_max, pp_max;
+    uint32_t zero_mask;         /* 4 bits */
+    uint32_t gc_mask;           /* 2 bits */
+    uint32_t off_mask;          /* 2 bits */
+} rk_plan_bounds;
+
+/* Plan table (CSR over jobs). Buffers are caller-owned [device]; the scalar
+ * fields and the optional host mirrors are written by rk_enumerate_plans. */
+typedef struct {
+    uint32_t *triple_off;       /* [device] [n_jobs+1] */
+    uint32_t *triples;          /* [device] [cap_triples] packed, order g, t, p ascending */
+    uint32_t *seg_off;          /* [device] [n_jobs+1] */
+    uint32_t *seg_g;            /* [device] [cap_segs] GPU count of each segment */
+    uint32_t *seg_first;        /* [device] [cap_segs] first triple of the segment (job-local) */
+    uint64_t cap_triples, cap_segs;
+    uint32_t *h_triple_off;     /* [host] optional mirror [n_jobs+1], may be NULL */
+    uint32_t *h_seg_off;        /* [host] optional mirror [n_jobs+1], may be NULL */
+    /* outputs */
+    uint64_t n_triples, n_segs;
+    uint32_t n_jobs;
+    uint32_t max_triples_per_job, max_segs_per_job;
+    uint32_t option_mask;       /* bit o set: option code o allowed by the bounds */
+} rk_plan_table;
+
+/* Allocation grid: CPU levels and host-memory tiers, both ascending. */
+typedef struct {
+    uint32_t n_cpu;
+    uint32_t cpu_levels[RK_MAX_CPU_LEVELS];   /* >= 1 */
+    uint32_t cpu_mode;          /* 0: CPUs of the whole job; 1: CPUs per GPU (c = level*g) */
+    uint32_t n_mem;
+    float mem_levels_gb[RK_MAX_MEM_LEVELS];   /* GiB */
+    uint32_t mem_mode;          /* 0: GiB of the whole job; 1: GiB per GPU */
+} rk_alloc_grid;
+
+/* Environment constants of Table 1 plus the node shape. */
+typedef struct {
+    float B_intra, B_inter, B_pcie;   /* bytes/s */
+    float gpu_mem_cap;                /* bytes */
+    uint32_t gpus_per_node;
+} rk_env;
+
+typedef struct {
+    uint32_t G, C;              /* free GPUs and CPUs of the cluster */
+    float host_mem_gb;          /* free host memory, GiB */
+} rk_cluster;
+
+/* Result of the allocation for one job; g == 0: not scheduled this round. */
+typedef struct {
+    uint32_t g, c;
+    float mem_gb;
+    uint32_t plan;              /* plan index inside the job, or RK_NO_PLAN */
+    float thr;                  /* predicted samples/s */
+} rk_assign;
+
+/* Context: binds a device and a stream.  hip_stream is a hipStream_t (NULL =
+ * the default stream).  rk_destroy frees the scratch memory. */
+int32_t rk_create(rk_ctx **ctx, int32_t device_id, void *hip_stream);
+int32_t rk_destroy(rk_ctx *ctx);
+int32_t rk_sync(rk_ctx *ctx);
+const char *rk_last_error(const rk_ctx *ctx);
+
+/* Plan enumeration (Sec. 3 "execution plans", Table 1: d*t*p = g; Fig. 6:
+ * only some GPU counts are valid because of the partitioning constraints).
+ * Factorises every g <= g_max on the device and writes the table.
+ * With table->triples == NULL only the counts (n_triples, n_segs, maxima) are
+ * produced.  Too small capacities give RK_ERR_CAPACITY with the counts set.
+ * Waits for the stream (the counts come back to the host). */
+int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                           rk_plan_table *table);
+
+/* Candidate evaluation (Sec. 4, Eq. 1: T_iter = T_cc + T_oo + k_const,
+ * throughput = b / T_iter) with memory-feasibility masking (Sec. 5.2: a plan
+ * must train without running out of GPU memory; host memory is allocated from
+ * the plan's estimate).  Jobs [job_begin, job_end).
+ *   thr  [device] float32 per candidate, 0 where infeasible
+ *   feas [device] optional reason bits per candidate (NULL to skip)
+ *   cap  capacity of thr (and feas) in elements; *n_needed (optional, [host])
+ *        receives the candidate count of the range.
+ * Memory estimate, float32, one rounding per operation in this order:
+ *   Psi = P_bytes/(t*p); kappa = 8 | 2+6/d | 1+7/d | 8/d (ZeRO 0..3),
+ *   with offload 1 (z=2) | 1/d (z=3); S = (mem_state*kappa)*Psi;
+ *   tok = (mu*seq)*hidden; base = ((tok*(l/p))/t)*min(p, b/(d*mu));
+ *   A = mem_act*base, or mem_act_gc*base + (mem_act*tok)/t with checkpointing;
+ *   M_gpu = (S+A)+mem_const <= gpu_mem_cap;
+ *   H_host = ((mem_state*(7/d))*Psi)*g <= tier bytes (GiB*2^30, *g per GPU).
+ * Needs the host offsets: uses the table's host mirrors when present, else
+ * copies two offsets back (waits for the stream). */
+int32_t rk_eval_candidates(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table,
+                           const rk_alloc_grid *grid, const rk_env *env,
+                           uint32_t job_begin, uint32_t job_end,
+                           float *thr, uint8_t *feas_or_null, uint64_t cap, uint64_t *n_needed);
+
+/* Best plan per segment and row (GetBestPlan, Sec. 5.2): maximum throughput,
+ * lowest plan index among equal maxima; a segment without a feasible plan
+ * gives (0, RK_NO_PLAN).  thr must hold non-negative, non-NaN values in the
+ * candidate layout of the same job range.  cap_segs = capacity of the outputs;
+ * *n_needed (optional, [host]) receives n_rows * segments of the range. */
+int32_t rk_best_plan(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_grid *grid,
+                     uint32_t job_begin, uint32_t job_end, const float *thr,
+                     float *best_thr, uint32_t *best_plan, uint64_t cap_segs, uint64_t *n_needed);
+
+/* Resource sensitivity curves from the per-segment maxima (Sec. 5.2, Fig. 6):
+ * per job and row, over the job's GPU counts in ascending order, the best
+ * throughput achievable within that many GPUs, its plan and the smallest GPU
+ * count reaching it (0 while nothing is feasible). Same layout as the inputs. */
+int32_t rk_curves(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_grid *grid,
+                  uint32_t job_begin, uint32_t job_end,
+                  const float *best_thr, const uint32_t *best_plan,
+                  float *curve_thr, uint32_t *curve_plan, uint32_t *curve_g, uint64_t cap_segs);
+
+/* Evaluation + best plan + curves in one pass without materialising the
+ * candidates; results are identical to rk_eval_candidates -> rk_best_plan ->
+ * rk_curves.  best_thr / best_plan may be NULL. */
+int32_t rk_job_curves(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table,
+                      const rk_alloc_grid *grid, const rk_env *env,
+                      uint32_t job_begin, uint32_t job_end,
+                      float *best_thr_or_null, uint32_t *best_plan_or_null,
+                      float *curve_thr, uint32_t *curve_plan, uint32_t *curve_g, uint64_t cap_segs);
+
+/* Greedy allocation over the curves of jobs [job_begin, job_end) (Sec. 5.2:
+ * jobs that gain the most per unit of resource first, GPU slopes before CPU
+ * slopes, memory from the chosen plan last).  The arrays are in segment
+ * layout of the same job range.  float32 slopes ((v1-v0)/ref_thr)/delta.
+ *   assign [device] one record per job of the range
+ *   total  [device] one float: sum of thr/ref_thr over scheduled jobs */
+int32_t rk_allocate(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                    const rk_alloc_grid *grid, const rk_cluster *cluster,
+                    uint32_t job_begin, uint32_t job_end,
+                    const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                    rk_assign *assign, float *total);
+
+/* One scheduling round end to end: enumerate -> evaluate -> best plan ->
+ * curves -> greedy allocation, all on the device.  Waits once for the plan
+ * counts. assign [device] n_jobs records, total [device] one float. */
+int32_t rk_schedule_round(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                          const rk_alloc_grid *grid, const rk_env *env, const rk_cluster *cluster,
+                          rk_assign *assign, float *total);
+
+/* n_rounds independent rounds over one concatenated job array: round r owns
+ * jobs [round_off[r], round_off[r+1]) and cluster clusters[r] (both [host]).
+ * assign [device] n_jobs records, totals [device] n_rounds floats. */
+int32_t rk_schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                           const rk_alloc_grid *grid, const rk_env *env,
+                           uint32_t n_rounds, const uint32_t *round_off, const rk_cluster *clusters,
+                           rk_assign *assign, float *totals);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RUBICK_H */

@@ -1,0 +1,292 @@
+"""Python binding of librubick.so (include/rubick.h): argument marshalling only.
+
+Every computation runs in the HIP library; PyTorch supplies device memory and
+the stream.  Importing the module does not need a GPU; loading the library
+does, and fails loudly when the library has not been built.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librubick.so")
+
+RK_OK, RK_ERR_INVALID_ARG, RK_ERR_CAPACITY, RK_ERR_DEVICE, RK_ERR_UNSUPPORTED = 0, -1, -2, -3, -4
+RK_NO_PLAN = 0xFFFFFFFF
+RK_MAX_CPU_LEVELS, RK_MAX_MEM_LEVELS = 64, 16
+RK_MAX_JOBS_PER_ROUND = 12288
+
+EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
+           "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds")
+
+_JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
+            "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
+_JOB_U32 = ("layers", "gbatch", "mbatch")
+
+
+class rk_jobs(C.Structure):
+    _fields_ = [("n_jobs", C.c_uint32)] + [(n, C.c_void_p) for n in _JOB_F32 + _JOB_U32]
+
+
+class rk_plan_bounds(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("g_max", "tp_max", "pp_max", "zero_mask", "gc_mask", "off_mask")]
+
+
+class rk_plan_table(C.Structure):
+    _fields_ = [("triple_off", C.c_void_p), ("triples", C.c_void_p), ("seg_off", C.c_void_p),
+                ("seg_g", C.c_void_p), ("seg_first", C.c_void_p),
+                ("cap_triples", C.c_uint64), ("cap_segs", C.c_uint64),
+                ("h_triple_off", C.c_void_p), ("h_seg_off", C.c_void_p),
+                ("n_triples", C.c_uint64), ("n_segs", C.c_uint64), ("n_jobs", C.c_uint32),
+                ("max_triples_per_job", C.c_uint32), ("max_segs_per_job", C.c_uint32),
+                ("option_mask", C.c_uint32)]
+
+
+class rk_alloc_grid(C.Structure):
+    _fields_ = [("n_cpu", C.c_uint32), ("cpu_levels", C.c_uint32 * RK_MAX_CPU_LEVELS), ("cpu_mode", C.c_uint32),
+                ("n_mem", C.c_uint32), ("mem_levels_gb", C.c_float * RK_MAX_MEM_LEVELS), ("mem_mode", C.c_uint32)]
+
+
+class rk_env(C.Structure):
+    _fields_ = [("B_intra", C.c_float), ("B_inter", C.c_float), ("B_pcie", C.c_float),
+                ("gpu_mem_cap", C.c_float), ("gpus_per_node", C.c_uint32)]
+
+
+class rk_cluster(C.Structure):
+    _fields_ = [("G", C.c_uint32), ("C", C.c_uint32), ("host_mem_gb", C.c_float)]
+
+
+ASSIGN_DTYPE = np.dtype([("g", np.uint32), ("c", np.uint32), ("mem_gb", np.float32),
+                         ("plan", np.uint32), ("thr", np.float32)])
+
+
+class RkError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"librubick error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library():
+    """Load librubick.so; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2408_08586_amd.build`")
+        lib = C.CDLL(LIB_PATH)
+        for name in EXPORTS:
+            getattr(lib, name).restype = C.c_int32
+        lib.rk_last_error.restype = C.c_char_p
+        _lib = lib
+    return _lib
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def make_bounds(b) -> rk_plan_bounds:
+    return rk_plan_bounds(b.g_max, b.tp_max, b.pp_max, b.zero_mask, b.gc_mask, b.off_mask)
+
+
+def make_grid(g) -> rk_alloc_grid:
+    out = rk_alloc_grid()
+    cpu = [int(v) for v in g.cpu_levels]
+    mem = [float(v) for v in g.mem_levels_gb]
+    out.n_cpu, out.cpu_mode, out.n_mem, out.mem_mode = len(cpu), int(g.cpu_mode), len(mem), int(g.mem_mode)
+    for i, v in enumerate(cpu[:RK_MAX_CPU_LEVELS]):
+        out.cpu_levels[i] = v
+    for i, v in enumerate(mem[:RK_MAX_MEM_LEVELS]):
+        out.mem_levels_gb[i] = v
+    return out
+
+
+def make_env(e) -> rk_env:
+    return rk_env(e.B_intra, e.B_inter, e.B_pcie, e.gpu_mem_cap, e.gpus_per_node)
+
+
+def make_cluster(c) -> rk_cluster:
+    return rk_cluster(int(c.G), int(c.C), float(c.host_mem_gb))
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _check(ctx, rc):
+    if rc != RK_OK:
+        raise RkError(rc, rk_last_error(ctx))
+
+
+class Jobs:
+    """Job descriptors on the device, struct of arrays."""
+
+    def __init__(self, coef: np.ndarray, ints: np.ndarray, device="cuda:0"):
+        import torch
+        coef = np.ascontiguousarray(coef, dtype=np.float32)
+        ints = np.ascontiguousarray(ints, dtype=np.uint32)
+        assert coef.ndim == 2 and coef.shape[1] == len(_JOB_F32) and ints.shape == (coef.shape[0], len(_JOB_U32))
+        self.n_jobs = coef.shape[0]
+        self.f32 = torch.from_numpy(np.ascontiguousarray(coef.T)).to(device)                       # [17, J]
+        self.u32 = torch.from_numpy(np.ascontiguousarray(ints.T).view(np.int32)).to(device)        # [3, J]
+        self.c = rk_jobs()
+        self.c.n_jobs = self.n_jobs
+        stride = self.n_jobs * 4
+        for k, name in enumerate(_JOB_F32):
+            setattr(self.c, name, self.f32.data_ptr() + k * stride)
+        for k, name in enumerate(_JOB_U32):
+            setattr(self.c, name, self.u32.data_ptr() + k * stride)
+
+    @property
+    def ref_thr(self):
+        return self.f32[len(_JOB_F32) - 1]
+
+
+class PlanTable:
+    """Device buffers of a plan table plus the C struct that points at them."""
+
+    def __init__(self, n_jobs, cap_triples, cap_segs, device="cuda:0"):
+        import torch
+        i32 = dict(dtype=torch.int32, device=device)
+        self.triple_off = torch.zeros(n_jobs + 1, **i32)
+        self.seg_off = torch.zeros(n_jobs + 1, **i32)
+        self.triples = torch.zeros(max(cap_triples, 1), **i32)
+        self.seg_g = torch.zeros(max(cap_segs, 1), **i32)
+        self.seg_first = torch.zeros(max(cap_segs, 1), **i32)
+        self.h_triple_off = np.zeros(n_jobs + 1, np.uint32)
+        self.h_seg_off = np.zeros(n_jobs + 1, np.uint32)
+        self.c = rk_plan_table()
+        self.c.triple_off, self.c.triples = self.triple_off.data_ptr(), self.triples.data_ptr()
+        self.c.seg_off, self.c.seg_g, self.c.seg_first = (self.seg_off.data_ptr(), self.seg_g.data_ptr(),
+                                                          self.seg_first.data_ptr())
+        self.c.cap_triples, self.c.cap_segs = cap_triples, cap_segs
+        self.c.h_triple_off = self.h_triple_off.ctypes.data
+        self.c.h_seg_off = self.h_seg_off.ctypes.data
+        self.c.n_jobs = n_jobs
+
+    n_triples = property(lambda self: int(self.c.n_triples))
+    n_segs = property(lambda self: int(self.c.n_segs))
+    n_jobs = property(lambda self: int(self.c.n_jobs))
+
+    def n_candidates(self, n_rows, jb=0, je=None):
+        je = self.n_jobs if je is None else je
+        return 16 * n_rows * int(self.h_triple_off[je] - self.h_triple_off[jb])
+
+    def n_segments(self, n_rows, jb=0, je=None):
+        je = self.n_jobs if je is None else je
+        return n_rows * int(self.h_seg_off[je] - self.h_seg_off[jb])
+
+    def unpack_triples(self) -> np.ndarray:
+        """Host copy of the triples as (d, t, p) rows."""
+        x = self.triples[:self.n_triples].cpu().numpy().view(np.uint32)
+        return np.stack([x & 0xFFFF, 1 << ((x >> 16) & 3), x >> 18], axis=1).astype(np.uint32)
+
+
+# ------------------------------------------------------------------ the C ABI, same names
+def rk_create(device_id=0, stream=None):
+    """stream: a torch.cuda.Stream, a raw hipStream_t value, or None for the current torch stream."""
+    import torch
+    lib = load_library()
+    if stream is None:
+        stream = torch.cuda.current_stream(device_id).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    ctx = C.c_void_p()
+    rc = lib.rk_create(C.byref(ctx), C.c_int32(device_id), C.c_void_p(stream))
+    if rc != RK_OK:
+        raise RkError(rc, "rk_create failed")
+    return ctx
+
+
+def rk_destroy(ctx):
+    return load_library().rk_destroy(ctx)
+
+
+def rk_sync(ctx):
+    _check(ctx, load_library().rk_sync(ctx))
+
+
+def rk_last_error(ctx) -> str:
+    return load_library().rk_last_error(ctx).decode()
+
+
+def rk_enumerate_plans(ctx, jobs: Jobs, bounds: rk_plan_bounds, table: rk_plan_table):
+    _check(ctx, load_library().rk_enumerate_plans(ctx, C.byref(jobs.c), C.byref(bounds), C.byref(table)))
+
+
+def rk_eval_candidates(ctx, jobs: Jobs, table: rk_plan_table, grid: rk_alloc_grid, env: rk_env,
+                       job_begin, job_end, thr, feas=None):
+    need = C.c_uint64(0)
+    _check(ctx, load_library().rk_eval_candidates(ctx, C.byref(jobs.c), C.byref(table), C.byref(grid), C.byref(env),
+                                                  C.c_uint32(job_begin), C.c_uint32(job_end), _ptr(thr), _ptr(feas),
+                                                  C.c_uint64(0 if thr is None else thr.numel()), C.byref(need)))
+    return need.value
+
+
+def rk_best_plan(ctx, table: rk_plan_table, grid: rk_alloc_grid, job_begin, job_end, thr, best_thr, best_plan):
+    need = C.c_uint64(0)
+    _check(ctx, load_library().rk_best_plan(ctx, C.byref(table), C.byref(grid), C.c_uint32(job_begin),
+                                            C.c_uint32(job_end), _ptr(thr), _ptr(best_thr), _ptr(best_plan),
+                                            C.c_uint64(0 if best_thr is None else best_thr.numel()), C.byref(need)))
+    return need.value
+
+
+def rk_curves(ctx, table, grid, job_begin, job_end, best_thr, best_plan, curve_thr, curve_plan, curve_g):
+    _check(ctx, load_library().rk_curves(ctx, C.byref(table), C.byref(grid), C.c_uint32(job_begin),
+                                         C.c_uint32(job_end), _ptr(best_thr), _ptr(best_plan), _ptr(curve_thr),
+                                         _ptr(curve_plan), _ptr(curve_g), C.c_uint64(curve_thr.numel())))
+
+
+def rk_job_curves(ctx, jobs: Jobs, table, grid, env, job_begin, job_end, best_thr, best_plan,
+                  curve_thr, curve_plan, curve_g):
+    _check(ctx, load_library().rk_job_curves(ctx, C.byref(jobs.c), C.byref(table), C.byref(grid), C.byref(env),
+                                             C.c_uint32(job_begin), C.c_uint32(job_end), _ptr(best_thr),
+                                             _ptr(best_plan), _ptr(curve_thr), _ptr(curve_plan), _ptr(curve_g),
+                                             C.c_uint64(curve_thr.numel())))
+
+
+def rk_allocate(ctx, ref_thr, table, grid, cluster: rk_cluster, job_begin, job_end, best_thr, best_plan,
+                curve_thr, assign, total):
+    _check(ctx, load_library().rk_allocate(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.byref(cluster),
+                                           C.c_uint32(job_begin), C.c_uint32(job_end), _ptr(best_thr),
+                                           _ptr(best_plan), _ptr(curve_thr), _ptr(assign), _ptr(total)))
+
+
+def rk_schedule_round(ctx, jobs: Jobs, bounds, grid, env, cluster, assign, total):
+    _check(ctx, load_library().rk_schedule_round(ctx, C.byref(jobs.c), C.byref(bounds), C.byref(grid), C.byref(env),
+                                                 C.byref(cluster), _ptr(assign), _ptr(total)))
+
+
+def rk_schedule_rounds(ctx, jobs: Jobs, bounds, grid, env, round_off: np.ndarray, clusters, assign, totals):
+    round_off = np.ascontiguousarray(round_off, dtype=np.uint32)
+    n_rounds = len(round_off) - 1
+    arr = (rk_cluster * n_rounds)(*clusters)
+    _check(ctx, load_library().rk_schedule_rounds(ctx, C.byref(jobs.c), C.byref(bounds), C.byref(grid), C.byref(env),
+                                                  C.c_uint32(n_rounds), round_off.ctypes.data_as(C.c_void_p), arr,
+                                                  _ptr(assign), _ptr(totals)))
+
+
+# ------------------------------------------------------------------ allocation helpers (no arithmetic)
+def enumerate_to_table(ctx, jobs: Jobs, bounds: rk_plan_bounds, device="cuda:0") -> PlanTable:
+    """Sizing call, allocation, fill call."""
+    probe = rk_plan_table()
+    rk_enumerate_plans(ctx, jobs, bounds, probe)
+    table = PlanTable(jobs.n_jobs, int(probe.n_triples), int(probe.n_segs), device)
+    rk_enumerate_plans(ctx, jobs, bounds, table.c)
+    return table
+
+
+def new_assign(n_jobs, device="cuda:0"):
+    import torch
+    return torch.zeros(n_jobs * ASSIGN_DTYPE.itemsize, dtype=torch.uint8, device=device)
+
+
+def assign_to_numpy(t) -> np.ndarray:
+    return t.cpu().numpy().view(ASSIGN_DTYPE)
+
+
+def u32(t) -> np.ndarray:
+    """Host copy of an int32 device tensor reinterpreted as uint32."""
+    return t.cpu().numpy().view(np.uint32)

@@ -1,0 +1,257 @@
+// Plan enumeration on the device (paper Sec. 3: 3D-parallel plans with
+// d*t*p = g, Table 1; Fig. 6: only some GPU counts are valid).
+//
+// One workgroup per job.  Instead of testing every g it builds the divisor
+// lists of b/mu (data-parallel sizes) and of the layer count (pipeline sizes),
+// forms the products d*t*p <= g_max with t in {1,2,4,8}, and orders them by
+// the key (g, t, p) with a rank sort in LDS.  Runs twice: once to count, once
+// to fill after the exclusive scan of the counts.
+#include "rk_internal.h"
+
+namespace {
+
+constexpr int ENUM_THREADS = 256;
+constexpr uint32_t MAX_T = RK_MAX_TRIPLES_PER_JOB;
+constexpr uint32_t MAX_DIV = 1024;
+
+enum { TOT_NT_LO = 0, TOT_NT_HI, TOT_NS_LO, TOT_NS_HI, TOT_MAX_T, TOT_MAX_S, TOT_ERR, TOT_WORDS };
+enum { ERR_TOO_MANY_TRIPLES = 1, ERR_TOO_MANY_DIVISORS = 2 };
+
+// exclusive prefix sum of one value per thread over the workgroup
+__device__ uint32_t block_excl_scan(uint32_t v, uint32_t *lds, uint32_t *total) {
+    const uint32_t tid = threadIdx.x, nth = blockDim.x;
+    lds[tid] = v;
+    __syncthreads();
+    for (uint32_t off = 1; off < nth; off <<= 1) {
+        uint32_t add = tid >= off ? lds[tid - off] : 0u;
+        __syncthreads();
+        lds[tid] += add;
+        __syncthreads();
+    }
+    const uint32_t incl = lds[tid];
+    *total = lds[nth - 1];
+    __syncthreads();
+    return incl - v;
+}
+
+template <bool FILL>
+__global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
+    const uint32_t *__restrict__ layers, const uint32_t *__restrict__ gbatch,
+    const uint32_t *__restrict__ mbatch, rk_plan_bounds bounds,
+    uint32_t *__restrict__ cnt_t, uint32_t *__restrict__ cnt_s,
+    const uint32_t *__restrict__ triple_off, const uint32_t *__restrict__ seg_off,
+    uint32_t *__restrict__ triples, uint32_t *__restrict__ seg_g, uint32_t *__restrict__ seg_first,
+    uint32_t *__restrict__ totals) {
+    __shared__ uint32_t dlist[MAX_DIV], plist[MAX_DIV];
+    __shared__ uint32_t keys[MAX_T], sorted[MAX_T];
+    __shared__ uint32_t scan_tmp[ENUM_THREADS];
+    __shared__ uint32_t nd, np, nk;
+
+    const uint32_t j = blockIdx.x, tid = threadIdx.x;
+    const uint32_t l = layers[j], b = gbatch[j], mu = mbatch[j];
+    if (tid == 0) { nd = 0; np = 0; nk = 0; }
+    __syncthreads();
+
+    const bool any = l > 0 && b > 0 && mu > 0 && (b % mu) == 0;
+    const uint32_t n = any ? b / mu : 0;
+    // divisors of n (data-parallel sizes) and of l (pipeline sizes), unordered
+    const uint32_t dmax = n < bounds.g_max ? n : bounds.g_max;
+    for (uint32_t d = tid + 1; d <= dmax; d += ENUM_THREADS)
+        if (n % d == 0) { uint32_t i = atomicAdd(&nd, 1u); if (i < MAX_DIV) dlist[i] = d; }
+    uint32_t pmax = l < bounds.pp_max ? l : bounds.pp_max;
+    pmax = pmax < bounds.g_max ? pmax : bounds.g_max;
+    if (!any) pmax = 0;
+    for (uint32_t p = tid + 1; p <= pmax; p += ENUM_THREADS)
+        if (l % p == 0) { uint32_t i = atomicAdd(&np, 1u); if (i < MAX_DIV) plist[i] = p; }
+    __syncthreads();
+    uint32_t err = 0;
+    if (nd > MAX_DIV || np > MAX_DIV) err |= ERR_TOO_MANY_DIVISORS;
+    const uint32_t cd = nd < MAX_DIV ? nd : MAX_DIV, cp = np < MAX_DIV ? np : MAX_DIV;
+
+    // products d * t * p <= g_max
+    uint32_t nlt = 0;                                   // tensor-parallel sizes allowed: 2^0..2^(nlt-1)
+    for (uint32_t t = 1; t <= 8 && t <= bounds.tp_max; t <<= 1) ++nlt;
+    const uint64_t combos = (uint64_t)cd * cp * nlt;
+    for (uint64_t c = tid; c < combos; c += ENUM_THREADS) {
+        const uint32_t lt = (uint32_t)(c % nlt);
+        const uint64_t r = c / nlt;
+        const uint32_t p = plist[r % cp], d = dlist[r / cp];
+        const uint64_t g = ((uint64_t)d * p) << lt;
+        if (g <= bounds.g_max) {
+            const uint32_t i = atomicAdd(&nk, 1u);
+            if (i < MAX_T) keys[i] = ((uint32_t)g << 16) | (lt << 14) | p;
+        }
+    }
+    __syncthreads();
+    if (nk > MAX_T) err |= ERR_TOO_MANY_TRIPLES;
+    const uint32_t cnt = nk < MAX_T ? nk : MAX_T;
+
+    // rank sort: keys are distinct, the rank is the number of smaller keys
+    for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) {
+        const uint32_t k = keys[i];
+        uint32_t rank = 0;
+        for (uint32_t x = 0; x < cnt; ++x) rank += keys[x] < k ? 1u : 0u;
+        sorted[rank] = k;
+    }
+    __syncthreads();
+
+    // segments: runs of equal g.  Each thread owns a contiguous chunk.
+    const uint32_t chunk = (cnt + ENUM_THREADS - 1) / ENUM_THREADS;
+    const uint32_t lo = tid * chunk < cnt ? tid * chunk : cnt;
+    const uint32_t hi = lo + chunk < cnt ? lo + chunk : cnt;
+    uint32_t starts = 0;
+    for (uint32_t i = lo; i < hi; ++i)
+        starts += (i == 0 || (sorted[i] >> 16) != (sorted[i - 1] >> 16)) ? 1u : 0u;
+    uint32_t nseg;
+    uint32_t sidx = block_excl_scan(starts, scan_tmp, &nseg);
+
+    if (!FILL) {
+        if (tid == 0) {
+            cnt_t[j] = cnt;
+            cnt_s[j] = nseg;
+            if (err) atomicOr(&totals[TOT_ERR], err);
+        }
+        return;
+    }
+    const uint32_t t0 = triple_off[j], s0 = seg_off[j];
+    for (uint32_t i = lo; i < hi; ++i) {
+        const uint32_t k = sorted[i];
+        const uint32_t g = k >> 16, lt = (k >> 14) & 3u, p = k & 0x3FFFu;
+        const uint32_t d = g / (p << lt);
+        triples[t0 + i] = d | (lt << 16) | (p << 18);
+        if (i == 0 || g != (sorted[i - 1] >> 16)) {
+            seg_g[s0 + sidx] = g;
+            seg_first[s0 + sidx] = i;
+            ++sidx;
+        }
+    }
+}
+
+// exclusive scan of the per-job counts, totals and maxima (one workgroup)
+__global__ __launch_bounds__(1024) void k_scan_counts(const uint32_t *__restrict__ cnt_t,
+                                                      const uint32_t *__restrict__ cnt_s, uint32_t n_jobs,
+                                                      uint32_t *__restrict__ off_t, uint32_t *__restrict__ off_s,
+                                                      uint32_t *__restrict__ totals) {
+    __shared__ unsigned long long part_t[1024], part_s[1024];
+    __shared__ uint32_t max_t[1024], max_s[1024];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t chunk = (n_jobs + 1023u) / 1024u;
+    const uint32_t lo = tid * chunk < n_jobs ? tid * chunk : n_jobs;
+    const uint32_t hi = lo + chunk < n_jobs ? lo + chunk : n_jobs;
+    unsigned long long st = 0, ss = 0;
+    uint32_t mt = 0, ms = 0;
+    for (uint32_t j = lo; j < hi; ++j) {
+        st += cnt_t[j]; ss += cnt_s[j];
+        mt = cnt_t[j] > mt ? cnt_t[j] : mt;
+        ms = cnt_s[j] > ms ? cnt_s[j] : ms;
+    }
+    part_t[tid] = st; part_s[tid] = ss; max_t[tid] = mt; max_s[tid] = ms;
+    __syncthreads();
+    for (uint32_t off = 1; off < 1024; off <<= 1) {
+        unsigned long long at = tid >= off ? part_t[tid - off] : 0ull;
+        unsigned long long as = tid >= off ? part_s[tid - off] : 0ull;
+        uint32_t xt = tid >= off ? max_t[tid - off] : 0u, xs = tid >= off ? max_s[tid - off] : 0u;
+        __syncthreads();
+        part_t[tid] += at; part_s[tid] += as;
+        max_t[tid] = max_t[tid] > xt ? max_t[tid] : xt;
+        max_s[tid] = max_s[tid] > xs ? max_s[tid] : xs;
+        __syncthreads();
+    }
+    unsigned long long rt = part_t[tid] - st, rs = part_s[tid] - ss;   // exclusive
+    for (uint32_t j = lo; j < hi; ++j) {
+        off_t[j] = (uint32_t)rt; off_s[j] = (uint32_t)rs;
+        rt += cnt_t[j]; rs += cnt_s[j];
+    }
+    if (tid == 1023) {
+        const unsigned long long tt = part_t[1023], ts = part_s[1023];
+        off_t[n_jobs] = (uint32_t)tt; off_s[n_jobs] = (uint32_t)ts;
+        totals[TOT_NT_LO] = (uint32_t)tt; totals[TOT_NT_HI] = (uint32_t)(tt >> 32);
+        totals[TOT_NS_LO] = (uint32_t)ts; totals[TOT_NS_HI] = (uint32_t)(ts >> 32);
+        totals[TOT_MAX_T] = max_t[1023]; totals[TOT_MAX_S] = max_s[1023];
+    }
+}
+
+__global__ void k_zero_words(uint32_t *p, uint32_t n) {
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+}  // namespace
+
+extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                                      rk_plan_table *table) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    if (!jobs || !bounds || !table) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (jobs->n_jobs > 0 && (!jobs->layers || !jobs->gbatch || !jobs->mbatch)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "job arrays are null");
+    if (bounds->g_max < 1 || bounds->g_max > RK_MAX_G) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "g_max must be in 1..%u", RK_MAX_G);
+    if (bounds->pp_max < 1 || bounds->pp_max > RK_MAX_PP) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "pp_max must be in 1..%u", RK_MAX_PP);
+    if (bounds->tp_max < 1) return rk_fail(ctx, RK_ERR_INVALID_ARG, "tp_max below 1");
+    if (bounds->zero_mask > 0xF || bounds->gc_mask > 3 || bounds->off_mask > 3)
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "option mask has unknown bits");
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+
+    const uint32_t J = jobs->n_jobs;
+    uint32_t opt = 0;
+    for (uint32_t o = 0; o < 16; ++o) {
+        const uint32_t z = o >> 2, gc = (o >> 1) & 1u, off = o & 1u;
+        if (((bounds->zero_mask >> z) & 1u) && ((bounds->gc_mask >> gc) & 1u) && ((bounds->off_mask >> off) & 1u))
+            opt |= 1u << o;
+    }
+    table->option_mask = opt;
+    table->n_jobs = J;
+    table->n_triples = table->n_segs = 0;
+    table->max_triples_per_job = table->max_segs_per_job = 0;
+
+    uint32_t *cnt_t, *cnt_s, *totals, *off_t, *off_s;
+    int32_t rc;
+    if ((rc = rk_scratch(ctx, SL_CNT_T, (size_t)(2 * (size_t)J + 2) * 4, (void **)&cnt_t))) return rc;
+    if ((rc = rk_scratch(ctx, SL_CNT_S, (size_t)(2 * (size_t)J + 2) * 4, (void **)&cnt_s))) return rc;
+    if ((rc = rk_scratch(ctx, SL_TOTALS, TOT_WORDS * 4, (void **)&totals))) return rc;
+    off_t = cnt_t + J;           // [J+1] after the counts
+    off_s = cnt_s + J;
+
+    k_zero_words<<<1, 64, 0, ctx->stream>>>(totals, TOT_WORDS);
+    if (J > 0) {
+        k_enumerate<false><<<J, ENUM_THREADS, 0, ctx->stream>>>(jobs->layers, jobs->gbatch, jobs->mbatch, *bounds,
+                                                                 cnt_t, cnt_s, nullptr, nullptr, nullptr, nullptr,
+                                                                 nullptr, totals);
+        RK_CHECK_LAUNCH(ctx, "k_enumerate<count>");
+    }
+    k_scan_counts<<<1, 1024, 0, ctx->stream>>>(cnt_t, cnt_s, J, off_t, off_s, totals);
+    RK_CHECK_LAUNCH(ctx, "k_scan_counts");
+    uint32_t *h = ctx->h_pinned;
+    RK_HIP(ctx, hipMemcpyAsync(h, totals, TOT_WORDS * 4, hipMemcpyDeviceToHost, ctx->stream));
+    RK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+
+    if (h[TOT_ERR] & ERR_TOO_MANY_TRIPLES) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "a job has more than %u triples", MAX_T);
+    if (h[TOT_ERR] & ERR_TOO_MANY_DIVISORS) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "a job has more than %u candidate d or p sizes", MAX_DIV);
+    const uint64_t nt = ((uint64_t)h[TOT_NT_HI] << 32) | h[TOT_NT_LO];
+    const uint64_t ns = ((uint64_t)h[TOT_NS_HI] << 32) | h[TOT_NS_LO];
+    if (nt > 0xFFFFFFFFull) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 2^32-1 triples");
+    table->n_triples = nt;
+    table->n_segs = ns;
+    table->max_triples_per_job = h[TOT_MAX_T];
+    table->max_segs_per_job = h[TOT_MAX_S];
+
+    if (!table->triples) return RK_OK;                        // sizing call
+    if (!table->triple_off || !table->seg_off || !table->seg_g || !table->seg_first)
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "table buffer is null");
+    if (table->cap_triples < nt || table->cap_segs < ns)
+        return rk_fail(ctx, RK_ERR_CAPACITY, "table too small: need %llu triples and %llu segments",
+                       (unsigned long long)nt, (unsigned long long)ns);
+
+    RK_HIP(ctx, hipMemcpyAsync(table->triple_off, off_t, ((size_t)J + 1) * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    RK_HIP(ctx, hipMemcpyAsync(table->seg_off, off_s, ((size_t)J + 1) * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    if (J > 0) {
+        k_enumerate<true><<<J, ENUM_THREADS, 0, ctx->stream>>>(jobs->layers, jobs->gbatch, jobs->mbatch, *bounds,
+                                                                nullptr, nullptr, off_t, off_s, table->triples,
+                                                                table->seg_g, table->seg_first, totals);
+        RK_CHECK_LAUNCH(ctx, "k_enumerate<fill>");
+    }
+    if (table->h_triple_off && table->h_seg_off) {
+        RK_HIP(ctx, hipMemcpyAsync(table->h_triple_off, off_t, ((size_t)J + 1) * 4, hipMemcpyDeviceToHost, ctx->stream));
+        RK_HIP(ctx, hipMemcpyAsync(table->h_seg_off, off_s, ((size_t)J + 1) * 4, hipMemcpyDeviceToHost, ctx->stream));
+        RK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    }
+    return RK_OK;
+}

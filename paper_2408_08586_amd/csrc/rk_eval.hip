@@ -1,0 +1,285 @@
+// Materialising path: candidate evaluation (paper Sec. 4, Eq. 1) with
+// feasibility masking, the segmented best-plan reduction (GetBestPlan,
+// Sec. 5.2) and the curve prefix maximum (Sec. 5.2, Fig. 6).
+#include "rk_internal.h"
+#include "rk_model.h"
+
+namespace {
+
+constexpr int EVAL_THREADS = 256;
+constexpr int TRIPLES_PER_BLOCK = EVAL_THREADS / 4;
+
+// ---------------------------------------------------------------- evaluation
+// A thread owns (triple, ZeRO stage z): the four options gc x off of that
+// stage, i.e. 16 contiguous bytes of every row.  A wavefront therefore writes
+// 1 KiB contiguous per row.  Everything that does not depend on the row is
+// computed once per thread; the CPU-dependent swap term once per CPU level.
+template <bool WITH_FEAS>
+__global__ __launch_bounds__(EVAL_THREADS) void k_eval(JobDev jobs, TableDev tb, GridDev grid, rk_env env,
+                                                       uint32_t jb, uint32_t option_mask, uint32_t c_per_block,
+                                                       float *__restrict__ thr, uint8_t *__restrict__ feas) {
+    const uint32_t j = jb + blockIdx.y;
+    const uint32_t t0 = tb.triple_off[j];
+    const uint32_t nt = tb.triple_off[j + 1] - t0;
+    const uint32_t tl = blockIdx.x * TRIPLES_PER_BLOCK + (threadIdx.x >> 2);
+    if (tl >= nt) return;
+    const uint32_t z = threadIdx.x & 3u;
+    const uint32_t n_rows = grid.n_cpu * grid.n_mem;
+    const uint64_t cbase = 16ull * n_rows * (uint64_t)(t0 - tb.triple_off[jb]);
+
+    const Job J = load_job(jobs, j);
+    const Triple T = triple_terms(J, env, tb.triples[t0 + tl]);
+
+    // options without offload: o = z*4 + gc*2
+    float plain[2];
+    uint32_t why_plain[2];
+#pragma unroll
+    for (uint32_t gc = 0; gc < 2; ++gc) {
+        const bool allowed = (option_mask >> (z * 4 + gc * 2)) & 1u;
+        const bool fits = gpu_mem_fits(J, env, T, z, gc, 0);
+        why_plain[gc] = allowed ? (fits ? 0u : RK_INFEASIBLE_GPU_MEM) : RK_INFEASIBLE_STRUCT;
+        plain[gc] = why_plain[gc] ? 0.f : thr_plain(J, T, z, gc);
+    }
+    // options with offload: o = z*4 + gc*2 + 1, need z >= 2
+    uint32_t why_off[2];
+#pragma unroll
+    for (uint32_t gc = 0; gc < 2; ++gc) {
+        const bool allowed = z >= 2 && ((option_mask >> (z * 4 + gc * 2 + 1)) & 1u);
+        why_off[gc] = allowed ? (gpu_mem_fits(J, env, T, z, gc, 1) ? 0u : RK_INFEASIBLE_GPU_MEM)
+                              : RK_INFEASIBLE_STRUCT;
+    }
+    const bool any_off = z >= 2 && (!(why_off[0] & RK_INFEASIBLE_STRUCT) || !(why_off[1] & RK_INFEASIBLE_STRUCT));
+    Offload O = {};
+    float need_host = 0.f;
+    if (any_off) {
+        O = offload_terms(J, env, T);
+        need_host = host_bytes_needed(J, T);
+    }
+
+    const uint32_t c_lo = blockIdx.z * c_per_block;
+    const uint32_t c_hi = c_lo + c_per_block < grid.n_cpu ? c_lo + c_per_block : grid.n_cpu;
+    for (uint32_t ci = c_lo; ci < c_hi; ++ci) {
+        float off_thr[2] = {0.f, 0.f};
+        if (any_off) {
+            const float sw = swap_term(J, O, cpus_of(grid, ci, T.g));
+            off_thr[0] = thr_offload(T, O, 0, sw);
+            off_thr[1] = thr_offload(T, O, 1, sw);
+        }
+        for (uint32_t mi = 0; mi < grid.n_mem; ++mi) {
+            uint32_t w0 = why_off[0], w1 = why_off[1];
+            if (any_off && !(need_host <= tier_bytes(grid, mi, T.g))) {
+                if (!(w0 & RK_INFEASIBLE_STRUCT)) w0 |= RK_INFEASIBLE_HOST_MEM;
+                if (!(w1 & RK_INFEASIBLE_STRUCT)) w1 |= RK_INFEASIBLE_HOST_MEM;
+            }
+            float4 v;
+            v.x = plain[0];
+            v.y = w0 ? 0.f : off_thr[0];
+            v.z = plain[1];
+            v.w = w1 ? 0.f : off_thr[1];
+            const uint64_t idx = cbase + ((uint64_t)(ci * grid.n_mem + mi) * nt + tl) * 16 + z * 4;
+            *reinterpret_cast<float4 *>(thr + idx) = v;
+            if (WITH_FEAS) {
+                const uint32_t packed = why_plain[0] | (w0 << 8) | (why_plain[1] << 16) | (w1 << 24);
+                *reinterpret_cast<uint32_t *>(feas + idx) = packed;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------- best plan per segment
+// One wavefront per (job, row).  Lanes read the row as float4 (four options of
+// one triple), four lanes reduce a triple, the per-triple maxima go to LDS and
+// lanes then reduce the job's segments.  Comparison on the packed key
+// (throughput bits, inverted plan index): larger throughput, then lower index.
+constexpr int BEST_WAVES = 4;
+
+__device__ __forceinline__ unsigned long long max_u64(unsigned long long a, unsigned long long b) {
+    return a > b ? a : b;
+}
+
+template <int CTRL>
+__device__ __forceinline__ unsigned long long dpp_u64(unsigned long long v) {
+    const uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    const uint32_t l2 = (uint32_t)__builtin_amdgcn_update_dpp((int)lo, (int)lo, CTRL, 0xF, 0xF, false);
+    const uint32_t h2 = (uint32_t)__builtin_amdgcn_update_dpp((int)hi, (int)hi, CTRL, 0xF, 0xF, false);
+    return ((unsigned long long)h2 << 32) | l2;
+}
+
+__global__ __launch_bounds__(BEST_WAVES * 64) void k_best_plan(TableDev tb, uint32_t n_rows, uint32_t jb,
+                                                               uint32_t je, uint32_t lds_per_wave,
+                                                               const float *__restrict__ thr,
+                                                               float *__restrict__ best_thr,
+                                                               uint32_t *__restrict__ best_plan) {
+    extern __shared__ unsigned long long lds_keys[];
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    const uint64_t row_id = (uint64_t)blockIdx.x * BEST_WAVES + wave;
+    const uint64_t total_rows = (uint64_t)(je - jb) * n_rows;
+    unsigned long long *keys = lds_keys + (size_t)wave * lds_per_wave;
+
+    const bool active = row_id < total_rows;
+    uint32_t j = 0, r = 0, nt = 0, ns = 0, t0 = 0, s0 = 0;
+    if (active) {
+        j = jb + (uint32_t)(row_id / n_rows);
+        r = (uint32_t)(row_id % n_rows);
+        t0 = tb.triple_off[j]; nt = tb.triple_off[j + 1] - t0;
+        s0 = tb.seg_off[j]; ns = tb.seg_off[j + 1] - s0;
+        const uint64_t cbase = 16ull * n_rows * (uint64_t)(t0 - tb.triple_off[jb]) + (uint64_t)r * nt * 16;
+        const float4 *row = reinterpret_cast<const float4 *>(thr + cbase);
+        const uint32_t n_vec = nt * 4;                      // float4 elements in the row
+        for (uint32_t base = 0; base < n_vec; base += 64) {
+            const uint32_t i = base + lane;
+            unsigned long long k = 0;
+            if (i < n_vec) {
+                const float4 v = row[i];
+                const uint32_t plan0 = i * 4;
+                k = make_key(v.x, plan0);
+                k = max_u64(k, make_key(v.y, plan0 + 1));
+                k = max_u64(k, make_key(v.z, plan0 + 2));
+                k = max_u64(k, make_key(v.w, plan0 + 3));
+            }
+            k = max_u64(k, dpp_u64<0xB1>(k));               // quad_perm [1,0,3,2]
+            k = max_u64(k, dpp_u64<0x4E>(k));               // quad_perm [2,3,0,1]
+            if ((lane & 3u) == 0 && i < n_vec) keys[i >> 2] = k;
+        }
+    }
+    __syncthreads();
+    if (!active) return;
+    const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]) + (uint64_t)r * ns;
+    for (uint32_t s = lane; s < ns; s += 64) {
+        const uint32_t first = tb.seg_first[s0 + s];
+        const uint32_t last = s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt;
+        unsigned long long k = 0;
+        for (uint32_t t = first; t < last; ++t) k = max_u64(k, keys[t]);
+        best_thr[sbase + s] = key_thr(k);
+        best_plan[sbase + s] = key_plan(k);
+    }
+}
+
+// ------------------------------------------------------------------- curves
+// One thread per (job, row): running maximum over the job's GPU counts.
+__global__ __launch_bounds__(256) void k_curves(TableDev tb, uint32_t n_rows, uint32_t jb, uint32_t je,
+                                                const float *__restrict__ best_thr,
+                                                const uint32_t *__restrict__ best_plan,
+                                                float *__restrict__ curve_thr, uint32_t *__restrict__ curve_plan,
+                                                uint32_t *__restrict__ curve_g) {
+    const uint64_t row_id = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (row_id >= (uint64_t)(je - jb) * n_rows) return;
+    const uint32_t j = jb + (uint32_t)(row_id / n_rows), r = (uint32_t)(row_id % n_rows);
+    const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
+    const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]) + (uint64_t)r * ns;
+    float cur = 0.f;
+    uint32_t plan = RK_NO_PLAN, g = 0;
+    for (uint32_t s = 0; s < ns; ++s) {
+        const float v = best_thr[sbase + s];
+        if (v > cur) { cur = v; plan = best_plan[sbase + s]; g = tb.seg_g[s0 + s]; }
+        curve_thr[sbase + s] = cur;
+        curve_plan[sbase + s] = plan;
+        curve_g[sbase + s] = g;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t rk_eval_candidates(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table,
+                           const rk_alloc_grid *grid, const rk_env *env, uint32_t jb, uint32_t je,
+                           float *thr, uint8_t *feas, uint64_t cap, uint64_t *n_needed) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if (!jobs) return rk_fail(ctx, RK_ERR_INVALID_ARG, "jobs is null");
+    if ((rc = rk_check_table(ctx, table, jb, je))) return rc;
+    if (jobs->n_jobs != table->n_jobs) return rk_fail(ctx, RK_ERR_INVALID_ARG, "jobs and table disagree on n_jobs");
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    if ((rc = rk_check_env(ctx, env))) return rc;
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    uint64_t nt, ns;
+    if ((rc = rk_range_offsets(ctx, table, jb, je, &nt, &ns))) return rc;
+    const uint64_t n_rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    const uint64_t need = 16ull * n_rows * nt;
+    if (n_needed) *n_needed = need;
+    if (need == 0) return RK_OK;
+    if (!thr) return rk_fail(ctx, RK_ERR_INVALID_ARG, "thr is null");
+    if (cap < need) return rk_fail(ctx, RK_ERR_CAPACITY, "thr holds %llu candidates, %llu needed",
+                                   (unsigned long long)cap, (unsigned long long)need);
+    if (((uintptr_t)thr & 15u) || ((uintptr_t)feas & 15u)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "output not 16-byte aligned");
+
+    const uint32_t bx = (table->max_triples_per_job + TRIPLES_PER_BLOCK - 1) / TRIPLES_PER_BLOCK;
+    const uint32_t nj = je - jb;
+    // split the CPU levels over blockIdx.z when there are few jobs, so the chip is filled
+    uint32_t split = 1;
+    const uint64_t blocks = (uint64_t)bx * nj;
+    if (blocks < 2048) {
+        split = (uint32_t)((2048 + blocks - 1) / blocks);
+        if (split > grid->n_cpu) split = grid->n_cpu;
+    }
+    const uint32_t c_per_block = (grid->n_cpu + split - 1) / split;
+    split = (grid->n_cpu + c_per_block - 1) / c_per_block;
+    if (nj > 65535u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 65535 jobs in one call; use job ranges");
+    const dim3 g3(bx, nj, split);
+    const JobDev jd = job_dev(jobs);
+    const TableDev td = table_dev(table);
+    const GridDev gd = grid_dev(grid);
+    if (feas)
+        k_eval<true><<<g3, EVAL_THREADS, 0, ctx->stream>>>(jd, td, gd, *env, jb, table->option_mask, c_per_block, thr, feas);
+    else
+        k_eval<false><<<g3, EVAL_THREADS, 0, ctx->stream>>>(jd, td, gd, *env, jb, table->option_mask, c_per_block, thr, nullptr);
+    RK_CHECK_LAUNCH(ctx, "k_eval");
+    return RK_OK;
+}
+
+int32_t rk_best_plan(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_grid *grid, uint32_t jb,
+                     uint32_t je, const float *thr, float *best_thr, uint32_t *best_plan, uint64_t cap_segs,
+                     uint64_t *n_needed) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if ((rc = rk_check_table(ctx, table, jb, je))) return rc;
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    uint64_t nt, ns;
+    if ((rc = rk_range_offsets(ctx, table, jb, je, &nt, &ns))) return rc;
+    const uint64_t n_rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    const uint64_t need = n_rows * ns;
+    if (n_needed) *n_needed = need;
+    if (need == 0) return RK_OK;
+    if (!thr || !best_thr || !best_plan) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null buffer");
+    if (cap_segs < need) return rk_fail(ctx, RK_ERR_CAPACITY, "outputs hold %llu entries, %llu needed",
+                                        (unsigned long long)cap_segs, (unsigned long long)need);
+    if ((uintptr_t)thr & 15u) return rk_fail(ctx, RK_ERR_INVALID_ARG, "thr not 16-byte aligned");
+    const uint64_t rows = (uint64_t)(je - jb) * n_rows;
+    const uint64_t blocks = (rows + BEST_WAVES - 1) / BEST_WAVES;
+    if (blocks > 0x7FFFFFFFull) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "too many rows in one call; use job ranges");
+    const uint32_t per_wave = table->max_triples_per_job;
+    const size_t lds = (size_t)BEST_WAVES * per_wave * sizeof(unsigned long long);
+    k_best_plan<<<(uint32_t)blocks, BEST_WAVES * 64, lds, ctx->stream>>>(table_dev(table), (uint32_t)n_rows, jb, je,
+                                                                        per_wave, thr, best_thr, best_plan);
+    RK_CHECK_LAUNCH(ctx, "k_best_plan");
+    return RK_OK;
+}
+
+int32_t rk_curves(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_grid *grid, uint32_t jb, uint32_t je,
+                  const float *best_thr, const uint32_t *best_plan, float *curve_thr, uint32_t *curve_plan,
+                  uint32_t *curve_g, uint64_t cap_segs) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if ((rc = rk_check_table(ctx, table, jb, je))) return rc;
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    uint64_t nt, ns;
+    if ((rc = rk_range_offsets(ctx, table, jb, je, &nt, &ns))) return rc;
+    const uint64_t n_rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    const uint64_t need = n_rows * ns;
+    if (need == 0) return RK_OK;
+    if (!best_thr || !best_plan || !curve_thr || !curve_plan || !curve_g) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null buffer");
+    if (cap_segs < need) return rk_fail(ctx, RK_ERR_CAPACITY, "outputs hold %llu entries, %llu needed",
+                                        (unsigned long long)cap_segs, (unsigned long long)need);
+    const uint64_t rows = (uint64_t)(je - jb) * n_rows;
+    const uint64_t blocks = (rows + 255) / 256;
+    if (blocks > 0x7FFFFFFFull) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "too many rows in one call; use job ranges");
+    k_curves<<<(uint32_t)blocks, 256, 0, ctx->stream>>>(table_dev(table), (uint32_t)n_rows, jb, je, best_thr, best_plan,
+                                                       curve_thr, curve_plan, curve_g);
+    RK_CHECK_LAUNCH(ctx, "k_curves");
+    return RK_OK;
+}
+
+}  // extern "C"

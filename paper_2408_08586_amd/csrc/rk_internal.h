@@ -1,0 +1,77 @@
+// Internal declarations shared by the translation units of the library:
+// the context, error helpers and host-side launch wrappers.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+
+#include "rubick.h"
+
+enum { RK_SCRATCH_SLOTS = 16 };
+
+struct rk_ctx {
+    int device;
+    hipStream_t stream;
+    char err[512];
+    void *scratch[RK_SCRATCH_SLOTS];        // grow-only device buffers owned by the context
+    size_t scratch_bytes[RK_SCRATCH_SLOTS];
+    uint32_t *h_pinned;                     // 64 pinned host words for counts coming back
+};
+
+// scratch slots
+enum {
+    SL_CNT_T = 0, SL_CNT_S, SL_TOTALS,            // enumeration: per-job counts, totals
+    SL_TB_TOFF, SL_TB_TRIPLES, SL_TB_SOFF, SL_TB_SEGG, SL_TB_SEGF,   // internal plan table of a round
+    SL_BEST_THR, SL_BEST_PLAN, SL_CURVE_THR, SL_CURVE_PLAN, SL_CURVE_G,  // round intermediates
+    SL_ROUND_META                                 // per-round job ranges and clusters
+};
+
+int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);
+int32_t rk_scratch(rk_ctx *ctx, int slot, size_t bytes, void **out);
+
+#define RK_HIP(ctx, call)                                                              \
+    do {                                                                               \
+        hipError_t e_ = (call);                                                        \
+        if (e_ != hipSuccess)                                                          \
+            return rk_fail((ctx), RK_ERR_DEVICE, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+#define RK_CHECK_LAUNCH(ctx, name)                                                     \
+    do {                                                                               \
+        hipError_t e_ = hipGetLastError();                                             \
+        if (e_ != hipSuccess)                                                          \
+            return rk_fail((ctx), RK_ERR_DEVICE, "launch of %s: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+// argument validation shared by the entry points
+int32_t rk_check_grid(rk_ctx *ctx, const rk_alloc_grid *grid);
+int32_t rk_check_env(rk_ctx *ctx, const rk_env *env);
+int32_t rk_check_table(rk_ctx *ctx, const rk_plan_table *table, uint32_t job_begin, uint32_t job_end);
+// triple_off / seg_off at job_begin and job_end (host mirrors, or two copies back)
+int32_t rk_range_offsets(rk_ctx *ctx, const rk_plan_table *table, uint32_t job_begin, uint32_t job_end,
+                         uint64_t *n_triples, uint64_t *n_segs);
+
+// device-side view of the plan table
+struct TableDev {
+    const uint32_t *__restrict__ triple_off;
+    const uint32_t *__restrict__ triples;
+    const uint32_t *__restrict__ seg_off;
+    const uint32_t *__restrict__ seg_g;
+    const uint32_t *__restrict__ seg_first;
+};
+
+static inline TableDev table_dev(const rk_plan_table *t) {
+    return TableDev{t->triple_off, t->triples, t->seg_off, t->seg_g, t->seg_first};
+}
+
+// launch wrappers (each enqueues on ctx->stream)
+int32_t rk_launch_fused(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table,
+                        const rk_alloc_grid *grid, const rk_env *env, uint32_t jb, uint32_t je,
+                        float *best_thr, uint32_t *best_plan, float *curve_thr, uint32_t *curve_plan,
+                        uint32_t *curve_g);
+int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb, const rk_alloc_grid *grid,
+                           uint32_t n_rounds, const uint32_t *d_round_off, const rk_cluster *d_clusters,
+                           uint32_t jb, uint32_t max_jobs_per_round, const float *best_thr, const uint32_t *best_plan,
+                           const float *curve_thr, rk_assign *assign, float *totals);

@@ -1,0 +1,91 @@
+// Whole scheduling rounds on the device: enumerate -> fused evaluation /
+// best plan / curves -> greedy allocation (paper Sec. 5.2, Algorithm 1 reduced
+// to best-effort jobs over cluster totals).
+#include <cstring>
+
+#include "rk_internal.h"
+
+extern "C" {
+
+int32_t rk_schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                           const rk_alloc_grid *grid, const rk_env *env, uint32_t n_rounds,
+                           const uint32_t *round_off, const rk_cluster *clusters, rk_assign *assign,
+                           float *totals) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if (!jobs || !bounds || !round_off || !clusters || !totals || (!assign && jobs->n_jobs > 0))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (!jobs->ref_thr && jobs->n_jobs > 0) return rk_fail(ctx, RK_ERR_INVALID_ARG, "ref_thr is null");
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    if ((rc = rk_check_env(ctx, env))) return rc;
+    if (n_rounds == 0) return RK_OK;
+    const uint32_t J = jobs->n_jobs;
+    uint32_t max_jobs = 0;
+    if (round_off[0] != 0 || round_off[n_rounds] != J) return rk_fail(ctx, RK_ERR_INVALID_ARG, "round_off must run from 0 to n_jobs");
+    for (uint32_t r = 0; r < n_rounds; ++r) {
+        if (round_off[r + 1] < round_off[r]) return rk_fail(ctx, RK_ERR_INVALID_ARG, "round_off not ascending");
+        const uint32_t n = round_off[r + 1] - round_off[r];
+        max_jobs = n > max_jobs ? n : max_jobs;
+        if (!(clusters[r].host_mem_gb >= 0.f)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "host_mem_gb negative or NaN");
+    }
+    if (max_jobs > RK_MAX_JOBS_PER_ROUND)
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "a round has %u jobs, the allocation kernel takes up to %u", max_jobs,
+                       RK_MAX_JOBS_PER_ROUND);
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+
+    // round ranges and clusters go up first; the wait inside the enumeration covers the copy
+    const size_t off_bytes = (((size_t)n_rounds + 1) * 4 + 15) & ~(size_t)15;
+    char *d_meta;
+    if ((rc = rk_scratch(ctx, SL_ROUND_META, off_bytes + (size_t)n_rounds * sizeof(rk_cluster), (void **)&d_meta))) return rc;
+    RK_HIP(ctx, hipMemcpyAsync(d_meta, round_off, ((size_t)n_rounds + 1) * 4, hipMemcpyHostToDevice, ctx->stream));
+    RK_HIP(ctx, hipMemcpyAsync(d_meta + off_bytes, clusters, (size_t)n_rounds * sizeof(rk_cluster), hipMemcpyHostToDevice, ctx->stream));
+
+    // internal plan table in scratch memory; grown on demand
+    rk_plan_table tb;
+    memset(&tb, 0, sizeof(tb));
+    uint64_t cap_t = ctx->scratch_bytes[SL_TB_TRIPLES] / 4, cap_s = ctx->scratch_bytes[SL_TB_SEGG] / 4;
+    if (cap_t < (uint64_t)J * 256) cap_t = (uint64_t)J * 256;
+    if (cap_s < (uint64_t)J * 32) cap_s = (uint64_t)J * 32;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        if ((rc = rk_scratch(ctx, SL_TB_TOFF, ((size_t)J + 1) * 4, (void **)&tb.triple_off))) return rc;
+        if ((rc = rk_scratch(ctx, SL_TB_SOFF, ((size_t)J + 1) * 4, (void **)&tb.seg_off))) return rc;
+        if ((rc = rk_scratch(ctx, SL_TB_TRIPLES, cap_t * 4, (void **)&tb.triples))) return rc;
+        if ((rc = rk_scratch(ctx, SL_TB_SEGG, cap_s * 4, (void **)&tb.seg_g))) return rc;
+        if ((rc = rk_scratch(ctx, SL_TB_SEGF, cap_s * 4, (void **)&tb.seg_first))) return rc;
+        tb.cap_triples = cap_t;
+        tb.cap_segs = cap_s;
+        rc = rk_enumerate_plans(ctx, jobs, bounds, &tb);
+        if (rc != RK_ERR_CAPACITY) break;
+        cap_t = tb.n_triples;
+        cap_s = tb.n_segs;
+    }
+    if (rc) return rc;
+    if (tb.max_segs_per_job > 32767u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 32767 segments per job");
+
+    const uint64_t n_rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    const size_t n_out = (size_t)(n_rows * tb.n_segs);
+    float *best_thr, *curve_thr;
+    uint32_t *best_plan, *curve_plan, *curve_g;
+    if ((rc = rk_scratch(ctx, SL_BEST_THR, n_out * 4, (void **)&best_thr))) return rc;
+    if ((rc = rk_scratch(ctx, SL_BEST_PLAN, n_out * 4, (void **)&best_plan))) return rc;
+    if ((rc = rk_scratch(ctx, SL_CURVE_THR, n_out * 4, (void **)&curve_thr))) return rc;
+    if ((rc = rk_scratch(ctx, SL_CURVE_PLAN, n_out * 4, (void **)&curve_plan))) return rc;
+    if ((rc = rk_scratch(ctx, SL_CURVE_G, n_out * 4, (void **)&curve_g))) return rc;
+
+    if ((rc = rk_launch_fused(ctx, jobs, &tb, grid, env, 0, J, best_thr, best_plan, curve_thr, curve_plan, curve_g))) return rc;
+    return rk_launch_allocate(ctx, jobs->ref_thr, table_dev(&tb), grid, n_rounds,
+                              reinterpret_cast<const uint32_t *>(d_meta),
+                              reinterpret_cast<const rk_cluster *>(d_meta + off_bytes), 0, max_jobs, best_thr,
+                              best_plan, curve_thr, assign, totals);
+}
+
+int32_t rk_schedule_round(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                          const rk_alloc_grid *grid, const rk_env *env, const rk_cluster *cluster,
+                          rk_assign *assign, float *total) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    if (!jobs || !cluster) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    const uint32_t off[2] = {0u, jobs->n_jobs};
+    return rk_schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, cluster, assign, total);
+}
+
+}  // extern "C"

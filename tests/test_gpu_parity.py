@@ -1,0 +1,337 @@
+"""GPU parity: every entry point of the library against the CPU oracle on the
+same seeded inputs.  Integer results (tables, feasibility bits, argmax on
+given values, curves, allocation on given curves) must be bit-exact; predicted
+throughputs must agree within 1e-5 relative; a best plan computed from the
+GPU's own float32 throughputs may differ from the oracle's only where the
+oracle's value of the GPU's choice is within 1e-5 relative of its maximum."""
+import numpy as np
+import pytest
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from gpu_harness import GpuRun
+    return GpuRun
+
+
+def oracle_table_equal(tn, ot):
+    assert np.array_equal(tn["triple_off"], ot.triple_off)
+    assert np.array_equal(tn["seg_off"], ot.seg_off)
+    assert np.array_equal(tn["triples"], ot.triples)
+    assert np.array_equal(tn["seg_g"], ot.seg_g)
+    assert np.array_equal(tn["seg_first"], ot.seg_first)
+
+
+def check_thr(gpu_thr, gpu_feas, o_thr, o_reason):
+    assert np.array_equal(gpu_feas, o_reason), "feasibility bits differ"
+    assert np.array_equal(gpu_thr == 0, o_reason != 0)
+    ok = o_reason == 0
+    rel = np.abs(gpu_thr[ok].astype(np.float64) - o_thr[ok]) / o_thr[ok]
+    assert rel.size == 0 or rel.max() <= REL, f"max rel err {rel.max():.3e}"
+    return float(rel.max()) if rel.size else 0.0
+
+
+def check_best_in_band(ot, n_rows, jb, je, o_thr, o_bt, o_bp, g_bt, g_bp):
+    """g_* computed from the GPU's float32 throughputs; o_* from the oracle's float64."""
+    assert np.array_equal(g_bp == 0xFFFFFFFF, o_bp == 0xFFFFFFFF)
+    has = o_bp != 0xFFFFFFFF
+    rel = np.abs(g_bt[has].astype(np.float64) - o_bt[has]) / o_bt[has]
+    assert rel.size == 0 or rel.max() <= REL
+    mism = np.flatnonzero(g_bp != o_bp)
+    # oracle value of the GPU's choice must be inside the band
+    if mism.size:
+        seg_cnt = (ot.seg_off[jb + 1:je + 1] - ot.seg_off[jb:je]).astype(np.int64) * n_rows
+        seg_end = np.cumsum(seg_cnt)
+        job_of = np.searchsorted(seg_end, mism, side="right")
+        for k, jl in zip(mism.tolist(), job_of.tolist()):
+            j = jb + jl
+            ns = int(ot.seg_off[j + 1] - ot.seg_off[j])
+            nt = int(ot.triple_off[j + 1] - ot.triple_off[j])
+            local = k - (seg_end[jl] - seg_cnt[jl])
+            r = local // ns
+            cbase = 16 * n_rows * int(ot.triple_off[j] - ot.triple_off[jb]) + r * nt * 16
+            v = o_thr[cbase + int(g_bp[k])]
+            assert v >= o_bt[k] * (1 - REL), f"segment {k}: GPU plan {g_bp[k]} is outside the tie band"
+    return mism.size
+
+
+@pytest.mark.parametrize("name", ["tiny", "paper_scale"])
+def test_enumerate_small_configs(gpu, orc, name):
+    wl = workloads.CONFIGS[name]()
+    run = gpu(wl)
+    run.enumerate()
+    oracle_table_equal(run.table_numpy(), orc.enumerate_plans(wl.ints, wl.bounds))
+    run.close()
+
+
+def test_enumerate_odd_jobs_and_bounds(gpu, orc):
+    ints = np.array([[12, 32, 1], [24, 64, 2], [40, 128, 4], [7, 6, 1], [32, 32, 4], [96, 48, 2],
+                     [5, 7, 2],           # micro-batch does not divide the batch: no plan
+                     [1, 1, 1], [60, 360, 1], [97, 128, 1]], np.uint32)
+    coef = np.tile(workloads.tiny().coef[:1], (len(ints), 1))
+    for b in (workloads.Bounds(g_max=8), workloads.Bounds(g_max=24, tp_max=4, pp_max=3),
+              workloads.Bounds(g_max=720, tp_max=2), workloads.Bounds(g_max=1, tp_max=1, pp_max=1)):
+        wl = workloads.Workload("odd", coef, ints, b, workloads.tiny().grid, workloads.Env(), workloads.Cluster(8, 8, 64.0))
+        run = gpu(wl)
+        run.enumerate()
+        oracle_table_equal(run.table_numpy(), orc.enumerate_plans(ints, b))
+        run.close()
+
+
+def test_enumerate_stress_sample(gpu, orc):
+    wl = workloads.stress()
+    run = gpu(wl)
+    t = run.enumerate()
+    tn = run.table_numpy()
+    assert t.n_jobs == 10000
+    pick = np.sort(np.random.default_rng(3).choice(wl.n_jobs, 150, replace=False))
+    ot = orc.enumerate_plans(wl.ints[pick], wl.bounds)
+    for i, j in enumerate(pick.tolist()):
+        a, b = tn["triple_off"][j], tn["triple_off"][j + 1]
+        assert np.array_equal(tn["triples"][a:b], ot.triples[ot.triple_off[i]:ot.triple_off[i + 1]])
+        a, b = tn["seg_off"][j], tn["seg_off"][j + 1]
+        assert np.array_equal(tn["seg_g"][a:b], ot.seg_g[ot.seg_off[i]:ot.seg_off[i + 1]])
+        assert np.array_equal(tn["seg_first"][a:b], ot.seg_first[ot.seg_off[i]:ot.seg_off[i + 1]])
+    run.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "paper_scale", "large"])
+def test_eval_and_selection_full_configs(gpu, orc, name):
+    wl = workloads.CONFIGS[name]()
+    run = gpu(wl)
+    run.enumerate()
+    ot = orc.enumerate_plans(wl.ints, wl.bounds)
+    o_thr, o_reason = orc.eval_jobs(wl.coef, wl.ints, wl.bounds, ot, wl.grid, wl.env, n_threads=16)
+    thr, feas, n = run.eval()
+    g_thr, g_feas = run.host(thr, n), run.host(feas, n)
+    err = check_thr(g_thr, g_feas, o_thr, o_reason)
+    # best plan on the oracle's own float32 values: exact
+    o32 = o_thr.astype(np.float32)
+    bt, bp, ns = run.best(run.dev_f32(o32))
+    e_bt, e_bp = orc.best_plan(ot, wl.grid, o32)
+    assert np.array_equal(run.host(bt, ns), e_bt) and np.array_equal(run.host(bp, ns).view(np.uint32), e_bp)
+    # best plan on the GPU's values against the oracle's float64 search: tie band
+    bt2, bp2, _ = run.best(thr)
+    o_bt, o_bp = orc.best_plan(ot, wl.grid, o_thr)
+    n_mis = check_best_in_band(ot, run.n_rows, 0, wl.n_jobs, o_thr, o_bt, o_bp, run.host(bt2, ns),
+                               run.host(bp2, ns).view(np.uint32))
+    assert n_mis <= 0.01 * ns
+    # curves on the oracle's best values: exact
+    ct, cp, cg = run.curves(run.dev_f32(e_bt), run.dev_u32(e_bp))
+    e_ct, e_cp, e_cg = orc.curves(ot, wl.grid, e_bt, e_bp)
+    assert np.array_equal(run.host(ct, ns), e_ct)
+    assert np.array_equal(run.host(cp, ns).view(np.uint32), e_cp)
+    assert np.array_equal(run.host(cg, ns).view(np.uint32), e_cg)
+    # the fused entry point gives exactly what the three calls give
+    fbt, fbp, fct, fcp, fcg, _ = run.fused()
+    ct2, cp2, cg2 = run.curves(bt2, bp2)
+    for a, b in ((fbt, bt2), (fbp, bp2), (fct, ct2), (fcp, cp2), (fcg, cg2)):
+        assert np.array_equal(run.host(a, ns), run.host(b, ns))
+    print(f"{name}: {n} candidates, max rel err {err:.2e}, {n_mis}/{ns} best plans differ inside the band")
+    run.close()
+
+
+def test_eval_job_ranges_match_full_run(gpu, orc):
+    wl = workloads.paper_scale()
+    run = gpu(wl)
+    run.enumerate()
+    thr, feas, n = run.eval()
+    full = run.host(thr, n)
+    ot = orc.enumerate_plans(wl.ints, wl.bounds)
+    for jb, je in ((0, 1), (5, 23), (63, 64), (17, 17)):
+        t2, _, n2 = run.eval(jb, je, want_feas=False)
+        a = 16 * run.n_rows * int(ot.triple_off[jb])
+        assert np.array_equal(run.host(t2, n2), full[a:a + n2])
+        if n2:
+            bt, bp, ns = run.best(t2, jb, je)
+            o_thr, _ = orc.eval_jobs(wl.coef, wl.ints, wl.bounds, ot, wl.grid, wl.env, jb, je)
+            o_bt, o_bp = orc.best_plan(ot, wl.grid, o_thr, jb, je)
+            check_best_in_band(ot, run.n_rows, jb, je, o_thr, o_bt, o_bp, run.host(bt, ns),
+                               run.host(bp, ns).view(np.uint32))
+    run.close()
+
+
+def test_stress_config_sampled_jobs(gpu, orc):
+    """Full 10,000-job configuration in the chunking the benchmark uses;
+    the oracle checks a seeded sample of jobs one by one."""
+    wl = workloads.stress()
+    run = gpu(wl)
+    t = run.enumerate()
+    tn = run.table_numpy()
+    rng = np.random.default_rng(5)
+    n_chunks = 3
+    edges = np.linspace(0, wl.n_jobs, n_chunks + 1).astype(int)
+    worst, n_mis, n_seg = 0.0, 0, 0
+    for jb, je in zip(edges[:-1], edges[1:]):
+        thr, feas, n = run.eval(int(jb), int(je))
+        bt, bp, ns = run.best(thr, int(jb), int(je))
+        g_thr, g_feas = run.host(thr, n), run.host(feas, n)
+        g_bt, g_bp = run.host(bt, ns), run.host(bp, ns).view(np.uint32)
+        for j in np.sort(rng.choice(np.arange(jb, je), 12, replace=False)).tolist():
+            sub = wl.subset([j])
+            ot = orc.enumerate_plans(sub.ints, sub.bounds)
+            o_thr, o_reason = orc.eval_jobs(sub.coef, sub.ints, sub.bounds, ot, sub.grid, sub.env)
+            a = 16 * run.n_rows * int(tn["triple_off"][j] - tn["triple_off"][jb])
+            worst = max(worst, check_thr(g_thr[a:a + o_thr.size], g_feas[a:a + o_thr.size], o_thr, o_reason))
+            o_bt, o_bp = orc.best_plan(ot, sub.grid, o_thr)
+            s = run.n_rows * int(tn["seg_off"][j] - tn["seg_off"][jb])
+            n_mis += check_best_in_band(ot, run.n_rows, 0, 1, o_thr, o_bt, o_bp, g_bt[s:s + o_bt.size],
+                                        g_bp[s:s + o_bt.size])
+            n_seg += o_bt.size
+    print(f"stress: max rel err {worst:.2e}; {n_mis}/{n_seg} sampled best plans differ inside the band")
+    assert n_mis <= 0.01 * n_seg
+    run.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "paper_scale", "large"])
+def test_allocate_on_oracle_curves_is_exact(gpu, orc, name):
+    wl = workloads.CONFIGS[name]()
+    r = orc.schedule_round(wl, n_threads=16)
+    run = gpu(wl)
+    run.enumerate()
+    assign, total = run.allocate(run.dev_f32(r["best_thr"]), run.dev_u32(r["best_plan"]), run.dev_f32(r["curve_thr"]))
+    assert np.array_equal(assign, r["assign"])
+    assert total == pytest.approx(r["total"], rel=1e-6)
+    # scarce capacities exercise the admissibility and memory rules
+    for G, Cc, M in ((wl.cluster.G // 3, wl.cluster.C // 50 + 3, wl.cluster.host_mem_gb / 7), (1, 1, 64.0), (0, 0, 0.0)):
+        cl = workloads.Cluster(G, Cc, M)
+        e_assign, e_total, _ = orc.greedy(wl.coef[:, 16], r["table"], wl.grid, cl, r["best_thr"], r["best_plan"], r["curve_thr"])
+        import paper_2408_08586_amd as rk
+        assign, total = run.allocate(run.dev_f32(r["best_thr"]), run.dev_u32(r["best_plan"]),
+                                     run.dev_f32(r["curve_thr"]), cluster=rk.make_cluster(cl))
+        assert np.array_equal(assign, e_assign)
+        assert total == pytest.approx(e_total, rel=1e-6, abs=1e-12)
+    run.close()
+
+
+def compare_rounds(assign, total, r):
+    """End-to-end result against the oracle's round.  Where every decision of
+    the oracle's greedy was clear (smallest slope gap well above float32
+    noise) the assignments must be equal; otherwise the totals must agree."""
+    same_g = np.array_equal(assign["g"], r["assign"]["g"]) and np.array_equal(assign["c"], r["assign"]["c"])
+    if r["min_gap"] > 1e-4:
+        assert same_g
+    if same_g:
+        assert np.array_equal(assign["mem_gb"], r["assign"]["mem_gb"])
+        sched = assign["g"] > 0
+        rel = np.abs(assign["thr"][sched].astype(np.float64) - r["assign"]["thr"][sched]) / r["assign"]["thr"][sched]
+        assert rel.size == 0 or rel.max() <= REL
+    assert total == pytest.approx(r["total"], rel=1e-4)
+    return same_g
+
+
+@pytest.mark.parametrize("name", ["tiny", "paper_scale", "large"])
+def test_schedule_round_end_to_end(gpu, orc, name):
+    wl = workloads.CONFIGS[name]()
+    r = orc.schedule_round(wl, n_threads=16)
+    run = gpu(wl)
+    assign, total = run.schedule_round()
+    same = compare_rounds(assign, total, r)
+    assert assign["g"].sum() <= wl.cluster.G and assign["c"].sum() <= wl.cluster.C
+    assert assign["mem_gb"].sum() <= wl.cluster.host_mem_gb * (1 + 1e-6)
+    # a second run is bit-identical
+    assign2, total2 = run.schedule_round()
+    assert np.array_equal(assign, assign2) and total == total2
+    print(f"{name}: assignments equal to the oracle's: {same}; oracle min slope gap {r['min_gap']:.2e}")
+    run.close()
+
+
+def test_schedule_rounds_batch_what_if(gpu, orc):
+    import paper_2408_08586_amd as rk
+    import torch
+    rounds = [workloads.what_if(i, n_jobs=120) for i in range(6)]
+    coef = np.concatenate([w.coef for w in rounds])
+    ints = np.concatenate([w.ints for w in rounds])
+    base = rounds[0]
+    wl = workloads.Workload("batch", coef, ints, base.bounds, base.grid, base.env, base.cluster)
+    run = gpu(wl)
+    round_off = np.arange(0, 121 * 6, 120, dtype=np.uint32)[:7]
+    assign = rk.new_assign(wl.n_jobs)
+    totals = torch.zeros(6, dtype=torch.float32, device="cuda:0")
+    rk.rk_schedule_rounds(run.ctx, run.jobs, run.bounds, run.grid, run.env, round_off,
+                          [rk.make_cluster(w.cluster) for w in rounds], assign, totals)
+    rk.rk_sync(run.ctx)
+    a = rk.assign_to_numpy(assign)
+    for i, w in enumerate(rounds):
+        r = orc.schedule_round(w, n_threads=8)
+        compare_rounds(a[i * 120:(i + 1) * 120], float(totals[i].item()), r)
+    run.close()
+
+
+def test_edge_cases(gpu, orc):
+    import paper_2408_08586_amd as rk
+    base = workloads.tiny()
+    # zero jobs
+    wl = workloads.Workload("empty", base.coef[:0], base.ints[:0], base.bounds, base.grid, base.env, base.cluster)
+    run = gpu(wl)
+    t = run.enumerate()
+    assert t.n_triples == 0 and t.n_segs == 0
+    thr, feas, n = run.eval()
+    assert n == 0
+    assign, total = run.schedule_round()
+    assert assign.size == 0 and total == 0.0
+    run.close()
+    # a job without any plan among jobs that have plans; a cap nothing fits in
+    ints = base.ints.copy()
+    ints[3] = (5, 7, 2)
+    env = workloads.Env(gpu_mem_cap=1.0)
+    wl = workloads.Workload("nofit", base.coef, ints, base.bounds, base.grid, env, base.cluster)
+    run = gpu(wl)
+    run.enumerate()
+    tn = run.table_numpy()
+    assert tn["triple_off"][4] == tn["triple_off"][3]
+    thr, feas, n = run.eval()
+    assert (run.host(thr, n) == 0).all() and (run.host(feas, n) != 0).all()
+    bt, bp, ns = run.best(thr)
+    assert (run.host(bp, ns).view(np.uint32) == 0xFFFFFFFF).all() and (run.host(bt, ns) == 0).all()
+    assign, total = run.schedule_round()
+    assert (assign["g"] == 0).all() and (assign["plan"] == 0xFFFFFFFF).all() and total == 0.0
+    # capacity errors report the needed size and leave the context usable
+    small = run.f32(16)
+    with pytest.raises(rk.RkError) as e:
+        rk.rk_eval_candidates(run.ctx, run.jobs, run.table.c, run.grid, run.env, 0, wl.n_jobs, small, None)
+    assert e.value.code == rk.RK_ERR_CAPACITY
+    tbl = rk.PlanTable(wl.n_jobs, 3, 3)
+    with pytest.raises(rk.RkError) as e:
+        rk.rk_enumerate_plans(run.ctx, run.jobs, run.bounds, tbl.c)
+    assert e.value.code == rk.RK_ERR_CAPACITY and tbl.n_triples == run.table.n_triples
+    bad = rk.make_grid(workloads.Grid(np.array([4, 2], np.uint32), 0, np.array([1.0], np.float32), 0))
+    with pytest.raises(rk.RkError) as e:
+        rk.rk_eval_candidates(run.ctx, run.jobs, run.table.c, bad, run.env, 0, wl.n_jobs, thr, None)
+    assert e.value.code == rk.RK_ERR_INVALID_ARG
+    with pytest.raises(rk.RkError) as e:
+        rk.rk_eval_candidates(run.ctx, run.jobs, run.table.c, run.grid, run.env, 5, 3, thr, None)
+    assert e.value.code == rk.RK_ERR_INVALID_ARG
+    thr2, _, n2 = run.eval()
+    assert np.array_equal(run.host(thr2, n2), run.host(thr, n))
+    run.close()
+
+
+def test_option_masks_and_memory_modes(gpu, orc):
+    base = workloads.paper_scale()
+    b = workloads.Bounds(g_max=32, tp_max=4, pp_max=8, zero_mask=0b1101, gc_mask=0b11, off_mask=0b11)
+    grid = workloads.Grid(np.array([1, 3, 4], np.uint32), 1, np.array([0.0, 8.0, 40.0], np.float32), 1)
+    env = workloads.Env(gpu_mem_cap=40e9, gpus_per_node=4)
+    wl = workloads.Workload("modes", base.coef[:24], base.ints[:24], b, grid, env, workloads.Cluster(40, 100, 900.0))
+    run = gpu(wl)
+    run.enumerate()
+    ot = orc.enumerate_plans(wl.ints, wl.bounds)
+    oracle_table_equal(run.table_numpy(), ot)
+    o_thr, o_reason = orc.eval_jobs(wl.coef, wl.ints, wl.bounds, ot, wl.grid, wl.env, n_threads=8)
+    thr, feas, n = run.eval()
+    check_thr(run.host(thr, n), run.host(feas, n), o_thr, o_reason)
+    r = orc.schedule_round(wl, n_threads=8)
+    assign, total = run.allocate(run.dev_f32(r["best_thr"]), run.dev_u32(r["best_plan"]), run.dev_f32(r["curve_thr"]))
+    assert np.array_equal(assign, r["assign"])
+    a2, t2 = run.schedule_round()
+    compare_rounds(a2, t2, r)
+    run.close()
