@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--chunks", type=int, default=3, help="job chunks streamed through one candidate buffer")
     ap.add_argument("--cpu-sample-jobs", type=int, default=1500)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB elementwise copy (reads 1 GiB, writes 1 GiB) three times, "
+                         "to scale the profiler's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this benchmark measures one GPU; the path runs on a single device (use --gpus 1)")
@@ -131,6 +134,14 @@ def main():
                                                  curve_thr[s0:], curve_plan[s0:], curve_g[s0:]), record)
         timed("allocate", lambda: rk.rk_allocate(ctx, jobs.ref_thr, table.c, grid, cluster, 0, J, best_thr, best_plan,
                                                  curve_thr, assign, total), record)
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step(False)

@@ -6,6 +6,8 @@
 
 namespace {
 
+typedef float v4f __attribute__((ext_vector_type(4)));   // 16-byte vector the streaming builtins accept
+
 constexpr int EVAL_THREADS = 256;
 constexpr int TRIPLES_PER_BLOCK = EVAL_THREADS / 4;
 
@@ -71,13 +73,13 @@ __global__ __launch_bounds__(EVAL_THREADS) void k_eval(JobDev jobs, TableDev tb,
                 if (!(w0 & RK_INFEASIBLE_STRUCT)) w0 |= RK_INFEASIBLE_HOST_MEM;
                 if (!(w1 & RK_INFEASIBLE_STRUCT)) w1 |= RK_INFEASIBLE_HOST_MEM;
             }
-            float4 v;
+            v4f v;
             v.x = plain[0];
             v.y = w0 ? 0.f : off_thr[0];
             v.z = plain[1];
             v.w = w1 ? 0.f : off_thr[1];
             const uint64_t idx = cbase + ((uint64_t)(ci * grid.n_mem + mi) * nt + tl) * 16 + z * 4;
-            *reinterpret_cast<float4 *>(thr + idx) = v;
+            __builtin_nontemporal_store(v, reinterpret_cast<v4f *>(thr + idx));
             if (WITH_FEAS) {
                 const uint32_t packed = why_plain[0] | (w0 << 8) | (why_plain[1] << 16) | (w1 << 24);
                 *reinterpret_cast<uint32_t *>(feas + idx) = packed;
@@ -124,22 +126,29 @@ __global__ __launch_bounds__(BEST_WAVES * 64) void k_best_plan(TableDev tb, uint
         t0 = tb.triple_off[j]; nt = tb.triple_off[j + 1] - t0;
         s0 = tb.seg_off[j]; ns = tb.seg_off[j + 1] - s0;
         const uint64_t cbase = 16ull * n_rows * (uint64_t)(t0 - tb.triple_off[jb]) + (uint64_t)r * nt * 16;
-        const float4 *row = reinterpret_cast<const float4 *>(thr + cbase);
+        const v4f *row = reinterpret_cast<const v4f *>(thr + cbase);
         const uint32_t n_vec = nt * 4;                      // float4 elements in the row
-        for (uint32_t base = 0; base < n_vec; base += 64) {
-            const uint32_t i = base + lane;
-            unsigned long long k = 0;
-            if (i < n_vec) {
-                const float4 v = row[i];
-                const uint32_t plan0 = i * 4;
-                k = make_key(v.x, plan0);
-                k = max_u64(k, make_key(v.y, plan0 + 1));
-                k = max_u64(k, make_key(v.z, plan0 + 2));
-                k = max_u64(k, make_key(v.w, plan0 + 3));
+        // four independent 1 KiB loads per wavefront are issued before any is used
+        for (uint32_t base = 0; base < n_vec; base += 4 * 64) {
+            v4f v[4];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                const uint32_t i = base + u * 64 + lane;
+                v[u] = i < n_vec ? __builtin_nontemporal_load(row + i) : (v4f)(0.f);
             }
-            k = max_u64(k, dpp_u64<0xB1>(k));               // quad_perm [1,0,3,2]
-            k = max_u64(k, dpp_u64<0x4E>(k));               // quad_perm [2,3,0,1]
-            if ((lane & 3u) == 0 && i < n_vec) keys[i >> 2] = k;
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                const uint32_t i = base + u * 64 + lane;
+                const uint32_t plan0 = i * 4;
+                unsigned long long k = make_key(v[u].x, plan0);
+                k = max_u64(k, make_key(v[u].y, plan0 + 1));
+                k = max_u64(k, make_key(v[u].z, plan0 + 2));
+                k = max_u64(k, make_key(v[u].w, plan0 + 3));
+                if (i >= n_vec) k = 0;
+                k = max_u64(k, dpp_u64<0xB1>(k));           // quad_perm [1,0,3,2]
+                k = max_u64(k, dpp_u64<0x4E>(k));           // quad_perm [2,3,0,1]
+                if ((lane & 3u) == 0 && i < n_vec) keys[i >> 2] = k;
+            }
         }
     }
     __syncthreads();
@@ -156,25 +165,47 @@ __global__ __launch_bounds__(BEST_WAVES * 64) void k_best_plan(TableDev tb, uint
 }
 
 // ------------------------------------------------------------------- curves
-// One thread per (job, row): running maximum over the job's GPU counts.
-__global__ __launch_bounds__(256) void k_curves(TableDev tb, uint32_t n_rows, uint32_t jb, uint32_t je,
-                                                const float *__restrict__ best_thr,
-                                                const uint32_t *__restrict__ best_plan,
-                                                float *__restrict__ curve_thr, uint32_t *__restrict__ curve_plan,
-                                                uint32_t *__restrict__ curve_g) {
-    const uint64_t row_id = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (row_id >= (uint64_t)(je - jb) * n_rows) return;
-    const uint32_t j = jb + (uint32_t)(row_id / n_rows), r = (uint32_t)(row_id % n_rows);
+// One workgroup per job.  The job's (row, segment) block is contiguous in
+// memory: it is staged through LDS in chunks of whole rows, one thread runs the
+// maximum along each row in LDS, and the results leave with contiguous stores.
+constexpr int CURVE_THREADS = 256;
+constexpr uint32_t CURVE_LDS_ENTRIES = 4096;
+
+__global__ __launch_bounds__(CURVE_THREADS) void k_curves(TableDev tb, uint32_t n_rows, uint32_t jb,
+                                                          const float *__restrict__ best_thr,
+                                                          const uint32_t *__restrict__ best_plan,
+                                                          float *__restrict__ curve_thr, uint32_t *__restrict__ curve_plan,
+                                                          uint32_t *__restrict__ curve_g) {
+    __shared__ float l_thr[CURVE_LDS_ENTRIES];
+    __shared__ uint32_t l_plan[CURVE_LDS_ENTRIES];
+    __shared__ uint32_t l_g[CURVE_LDS_ENTRIES];
+    const uint32_t j = jb + blockIdx.x, tid = threadIdx.x;
     const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
-    const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]) + (uint64_t)r * ns;
-    float cur = 0.f;
-    uint32_t plan = RK_NO_PLAN, g = 0;
-    for (uint32_t s = 0; s < ns; ++s) {
-        const float v = best_thr[sbase + s];
-        if (v > cur) { cur = v; plan = best_plan[sbase + s]; g = tb.seg_g[s0 + s]; }
-        curve_thr[sbase + s] = cur;
-        curve_plan[sbase + s] = plan;
-        curve_g[sbase + s] = g;
+    if (ns == 0) return;
+    const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]);
+    const uint32_t rows_per_chunk = CURVE_LDS_ENTRIES / ns;          // ns <= 2048, so at least 2
+    for (uint32_t r0 = 0; r0 < n_rows; r0 += rows_per_chunk) {
+        const uint32_t rows = r0 + rows_per_chunk < n_rows ? rows_per_chunk : n_rows - r0;
+        const uint32_t cnt = rows * ns;
+        const uint64_t off = sbase + (uint64_t)r0 * ns;
+        for (uint32_t i = tid; i < cnt; i += CURVE_THREADS) { l_thr[i] = best_thr[off + i]; l_plan[i] = best_plan[off + i]; }
+        __syncthreads();
+        for (uint32_t r = tid; r < rows; r += CURVE_THREADS) {
+            float cur = 0.f;
+            uint32_t plan = RK_NO_PLAN, g = 0;
+            for (uint32_t s = 0; s < ns; ++s) {
+                const float v = l_thr[r * ns + s];
+                if (v > cur) { cur = v; plan = l_plan[r * ns + s]; g = tb.seg_g[s0 + s]; }
+                l_thr[r * ns + s] = cur;
+                l_plan[r * ns + s] = plan;
+                l_g[r * ns + s] = g;
+            }
+        }
+        __syncthreads();
+        for (uint32_t i = tid; i < cnt; i += CURVE_THREADS) {
+            curve_thr[off + i] = l_thr[i]; curve_plan[off + i] = l_plan[i]; curve_g[off + i] = l_g[i];
+        }
+        __syncthreads();
     }
 }
 
@@ -273,11 +304,8 @@ int32_t rk_curves(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_grid *
     if (!best_thr || !best_plan || !curve_thr || !curve_plan || !curve_g) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null buffer");
     if (cap_segs < need) return rk_fail(ctx, RK_ERR_CAPACITY, "outputs hold %llu entries, %llu needed",
                                         (unsigned long long)cap_segs, (unsigned long long)need);
-    const uint64_t rows = (uint64_t)(je - jb) * n_rows;
-    const uint64_t blocks = (rows + 255) / 256;
-    if (blocks > 0x7FFFFFFFull) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "too many rows in one call; use job ranges");
-    k_curves<<<(uint32_t)blocks, 256, 0, ctx->stream>>>(table_dev(table), (uint32_t)n_rows, jb, je, best_thr, best_plan,
-                                                       curve_thr, curve_plan, curve_g);
+    k_curves<<<je - jb, CURVE_THREADS, 0, ctx->stream>>>(table_dev(table), (uint32_t)n_rows, jb, best_thr, best_plan,
+                                                        curve_thr, curve_plan, curve_g);
     RK_CHECK_LAUNCH(ctx, "k_curves");
     return RK_OK;
 }

@@ -9,7 +9,7 @@
 
 #include "rubick.h"
 
-enum { RK_SCRATCH_SLOTS = 16 };
+enum { RK_SCRATCH_SLOTS = 24 };
 
 struct rk_ctx {
     int device;
@@ -25,7 +25,8 @@ enum {
     SL_CNT_T = 0, SL_CNT_S, SL_TOTALS,            // enumeration: per-job counts, totals
     SL_TB_TOFF, SL_TB_TRIPLES, SL_TB_SOFF, SL_TB_SEGG, SL_TB_SEGF,   // internal plan table of a round
     SL_BEST_THR, SL_BEST_PLAN, SL_CURVE_THR, SL_CURVE_PLAN, SL_CURVE_G,  // round intermediates
-    SL_ROUND_META                                 // per-round job ranges and clusters
+    SL_ROUND_META,                                // per-round job ranges and clusters
+    SL_HULL_KEY, SL_HULL_DG, SL_HULL_TGT          // walk steps of the greedy allocation
 };
 
 int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);
@@ -71,7 +72,10 @@ int32_t rk_launch_fused(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *t
                         const rk_alloc_grid *grid, const rk_env *env, uint32_t jb, uint32_t je,
                         float *best_thr, uint32_t *best_plan, float *curve_thr, uint32_t *curve_plan,
                         uint32_t *curve_g);
+// one_cluster != NULL: a single round over [jb, jb + n_jobs) with that cluster, carried in the
+// kernel arguments; otherwise n_rounds rounds described by the device arrays.
 int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb, const rk_alloc_grid *grid,
                            uint32_t n_rounds, const uint32_t *d_round_off, const rk_cluster *d_clusters,
-                           uint32_t jb, uint32_t max_jobs_per_round, const float *best_thr, const uint32_t *best_plan,
+                           const rk_cluster *one_cluster, uint32_t jb, uint32_t n_jobs, uint32_t max_jobs,
+                           uint32_t max_segs_per_job, const float *best_thr, const uint32_t *best_plan,
                            const float *curve_thr, rk_assign *assign, float *totals);

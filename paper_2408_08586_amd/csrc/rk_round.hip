@@ -33,12 +33,15 @@ int32_t rk_schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bound
                        RK_MAX_JOBS_PER_ROUND);
     RK_HIP(ctx, hipSetDevice(ctx->device));
 
-    // round ranges and clusters go up first; the wait inside the enumeration covers the copy
+    // round ranges and clusters go up first; the wait inside the enumeration covers the copy.
+    // A single round travels in the kernel arguments instead.
     const size_t off_bytes = (((size_t)n_rounds + 1) * 4 + 15) & ~(size_t)15;
-    char *d_meta;
-    if ((rc = rk_scratch(ctx, SL_ROUND_META, off_bytes + (size_t)n_rounds * sizeof(rk_cluster), (void **)&d_meta))) return rc;
-    RK_HIP(ctx, hipMemcpyAsync(d_meta, round_off, ((size_t)n_rounds + 1) * 4, hipMemcpyHostToDevice, ctx->stream));
-    RK_HIP(ctx, hipMemcpyAsync(d_meta + off_bytes, clusters, (size_t)n_rounds * sizeof(rk_cluster), hipMemcpyHostToDevice, ctx->stream));
+    char *d_meta = nullptr;
+    if (n_rounds > 1) {
+        if ((rc = rk_scratch(ctx, SL_ROUND_META, off_bytes + (size_t)n_rounds * sizeof(rk_cluster), (void **)&d_meta))) return rc;
+        RK_HIP(ctx, hipMemcpyAsync(d_meta, round_off, ((size_t)n_rounds + 1) * 4, hipMemcpyHostToDevice, ctx->stream));
+        RK_HIP(ctx, hipMemcpyAsync(d_meta + off_bytes, clusters, (size_t)n_rounds * sizeof(rk_cluster), hipMemcpyHostToDevice, ctx->stream));
+    }
 
     // internal plan table in scratch memory; grown on demand
     rk_plan_table tb;
@@ -75,8 +78,9 @@ int32_t rk_schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bound
     if ((rc = rk_launch_fused(ctx, jobs, &tb, grid, env, 0, J, best_thr, best_plan, curve_thr, curve_plan, curve_g))) return rc;
     return rk_launch_allocate(ctx, jobs->ref_thr, table_dev(&tb), grid, n_rounds,
                               reinterpret_cast<const uint32_t *>(d_meta),
-                              reinterpret_cast<const rk_cluster *>(d_meta + off_bytes), 0, max_jobs, best_thr,
-                              best_plan, curve_thr, assign, totals);
+                              d_meta ? reinterpret_cast<const rk_cluster *>(d_meta + off_bytes) : nullptr,
+                              n_rounds == 1 ? &clusters[0] : nullptr, 0, J, max_jobs, tb.max_segs_per_job,
+                              best_thr, best_plan, curve_thr, assign, totals);
 }
 
 int32_t rk_schedule_round(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,

@@ -213,6 +213,42 @@ def test_allocate_on_oracle_curves_is_exact(gpu, orc, name):
     run.close()
 
 
+@pytest.mark.parametrize("n_jobs", [3000, 12288])
+def test_allocate_many_jobs_random_curves(gpu, orc, n_jobs):
+    """The allocation alone at its largest sizes: the per-segment values are
+    drawn here (not produced by either implementation), so both sides see the
+    same float32 inputs and must return identical records."""
+    import paper_2408_08586_amd as rk
+    rng = np.random.default_rng(n_jobs)
+    base = workloads.stress(n_jobs=n_jobs)
+    b = workloads.Bounds(g_max=64)
+    wl = workloads.Workload("alloc", base.coef, base.ints, b, base.grid, base.env, workloads.Cluster(4096, 30000, 2.0e5))
+    ot = orc.enumerate_plans(wl.ints, wl.bounds)
+    n_rows = 20
+    n = ot.n_segments(n_rows)
+    # throughput grows roughly with g, is noisy, sometimes infeasible, sometimes exactly tied
+    g_of = np.concatenate([np.tile(ot.seg_g[ot.seg_off[j]:ot.seg_off[j + 1]], n_rows) for j in range(n_jobs)])
+    bt = (g_of ** rng.uniform(0.3, 1.0, n)) * rng.uniform(0.5, 1.5, n)
+    bt = np.round(bt * 8) / 8                                    # coarse values: many exact ties
+    bt[rng.uniform(size=n) < 0.15] = 0
+    bt = bt.astype(np.float32)
+    bp = rng.integers(0, 1000, n).astype(np.uint32)
+    bp[bt == 0] = 0xFFFFFFFF
+    ct, _, _ = orc.curves(ot, wl.grid, bt, bp)
+    run = gpu(wl)
+    run.enumerate()
+    oracle_table_equal(run.table_numpy(), ot)
+    d_bt, d_bp, d_ct = run.dev_f32(bt), run.dev_u32(bp), run.dev_f32(ct)
+    for G, Cc, M in ((4096, 30000, 2.0e5), (4096, 5000, 1.0e9), (300, 100000, 3000.0), (20000, 10 ** 6, 1.0e9)):
+        cl = workloads.Cluster(G, Cc, M)
+        e_assign, e_total, _ = orc.greedy(wl.coef[:, 16], ot, wl.grid, cl, bt, bp, ct)
+        assign, total = run.allocate(d_bt, d_bp, d_ct, cluster=rk.make_cluster(cl))
+        assert np.array_equal(assign, e_assign), (G, Cc, M)
+        assert total == pytest.approx(e_total, rel=1e-6)
+        assert assign["g"].sum() <= G and assign["c"].sum() <= Cc
+    run.close()
+
+
 def compare_rounds(assign, total, r):
     """End-to-end result against the oracle's round.  Where every decision of
     the oracle's greedy was clear (smallest slope gap well above float32
