@@ -79,7 +79,7 @@ __global__ __launch_bounds__(EVAL_THREADS) void k_eval(JobDev jobs, TableDev tb,
             v.z = plain[1];
             v.w = w1 ? 0.f : off_thr[1];
             const uint64_t idx = cbase + ((uint64_t)(ci * grid.n_mem + mi) * nt + tl) * 16 + z * 4;
-            __builtin_nontemporal_store(v, reinterpret_cast<v4f *>(thr + idx));
+            *reinterpret_cast<v4f *>(thr + idx) = v;
             if (WITH_FEAS) {
                 const uint32_t packed = why_plain[0] | (w0 << 8) | (why_plain[1] << 16) | (w1 << 24);
                 *reinterpret_cast<uint32_t *>(feas + idx) = packed;

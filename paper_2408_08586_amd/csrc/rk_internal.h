@@ -9,7 +9,7 @@
 
 #include "rubick.h"
 
-enum { RK_SCRATCH_SLOTS = 24 };
+enum { RK_SCRATCH_SLOTS = 32 };
 
 struct rk_ctx {
     int device;
@@ -26,7 +26,8 @@ enum {
     SL_TB_TOFF, SL_TB_TRIPLES, SL_TB_SOFF, SL_TB_SEGG, SL_TB_SEGF,   // internal plan table of a round
     SL_BEST_THR, SL_BEST_PLAN, SL_CURVE_THR, SL_CURVE_PLAN, SL_CURVE_G,  // round intermediates
     SL_ROUND_META,                                // per-round job ranges and clusters
-    SL_HULL_KEY, SL_HULL_DG, SL_HULL_TGT          // walk steps of the greedy allocation
+    SL_HULL_KEY, SL_HULL_RAW, SL_HULL_DG, SL_HULL_DC, SL_HULL_TGT,   // walk steps of the greedy allocation
+    SL_ST_GI, SL_ST_G, SL_ST_CI, SL_ST_FREEC, SL_ST_PARTIAL          // its per-job and per-round state
 };
 
 int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);
