@@ -6,19 +6,24 @@
 // The rule is sequential: repeatedly take the (job, larger amount) with the
 // highest float32 slope ((v1 - v0) / ref_thr) / delta among the steps that
 // still fit; ties go to the smaller amount, then to the lower job index.
-// It is evaluated without running every step in sequence:
+// It is evaluated without running every step in sequence.  Per pass (GPUs,
+// then CPUs):
 //
-//  1. Each job's steps, were capacity never short, form a fixed walk over the
-//     upper hull of its curve (k_hull, one wavefront per job).  With each
-//     slope replaced by the running minimum of the walk, the sequential order
-//     is the descending order of these keys (then job, then walk position).
-//  2. A radix select over the key bits finds the largest key threshold whose
-//     whole set of steps fits the capacity; that set is a prefix of the
-//     sequential order and is applied at once (k_pass, one workgroup per round).
-//  3. From there the plain step-by-step loop runs on the little capacity that
-//     is left: a workgroup-wide argmax over cached per-job best steps.
+//  k_hull   Each job's steps, were capacity never short, form a fixed walk
+//           over the upper hull of its curve (one wavefront per job).  With
+//           each slope replaced by the running minimum of the walk, the
+//           sequential order is the descending order of these keys (then job,
+//           then position in the walk).
+//  k_hist   Any key threshold whose whole set of steps {key > threshold} fits
+//           the capacity selects a prefix of the sequential order.  Two
+//           histogram levels over the top 12 + 12 key bits (cost per bin) find
+//           the largest such threshold at 24-bit resolution.
+//  k_apply  applies that prefix to every job at once and caches each job's
+//           next step (the walk's next step if it still fits, otherwise a fresh
+//           search within the capacity that is left).
+//  k_tail   the plain step-by-step loop on the little capacity that is left:
+//           one workgroup per round, argmax over the cached steps in LDS.
 //
-// The same three stages run for the GPU pass and then for the CPU pass.
 // Memory (k_mem_wish / k_mem_finish): when the tiers every job would like fit
 // with margin, all are granted in parallel; otherwise one wavefront takes the
 // decisions in job order.
@@ -27,13 +32,14 @@
 
 namespace {
 
-constexpr int PASS_THREADS = 1024;
-constexpr int PASS_WAVES = PASS_THREADS / 64;
+constexpr int TAIL_THREADS = 1024;
+constexpr int TAIL_WAVES = TAIL_THREADS / 64;
 constexpr int HULL_THREADS = 256;
-constexpr int WISH_THREADS = 256;
+constexpr int JOB_THREADS = 256;           // kernels with one thread per job
+constexpr uint32_t BINS = 4096;            // 12 key bits per histogram level
 
 struct HullBuf {             // walk steps, entry (k, job) at k*stride + job (job relative to the call's first job)
-    uint32_t *key;           // float bits of the running-minimum slope; 0 ends a walk
+    uint32_t *key;           // float bits of the running-minimum slope; 0 from the end of the walk on
     float *raw;              // the step's own slope
     uint16_t *tgt;           // target: segment index (GPU pass) or CPU level (CPU pass)
     uint32_t *dg;            // GPUs the step adds
@@ -41,11 +47,18 @@ struct HullBuf {             // walk steps, entry (k, job) at k*stride + job (jo
     uint32_t stride, width;
 };
 
+struct Hist {                // per round, pass and level: cost of the steps per key bin
+    uint32_t *g;             // [n_rounds][2 passes][2 levels][BINS]
+    unsigned long long *c;
+};
+
 struct JobState {            // per job of the call, between the kernels
     int32_t *gi;             // granted segment index, -1 = no GPUs
     uint32_t *g;             // granted GPUs
     uint32_t *ci;            // granted CPU level
-    unsigned long long *free_c;   // per round: CPUs left after the GPU pass
+    float *step_slope;       // cached best next step: slope (0 = none), target, GPUs it adds
+    uint16_t *step_tgt, *step_dg;
+    unsigned long long *free_g, *free_c;   // per round: capacity left (after apply; after the tail)
     double *partial;         // per round and block of k_mem_wish: {sum of wish GiB, sum of thr/ref}
     uint32_t blocks_per_round;
 };
@@ -58,6 +71,17 @@ struct RoundArgs {
     uint32_t n_rounds, inline_one;
     uint32_t off0, off1;
     rk_cluster cl;
+};
+
+struct Ctx {                 // what every kernel of the allocation needs
+    const float *ref_thr;
+    TableDev tb;
+    GridDev grid;
+    RoundArgs R;
+    uint32_t jb;             // first job of the call (origin of the segment-layout arrays)
+    const float *best_thr;
+    const uint32_t *best_plan;
+    const float *curve_thr;
 };
 
 __device__ __forceinline__ void round_of(const RoundArgs &R, uint32_t r, uint32_t &j0, uint32_t &j1, rk_cluster &cl) {
@@ -93,27 +117,39 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
     return v;
 }
 
+__device__ __forceinline__ size_t hist_at(uint32_t rnd, int pass, int level) {
+    return (((size_t)rnd * 2 + pass) * 2 + level) * BINS;
+}
+
+// capacities a pass starts from
+template <int PASS>
+__device__ __forceinline__ void pass_caps(const rk_cluster &cl, const JobState &st, uint32_t rnd,
+                                          unsigned long long &capG, unsigned long long &capC) {
+    if (PASS == 0) { capG = cl.G; capC = cl.C; }
+    else { capG = 0; capC = st.free_c[rnd]; }
+}
+
 // ------------------------------------------------------------------ hull walks
 // One wavefront per job; lanes hold the candidate amounts.  PASS 0: GPU counts
 // of the job (lowest CPU level, highest memory tier, values from the curves);
 // PASS 1: CPU levels at the granted GPU count (values from the per-segment
 // maxima).  Amounts that the whole round could never afford are left out.
 template <int PASS>
-__global__ __launch_bounds__(HULL_THREADS) void k_hull(const float *__restrict__ ref_thr, TableDev tb, GridDev grid,
-                                                       RoundArgs R, uint32_t jb, const float *__restrict__ vals,
-                                                       JobState st, HullBuf H) {
+__global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullBuf H) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t jrel = blockIdx.x * (HULL_THREADS / 64) + (threadIdx.x >> 6);
     if (jrel >= H.stride) return;                         // whole wavefront
-    const uint32_t j = jb + jrel;
-    const uint32_t rnd = round_index_of(R, j);
+    const uint32_t j = X.jb + jrel;
+    const uint32_t rnd = round_index_of(X.R, j);
     uint32_t rj0, rj1;
     rk_cluster cl;
-    round_of(R, rnd, rj0, rj1, cl);
+    round_of(X.R, rnd, rj0, rj1, cl);
+    const GridDev &grid = X.grid;
+    const float *__restrict__ vals = PASS == 0 ? X.curve_thr : X.best_thr;
     const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem;
-    const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
-    const uint64_t jbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]);
-    const float ref = ref_thr[j];
+    const uint32_t s0 = X.tb.seg_off[j], ns = X.tb.seg_off[j + 1] - s0;
+    const uint64_t jbase = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]);
+    const float ref = X.ref_thr[j];
 
     uint32_t npts, g_fixed = 0;
     int32_t cur_i;
@@ -133,13 +169,13 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(const float *__restrict__
     }
     // amount s: its cost in the pass's resource and its value
     auto cost_of = [&](uint32_t s) -> unsigned long long {
-        return PASS == 0 ? (unsigned long long)tb.seg_g[s0 + s] : cpu_cost(grid, s, g_fixed);
+        return PASS == 0 ? (unsigned long long)X.tb.seg_g[s0 + s] : cpu_cost(grid, s, g_fixed);
     };
     auto value_of = [&](uint32_t s) -> float {
         return PASS == 0 ? vals[jbase + (uint64_t)(n_mem - 1) * ns + s]
                          : vals[jbase + (uint64_t)(s * n_mem + n_mem - 1) * ns + gi];
     };
-    auto affordable = [&](uint32_t s, unsigned long long cost) -> bool {
+    auto affordable = [&](unsigned long long cost) -> bool {
         if (PASS == 0) return cost <= cl.G && cpu_cost(grid, 0, (uint32_t)cost) <= cap_c;
         return cost <= cap_c;
     };
@@ -152,7 +188,7 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(const float *__restrict__
             const uint32_t s = base + lane;
             if (s < npts && (int32_t)s > cur_i) {
                 const unsigned long long cost = cost_of(s);
-                if (affordable(s, cost)) {
+                if (affordable(cost)) {
                     const float v = value_of(s);
                     if (v > cur) {
                         float sl = (v - cur) / ref;
@@ -187,18 +223,214 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(const float *__restrict__
         cost_cur = top_cost;
         ++k;
     }
-    if (k < H.width && lane == 0) H.key[(size_t)k * H.stride + jrel] = 0u;
+    for (uint32_t kk = k + lane; kk < H.width; kk += 64) H.key[(size_t)kk * H.stride + jrel] = 0u;   // unused positions
 }
 
-// ------------------------------------------------------------------ one pass of a round
-struct SelectShared {
-    unsigned long long baseG, baseC;
-    unsigned int prefix, done, thr;
-    unsigned int histG[256];
-    unsigned long long histC[256];
-    unsigned long long red[PASS_WAVES];
+// ------------------------------------------------------------------ threshold search
+// Highest bin whose steps, added to everything above it, no longer fit.
+// bin = -1: all bins fit.  base*: cost of the bins above `bin`.
+struct Cut { int32_t bin; unsigned long long baseG, baseC; };
+
+struct CutScratch {
+    unsigned long long sg[JOB_THREADS], sc[JOB_THREADS];
+    int32_t cand[JOB_THREADS];
+    unsigned long long candG[JOB_THREADS], candC[JOB_THREADS];
 };
 
+// Workgroup-wide (JOB_THREADS threads), every thread gets the result.
+__device__ Cut find_cut(const uint32_t *__restrict__ hG, const unsigned long long *__restrict__ hC,
+                        unsigned long long baseG, unsigned long long baseC, unsigned long long capG,
+                        unsigned long long capC, CutScratch &S) {
+    constexpr uint32_t PER = BINS / JOB_THREADS;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t top = BINS - 1 - tid * PER;           // this thread's bins: top, top-1, ... (descending)
+    unsigned long long sg = 0, sc = 0;
+    for (uint32_t i = 0; i < PER; ++i) { sg += hG[top - i]; sc += hC[top - i]; }
+    S.sg[tid] = sg; S.sc[tid] = sc;
+    __syncthreads();
+    for (uint32_t off = 1; off < JOB_THREADS; off <<= 1) {
+        const unsigned long long ag = tid >= off ? S.sg[tid - off] : 0ull, ac = tid >= off ? S.sc[tid - off] : 0ull;
+        __syncthreads();
+        S.sg[tid] += ag; S.sc[tid] += ac;
+        __syncthreads();
+    }
+    unsigned long long cg = baseG + S.sg[tid] - sg, cc = baseC + S.sc[tid] - sc;   // everything above this thread's bins
+    int32_t cand = -1;
+    for (uint32_t i = 0; i < PER; ++i) {
+        const uint32_t b = top - i;
+        if (cg + hG[b] > capG || cc + hC[b] > capC) { cand = (int32_t)b; break; }
+        cg += hG[b]; cc += hC[b];
+    }
+    S.cand[tid] = cand; S.candG[tid] = cg; S.candC[tid] = cc;
+    __syncthreads();
+    Cut out;
+    out.bin = -1;
+    out.baseG = baseG + S.sg[JOB_THREADS - 1];
+    out.baseC = baseC + S.sc[JOB_THREADS - 1];
+    for (uint32_t t = 0; t < JOB_THREADS; ++t) {          // the first thread (highest bins) with a failing bin
+        if (S.cand[t] >= 0) { out.bin = S.cand[t]; out.baseG = S.candG[t]; out.baseC = S.candC[t]; break; }
+    }
+    __syncthreads();
+    return out;
+}
+
+// Cost histogram of one level.  Level 0: bin = key bits 31..20 of every step.
+// Level 1: key bits 19..8 of the steps inside the bin where level 0 was cut.
+template <int PASS, int LEVEL>
+__global__ __launch_bounds__(JOB_THREADS) void k_hist(Ctx X, JobState st, HullBuf H, Hist hist) {
+    __shared__ uint32_t lg[BINS];
+    __shared__ unsigned long long lc[BINS];
+    __shared__ CutScratch cs;
+    const uint32_t rnd = blockIdx.y, tid = threadIdx.x;
+    uint32_t J0, J1;
+    rk_cluster cl;
+    round_of(X.R, rnd, J0, J1, cl);
+    int32_t want_top = 0;
+    if (LEVEL == 1) {
+        unsigned long long capG, capC;
+        pass_caps<PASS>(cl, st, rnd, capG, capC);
+        const size_t h0 = hist_at(rnd, PASS, 0);
+        const Cut c0 = find_cut(hist.g + h0, hist.c + h0, 0, 0, capG, capC, cs);
+        if (c0.bin < 0) return;                           // everything fits: no second level needed
+        want_top = c0.bin;
+    }
+    for (uint32_t i = tid; i < BINS; i += JOB_THREADS) { lg[i] = 0; lc[i] = 0; }
+    __syncthreads();
+    const uint32_t jl = blockIdx.x * JOB_THREADS + tid;
+    const uint32_t width = PASS == 0 ? H.width : (X.grid.n_cpu - 1 < H.width ? X.grid.n_cpu - 1 : H.width);
+    if (J0 + jl < J1) {
+        const uint32_t jrel = J0 + jl - X.jb;
+        for (uint32_t k = 0; k < width; ++k) {
+            const size_t e = (size_t)k * H.stride + jrel;
+            const uint32_t key = H.key[e];
+            if (!key) break;
+            uint32_t bin;
+            if (LEVEL == 0) bin = key >> 20;
+            else {
+                if ((int32_t)(key >> 20) > want_top) continue;
+                if ((int32_t)(key >> 20) < want_top) break;   // keys only decrease along a walk
+                bin = (key >> 8) & (BINS - 1);
+            }
+            const uint32_t dg = H.dg[e];
+            const unsigned long long dc = H.dc[e];
+            if (dg) atomicAdd(&lg[bin], dg);
+            if (dc) atomicAdd(&lc[bin], dc);
+        }
+    }
+    __syncthreads();
+    const size_t h = hist_at(rnd, PASS, LEVEL);
+    for (uint32_t i = tid; i < BINS; i += JOB_THREADS) {
+        if (lg[i]) atomicAdd(&hist.g[h + i], lg[i]);
+        if (lc[i]) atomicAdd(&hist.c[h + i], lc[i]);
+    }
+}
+
+// ------------------------------------------------------------------ best step from scratch
+struct Step { float slope; uint32_t tgt, dg; };
+
+// Best step of job j from its current state under the free capacity.
+template <int PASS>
+__device__ __forceinline__ Step best_step(const Ctx &X, uint32_t j, int32_t gi, uint32_t g_held, uint32_t ci,
+                                          unsigned long long freeG, unsigned long long freeC) {
+    const GridDev &grid = X.grid;
+    const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem, m_top = n_mem - 1;
+    const uint32_t s0 = X.tb.seg_off[j], ns = X.tb.seg_off[j + 1] - s0;
+    const uint64_t jbase = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]);
+    const float ref = X.ref_thr[j];
+    Step out = {0.f, 0u, 0u};
+    if (PASS == 0) {
+        const uint32_t g_cur = gi < 0 ? 0u : X.tb.seg_g[s0 + gi];
+        const uint64_t row = jbase + (uint64_t)m_top * ns;                     // CPU level 0
+        const float cur = gi < 0 ? 0.f : X.curve_thr[row + gi];
+        const unsigned long long c_cur = gi < 0 ? 0ull : cpu_cost(grid, 0, g_cur);
+        for (uint32_t s = (uint32_t)(gi + 1); s < ns; ++s) {
+            const uint32_t dg = X.tb.seg_g[s0 + s] - g_cur;
+            if (dg > freeG) break;
+            const float v = X.curve_thr[row + s];
+            if (!(v > cur)) continue;
+            if (cpu_cost(grid, 0, g_cur + dg) - c_cur > freeC) continue;
+            float sl = (v - cur) / ref;
+            sl = sl / (float)dg;
+            if (sl > out.slope) { out.slope = sl; out.tgt = s; out.dg = dg; }
+        }
+    } else if (gi >= 0) {
+        const float cur = X.best_thr[jbase + (uint64_t)(ci * n_mem + m_top) * ns + gi];
+        const unsigned long long have = cpu_cost(grid, ci, g_held);
+        for (uint32_t c = ci + 1; c < grid.n_cpu; ++c) {
+            const unsigned long long dc = cpu_cost(grid, c, g_held) - have;
+            if (dc > freeC) break;
+            const float v = X.best_thr[jbase + (uint64_t)(c * n_mem + m_top) * ns + gi];
+            if (!(v > cur)) continue;
+            float sl = (v - cur) / ref;
+            sl = sl / (float)dc;
+            if (sl > out.slope) { out.slope = sl; out.tgt = c; }
+        }
+    }
+    return out;
+}
+
+// ------------------------------------------------------------------ apply the selected prefix
+// One thread per job.  Every workgroup derives the threshold from the two
+// histogram levels (same inputs, same result in all of them).
+template <int PASS>
+__global__ __launch_bounds__(JOB_THREADS) void k_apply(Ctx X, JobState st, HullBuf H, Hist hist) {
+    __shared__ CutScratch cs;
+    const uint32_t rnd = blockIdx.y, tid = threadIdx.x;
+    uint32_t J0, J1;
+    rk_cluster cl;
+    round_of(X.R, rnd, J0, J1, cl);
+    unsigned long long capG, capC;
+    pass_caps<PASS>(cl, st, rnd, capG, capC);
+    const size_t h0 = hist_at(rnd, PASS, 0), h1 = hist_at(rnd, PASS, 1);
+    const Cut c0 = find_cut(hist.g + h0, hist.c + h0, 0, 0, capG, capC, cs);
+    long long thr24 = -1;                                  // steps with (key >> 8) > thr24 are applied
+    unsigned long long usedG = c0.baseG, usedC = c0.baseC;
+    if (c0.bin >= 0) {
+        const Cut c1 = find_cut(hist.g + h1, hist.c + h1, c0.baseG, c0.baseC, capG, capC, cs);
+        thr24 = ((long long)c0.bin << 12) + (long long)c1.bin;   // c1.bin = -1: the whole of c0.bin fits as well
+        usedG = c1.baseG; usedC = c1.baseC;
+    }
+    const unsigned long long freeG = capG - usedG, freeC = capC - usedC;
+
+    const uint32_t jl = blockIdx.x * JOB_THREADS + tid;
+    if (J0 + jl < J1) {
+        const uint32_t j = J0 + jl, jrel = j - X.jb;
+        const uint32_t width = PASS == 0 ? H.width : (X.grid.n_cpu - 1 < H.width ? X.grid.n_cpu - 1 : H.width);
+        int32_t gi = PASS == 0 ? -1 : st.gi[jrel];
+        uint32_t g_held = PASS == 0 ? 0u : st.g[jrel];
+        uint32_t ci = 0;
+        uint32_t k = 0, key = 0;
+        size_t e = 0;
+        for (; k < width; ++k) {
+            e = (size_t)k * H.stride + jrel;
+            key = H.key[e];
+            if (!key || (long long)(key >> 8) <= thr24) break;
+            if (PASS == 0) gi = (int32_t)H.tgt[e]; else ci = H.tgt[e];
+        }
+        if (k == width) key = 0;
+        if (PASS == 0) {
+            g_held = gi < 0 ? 0u : X.tb.seg_g[X.tb.seg_off[j] + gi];
+            st.gi[jrel] = gi;
+            st.g[jrel] = g_held;
+        } else {
+            st.ci[jrel] = ci;
+        }
+        // the job's best next step: the walk's next step if it still fits, else a fresh search
+        Step nx = {0.f, 0u, 0u};
+        if (key) {
+            if (H.dg[e] <= freeG && H.dc[e] <= freeC) { nx.slope = H.raw[e]; nx.tgt = H.tgt[e]; nx.dg = H.dg[e]; }
+            else nx = best_step<PASS>(X, j, gi, g_held, ci, freeG, freeC);
+        }
+        st.step_slope[jrel] = nx.slope;
+        st.step_tgt[jrel] = (uint16_t)nx.tgt;
+        st.step_dg[jrel] = (uint16_t)nx.dg;
+    }
+    // the capacity left goes to the tail through a second pair of words: the
+    // pass's starting capacity (free_c) is still being read by other workgroups
+    if (blockIdx.x == 0 && tid == 0) { st.free_g[rnd] = freeG; st.free_g[X.R.n_rounds + rnd] = freeC; }
+}
+
+// ------------------------------------------------------------------ step by step on what is left
 // workgroup-wide maximum of a key; every thread gets the result
 __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v, unsigned long long *red) {
     v = wave_max_u64(v);
@@ -206,17 +438,15 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
     __syncthreads();
     unsigned long long m = red[0];
 #pragma unroll
-    for (int w = 1; w < PASS_WAVES; ++w) m = red[w] > m ? red[w] : m;
+    for (int w = 1; w < TAIL_WAVES; ++w) m = red[w] > m ? red[w] : m;
     __syncthreads();
     return m;
 }
 
 template <int PASS>
-__global__ __launch_bounds__(PASS_THREADS) void k_pass(const float *__restrict__ ref_thr, TableDev tb, GridDev grid,
-                                                       RoundArgs R, uint32_t jb, uint32_t max_jobs,
-                                                       const float *__restrict__ vals, HullBuf H, JobState st) {
+__global__ __launch_bounds__(TAIL_THREADS) void k_tail(Ctx X, uint32_t max_jobs, JobState st) {
     extern __shared__ float lds_dyn[];
-    __shared__ SelectShared sel;
+    __shared__ unsigned long long red[TAIL_WAVES];
     float *slope = lds_dyn;                                        // cached best step of each job (0 = none)
     uint16_t *tgt = reinterpret_cast<uint16_t *>(slope + max_jobs);   // its target (segment index or CPU level)
     uint16_t *aux = tgt + max_jobs;                                // PASS 0: GPUs the step adds; PASS 1: GPUs held
@@ -226,114 +456,20 @@ __global__ __launch_bounds__(PASS_THREADS) void k_pass(const float *__restrict__
     const uint32_t tid = threadIdx.x, rnd = blockIdx.x;
     uint32_t J0, J1;
     rk_cluster cl;
-    round_of(R, rnd, J0, J1, cl);
-    const uint32_t nj = J1 - J0;
-    const uint32_t jrel0 = J0 - jb;
-    const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem, m_top = n_mem - 1;
-    const uint32_t seg_base = tb.seg_off[jb];
-    unsigned long long freeG = PASS == 0 ? cl.G : 0ull;
-    unsigned long long freeC = PASS == 0 ? cl.C : st.free_c[rnd];
-    const uint32_t width = PASS == 0 ? H.width : (grid.n_cpu - 1 < H.width ? grid.n_cpu - 1 : H.width);
+    round_of(X.R, rnd, J0, J1, cl);
+    const uint32_t nj = J1 - J0, jrel0 = J0 - X.jb;
+    const GridDev &grid = X.grid;
+    unsigned long long freeG = st.free_g[rnd], freeC = st.free_g[X.R.n_rounds + rnd];
 
-    for (uint32_t jl = tid; jl < nj; jl += PASS_THREADS) {
-        if (PASS == 0) { gi[jl] = -1; ci[jl] = 0; }
-        else { gi[jl] = (int16_t)st.gi[jrel0 + jl]; aux[jl] = (uint16_t)st.g[jrel0 + jl]; ci[jl] = 0; }
+    for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {
+        slope[jl] = st.step_slope[jrel0 + jl];
+        tgt[jl] = st.step_tgt[jrel0 + jl];
+        gi[jl] = (int16_t)st.gi[jrel0 + jl];
+        if (PASS == 0) { aux[jl] = st.step_dg[jrel0 + jl]; ci[jl] = 0; }
+        else { aux[jl] = (uint16_t)st.g[jrel0 + jl]; ci[jl] = (uint16_t)st.ci[jrel0 + jl]; }
     }
-    if (tid == 0) { sel.baseG = 0; sel.baseC = 0; sel.prefix = 0; sel.done = 0; sel.thr = 0; }
     __syncthreads();
 
-    // ---- radix select: the largest set {key > thr} whose total cost fits
-    for (int shift = 24; shift >= 0 && width > 0; shift -= 8) {
-        for (uint32_t i = tid; i < 256; i += PASS_THREADS) { sel.histG[i] = 0; sel.histC[i] = 0; }
-        __syncthreads();
-        const uint32_t prefix = sel.prefix;
-        for (uint32_t jl = tid; jl < nj; jl += PASS_THREADS) {
-            for (uint32_t k = 0; k < width; ++k) {
-                const size_t e = (size_t)k * H.stride + jrel0 + jl;
-                const uint32_t key = H.key[e];
-                if (!key) break;
-                const uint32_t hi = shift == 24 ? 0u : key >> (shift + 8);
-                if (hi < prefix) break;                        // keys only decrease along a walk
-                if (hi == prefix) {
-                    const uint32_t bin = (key >> shift) & 255u;
-                    const uint32_t dg = H.dg[e];
-                    const unsigned long long dc = H.dc[e];
-                    if (dg) atomicAdd(&sel.histG[bin], dg);
-                    if (dc) atomicAdd(&sel.histC[bin], dc);
-                }
-            }
-        }
-        __syncthreads();
-        if (tid == 0) {
-            unsigned long long cg = sel.baseG, cc = sel.baseC;
-            int b = 255;
-            while (b >= 0 && cg + sel.histG[b] <= freeG && cc + sel.histC[b] <= freeC) {
-                cg += sel.histG[b]; cc += sel.histC[b]; --b;
-            }
-            sel.baseG = cg; sel.baseC = cc;
-            if (b < 0) {                                       // everything under this prefix fits
-                const unsigned long long lower = (unsigned long long)prefix << (shift + 8);
-                sel.thr = lower ? (unsigned int)(lower - 1) : 0u;
-                sel.done = 1;
-            } else {
-                sel.prefix = (prefix << 8) | (unsigned int)b;
-                if (shift == 0) sel.thr = sel.prefix;          // this key's group does not fit as a whole
-            }
-        }
-        __syncthreads();
-        if (sel.done) break;
-    }
-    const uint32_t thr = sel.thr;
-    freeG -= sel.baseG;
-    freeC -= sel.baseC;
-
-    // position of (job, row, segment) in the segment-layout arrays
-    auto at = [&](uint32_t j, uint32_t c, uint32_t mi, uint32_t s) -> uint64_t {
-        const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
-        return (uint64_t)n_rows * (s0 - seg_base) + (uint64_t)(c * n_mem + mi) * ns + s;
-    };
-    // best step of local job jl under the current free capacity, from scratch
-    auto best_step = [&](uint32_t jl) {
-        const uint32_t j = J0 + jl;
-        float top = 0.f;
-        uint32_t top_t = 0, top_aux = 0;
-        if (PASS == 0) {
-            const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
-            const int32_t cur_i = gi[jl];
-            const uint32_t g_cur = cur_i < 0 ? 0u : tb.seg_g[s0 + cur_i];
-            const uint64_t row = (uint64_t)n_rows * (s0 - seg_base) + (uint64_t)m_top * ns;   // CPU level 0
-            const float cur = cur_i < 0 ? 0.f : vals[row + cur_i];
-            const float ref = ref_thr[j];
-            const unsigned long long c_cur = cur_i < 0 ? 0ull : cpu_cost(grid, 0, g_cur);
-            for (uint32_t s = (uint32_t)(cur_i + 1); s < ns; ++s) {
-                const uint32_t dg = tb.seg_g[s0 + s] - g_cur;
-                if (dg > freeG) break;
-                const float v = vals[row + s];
-                if (!(v > cur)) continue;
-                if (cpu_cost(grid, 0, g_cur + dg) - c_cur > freeC) continue;
-                float sl = (v - cur) / ref;
-                sl = sl / (float)dg;
-                if (sl > top) { top = sl; top_t = s; top_aux = dg; }
-            }
-            aux[jl] = (uint16_t)top_aux;
-        } else if (gi[jl] >= 0) {
-            const uint32_t g = aux[jl], c0 = ci[jl], s_i = (uint32_t)gi[jl];
-            const float cur = vals[at(j, c0, m_top, s_i)];
-            const float ref = ref_thr[j];
-            const unsigned long long have = cpu_cost(grid, c0, g);
-            for (uint32_t c = c0 + 1; c < grid.n_cpu; ++c) {
-                const unsigned long long dc = cpu_cost(grid, c, g) - have;
-                if (dc > freeC) break;
-                const float v = vals[at(j, c, m_top, s_i)];
-                if (!(v > cur)) continue;
-                float sl = (v - cur) / ref;
-                sl = sl / (float)dc;
-                if (sl > top) { top = sl; top_t = c; }
-            }
-        }
-        slope[jl] = top;
-        tgt[jl] = (uint16_t)top_t;
-    };
     // CPUs a cached step of job jl costs
     auto step_cpus = [&](uint32_t jl) -> unsigned long long {
         if (PASS == 0)
@@ -341,63 +477,69 @@ __global__ __launch_bounds__(PASS_THREADS) void k_pass(const float *__restrict__
                                  : (gi[jl] < 0 ? (unsigned long long)grid.cpu_levels[0] : 0ull);
         return cpu_cost(grid, tgt[jl], aux[jl]) - cpu_cost(grid, ci[jl], aux[jl]);
     };
-
-    // ---- apply the selected prefix of every walk; the next step of the walk,
-    // if it still fits, is the job's best step, otherwise it is searched anew
-    for (uint32_t jl = tid; jl < nj; jl += PASS_THREADS) {
-        uint32_t k = 0;
-        uint32_t key = 0;
-        size_t e = 0;
-        for (; k < width; ++k) {
-            e = (size_t)k * H.stride + jrel0 + jl;
-            key = H.key[e];
-            if (!key || key <= thr) break;
-            if (PASS == 0) gi[jl] = (int16_t)H.tgt[e]; else ci[jl] = H.tgt[e];
-        }
-        if (k == width) key = 0;
-        if (!key) {                                            // the walk is over: nothing left to gain
-            slope[jl] = 0.f; tgt[jl] = 0; if (PASS == 0) aux[jl] = 0;
-        } else if (H.dg[e] <= freeG && H.dc[e] <= freeC) {
-            slope[jl] = H.raw[e]; tgt[jl] = H.tgt[e]; if (PASS == 0) aux[jl] = (uint16_t)H.dg[e];
-        } else {
-            best_step(jl);
-        }
-    }
-    __syncthreads();
-
-    // ---- step by step on what is left
+    // A cached step that stops fitting is not searched anew at once: it is
+    // kept, negated, as an upper bound of whatever the job can still do (the
+    // job's state is unchanged and the capacity only shrank).  A step is
+    // taken when the best exact entry beats every such bound under the tie
+    // rule (lower job index first); bounds that could win are made exact
+    // first, all of them in one go.
+    auto key_of = [](float v, uint32_t jl) -> unsigned long long {
+        return ((unsigned long long)__float_as_uint(v) << 32) | (0xFFFFFFFFu - jl);
+    };
+    auto refresh = [&](uint32_t jl) {
+        const Step nx = best_step<PASS>(X, J0 + jl, gi[jl], PASS == 0 ? 0u : aux[jl], ci[jl], freeG, freeC);
+        slope[jl] = nx.slope;
+        tgt[jl] = (uint16_t)nx.tgt;
+        if (PASS == 0) aux[jl] = (uint16_t)nx.dg;
+    };
+    uint32_t steps = 0;
     for (;;) {
-        unsigned long long k = 0;
-        for (uint32_t jl = tid; jl < nj; jl += PASS_THREADS) {
-            const unsigned long long c = ((unsigned long long)__float_as_uint(slope[jl]) << 32) | (0xFFFFFFFFu - jl);
-            k = c > k ? c : k;
+        if (PASS == 0 ? freeG == 0 : freeC == 0) break;         // nothing can fit any more
+        unsigned long long kf = 0, ks = 0;
+        for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {
+            const float v = slope[jl];
+            if (v > 0.f) { const unsigned long long c = key_of(v, jl); kf = c > kf ? c : kf; }
+            else if (v < 0.f) { const unsigned long long c = key_of(-v, jl); ks = c > ks ? c : ks; }
         }
-        k = block_max_u64(k, sel.red);
-        if (!(k >> 32)) break;                                  // no positive slope left
-        const uint32_t jw = 0xFFFFFFFFu - (uint32_t)k;
+        kf = block_max_u64(kf, red);
+        ks = block_max_u64(ks, red);
+        if (ks > kf) {                                          // a bound could still win: make those exact
+            for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {
+                const float v = slope[jl];
+                if (v < 0.f && key_of(-v, jl) > kf) refresh(jl);
+            }
+            __syncthreads();
+            continue;
+        }
+        if (!(kf >> 32)) break;                                 // no positive slope left
+        ++steps;
+        const uint32_t jw = 0xFFFFFFFFu - (uint32_t)kf;
         if (PASS == 0) freeG -= aux[jw];
         freeC -= step_cpus(jw);
         __syncthreads();                                        // everyone has read the winner's state
-        if (tid == (jw % PASS_THREADS)) { if (PASS == 0) gi[jw] = (int16_t)tgt[jw]; else ci[jw] = tgt[jw]; }
-        // cached steps that no longer fit, and the winner's next step, are recomputed
-        for (uint32_t jl = tid; jl < nj; jl += PASS_THREADS) {
-            bool redo = jl == jw;
-            if (!redo && slope[jl] > 0.f) redo = (PASS == 0 && aux[jl] > freeG) || step_cpus(jl) > freeC;
-            if (redo) best_step(jl);
+        if (tid == (jw % TAIL_THREADS)) {
+            if (PASS == 0) gi[jw] = (int16_t)tgt[jw]; else ci[jw] = tgt[jw];
+            refresh(jw);
+        }
+        for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {
+            if (jl == jw) continue;
+            const float v = slope[jl];
+            if (v > 0.f && ((PASS == 0 && aux[jl] > freeG) || step_cpus(jl) > freeC)) slope[jl] = -v;
         }
         __syncthreads();
     }
-
-    for (uint32_t jl = tid; jl < nj; jl += PASS_THREADS) {
-        if (PASS == 0) {
-            const int32_t s_i = gi[jl];
-            st.gi[jrel0 + jl] = s_i;
-            st.g[jrel0 + jl] = s_i < 0 ? 0u : tb.seg_g[tb.seg_off[J0 + jl] + s_i];
-        } else {
-            st.ci[jrel0 + jl] = ci[jl];
+    if (steps) {                                                // something changed since k_apply
+        for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {
+            if (PASS == 0) {
+                const int32_t s_i = gi[jl];
+                st.gi[jrel0 + jl] = s_i;
+                st.g[jrel0 + jl] = s_i < 0 ? 0u : X.tb.seg_g[X.tb.seg_off[J0 + jl] + s_i];
+            } else {
+                st.ci[jrel0 + jl] = ci[jl];
+            }
         }
     }
-    if (PASS == 0 && tid == 0) st.free_c[rnd] = freeC;
+    if (PASS == 0 && tid == 0) st.free_c[rnd] = freeC;          // what the CPU pass starts from
 }
 
 // ------------------------------------------------------------------ memory
@@ -407,31 +549,28 @@ __global__ __launch_bounds__(PASS_THREADS) void k_pass(const float *__restrict__
 // finds its wish still free when its turn comes: the float32 running remainder
 // of the in-order rule drifts by far less), and redoes the round in job order
 // otherwise.
-__global__ __launch_bounds__(WISH_THREADS) void k_mem_wish(const float *__restrict__ ref_thr, TableDev tb,
-                                                           GridDev grid, RoundArgs R, uint32_t jb,
-                                                           const float *__restrict__ best_thr,
-                                                           const uint32_t *__restrict__ best_plan, JobState st,
-                                                           rk_assign *__restrict__ assign) {
-    __shared__ double red[2][WISH_THREADS / 64];
+__global__ __launch_bounds__(JOB_THREADS) void k_mem_wish(Ctx X, JobState st, rk_assign *__restrict__ assign) {
+    __shared__ double red[2][JOB_THREADS / 64];
     const uint32_t rnd = blockIdx.y, tid = threadIdx.x;
     uint32_t J0, J1;
     rk_cluster cl;
-    round_of(R, rnd, J0, J1, cl);
-    const uint32_t jl = blockIdx.x * WISH_THREADS + tid;
+    round_of(X.R, rnd, J0, J1, cl);
+    const GridDev &grid = X.grid;
+    const uint32_t jl = blockIdx.x * JOB_THREADS + tid;
     const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem;
     double cost_d = 0.0, val_d = 0.0;
     if (J0 + jl < J1) {
-        const uint32_t j = J0 + jl, jrel = j - jb;
+        const uint32_t j = J0 + jl, jrel = j - X.jb;
         rk_assign out = {0u, 0u, 0.f, RK_NO_PLAN, 0.f};
         const int32_t gi = st.gi[jrel];
         if (gi >= 0) {
             const uint32_t g = st.g[jrel], c_lvl = st.ci[jrel];
-            const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
-            const uint64_t base = (uint64_t)n_rows * (s0 - tb.seg_off[jb]) + (uint64_t)(c_lvl * n_mem) * ns + gi;
+            const uint32_t s0 = X.tb.seg_off[j], ns = X.tb.seg_off[j + 1] - s0;
+            const uint64_t base = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]) + (uint64_t)(c_lvl * n_mem) * ns + gi;
             float bv = 0.f;
             uint32_t bm = 0;
             for (uint32_t m = 0; m < n_mem; ++m) {
-                const float v = best_thr[base + (uint64_t)m * ns];
+                const float v = X.best_thr[base + (uint64_t)m * ns];
                 if (v > bv) { bv = v; bm = m; }
             }
             if (bv > 0.f) {
@@ -440,10 +579,10 @@ __global__ __launch_bounds__(WISH_THREADS) void k_mem_wish(const float *__restri
                 out.g = g;
                 out.c = (uint32_t)cpu_cost(grid, c_lvl, g);
                 out.mem_gb = cost;
-                out.plan = best_plan[base + (uint64_t)bm * ns];
+                out.plan = X.best_plan[base + (uint64_t)bm * ns];
                 out.thr = bv;
                 cost_d = (double)cost;
-                val_d = (double)bv / (double)ref_thr[j];
+                val_d = (double)bv / (double)X.ref_thr[j];
             }
         }
         assign[jrel] = out;
@@ -454,24 +593,23 @@ __global__ __launch_bounds__(WISH_THREADS) void k_mem_wish(const float *__restri
     __syncthreads();
     if (tid == 0) {
         double a = 0.0, b = 0.0;
-        for (int w = 0; w < WISH_THREADS / 64; ++w) { a += red[0][w]; b += red[1][w]; }
+        for (int w = 0; w < JOB_THREADS / 64; ++w) { a += red[0][w]; b += red[1][w]; }
         st.partial[((size_t)rnd * st.blocks_per_round + blockIdx.x) * 2 + 0] = a;
         st.partial[((size_t)rnd * st.blocks_per_round + blockIdx.x) * 2 + 1] = b;
     }
 }
 
 // One wavefront per round.
-__global__ __launch_bounds__(64) void k_mem_finish(const float *__restrict__ ref_thr, TableDev tb, GridDev grid,
-                                                   RoundArgs R, uint32_t jb, const float *__restrict__ best_thr,
-                                                   const uint32_t *__restrict__ best_plan, JobState st,
-                                                   rk_assign *__restrict__ assign, float *__restrict__ totals) {
+__global__ __launch_bounds__(64) void k_mem_finish(Ctx X, JobState st, rk_assign *__restrict__ assign,
+                                                   float *__restrict__ totals) {
     const uint32_t rnd = blockIdx.x, tid = threadIdx.x;
     uint32_t J0, J1;
     rk_cluster cl;
-    round_of(R, rnd, J0, J1, cl);
-    const uint32_t nj = J1 - J0, jrel0 = J0 - jb;
+    round_of(X.R, rnd, J0, J1, cl);
+    const GridDev &grid = X.grid;
+    const uint32_t nj = J1 - J0, jrel0 = J0 - X.jb;
     const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem;
-    const uint32_t used_blocks = (nj + WISH_THREADS - 1) / WISH_THREADS;
+    const uint32_t used_blocks = (nj + JOB_THREADS - 1) / JOB_THREADS;
     double wish = 0.0, val = 0.0;
     for (uint32_t b = tid; b < used_blocks; b += 64) {
         wish += st.partial[((size_t)rnd * st.blocks_per_round + b) * 2 + 0];
@@ -499,15 +637,15 @@ __global__ __launch_bounds__(64) void k_mem_finish(const float *__restrict__ ref
         if (have) {
             const uint32_t j = J0 + jl;
             g = st.g[jrel0 + jl]; c_lvl = st.ci[jrel0 + jl];
-            const uint32_t s0 = tb.seg_off[j];
-            ns = tb.seg_off[j + 1] - s0;
-            at0 = (uint64_t)n_rows * (s0 - tb.seg_off[jb]) + (uint64_t)(c_lvl * n_mem) * ns + (uint32_t)st.gi[jrel0 + jl];
+            const uint32_t s0 = X.tb.seg_off[j];
+            ns = X.tb.seg_off[j + 1] - s0;
+            at0 = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]) + (uint64_t)(c_lvl * n_mem) * ns + (uint32_t)st.gi[jrel0 + jl];
             float bv = 0.f;
             uint32_t bm = 0;
 #pragma unroll
             for (uint32_t m = 0; m < RK_MAX_MEM_LEVELS; ++m) {
                 if (m < n_mem) {
-                    const float v = best_thr[at0 + (uint64_t)m * ns];
+                    const float v = X.best_thr[at0 + (uint64_t)m * ns];
                     thr_m[m] = v;
                     if (v > bv) { bv = v; bm = m; }
                     choice |= (unsigned long long)bm << (4 * m);
@@ -536,9 +674,9 @@ __global__ __launch_bounds__(64) void k_mem_finish(const float *__restrict__ ref
                     out.g = g;
                     out.c = (uint32_t)cpu_cost(grid, c_lvl, g);
                     out.mem_gb = cost;
-                    out.plan = best_plan[at0 + (uint64_t)bm * ns];
+                    out.plan = X.best_plan[at0 + (uint64_t)bm * ns];
                     out.thr = v;
-                    sum += (double)v / (double)ref_thr[J0 + jl];
+                    sum += (double)v / (double)X.ref_thr[J0 + jl];
                 }
             }
             spent = __shfl(spent, (int)turn, 64);
@@ -550,9 +688,35 @@ __global__ __launch_bounds__(64) void k_mem_finish(const float *__restrict__ ref
     if (tid == 0) totals[rnd] = (float)sum;
 }
 
+__global__ void k_zero_u32(uint32_t *p, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
 template <typename T>
 int32_t scratch_typed(rk_ctx *ctx, int slot, size_t count, T **out) {
     return rk_scratch(ctx, slot, count * sizeof(T), reinterpret_cast<void **>(out));
+}
+
+template <int PASS>
+int32_t launch_pass(rk_ctx *ctx, const Ctx &X, const JobState &st, const HullBuf &H, const Hist &hist,
+                    uint32_t n_rounds, uint32_t n_jobs, uint32_t mj, size_t tail_lds) {
+    hipStream_t s = ctx->stream;
+    const uint32_t hull_blocks = (n_jobs + (HULL_THREADS / 64) - 1) / (HULL_THREADS / 64);
+    const dim3 job_grid(st.blocks_per_round, n_rounds);
+    if (n_jobs > 0) {
+        k_hull<PASS><<<hull_blocks, HULL_THREADS, 0, s>>>(X, st, H);
+        RK_CHECK_LAUNCH(ctx, "k_hull");
+        k_hist<PASS, 0><<<job_grid, JOB_THREADS, 0, s>>>(X, st, H, hist);
+        RK_CHECK_LAUNCH(ctx, "k_hist<0>");
+        k_hist<PASS, 1><<<job_grid, JOB_THREADS, 0, s>>>(X, st, H, hist);
+        RK_CHECK_LAUNCH(ctx, "k_hist<1>");
+    }
+    k_apply<PASS><<<job_grid, JOB_THREADS, 0, s>>>(X, st, H, hist);
+    RK_CHECK_LAUNCH(ctx, "k_apply");
+    k_tail<PASS><<<n_rounds, TAIL_THREADS, tail_lds, s>>>(X, mj, st);
+    RK_CHECK_LAUNCH(ctx, "k_tail");
+    return RK_OK;
 }
 
 }  // namespace
@@ -578,51 +742,54 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
     if ((rc = scratch_typed(ctx, SL_HULL_DG, entries, &H.dg))) return rc;
     if ((rc = scratch_typed(ctx, SL_HULL_DC, entries, &H.dc))) return rc;
     JobState st;
-    st.blocks_per_round = (max_jobs + WISH_THREADS - 1) / WISH_THREADS;
+    st.blocks_per_round = (max_jobs + JOB_THREADS - 1) / JOB_THREADS;
     if (st.blocks_per_round == 0) st.blocks_per_round = 1;
     if ((rc = scratch_typed(ctx, SL_ST_GI, (size_t)H.stride, &st.gi))) return rc;
     if ((rc = scratch_typed(ctx, SL_ST_G, (size_t)H.stride, &st.g))) return rc;
     if ((rc = scratch_typed(ctx, SL_ST_CI, (size_t)H.stride, &st.ci))) return rc;
+    if ((rc = scratch_typed(ctx, SL_ST_STEP_SLOPE, (size_t)H.stride, &st.step_slope))) return rc;
+    if ((rc = scratch_typed(ctx, SL_ST_STEP_TGT, (size_t)H.stride, &st.step_tgt))) return rc;
+    if ((rc = scratch_typed(ctx, SL_ST_STEP_DG, (size_t)H.stride, &st.step_dg))) return rc;
+    if ((rc = scratch_typed(ctx, SL_ST_FREEG, (size_t)n_rounds * 2, &st.free_g))) return rc;   // [free G | free C] after apply
     if ((rc = scratch_typed(ctx, SL_ST_FREEC, (size_t)n_rounds, &st.free_c))) return rc;
     if ((rc = scratch_typed(ctx, SL_ST_PARTIAL, (size_t)n_rounds * st.blocks_per_round * 2, &st.partial))) return rc;
+    Hist hist;
+    const size_t hist_bins = (size_t)n_rounds * 4 * BINS;
+    if ((rc = scratch_typed(ctx, SL_HIST_G, hist_bins, &hist.g))) return rc;
+    if ((rc = scratch_typed(ctx, SL_HIST_C, hist_bins, &hist.c))) return rc;
 
-    const GridDev gd = grid_dev(grid);
-    RoundArgs R;
-    R.round_off = d_round_off; R.clusters = d_clusters; R.n_rounds = n_rounds;
-    R.inline_one = one_cluster ? 1u : 0u;
-    R.off0 = jb; R.off1 = jb + n_jobs;
-    R.cl = one_cluster ? *one_cluster : rk_cluster{0u, 0u, 0.f};
+    Ctx X;
+    X.ref_thr = ref_thr; X.tb = tb; X.grid = grid_dev(grid); X.jb = jb;
+    X.best_thr = best_thr; X.best_plan = best_plan; X.curve_thr = curve_thr;
+    X.R.round_off = d_round_off; X.R.clusters = d_clusters; X.R.n_rounds = n_rounds;
+    X.R.inline_one = one_cluster ? 1u : 0u;
+    X.R.off0 = jb; X.R.off1 = jb + n_jobs;
+    X.R.cl = one_cluster ? *one_cluster : rk_cluster{0u, 0u, 0.f};
 
     const uint32_t mj = max_jobs ? ((max_jobs + 1u) & ~1u) : 2u;
     const size_t lds = (size_t)mj * (4 + 2 + 2 + 2 + 2);
     static bool raised[64] = {};
     if (lds > 48 * 1024 && !raised[ctx->device & 63]) {
-        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_pass<0>),
+        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_tail<0>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
-        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_pass<1>),
+        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_tail<1>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
         raised[ctx->device & 63] = true;
     }
-    const uint32_t hull_blocks = (n_jobs + (HULL_THREADS / 64) - 1) / (HULL_THREADS / 64);
     hipStream_t s = ctx->stream;
-    if (n_jobs > 0) {
-        k_hull<0><<<hull_blocks, HULL_THREADS, 0, s>>>(ref_thr, tb, gd, R, jb, curve_thr, st, H);
-        RK_CHECK_LAUNCH(ctx, "k_hull<gpu>");
+    {   // histograms start at zero (fill kernels, so the sequence can be captured in a graph)
+        const size_t n32 = hist_bins, n64 = hist_bins * 2;
+        k_zero_u32<<<(unsigned)((n32 + 255) / 256), 256, 0, s>>>(hist.g, n32);
+        k_zero_u32<<<(unsigned)((n64 + 255) / 256), 256, 0, s>>>(reinterpret_cast<uint32_t *>(hist.c), n64);
+        RK_CHECK_LAUNCH(ctx, "k_zero_u32");
     }
-    k_pass<0><<<n_rounds, PASS_THREADS, lds, s>>>(ref_thr, tb, gd, R, jb, mj, curve_thr, H, st);
-    RK_CHECK_LAUNCH(ctx, "k_pass<gpu>");
-    if (n_jobs > 0) {
-        k_hull<1><<<hull_blocks, HULL_THREADS, 0, s>>>(ref_thr, tb, gd, R, jb, best_thr, st, H);
-        RK_CHECK_LAUNCH(ctx, "k_hull<cpu>");
-    }
-    k_pass<1><<<n_rounds, PASS_THREADS, lds, s>>>(ref_thr, tb, gd, R, jb, mj, best_thr, H, st);
-    RK_CHECK_LAUNCH(ctx, "k_pass<cpu>");
+    if ((rc = launch_pass<0>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, lds))) return rc;
+    if ((rc = launch_pass<1>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, lds))) return rc;
     if (max_jobs > 0) {
-        k_mem_wish<<<dim3(st.blocks_per_round, n_rounds), WISH_THREADS, 0, s>>>(ref_thr, tb, gd, R, jb, best_thr,
-                                                                                best_plan, st, assign);
+        k_mem_wish<<<dim3(st.blocks_per_round, n_rounds), JOB_THREADS, 0, s>>>(X, st, assign);
         RK_CHECK_LAUNCH(ctx, "k_mem_wish");
     }
-    k_mem_finish<<<n_rounds, 64, 0, s>>>(ref_thr, tb, gd, R, jb, best_thr, best_plan, st, assign, totals);
+    k_mem_finish<<<n_rounds, 64, 0, s>>>(X, st, assign, totals);
     RK_CHECK_LAUNCH(ctx, "k_mem_finish");
     return RK_OK;
 }

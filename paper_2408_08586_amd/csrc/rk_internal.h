@@ -27,7 +27,9 @@ enum {
     SL_BEST_THR, SL_BEST_PLAN, SL_CURVE_THR, SL_CURVE_PLAN, SL_CURVE_G,  // round intermediates
     SL_ROUND_META,                                // per-round job ranges and clusters
     SL_HULL_KEY, SL_HULL_RAW, SL_HULL_DG, SL_HULL_DC, SL_HULL_TGT,   // walk steps of the greedy allocation
-    SL_ST_GI, SL_ST_G, SL_ST_CI, SL_ST_FREEC, SL_ST_PARTIAL          // its per-job and per-round state
+    SL_ST_GI, SL_ST_G, SL_ST_CI, SL_ST_FREEC, SL_ST_PARTIAL,         // its per-job and per-round state
+    SL_ST_STEP_SLOPE, SL_ST_STEP_TGT, SL_ST_STEP_DG, SL_ST_FREEG,
+    SL_HIST_G, SL_HIST_C                                              // cost histograms over the step keys
 };
 
 int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);
