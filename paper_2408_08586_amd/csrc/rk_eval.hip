@@ -89,11 +89,15 @@ __global__ __launch_bounds__(EVAL_THREADS) void k_eval(JobDev jobs, TableDev tb,
 }
 
 // ---------------------------------------------------------- best plan per segment
-// One wavefront per (job, row).  Lanes read the row as float4 (four options of
-// one triple), four lanes reduce a triple, the per-triple maxima go to LDS and
-// lanes then reduce the job's segments.  Comparison on the packed key
-// (throughput bits, inverted plan index): larger throughput, then lower index.
-constexpr int BEST_WAVES = 4;
+// A workgroup of `wpb` wavefronts takes wpb rows of one job, one wavefront per
+// row.  The triple -> segment map of the job is built once per workgroup in
+// LDS.  Lanes stream the row as 16-byte streaming loads (four options of one
+// triple), the next chunk being requested before the current one is reduced;
+// four lanes reduce a triple with DPP and the quad leader pushes the triple's
+// packed key (throughput bits, inverted plan index: larger throughput, then
+// lower index) into the wavefront's per-segment keys with an LDS atomic max.
+constexpr int BEST_MAX_WAVES = 16;
+constexpr int BEST_UNROLL = 4;
 
 __device__ __forceinline__ unsigned long long max_u64(unsigned long long a, unsigned long long b) {
     return a > b ? a : b;
@@ -107,58 +111,63 @@ __device__ __forceinline__ unsigned long long dpp_u64(unsigned long long v) {
     return ((unsigned long long)h2 << 32) | l2;
 }
 
-__global__ __launch_bounds__(BEST_WAVES * 64) void k_best_plan(TableDev tb, uint32_t n_rows, uint32_t jb,
-                                                               uint32_t je, uint32_t lds_per_wave,
-                                                               const float *__restrict__ thr,
-                                                               float *__restrict__ best_thr,
-                                                               uint32_t *__restrict__ best_plan) {
-    extern __shared__ unsigned long long lds_keys[];
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
-    const uint64_t row_id = (uint64_t)blockIdx.x * BEST_WAVES + wave;
-    const uint64_t total_rows = (uint64_t)(je - jb) * n_rows;
-    unsigned long long *keys = lds_keys + (size_t)wave * lds_per_wave;
-
-    const bool active = row_id < total_rows;
-    uint32_t j = 0, r = 0, nt = 0, ns = 0, t0 = 0, s0 = 0;
-    if (active) {
-        j = jb + (uint32_t)(row_id / n_rows);
-        r = (uint32_t)(row_id % n_rows);
-        t0 = tb.triple_off[j]; nt = tb.triple_off[j + 1] - t0;
-        s0 = tb.seg_off[j]; ns = tb.seg_off[j + 1] - s0;
-        const uint64_t cbase = 16ull * n_rows * (uint64_t)(t0 - tb.triple_off[jb]) + (uint64_t)r * nt * 16;
-        const v4f *row = reinterpret_cast<const v4f *>(thr + cbase);
-        const uint32_t n_vec = nt * 4;                      // float4 elements in the row
-        // four independent 1 KiB loads per wavefront are issued before any is used
-        for (uint32_t base = 0; base < n_vec; base += 4 * 64) {
-            v4f v[4];
-#pragma unroll
-            for (uint32_t u = 0; u < 4; ++u) {
-                const uint32_t i = base + u * 64 + lane;
-                v[u] = i < n_vec ? __builtin_nontemporal_load(row + i) : (v4f)(0.f);
-            }
-#pragma unroll
-            for (uint32_t u = 0; u < 4; ++u) {
-                const uint32_t i = base + u * 64 + lane;
-                const uint32_t plan0 = i * 4;
-                unsigned long long k = make_key(v[u].x, plan0);
-                k = max_u64(k, make_key(v[u].y, plan0 + 1));
-                k = max_u64(k, make_key(v[u].z, plan0 + 2));
-                k = max_u64(k, make_key(v[u].w, plan0 + 3));
-                if (i >= n_vec) k = 0;
-                k = max_u64(k, dpp_u64<0xB1>(k));           // quad_perm [1,0,3,2]
-                k = max_u64(k, dpp_u64<0x4E>(k));           // quad_perm [2,3,0,1]
-                if ((lane & 3u) == 0 && i < n_vec) keys[i >> 2] = k;
-            }
-        }
-    }
-    __syncthreads();
-    if (!active) return;
-    const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]) + (uint64_t)r * ns;
-    for (uint32_t s = lane; s < ns; s += 64) {
+__global__ __launch_bounds__(BEST_MAX_WAVES * 64) void k_best_plan(TableDev tb, uint32_t n_rows, uint32_t jb,
+                                                                   uint32_t wpb, uint32_t grp_per_job, uint32_t max_nt,
+                                                                   uint32_t max_ns,
+                                                                   const float *__restrict__ thr,
+                                                                   float *__restrict__ best_thr,
+                                                                   uint32_t *__restrict__ best_plan) {
+    extern __shared__ unsigned long long lds64[];
+    unsigned long long *seg_key = lds64;                                          // [wpb][max_ns]
+    uint16_t *seg_of = reinterpret_cast<uint16_t *>(seg_key + (size_t)wpb * max_ns);   // [max_nt]
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u, tid = threadIdx.x, nthr = wpb * 64;
+    const uint32_t j = jb + blockIdx.x / grp_per_job;
+    const uint32_t r = (blockIdx.x % grp_per_job) * wpb + wave;
+    const uint32_t t0 = tb.triple_off[j], nt = tb.triple_off[j + 1] - t0;
+    const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
+    for (uint32_t s = tid; s < ns; s += nthr) {
         const uint32_t first = tb.seg_first[s0 + s];
         const uint32_t last = s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt;
-        unsigned long long k = 0;
-        for (uint32_t t = first; t < last; ++t) k = max_u64(k, keys[t]);
+        for (uint32_t t = first; t < last; ++t) seg_of[t] = (uint16_t)s;
+    }
+    for (uint32_t i = tid; i < wpb * max_ns; i += nthr) seg_key[i] = 0ull;
+    __syncthreads();
+    if (r >= n_rows || nt == 0) return;
+    unsigned long long *my = seg_key + (size_t)wave * max_ns;
+    const v4f *row = reinterpret_cast<const v4f *>(thr + 16ull * n_rows * (uint64_t)(t0 - tb.triple_off[jb]) +
+                                                   (uint64_t)r * nt * 16);
+    const uint32_t n_vec = nt * 4, last_vec = n_vec - 1;      // 16-byte elements of the row
+    // loads past the end are clamped to the last element (and ignored), which keeps them branch-free
+    v4f cur[BEST_UNROLL], nxt[BEST_UNROLL];
+#pragma unroll
+    for (uint32_t u = 0; u < BEST_UNROLL; ++u) {
+        const uint32_t i = u * 64 + lane;
+        cur[u] = __builtin_nontemporal_load(row + (i < n_vec ? i : last_vec));
+    }
+    for (uint32_t base = 0; base < n_vec; base += BEST_UNROLL * 64) {
+#pragma unroll
+        for (uint32_t u = 0; u < BEST_UNROLL; ++u) {
+            const uint32_t i = base + (BEST_UNROLL + u) * 64 + lane;
+            nxt[u] = __builtin_nontemporal_load(row + (i < n_vec ? i : last_vec));
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < BEST_UNROLL; ++u) {
+            const uint32_t i = base + u * 64 + lane;
+            const uint32_t plan0 = i * 4;
+            unsigned long long k = make_key(cur[u].x, plan0);
+            k = max_u64(k, make_key(cur[u].y, plan0 + 1));
+            k = max_u64(k, make_key(cur[u].z, plan0 + 2));
+            k = max_u64(k, make_key(cur[u].w, plan0 + 3));
+            k = max_u64(k, dpp_u64<0xB1>(k));               // quad_perm [1,0,3,2]
+            k = max_u64(k, dpp_u64<0x4E>(k));               // quad_perm [2,3,0,1]
+            if ((lane & 3u) == 0 && i < n_vec && (k >> 32)) atomicMax(&my[seg_of[i >> 2]], k);
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < BEST_UNROLL; ++u) cur[u] = nxt[u];
+    }
+    const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]) + (uint64_t)r * ns;
+    for (uint32_t s = lane; s < ns; s += 64) {
+        const unsigned long long k = my[s];
         best_thr[sbase + s] = key_thr(k);
         best_plan[sbase + s] = key_plan(k);
     }
@@ -277,13 +286,19 @@ int32_t rk_best_plan(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_gri
     if (cap_segs < need) return rk_fail(ctx, RK_ERR_CAPACITY, "outputs hold %llu entries, %llu needed",
                                         (unsigned long long)cap_segs, (unsigned long long)need);
     if ((uintptr_t)thr & 15u) return rk_fail(ctx, RK_ERR_INVALID_ARG, "thr not 16-byte aligned");
-    const uint64_t rows = (uint64_t)(je - jb) * n_rows;
-    const uint64_t blocks = (rows + BEST_WAVES - 1) / BEST_WAVES;
+    // wavefronts (rows) per workgroup: split the job's rows evenly over as few workgroups as possible
+    const uint32_t max_nt = table->max_triples_per_job ? table->max_triples_per_job : 1;
+    const uint32_t max_ns = table->max_segs_per_job ? table->max_segs_per_job : 1;
+    uint32_t cap_waves = (uint32_t)((56 * 1024 - ((size_t)max_nt * 2 + 8)) / ((size_t)max_ns * 8));
+    if (cap_waves < 1) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "too many segments per job for the best-plan kernel");
+    if (cap_waves > BEST_MAX_WAVES) cap_waves = BEST_MAX_WAVES;
+    const uint32_t groups = (uint32_t)((n_rows + cap_waves - 1) / cap_waves);
+    const uint32_t wpb = (uint32_t)((n_rows + groups - 1) / groups);
+    const uint64_t blocks = (uint64_t)(je - jb) * groups;
     if (blocks > 0x7FFFFFFFull) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "too many rows in one call; use job ranges");
-    const uint32_t per_wave = table->max_triples_per_job;
-    const size_t lds = (size_t)BEST_WAVES * per_wave * sizeof(unsigned long long);
-    k_best_plan<<<(uint32_t)blocks, BEST_WAVES * 64, lds, ctx->stream>>>(table_dev(table), (uint32_t)n_rows, jb, je,
-                                                                        per_wave, thr, best_thr, best_plan);
+    const size_t lds = (size_t)wpb * max_ns * 8 + (((size_t)max_nt * 2 + 7) & ~(size_t)7);
+    k_best_plan<<<(uint32_t)blocks, wpb * 64, lds, ctx->stream>>>(table_dev(table), (uint32_t)n_rows, jb, wpb, groups,
+                                                                 max_nt, max_ns, thr, best_thr, best_plan);
     RK_CHECK_LAUNCH(ctx, "k_best_plan");
     return RK_OK;
 }
