@@ -117,6 +117,7 @@ int32_t rk_destroy(rk_ctx *ctx) {
     for (int i = 0; i < RK_SCRATCH_SLOTS; ++i)
         if (ctx->scratch[i]) (void)hipFree(ctx->scratch[i]);
     if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
+    if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
     free(ctx);
     return RK_OK;
 }

@@ -4,8 +4,12 @@
 // One workgroup per job.  Instead of testing every g it builds the divisor
 // lists of b/mu (data-parallel sizes) and of the layer count (pipeline sizes),
 // forms the products d*t*p <= g_max with t in {1,2,4,8}, and orders them by
-// the key (g, t, p) with a rank sort in LDS.  Runs twice: once to count, once
-// to fill after the exclusive scan of the counts.
+// the key (g, t, p) with a rank sort in LDS.  The counting pass also parks the
+// sorted keys in a scratch buffer; after the exclusive scan of the counts the
+// fill pass only decodes them into place (it repeats the search only when the
+// scratch buffer was too small).
+#include <cstring>
+
 #include "rk_internal.h"
 
 namespace {
@@ -14,8 +18,9 @@ constexpr int ENUM_THREADS = 256;
 constexpr uint32_t MAX_T = RK_MAX_TRIPLES_PER_JOB;
 constexpr uint32_t MAX_DIV = 1024;
 
-enum { TOT_NT_LO = 0, TOT_NT_HI, TOT_NS_LO, TOT_NS_HI, TOT_MAX_T, TOT_MAX_S, TOT_ERR, TOT_WORDS };
-enum { ERR_TOO_MANY_TRIPLES = 1, ERR_TOO_MANY_DIVISORS = 2 };
+enum { TOT_NT_LO = 0, TOT_NT_HI, TOT_NS_LO, TOT_NS_HI, TOT_MAX_T, TOT_MAX_S, TOT_ERR, TOT_CURSOR, TOT_WORDS };
+enum { ERR_TOO_MANY_TRIPLES = 1, ERR_TOO_MANY_DIVISORS = 2, ERR_PARK_FULL = 4 };
+enum { MODE_COUNT = 0, MODE_FILL_SEARCH = 1, MODE_FILL_PARKED = 2 };
 
 // exclusive prefix sum of one value per thread over the workgroup
 __device__ uint32_t block_excl_scan(uint32_t v, uint32_t *lds, uint32_t *total) {
@@ -34,11 +39,12 @@ __device__ uint32_t block_excl_scan(uint32_t v, uint32_t *lds, uint32_t *total) 
     return incl - v;
 }
 
-template <bool FILL>
+template <int MODE>
 __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     const uint32_t *__restrict__ layers, const uint32_t *__restrict__ gbatch,
     const uint32_t *__restrict__ mbatch, rk_plan_bounds bounds,
     uint32_t *__restrict__ cnt_t, uint32_t *__restrict__ cnt_s,
+    uint32_t *__restrict__ park, uint32_t park_stride,
     const uint32_t *__restrict__ triple_off, const uint32_t *__restrict__ seg_off,
     uint32_t *__restrict__ triples, uint32_t *__restrict__ seg_g, uint32_t *__restrict__ seg_first,
     uint32_t *__restrict__ totals) {
@@ -48,52 +54,60 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     __shared__ uint32_t nd, np, nk;
 
     const uint32_t j = blockIdx.x, tid = threadIdx.x;
-    const uint32_t l = layers[j], b = gbatch[j], mu = mbatch[j];
-    if (tid == 0) { nd = 0; np = 0; nk = 0; }
-    __syncthreads();
+    uint32_t cnt, err = 0;
+    if (MODE == MODE_FILL_PARKED) {
+        cnt = cnt_t[j];
+        const size_t at = (size_t)j * park_stride;
+        for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) sorted[i] = park[at + i];
+        __syncthreads();
+    } else {
+        const uint32_t l = layers[j], b = gbatch[j], mu = mbatch[j];
+        if (tid == 0) { nd = 0; np = 0; nk = 0; }
+        __syncthreads();
 
-    const bool any = l > 0 && b > 0 && mu > 0 && (b % mu) == 0;
-    const uint32_t n = any ? b / mu : 0;
-    // divisors of n (data-parallel sizes) and of l (pipeline sizes), unordered
-    const uint32_t dmax = n < bounds.g_max ? n : bounds.g_max;
-    for (uint32_t d = tid + 1; d <= dmax; d += ENUM_THREADS)
-        if (n % d == 0) { uint32_t i = atomicAdd(&nd, 1u); if (i < MAX_DIV) dlist[i] = d; }
-    uint32_t pmax = l < bounds.pp_max ? l : bounds.pp_max;
-    pmax = pmax < bounds.g_max ? pmax : bounds.g_max;
-    if (!any) pmax = 0;
-    for (uint32_t p = tid + 1; p <= pmax; p += ENUM_THREADS)
-        if (l % p == 0) { uint32_t i = atomicAdd(&np, 1u); if (i < MAX_DIV) plist[i] = p; }
-    __syncthreads();
-    uint32_t err = 0;
-    if (nd > MAX_DIV || np > MAX_DIV) err |= ERR_TOO_MANY_DIVISORS;
-    const uint32_t cd = nd < MAX_DIV ? nd : MAX_DIV, cp = np < MAX_DIV ? np : MAX_DIV;
+        const bool any = l > 0 && b > 0 && mu > 0 && (b % mu) == 0;
+        const uint32_t n = any ? b / mu : 0;
+        // divisors of n (data-parallel sizes) and of l (pipeline sizes), unordered
+        const uint32_t dmax = n < bounds.g_max ? n : bounds.g_max;
+        for (uint32_t d = tid + 1; d <= dmax; d += ENUM_THREADS)
+            if (n % d == 0) { uint32_t i = atomicAdd(&nd, 1u); if (i < MAX_DIV) dlist[i] = d; }
+        uint32_t pmax = l < bounds.pp_max ? l : bounds.pp_max;
+        pmax = pmax < bounds.g_max ? pmax : bounds.g_max;
+        if (!any) pmax = 0;
+        for (uint32_t p = tid + 1; p <= pmax; p += ENUM_THREADS)
+            if (l % p == 0) { uint32_t i = atomicAdd(&np, 1u); if (i < MAX_DIV) plist[i] = p; }
+        __syncthreads();
+        if (nd > MAX_DIV || np > MAX_DIV) err |= ERR_TOO_MANY_DIVISORS;
+        const uint32_t cd = nd < MAX_DIV ? nd : MAX_DIV, cp = np < MAX_DIV ? np : MAX_DIV;
 
-    // products d * t * p <= g_max
-    uint32_t nlt = 0;                                   // tensor-parallel sizes allowed: 2^0..2^(nlt-1)
-    for (uint32_t t = 1; t <= 8 && t <= bounds.tp_max; t <<= 1) ++nlt;
-    const uint64_t combos = (uint64_t)cd * cp * nlt;
-    for (uint64_t c = tid; c < combos; c += ENUM_THREADS) {
-        const uint32_t lt = (uint32_t)(c % nlt);
-        const uint64_t r = c / nlt;
-        const uint32_t p = plist[r % cp], d = dlist[r / cp];
-        const uint64_t g = ((uint64_t)d * p) << lt;
-        if (g <= bounds.g_max) {
-            const uint32_t i = atomicAdd(&nk, 1u);
-            if (i < MAX_T) keys[i] = ((uint32_t)g << 16) | (lt << 14) | p;
+        // products d * 2^lt * p <= g_max (at most 1024 * 1024 * 4 combinations: 32-bit arithmetic)
+        uint32_t nlt = 0;                               // tensor-parallel sizes allowed: 2^0..2^(nlt-1)
+        for (uint32_t t = 1; t <= 8 && t <= bounds.tp_max; t <<= 1) ++nlt;
+        const uint32_t pairs = cd * cp;
+        for (uint32_t c = tid; c < pairs; c += ENUM_THREADS) {
+            const uint32_t p = plist[c % cp], d = dlist[c / cp];
+            const uint64_t dp = (uint64_t)d * p;
+            for (uint32_t lt = 0; lt < nlt; ++lt) {
+                const uint64_t g = dp << lt;
+                if (g <= bounds.g_max) {
+                    const uint32_t i = atomicAdd(&nk, 1u);
+                    if (i < MAX_T) keys[i] = ((uint32_t)g << 16) | (lt << 14) | p;
+                }
+            }
         }
-    }
-    __syncthreads();
-    if (nk > MAX_T) err |= ERR_TOO_MANY_TRIPLES;
-    const uint32_t cnt = nk < MAX_T ? nk : MAX_T;
+        __syncthreads();
+        if (nk > MAX_T) err |= ERR_TOO_MANY_TRIPLES;
+        cnt = nk < MAX_T ? nk : MAX_T;
 
-    // rank sort: keys are distinct, the rank is the number of smaller keys
-    for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) {
-        const uint32_t k = keys[i];
-        uint32_t rank = 0;
-        for (uint32_t x = 0; x < cnt; ++x) rank += keys[x] < k ? 1u : 0u;
-        sorted[rank] = k;
+        // rank sort: keys are distinct, the rank is the number of smaller keys
+        for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) {
+            const uint32_t k = keys[i];
+            uint32_t rank = 0;
+            for (uint32_t x = 0; x < cnt; ++x) rank += keys[x] < k ? 1u : 0u;
+            sorted[rank] = k;
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     // segments: runs of equal g.  Each thread owns a contiguous chunk.
     const uint32_t chunk = (cnt + ENUM_THREADS - 1) / ENUM_THREADS;
@@ -105,11 +119,17 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     uint32_t nseg;
     uint32_t sidx = block_excl_scan(starts, scan_tmp, &nseg);
 
-    if (!FILL) {
+    if (MODE == MODE_COUNT) {
         if (tid == 0) {
             cnt_t[j] = cnt;
             cnt_s[j] = nseg;
+            if (cnt > park_stride) err |= ERR_PARK_FULL;
             if (err) atomicOr(&totals[TOT_ERR], err);
+        }
+        // park the sorted keys in the job's slot for the fill pass, if they fit
+        if (cnt <= park_stride) {
+            const size_t at = (size_t)j * park_stride;
+            for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) park[at + i] = sorted[i];
         }
         return;
     }
@@ -202,25 +222,43 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
     table->n_triples = table->n_segs = 0;
     table->max_triples_per_job = table->max_segs_per_job = 0;
 
-    uint32_t *cnt_t, *cnt_s, *totals, *off_t, *off_s;
+    uint32_t *cnt_t, *cnt_s, *totals, *off_t, *off_s, *park;
     int32_t rc;
     if ((rc = rk_scratch(ctx, SL_CNT_T, (size_t)(2 * (size_t)J + 2) * 4, (void **)&cnt_t))) return rc;
     if ((rc = rk_scratch(ctx, SL_CNT_S, (size_t)(2 * (size_t)J + 2) * 4, (void **)&cnt_s))) return rc;
     if ((rc = rk_scratch(ctx, SL_TOTALS, TOT_WORDS * 4, (void **)&totals))) return rc;
-    off_t = cnt_t + J;           // [J+1] after the counts
-    off_s = cnt_s + J;
+    // one slot per job for the parked keys: as wide as the widest job seen so far, or a first guess
+    if (ctx->park_stride == 0) ctx->park_stride = 512;
+    const uint32_t park_stride = ctx->park_stride;
+    if ((rc = rk_scratch(ctx, SL_PARK, ((size_t)J * park_stride + 1) * 4, (void **)&park))) return rc;
+    const bool direct = table->triples && table->triple_off && table->seg_off;   // offsets go straight into the table
+    off_t = direct ? table->triple_off : cnt_t + J;
+    off_s = direct ? table->seg_off : cnt_s + J;
+    // pinned staging for what comes back: totals, then the two offset arrays
+    const size_t words_back = 16 + 2 * ((size_t)J + 1);
+    if (ctx->h_stage_words < words_back) {
+        if (ctx->h_stage) RK_HIP(ctx, hipHostFree(ctx->h_stage));
+        ctx->h_stage = nullptr; ctx->h_stage_words = 0;
+        RK_HIP(ctx, hipHostMalloc((void **)&ctx->h_stage, (words_back + words_back / 4) * 4, hipHostMallocDefault));
+        ctx->h_stage_words = words_back + words_back / 4;
+    }
+    uint32_t *h = ctx->h_stage;
 
     k_zero_words<<<1, 64, 0, ctx->stream>>>(totals, TOT_WORDS);
     if (J > 0) {
-        k_enumerate<false><<<J, ENUM_THREADS, 0, ctx->stream>>>(jobs->layers, jobs->gbatch, jobs->mbatch, *bounds,
-                                                                 cnt_t, cnt_s, nullptr, nullptr, nullptr, nullptr,
-                                                                 nullptr, totals);
+        k_enumerate<MODE_COUNT><<<J, ENUM_THREADS, 0, ctx->stream>>>(
+            jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
+            nullptr, nullptr, nullptr, nullptr, nullptr, totals);
         RK_CHECK_LAUNCH(ctx, "k_enumerate<count>");
     }
     k_scan_counts<<<1, 1024, 0, ctx->stream>>>(cnt_t, cnt_s, J, off_t, off_s, totals);
     RK_CHECK_LAUNCH(ctx, "k_scan_counts");
-    uint32_t *h = ctx->h_pinned;
+    const bool mirrors = table->triples && table->h_triple_off && table->h_seg_off;
     RK_HIP(ctx, hipMemcpyAsync(h, totals, TOT_WORDS * 4, hipMemcpyDeviceToHost, ctx->stream));
+    if (mirrors) {
+        RK_HIP(ctx, hipMemcpyAsync(h + 16, off_t, ((size_t)J + 1) * 4, hipMemcpyDeviceToHost, ctx->stream));
+        RK_HIP(ctx, hipMemcpyAsync(h + 16 + J + 1, off_s, ((size_t)J + 1) * 4, hipMemcpyDeviceToHost, ctx->stream));
+    }
     RK_HIP(ctx, hipStreamSynchronize(ctx->stream));
 
     if (h[TOT_ERR] & ERR_TOO_MANY_TRIPLES) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "a job has more than %u triples", MAX_T);
@@ -232,6 +270,12 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
     table->n_segs = ns;
     table->max_triples_per_job = h[TOT_MAX_T];
     table->max_segs_per_job = h[TOT_MAX_S];
+    const bool parked = !(h[TOT_ERR] & ERR_PARK_FULL);
+    if (!parked) {                                            // next time the slots will be wide enough
+        uint32_t want = h[TOT_MAX_T] + h[TOT_MAX_T] / 4;
+        want = (want + 63u) & ~63u;
+        ctx->park_stride = want > MAX_T ? MAX_T : want;
+    }
 
     if (!table->triples) return RK_OK;                        // sizing call
     if (!table->triple_off || !table->seg_off || !table->seg_g || !table->seg_first)
@@ -239,19 +283,20 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
     if (table->cap_triples < nt || table->cap_segs < ns)
         return rk_fail(ctx, RK_ERR_CAPACITY, "table too small: need %llu triples and %llu segments",
                        (unsigned long long)nt, (unsigned long long)ns);
-
-    RK_HIP(ctx, hipMemcpyAsync(table->triple_off, off_t, ((size_t)J + 1) * 4, hipMemcpyDeviceToDevice, ctx->stream));
-    RK_HIP(ctx, hipMemcpyAsync(table->seg_off, off_s, ((size_t)J + 1) * 4, hipMemcpyDeviceToDevice, ctx->stream));
-    if (J > 0) {
-        k_enumerate<true><<<J, ENUM_THREADS, 0, ctx->stream>>>(jobs->layers, jobs->gbatch, jobs->mbatch, *bounds,
-                                                                nullptr, nullptr, off_t, off_s, table->triples,
-                                                                table->seg_g, table->seg_first, totals);
-        RK_CHECK_LAUNCH(ctx, "k_enumerate<fill>");
+    if (mirrors) {
+        memcpy(table->h_triple_off, h + 16, ((size_t)J + 1) * 4);
+        memcpy(table->h_seg_off, h + 16 + J + 1, ((size_t)J + 1) * 4);
     }
-    if (table->h_triple_off && table->h_seg_off) {
-        RK_HIP(ctx, hipMemcpyAsync(table->h_triple_off, off_t, ((size_t)J + 1) * 4, hipMemcpyDeviceToHost, ctx->stream));
-        RK_HIP(ctx, hipMemcpyAsync(table->h_seg_off, off_s, ((size_t)J + 1) * 4, hipMemcpyDeviceToHost, ctx->stream));
-        RK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (J > 0) {
+        if (parked)
+            k_enumerate<MODE_FILL_PARKED><<<J, ENUM_THREADS, 0, ctx->stream>>>(
+                jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
+                off_t, off_s, table->triples, table->seg_g, table->seg_first, totals);
+        else
+            k_enumerate<MODE_FILL_SEARCH><<<J, ENUM_THREADS, 0, ctx->stream>>>(
+                jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
+                off_t, off_s, table->triples, table->seg_g, table->seg_first, totals);
+        RK_CHECK_LAUNCH(ctx, "k_enumerate<fill>");
     }
     return RK_OK;
 }

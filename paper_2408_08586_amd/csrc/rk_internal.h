@@ -9,7 +9,7 @@
 
 #include "rubick.h"
 
-enum { RK_SCRATCH_SLOTS = 32 };
+enum { RK_SCRATCH_SLOTS = 40 };
 
 struct rk_ctx {
     int device;
@@ -18,6 +18,9 @@ struct rk_ctx {
     void *scratch[RK_SCRATCH_SLOTS];        // grow-only device buffers owned by the context
     size_t scratch_bytes[RK_SCRATCH_SLOTS];
     uint32_t *h_pinned;                     // 64 pinned host words for counts coming back
+    uint32_t *h_stage;                      // pinned staging for the plan-table offsets, grown on demand
+    size_t h_stage_words;
+    uint32_t park_stride;                   // enumeration: words per job between its two passes
 };
 
 // scratch slots
@@ -29,7 +32,8 @@ enum {
     SL_HULL_KEY, SL_HULL_RAW, SL_HULL_DG, SL_HULL_DC, SL_HULL_TGT,   // walk steps of the greedy allocation
     SL_ST_GI, SL_ST_G, SL_ST_CI, SL_ST_FREEC, SL_ST_PARTIAL,         // its per-job and per-round state
     SL_ST_STEP_SLOPE, SL_ST_STEP_TGT, SL_ST_STEP_DG, SL_ST_FREEG,
-    SL_HIST_G, SL_HIST_C                                              // cost histograms over the step keys
+    SL_HIST_G, SL_HIST_C,                                             // cost histograms over the step keys
+    SL_PARK                                              // enumeration: sorted keys between its two passes
 };
 
 int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);

@@ -87,6 +87,41 @@ def test_enumerate_odd_jobs_and_bounds(gpu, orc):
         run.close()
 
 
+def test_enumerate_wide_jobs_and_limits(gpu, orc):
+    """Jobs with far more triples than usual (the two-pass hand-over inside the
+    enumeration has to widen its slots), and a job beyond the documented limit."""
+    import paper_2408_08586_amd as rk
+    base = workloads.tiny()
+    ints = np.array([[96, 5040, 1], [60, 2520, 1], [12, 32, 1], [96, 1680, 1]], np.uint32)
+    coef = np.tile(base.coef[:1], (len(ints), 1))
+    b = workloads.Bounds(g_max=1024)
+    wl = workloads.Workload("wide", coef, ints, b, base.grid, workloads.Env(), workloads.Cluster(8, 8, 64.0))
+    ot = orc.enumerate_plans(ints, b)
+    assert 1000 < int(ot.triple_off[1] - ot.triple_off[0]) <= 2048
+    for _ in range(2):                       # first context call widens, later calls take the direct path
+        run = gpu(wl)
+        run.enumerate()
+        oracle_table_equal(run.table_numpy(), ot)
+        run.enumerate()
+        oracle_table_equal(run.table_numpy(), ot)
+        o_thr, o_reason = orc.eval_jobs(wl.coef, wl.ints, wl.bounds, ot, wl.grid, wl.env, n_threads=8)
+        thr, feas, n = run.eval()
+        check_thr(run.host(thr, n), run.host(feas, n), o_thr, o_reason)
+        bt, bp, ns = run.best(thr)
+        o_bt, o_bp = orc.best_plan(ot, wl.grid, o_thr)
+        check_best_in_band(ot, run.n_rows, 0, wl.n_jobs, o_thr, o_bt, o_bp, run.host(bt, ns), run.host(bp, ns).view(np.uint32))
+        fbt, fbp, fct, fcp, fcg, _ = run.fused()
+        assert np.array_equal(run.host(fbt, ns), run.host(bt, ns)) and np.array_equal(run.host(fbp, ns), run.host(bp, ns))
+        run.close()
+    too_wide = workloads.Workload("too_wide", coef[:1], np.array([[96, 720720, 1]], np.uint32), workloads.Bounds(g_max=4096),
+                                  base.grid, workloads.Env(), workloads.Cluster(8, 8, 64.0))
+    run = gpu(too_wide)
+    with pytest.raises(rk.RkError) as e:
+        run.enumerate()
+    assert e.value.code == rk.RK_ERR_UNSUPPORTED
+    run.close()
+
+
 def test_enumerate_stress_sample(gpu, orc):
     wl = workloads.stress()
     run = gpu(wl)
