@@ -21,6 +21,24 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the stress workload with 3 job
+# chunks (profiles/hbm_traffic_stress.txt), already scaled by the plain-copy calibration (fetch x2.0, write x1.0).
+# Valid only for the kernel sources they were taken with: keyed by the digest of those sources.
+KERNEL_SOURCES = ("paper_2408_08586_amd/csrc/rk_eval.hip", "paper_2408_08586_amd/csrc/rk_model.h")
+MEASURED_TRAFFIC = {
+    # digest: {kernel: bytes per launch}
+    "66a0e49b091be0b2": {"k_eval": 918790631, "k_best_plan": 932049984},
+}
+
+
+def kernel_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
 
 def build_workload(name):
     import workloads
@@ -64,6 +82,47 @@ def cpu_baseline(wl, sample_jobs, threads):
             "eval_only_candidates_per_s": n / (t2 - t1)}
 
 
+def what_if_batch(rk, ctx, dev, n_rounds):
+    """What-if configuration: independent rounds of 500 jobs on about 512 GPUs.  Latency of each round run on
+    its own (rk_schedule_round, host-synchronous) and time of all rounds as one rk_schedule_rounds batch."""
+    import torch
+    import workloads
+    rounds = [workloads.what_if(r) for r in range(n_rounds)]
+    coef = np.concatenate([w.coef for w in rounds])
+    ints = np.concatenate([w.ints for w in rounds])
+    base = rounds[0]
+    bounds, grid, env = rk.make_bounds(base.bounds), rk.make_grid(base.grid), rk.make_env(base.env)
+    clusters = [rk.make_cluster(w.cluster) for w in rounds]
+    jobs_all = rk.Jobs(coef, ints, dev)
+    round_off = np.concatenate([[0], np.cumsum([w.n_jobs for w in rounds])]).astype(np.uint32)
+    assign = rk.new_assign(len(coef), dev)
+    totals = torch.zeros(n_rounds, dtype=torch.float32, device=dev)
+    batch_ms = []
+    for it in range(4):
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        rk.rk_schedule_rounds(ctx, jobs_all, bounds, grid, env, round_off, clusters, assign, totals)
+        torch.cuda.synchronize()
+        if it:
+            batch_ms.append((time.perf_counter() - a) * 1e3)
+    single = rk.Jobs(rounds[0].coef, rounds[0].ints, dev)
+    a1, t1 = rk.new_assign(rounds[0].n_jobs, dev), torch.zeros(1, dtype=torch.float32, device=dev)
+    lat = []
+    for r, w in enumerate(rounds):
+        single = rk.Jobs(w.coef, w.ints, dev)
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        rk.rk_schedule_round(ctx, single, bounds, grid, env, clusters[r], a1, t1)
+        torch.cuda.synchronize()
+        lat.append((time.perf_counter() - a) * 1e3)
+    lat = np.array(lat[1:])                                     # the first call sizes the scratch buffers
+    q = lambda p: float(np.percentile(lat, p))
+    return {"rounds": n_rounds, "jobs_per_round": rounds[0].n_jobs,
+            "single_round_latency_ms": {"min": float(lat.min()), "median": q(50), "p95": q(95), "p99": q(99),
+                                        "max": float(lat.max())},
+            "batch_ms": float(np.median(batch_ms)), "batch_rounds_per_s": n_rounds / (float(np.median(batch_ms)) * 1e-3)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +132,8 @@ def main():
     ap.add_argument("--chunks", type=int, default=3, help="job chunks streamed through one candidate buffer")
     ap.add_argument("--cpu-sample-jobs", type=int, default=1500)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-what-if", action="store_true")
+    ap.add_argument("--what-if-rounds", type=int, default=256)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (reads 1 GiB, writes 1 GiB) three times, "
                          "to scale the profiler's FETCH_SIZE / WRITE_SIZE counters")
@@ -178,6 +239,11 @@ def main():
     achieved = gbs_eval if dom == "eval" else gbs_best
     pair_gbs = (bytes_eval + bytes_best) / ((avg_ms["eval"] + avg_ms["best_plan"]) * 1e-3) / 1e9
 
+    digest = kernel_digest()
+    traffic = None
+    if args.workload == "stress" and n_chunks == 3:
+        traffic = MEASURED_TRAFFIC.get(digest, {}).get("k_eval" if dom == "eval" else "k_best_plan")
+
     out = {
         "metric": "candidate plan evaluations/sec (whole path: enumerate + evaluate + best plan + curves + greedy), 1 GPU",
         "value": n_cand / (ms_per_step * 1e-3),
@@ -188,7 +254,8 @@ def main():
                    "n_triples": table.n_triples, "job_chunks": n_chunks},
         "roofline": {"bound": "hbm", "kernel": "k_eval" if dom == "eval" else "k_best_plan",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None},
+                     "algorithmic_bytes_per_launch": bytes_eval if dom == "eval" else bytes_best,
+                     "traffic": traffic, "kernel_source_digest": digest},
         "kernels": {"avg_launch_ms": avg_ms, "per_step_ms": per_step_ms,
                     "eval_GBps": gbs_eval, "best_plan_GBps": gbs_best,
                     "eval_plus_best_plan_GBps": pair_gbs, "eval_plus_best_plan_frac_of_hbm": pair_gbs / HBM_PEAK_GBS,
@@ -196,6 +263,8 @@ def main():
         "round_latency_ms": {"entry": "rk_schedule_round (fused evaluation, host-synchronous)",
                              "min": float(lat.min()), "median": float(np.median(lat)), "max": float(lat.max())},
     }
+    if not args.no_what_if:
+        out["what_if"] = what_if_batch(rk, ctx, dev, args.what_if_rounds)
     if not args.no_cpu_baseline:
         threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_jobs, threads)
