@@ -316,6 +316,46 @@ def test_schedule_round_end_to_end(gpu, orc, name):
     run.close()
 
 
+def test_schedule_round_stress_against_stored_oracle(gpu, orc):
+    """Whole round on the 10,000-job workload against the oracle's stored result
+    (tests/golden/stress_round.json, written by make_stress_round.py from the oracle alone)."""
+    import json
+    import os
+    import paper_2408_08586_amd as rk
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "stress_round.json")))
+    wl = workloads.stress()
+    assert g["n_jobs"] == wl.n_jobs
+    ref = np.zeros(wl.n_jobs, rk.ASSIGN_DTYPE)
+    ref["plan"] = 0xFFFFFFFF
+    for j, gg, c, mem, plan, thr in g["scheduled"]:
+        ref[j] = (gg, c, mem, plan, thr)
+    run = gpu(wl)
+    assign, total = run.schedule_round()
+    same = compare_rounds(assign, total, dict(assign=ref, total=g["total"], min_gap=g["min_gap"]))
+    assert assign["g"].sum() <= wl.cluster.G and assign["c"].sum() <= wl.cluster.C
+    assert run_table_counts(run) == (g["n_triples"], g["n_segments"])
+    # the materialising entry points, chunked as in the benchmark, end in the same allocation
+    t = run.enumerate()
+    ns = t.n_segments(run.n_rows)
+    bt, bp = run.f32(ns), run.i32(ns)
+    ct, cp, cg = run.f32(ns), run.i32(ns), run.i32(ns)
+    edges = np.linspace(0, wl.n_jobs, 4).astype(int)
+    for jb, je in zip(edges[:-1], edges[1:]):
+        thr, _, n = run.eval(int(jb), int(je), want_feas=False)
+        s0 = run.n_rows * int(t.h_seg_off[jb])
+        rk.rk_best_plan(run.ctx, t.c, run.grid, int(jb), int(je), thr, bt[s0:], bp[s0:])
+        rk.rk_curves(run.ctx, t.c, run.grid, int(jb), int(je), bt[s0:], bp[s0:], ct[s0:], cp[s0:], cg[s0:])
+    assign2, total2 = run.allocate(bt, bp, ct)
+    assert np.array_equal(assign, assign2) and total == total2
+    print(f"stress round: {int((assign['g'] > 0).sum())} jobs scheduled, equal to the oracle's records: {same}")
+    run.close()
+
+
+def run_table_counts(run):
+    t = run.enumerate()
+    return t.n_triples, t.n_segs
+
+
 def test_schedule_rounds_batch_what_if(gpu, orc):
     import paper_2408_08586_amd as rk
     import torch
