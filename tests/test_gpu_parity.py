@@ -284,6 +284,54 @@ def test_allocate_many_jobs_random_curves(gpu, orc, n_jobs):
     run.close()
 
 
+def test_allocate_on_a_job_range(gpu, orc):
+    """rk_allocate on jobs [5, 23) of a larger table, arrays in the layout of that range."""
+    import paper_2408_08586_amd as rk
+    wl = workloads.paper_scale()
+    jb, je = 5, 23
+    sub = wl.subset(np.arange(jb, je))
+    sub.cluster = workloads.Cluster(20, 40, 600.0)
+    r = orc.schedule_round(sub, n_threads=8)
+    run = gpu(wl)
+    run.enumerate()
+    assign, total = run.allocate(run.dev_f32(r["best_thr"]), run.dev_u32(r["best_plan"]), run.dev_f32(r["curve_thr"]),
+                                 cluster=rk.make_cluster(sub.cluster), jb=jb, je=je)
+    assert np.array_equal(assign, r["assign"])
+    assert total == pytest.approx(r["total"], rel=1e-6)
+    run.close()
+
+
+def test_schedule_rounds_uneven_batch(gpu, orc):
+    """Rounds of different sizes in one batch, one of them empty."""
+    import paper_2408_08586_amd as rk
+    import torch
+    sizes = [37, 0, 120, 5, 64]
+    rounds = [workloads.what_if(10 + i, n_jobs=max(n, 1)).subset(np.arange(n)) for i, n in enumerate(sizes)]
+    for i, w in enumerate(rounds):
+        w.cluster = workloads.Cluster(40 + 30 * i, 300 + 200 * i, 3000.0 * (i + 1))
+    coef = np.concatenate([w.coef for w in rounds])
+    ints = np.concatenate([w.ints for w in rounds])
+    base = rounds[0]
+    wl = workloads.Workload("batch", coef, ints, base.bounds, base.grid, base.env, base.cluster)
+    run = gpu(wl)
+    round_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint32)
+    assign = rk.new_assign(wl.n_jobs)
+    totals = torch.zeros(len(sizes), dtype=torch.float32, device="cuda:0")
+    rk.rk_schedule_rounds(run.ctx, run.jobs, run.bounds, run.grid, run.env, round_off,
+                          [rk.make_cluster(w.cluster) for w in rounds], assign, totals)
+    rk.rk_sync(run.ctx)
+    a = rk.assign_to_numpy(assign)
+    for i, w in enumerate(rounds):
+        lo, hi = int(round_off[i]), int(round_off[i + 1])
+        if hi == lo:
+            assert float(totals[i].item()) == 0.0
+            continue
+        r = orc.schedule_round(w, n_threads=8)
+        compare_rounds(a[lo:hi], float(totals[i].item()), r)
+        assert a[lo:hi]["g"].sum() <= w.cluster.G and a[lo:hi]["c"].sum() <= w.cluster.C
+    run.close()
+
+
 def compare_rounds(assign, total, r):
     """End-to-end result against the oracle's round.  Where every decision of
     the oracle's greedy was clear (smallest slope gap well above float32
