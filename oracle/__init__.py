@@ -220,3 +220,40 @@ def schedule_round(wl, n_threads=1):
     assign, total, gap = greedy(wl.coef[:, 16], table, wl.grid, wl.cluster, bt, bp, ct)
     return dict(table=table, thr=thr, reason=reason, best_thr64=bt64, best_thr=bt, best_plan=bp,
                 curve_thr=ct, curve_plan=cp, curve_g=cg, assign=assign, total=total, min_gap=gap)
+
+
+def min_res(table, grid, best_thr, guaranteed, req_g, req_c, req_m, base_thr, jb=0, je=None):
+    """Minimum demand of guaranteed jobs -> (segment index or -1, CPU level, memory tier) per job of the range."""
+    je = table.n_jobs if je is None else je
+    gh = _GridHolder(grid)
+    best_thr = np.ascontiguousarray(best_thr, dtype=np.float32)
+    u = lambda a: np.ascontiguousarray(a, dtype=np.uint32)
+    guaranteed, req_g, req_c, req_m = u(guaranteed), u(req_g), u(req_c), u(req_m)
+    base_thr = np.ascontiguousarray(base_thr, dtype=np.float32)
+    n = je - jb
+    seg, c, m = np.zeros(n, np.int32), np.zeros(n, np.uint32), np.zeros(n, np.uint32)
+    rc = lib().ork_min_res_f32(C.byref(table.c), C.byref(gh.c), C.c_uint32(jb), C.c_uint32(je), _p(best_thr),
+                               _p(guaranteed), _p(req_g), _p(req_c), _p(req_m), _p(base_thr), _p(seg), _p(c), _p(m))
+    assert rc == 0
+    return seg, c, m
+
+
+def policy(ref_thr, table, grid, cluster, best_thr, best_idx, curve_thr, guaranteed, tenant, min_seg, min_c,
+           quota_g, quota_c):
+    """Greedy with service-level floors and tenant quotas."""
+    gh = _GridHolder(grid)
+    J = table.n_jobs
+    f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    u = lambda a: np.ascontiguousarray(a, dtype=np.uint32)
+    ref_thr, best_thr, curve_thr = f(ref_thr), f(best_thr), f(curve_thr)
+    best_idx, guaranteed, tenant, min_c, quota_g, quota_c = u(best_idx), u(guaranteed), u(tenant), u(min_c), u(quota_g), u(quota_c)
+    min_seg = np.ascontiguousarray(min_seg, dtype=np.int32)
+    assign = np.zeros(J, ASSIGN_DTYPE)
+    total, gap = C.c_double(0), C.c_double(0)
+    rc = lib().ork_policy_f32(C.c_uint32(J), _p(ref_thr), C.byref(table.c), C.byref(gh.c), C.c_uint32(cluster.G),
+                              C.c_uint32(cluster.C), C.c_float(cluster.host_mem_gb), _p(best_thr), _p(best_idx),
+                              _p(curve_thr), _p(guaranteed), _p(tenant), _p(min_seg), _p(min_c),
+                              C.c_uint32(len(quota_g)), _p(quota_g), _p(quota_c), _p(assign),
+                              C.byref(total), C.byref(gap))
+    assert rc == 0
+    return assign, total.value, gap.value

@@ -373,6 +373,44 @@ int ork_curves_f32(const ork_table *tb, const ork_grid *grid, uint32_t jb, uint3
     return 0;
 }
 
+/* Minimum demand of guaranteed jobs (Sec. 5.2 "Scheduling algorithm design"):
+ * the fewest resources, not above the request in any dimension, whose best
+ * plan reaches the performance of the requested resources with the original
+ * plan (base_thr).  "Fewest" is read as: fewest GPUs, then fewest CPUs, then
+ * smallest memory tier.  If nothing qualifies the request itself is the
+ * minimum.  Best-effort jobs have no minimum (segment -1).  A guaranteed job
+ * whose request is below its smallest valid GPU count gets -1 as well.
+ * Pinned: brute force over the same arrays in the tests, hand cases. */
+int ork_min_res_f32(const ork_table *tb, const ork_grid *grid, uint32_t jb, uint32_t je,
+                    const float *best_thr, const uint32_t *guaranteed, const uint32_t *req_g,
+                    const uint32_t *req_c, const uint32_t *req_m, const float *base_thr,
+                    int32_t *min_seg, uint32_t *min_c, uint32_t *min_m) {
+    const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    for (uint32_t j = jb; j < je; ++j) {
+        const uint32_t o = j - jb;
+        min_seg[o] = -1; min_c[o] = 0; min_m[o] = 0;
+        if (!guaranteed[j]) continue;
+        const uint64_t ns = tb->seg_off[j + 1] - tb->seg_off[j];
+        const uint64_t sbase = rows * (tb->seg_off[j] - tb->seg_off[jb]);
+        int64_t s_req = -1;
+        for (uint64_t s = 0; s < ns; ++s) if (tb->seg_g[tb->seg_off[j] + s] <= req_g[j]) s_req = (int64_t)s;
+        if (s_req < 0) continue;
+        const uint32_t c_req = req_c[j] < grid->n_cpu ? req_c[j] : grid->n_cpu - 1;
+        const uint32_t m_req = req_m[j] < grid->n_mem ? req_m[j] : grid->n_mem - 1;
+        bool found = false;
+        for (int64_t s = 0; s <= s_req && !found; ++s)
+            for (uint32_t c = 0; c <= c_req && !found; ++c)
+                for (uint32_t m = 0; m <= m_req && !found; ++m) {
+                    const float v = best_thr[sbase + ((uint64_t)c * grid->n_mem + m) * ns + s];
+                    if (v > 0.0f && v >= base_thr[j]) {
+                        min_seg[o] = (int32_t)s; min_c[o] = c; min_m[o] = m; found = true;
+                    }
+                }
+        if (!found) { min_seg[o] = (int32_t)s_req; min_c[o] = c_req; min_m[o] = m_req; }
+    }
+    return 0;
+}
+
 /* Greedy marginal-gain allocation: a reading of Sec. 5.2 (slopes of the
  * curves, "slopes of GPUs and then CPUs", memory allocated last from the
  * chosen plan's estimate) with every job best-effort and the cluster as
@@ -390,12 +428,47 @@ int ork_greedy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb,
                    const ork_grid *grid, uint32_t G, uint32_t C, float host_mem_gb,
                    const float *best_thr, const uint32_t *best_plan,
                    const float *curve_thr, ork_assign *assign, double *total, double *min_gap) {
+    return ork_policy_f32(n_jobs, ref_thr, tb, grid, G, C, host_mem_gb, best_thr, best_plan, curve_thr,
+                          nullptr, nullptr, nullptr, nullptr, 0, nullptr, nullptr, assign, total, min_gap);
+}
+
+/* The greedy with service-level floors (Sec. 5.2: guaranteed jobs within their
+ * tenant's quota are scheduled first with at least their minimum demand; the
+ * remaining resources go to the jobs with the highest slopes).
+ *  Privileged phase: guaranteed jobs in job order; a job whose minimum demand
+ *  (GPUs, CPUs) fits its tenant's remaining quota and the free capacity is
+ *  granted it; otherwise it waits for a later round and takes no part in this
+ *  one.  Then the GPU pass, CPU pass and memory step of the greedy run from
+ *  these floors; a job's GPU pass uses its floor's CPU level.
+ * PARITY UNPINNED as a reading; pinned by invariants and hand cases. */
+int ork_policy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb,
+                   const ork_grid *grid, uint32_t G, uint32_t C, float host_mem_gb,
+                   const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                   const uint32_t *guaranteed, const uint32_t *tenant, const int32_t *min_seg,
+                   const uint32_t *min_c, uint32_t n_tenants, const uint32_t *quota_g,
+                   const uint32_t *quota_c, ork_assign *assign, double *total, double *min_gap) {
     const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
     const uint32_t m_top = grid->n_mem - 1;
     std::vector<int64_t> gi(n_jobs, -1);
     std::vector<uint32_t> ci(n_jobs, 0);
+    std::vector<uint8_t> waits(n_jobs, 0);
     uint64_t freeG = G, freeC = C;
     double gap_min = INFINITY;
+    if (guaranteed) {                                       /* privileged phase */
+        std::vector<uint64_t> qg(quota_g, quota_g + n_tenants), qc(quota_c, quota_c + n_tenants);
+        for (uint32_t j = 0; j < n_jobs; ++j) {
+            if (!guaranteed[j]) continue;
+            waits[j] = 1;
+            if (min_seg[j] < 0 || tenant[j] >= n_tenants) continue;
+            const uint64_t g = tb->seg_g[tb->seg_off[j] + min_seg[j]];
+            const uint64_t c = cpus_of(grid, min_c[j], (uint32_t)g);
+            const uint32_t t = tenant[j];
+            if (g <= qg[t] && c <= qc[t] && g <= freeG && c <= freeC) {
+                qg[t] -= g; qc[t] -= c; freeG -= g; freeC -= c;
+                gi[j] = min_seg[j]; ci[j] = min_c[j]; waits[j] = 0;
+            }
+        }
+    }
 
     auto ns_of = [&](uint32_t j) { return (uint64_t)(tb->seg_off[j + 1] - tb->seg_off[j]); };
     auto g_of = [&](uint32_t j, int64_t s) -> uint64_t { return s < 0 ? 0 : tb->seg_g[tb->seg_off[j] + s]; };
@@ -413,13 +486,14 @@ int ork_greedy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb,
     for (;;) {
         float top = 0.0f, second = 0.0f; uint32_t tj = 0; int64_t ts = -1;
         for (uint32_t j = 0; j < n_jobs; ++j) {
-            const float cur = gi[j] < 0 ? 0.0f : at(curve_thr, j, 0, m_top, gi[j]);
+            if (waits[j]) continue;
+            const float cur = gi[j] < 0 ? 0.0f : at(curve_thr, j, ci[j], m_top, gi[j]);
             for (int64_t s = gi[j] + 1; s < (int64_t)ns_of(j); ++s) {
                 const uint64_t dg = g_of(j, s) - g_of(j, gi[j]);
                 if (dg > freeG) break;
-                const float v = at(curve_thr, j, 0, m_top, s);
+                const float v = at(curve_thr, j, ci[j], m_top, s);
                 if (!(v > cur)) continue;
-                const uint64_t dc = cpu_cost(j, 0, s) - cpu_cost(j, 0, gi[j]);
+                const uint64_t dc = cpu_cost(j, ci[j], s) - cpu_cost(j, ci[j], gi[j]);
                 if (dc > freeC) continue;
                 float sl = (v - cur) / ref_thr[j];
                 sl = sl / (float)dg;
@@ -430,7 +504,7 @@ int ork_greedy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb,
         if (ts < 0) break;
         note_gap(top, second);
         freeG -= g_of(tj, ts) - g_of(tj, gi[tj]);
-        freeC -= cpu_cost(tj, 0, ts) - cpu_cost(tj, 0, gi[tj]);
+        freeC -= cpu_cost(tj, ci[tj], ts) - cpu_cost(tj, ci[tj], gi[tj]);
         gi[tj] = ts;
     }
     /* CPU pass */

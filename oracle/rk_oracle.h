@@ -106,6 +106,21 @@ int ork_greedy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *table
                    const float *best_thr, const uint32_t *best_plan,
                    const float *curve_thr, ork_assign *assign, double *total, double *min_gap);
 
+/* Minimum demand of guaranteed jobs: (segment, CPU level, memory tier), -1 if
+ * none; outputs indexed by job - job_begin. */
+int ork_min_res_f32(const ork_table *table, const ork_grid *grid, uint32_t job_begin, uint32_t job_end,
+                    const float *best_thr, const uint32_t *guaranteed, const uint32_t *req_g,
+                    const uint32_t *req_c, const uint32_t *req_m, const float *base_thr,
+                    int32_t *min_seg, uint32_t *min_c, uint32_t *min_m);
+
+/* Greedy with service-level floors and tenant quotas (guaranteed == NULL: plain greedy). */
+int ork_policy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *table,
+                   const ork_grid *grid, uint32_t G, uint32_t C, float host_mem_gb,
+                   const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                   const uint32_t *guaranteed, const uint32_t *tenant, const int32_t *min_seg,
+                   const uint32_t *min_c, uint32_t n_tenants, const uint32_t *quota_g,
+                   const uint32_t *quota_c, ork_assign *assign, double *total, double *min_gap);
+
 #ifdef __cplusplus
 }
 #endif
