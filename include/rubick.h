@@ -245,6 +245,70 @@ int32_t rk_schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bound
                            uint32_t n_rounds, const uint32_t *round_off, const rk_cluster *clusters,
                            rk_assign *assign, float *totals);
 
+/* ---- service-level floors (Sec. 5.2 "Scheduling algorithm design") -------- */
+
+#define RK_MAX_TENANTS 256u
+
+/* Service-level inputs.  Per-job arrays are [device], length n_jobs of the
+ * job array, indexed by job.  quota_* are [device] [n_tenants]. */
+typedef struct {
+    const uint32_t *guaranteed; /* != 0: guaranteed job; 0: best-effort */
+    const uint32_t *tenant;     /* tenant index (>= n_tenants: the job waits) */
+    const uint32_t *req_g;      /* requested GPUs */
+    const uint32_t *req_c;      /* requested CPU level (index into the grid, clamped) */
+    const uint32_t *req_m;      /* requested memory tier (index into the grid, clamped) */
+    const float *base_thr;      /* throughput of the request with the job's original plan */
+    uint32_t n_tenants;         /* <= RK_MAX_TENANTS */
+    const uint32_t *quota_g;    /* GPUs the tenant's guaranteed jobs may hold */
+    const uint32_t *quota_c;    /* CPUs likewise */
+} rk_sla;
+
+/* Throughput of chosen points (Sec. 4, Eq. 1, same arithmetic and masking as
+ * rk_eval_candidates): point i is job pt_job[i], plan index pt_plan[i] inside
+ * the job (triple*16 + option), CPU level pt_c[i], memory tier pt_m[i], all
+ * [device] [n_points].  thr [device] receives 0 for infeasible points and for
+ * points whose indices are out of range; feas_or_null [device] the reason
+ * bits (RK_INFEASIBLE_STRUCT for out-of-range points).  Serves e.g. the
+ * baseline of a guaranteed job: its original plan at its requested resources. */
+int32_t rk_eval_points(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table,
+                       const rk_alloc_grid *grid, const rk_env *env, uint64_t n_points,
+                       const uint32_t *pt_job, const uint32_t *pt_plan, const uint32_t *pt_c,
+                       const uint32_t *pt_m, float *thr, uint8_t *feas_or_null);
+
+/* Minimum demand of the guaranteed jobs in [job_begin, job_end) (Sec. 5.2: the
+ * fewest resources, not above the request in any dimension, with which the
+ * best plan reaches the baseline performance).  "Fewest" = fewest GPUs, then
+ * fewest CPUs, then the smallest memory tier; a point qualifies when
+ * best_thr > 0 and best_thr >= base_thr.  If none qualifies the request itself
+ * (GPU count rounded down to a valid one) is the minimum.  best_thr is in
+ * segment layout of the range.  Outputs [device], one per job of the range:
+ * min_seg = segment index inside the job, or -1 for best-effort jobs and for
+ * requests below the job's smallest valid GPU count; min_c, min_m = levels. */
+int32_t rk_min_res(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_grid *grid,
+                   uint32_t job_begin, uint32_t job_end, const float *best_thr, const rk_sla *sla,
+                   int32_t *min_seg, uint32_t *min_c, uint32_t *min_m);
+
+/* rk_allocate with service-level floors (Sec. 5.2: guaranteed jobs within
+ * their tenant's quota are served first with at least their minimum demand,
+ * the rest goes to the highest slopes).  Privileged phase, in job order: a
+ * guaranteed job whose minimum (min_seg, min_c of the range, [device]) fits
+ * its tenant's remaining quota and the free GPUs and CPUs is granted it;
+ * otherwise it waits (g = 0 in the result) and takes no part in the round.
+ * Then the greedy runs from these floors on what is left; a job's GPU steps
+ * are valued at its floor's CPU level.  sla->req_* and base_thr are not read. */
+int32_t rk_allocate_sla(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                        const rk_alloc_grid *grid, const rk_cluster *cluster,
+                        uint32_t job_begin, uint32_t job_end,
+                        const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                        const rk_sla *sla, const int32_t *min_seg, const uint32_t *min_c,
+                        rk_assign *assign, float *total);
+
+/* rk_schedule_round with service levels: enumerate -> evaluate / best plan /
+ * curves -> minimum demands -> privileged phase -> greedy from the floors. */
+int32_t rk_schedule_round_sla(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                              const rk_alloc_grid *grid, const rk_env *env, const rk_cluster *cluster,
+                              const rk_sla *sla, rk_assign *assign, float *total);
+
 #ifdef __cplusplus
 }
 #endif

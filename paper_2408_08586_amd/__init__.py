@@ -18,9 +18,11 @@ RK_OK, RK_ERR_INVALID_ARG, RK_ERR_CAPACITY, RK_ERR_DEVICE, RK_ERR_UNSUPPORTED = 
 RK_NO_PLAN = 0xFFFFFFFF
 RK_MAX_CPU_LEVELS, RK_MAX_MEM_LEVELS = 64, 16
 RK_MAX_JOBS_PER_ROUND = 12288
+RK_MAX_TENANTS = 256
 
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
-           "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds")
+           "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
+           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -57,6 +59,11 @@ class rk_env(C.Structure):
 
 class rk_cluster(C.Structure):
     _fields_ = [("G", C.c_uint32), ("C", C.c_uint32), ("host_mem_gb", C.c_float)]
+
+
+class rk_sla(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("guaranteed", "tenant", "req_g", "req_c", "req_m", "base_thr")] + \
+               [("n_tenants", C.c_uint32), ("quota_g", C.c_void_p), ("quota_c", C.c_void_p)]
 
 
 ASSIGN_DTYPE = np.dtype([("g", np.uint32), ("c", np.uint32), ("mem_gb", np.float32),
@@ -266,6 +273,54 @@ def rk_schedule_rounds(ctx, jobs: Jobs, bounds, grid, env, round_off: np.ndarray
     _check(ctx, load_library().rk_schedule_rounds(ctx, C.byref(jobs.c), C.byref(bounds), C.byref(grid), C.byref(env),
                                                   C.c_uint32(n_rounds), round_off.ctypes.data_as(C.c_void_p), arr,
                                                   _ptr(assign), _ptr(totals)))
+
+
+class Sla:
+    """Service-level inputs on the device (int32 tensors hold the uint32 values)."""
+
+    def __init__(self, guaranteed, tenant, quota_g, quota_c, req_g=None, req_c=None, req_m=None, base_thr=None,
+                 device="cuda:0"):
+        import torch
+        dev_u32 = lambda a: None if a is None else torch.from_numpy(
+            np.ascontiguousarray(a, dtype=np.uint32).view(np.int32)).to(device)
+        self.guaranteed, self.tenant = dev_u32(guaranteed), dev_u32(tenant)
+        self.req_g, self.req_c, self.req_m = dev_u32(req_g), dev_u32(req_c), dev_u32(req_m)
+        self.quota_g, self.quota_c = dev_u32(quota_g), dev_u32(quota_c)
+        if base_thr is None or hasattr(base_thr, "data_ptr"):
+            self.base_thr = base_thr
+        else:
+            self.base_thr = torch.from_numpy(np.ascontiguousarray(base_thr, dtype=np.float32)).to(device)
+        self.c = rk_sla()
+        for name in ("guaranteed", "tenant", "req_g", "req_c", "req_m", "base_thr", "quota_g", "quota_c"):
+            t = getattr(self, name)
+            setattr(self.c, name, None if t is None or t.numel() == 0 else t.data_ptr())
+        self.c.n_tenants = 0 if self.quota_g is None else int(self.quota_g.numel())
+
+
+def rk_eval_points(ctx, jobs: Jobs, table, grid, env, pt_job, pt_plan, pt_c, pt_m, thr, feas=None):
+    _check(ctx, load_library().rk_eval_points(ctx, C.byref(jobs.c), C.byref(table), C.byref(grid), C.byref(env),
+                                              C.c_uint64(thr.numel()), _ptr(pt_job), _ptr(pt_plan), _ptr(pt_c),
+                                              _ptr(pt_m), _ptr(thr), _ptr(feas)))
+
+
+def rk_min_res(ctx, table, grid, job_begin, job_end, best_thr, sla: Sla, min_seg, min_c, min_m):
+    _check(ctx, load_library().rk_min_res(ctx, C.byref(table), C.byref(grid), C.c_uint32(job_begin),
+                                          C.c_uint32(job_end), _ptr(best_thr), C.byref(sla.c), _ptr(min_seg),
+                                          _ptr(min_c), _ptr(min_m)))
+
+
+def rk_allocate_sla(ctx, ref_thr, table, grid, cluster: rk_cluster, job_begin, job_end, best_thr, best_plan,
+                    curve_thr, sla: Sla, min_seg, min_c, assign, total):
+    _check(ctx, load_library().rk_allocate_sla(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.byref(cluster),
+                                               C.c_uint32(job_begin), C.c_uint32(job_end), _ptr(best_thr),
+                                               _ptr(best_plan), _ptr(curve_thr), C.byref(sla.c), _ptr(min_seg),
+                                               _ptr(min_c), _ptr(assign), _ptr(total)))
+
+
+def rk_schedule_round_sla(ctx, jobs: Jobs, bounds, grid, env, cluster, sla: Sla, assign, total):
+    _check(ctx, load_library().rk_schedule_round_sla(ctx, C.byref(jobs.c), C.byref(bounds), C.byref(grid),
+                                                     C.byref(env), C.byref(cluster), C.byref(sla.c), _ptr(assign),
+                                                     _ptr(total)))
 
 
 # ------------------------------------------------------------------ allocation helpers (no arithmetic)

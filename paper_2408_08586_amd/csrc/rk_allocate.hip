@@ -27,6 +27,11 @@
 // Memory (k_mem_wish / k_mem_finish): when the tiers every job would like fit
 // with margin, all are granted in parallel; otherwise one wavefront takes the
 // decisions in job order.
+//
+// Service-level floors (k_floors, optional): before the passes, guaranteed
+// jobs are granted their minimum demand in job order while their tenant's
+// quota and the free capacity last; the passes then start from these floors
+// and leave out the guaranteed jobs that have to wait.
 #include "rk_internal.h"
 #include "rk_model.h"
 
@@ -61,7 +66,22 @@ struct JobState {            // per job of the call, between the kernels
     unsigned long long *free_g, *free_c;   // per round: capacity left (after apply; after the tail)
     double *partial;         // per round and block of k_mem_wish: {sum of wish GiB, sum of thr/ref}
     uint32_t blocks_per_round;
+    // service-level floors, all null without them: the state a job starts from
+    // (segment index or -1, CPU level), whether it sits the round out, and per
+    // round the capacity left after the floors ([free G | free C])
+    int32_t *fl_gi;
+    uint32_t *fl_ci;
+    uint8_t *waits;
+    unsigned long long *cap0;
 };
+
+struct Floor { int32_t gi; uint32_t ci; bool waits; };
+
+__device__ __forceinline__ Floor floor_of(const JobState &st, uint32_t jrel) {
+    Floor f = {-1, 0u, false};
+    if (st.fl_gi) { f.gi = st.fl_gi[jrel]; f.ci = st.fl_ci[jrel]; f.waits = st.waits[jrel] != 0; }
+    return f;
+}
 
 // Rounds: job ranges and cluster capacities, either device arrays or, for a
 // single round, values carried in the kernel arguments.
@@ -123,17 +143,20 @@ __device__ __forceinline__ size_t hist_at(uint32_t rnd, int pass, int level) {
 
 // capacities a pass starts from
 template <int PASS>
-__device__ __forceinline__ void pass_caps(const rk_cluster &cl, const JobState &st, uint32_t rnd,
+__device__ __forceinline__ void pass_caps(const RoundArgs &R, const rk_cluster &cl, const JobState &st, uint32_t rnd,
                                           unsigned long long &capG, unsigned long long &capC) {
-    if (PASS == 0) { capG = cl.G; capC = cl.C; }
-    else { capG = 0; capC = st.free_c[rnd]; }
+    if (PASS == 0) {
+        if (st.cap0) { capG = st.cap0[rnd]; capC = st.cap0[R.n_rounds + rnd]; }
+        else { capG = cl.G; capC = cl.C; }
+    } else { capG = 0; capC = st.free_c[rnd]; }
 }
 
 // ------------------------------------------------------------------ hull walks
 // One wavefront per job; lanes hold the candidate amounts.  PASS 0: GPU counts
-// of the job (lowest CPU level, highest memory tier, values from the curves);
-// PASS 1: CPU levels at the granted GPU count (values from the per-segment
-// maxima).  Amounts that the whole round could never afford are left out.
+// of the job (CPU level of its floor, the lowest without one; highest memory
+// tier; values from the curves); PASS 1: CPU levels at the granted GPU count
+// (values from the per-segment maxima).  Amounts that the whole round could
+// never afford are left out.
 template <int PASS>
 __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullBuf H) {
     const uint32_t lane = threadIdx.x & 63u;
@@ -151,32 +174,41 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
     const uint64_t jbase = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]);
     const float ref = X.ref_thr[j];
 
-    uint32_t npts, g_fixed = 0;
+    uint32_t npts, g_fixed = 0, c_fixed = 0;
     int32_t cur_i;
-    unsigned long long cost_cur, cap_c;
+    unsigned long long cost_cur, cap_c, cap_g = 0;
     float cur;
     int32_t gi = -1;
     if (PASS == 0) {
-        npts = ns; cur_i = -1; cost_cur = 0; cur = 0.f; cap_c = cl.C;
+        const Floor fl = floor_of(st, jrel);
+        unsigned long long startG, startC;
+        pass_caps<0>(X.R, cl, st, rnd, startG, startC);
+        c_fixed = fl.ci;
+        npts = fl.waits ? 0u : ns;
+        cur_i = fl.gi;
+        cost_cur = fl.gi < 0 ? 0ull : (unsigned long long)X.tb.seg_g[s0 + fl.gi];
+        cur = fl.gi < 0 ? 0.f : vals[jbase + (uint64_t)(c_fixed * n_mem + n_mem - 1) * ns + fl.gi];
+        cap_g = startG + cost_cur;                       // the floor is already paid for
+        cap_c = startC + (fl.gi < 0 ? 0ull : cpu_cost(grid, c_fixed, (uint32_t)cost_cur));
     } else {
         gi = st.gi[jrel];
         npts = gi < 0 ? 0u : grid.n_cpu;
         g_fixed = gi < 0 ? 0u : st.g[jrel];
-        cur_i = 0;
-        cost_cur = cpu_cost(grid, 0, g_fixed);
-        cap_c = st.free_c[rnd] + cost_cur;               // level 0 is already paid for
-        cur = gi < 0 ? 0.f : vals[jbase + (uint64_t)(n_mem - 1) * ns + gi];
+        cur_i = (int32_t)st.ci[jrel];
+        cost_cur = cpu_cost(grid, (uint32_t)cur_i, g_fixed);
+        cap_c = st.free_c[rnd] + cost_cur;               // the level held is already paid for
+        cur = gi < 0 ? 0.f : vals[jbase + (uint64_t)((uint32_t)cur_i * n_mem + n_mem - 1) * ns + gi];
     }
     // amount s: its cost in the pass's resource and its value
     auto cost_of = [&](uint32_t s) -> unsigned long long {
         return PASS == 0 ? (unsigned long long)X.tb.seg_g[s0 + s] : cpu_cost(grid, s, g_fixed);
     };
     auto value_of = [&](uint32_t s) -> float {
-        return PASS == 0 ? vals[jbase + (uint64_t)(n_mem - 1) * ns + s]
+        return PASS == 0 ? vals[jbase + (uint64_t)(c_fixed * n_mem + n_mem - 1) * ns + s]
                          : vals[jbase + (uint64_t)(s * n_mem + n_mem - 1) * ns + gi];
     };
     auto affordable = [&](unsigned long long cost) -> bool {
-        if (PASS == 0) return cost <= cl.G && cpu_cost(grid, 0, (uint32_t)cost) <= cap_c;
+        if (PASS == 0) return cost <= cap_g && cpu_cost(grid, c_fixed, (uint32_t)cost) <= cap_c;
         return cost <= cap_c;
     };
 
@@ -212,7 +244,7 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
             H.tgt[e] = (uint16_t)top_s;
             if (PASS == 0) {
                 H.dg[e] = (uint32_t)(top_cost - cost_cur);
-                H.dc[e] = cpu_cost(grid, 0, (uint32_t)top_cost) - (cost_cur ? cpu_cost(grid, 0, (uint32_t)cost_cur) : 0ull);
+                H.dc[e] = cpu_cost(grid, c_fixed, (uint32_t)top_cost) - (cost_cur ? cpu_cost(grid, c_fixed, (uint32_t)cost_cur) : 0ull);
             } else {
                 H.dg[e] = 0u;
                 H.dc[e] = top_cost - cost_cur;
@@ -288,7 +320,7 @@ __global__ __launch_bounds__(JOB_THREADS) void k_hist(Ctx X, JobState st, HullBu
     int32_t want_top = 0;
     if (LEVEL == 1) {
         unsigned long long capG, capC;
-        pass_caps<PASS>(cl, st, rnd, capG, capC);
+        pass_caps<PASS>(X.R, cl, st, rnd, capG, capC);
         const size_t h0 = hist_at(rnd, PASS, 0);
         const Cut c0 = find_cut(hist.g + h0, hist.c + h0, 0, 0, capG, capC, cs);
         if (c0.bin < 0) return;                           // everything fits: no second level needed
@@ -340,15 +372,15 @@ __device__ __forceinline__ Step best_step(const Ctx &X, uint32_t j, int32_t gi, 
     Step out = {0.f, 0u, 0u};
     if (PASS == 0) {
         const uint32_t g_cur = gi < 0 ? 0u : X.tb.seg_g[s0 + gi];
-        const uint64_t row = jbase + (uint64_t)m_top * ns;                     // CPU level 0
+        const uint64_t row = jbase + (uint64_t)(ci * n_mem + m_top) * ns;      // the CPU level the job holds
         const float cur = gi < 0 ? 0.f : X.curve_thr[row + gi];
-        const unsigned long long c_cur = gi < 0 ? 0ull : cpu_cost(grid, 0, g_cur);
+        const unsigned long long c_cur = gi < 0 ? 0ull : cpu_cost(grid, ci, g_cur);
         for (uint32_t s = (uint32_t)(gi + 1); s < ns; ++s) {
             const uint32_t dg = X.tb.seg_g[s0 + s] - g_cur;
             if (dg > freeG) break;
             const float v = X.curve_thr[row + s];
             if (!(v > cur)) continue;
-            if (cpu_cost(grid, 0, g_cur + dg) - c_cur > freeC) continue;
+            if (cpu_cost(grid, ci, g_cur + dg) - c_cur > freeC) continue;
             float sl = (v - cur) / ref;
             sl = sl / (float)dg;
             if (sl > out.slope) { out.slope = sl; out.tgt = s; out.dg = dg; }
@@ -380,7 +412,7 @@ __global__ __launch_bounds__(JOB_THREADS) void k_apply(Ctx X, JobState st, HullB
     rk_cluster cl;
     round_of(X.R, rnd, J0, J1, cl);
     unsigned long long capG, capC;
-    pass_caps<PASS>(cl, st, rnd, capG, capC);
+    pass_caps<PASS>(X.R, cl, st, rnd, capG, capC);
     const size_t h0 = hist_at(rnd, PASS, 0), h1 = hist_at(rnd, PASS, 1);
     const Cut c0 = find_cut(hist.g + h0, hist.c + h0, 0, 0, capG, capC, cs);
     long long thr24 = -1;                                  // steps with (key >> 8) > thr24 are applied
@@ -396,9 +428,10 @@ __global__ __launch_bounds__(JOB_THREADS) void k_apply(Ctx X, JobState st, HullB
     if (J0 + jl < J1) {
         const uint32_t j = J0 + jl, jrel = j - X.jb;
         const uint32_t width = PASS == 0 ? H.width : (X.grid.n_cpu - 1 < H.width ? X.grid.n_cpu - 1 : H.width);
-        int32_t gi = PASS == 0 ? -1 : st.gi[jrel];
+        const Floor fl = PASS == 0 ? floor_of(st, jrel) : Floor{-1, 0u, false};
+        int32_t gi = PASS == 0 ? fl.gi : st.gi[jrel];
         uint32_t g_held = PASS == 0 ? 0u : st.g[jrel];
-        uint32_t ci = 0;
+        uint32_t ci = PASS == 0 ? fl.ci : st.ci[jrel];
         uint32_t k = 0, key = 0;
         size_t e = 0;
         for (; k < width; ++k) {
@@ -412,9 +445,8 @@ __global__ __launch_bounds__(JOB_THREADS) void k_apply(Ctx X, JobState st, HullB
             g_held = gi < 0 ? 0u : X.tb.seg_g[X.tb.seg_off[j] + gi];
             st.gi[jrel] = gi;
             st.g[jrel] = g_held;
-        } else {
-            st.ci[jrel] = ci;
         }
+        st.ci[jrel] = ci;
         // the job's best next step: the walk's next step if it still fits, else a fresh search
         Step nx = {0.f, 0u, 0u};
         if (key) {
@@ -465,16 +497,16 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_tail(Ctx X, uint32_t max_jobs,
         slope[jl] = st.step_slope[jrel0 + jl];
         tgt[jl] = st.step_tgt[jrel0 + jl];
         gi[jl] = (int16_t)st.gi[jrel0 + jl];
-        if (PASS == 0) { aux[jl] = st.step_dg[jrel0 + jl]; ci[jl] = 0; }
-        else { aux[jl] = (uint16_t)st.g[jrel0 + jl]; ci[jl] = (uint16_t)st.ci[jrel0 + jl]; }
+        ci[jl] = (uint16_t)st.ci[jrel0 + jl];
+        aux[jl] = PASS == 0 ? st.step_dg[jrel0 + jl] : (uint16_t)st.g[jrel0 + jl];
     }
     __syncthreads();
 
     // CPUs a cached step of job jl costs
     auto step_cpus = [&](uint32_t jl) -> unsigned long long {
         if (PASS == 0)
-            return grid.cpu_mode ? (unsigned long long)grid.cpu_levels[0] * aux[jl]
-                                 : (gi[jl] < 0 ? (unsigned long long)grid.cpu_levels[0] : 0ull);
+            return grid.cpu_mode ? (unsigned long long)grid.cpu_levels[ci[jl]] * aux[jl]
+                                 : (gi[jl] < 0 ? (unsigned long long)grid.cpu_levels[ci[jl]] : 0ull);
         return cpu_cost(grid, tgt[jl], aux[jl]) - cpu_cost(grid, ci[jl], aux[jl]);
     };
     // A cached step that stops fitting is not searched anew at once: it is
@@ -688,6 +720,84 @@ __global__ __launch_bounds__(64) void k_mem_finish(Ctx X, JobState st, rk_assign
     if (tid == 0) totals[rnd] = (float)sum;
 }
 
+// ------------------------------------------------------------------ service-level floors
+// One wavefront per round takes the decisions in job order.  Lanes load 64
+// jobs at a time; the guaranteed ones among them are then decided one after
+// the other with wavefront-uniform arithmetic: the job's demand is broadcast
+// from its lane, the quotas of tenant t live in lane t % 64 (register t / 64),
+// the free capacity in uniform registers.
+__device__ __forceinline__ uint32_t lane_value(uint32_t v, uint32_t lane) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)lane);
+}
+
+__global__ __launch_bounds__(64) void k_floors(Ctx X, JobState st, SlaDev S) {
+    constexpr uint32_t QREGS = RK_MAX_TENANTS / 64;
+    const uint32_t rnd = blockIdx.x, lane = threadIdx.x;
+    uint32_t J0, J1;
+    rk_cluster cl;
+    round_of(X.R, rnd, J0, J1, cl);
+    const GridDev &grid = X.grid;
+    const uint32_t nj = J1 - J0;
+    uint32_t qg[QREGS], qc[QREGS];
+#pragma unroll
+    for (uint32_t r = 0; r < QREGS; ++r) {
+        const uint32_t t = r * 64 + lane;
+        qg[r] = t < S.n_tenants ? S.quota_g[t] : 0u;
+        qc[r] = t < S.n_tenants ? S.quota_c[t] : 0u;
+    }
+    uint32_t freeG = cl.G, freeC = cl.C;
+    for (uint32_t base = 0; base < nj; base += 64) {
+        const uint32_t jl = base + lane;
+        bool guar = false, cand = false;
+        int32_t ms = -1;
+        uint32_t mc = 0, g = 0, c = 0, t = 0;
+        if (jl < nj) {
+            const uint32_t j = J0 + jl;
+            guar = S.guaranteed[j] != 0;
+            if (guar) {
+                ms = S.min_seg[j - X.jb];
+                mc = S.min_c[j - X.jb];
+                t = S.tenant[j];
+                const uint32_t s0 = X.tb.seg_off[j], ns = X.tb.seg_off[j + 1] - s0;
+                if (ms >= 0 && (uint32_t)ms < ns && mc < grid.n_cpu && t < S.n_tenants) {
+                    g = X.tb.seg_g[s0 + ms];
+                    const unsigned long long c64 = cpu_cost(grid, mc, g);
+                    cand = c64 <= 0xFFFFFFFFull;           // more can never fit a 32-bit capacity
+                    c = (uint32_t)c64;
+                }
+            }
+        }
+        bool granted = false;
+        unsigned long long todo = __ballot(cand);
+        while (todo) {
+            const uint32_t turn = (uint32_t)__ffsll((long long)todo) - 1u;
+            todo &= todo - 1;
+            const uint32_t tg = lane_value(g, turn), tc = lane_value(c, turn), tt = lane_value(t, turn);
+            const uint32_t ql = tt & 63u, qr = tt >> 6;
+            uint32_t vg = 0, vc = 0;
+#pragma unroll
+            for (uint32_t r = 0; r < QREGS; ++r) {
+                const uint32_t a = lane_value(qg[r], ql), b = lane_value(qc[r], ql);
+                if (r == qr) { vg = a; vc = b; }
+            }
+            if (tg <= vg && tc <= vc && tg <= freeG && tc <= freeC) {
+                freeG -= tg; freeC -= tc;
+#pragma unroll
+                for (uint32_t r = 0; r < QREGS; ++r)
+                    if (r == qr && lane == ql) { qg[r] -= tg; qc[r] -= tc; }
+                if (lane == turn) granted = true;
+            }
+        }
+        if (jl < nj) {
+            const uint32_t jrel = J0 + jl - X.jb;
+            st.fl_gi[jrel] = granted ? ms : -1;
+            st.fl_ci[jrel] = granted ? mc : 0u;
+            st.waits[jrel] = (guar && !granted) ? 1 : 0;
+        }
+    }
+    if (lane == 0) { st.cap0[rnd] = freeG; st.cap0[X.R.n_rounds + rnd] = freeC; }
+}
+
 __global__ void k_zero_u32(uint32_t *p, size_t n) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0u;
@@ -725,7 +835,7 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
                            uint32_t n_rounds, const uint32_t *d_round_off, const rk_cluster *d_clusters,
                            const rk_cluster *one_cluster, uint32_t jb, uint32_t n_jobs, uint32_t max_jobs,
                            uint32_t max_segs_per_job, const float *best_thr, const uint32_t *best_plan,
-                           const float *curve_thr, rk_assign *assign, float *totals) {
+                           const float *curve_thr, const SlaDev *sla, rk_assign *assign, float *totals) {
     if (n_rounds == 0) return RK_OK;
     if (max_jobs > RK_MAX_JOBS_PER_ROUND)
         return rk_fail(ctx, RK_ERR_UNSUPPORTED, "a round has %u jobs, the allocation kernels take up to %u", max_jobs,
@@ -753,6 +863,13 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
     if ((rc = scratch_typed(ctx, SL_ST_FREEG, (size_t)n_rounds * 2, &st.free_g))) return rc;   // [free G | free C] after apply
     if ((rc = scratch_typed(ctx, SL_ST_FREEC, (size_t)n_rounds, &st.free_c))) return rc;
     if ((rc = scratch_typed(ctx, SL_ST_PARTIAL, (size_t)n_rounds * st.blocks_per_round * 2, &st.partial))) return rc;
+    st.fl_gi = nullptr; st.fl_ci = nullptr; st.waits = nullptr; st.cap0 = nullptr;
+    if (sla) {
+        if ((rc = scratch_typed(ctx, SL_FL_GI, (size_t)H.stride, &st.fl_gi))) return rc;
+        if ((rc = scratch_typed(ctx, SL_FL_CI, (size_t)H.stride, &st.fl_ci))) return rc;
+        if ((rc = scratch_typed(ctx, SL_FL_WAITS, (size_t)H.stride, &st.waits))) return rc;
+        if ((rc = scratch_typed(ctx, SL_FL_CAP0, (size_t)n_rounds * 2, &st.cap0))) return rc;
+    }
     Hist hist;
     const size_t hist_bins = (size_t)n_rounds * 4 * BINS;
     if ((rc = scratch_typed(ctx, SL_HIST_G, hist_bins, &hist.g))) return rc;
@@ -783,6 +900,10 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
         k_zero_u32<<<(unsigned)((n64 + 255) / 256), 256, 0, s>>>(reinterpret_cast<uint32_t *>(hist.c), n64);
         RK_CHECK_LAUNCH(ctx, "k_zero_u32");
     }
+    if (sla) {
+        k_floors<<<n_rounds, 64, 0, s>>>(X, st, *sla);
+        RK_CHECK_LAUNCH(ctx, "k_floors");
+    }
     if ((rc = launch_pass<0>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, lds))) return rc;
     if ((rc = launch_pass<1>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, lds))) return rc;
     if (max_jobs > 0) {
@@ -809,5 +930,39 @@ extern "C" int32_t rk_allocate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
     if (table->max_segs_per_job > 32767u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 32767 segments per job");
     RK_HIP(ctx, hipSetDevice(ctx->device));
     return rk_launch_allocate(ctx, ref_thr, table_dev(table), grid, 1, nullptr, nullptr, cluster, jb, je - jb, je - jb,
-                              table->max_segs_per_job, best_thr, best_plan, curve_thr, assign, total);
+                              table->max_segs_per_job, best_thr, best_plan, curve_thr, nullptr, assign, total);
+}
+
+int32_t rk_check_sla(rk_ctx *ctx, const rk_sla *sla, bool need_request) {
+    if (!sla) return rk_fail(ctx, RK_ERR_INVALID_ARG, "sla is null");
+    if (!sla->guaranteed || !sla->tenant) return rk_fail(ctx, RK_ERR_INVALID_ARG, "sla: guaranteed or tenant is null");
+    if (sla->n_tenants > RK_MAX_TENANTS)
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "%u tenants, at most %u", sla->n_tenants, RK_MAX_TENANTS);
+    if (sla->n_tenants > 0 && (!sla->quota_g || !sla->quota_c)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "sla: quota array is null");
+    if (need_request && (!sla->req_g || !sla->req_c || !sla->req_m || !sla->base_thr))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "sla: request or baseline array is null");
+    return RK_OK;
+}
+
+extern "C" int32_t rk_allocate_sla(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                                   const rk_alloc_grid *grid, const rk_cluster *cluster, uint32_t jb, uint32_t je,
+                                   const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                                   const rk_sla *sla, const int32_t *min_seg, const uint32_t *min_c,
+                                   rk_assign *assign, float *total) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if ((rc = rk_check_table(ctx, table, jb, je))) return rc;
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    if (!cluster || !total) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (je > jb && (!ref_thr || !best_thr || !best_plan || !curve_thr || !assign || !min_seg || !min_c))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (je > jb && (rc = rk_check_sla(ctx, sla, false))) return rc;
+    if (!(cluster->host_mem_gb >= 0.f)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "host_mem_gb negative or NaN");
+    if (table->max_segs_per_job > 32767u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 32767 segments per job");
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    SlaDev S = {};
+    if (je > jb) S = SlaDev{sla->guaranteed, sla->tenant, min_seg, min_c, sla->n_tenants, sla->quota_g, sla->quota_c};
+    return rk_launch_allocate(ctx, ref_thr, table_dev(table), grid, 1, nullptr, nullptr, cluster, jb, je - jb, je - jb,
+                              table->max_segs_per_job, best_thr, best_plan, curve_thr, je > jb ? &S : nullptr, assign,
+                              total);
 }

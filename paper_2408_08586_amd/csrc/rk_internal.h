@@ -33,7 +33,9 @@ enum {
     SL_ST_GI, SL_ST_G, SL_ST_CI, SL_ST_FREEC, SL_ST_PARTIAL,         // its per-job and per-round state
     SL_ST_STEP_SLOPE, SL_ST_STEP_TGT, SL_ST_STEP_DG, SL_ST_FREEG,
     SL_HIST_G, SL_HIST_C,                                             // cost histograms over the step keys
-    SL_PARK                                              // enumeration: sorted keys between its two passes
+    SL_PARK,                                             // enumeration: sorted keys between its two passes
+    SL_FL_GI, SL_FL_CI, SL_FL_WAITS, SL_FL_CAP0,         // service-level floors of the allocation
+    SL_MIN_SEG, SL_MIN_C, SL_MIN_M                       // minimum demands of a round
 };
 
 int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);
@@ -57,6 +59,8 @@ int32_t rk_scratch(rk_ctx *ctx, int slot, size_t bytes, void **out);
 int32_t rk_check_grid(rk_ctx *ctx, const rk_alloc_grid *grid);
 int32_t rk_check_env(rk_ctx *ctx, const rk_env *env);
 int32_t rk_check_table(rk_ctx *ctx, const rk_plan_table *table, uint32_t job_begin, uint32_t job_end);
+// need_request: the request and baseline arrays must be present as well
+int32_t rk_check_sla(rk_ctx *ctx, const rk_sla *sla, bool need_request);
 // triple_off / seg_off at job_begin and job_end (host mirrors, or two copies back)
 int32_t rk_range_offsets(rk_ctx *ctx, const rk_plan_table *table, uint32_t job_begin, uint32_t job_end,
                          uint64_t *n_triples, uint64_t *n_segs);
@@ -74,6 +78,15 @@ static inline TableDev table_dev(const rk_plan_table *t) {
     return TableDev{t->triple_off, t->triples, t->seg_off, t->seg_g, t->seg_first};
 }
 
+// service-level inputs of the allocation; min_seg / min_c are indexed from the call's first job
+struct SlaDev {
+    const uint32_t *guaranteed, *tenant;
+    const int32_t *min_seg;
+    const uint32_t *min_c;
+    uint32_t n_tenants;
+    const uint32_t *quota_g, *quota_c;
+};
+
 // launch wrappers (each enqueues on ctx->stream)
 int32_t rk_launch_fused(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table,
                         const rk_alloc_grid *grid, const rk_env *env, uint32_t jb, uint32_t je,
@@ -81,8 +94,13 @@ int32_t rk_launch_fused(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *t
                         uint32_t *curve_g);
 // one_cluster != NULL: a single round over [jb, jb + n_jobs) with that cluster, carried in the
 // kernel arguments; otherwise n_rounds rounds described by the device arrays.
+// sla != NULL: service-level floors first (the quotas apply to every round alike).
 int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb, const rk_alloc_grid *grid,
                            uint32_t n_rounds, const uint32_t *d_round_off, const rk_cluster *d_clusters,
                            const rk_cluster *one_cluster, uint32_t jb, uint32_t n_jobs, uint32_t max_jobs,
                            uint32_t max_segs_per_job, const float *best_thr, const uint32_t *best_plan,
-                           const float *curve_thr, rk_assign *assign, float *totals);
+                           const float *curve_thr, const SlaDev *sla, rk_assign *assign, float *totals);
+// minimum demands of the guaranteed jobs of [jb, je)
+int32_t rk_launch_min_res(rk_ctx *ctx, const TableDev &tb, const rk_alloc_grid *grid, uint32_t jb, uint32_t je,
+                          const float *best_thr, const rk_sla *sla, int32_t *min_seg, uint32_t *min_c,
+                          uint32_t *min_m);

@@ -1,17 +1,17 @@
 // Whole scheduling rounds on the device: enumerate -> fused evaluation /
-// best plan / curves -> greedy allocation (paper Sec. 5.2, Algorithm 1 reduced
-// to best-effort jobs over cluster totals).
+// best plan / curves -> [minimum demands, privileged phase] -> greedy
+// allocation (paper Sec. 5.2, Algorithm 1 over cluster totals).
 #include <cstring>
 
 #include "rk_internal.h"
 
-extern "C" {
+namespace {
 
-int32_t rk_schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
-                           const rk_alloc_grid *grid, const rk_env *env, uint32_t n_rounds,
-                           const uint32_t *round_off, const rk_cluster *clusters, rk_assign *assign,
-                           float *totals) {
-    if (!ctx) return RK_ERR_INVALID_ARG;
+// sla == NULL: every job is best-effort
+int32_t schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                        const rk_alloc_grid *grid, const rk_env *env, uint32_t n_rounds,
+                        const uint32_t *round_off, const rk_cluster *clusters, const rk_sla *sla,
+                        rk_assign *assign, float *totals) {
     int32_t rc;
     if (!jobs || !bounds || !round_off || !clusters || !totals || (!assign && jobs->n_jobs > 0))
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
@@ -76,11 +76,33 @@ int32_t rk_schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bound
     if ((rc = rk_scratch(ctx, SL_CURVE_G, n_out * 4, (void **)&curve_g))) return rc;
 
     if ((rc = rk_launch_fused(ctx, jobs, &tb, grid, env, 0, J, best_thr, best_plan, curve_thr, curve_plan, curve_g))) return rc;
+    SlaDev S = {};
+    if (sla && J > 0) {
+        int32_t *min_seg;
+        uint32_t *min_c, *min_m;
+        if ((rc = rk_scratch(ctx, SL_MIN_SEG, (size_t)J * 4, (void **)&min_seg))) return rc;
+        if ((rc = rk_scratch(ctx, SL_MIN_C, (size_t)J * 4, (void **)&min_c))) return rc;
+        if ((rc = rk_scratch(ctx, SL_MIN_M, (size_t)J * 4, (void **)&min_m))) return rc;
+        if ((rc = rk_launch_min_res(ctx, table_dev(&tb), grid, 0, J, best_thr, sla, min_seg, min_c, min_m))) return rc;
+        S = SlaDev{sla->guaranteed, sla->tenant, min_seg, min_c, sla->n_tenants, sla->quota_g, sla->quota_c};
+    }
     return rk_launch_allocate(ctx, jobs->ref_thr, table_dev(&tb), grid, n_rounds,
                               reinterpret_cast<const uint32_t *>(d_meta),
                               d_meta ? reinterpret_cast<const rk_cluster *>(d_meta + off_bytes) : nullptr,
                               n_rounds == 1 ? &clusters[0] : nullptr, 0, J, max_jobs, tb.max_segs_per_job,
-                              best_thr, best_plan, curve_thr, assign, totals);
+                              best_thr, best_plan, curve_thr, (sla && J > 0) ? &S : nullptr, assign, totals);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t rk_schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                           const rk_alloc_grid *grid, const rk_env *env, uint32_t n_rounds,
+                           const uint32_t *round_off, const rk_cluster *clusters, rk_assign *assign,
+                           float *totals) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    return schedule_rounds(ctx, jobs, bounds, grid, env, n_rounds, round_off, clusters, nullptr, assign, totals);
 }
 
 int32_t rk_schedule_round(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
@@ -89,7 +111,18 @@ int32_t rk_schedule_round(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds
     if (!ctx) return RK_ERR_INVALID_ARG;
     if (!jobs || !cluster) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
     const uint32_t off[2] = {0u, jobs->n_jobs};
-    return rk_schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, cluster, assign, total);
+    return schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, cluster, nullptr, assign, total);
+}
+
+int32_t rk_schedule_round_sla(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                              const rk_alloc_grid *grid, const rk_env *env, const rk_cluster *cluster,
+                              const rk_sla *sla, rk_assign *assign, float *total) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    if (!jobs || !cluster) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    int32_t rc;
+    if (jobs->n_jobs > 0 && (rc = rk_check_sla(ctx, sla, true))) return rc;
+    const uint32_t off[2] = {0u, jobs->n_jobs};
+    return schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, cluster, jobs->n_jobs > 0 ? sla : nullptr, assign, total);
 }
 
 }  // extern "C"

@@ -1,0 +1,172 @@
+// Service-level support (paper Sec. 5.2, "Scheduling algorithm design"):
+// the minimum demand of guaranteed jobs, and the evaluation of chosen points
+// of the plan space (a guaranteed job's baseline is its original plan at its
+// requested resources).
+#include "rk_internal.h"
+#include "rk_model.h"
+
+namespace {
+
+constexpr int MINRES_THREADS = 256;
+constexpr int POINT_THREADS = 256;
+
+struct SlaReq {
+    const uint32_t *guaranteed, *req_g, *req_c, *req_m;
+    const float *base_thr;
+};
+
+// One wavefront per job.  Lanes take consecutive GPU counts (segments) of the
+// job, so every (CPU level, memory tier) row is read coalesced; a lane keeps
+// the first (level, tier) in ascending order that qualifies at its segment,
+// and the lowest qualifying segment of the wavefront wins.
+__global__ __launch_bounds__(MINRES_THREADS) void k_min_res(TableDev tb, GridDev grid, uint32_t jb, uint32_t je,
+                                                            const float *__restrict__ best_thr, SlaReq R,
+                                                            int32_t *__restrict__ min_seg,
+                                                            uint32_t *__restrict__ min_c,
+                                                            uint32_t *__restrict__ min_m) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t j = jb + blockIdx.x * (MINRES_THREADS / 64) + (threadIdx.x >> 6);
+    if (j >= je) return;                                   // whole wavefront
+    const uint32_t o = j - jb;
+    int32_t out_s = -1;
+    uint32_t out_c = 0, out_m = 0;
+    if (R.guaranteed[j]) {
+        const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
+        const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem;
+        const uint64_t jbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]);
+        const uint32_t rg = R.req_g[j];
+        const uint32_t c_req = R.req_c[j] < grid.n_cpu ? R.req_c[j] : grid.n_cpu - 1;
+        const uint32_t m_req = R.req_m[j] < n_mem ? R.req_m[j] : n_mem - 1;
+        const float base_thr = R.base_thr[j];
+        // number of segments within the request (GPU counts ascend)
+        uint32_t lo = 0, hi = ns;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (tb.seg_g[s0 + mid] <= rg) lo = mid + 1; else hi = mid;
+        }
+        const uint32_t n_ok = lo;
+        if (n_ok > 0) {
+            out_s = (int32_t)(n_ok - 1); out_c = c_req; out_m = m_req;   // the request itself unless less will do
+            for (uint32_t base = 0; base < n_ok; base += 64) {
+                const uint32_t s = base + lane;
+                uint32_t mine = 0xFFFFFFFFu;               // (level << 8 | tier) of this lane's first hit
+                if (s < n_ok) {
+                    for (uint32_t c = 0; c <= c_req && mine == 0xFFFFFFFFu; ++c)
+                        for (uint32_t m = 0; m <= m_req; ++m) {
+                            const float v = best_thr[jbase + (uint64_t)(c * n_mem + m) * ns + s];
+                            if (v > 0.f && v >= base_thr) { mine = (c << 8) | m; break; }
+                        }
+                }
+                const unsigned long long hits = __ballot(mine != 0xFFFFFFFFu);
+                if (hits) {
+                    const uint32_t first = (uint32_t)__ffsll((long long)hits) - 1u;
+                    const uint32_t cm = (uint32_t)__builtin_amdgcn_readlane((int)mine, (int)first);
+                    out_s = (int32_t)(base + first); out_c = cm >> 8; out_m = cm & 255u;
+                    break;
+                }
+            }
+        }
+    }
+    if (lane == 0) { min_seg[o] = out_s; min_c[o] = out_c; min_m[o] = out_m; }
+}
+
+// One thread per point: the candidate's value exactly as the candidate
+// evaluation computes it (same functions, same order).
+template <bool WITH_FEAS>
+__global__ __launch_bounds__(POINT_THREADS) void k_eval_points(JobDev jobs, TableDev tb, GridDev grid, rk_env env,
+                                                               uint32_t n_jobs, uint32_t option_mask, uint64_t n_points,
+                                                               const uint32_t *__restrict__ pt_job,
+                                                               const uint32_t *__restrict__ pt_plan,
+                                                               const uint32_t *__restrict__ pt_c,
+                                                               const uint32_t *__restrict__ pt_m,
+                                                               float *__restrict__ thr, uint8_t *__restrict__ feas) {
+    const uint64_t i = (uint64_t)blockIdx.x * POINT_THREADS + threadIdx.x;
+    if (i >= n_points) return;
+    const uint32_t j = pt_job[i], plan = pt_plan[i], ci = pt_c[i], mi = pt_m[i];
+    float out = 0.f;
+    uint32_t why = RK_INFEASIBLE_STRUCT;
+    bool valid = j < n_jobs && ci < grid.n_cpu && mi < grid.n_mem;
+    uint32_t t0 = 0;
+    if (valid) {
+        t0 = tb.triple_off[j];
+        valid = (plan >> 4) < tb.triple_off[j + 1] - t0;
+    }
+    if (valid) {
+        const uint32_t o = plan & 15u, z = o >> 2, gc = (o >> 1) & 1u, off = o & 1u;
+        const bool allowed = ((option_mask >> o) & 1u) && (!off || z >= 2);
+        if (allowed) {
+            const Job J = load_job(jobs, j);
+            const Triple T = triple_terms(J, env, tb.triples[t0 + (plan >> 4)]);
+            why = gpu_mem_fits(J, env, T, z, gc, off) ? 0u : RK_INFEASIBLE_GPU_MEM;
+            if (!off) {
+                if (!why) out = thr_plain(J, T, z, gc);
+            } else {
+                if (!(host_bytes_needed(J, T) <= tier_bytes(grid, mi, T.g))) why |= RK_INFEASIBLE_HOST_MEM;
+                if (!why) {
+                    const Offload O = offload_terms(J, env, T);
+                    out = thr_offload(T, O, gc, swap_term(J, O, cpus_of(grid, ci, T.g)));
+                }
+            }
+        }
+    }
+    thr[i] = out;
+    if (WITH_FEAS) feas[i] = (uint8_t)why;
+}
+
+}  // namespace
+
+int32_t rk_launch_min_res(rk_ctx *ctx, const TableDev &tb, const rk_alloc_grid *grid, uint32_t jb, uint32_t je,
+                          const float *best_thr, const rk_sla *sla, int32_t *min_seg, uint32_t *min_c,
+                          uint32_t *min_m) {
+    if (je <= jb) return RK_OK;
+    const uint32_t per_block = MINRES_THREADS / 64;
+    const uint32_t blocks = (je - jb + per_block - 1) / per_block;
+    const SlaReq R = {sla->guaranteed, sla->req_g, sla->req_c, sla->req_m, sla->base_thr};
+    k_min_res<<<blocks, MINRES_THREADS, 0, ctx->stream>>>(tb, grid_dev(grid), jb, je, best_thr, R, min_seg, min_c, min_m);
+    RK_CHECK_LAUNCH(ctx, "k_min_res");
+    return RK_OK;
+}
+
+extern "C" {
+
+int32_t rk_min_res(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_grid *grid, uint32_t jb, uint32_t je,
+                   const float *best_thr, const rk_sla *sla, int32_t *min_seg, uint32_t *min_c, uint32_t *min_m) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if ((rc = rk_check_table(ctx, table, jb, je))) return rc;
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    if (je == jb) return RK_OK;
+    if (!best_thr || !min_seg || !min_c || !min_m) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (!sla || !sla->guaranteed || !sla->req_g || !sla->req_c || !sla->req_m || !sla->base_thr)
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "sla: guaranteed, request or baseline array is null");
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    return rk_launch_min_res(ctx, table_dev(table), grid, jb, je, best_thr, sla, min_seg, min_c, min_m);
+}
+
+int32_t rk_eval_points(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table, const rk_alloc_grid *grid,
+                       const rk_env *env, uint64_t n_points, const uint32_t *pt_job, const uint32_t *pt_plan,
+                       const uint32_t *pt_c, const uint32_t *pt_m, float *thr, uint8_t *feas) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if (!jobs) return rk_fail(ctx, RK_ERR_INVALID_ARG, "jobs is null");
+    if ((rc = rk_check_table(ctx, table, 0, jobs->n_jobs))) return rc;
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    if ((rc = rk_check_env(ctx, env))) return rc;
+    if (n_points == 0) return RK_OK;
+    if (!pt_job || !pt_plan || !pt_c || !pt_m || !thr) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (n_points > 0x7FFFFFFFull * POINT_THREADS) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "too many points for one call");
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    const unsigned blocks = (unsigned)((n_points + POINT_THREADS - 1) / POINT_THREADS);
+    if (feas)
+        k_eval_points<true><<<blocks, POINT_THREADS, 0, ctx->stream>>>(job_dev(jobs), table_dev(table), grid_dev(grid), *env,
+                                                                      jobs->n_jobs, table->option_mask, n_points, pt_job,
+                                                                      pt_plan, pt_c, pt_m, thr, feas);
+    else
+        k_eval_points<false><<<blocks, POINT_THREADS, 0, ctx->stream>>>(job_dev(jobs), table_dev(table), grid_dev(grid), *env,
+                                                                       jobs->n_jobs, table->option_mask, n_points, pt_job,
+                                                                       pt_plan, pt_c, pt_m, thr, nullptr);
+    RK_CHECK_LAUNCH(ctx, "k_eval_points");
+    return RK_OK;
+}
+
+}  // extern "C"

@@ -42,14 +42,15 @@ def test_header_functions_are_exported(rk):
 
 
 def test_struct_layouts_match_the_header(rk):
-    structs = ["rk_jobs", "rk_plan_bounds", "rk_plan_table", "rk_alloc_grid", "rk_env", "rk_cluster", "rk_assign"]
+    structs = ["rk_jobs", "rk_plan_bounds", "rk_plan_table", "rk_alloc_grid", "rk_env", "rk_cluster", "rk_assign", "rk_sla"]
     prog = ['#include <stdio.h>', '#include <stddef.h>', '#include "rubick.h"', 'int main(void){']
     for s in structs:
         prog.append(f'printf("{s} %zu\\n", sizeof({s}));')
     fields = {"rk_plan_table": ["cap_triples", "h_triple_off", "n_triples", "n_jobs", "option_mask"],
               "rk_alloc_grid": ["cpu_mode", "n_mem", "mem_levels_gb", "mem_mode"],
               "rk_jobs": ["P_bytes", "ref_thr", "layers", "mbatch"],
-              "rk_assign": ["mem_gb", "plan", "thr"]}
+              "rk_assign": ["mem_gb", "plan", "thr"],
+              "rk_sla": ["tenant", "base_thr", "n_tenants", "quota_g", "quota_c"]}
     for s, fs in fields.items():
         for f in fs:
             prog.append(f'printf("{s}.{f} %zu\\n", offsetof({s}, {f}));')
@@ -61,7 +62,7 @@ def test_struct_layouts_match_the_header(rk):
         out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout
     want = dict(line.split() for line in out.strip().splitlines())
     py = {"rk_jobs": rk.rk_jobs, "rk_plan_bounds": rk.rk_plan_bounds, "rk_plan_table": rk.rk_plan_table,
-          "rk_alloc_grid": rk.rk_alloc_grid, "rk_env": rk.rk_env, "rk_cluster": rk.rk_cluster}
+          "rk_alloc_grid": rk.rk_alloc_grid, "rk_env": rk.rk_env, "rk_cluster": rk.rk_cluster, "rk_sla": rk.rk_sla}
     for s, cls in py.items():
         assert C.sizeof(cls) == int(want[s]), s
         for f in fields.get(s, []):

@@ -261,4 +261,38 @@ def what_if(round_index: int, seed: int = BASE_SEED, n_jobs: int = 500) -> Workl
                     Env(), Cluster(G, C, 64 * 2048.0), {"round": r})
 
 
+@dataclass
+class SlaDraws:
+    """Service-level side of a round (Sec. 5.2 / 7.1: guaranteed and best-effort
+    jobs of several tenants).  Positions inside a job's plan space are given as
+    uniform draws in [0,1); whoever holds the plan table maps them to indices."""
+    guaranteed: np.ndarray           # uint32 [J], 0/1
+    tenant: np.ndarray               # uint32 [J]
+    u_seg: np.ndarray                # float64 [J]: position of the requested GPU count among the job's valid counts
+    req_c: np.ndarray                # uint32 [J] requested CPU level
+    req_m: np.ndarray                # uint32 [J] requested memory tier
+    u_plan: np.ndarray               # float64 [J]: position of the original plan among the plans of that GPU count
+    quota_g: np.ndarray              # uint32 [n_tenants]
+    quota_c: np.ndarray              # uint32 [n_tenants]
+
+
+def sla_draws(wl: Workload, seed: int = BASE_SEED, frac_guaranteed: float = 0.3, n_tenants: int = 6,
+              quota_share: float = 1.0) -> SlaDraws:
+    """Requests skewed to small GPU counts (most jobs ask for few GPUs, as in the
+    paper's traces); tenant quotas sum to about quota_share of the cluster."""
+    ids = np.arange(wl.n_jobs)
+    guaranteed = (uniform(seed, 7, 0, ids, 1) < frac_guaranteed).astype(np.uint32)
+    tenant = np.minimum((uniform(seed, 7, 0, ids, 2) * n_tenants).astype(np.uint32), n_tenants - 1)
+    u_seg = uniform(seed, 7, 0, ids, 3) ** 2
+    n_cpu, n_mem = len(wl.grid.cpu_levels), len(wl.grid.mem_levels_gb)
+    req_c = np.minimum((uniform(seed, 7, 0, ids, 4) * n_cpu).astype(np.uint32), n_cpu - 1)
+    req_m = np.minimum((uniform(seed, 7, 0, ids, 5) * n_mem).astype(np.uint32), n_mem - 1)
+    u_plan = uniform(seed, 7, 0, ids, 6)
+    w = 0.5 + uniform(seed, 7, 1, np.arange(n_tenants), 0)
+    w = w / w.sum() * quota_share
+    quota_g = np.floor(w * wl.cluster.G).astype(np.uint32)
+    quota_c = np.floor(w * wl.cluster.C).astype(np.uint32)
+    return SlaDraws(guaranteed, tenant, u_seg, req_c, req_m, u_plan, quota_g, quota_c)
+
+
 CONFIGS = {"tiny": tiny, "paper_scale": paper_scale, "large": large, "stress": stress}
