@@ -123,6 +123,59 @@ def what_if_batch(rk, ctx, dev, n_rounds):
             "batch_ms": float(np.median(batch_ms)), "batch_rounds_per_s": n_rounds / (float(np.median(batch_ms)) * 1e-3)}
 
 
+def sla_round(rk, ctx, dev, wl, jobs, table, bounds, grid, env, cluster, best_plan, n_rows, reps):
+    """Service-level variant of the round on the same workload: 30 % guaranteed
+    jobs of 6 tenants whose quotas sum to half the cluster.  A job's original
+    plan is the best plan of its requested GPU count at the lowest CPU level and
+    memory tier (taken from the library's own output), evaluated at the
+    requested resources by rk_eval_points.  Times of the added calls (HIP
+    events) and the latency of the single-call round."""
+    import torch
+    import workloads
+    J = wl.n_jobs
+    d = workloads.sla_draws(wl, quota_share=0.5)
+    seg_off = np.asarray(table.h_seg_off[:J + 1], dtype=np.int64)
+    seg_g = rk.u32(table.seg_g)
+    ns = seg_off[1:] - seg_off[:-1]
+    s_req = np.minimum((d.u_seg * ns).astype(np.int64), np.maximum(ns - 1, 0))
+    req_g = np.where(ns > 0, seg_g[np.minimum(seg_off[:-1] + s_req, len(seg_g) - 1)], 0).astype(np.uint32)
+    bp = rk.u32(best_plan)
+    plan = bp[np.minimum(n_rows * seg_off[:-1] + s_req, len(bp) - 1)]      # row 0: lowest CPU level and memory tier
+    seg_first = rk.u32(table.seg_first)
+    fallback = (seg_first[np.minimum(seg_off[:-1] + s_req, len(seg_first) - 1)] * 16).astype(np.uint32)
+    plan = np.where((plan == rk.RK_NO_PLAN) | (ns == 0), fallback, plan).astype(np.uint32)
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint32).view(np.int32)).to(dev)
+    base = torch.zeros(J + 4, dtype=torch.float32, device=dev)
+    pj, pp, pc, pm = to_dev(np.arange(J)), to_dev(plan), to_dev(d.req_c), to_dev(d.req_m)
+    sla = rk.Sla(d.guaranteed, d.tenant, d.quota_g, d.quota_c, req_g, d.req_c, d.req_m, base[:J], device=dev)
+    assign = rk.new_assign(J, dev)
+    total = torch.zeros(1, dtype=torch.float32, device=dev)
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    t_points, lat = [], []
+    for i in range(reps + 2):
+        a, b = ev(), ev()
+        a.record()
+        rk.rk_eval_points(ctx, jobs, table.c, grid, env, pj, pp, pc, pm, base[:J])
+        b.record()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rk.rk_schedule_round_sla(ctx, jobs, bounds, grid, env, cluster, sla, assign, total)
+        torch.cuda.synchronize()
+        if i >= 2:
+            t_points.append(a.elapsed_time(b))
+            lat.append((time.perf_counter() - t0) * 1e3)
+    res = rk.assign_to_numpy(assign)
+    gu = d.guaranteed != 0
+    return {"entry": "rk_eval_points (baselines) + rk_schedule_round_sla (host-synchronous)",
+            "guaranteed_jobs": int(gu.sum()), "guaranteed_served": int((gu & (res["g"] > 0)).sum()),
+            "jobs_served": int((res["g"] > 0).sum()), "gpus_granted": int(res["g"].sum()),
+            "eval_points_ms": float(np.mean(t_points)),
+            "round_ms": {"min": float(np.min(lat)), "median": float(np.median(lat)), "max": float(np.max(lat))}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -133,6 +186,7 @@ def main():
     ap.add_argument("--cpu-sample-jobs", type=int, default=1500)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-what-if", action="store_true")
+    ap.add_argument("--no-sla", action="store_true")
     ap.add_argument("--what-if-rounds", type=int, default=256)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (reads 1 GiB, writes 1 GiB) three times, "
@@ -263,6 +317,9 @@ def main():
         "round_latency_ms": {"entry": "rk_schedule_round (fused evaluation, host-synchronous)",
                              "min": float(lat.min()), "median": float(np.median(lat)), "max": float(lat.max())},
     }
+    if not args.no_sla:
+        out["sla_round"] = sla_round(rk, ctx, dev, wl, jobs, table, bounds, grid, env, cluster, best_plan, n_rows,
+                                     max(5, args.steps))
     if not args.no_what_if:
         out["what_if"] = what_if_batch(rk, ctx, dev, args.what_if_rounds)
     if not args.no_cpu_baseline:

@@ -721,81 +721,127 @@ __global__ __launch_bounds__(64) void k_mem_finish(Ctx X, JobState st, rk_assign
 }
 
 // ------------------------------------------------------------------ service-level floors
-// One wavefront per round takes the decisions in job order.  Lanes load 64
-// jobs at a time; the guaranteed ones among them are then decided one after
-// the other with wavefront-uniform arithmetic: the job's demand is broadcast
-// from its lane, the quotas of tenant t live in lane t % 64 (register t / 64),
-// the free capacity in uniform registers.
+// One workgroup per round.  All threads first stage every job's demand in LDS
+// (one word: GPUs, tenant, flags; one word: CPUs), so that the global-memory
+// latency is paid once.  The first wavefront then takes the decisions in job
+// order, 64 jobs at a time: demands that do not fit what is left right now can
+// never fit later and drop out in parallel; the others are decided one after
+// the other with wavefront-uniform arithmetic (the demand is broadcast from its
+// lane, the quotas of tenant t live in lane t % 64, register t / 64, the free
+// capacity in uniform registers).  All threads then write the floors.
+constexpr int FLOOR_THREADS = 1024;
+constexpr uint32_t FL_CAND = 1u << 24, FL_GUAR = 1u << 25, FL_GRANTED = 1u << 31;
+
 __device__ __forceinline__ uint32_t lane_value(uint32_t v, uint32_t lane) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)lane);
 }
 
-__global__ __launch_bounds__(64) void k_floors(Ctx X, JobState st, SlaDev S) {
+__global__ __launch_bounds__(FLOOR_THREADS) void k_floors(Ctx X, JobState st, SlaDev S, uint32_t max_jobs) {
+    extern __shared__ uint32_t lds_floor[];
+    uint32_t *word = lds_floor;                 // GPUs (16 bits) | tenant (8 bits) | flags
+    uint32_t *cpus = lds_floor + max_jobs;
     constexpr uint32_t QREGS = RK_MAX_TENANTS / 64;
-    const uint32_t rnd = blockIdx.x, lane = threadIdx.x;
+    const uint32_t rnd = blockIdx.x, tid = threadIdx.x, lane = tid & 63u;
     uint32_t J0, J1;
     rk_cluster cl;
     round_of(X.R, rnd, J0, J1, cl);
     const GridDev &grid = X.grid;
     const uint32_t nj = J1 - J0;
-    uint32_t qg[QREGS], qc[QREGS];
-#pragma unroll
-    for (uint32_t r = 0; r < QREGS; ++r) {
-        const uint32_t t = r * 64 + lane;
-        qg[r] = t < S.n_tenants ? S.quota_g[t] : 0u;
-        qc[r] = t < S.n_tenants ? S.quota_c[t] : 0u;
-    }
-    uint32_t freeG = cl.G, freeC = cl.C;
-    for (uint32_t base = 0; base < nj; base += 64) {
-        const uint32_t jl = base + lane;
-        bool guar = false, cand = false;
-        int32_t ms = -1;
-        uint32_t mc = 0, g = 0, c = 0, t = 0;
-        if (jl < nj) {
-            const uint32_t j = J0 + jl;
-            guar = S.guaranteed[j] != 0;
-            if (guar) {
-                ms = S.min_seg[j - X.jb];
-                mc = S.min_c[j - X.jb];
-                t = S.tenant[j];
-                const uint32_t s0 = X.tb.seg_off[j], ns = X.tb.seg_off[j + 1] - s0;
-                if (ms >= 0 && (uint32_t)ms < ns && mc < grid.n_cpu && t < S.n_tenants) {
-                    g = X.tb.seg_g[s0 + ms];
-                    const unsigned long long c64 = cpu_cost(grid, mc, g);
-                    cand = c64 <= 0xFFFFFFFFull;           // more can never fit a 32-bit capacity
+
+    for (uint32_t jl = tid; jl < nj; jl += FLOOR_THREADS) {
+        const uint32_t j = J0 + jl;
+        uint32_t w = 0, c = 0;
+        // loaded for every job, so that the loads do not wait for one another
+        const bool guar = S.guaranteed[j] != 0;
+        const int32_t ms = S.min_seg[j - X.jb];
+        const uint32_t mc = S.min_c[j - X.jb], t = S.tenant[j];
+        const uint32_t s0 = X.tb.seg_off[j], ns = X.tb.seg_off[j + 1] - s0;
+        if (guar) {
+            w = FL_GUAR;
+            if (ms >= 0 && (uint32_t)ms < ns && mc < grid.n_cpu && t < S.n_tenants) {
+                const uint32_t g = X.tb.seg_g[s0 + ms];
+                const unsigned long long c64 = cpu_cost(grid, mc, g);
+                if (g <= 0xFFFFu && c64 <= 0xFFFFFFFFull) {          // more can never fit a 32-bit capacity
+                    w |= FL_CAND | g | (t << 16);
                     c = (uint32_t)c64;
                 }
             }
         }
-        bool granted = false;
-        unsigned long long todo = __ballot(cand);
-        while (todo) {
-            const uint32_t turn = (uint32_t)__ffsll((long long)todo) - 1u;
-            todo &= todo - 1;
-            const uint32_t tg = lane_value(g, turn), tc = lane_value(c, turn), tt = lane_value(t, turn);
-            const uint32_t ql = tt & 63u, qr = tt >> 6;
-            uint32_t vg = 0, vc = 0;
-#pragma unroll
-            for (uint32_t r = 0; r < QREGS; ++r) {
-                const uint32_t a = lane_value(qg[r], ql), b = lane_value(qc[r], ql);
-                if (r == qr) { vg = a; vc = b; }
-            }
-            if (tg <= vg && tc <= vc && tg <= freeG && tc <= freeC) {
-                freeG -= tg; freeC -= tc;
-#pragma unroll
-                for (uint32_t r = 0; r < QREGS; ++r)
-                    if (r == qr && lane == ql) { qg[r] -= tg; qc[r] -= tc; }
-                if (lane == turn) granted = true;
-            }
-        }
-        if (jl < nj) {
-            const uint32_t jrel = J0 + jl - X.jb;
-            st.fl_gi[jrel] = granted ? ms : -1;
-            st.fl_ci[jrel] = granted ? mc : 0u;
-            st.waits[jrel] = (guar && !granted) ? 1 : 0;
-        }
+        word[jl] = w;
+        cpus[jl] = c;
     }
-    if (lane == 0) { st.cap0[rnd] = freeG; st.cap0[X.R.n_rounds + rnd] = freeC; }
+    __syncthreads();
+
+    if (tid < 64) {
+        uint32_t qg[QREGS], qc[QREGS];
+#pragma unroll
+        for (uint32_t r = 0; r < QREGS; ++r) {
+            const uint32_t t = r * 64 + lane;
+            qg[r] = t < S.n_tenants ? S.quota_g[t] : 0u;
+            qc[r] = t < S.n_tenants ? S.quota_c[t] : 0u;
+        }
+        const uint32_t n_qregs = (S.n_tenants + 63u) / 64u;
+        uint32_t freeG = cl.G, freeC = cl.C;
+        for (uint32_t base = 0; base < nj; base += 64) {
+            if (freeG == 0) break;                            // every demand asks for at least one GPU
+            const uint32_t jl = base + lane;
+            const uint32_t w = jl < nj ? word[jl] : 0u;
+            const uint32_t c = jl < nj ? cpus[jl] : 0u;
+            const uint32_t g = w & 0xFFFFu, t = (w >> 16) & 0xFFu;
+            bool cand = (w & FL_CAND) != 0;
+            if (__ballot(cand) == 0ull) continue;
+            {   // what does not fit now cannot fit later
+                uint32_t vg = 0, vc = 0;
+#pragma unroll
+                for (uint32_t r = 0; r < QREGS; ++r) {
+                    if (r < n_qregs) {
+                        const uint32_t a = (uint32_t)__shfl((int)qg[r], (int)(t & 63u), 64);
+                        const uint32_t b = (uint32_t)__shfl((int)qc[r], (int)(t & 63u), 64);
+                        if (r == (t >> 6)) { vg = a; vc = b; }
+                    }
+                }
+                cand = cand && g <= vg && c <= vc && g <= freeG && c <= freeC;
+            }
+            bool granted = false;
+            unsigned long long todo = __ballot(cand);
+            while (todo) {
+                const uint32_t turn = (uint32_t)__ffsll((long long)todo) - 1u;
+                todo &= todo - 1;
+                const uint32_t tg = lane_value(g, turn), tc = lane_value(c, turn), tt = lane_value(t, turn);
+                const uint32_t ql = tt & 63u, qr = tt >> 6;
+                uint32_t vg = 0, vc = 0;
+#pragma unroll
+                for (uint32_t r = 0; r < QREGS; ++r) {
+                    const uint32_t a = lane_value(qg[r], ql), b = lane_value(qc[r], ql);
+                    if (r == qr) { vg = a; vc = b; }
+                }
+                if (tg <= vg && tc <= vc && tg <= freeG && tc <= freeC) {
+                    freeG -= tg; freeC -= tc;
+#pragma unroll
+                    for (uint32_t r = 0; r < QREGS; ++r)
+                        if (r == qr && lane == ql) { qg[r] -= tg; qc[r] -= tc; }
+                    if (lane == turn) granted = true;
+                }
+            }
+            if (granted) word[jl] = w | FL_GRANTED;
+            if (__ballot(granted)) {                          // quotas changed: is any GPU quota left at all?
+                bool left = false;
+#pragma unroll
+                for (uint32_t r = 0; r < QREGS; ++r) left = left || qg[r] > 0;
+                if (__ballot(left) == 0ull) break;
+            }
+        }
+        if (lane == 0) { st.cap0[rnd] = freeG; st.cap0[X.R.n_rounds + rnd] = freeC; }
+    }
+    __syncthreads();
+
+    for (uint32_t jl = tid; jl < nj; jl += FLOOR_THREADS) {
+        const uint32_t jrel = J0 + jl - X.jb, w = word[jl];
+        const bool granted = (w & FL_GRANTED) != 0;
+        st.fl_gi[jrel] = granted ? S.min_seg[jrel] : -1;
+        st.fl_ci[jrel] = granted ? S.min_c[jrel] : 0u;
+        st.waits[jrel] = ((w & FL_GUAR) && !granted) ? 1 : 0;
+    }
 }
 
 __global__ void k_zero_u32(uint32_t *p, size_t n) {
@@ -891,6 +937,8 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
         RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_tail<1>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
+        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_floors),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
         raised[ctx->device & 63] = true;
     }
     hipStream_t s = ctx->stream;
@@ -901,7 +949,7 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
         RK_CHECK_LAUNCH(ctx, "k_zero_u32");
     }
     if (sla) {
-        k_floors<<<n_rounds, 64, 0, s>>>(X, st, *sla);
+        k_floors<<<n_rounds, FLOOR_THREADS, (size_t)mj * 8, s>>>(X, st, *sla, mj);
         RK_CHECK_LAUNCH(ctx, "k_floors");
     }
     if ((rc = launch_pass<0>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, lds))) return rc;
