@@ -257,3 +257,6 @@ def policy(ref_thr, table, grid, cluster, best_thr, best_idx, curve_thr, guarant
                               C.byref(total), C.byref(gap))
     assert rc == 0
     return assign, total.value, gap.value
+
+
+from . import fitting  # noqa: E402  (model fitting on top of the functions above)

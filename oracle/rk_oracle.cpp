@@ -125,9 +125,15 @@ void memory_f32(const float *cf, const uint32_t *in, uint32_t d, uint32_t t, uin
  * Pinned by tests/test_oracle_model.py: hand-computed sums with all overlap
  * exponents 1, the single-GPU closed form, volume special cases, V = 0 at
  * size 1, monotonicity in c for offload plans. */
-uint32_t eval_candidate(const float *cf, const uint32_t *in, const ork_bounds *bounds,
-                        const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t z,
-                        uint32_t gc, uint32_t off, uint32_t c, float host_bytes, double *x) {
+/* th = the seven fittable parameters of Table 1 in double, in the order
+ * k_bwd, k_sync, k_opt, k_opt_off, k_off, k_swap, k_const (the model fitting
+ * varies them continuously; the float32 descriptor values convert exactly). */
+enum { TH_BWD, TH_SYNC, TH_OPT, TH_OPT_OFF, TH_OFF, TH_SWAP, TH_CONST, N_TH };
+
+uint32_t eval_candidate_th(const float *cf, const uint32_t *in, const ork_bounds *bounds,
+                           const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t z,
+                           uint32_t gc, uint32_t off, uint32_t c, float host_bytes, const double *th,
+                           double *x) {
     for (int i = 0; i < ORK_N_TERMS; ++i) x[i] = 0.0;
     if (!option_valid(bounds, z, gc, off)) return 1u;
 
@@ -145,7 +151,7 @@ uint32_t eval_candidate(const float *cf, const uint32_t *in, const ork_bounds *b
     const double Tf_mb = (double)cf[T_FWD_SAMPLE] * mu / ((double)t * p);
     const double T_fwd = Tf_mb * (m + p - 1.0);
     /* T_bwd proportional to T_fwd; checkpointing recomputes one forward */
-    const double T_bwd = (double)cf[K_BWD] * T_fwd + (gc ? T_fwd : 0.0);
+    const double T_bwd = th[TH_BWD] * T_fwd + (gc ? T_fwd : 0.0);
 
     /* communication volumes, zero when the corresponding size is 1 */
     const double V_dp = (d > 1) ? P * 2.0 * (d - 1.0) / ((double)d * t * p) : 0.0;
@@ -157,7 +163,7 @@ uint32_t eval_candidate(const float *cf, const uint32_t *in, const ork_bounds *b
 
     /* computation + communication; the accumulation form reduces to the 3D
      * form at a = 1 */
-    const double sync = ork_f_overlap(cf[K_SYNC], T_bwd, T_dp);
+    const double sync = ork_f_overlap(th[TH_SYNC], T_bwd, T_dp);
     double T_cc;
     if (p > 1) T_cc = T_fwd + sync + T_tp + T_pp;
     else       T_cc = a * T_fwd + (a - 1.0) * T_bwd + sync + T_tp;
@@ -166,14 +172,14 @@ uint32_t eval_candidate(const float *cf, const uint32_t *in, const ork_bounds *b
     const double Psi = P / ((double)t * p);
     double T_opt, T_off = 0.0, T_oo;
     if (off) {
-        T_opt = (double)cf[K_OPT_OFF] * Psi / ((double)d * c);
+        T_opt = th[TH_OPT_OFF] * Psi / ((double)d * c);
         T_off = Psi / ((double)d * env->B_pcie);
-        T_oo = ork_f_overlap(cf[K_OFF], T_dp, T_off) + ork_f_overlap(cf[K_SWAP], T_opt, T_off);
+        T_oo = ork_f_overlap(th[TH_OFF], T_dp, T_off) + ork_f_overlap(th[TH_SWAP], T_opt, T_off);
     } else {
-        T_opt = (double)cf[K_OPT] * Psi / ((z >= 1) ? (double)d : 1.0);
+        T_opt = th[TH_OPT] * Psi / ((z >= 1) ? (double)d : 1.0);
         T_oo = T_opt;
     }
-    const double T_iter = T_cc + T_oo + (double)cf[K_CONST];
+    const double T_iter = T_cc + T_oo + th[TH_CONST];
     const double thr = b / T_iter;
 
     float M_gpu, H_host;
@@ -188,6 +194,13 @@ uint32_t eval_candidate(const float *cf, const uint32_t *in, const ork_bounds *b
     x[X_T_OO] = T_oo; x[X_T_ITER] = T_iter; x[X_THR] = thr; x[X_M_GPU] = M_gpu; x[X_H_HOST] = H_host;
     x[X_B_DP] = B_dp; x[X_B_TP] = B_tp; x[X_B_PP] = B_pp;
     return reason;
+}
+
+uint32_t eval_candidate(const float *cf, const uint32_t *in, const ork_bounds *bounds,
+                        const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t z,
+                        uint32_t gc, uint32_t off, uint32_t c, float host_bytes, double *x) {
+    const double th[N_TH] = {cf[K_BWD], cf[K_SYNC], cf[K_OPT], cf[K_OPT_OFF], cf[K_OFF], cf[K_SWAP], cf[K_CONST]};
+    return eval_candidate_th(cf, in, bounds, env, d, t, p, z, gc, off, c, host_bytes, th, x);
 }
 
 uint32_t cpus_of(const ork_grid *grid, uint32_t ci, uint32_t g) {
@@ -295,6 +308,33 @@ uint32_t ork_eval_one(const float *coef17, const uint32_t *ints3, const ork_boun
                       const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t z,
                       uint32_t gc, uint32_t off, uint32_t c, float host_bytes, double *terms) {
     return eval_candidate(coef17, ints3, bounds, env, d, t, p, z, gc, off, c, host_bytes, terms);
+}
+
+/* Predicted throughput of measured runs ("samples") of one model type under
+ * the parameter tuple th (Sec. 4 "Continuous model fitting": the fit compares
+ * Eq. (1) with the collected data).  Sample i = plan (d,t,p, option code) on
+ * cpus[i] CPUs; memory feasibility plays no part (the runs did happen).
+ * Structurally invalid samples (d*mu does not divide b, p does not divide l)
+ * give 0.  Same arithmetic as every other evaluation here. */
+int ork_predict_f64(const float *coef17, const uint32_t *ints3, const ork_env *env, const double *th,
+                    uint32_t n_samples, const uint32_t *d, const uint32_t *t, const uint32_t *p,
+                    const uint32_t *option, const uint32_t *cpus, double *thr, double *t_iter) {
+    const ork_bounds all = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xF, 0x3, 0x3};
+    double x[ORK_N_TERMS];
+    for (uint32_t i = 0; i < n_samples; ++i) {
+        const uint32_t o = option[i], z = o >> 2, gc = (o >> 1) & 1u, off = o & 1u;
+        thr[i] = 0.0;
+        if (t_iter) t_iter[i] = 0.0;
+        if (d[i] == 0 || t[i] == 0 || p[i] == 0 || o > 15u) continue;
+        if (ints3[GBATCH] % (d[i] * ints3[MBATCH]) != 0 || ints3[LAYERS] % p[i] != 0) continue;
+        if (off && cpus[i] == 0) continue;
+        const uint32_t reason = eval_candidate_th(coef17, ints3, &all, env, d[i], t[i], p[i], z, gc, off, cpus[i],
+                                                  INFINITY, th, x);
+        if (reason & 1u) continue;
+        thr[i] = x[X_THR];
+        if (t_iter) t_iter[i] = x[X_T_ITER];
+    }
+    return 0;
 }
 
 /* The plain definition: every candidate evaluated from scratch. */

@@ -79,6 +79,14 @@ uint32_t ork_eval_one(const float *coef17, const uint32_t *ints3, const ork_boun
                       uint32_t z, uint32_t gc, uint32_t off, uint32_t c, float host_bytes,
                       double *terms);
 
+/* Predicted throughput (and iteration time, optional) of n_samples measured
+ * runs of one model type under the seven fittable parameters th (double:
+ * k_bwd, k_sync, k_opt, k_opt_off, k_off, k_swap, k_const); the other
+ * coefficients come from coef17.  0 for structurally invalid samples. */
+int ork_predict_f64(const float *coef17, const uint32_t *ints3, const ork_env *env, const double *th,
+                    uint32_t n_samples, const uint32_t *d, const uint32_t *t, const uint32_t *p,
+                    const uint32_t *option, const uint32_t *cpus, double *thr, double *t_iter_or_null);
+
 /* Every candidate of jobs [job_begin, job_end): thr (0 when infeasible) and
  * optional reason bits, candidate order [job][cpu level][mem tier][plan],
  * plan = triple*16 + (z*4 + gc*2 + off). */

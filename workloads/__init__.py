@@ -295,4 +295,50 @@ def sla_draws(wl: Workload, seed: int = BASE_SEED, frac_guaranteed: float = 0.3,
     return SlaDraws(guaranteed, tenant, u_seg, req_c, req_m, u_plan, quota_g, quota_c)
 
 
+@dataclass
+class FitDraws:
+    """Sampled test runs for the model fitting (Sec. 4 "Continuous model
+    fitting": at least seven runs per model type, three of them with
+    ZeRO-Offload).  Plans are given as positions in [0,1) inside the model's
+    enumerated (d,t,p) list; whoever holds the plan table maps them to triples."""
+    u_triple: np.ndarray             # float64 [J, S]
+    option: np.ndarray               # uint32 [J, S] option code z*4 + gc*2 + off
+    cpus: np.ndarray                 # uint32 [J, S] CPUs of the job in that run
+    noise_z: np.ndarray              # float64 [J, S] standard normal: measured = true * exp(sigma * z)
+    start_factor: np.ndarray         # float64 [J, 7] initial guess = true parameter * factor
+    start_offsets: np.ndarray        # float64 [R, 7] extra starting points, offsets in the log-parameter space
+
+
+def fit_draws(n_models: int, n_samples: int = 16, n_offload: int = 5, n_restarts: int = 4,
+              seed: int = BASE_SEED) -> FitDraws:
+    ids = np.arange(n_models)[:, None]
+    k = np.arange(n_samples)[None, :]
+    u_triple = uniform(seed, 8, 0, ids, 10 + k * 8)
+    z = (uniform(seed, 8, 0, ids, 11 + k * 8) * 4).astype(np.uint32)
+    gc = (uniform(seed, 8, 0, ids, 12 + k * 8) * 2).astype(np.uint32)
+    off = np.broadcast_to(k < n_offload, z.shape).astype(np.uint32)
+    z = np.where(off == 1, 2 + (z & 1), z).astype(np.uint32)             # offload needs stage 2 or 3
+    option = (z * 4 + gc * 2 + off).astype(np.uint32)
+    cpus = np.array([1, 2, 4, 8, 16, 32], np.uint32)[(uniform(seed, 8, 0, ids, 13 + k * 8) * 6).astype(np.int64)]
+    u1, u2 = uniform(seed, 8, 0, ids, 14 + k * 8), uniform(seed, 8, 0, ids, 15 + k * 8)
+    noise_z = np.sqrt(-2.0 * np.log(1.0 - u1)) * np.cos(2.0 * np.pi * u2)
+    par = np.arange(7)[None, :]
+    start_factor = np.exp((uniform(seed, 8, 1, ids, par) * 2.0 - 1.0) * np.log(2.0))
+    r = np.arange(n_restarts)[:, None]
+    a, b = uniform(seed, 8, 2, r, par * 2), uniform(seed, 8, 2, r, par * 2 + 1)
+    start_offsets = 0.7 * np.sqrt(-2.0 * np.log(1.0 - a)) * np.cos(2.0 * np.pi * b)
+    return FitDraws(u_triple, option, cpus, noise_z, start_factor, start_offsets)
+
+
+def fit_sample_triples(draws: FitDraws, triple_off: np.ndarray, triples: np.ndarray):
+    """Map the plan positions of the draws onto a plan table (CSR offsets and
+    [n][3] unpacked triples): returns d, t, p as uint32 [J, S]."""
+    J, S = draws.u_triple.shape
+    t0 = np.asarray(triple_off[:J], np.int64)[:, None]
+    nt = (np.asarray(triple_off[1:J + 1], np.int64) - np.asarray(triple_off[:J], np.int64))[:, None]
+    idx = t0 + np.minimum((draws.u_triple * nt).astype(np.int64), np.maximum(nt - 1, 0))
+    tr = np.asarray(triples)[idx]
+    return tr[..., 0].astype(np.uint32), tr[..., 1].astype(np.uint32), tr[..., 2].astype(np.uint32)
+
+
 CONFIGS = {"tiny": tiny, "paper_scale": paper_scale, "large": large, "stress": stress}
