@@ -309,6 +309,58 @@ int32_t rk_schedule_round_sla(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bo
                               const rk_alloc_grid *grid, const rk_env *env, const rk_cluster *cluster,
                               const rk_sla *sla, rk_assign *assign, float *total);
 
+/* ---- model fitting (Sec. 4 "Continuous model fitting") -------------------- */
+
+#define RK_FIT_PARAMS 7          /* k_bwd, k_sync, k_opt, k_opt_off, k_off, k_swap, k_const */
+#define RK_FIT_MAX_STARTS 8u
+#define RK_FIT_MAX_SAMPLES 64u   /* per model */
+#define RK_FIT_K_MAX 32.0        /* largest overlap exponent the fit may choose */
+
+/* Measured test runs, CSR over the models (= jobs of the job array): run i of
+ * model j used the plan (triple[i], option[i]) on cpus[i] CPUs and reached
+ * thr[i] samples/s.  Arrays are [device]. */
+typedef struct {
+    const uint32_t *sample_off; /* [n_jobs+1] */
+    const uint32_t *triple;     /* packed (d,t,p) as in the plan table */
+    const uint32_t *option;     /* option code z*4 + gc*2 + off */
+    const uint32_t *cpus;       /* CPUs of the job in that run */
+    const float *thr;           /* measured throughput */
+    uint32_t max_samples;       /* largest number of runs of one model, <= RK_FIT_MAX_SAMPLES */
+} rk_samples;
+
+typedef struct {
+    uint32_t max_iter;          /* iterations per starting point */
+    float refit_threshold;      /* a model whose current RMSLE is <= this keeps its parameters */
+    uint32_t n_starts;          /* extra starting points, <= RK_FIT_MAX_STARTS */
+    const double *start_offsets;/* [host] [n_starts][7]: the four scales are multiplied by exp(offset),
+                                   1/k of the three exponents likewise */
+} rk_fit_options;
+
+/* Results, all [device], one entry per model; any pointer may be NULL. */
+typedef struct {
+    float *k_bwd, *k_sync, *k_opt, *k_opt_off, *k_off, *k_swap, *k_const;   /* fitted parameters, float32 */
+    double *theta;              /* [n_jobs][7] the same in float64 */
+    float *rmsle_before;        /* error of the current parameters (projected onto the feasible set) */
+    float *rmsle_after;         /* error of the returned parameters */
+    uint32_t *iters;            /* iterations spent, all starting points together; 0 = left unchanged;
+                                   UINT32_MAX = the model has more runs than max_samples and was left unchanged */
+} rk_fit_result;
+
+/* Fits the seven fittable parameters of every model (Table 1; Sec. 4: they
+ * minimise the root mean squared logarithmic error between Eq. 1 and the
+ * measured runs, at least seven runs per model, three of them offloaded; the
+ * model is updated again when its error exceeds a threshold).
+ *   error   = sqrt(mean((ln(1+pred) - ln(1+thr))^2)) over the model's runs, float64;
+ *             a structurally invalid run predicts 0
+ *   set     = k_bwd, k_opt, k_opt_off, k_const >= 0; k_sync, k_off, k_swap in [1, RK_FIT_K_MAX]
+ *   method  = projected Levenberg-Marquardt in (scales, 1/k) from the job's current
+ *             parameters and from each extra starting point; the lowest error wins,
+ *             the earlier start on ties
+ * The remaining coefficients of the jobs (P_bytes ... t_fwd_sample, layers, batch
+ * sizes) are the known constants of the model.  Memory feasibility plays no part. */
+int32_t rk_fit_models(rk_ctx *ctx, const rk_jobs *jobs, const rk_env *env, const rk_samples *samples,
+                      const rk_fit_options *options, const rk_fit_result *result);
+
 #ifdef __cplusplus
 }
 #endif

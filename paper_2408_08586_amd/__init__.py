@@ -19,10 +19,12 @@ RK_NO_PLAN = 0xFFFFFFFF
 RK_MAX_CPU_LEVELS, RK_MAX_MEM_LEVELS = 64, 16
 RK_MAX_JOBS_PER_ROUND = 12288
 RK_MAX_TENANTS = 256
+RK_FIT_PARAMS, RK_FIT_MAX_STARTS, RK_FIT_MAX_SAMPLES, RK_FIT_K_MAX = 7, 8, 64, 32.0
+FIT_FIELDS = ("k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_const")
 
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
            "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
-           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla")
+           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -64,6 +66,19 @@ class rk_cluster(C.Structure):
 class rk_sla(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("guaranteed", "tenant", "req_g", "req_c", "req_m", "base_thr")] + \
                [("n_tenants", C.c_uint32), ("quota_g", C.c_void_p), ("quota_c", C.c_void_p)]
+
+
+class rk_samples(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("sample_off", "triple", "option", "cpus", "thr")] + [("max_samples", C.c_uint32)]
+
+
+class rk_fit_options(C.Structure):
+    _fields_ = [("max_iter", C.c_uint32), ("refit_threshold", C.c_float), ("n_starts", C.c_uint32),
+                ("start_offsets", C.c_void_p)]
+
+
+class rk_fit_result(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in FIT_FIELDS + ("theta", "rmsle_before", "rmsle_after", "iters")]
 
 
 ASSIGN_DTYPE = np.dtype([("g", np.uint32), ("c", np.uint32), ("mem_gb", np.float32),
@@ -321,6 +336,48 @@ def rk_schedule_round_sla(ctx, jobs: Jobs, bounds, grid, env, cluster, sla: Sla,
     _check(ctx, load_library().rk_schedule_round_sla(ctx, C.byref(jobs.c), C.byref(bounds), C.byref(grid),
                                                      C.byref(env), C.byref(cluster), C.byref(sla.c), _ptr(assign),
                                                      _ptr(total)))
+
+
+def pack_triples(d, t, p) -> np.ndarray:
+    """(d, t, p) -> the packed form of the plan table (t must be 1, 2, 4 or 8)."""
+    d, t, p = (np.asarray(a, dtype=np.uint32) for a in (d, t, p))
+    log2t = np.select([t == 1, t == 2, t == 4, t == 8], [0, 1, 2, 3], default=0).astype(np.uint32)
+    return (d | (log2t << np.uint32(16)) | (p << np.uint32(18))).astype(np.uint32)
+
+
+class Samples:
+    """Measured runs on the device, CSR over the models."""
+
+    def __init__(self, sample_off, triple, option, cpus, thr, device="cuda:0"):
+        import torch
+        dev_u32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint32).view(np.int32)).to(device)
+        sample_off = np.ascontiguousarray(sample_off, dtype=np.uint32)
+        self.sample_off, self.triple, self.option, self.cpus = (dev_u32(a) for a in (sample_off, triple, option, cpus))
+        self.thr = torch.from_numpy(np.ascontiguousarray(thr, dtype=np.float32)).to(device)
+        self.c = rk_samples(self.sample_off.data_ptr(), self.triple.data_ptr(), self.option.data_ptr(),
+                            self.cpus.data_ptr(), self.thr.data_ptr(),
+                            int(np.max(np.diff(sample_off.astype(np.int64)))) if len(sample_off) > 1 else 0)
+
+
+class FitResult:
+    def __init__(self, n_models, device="cuda:0"):
+        import torch
+        self.params = torch.zeros((len(FIT_FIELDS), max(n_models, 1)), dtype=torch.float32, device=device)
+        self.theta = torch.zeros((max(n_models, 1), RK_FIT_PARAMS), dtype=torch.float64, device=device)
+        self.rmsle_before = torch.zeros(max(n_models, 1), dtype=torch.float32, device=device)
+        self.rmsle_after = torch.zeros(max(n_models, 1), dtype=torch.float32, device=device)
+        self.iters = torch.zeros(max(n_models, 1), dtype=torch.int32, device=device)
+        self.c = rk_fit_result(*[self.params[i].data_ptr() for i in range(len(FIT_FIELDS))], self.theta.data_ptr(),
+                               self.rmsle_before.data_ptr(), self.rmsle_after.data_ptr(), self.iters.data_ptr())
+
+
+def rk_fit_models(ctx, jobs: Jobs, env, samples: Samples, result: FitResult, max_iter=100, refit_threshold=0.0,
+                  start_offsets=None):
+    offs = np.zeros((0, RK_FIT_PARAMS)) if start_offsets is None else np.ascontiguousarray(start_offsets, dtype=np.float64)
+    opt = rk_fit_options(int(max_iter), float(refit_threshold), int(offs.shape[0]),
+                         offs.ctypes.data if offs.size else None)
+    _check(ctx, load_library().rk_fit_models(ctx, C.byref(jobs.c), C.byref(env), C.byref(samples.c), C.byref(opt),
+                                             C.byref(result.c)))
 
 
 # ------------------------------------------------------------------ allocation helpers (no arithmetic)
