@@ -176,6 +176,60 @@ def sla_round(rk, ctx, dev, wl, jobs, table, bounds, grid, env, cluster, best_pl
             "round_ms": {"min": float(np.min(lat)), "median": float(np.median(lat)), "max": float(np.max(lat))}}
 
 
+def fit_bench(rk, ctx, dev, wl, env, reps):
+    """Model fitting on the same 10,000 job descriptors, each taken as a model
+    type with 16 measured runs (5 of them offloaded) on at most 64 GPUs.  The
+    "measurements" are the library's own float32 predictions under the true
+    parameters times 5 % log-normal noise; the fit starts from parameters that
+    are off by up to a factor of two, plus 4 perturbed starting points."""
+    import torch
+    import workloads
+    J, S = wl.n_jobs, 16
+    dr = workloads.fit_draws(J, S)
+    jobs_true = rk.Jobs(wl.coef, wl.ints, dev)
+    b64 = rk.make_bounds(workloads.Bounds(g_max=64))
+    table = rk.enumerate_to_table(ctx, jobs_true, b64, dev)
+    triples = table.unpack_triples()
+    d, t, p = workloads.fit_sample_triples(dr, table.h_triple_off, triples)
+    levels = np.array([1, 2, 4, 8, 16, 32], np.uint32)
+    grid = rk.make_grid(workloads.Grid(levels, 0, np.array([1.0e9], np.float32), 0))
+    t0 = np.asarray(table.h_triple_off[:J], np.int64)[:, None]
+    nt = (np.asarray(table.h_triple_off[1:J + 1], np.int64) - t0[:, 0])[:, None]
+    local = np.minimum((dr.u_triple * nt).astype(np.int64), np.maximum(nt - 1, 0))
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint32).reshape(-1).view(np.int32)).to(dev)
+    clean = torch.zeros(J * S + 4, dtype=torch.float32, device=dev)
+    rk.rk_eval_points(ctx, jobs_true, table.c, grid, env, to_dev(np.repeat(np.arange(J), S)),
+                      to_dev(local * 16 + dr.option), to_dev(np.searchsorted(levels, dr.cpus)),
+                      to_dev(np.zeros((J, S))), clean[:J * S])
+    rk.rk_sync(ctx)
+    y = clean[:J * S].cpu().numpy().reshape(J, S) * np.exp(0.05 * dr.noise_z)
+    coef0 = wl.coef.copy()
+    cols = [5, 6, 7, 8, 9, 10, 11]
+    start = coef0[:, cols].astype(np.float64) * dr.start_factor
+    start[:, [1, 4, 5]] = np.clip(start[:, [1, 4, 5]], 1.0, rk.RK_FIT_K_MAX)
+    coef0[:, cols] = start.astype(np.float32)
+    jobs0 = rk.Jobs(coef0, wl.ints, dev)
+    smp = rk.Samples(np.arange(J + 1) * S, rk.pack_triples(d, t, p).reshape(-1), dr.option.reshape(-1),
+                     dr.cpus.reshape(-1), y.reshape(-1), device=dev)
+    res = rk.FitResult(J, dev)
+    ms = []
+    for i in range(reps + 1):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        rk.rk_fit_models(ctx, jobs0, env, smp, res, max_iter=100, start_offsets=dr.start_offsets)
+        b.record()
+        torch.cuda.synchronize()
+        if i:
+            ms.append(a.elapsed_time(b))
+    before, after = res.rmsle_before.cpu().numpy()[:J], res.rmsle_after.cpu().numpy()[:J]
+    iters = res.iters.cpu().numpy()[:J].astype(np.int64)
+    return {"entry": "rk_fit_models", "models": J, "runs_per_model": S, "starting_points": 1 + len(dr.start_offsets),
+            "dtype": "f64", "ms": float(np.median(ms)), "models_per_s": J / (float(np.median(ms)) * 1e-3),
+            "iterations_per_model": float(iters.mean()), "model_evaluations_per_s": float(iters.sum()) * S / (float(np.median(ms)) * 1e-3),
+            "rmsle_before_median": float(np.median(before)), "rmsle_after_median": float(np.median(after)),
+            "noise_sigma": 0.05}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -187,6 +241,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-what-if", action="store_true")
     ap.add_argument("--no-sla", action="store_true")
+    ap.add_argument("--no-fit", action="store_true")
     ap.add_argument("--what-if-rounds", type=int, default=256)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (reads 1 GiB, writes 1 GiB) three times, "
@@ -320,6 +375,8 @@ def main():
     if not args.no_sla:
         out["sla_round"] = sla_round(rk, ctx, dev, wl, jobs, table, bounds, grid, env, cluster, best_plan, n_rows,
                                      max(5, args.steps))
+    if not args.no_fit:
+        out["fit"] = fit_bench(rk, ctx, dev, wl, env, 3)
     if not args.no_what_if:
         out["what_if"] = what_if_batch(rk, ctx, dev, args.what_if_rounds)
     if not args.no_cpu_baseline:

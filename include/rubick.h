@@ -354,8 +354,9 @@ typedef struct {
  *             a structurally invalid run predicts 0
  *   set     = k_bwd, k_opt, k_opt_off, k_const >= 0; k_sync, k_off, k_swap in [1, RK_FIT_K_MAX]
  *   method  = projected Levenberg-Marquardt in (scales, 1/k) from the job's current
- *             parameters and from each extra starting point; the lowest error wins,
- *             the earlier start on ties
+ *             parameters and from each extra starting point; then, twice over the three
+ *             exponents, one that sits on a bound is moved to k = 1/0.3 and the descent
+ *             repeated from the best point; the lowest error wins, the earlier on ties
  * The remaining coefficients of the jobs (P_bytes ... t_fwd_sample, layers, batch
  * sizes) are the known constants of the model.  Memory feasibility plays no part. */
 int32_t rk_fit_models(rk_ctx *ctx, const rk_jobs *jobs, const rk_env *env, const rk_samples *samples,
