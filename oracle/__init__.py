@@ -260,3 +260,26 @@ def policy(ref_thr, table, grid, cluster, best_thr, best_idx, curve_thr, guarant
 
 
 from . import fitting  # noqa: E402  (model fitting on top of the functions above)
+
+
+def frozen_round(ref_thr, table, grid, cluster, best_thr, best_idx, curve_thr, state, cur_seg, cur_c):
+    """Greedy round with per-job state: 0 takes part, 1 takes no part, 2 keeps (cur_seg, cur_c)."""
+    gh = _GridHolder(grid)
+    J = table.n_jobs
+    f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    ref_thr, best_thr, curve_thr = f(ref_thr), f(best_thr), f(curve_thr)
+    best_idx = np.ascontiguousarray(best_idx, dtype=np.uint32)
+    state = np.ascontiguousarray(state, dtype=np.uint8)
+    cur_seg = np.ascontiguousarray(cur_seg, dtype=np.int32)
+    cur_c = np.ascontiguousarray(cur_c, dtype=np.uint32)
+    assign = np.zeros(J, ASSIGN_DTYPE)
+    total, gap = C.c_double(0), C.c_double(0)
+    rc = lib().ork_frozen_round_f32(C.c_uint32(J), _p(ref_thr), C.byref(table.c), C.byref(gh.c), C.c_uint32(cluster.G),
+                                    C.c_uint32(cluster.C), C.c_float(cluster.host_mem_gb), _p(best_thr), _p(best_idx),
+                                    _p(curve_thr), _p(state), _p(cur_seg), _p(cur_c), _p(assign), C.byref(total),
+                                    C.byref(gap))
+    assert rc == 0
+    return assign, total.value, gap.value
+
+
+from . import simulator  # noqa: E402

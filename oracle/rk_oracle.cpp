@@ -203,6 +203,12 @@ uint32_t eval_candidate(const float *cf, const uint32_t *in, const ork_bounds *b
     return eval_candidate_th(cf, in, bounds, env, d, t, p, z, gc, off, c, host_bytes, th, x);
 }
 
+int greedy_from(uint32_t n_jobs, const float *ref_thr, const ork_table *tb, const ork_grid *grid,
+                uint64_t freeG, uint64_t freeC, float host_mem_gb, const float *best_thr,
+                const uint32_t *best_plan, const float *curve_thr, std::vector<int64_t> &gi,
+                std::vector<uint32_t> &ci, const std::vector<uint8_t> &waits, ork_assign *assign,
+                double *total, double *min_gap);
+
 uint32_t cpus_of(const ork_grid *grid, uint32_t ci, uint32_t g) {
     return grid->cpu_mode ? grid->cpu_levels[ci] * g : grid->cpu_levels[ci];
 }
@@ -487,13 +493,10 @@ int ork_policy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb,
                    const uint32_t *guaranteed, const uint32_t *tenant, const int32_t *min_seg,
                    const uint32_t *min_c, uint32_t n_tenants, const uint32_t *quota_g,
                    const uint32_t *quota_c, ork_assign *assign, double *total, double *min_gap) {
-    const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
-    const uint32_t m_top = grid->n_mem - 1;
     std::vector<int64_t> gi(n_jobs, -1);
     std::vector<uint32_t> ci(n_jobs, 0);
     std::vector<uint8_t> waits(n_jobs, 0);
     uint64_t freeG = G, freeC = C;
-    double gap_min = INFINITY;
     if (guaranteed) {                                       /* privileged phase */
         std::vector<uint64_t> qg(quota_g, quota_g + n_tenants), qc(quota_c, quota_c + n_tenants);
         for (uint32_t j = 0; j < n_jobs; ++j) {
@@ -509,6 +512,54 @@ int ork_policy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb,
             }
         }
     }
+    return greedy_from(n_jobs, ref_thr, tb, grid, freeG, freeC, host_mem_gb, best_thr, best_plan, curve_thr,
+                       gi, ci, waits, assign, total, min_gap);
+}
+
+/* A round in which some jobs take no part (state 1) and some keep what they
+ * hold (state 2: frozen at segment cur_seg and CPU level cur_c, e.g. because a
+ * reconfiguration would cost them too much, Sec. 5.2 "Incorporating
+ * reconfiguration penalty").  Frozen jobs are charged first; if they hold more
+ * than the cluster has, nothing is left for the others.  Everything else is the
+ * greedy.  Pinned: hand cases; all-normal equals the plain greedy. */
+int ork_frozen_round_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb,
+                         const ork_grid *grid, uint32_t G, uint32_t C, float host_mem_gb,
+                         const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                         const uint8_t *state, const int32_t *cur_seg, const uint32_t *cur_c,
+                         ork_assign *assign, double *total, double *min_gap) {
+    std::vector<int64_t> gi(n_jobs, -1);
+    std::vector<uint32_t> ci(n_jobs, 0);
+    std::vector<uint8_t> skip(n_jobs, 0);
+    uint64_t heldG = 0, heldC = 0;
+    for (uint32_t j = 0; j < n_jobs; ++j) {
+        skip[j] = state[j];
+        if (state[j] == 2) {
+            const uint64_t ns = tb->seg_off[j + 1] - tb->seg_off[j];
+            if (cur_seg[j] < 0 || (uint64_t)cur_seg[j] >= ns || cur_c[j] >= grid->n_cpu) { skip[j] = 1; continue; }
+            gi[j] = cur_seg[j]; ci[j] = cur_c[j];
+            const uint32_t g = tb->seg_g[tb->seg_off[j] + cur_seg[j]];
+            heldG += g; heldC += cpus_of(grid, cur_c[j], g);
+        }
+    }
+    const uint64_t freeG = heldG < G ? G - heldG : 0, freeC = heldC < C ? C - heldC : 0;
+    return greedy_from(n_jobs, ref_thr, tb, grid, freeG, freeC, host_mem_gb, best_thr, best_plan, curve_thr,
+                       gi, ci, skip, assign, total, min_gap);
+}
+
+}  // extern "C"
+
+namespace {
+
+/* The greedy proper, from a starting state: gi/ci = what every job holds
+ * already, skip != 0 = the job neither gains GPUs nor CPUs in this round. */
+int greedy_from(uint32_t n_jobs, const float *ref_thr, const ork_table *tb, const ork_grid *grid,
+                uint64_t freeG, uint64_t freeC, float host_mem_gb, const float *best_thr,
+                const uint32_t *best_plan, const float *curve_thr, std::vector<int64_t> &gi,
+                std::vector<uint32_t> &ci, const std::vector<uint8_t> &waits, ork_assign *assign,
+                double *total, double *min_gap) {
+    const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    const uint32_t m_top = grid->n_mem - 1;
+    double gap_min = INFINITY;
 
     auto ns_of = [&](uint32_t j) { return (uint64_t)(tb->seg_off[j + 1] - tb->seg_off[j]); };
     auto g_of = [&](uint32_t j, int64_t s) -> uint64_t { return s < 0 ? 0 : tb->seg_g[tb->seg_off[j] + s]; };
@@ -551,7 +602,7 @@ int ork_policy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb,
     for (;;) {
         float top = 0.0f, second = 0.0f; uint32_t tj = 0; int64_t tc = -1;
         for (uint32_t j = 0; j < n_jobs; ++j) {
-            if (gi[j] < 0) continue;
+            if (gi[j] < 0 || waits[j]) continue;
             const float cur = at(best_thr, j, ci[j], m_top, gi[j]);
             for (uint32_t c = ci[j] + 1; c < grid->n_cpu; ++c) {
                 const uint64_t dc = cpu_cost(j, c, gi[j]) - cpu_cost(j, ci[j], gi[j]);
@@ -598,4 +649,4 @@ int ork_policy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb,
     return 0;
 }
 
-}  // extern "C"
+}  // namespace

@@ -129,6 +129,14 @@ int ork_policy_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *table
                    const uint32_t *min_c, uint32_t n_tenants, const uint32_t *quota_g,
                    const uint32_t *quota_c, ork_assign *assign, double *total, double *min_gap);
 
+/* A round with per-job state: 0 takes part, 1 takes no part, 2 keeps the
+ * allocation (cur_seg, cur_c) it holds and is charged for it first. */
+int ork_frozen_round_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *table,
+                         const ork_grid *grid, uint32_t G, uint32_t C, float host_mem_gb,
+                         const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                         const uint8_t *state, const int32_t *cur_seg, const uint32_t *cur_c,
+                         ork_assign *assign, double *total, double *min_gap);
+
 #ifdef __cplusplus
 }
 #endif

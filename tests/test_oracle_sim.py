@@ -1,0 +1,137 @@
+"""Pins for the oracle's rounds with frozen jobs and its discrete-time
+simulation (paper Sec. 5.2 "Incorporating reconfiguration penalty": reconfigure
+only if (T - N*delta)/T > 0.97; Sec. 7.4: discrete-time simulator)."""
+import numpy as np
+import pytest
+
+import workloads
+from test_oracle_policy import one_job_table  # noqa: F401  (same tiny tables)
+
+
+def tiny_round(orc, curves, state, cur_seg, cur_c, G, C=10 ** 6, host=1e9, n_cpu=2):
+    """curves[j][s] = best throughput of job j at 1, 2, 4, 8 GPUs (every CPU level alike)."""
+    J = len(curves)
+    ints = np.tile(np.array([[8, 8, 1]], np.uint32), (J, 1))
+    tb = orc.enumerate_plans(ints, workloads.Bounds(g_max=8))
+    grid = workloads.Grid(np.arange(1, n_cpu + 1, dtype=np.uint32), 0, np.array([1.0], np.float32), 0)
+    bt = np.zeros((J, n_cpu, 1, 4), np.float32)
+    for j, cv in enumerate(curves):
+        bt[j, :, 0, :] = np.asarray(cv, np.float32)[None, :]
+    bt = bt.reshape(-1)
+    bp = np.arange(bt.size, dtype=np.uint32)
+    ct, _, _ = orc.curves(tb, grid, bt, bp)
+    ref = np.ones(J, np.float32)
+    return orc.frozen_round(ref, tb, grid, workloads.Cluster(G, C, host), bt, bp, ct, state, cur_seg, cur_c), (tb, grid, bt, bp, ct, ref)
+
+
+def test_frozen_round_hand_cases(orc):
+    steep, flat = [4.0, 8.0, 12.0, 17.0], [1.0, 1.1, 1.2, 1.3]
+    # all jobs normal: the greedy (the steep job takes everything)
+    (a, total, _), _ = tiny_round(orc, [flat, steep], [0, 0], [-1, -1], [0, 0], G=8)
+    assert a["g"].tolist() == [0, 8]
+    # the flat job is frozen at 4 GPUs, CPU level 1: it keeps exactly that, the steep job gets the rest
+    (a, total, _), _ = tiny_round(orc, [flat, steep], [2, 0], [2, -1], [1, 0], G=8)
+    assert a["g"].tolist() == [4, 4] and a["c"][0] == 2
+    assert total == pytest.approx(1.2 + 12.0)
+    # a frozen job does not grow even when resources are plentiful, nor gain CPUs
+    (a, _, _), _ = tiny_round(orc, [steep, flat], [2, 0], [0, -1], [0, 0], G=64)
+    assert a["g"].tolist() == [1, 8] and a["c"][0] == 1
+    # a job that takes no part gets nothing, whatever its slope
+    (a, _, _), _ = tiny_round(orc, [steep, flat], [1, 0], [-1, -1], [0, 0], G=8)
+    assert a["g"].tolist() == [0, 8]
+    # frozen jobs holding more than the cluster has: nothing is left for the others
+    (a, _, _), _ = tiny_round(orc, [flat, flat, steep], [2, 2, 0], [3, 2, -1], [0, 0, 0], G=10)
+    assert a["g"].tolist() == [8, 4, 0]
+    # CPUs of frozen jobs are charged: 2 CPUs in all, the frozen job holds both
+    (a, _, _), _ = tiny_round(orc, [flat, steep], [2, 0], [0, -1], [1, 0], G=8, C=2)
+    assert a["g"].tolist() == [1, 0]
+
+
+def test_frozen_round_without_states_is_the_plain_greedy(orc):
+    wl = workloads.paper_scale()
+    r = orc.schedule_round(wl, n_threads=4)
+    J = wl.n_jobs
+    a, total, gap = orc.frozen_round(wl.coef[:, 16], r["table"], wl.grid, wl.cluster, r["best_thr"], r["best_plan"],
+                                     r["curve_thr"], np.zeros(J, np.uint8), np.full(J, -1, np.int32), np.zeros(J, np.uint32))
+    assert np.array_equal(a, r["assign"]) and total == r["total"] and gap == r["min_gap"]
+
+
+def lone_job(orc, work, arrival, delta=50.0, dt=60.0, n_ticks=40):
+    curve = [2.0, 3.5, 6.0, 8.0]
+    _, (tb, grid, bt, bp, ct, ref) = tiny_round(orc, [curve], [0], [-1], [0], G=4)
+    return orc.simulator.simulate(ref, tb, grid, workloads.Cluster(4, 100, 1e9), bt, bp, ct, [arrival], [work], [delta], dt,
+                                  n_ticks)
+
+
+def test_lone_job_finishes_at_the_closed_form_time(orc):
+    # arrives at 130 s: first seen by the tick at 180 s; 4 GPUs give 6 samples/s
+    out = lone_job(orc, work=6.0 * 1000.0, arrival=130.0)
+    assert out["finish"][0] == pytest.approx(180.0 + 1000.0, rel=1e-15)
+    assert out["n_reconf"][0] == 0 and out["progress"][0] == 6000.0
+    assert out["held"][0] == 60.0 * 17                       # ticks at 180 ... 1140 s
+    assert out["gpus_in_use"].tolist()[:3] == [0, 0, 0] and set(out["gpus_in_use"][3:20]) == {4} and out["gpus_in_use"][20] == 0
+    # arrival exactly on a tick counts for that tick; work that ends exactly with a tick
+    out = lone_job(orc, work=6.0 * 120.0, arrival=120.0)
+    assert out["finish"][0] == 240.0
+    # never finishing inside the horizon
+    out = lone_job(orc, work=1e9, arrival=0.0)
+    assert out["finish"][0] == -1.0 and out["progress"][0] == pytest.approx(6.0 * 60.0 * 40)
+
+
+def two_jobs(orc, gate, delta_a, n_ticks=60, trace=True):
+    """Job A alone takes all 8 GPUs; job B arrives at 300 s and is worth half of them."""
+    a_curve, b_curve = [1.0, 2.0, 4.0, 6.0], [1.5, 3.0, 5.0, 5.5]
+    _, (tb, grid, bt, bp, ct, ref) = tiny_round(orc, [a_curve, b_curve], [0, 0], [-1, -1], [0, 0], G=8)
+    out = orc.simulator.simulate(ref, tb, grid, workloads.Cluster(8, 100, 1e9), bt, bp, ct, [0.0, 300.0], [1e9, 1e9],
+                                 [delta_a, 10.0], 60.0, n_ticks, gate=gate, trace=trace)
+    return out
+
+
+def test_gate_freezes_until_the_reconfiguration_is_cheap_enough(orc):
+    # without B, A holds 8 GPUs; with B the greedy gives both 4 (A: 4, B: 5 beats A: 6, B: 0 ...)
+    out = two_jobs(orc, gate=0.97, delta_a=30.0)
+    g_a = [int(h["g"][0]) for h in out["history"]]
+    g_b = [int(h["g"][1]) for h in out["history"]]
+    # A may move once T - delta > 0.97 T, i.e. T > 1000 s: T = 1020 s after 17 ticks, seen by the tick with k = 17
+    first_change = next(k for k, g in enumerate(g_a) if g != 8)
+    assert first_change == 17
+    assert g_a[:17] == [8] * 17 and g_a[17] == 4
+    assert g_b[:5] == [0] * 5 and g_b[5:17] == [0] * 12 and g_b[17] == 4      # B waits while A is frozen on all GPUs
+    assert out["n_reconf"][0] == 1 and out["n_reconf"][1] == 0
+    assert out["frozen"][:17].tolist() == [0] + [1] * 16                      # A is not running at the very first tick
+    # the reconfiguration costs A 30 s of the tick in which it happens
+    assert out["progress"][0] == pytest.approx(6.0 * 60 * 17 + 4.0 * 30 + 4.0 * 60 * (60 - 18))
+    # a gate of 1 can never be passed, a gate of minus infinity always
+    assert two_jobs(orc, gate=1.0, delta_a=30.0)["n_reconf"].tolist() == [0, 0]
+    free = two_jobs(orc, gate=-np.inf, delta_a=30.0)
+    assert [int(h["g"][0]) for h in free["history"]][:7] == [8] * 5 + [4, 4] and free["frozen"].sum() == 0
+    # a checkpoint-resume cost longer than a tick is paid over several ticks
+    slow = two_jobs(orc, gate=-np.inf, delta_a=150.0)
+    assert slow["progress"][0] == pytest.approx(6.0 * 60 * 5 + 4.0 * 30 + 4.0 * 60 * (60 - 8))
+
+
+def test_simulation_conserves_what_it_should(orc):
+    wl = workloads.paper_scale()
+    r = orc.schedule_round(wl, n_threads=4)
+    tr = workloads.trace(wl.n_jobs, horizon_s=2 * 3600.0)
+    work = workloads.job_lengths_s(tr.u_duration) * wl.coef[:, 16] * 4
+    args = (wl.coef[:, 16], r["table"], wl.grid, wl.cluster, r["best_thr"], r["best_plan"], r["curve_thr"], tr.arrival, work,
+            tr.delta, 60.0, 300)
+    out = orc.simulator.simulate(*args, trace=True)
+    fin = out["finish"] >= 0
+    assert 10 < fin.sum() < wl.n_jobs
+    assert np.all(out["gpus_in_use"] <= wl.cluster.G)
+    assert np.all(out["finish"][fin] > tr.arrival[fin]) and np.all(out["progress"][fin] == work[fin])
+    assert np.all(out["progress"][~fin] < work[~fin])
+    assert out["n_reconf"].sum() > 0 and out["frozen"].sum() > 0
+    # no job runs before it arrives or after it has finished
+    for k, h in enumerate(out["history"]):
+        t = 60.0 * k
+        assert np.all(h["g"][tr.arrival > t] == 0)
+        assert np.all(h["g"][fin & (out["finish"] <= t)] == 0)
+    # progress never exceeds the best throughput times the time held
+    best = np.array([r["best_thr"][20 * 0:].max()])       # a loose global bound
+    assert np.all(out["progress"] <= best * out["held"] + 1e-6)
+    # a stricter gate can only reduce reconfigurations to zero; with no gate none is frozen
+    assert orc.simulator.simulate(*args, gate=1.0)["n_reconf"].sum() == 0
+    assert orc.simulator.simulate(*args, gate=-np.inf)["frozen"].sum() == 0

@@ -341,4 +341,28 @@ def fit_sample_triples(draws: FitDraws, triple_off: np.ndarray, triples: np.ndar
     return tr[..., 0].astype(np.uint32), tr[..., 1].astype(np.uint32), tr[..., 2].astype(np.uint32)
 
 
+@dataclass
+class Trace:
+    """Arrival trace for the cluster simulation (Sec. 7.1 / 7.4: a busy 12-hour
+    window of a production trace, down-sampled to the cluster's size)."""
+    arrival: np.ndarray              # float64 [J] seconds, ascending
+    u_duration: np.ndarray           # float64 [J] in [0,1): position of the job's length in the length distribution
+    delta: np.ndarray                # float64 [J] checkpoint-resume cost, seconds
+
+
+def trace(n_jobs: int, horizon_s: float = 12 * 3600.0, seed: int = BASE_SEED) -> Trace:
+    """Poisson arrivals over the horizon; lengths are mapped by the caller
+    (heavy-tailed: most jobs short, a few long); checkpoint-resume 30-120 s."""
+    ids = np.arange(n_jobs)
+    gaps = -np.log(1.0 - uniform(seed, 9, 0, ids, 0))
+    arrival = np.cumsum(gaps)
+    arrival = arrival / arrival[-1] * horizon_s * (1.0 - 1.0 / max(n_jobs, 1))
+    return Trace(arrival, uniform(seed, 9, 0, ids, 1), 30.0 + 90.0 * uniform(seed, 9, 0, ids, 2))
+
+
+def job_lengths_s(u: np.ndarray) -> np.ndarray:
+    """Job length in seconds on its reference allocation: log-uniform from 5 minutes to 8 hours."""
+    return 300.0 * np.exp(u * np.log(8 * 3600.0 / 300.0))
+
+
 CONFIGS = {"tiny": tiny, "paper_scale": paper_scale, "large": large, "stress": stress}
