@@ -362,6 +362,55 @@ typedef struct {
 int32_t rk_fit_models(rk_ctx *ctx, const rk_jobs *jobs, const rk_env *env, const rk_samples *samples,
                       const rk_fit_options *options, const rk_fit_result *result);
 
+/* ---- reconfiguration penalty and discrete-time simulation (Sec. 5.2, 7.4) -- */
+
+/* Arrival trace, [device] arrays of one entry per job of the plan table. */
+typedef struct {
+    const double *arrival;      /* seconds */
+    const double *work;         /* samples to train */
+    const double *delta;        /* checkpoint-resume cost of one reconfiguration, seconds */
+} rk_trace;
+
+typedef struct {
+    double dt;                  /* tick length, seconds, > 0 */
+    uint32_t n_ticks;
+    double gate;                /* threshold of the reconfiguration rule (the paper uses 0.97) */
+} rk_sim_options;
+
+/* Results, all [device]; per job: finish (seconds, -1 if unfinished), n_reconf,
+ * progress (samples), held (seconds with resources); per tick: GPUs in use,
+ * total normalised throughput, number of frozen jobs.  Any pointer may be NULL. */
+typedef struct {
+    double *finish;
+    uint32_t *n_reconf;
+    double *progress;
+    double *held;
+    uint32_t *gpus_in_use;      /* [n_ticks] */
+    float *totals;              /* [n_ticks] */
+    uint32_t *frozen;           /* [n_ticks] */
+} rk_sim_result;
+
+/* Discrete-time simulation of the whole job set on cached curves (Sec. 5.2: the
+ * curves do not depend on the cluster's state and can be computed once; "a job
+ * is reconfigured only if (T - N*delta)/T exceeds a threshold"; Sec. 7.4: a
+ * discrete-time simulator).  The arrays best_thr, best_plan, curve_thr are in
+ * segment layout of all jobs (as rk_job_curves writes them for [0, n_jobs)).
+ * Every tick k, at t = k*dt:
+ *   - a job is active when arrival <= t and it has not finished;
+ *   - an active job holding GPUs is frozen unless T - (N+1)*delta > gate*T, with
+ *     T the seconds it has held resources and N its reconfigurations so far;
+ *   - one greedy round (as rk_allocate): inactive jobs take no part, frozen jobs
+ *     keep their GPUs and CPUs and are charged for them first;
+ *   - a job that keeps running with different (GPUs, CPUs, plan) is reconfigured:
+ *     N += 1 and delta seconds are owed; starting from or stopping at zero is free;
+ *   - a job holding GPUs pays owed seconds out of the tick, then trains at the
+ *     round's throughput; it finishes inside the tick at t + paid + remaining/thr.
+ * Times and progress are float64.  All ticks are enqueued without waiting. */
+int32_t rk_simulate(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                    const rk_alloc_grid *grid, const rk_cluster *cluster,
+                    const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                    const rk_trace *trace, const rk_sim_options *options, const rk_sim_result *result);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ FIT_FIELDS = ("k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_con
 
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
            "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
-           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models")
+           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -79,6 +79,18 @@ class rk_fit_options(C.Structure):
 
 class rk_fit_result(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in FIT_FIELDS + ("theta", "rmsle_before", "rmsle_after", "iters")]
+
+
+class rk_trace(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("arrival", "work", "delta")]
+
+
+class rk_sim_options(C.Structure):
+    _fields_ = [("dt", C.c_double), ("n_ticks", C.c_uint32), ("gate", C.c_double)]
+
+
+class rk_sim_result(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("finish", "n_reconf", "progress", "held", "gpus_in_use", "totals", "frozen")]
 
 
 ASSIGN_DTYPE = np.dtype([("g", np.uint32), ("c", np.uint32), ("mem_gb", np.float32),
@@ -378,6 +390,31 @@ def rk_fit_models(ctx, jobs: Jobs, env, samples: Samples, result: FitResult, max
                          offs.ctypes.data if offs.size else None)
     _check(ctx, load_library().rk_fit_models(ctx, C.byref(jobs.c), C.byref(env), C.byref(samples.c), C.byref(opt),
                                              C.byref(result.c)))
+
+
+class SimResult:
+    def __init__(self, n_jobs, n_ticks, device="cuda:0"):
+        import torch
+        nj, nt = max(n_jobs, 1), max(n_ticks, 1)
+        self.finish = torch.zeros(nj, dtype=torch.float64, device=device)
+        self.n_reconf = torch.zeros(nj, dtype=torch.int32, device=device)
+        self.progress = torch.zeros(nj, dtype=torch.float64, device=device)
+        self.held = torch.zeros(nj, dtype=torch.float64, device=device)
+        self.gpus_in_use = torch.zeros(nt, dtype=torch.int32, device=device)
+        self.totals = torch.zeros(nt, dtype=torch.float32, device=device)
+        self.frozen = torch.zeros(nt, dtype=torch.int32, device=device)
+        self.c = rk_sim_result(*[getattr(self, n).data_ptr() for n in
+                                 ("finish", "n_reconf", "progress", "held", "gpus_in_use", "totals", "frozen")])
+
+
+def rk_simulate(ctx, ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, arrival, work, delta, dt, n_ticks,
+                gate, result: SimResult):
+    """arrival, work, delta: float64 device tensors."""
+    tr = rk_trace(arrival.data_ptr(), work.data_ptr(), delta.data_ptr())
+    opt = rk_sim_options(float(dt), int(n_ticks), float(gate))
+    _check(ctx, load_library().rk_simulate(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.byref(cluster),
+                                           _ptr(best_thr), _ptr(best_plan), _ptr(curve_thr), C.byref(tr), C.byref(opt),
+                                           C.byref(result.c)))
 
 
 # ------------------------------------------------------------------ allocation helpers (no arithmetic)

@@ -66,20 +66,21 @@ struct JobState {            // per job of the call, between the kernels
     unsigned long long *free_g, *free_c;   // per round: capacity left (after apply; after the tail)
     double *partial;         // per round and block of k_mem_wish: {sum of wish GiB, sum of thr/ref}
     uint32_t blocks_per_round;
-    // service-level floors, all null without them: the state a job starts from
-    // (segment index or -1, CPU level), whether it sits the round out, and per
-    // round the capacity left after the floors ([free G | free C])
+    // floors, all null without them: the state a job starts from (segment index
+    // or -1, CPU level), whether it takes part (RK_JOB_NORMAL), sits the round
+    // out (RK_JOB_OUT) or keeps exactly its floor (RK_JOB_FROZEN), and per round
+    // the capacity left after the floors ([free G | free C])
     int32_t *fl_gi;
     uint32_t *fl_ci;
     uint8_t *waits;
     unsigned long long *cap0;
 };
 
-struct Floor { int32_t gi; uint32_t ci; bool waits; };
+struct Floor { int32_t gi; uint32_t ci; uint32_t state; };
 
 __device__ __forceinline__ Floor floor_of(const JobState &st, uint32_t jrel) {
-    Floor f = {-1, 0u, false};
-    if (st.fl_gi) { f.gi = st.fl_gi[jrel]; f.ci = st.fl_ci[jrel]; f.waits = st.waits[jrel] != 0; }
+    Floor f = {-1, 0u, RK_JOB_NORMAL};
+    if (st.fl_gi) { f.gi = st.fl_gi[jrel]; f.ci = st.fl_ci[jrel]; f.state = st.waits[jrel]; }
     return f;
 }
 
@@ -184,7 +185,7 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
         unsigned long long startG, startC;
         pass_caps<0>(X.R, cl, st, rnd, startG, startC);
         c_fixed = fl.ci;
-        npts = fl.waits ? 0u : ns;
+        npts = fl.state != RK_JOB_NORMAL ? 0u : ns;
         cur_i = fl.gi;
         cost_cur = fl.gi < 0 ? 0ull : (unsigned long long)X.tb.seg_g[s0 + fl.gi];
         cur = fl.gi < 0 ? 0.f : vals[jbase + (uint64_t)(c_fixed * n_mem + n_mem - 1) * ns + fl.gi];
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
         cap_c = startC + (fl.gi < 0 ? 0ull : cpu_cost(grid, c_fixed, (uint32_t)cost_cur));
     } else {
         gi = st.gi[jrel];
-        npts = gi < 0 ? 0u : grid.n_cpu;
+        npts = (gi < 0 || (st.waits && st.waits[jrel] != RK_JOB_NORMAL)) ? 0u : grid.n_cpu;
         g_fixed = gi < 0 ? 0u : st.g[jrel];
         cur_i = (int32_t)st.ci[jrel];
         cost_cur = cpu_cost(grid, (uint32_t)cur_i, g_fixed);
@@ -428,7 +429,7 @@ __global__ __launch_bounds__(JOB_THREADS) void k_apply(Ctx X, JobState st, HullB
     if (J0 + jl < J1) {
         const uint32_t j = J0 + jl, jrel = j - X.jb;
         const uint32_t width = PASS == 0 ? H.width : (X.grid.n_cpu - 1 < H.width ? X.grid.n_cpu - 1 : H.width);
-        const Floor fl = PASS == 0 ? floor_of(st, jrel) : Floor{-1, 0u, false};
+        const Floor fl = PASS == 0 ? floor_of(st, jrel) : Floor{-1, 0u, RK_JOB_NORMAL};
         int32_t gi = PASS == 0 ? fl.gi : st.gi[jrel];
         uint32_t g_held = PASS == 0 ? 0u : st.g[jrel];
         uint32_t ci = PASS == 0 ? fl.ci : st.ci[jrel];
@@ -840,7 +841,7 @@ __global__ __launch_bounds__(FLOOR_THREADS) void k_floors(Ctx X, JobState st, Sl
         const bool granted = (w & FL_GRANTED) != 0;
         st.fl_gi[jrel] = granted ? S.min_seg[jrel] : -1;
         st.fl_ci[jrel] = granted ? S.min_c[jrel] : 0u;
-        st.waits[jrel] = ((w & FL_GUAR) && !granted) ? 1 : 0;
+        st.waits[jrel] = ((w & FL_GUAR) && !granted) ? RK_JOB_OUT : RK_JOB_NORMAL;
     }
 }
 
@@ -881,7 +882,8 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
                            uint32_t n_rounds, const uint32_t *d_round_off, const rk_cluster *d_clusters,
                            const rk_cluster *one_cluster, uint32_t jb, uint32_t n_jobs, uint32_t max_jobs,
                            uint32_t max_segs_per_job, const float *best_thr, const uint32_t *best_plan,
-                           const float *curve_thr, const SlaDev *sla, rk_assign *assign, float *totals) {
+                           const float *curve_thr, const SlaDev *sla, const FloorsDev *given, rk_assign *assign,
+                           float *totals) {
     if (n_rounds == 0) return RK_OK;
     if (max_jobs > RK_MAX_JOBS_PER_ROUND)
         return rk_fail(ctx, RK_ERR_UNSUPPORTED, "a round has %u jobs, the allocation kernels take up to %u", max_jobs,
@@ -910,7 +912,9 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
     if ((rc = scratch_typed(ctx, SL_ST_FREEC, (size_t)n_rounds, &st.free_c))) return rc;
     if ((rc = scratch_typed(ctx, SL_ST_PARTIAL, (size_t)n_rounds * st.blocks_per_round * 2, &st.partial))) return rc;
     st.fl_gi = nullptr; st.fl_ci = nullptr; st.waits = nullptr; st.cap0 = nullptr;
-    if (sla) {
+    if (given) {
+        st.fl_gi = given->gi; st.fl_ci = given->ci; st.waits = given->state; st.cap0 = given->cap0;
+    } else if (sla) {
         if ((rc = scratch_typed(ctx, SL_FL_GI, (size_t)H.stride, &st.fl_gi))) return rc;
         if ((rc = scratch_typed(ctx, SL_FL_CI, (size_t)H.stride, &st.fl_ci))) return rc;
         if ((rc = scratch_typed(ctx, SL_FL_WAITS, (size_t)H.stride, &st.waits))) return rc;
@@ -948,7 +952,7 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
         k_zero_u32<<<(unsigned)((n64 + 255) / 256), 256, 0, s>>>(reinterpret_cast<uint32_t *>(hist.c), n64);
         RK_CHECK_LAUNCH(ctx, "k_zero_u32");
     }
-    if (sla) {
+    if (sla && !given) {
         k_floors<<<n_rounds, FLOOR_THREADS, (size_t)mj * 8, s>>>(X, st, *sla, mj);
         RK_CHECK_LAUNCH(ctx, "k_floors");
     }
@@ -978,7 +982,7 @@ extern "C" int32_t rk_allocate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
     if (table->max_segs_per_job > 32767u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 32767 segments per job");
     RK_HIP(ctx, hipSetDevice(ctx->device));
     return rk_launch_allocate(ctx, ref_thr, table_dev(table), grid, 1, nullptr, nullptr, cluster, jb, je - jb, je - jb,
-                              table->max_segs_per_job, best_thr, best_plan, curve_thr, nullptr, assign, total);
+                              table->max_segs_per_job, best_thr, best_plan, curve_thr, nullptr, nullptr, assign, total);
 }
 
 int32_t rk_check_sla(rk_ctx *ctx, const rk_sla *sla, bool need_request) {
@@ -1011,6 +1015,6 @@ extern "C" int32_t rk_allocate_sla(rk_ctx *ctx, const float *ref_thr, const rk_p
     SlaDev S = {};
     if (je > jb) S = SlaDev{sla->guaranteed, sla->tenant, min_seg, min_c, sla->n_tenants, sla->quota_g, sla->quota_c};
     return rk_launch_allocate(ctx, ref_thr, table_dev(table), grid, 1, nullptr, nullptr, cluster, jb, je - jb, je - jb,
-                              table->max_segs_per_job, best_thr, best_plan, curve_thr, je > jb ? &S : nullptr, assign,
-                              total);
+                              table->max_segs_per_job, best_thr, best_plan, curve_thr, je > jb ? &S : nullptr, nullptr,
+                              assign, total);
 }

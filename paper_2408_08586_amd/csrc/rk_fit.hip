@@ -11,6 +11,8 @@
 // by Cholesky factorisation.  All control flow is uniform over the wavefront
 // (groups that have finished idle under a predicate) so that the shuffles are
 // always executed by every lane.  float64 throughout.
+#include <type_traits>
+
 #include "rk_internal.h"
 #include "rk_model.h"
 
@@ -341,17 +343,19 @@ __global__ __launch_bounds__(FIT_THREADS) void k_fit(FitArgs A) {
     // An overlap exponent that ended on a bound sits on a plateau (at k = 32 the
     // overlap function no longer feels k): try again from the best point with
     // that exponent moved back inside, twice over the three exponents.
+    auto kick = [&](auto which) {
+        constexpr int i = decltype(which)::value;
+        double x[NP];
+#pragma unroll
+        for (int k = 0; k < NP; ++k) x[k] = best_x[k];
+        const bool on_bound = x[i] <= lower_of(i) * (1.0 + 1e-9) || x[i] >= 1.0 - 1e-9;
+        x[i] = KICK_TO;
+        descend(x, refit && on_bound);
+    };
     for (int round = 0; round < 2; ++round) {
-#pragma unroll
-        for (int e = 0; e < 3; ++e) {
-            const int i = e == 0 ? TH_SYNC : (e == 1 ? TH_OFF : TH_SWAP);
-            double x[NP];
-#pragma unroll
-            for (int k = 0; k < NP; ++k) x[k] = best_x[k];
-            const bool on_bound = x[i] <= lower_of(i) * (1.0 + 1e-9) || x[i] >= 1.0 - 1e-9;
-            x[i] = KICK_TO;
-            descend(x, refit && on_bound);
-        }
+        kick(std::integral_constant<int, TH_SYNC>{});
+        kick(std::integral_constant<int, TH_OFF>{});
+        kick(std::integral_constant<int, TH_SWAP>{});
     }
 
     if (have_fit && lane == 0) {

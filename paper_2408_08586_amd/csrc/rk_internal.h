@@ -9,7 +9,7 @@
 
 #include "rubick.h"
 
-enum { RK_SCRATCH_SLOTS = 40 };
+enum { RK_SCRATCH_SLOTS = 48 };
 
 struct rk_ctx {
     int device;
@@ -35,7 +35,8 @@ enum {
     SL_HIST_G, SL_HIST_C,                                             // cost histograms over the step keys
     SL_PARK,                                             // enumeration: sorted keys between its two passes
     SL_FL_GI, SL_FL_CI, SL_FL_WAITS, SL_FL_CAP0,         // service-level floors of the allocation
-    SL_MIN_SEG, SL_MIN_C, SL_MIN_M                       // minimum demands of a round
+    SL_MIN_SEG, SL_MIN_C, SL_MIN_M,                      // minimum demands of a round
+    SL_SIM_STATE, SL_SIM_ASSIGN                          // simulation: per-job state, the tick's assignment
 };
 
 int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);
@@ -87,6 +88,18 @@ struct SlaDev {
     const uint32_t *quota_g, *quota_c;
 };
 
+// what a job does in a round that starts from floors
+enum : uint8_t { RK_JOB_NORMAL = 0, RK_JOB_OUT = 1, RK_JOB_FROZEN = 2 };
+
+// floors computed by the caller of the allocation (device arrays, indexed from the call's first job;
+// cap0 = per round [free GPUs | free CPUs] left after the floors)
+struct FloorsDev {
+    int32_t *gi;
+    uint32_t *ci;
+    uint8_t *state;
+    unsigned long long *cap0;
+};
+
 // launch wrappers (each enqueues on ctx->stream)
 int32_t rk_launch_fused(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table,
                         const rk_alloc_grid *grid, const rk_env *env, uint32_t jb, uint32_t je,
@@ -94,12 +107,14 @@ int32_t rk_launch_fused(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *t
                         uint32_t *curve_g);
 // one_cluster != NULL: a single round over [jb, jb + n_jobs) with that cluster, carried in the
 // kernel arguments; otherwise n_rounds rounds described by the device arrays.
-// sla != NULL: service-level floors first (the quotas apply to every round alike).
+// sla != NULL: service-level floors first (the quotas apply to every round alike);
+// given != NULL: the floors are there already.
 int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb, const rk_alloc_grid *grid,
                            uint32_t n_rounds, const uint32_t *d_round_off, const rk_cluster *d_clusters,
                            const rk_cluster *one_cluster, uint32_t jb, uint32_t n_jobs, uint32_t max_jobs,
                            uint32_t max_segs_per_job, const float *best_thr, const uint32_t *best_plan,
-                           const float *curve_thr, const SlaDev *sla, rk_assign *assign, float *totals);
+                           const float *curve_thr, const SlaDev *sla, const FloorsDev *given, rk_assign *assign,
+                           float *totals);
 // minimum demands of the guaranteed jobs of [jb, je)
 int32_t rk_launch_min_res(rk_ctx *ctx, const TableDev &tb, const rk_alloc_grid *grid, uint32_t jb, uint32_t je,
                           const float *best_thr, const rk_sla *sla, int32_t *min_seg, uint32_t *min_c,

@@ -90,7 +90,7 @@ int32_t schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *
                               reinterpret_cast<const uint32_t *>(d_meta),
                               d_meta ? reinterpret_cast<const rk_cluster *>(d_meta + off_bytes) : nullptr,
                               n_rounds == 1 ? &clusters[0] : nullptr, 0, J, max_jobs, tb.max_segs_per_job,
-                              best_thr, best_plan, curve_thr, (sla && J > 0) ? &S : nullptr, assign, totals);
+                              best_thr, best_plan, curve_thr, (sla && J > 0) ? &S : nullptr, nullptr, assign, totals);
 }
 
 }  // namespace

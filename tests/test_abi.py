@@ -42,7 +42,7 @@ def test_header_functions_are_exported(rk):
 
 
 def test_struct_layouts_match_the_header(rk):
-    structs = ["rk_jobs", "rk_plan_bounds", "rk_plan_table", "rk_alloc_grid", "rk_env", "rk_cluster", "rk_assign", "rk_sla", "rk_samples", "rk_fit_options", "rk_fit_result"]
+    structs = ["rk_jobs", "rk_plan_bounds", "rk_plan_table", "rk_alloc_grid", "rk_env", "rk_cluster", "rk_assign", "rk_sla", "rk_samples", "rk_fit_options", "rk_fit_result", "rk_trace", "rk_sim_options", "rk_sim_result"]
     prog = ['#include <stdio.h>', '#include <stddef.h>', '#include "rubick.h"', 'int main(void){']
     for s in structs:
         prog.append(f'printf("{s} %zu\\n", sizeof({s}));')
@@ -53,7 +53,9 @@ def test_struct_layouts_match_the_header(rk):
               "rk_sla": ["tenant", "base_thr", "n_tenants", "quota_g", "quota_c"],
               "rk_samples": ["cpus", "thr", "max_samples"],
               "rk_fit_options": ["refit_threshold", "n_starts", "start_offsets"],
-              "rk_fit_result": ["k_const", "theta", "rmsle_after", "iters"]}
+              "rk_fit_result": ["k_const", "theta", "rmsle_after", "iters"],
+              "rk_trace": ["work", "delta"], "rk_sim_options": ["n_ticks", "gate"],
+              "rk_sim_result": ["n_reconf", "held", "totals", "frozen"]}
     for s, fs in fields.items():
         for f in fs:
             prog.append(f'printf("{s}.{f} %zu\\n", offsetof({s}, {f}));')
@@ -66,7 +68,8 @@ def test_struct_layouts_match_the_header(rk):
     want = dict(line.split() for line in out.strip().splitlines())
     py = {"rk_jobs": rk.rk_jobs, "rk_plan_bounds": rk.rk_plan_bounds, "rk_plan_table": rk.rk_plan_table,
           "rk_alloc_grid": rk.rk_alloc_grid, "rk_env": rk.rk_env, "rk_cluster": rk.rk_cluster, "rk_sla": rk.rk_sla,
-          "rk_samples": rk.rk_samples, "rk_fit_options": rk.rk_fit_options, "rk_fit_result": rk.rk_fit_result}
+          "rk_samples": rk.rk_samples, "rk_fit_options": rk.rk_fit_options, "rk_fit_result": rk.rk_fit_result,
+          "rk_trace": rk.rk_trace, "rk_sim_options": rk.rk_sim_options, "rk_sim_result": rk.rk_sim_result}
     for s, cls in py.items():
         assert C.sizeof(cls) == int(want[s]), s
         for f in fields.get(s, []):
