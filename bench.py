@@ -230,6 +230,52 @@ def fit_bench(rk, ctx, dev, wl, env, reps):
             "noise_sigma": 0.05}
 
 
+def sim_bench(rk, ctx, dev, reps):
+    """Discrete-time simulation in the shape of the paper's trace experiment:
+    406 jobs arriving over 12 hours on 64 GPUs, one-minute ticks (720 rounds with
+    the reconfiguration-penalty gate), curves computed once by the library."""
+    import torch
+    import workloads
+    wl = workloads.trace_scale()
+    J = wl.n_jobs
+    jobs = rk.Jobs(wl.coef, wl.ints, dev)
+    bounds, grid, env = rk.make_bounds(wl.bounds), rk.make_grid(wl.grid), rk.make_env(wl.env)
+    cluster = rk.make_cluster(wl.cluster)
+    table = rk.enumerate_to_table(ctx, jobs, bounds, dev)
+    n_rows = len(wl.grid.cpu_levels) * len(wl.grid.mem_levels_gb)
+    n = table.n_segments(n_rows)
+    f32 = lambda: torch.empty(n + 4, dtype=torch.float32, device=dev)
+    i32 = lambda: torch.empty(n + 4, dtype=torch.int32, device=dev)
+    bt, bp, ct, cp, cg = f32(), i32(), f32(), i32(), i32()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    rk.rk_job_curves(ctx, jobs, table.c, grid, env, 0, J, bt, bp, ct, cp, cg)
+    b.record()
+    tr = workloads.trace(J, horizon_s=12 * 3600.0)
+    work = workloads.job_lengths_s(tr.u_duration) * wl.coef[:, 16] * 4.0
+    f64 = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.float64)).to(dev)
+    arrival, work_d, delta = f64(tr.arrival), f64(work), f64(tr.delta)
+    n_ticks = 720
+    res = rk.SimResult(J, n_ticks, dev)
+    wall = []
+    for i in range(reps + 1):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rk.rk_simulate(ctx, jobs.ref_thr, table.c, grid, cluster, bt, bp, ct, arrival, work_d, delta, 60.0, n_ticks, 0.97, res)
+        torch.cuda.synchronize()
+        if i:
+            wall.append((time.perf_counter() - t0) * 1e3)
+    fin = res.finish.cpu().numpy()[:J]
+    done = fin >= 0
+    ms = float(np.median(wall))
+    return {"entry": "rk_job_curves once + rk_simulate", "jobs": J, "gpus": int(wl.cluster.G), "ticks": n_ticks,
+            "tick_s": 60.0, "gate": 0.97, "curves_ms": a.elapsed_time(b), "simulate_ms": ms, "ms_per_tick": ms / n_ticks,
+            "ticks_per_s": n_ticks / (ms * 1e-3), "jobs_finished": int(done.sum()),
+            "mean_jct_s": float(np.mean((fin - tr.arrival)[done])) if done.any() else None,
+            "reconfigurations": int(res.n_reconf.cpu().numpy()[:J].sum()),
+            "mean_gpus_in_use": float(res.gpus_in_use.cpu().numpy()[:n_ticks].mean())}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -242,6 +288,7 @@ def main():
     ap.add_argument("--no-what-if", action="store_true")
     ap.add_argument("--no-sla", action="store_true")
     ap.add_argument("--no-fit", action="store_true")
+    ap.add_argument("--no-sim", action="store_true")
     ap.add_argument("--what-if-rounds", type=int, default=256)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (reads 1 GiB, writes 1 GiB) three times, "
@@ -377,6 +424,8 @@ def main():
                                      max(5, args.steps))
     if not args.no_fit:
         out["fit"] = fit_bench(rk, ctx, dev, wl, env, 3)
+    if not args.no_sim:
+        out["simulation"] = sim_bench(rk, ctx, dev, 3)
     if not args.no_what_if:
         out["what_if"] = what_if_batch(rk, ctx, dev, args.what_if_rounds)
     if not args.no_cpu_baseline:

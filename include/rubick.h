@@ -405,7 +405,10 @@ typedef struct {
  *     N += 1 and delta seconds are owed; starting from or stopping at zero is free;
  *   - a job holding GPUs pays owed seconds out of the tick, then trains at the
  *     round's throughput; it finishes inside the tick at t + paid + remaining/thr.
- * Times and progress are float64.  All ticks are enqueued without waiting. */
+ * Times and progress are float64.  Runs on a stream of its own, ordered after the
+ * work already enqueued on the context's stream (the first tick eagerly, the
+ * others as replays of one captured HIP graph); with more than one tick the call
+ * returns when the simulation has finished. */
 int32_t rk_simulate(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
                     const rk_alloc_grid *grid, const rk_cluster *cluster,
                     const float *best_thr, const uint32_t *best_plan, const float *curve_thr,

@@ -118,6 +118,12 @@ int32_t rk_destroy(rk_ctx *ctx) {
         if (ctx->scratch[i]) (void)hipFree(ctx->scratch[i]);
     if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
     if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
+    if (ctx->sim_stream) {
+        (void)hipStreamSynchronize(ctx->sim_stream);
+        (void)hipStreamDestroy(ctx->sim_stream);
+        (void)hipEventDestroy(ctx->sim_ev[0]);
+        (void)hipEventDestroy(ctx->sim_ev[1]);
+    }
     free(ctx);
     return RK_OK;
 }

@@ -21,6 +21,8 @@ struct rk_ctx {
     uint32_t *h_stage;                      // pinned staging for the plan-table offsets, grown on demand
     size_t h_stage_words;
     uint32_t park_stride;                   // enumeration: words per job between its two passes
+    hipStream_t sim_stream;                 // simulation: its own stream (a tick is captured as a graph), made on demand
+    hipEvent_t sim_ev[2];                   // ... ordered after and before the context's stream with these
 };
 
 // scratch slots

@@ -1,12 +1,17 @@
 // Discrete-time simulation of a job trace through the greedy allocation with
 // the reconfiguration-penalty gate (paper Sec. 5.2 "Incorporating
 // reconfiguration penalty", Sec. 7.4).  The curves are computed once by the
-// caller; a tick is three launches that never wait for the host:
-//   k_sim_begin   (one workgroup) per-job state of the tick: inactive, frozen
-//                 or free to move; floors of the frozen jobs; capacity left
+// caller; a tick is
+//   k_sim_begin   (one workgroup) advances the tick counter; per-job state of
+//                 the tick: inactive, frozen or free to move; floors of the
+//                 frozen jobs; capacity left
 //   the allocation kernels from these floors
 //   k_sim_commit  (thread per job) reconfiguration count and cost, progress,
 //                 completion; remembers what every job holds
+// The tick counter lives on the device, so every tick is the same sequence of
+// launches with the same arguments: the first tick runs eagerly (it also sizes
+// the scratch memory), the sequence is then captured once as a HIP graph on a
+// stream of the simulation's own and replayed for the remaining ticks.
 #include "rk_internal.h"
 #include "rk_model.h"
 
@@ -33,6 +38,8 @@ struct SimArgs {
     SimState S;
     FloorsDev F;
     const rk_assign *assign;
+    uint32_t *tick;             // device counter, advanced by k_sim_begin
+    float *tick_total;          // the allocation's total of the current tick
     rk_sim_result out;
     double *held;               // result arrays or scratch when the caller passes none
     double *progress, *finish;
@@ -45,12 +52,17 @@ __global__ __launch_bounds__(SIM_THREADS) void k_sim_init(SimArgs A) {
     A.S.g[j] = 0; A.S.c[j] = 0; A.S.plan[j] = RK_NO_PLAN; A.S.seg[j] = -1; A.S.lvl[j] = 0;
     A.S.owed[j] = 0.0; A.S.done[j] = 0;
     A.held[j] = 0.0; A.progress[j] = 0.0; A.finish[j] = -1.0; A.n_reconf[j] = 0;
+    if (j == 0) *A.tick = 0xFFFFFFFFu;                    // the first k_sim_begin makes it 0
 }
 
-__global__ __launch_bounds__(SIM_THREADS) void k_sim_begin(SimArgs A, uint32_t tick) {
+__global__ __launch_bounds__(SIM_THREADS) void k_sim_begin(SimArgs A) {
     __shared__ unsigned long long red_g[SIM_THREADS / 64], red_c[SIM_THREADS / 64];
     __shared__ uint32_t red_f[SIM_THREADS / 64];
+    __shared__ uint32_t tick_now;
     const uint32_t tid = threadIdx.x;
+    if (tid == 0) { tick_now = *A.tick + 1u; *A.tick = tick_now; }
+    __syncthreads();
+    const uint32_t tick = tick_now;
     const double t = (double)tick * A.dt;
     unsigned long long held_g = 0, held_c = 0;
     uint32_t n_frozen = 0;
@@ -99,8 +111,10 @@ __global__ __launch_bounds__(SIM_THREADS) void k_sim_begin(SimArgs A, uint32_t t
     }
 }
 
-__global__ __launch_bounds__(COMMIT_THREADS) void k_sim_commit(SimArgs A, uint32_t tick) {
+__global__ __launch_bounds__(COMMIT_THREADS) void k_sim_commit(SimArgs A) {
     const uint32_t j = blockIdx.x * COMMIT_THREADS + threadIdx.x;
+    const uint32_t tick = *A.tick;
+    if (j == 0 && A.out.totals) A.out.totals[tick] = *A.tick_total;
     uint32_t g_used = 0;
     if (j < A.n_jobs && A.F.state[j] != RK_JOB_OUT) {
         const double t = (double)tick * A.dt;
@@ -204,19 +218,52 @@ extern "C" int32_t rk_simulate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
     A.n_reconf = result->n_reconf ? result->n_reconf : s_nrec;
     A.assign = assign;
 
-    hipStream_t s = ctx->stream;
+    A.tick = reinterpret_cast<uint32_t *>(A.F.cap0 + 4);       // inside the 256-byte capacity block
+    A.tick_total = reinterpret_cast<float *>(A.F.cap0 + 5);
+
+    // the simulation's own stream, ordered after what the context's stream holds
+    if (!ctx->sim_stream) {
+        RK_HIP(ctx, hipStreamCreateWithFlags(&ctx->sim_stream, hipStreamNonBlocking));
+        RK_HIP(ctx, hipEventCreateWithFlags(&ctx->sim_ev[0], hipEventDisableTiming));
+        RK_HIP(ctx, hipEventCreateWithFlags(&ctx->sim_ev[1], hipEventDisableTiming));
+    }
+    hipStream_t user = ctx->stream, s = ctx->sim_stream;
+    RK_HIP(ctx, hipEventRecord(ctx->sim_ev[0], user));
+    RK_HIP(ctx, hipStreamWaitEvent(s, ctx->sim_ev[0], 0));
+
+    auto tick_body = [&]() -> int32_t {
+        k_sim_begin<<<1, SIM_THREADS, 0, s>>>(A);
+        RK_CHECK_LAUNCH(ctx, "k_sim_begin");
+        ctx->stream = s;                                       // the allocation enqueues on the context's stream
+        const int32_t r = rk_launch_allocate(ctx, ref_thr, A.tb, grid, 1, nullptr, nullptr, cluster, 0, J, J,
+                                             table->max_segs_per_job, best_thr, best_plan, curve_thr, nullptr, &A.F,
+                                             assign, A.tick_total);
+        ctx->stream = user;
+        if (r) return r;
+        k_sim_commit<<<(J + COMMIT_THREADS - 1) / COMMIT_THREADS, COMMIT_THREADS, 0, s>>>(A);
+        RK_CHECK_LAUNCH(ctx, "k_sim_commit");
+        return RK_OK;
+    };
+
     k_sim_init<<<(J + SIM_THREADS - 1) / SIM_THREADS, SIM_THREADS, 0, s>>>(A);
     RK_CHECK_LAUNCH(ctx, "k_sim_init");
-    float *dummy_total = reinterpret_cast<float *>(A.F.cap0 + 4);   // inside the 256-byte capacity block
-    for (uint32_t k = 0; k < options->n_ticks; ++k) {
-        k_sim_begin<<<1, SIM_THREADS, 0, s>>>(A, k);
-        RK_CHECK_LAUNCH(ctx, "k_sim_begin");
-        if ((rc = rk_launch_allocate(ctx, ref_thr, A.tb, grid, 1, nullptr, nullptr, cluster, 0, J, J, table->max_segs_per_job,
-                                     best_thr, best_plan, curve_thr, nullptr, &A.F, assign,
-                                     result->totals ? result->totals + k : dummy_total)))
-            return rc;
-        k_sim_commit<<<(J + COMMIT_THREADS - 1) / COMMIT_THREADS, COMMIT_THREADS, 0, s>>>(A, k);
-        RK_CHECK_LAUNCH(ctx, "k_sim_commit");
+    if ((rc = tick_body())) return rc;                         // tick 0, eagerly
+    if (options->n_ticks > 1) {
+        hipGraph_t graph = nullptr;
+        hipGraphExec_t exec = nullptr;
+        RK_HIP(ctx, hipStreamBeginCapture(s, hipStreamCaptureModeRelaxed));
+        rc = tick_body();
+        const hipError_t e_end = hipStreamEndCapture(s, &graph);
+        if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+        if (e_end != hipSuccess) return rk_fail(ctx, RK_ERR_DEVICE, "hipStreamEndCapture: %s", hipGetErrorString(e_end));
+        hipError_t e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        for (uint32_t k = 1; e == hipSuccess && k < options->n_ticks; ++k) e = hipGraphLaunch(exec, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);      // the graph must outlive its launches
+        if (exec) (void)hipGraphExecDestroy(exec);
+        (void)hipGraphDestroy(graph);
+        if (e != hipSuccess) return rk_fail(ctx, RK_ERR_DEVICE, "simulation graph: %s", hipGetErrorString(e));
     }
+    RK_HIP(ctx, hipEventRecord(ctx->sim_ev[1], s));
+    RK_HIP(ctx, hipStreamWaitEvent(user, ctx->sim_ev[1], 0));
     return RK_OK;
 }

@@ -365,4 +365,14 @@ def job_lengths_s(u: np.ndarray) -> np.ndarray:
     return 300.0 * np.exp(u * np.log(8 * 3600.0 / 300.0))
 
 
+def trace_scale(seed: int = BASE_SEED, n_jobs: int = 406) -> Workload:
+    """The shape of the paper's trace experiment: 406 jobs on 8 nodes x 8 GPUs (models as in paper_scale)."""
+    coef, ints = draw_jobs(seed, 6, 0, np.arange(n_jobs),
+                           param_buckets=[(0.4, 0.1e9, 1.3e9), (0.4, 1.3e9, 13e9), (0.2, 13e9, 70e9)],
+                           layer_choices=(12, 24, 32, 40))
+    return Workload("trace_scale", coef, ints, Bounds(g_max=64),
+                    Grid(_abs_levels(32), 0, np.array([64.0], np.float32), 0),
+                    Env(), Cluster(64, 256, 4096.0))
+
+
 CONFIGS = {"tiny": tiny, "paper_scale": paper_scale, "large": large, "stress": stress}
