@@ -265,46 +265,102 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
 struct Cut { int32_t bin; unsigned long long baseG, baseC; };
 
 struct CutScratch {
-    unsigned long long sg[JOB_THREADS], sc[JOB_THREADS];
+    unsigned long long wave_g[JOB_THREADS / 64], wave_c[JOB_THREADS / 64];   // totals of the wavefronts
+    unsigned long long mask[JOB_THREADS / 64];                               // lanes that found a failing bin
     int32_t cand[JOB_THREADS];
     unsigned long long candG[JOB_THREADS], candC[JOB_THREADS];
 };
 
-// Workgroup-wide (JOB_THREADS threads), every thread gets the result.
+// Workgroup-wide: the first JOB_THREADS threads do the work (thread t owns the
+// bins BINS-1-16t downwards), every thread of the workgroup must call it
+// (barriers) and gets the result.
 __device__ Cut find_cut(const uint32_t *__restrict__ hG, const unsigned long long *__restrict__ hC,
                         unsigned long long baseG, unsigned long long baseC, unsigned long long capG,
                         unsigned long long capC, CutScratch &S) {
-    constexpr uint32_t PER = BINS / JOB_THREADS;
-    const uint32_t tid = threadIdx.x;
-    const uint32_t top = BINS - 1 - tid * PER;           // this thread's bins: top, top-1, ... (descending)
+    constexpr uint32_t PER = BINS / JOB_THREADS, NW = JOB_THREADS / 64;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const bool part = tid < JOB_THREADS;
+    const uint32_t top = BINS - 1 - (part ? tid : 0u) * PER;
+    uint32_t vg[PER];
+    unsigned long long vc[PER];
     unsigned long long sg = 0, sc = 0;
-    for (uint32_t i = 0; i < PER; ++i) { sg += hG[top - i]; sc += hC[top - i]; }
-    S.sg[tid] = sg; S.sc[tid] = sc;
-    __syncthreads();
-    for (uint32_t off = 1; off < JOB_THREADS; off <<= 1) {
-        const unsigned long long ag = tid >= off ? S.sg[tid - off] : 0ull, ac = tid >= off ? S.sc[tid - off] : 0ull;
-        __syncthreads();
-        S.sg[tid] += ag; S.sc[tid] += ac;
-        __syncthreads();
-    }
-    unsigned long long cg = baseG + S.sg[tid] - sg, cc = baseC + S.sc[tid] - sc;   // everything above this thread's bins
-    int32_t cand = -1;
+#pragma unroll
     for (uint32_t i = 0; i < PER; ++i) {
-        const uint32_t b = top - i;
-        if (cg + hG[b] > capG || cc + hC[b] > capC) { cand = (int32_t)b; break; }
-        cg += hG[b]; cc += hC[b];
+        vg[i] = part ? hG[top - i] : 0u;
+        vc[i] = part ? hC[top - i] : 0ull;
+        sg += vg[i]; sc += vc[i];
     }
-    S.cand[tid] = cand; S.candG[tid] = cg; S.candC[tid] = cc;
+    // inclusive scan over the threads: inside the wavefront by shuffles, then the wavefronts' totals
+    unsigned long long ig = sg, ic = sc;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const unsigned long long ag = __shfl_up(ig, off, 64), ac = __shfl_up(ic, off, 64);
+        if ((int)lane >= off) { ig += ag; ic += ac; }
+    }
+    if (part && lane == 63u) { S.wave_g[tid >> 6] = ig; S.wave_c[tid >> 6] = ic; }
+    __syncthreads();
+    unsigned long long allG = 0, allC = 0, beforeG = 0, beforeC = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < NW; ++w) {
+        if (w < (tid >> 6)) { beforeG += S.wave_g[w]; beforeC += S.wave_c[w]; }
+        allG += S.wave_g[w]; allC += S.wave_c[w];
+    }
+    unsigned long long cg = baseG + beforeG + ig - sg, cc = baseC + beforeC + ic - sc;   // everything above this thread's bins
+    int32_t cand = -1;
+#pragma unroll
+    for (uint32_t i = 0; i < PER; ++i) {
+        if (cand < 0) {
+            if (cg + vg[i] > capG || cc + vc[i] > capC) cand = (int32_t)(top - i);
+            else { cg += vg[i]; cc += vc[i]; }
+        }
+    }
+    const unsigned long long found = __ballot(part && cand >= 0);
+    if (part) {
+        if (cand >= 0) { S.cand[tid] = cand; S.candG[tid] = cg; S.candC[tid] = cc; }
+        if (lane == 0) S.mask[tid >> 6] = found;
+    }
     __syncthreads();
     Cut out;
     out.bin = -1;
-    out.baseG = baseG + S.sg[JOB_THREADS - 1];
-    out.baseC = baseC + S.sc[JOB_THREADS - 1];
-    for (uint32_t t = 0; t < JOB_THREADS; ++t) {          // the first thread (highest bins) with a failing bin
-        if (S.cand[t] >= 0) { out.bin = S.cand[t]; out.baseG = S.candG[t]; out.baseC = S.candC[t]; break; }
+    out.baseG = baseG + allG;
+    out.baseC = baseC + allC;
+    int32_t first = -1;                                   // the first thread (highest bins) with a failing bin
+#pragma unroll
+    for (uint32_t w = 0; w < NW; ++w) {
+        const unsigned long long m = S.mask[w];
+        if (first < 0 && m) first = (int32_t)(w * 64 + (uint32_t)__ffsll((long long)m) - 1u);
     }
+    if (first >= 0) { out.bin = S.cand[first]; out.baseG = S.candG[first]; out.baseC = S.candC[first]; }
     __syncthreads();
     return out;
+}
+
+template <int PASS>
+__device__ __forceinline__ uint32_t walk_width(const Ctx &X, const HullBuf &H) {
+    return PASS == 0 ? H.width : (X.grid.n_cpu - 1 < H.width ? X.grid.n_cpu - 1 : H.width);
+}
+
+// Adds the steps of one job's walk to a histogram in LDS.
+template <int PASS, int LEVEL>
+__device__ __forceinline__ void hist_add(const Ctx &X, const HullBuf &H, uint32_t jrel, int32_t want_top, uint32_t *lg,
+                                         unsigned long long *lc) {
+    const uint32_t width = walk_width<PASS>(X, H);
+    for (uint32_t k = 0; k < width; ++k) {
+        const size_t e = (size_t)k * H.stride + jrel;
+        const uint32_t key = H.key[e];
+        if (!key) break;
+        uint32_t bin;
+        if (LEVEL == 0) bin = key >> 20;
+        else {
+            if ((int32_t)(key >> 20) > want_top) continue;
+            if ((int32_t)(key >> 20) < want_top) break;   // keys only decrease along a walk
+            bin = (key >> 8) & (BINS - 1);
+        }
+        const uint32_t dg = H.dg[e];
+        const unsigned long long dc = H.dc[e];
+        if (dg) atomicAdd(&lg[bin], dg);
+        if (dc) atomicAdd(&lc[bin], dc);
+    }
 }
 
 // Cost histogram of one level.  Level 0: bin = key bits 31..20 of every step.
@@ -330,26 +386,7 @@ __global__ __launch_bounds__(JOB_THREADS) void k_hist(Ctx X, JobState st, HullBu
     for (uint32_t i = tid; i < BINS; i += JOB_THREADS) { lg[i] = 0; lc[i] = 0; }
     __syncthreads();
     const uint32_t jl = blockIdx.x * JOB_THREADS + tid;
-    const uint32_t width = PASS == 0 ? H.width : (X.grid.n_cpu - 1 < H.width ? X.grid.n_cpu - 1 : H.width);
-    if (J0 + jl < J1) {
-        const uint32_t jrel = J0 + jl - X.jb;
-        for (uint32_t k = 0; k < width; ++k) {
-            const size_t e = (size_t)k * H.stride + jrel;
-            const uint32_t key = H.key[e];
-            if (!key) break;
-            uint32_t bin;
-            if (LEVEL == 0) bin = key >> 20;
-            else {
-                if ((int32_t)(key >> 20) > want_top) continue;
-                if ((int32_t)(key >> 20) < want_top) break;   // keys only decrease along a walk
-                bin = (key >> 8) & (BINS - 1);
-            }
-            const uint32_t dg = H.dg[e];
-            const unsigned long long dc = H.dc[e];
-            if (dg) atomicAdd(&lg[bin], dg);
-            if (dc) atomicAdd(&lc[bin], dc);
-        }
-    }
+    if (J0 + jl < J1) hist_add<PASS, LEVEL>(X, H, J0 + jl - X.jb, want_top, lg, lc);
     __syncthreads();
     const size_t h = hist_at(rnd, PASS, LEVEL);
     for (uint32_t i = tid; i < BINS; i += JOB_THREADS) {
@@ -403,32 +440,35 @@ __device__ __forceinline__ Step best_step(const Ctx &X, uint32_t j, int32_t gi, 
 }
 
 // ------------------------------------------------------------------ apply the selected prefix
-// One thread per job.  Every workgroup derives the threshold from the two
-// histogram levels (same inputs, same result in all of them).
-template <int PASS>
-__global__ __launch_bounds__(JOB_THREADS) void k_apply(Ctx X, JobState st, HullBuf H, Hist hist) {
-    __shared__ CutScratch cs;
-    const uint32_t rnd = blockIdx.y, tid = threadIdx.x;
-    uint32_t J0, J1;
-    rk_cluster cl;
-    round_of(X.R, rnd, J0, J1, cl);
-    unsigned long long capG, capC;
-    pass_caps<PASS>(X.R, cl, st, rnd, capG, capC);
-    const size_t h0 = hist_at(rnd, PASS, 0), h1 = hist_at(rnd, PASS, 1);
-    const Cut c0 = find_cut(hist.g + h0, hist.c + h0, 0, 0, capG, capC, cs);
-    long long thr24 = -1;                                  // steps with (key >> 8) > thr24 are applied
+// The threshold from the two histogram levels: steps with (key >> 8) > thr24
+// are applied; freeG / freeC = what is left after them.  Workgroup-wide.
+struct Selection { long long thr24; unsigned long long freeG, freeC; };
+
+__device__ Selection select_threshold(const uint32_t *h0g, const unsigned long long *h0c, const uint32_t *h1g,
+                                      const unsigned long long *h1c, unsigned long long capG, unsigned long long capC,
+                                      CutScratch &cs) {
+    const Cut c0 = find_cut(h0g, h0c, 0, 0, capG, capC, cs);
+    Selection sel;
+    sel.thr24 = -1;
     unsigned long long usedG = c0.baseG, usedC = c0.baseC;
     if (c0.bin >= 0) {
-        const Cut c1 = find_cut(hist.g + h1, hist.c + h1, c0.baseG, c0.baseC, capG, capC, cs);
-        thr24 = ((long long)c0.bin << 12) + (long long)c1.bin;   // c1.bin = -1: the whole of c0.bin fits as well
+        const Cut c1 = find_cut(h1g, h1c, c0.baseG, c0.baseC, capG, capC, cs);
+        sel.thr24 = ((long long)c0.bin << 12) + (long long)c1.bin;   // c1.bin = -1: the whole of c0.bin fits as well
         usedG = c1.baseG; usedC = c1.baseC;
     }
-    const unsigned long long freeG = capG - usedG, freeC = capC - usedC;
+    sel.freeG = capG - usedG;
+    sel.freeC = capC - usedC;
+    return sel;
+}
 
-    const uint32_t jl = blockIdx.x * JOB_THREADS + tid;
-    if (J0 + jl < J1) {
-        const uint32_t j = J0 + jl, jrel = j - X.jb;
-        const uint32_t width = PASS == 0 ? H.width : (X.grid.n_cpu - 1 < H.width ? X.grid.n_cpu - 1 : H.width);
+// Applies the selected prefix (steps with key >> 8 above thr24) to job j and
+// caches its best next step under what is left.
+template <int PASS>
+__device__ __forceinline__ void apply_job(const Ctx &X, const JobState &st, const HullBuf &H, uint32_t j, long long thr24,
+                                          unsigned long long freeG, unsigned long long freeC) {
+    {
+        const uint32_t jrel = j - X.jb;
+        const uint32_t width = walk_width<PASS>(X, H);
         const Floor fl = PASS == 0 ? floor_of(st, jrel) : Floor{-1, 0u, RK_JOB_NORMAL};
         int32_t gi = PASS == 0 ? fl.gi : st.gi[jrel];
         uint32_t g_held = PASS == 0 ? 0u : st.g[jrel];
@@ -458,9 +498,27 @@ __global__ __launch_bounds__(JOB_THREADS) void k_apply(Ctx X, JobState st, HullB
         st.step_tgt[jrel] = (uint16_t)nx.tgt;
         st.step_dg[jrel] = (uint16_t)nx.dg;
     }
+}
+
+// One thread per job.  Every workgroup derives the threshold from the two
+// histogram levels (same inputs, same result in all of them).
+template <int PASS>
+__global__ __launch_bounds__(JOB_THREADS) void k_apply(Ctx X, JobState st, HullBuf H, Hist hist) {
+    __shared__ CutScratch cs;
+    const uint32_t rnd = blockIdx.y, tid = threadIdx.x;
+    uint32_t J0, J1;
+    rk_cluster cl;
+    round_of(X.R, rnd, J0, J1, cl);
+    unsigned long long capG, capC;
+    pass_caps<PASS>(X.R, cl, st, rnd, capG, capC);
+    const size_t h0 = hist_at(rnd, PASS, 0), h1 = hist_at(rnd, PASS, 1);
+    const Selection sel = select_threshold(hist.g + h0, hist.c + h0, hist.g + h1, hist.c + h1, capG, capC, cs);
+
+    const uint32_t jl = blockIdx.x * JOB_THREADS + tid;
+    if (J0 + jl < J1) apply_job<PASS>(X, st, H, J0 + jl, sel.thr24, sel.freeG, sel.freeC);
     // the capacity left goes to the tail through a second pair of words: the
     // pass's starting capacity (free_c) is still being read by other workgroups
-    if (blockIdx.x == 0 && tid == 0) { st.free_g[rnd] = freeG; st.free_g[X.R.n_rounds + rnd] = freeC; }
+    if (blockIdx.x == 0 && tid == 0) { st.free_g[rnd] = sel.freeG; st.free_g[X.R.n_rounds + rnd] = sel.freeC; }
 }
 
 // ------------------------------------------------------------------ step by step on what is left
@@ -476,23 +534,21 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
     return m;
 }
 
+// Workgroup of TAIL_THREADS threads; lds = max_jobs * 12 bytes of scratch, red =
+// TAIL_WAVES words.  Starts from the state k_apply / apply_job left in st.
 template <int PASS>
-__global__ __launch_bounds__(TAIL_THREADS) void k_tail(Ctx X, uint32_t max_jobs, JobState st) {
-    extern __shared__ float lds_dyn[];
-    __shared__ unsigned long long red[TAIL_WAVES];
-    float *slope = lds_dyn;                                        // cached best step of each job (0 = none)
+__device__ __forceinline__ void tail_run(const Ctx &X, const JobState &st, uint32_t rnd, uint32_t J0, uint32_t J1,
+                                         unsigned long long freeG, unsigned long long freeC, uint32_t max_jobs,
+                                         float *lds, unsigned long long *red) {
+    float *slope = lds;                                            // cached best step of each job (0 = none)
     uint16_t *tgt = reinterpret_cast<uint16_t *>(slope + max_jobs);   // its target (segment index or CPU level)
     uint16_t *aux = tgt + max_jobs;                                // PASS 0: GPUs the step adds; PASS 1: GPUs held
     int16_t *gi = reinterpret_cast<int16_t *>(aux + max_jobs);     // granted segment index, -1 = none
     uint16_t *ci = reinterpret_cast<uint16_t *>(gi + max_jobs);    // granted CPU level
 
-    const uint32_t tid = threadIdx.x, rnd = blockIdx.x;
-    uint32_t J0, J1;
-    rk_cluster cl;
-    round_of(X.R, rnd, J0, J1, cl);
+    const uint32_t tid = threadIdx.x;
     const uint32_t nj = J1 - J0, jrel0 = J0 - X.jb;
     const GridDev &grid = X.grid;
-    unsigned long long freeG = st.free_g[rnd], freeC = st.free_g[X.R.n_rounds + rnd];
 
     for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {
         slope[jl] = st.step_slope[jrel0 + jl];
@@ -573,6 +629,61 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_tail(Ctx X, uint32_t max_jobs,
         }
     }
     if (PASS == 0 && tid == 0) st.free_c[rnd] = freeC;          // what the CPU pass starts from
+}
+
+template <int PASS>
+__global__ __launch_bounds__(TAIL_THREADS) void k_tail(Ctx X, uint32_t max_jobs, JobState st) {
+    extern __shared__ float lds_dyn[];
+    __shared__ unsigned long long red[TAIL_WAVES];
+    const uint32_t rnd = blockIdx.x;
+    uint32_t J0, J1;
+    rk_cluster cl;
+    round_of(X.R, rnd, J0, J1, cl);
+    tail_run<PASS>(X, st, rnd, J0, J1, st.free_g[rnd], st.free_g[X.R.n_rounds + rnd], max_jobs, lds_dyn, red);
+}
+
+// ------------------------------------------------------------------ small rounds: selection in one workgroup
+// For rounds of at most SMALL_ROUND_JOBS jobs the histograms, the threshold,
+// the application and the step-by-step tail of a pass run in one workgroup per
+// round, with the histograms in LDS: one launch instead of six.
+constexpr uint32_t SMALL_ROUND_JOBS = 2048;
+
+template <int PASS>
+__global__ __launch_bounds__(TAIL_THREADS) void k_select_small(Ctx X, uint32_t max_jobs, JobState st, HullBuf H) {
+    extern __shared__ float lds_dyn[];                          // tail scratch: max_jobs * 12 bytes
+    __shared__ uint32_t hg[BINS];                               // one histogram, used for level 0 and then level 1
+    __shared__ unsigned long long hc[BINS];
+    __shared__ CutScratch cs;
+    __shared__ unsigned long long red[TAIL_WAVES];
+    const uint32_t rnd = blockIdx.x, tid = threadIdx.x;
+    uint32_t J0, J1;
+    rk_cluster cl;
+    round_of(X.R, rnd, J0, J1, cl);
+    const uint32_t nj = J1 - J0;
+    unsigned long long capG, capC;
+    pass_caps<PASS>(X.R, cl, st, rnd, capG, capC);
+    for (uint32_t i = tid; i < BINS; i += TAIL_THREADS) { hg[i] = 0; hc[i] = 0; }
+    __syncthreads();
+    for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) hist_add<PASS, 0>(X, H, J0 + jl - X.jb, 0, hg, hc);
+    __syncthreads();
+    const Cut c0 = find_cut(hg, hc, 0, 0, capG, capC, cs);
+    Selection sel;
+    sel.thr24 = -1;
+    unsigned long long usedG = c0.baseG, usedC = c0.baseC;
+    if (c0.bin >= 0) {                                          // uniform over the workgroup
+        for (uint32_t i = tid; i < BINS; i += TAIL_THREADS) { hg[i] = 0; hc[i] = 0; }
+        __syncthreads();
+        for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) hist_add<PASS, 1>(X, H, J0 + jl - X.jb, c0.bin, hg, hc);
+        __syncthreads();
+        const Cut c1 = find_cut(hg, hc, c0.baseG, c0.baseC, capG, capC, cs);
+        sel.thr24 = ((long long)c0.bin << 12) + (long long)c1.bin;
+        usedG = c1.baseG; usedC = c1.baseC;
+    }
+    sel.freeG = capG - usedG;
+    sel.freeC = capC - usedC;
+    for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) apply_job<PASS>(X, st, H, J0 + jl, sel.thr24, sel.freeG, sel.freeC);
+    __syncthreads();                                            // the state in st is read back by the whole workgroup
+    tail_run<PASS>(X, st, rnd, J0, J1, sel.freeG, sel.freeC, max_jobs, lds_dyn, red);
 }
 
 // ------------------------------------------------------------------ memory
@@ -864,6 +975,13 @@ int32_t launch_pass(rk_ctx *ctx, const Ctx &X, const JobState &st, const HullBuf
     if (n_jobs > 0) {
         k_hull<PASS><<<hull_blocks, HULL_THREADS, 0, s>>>(X, st, H);
         RK_CHECK_LAUNCH(ctx, "k_hull");
+    }
+    if (mj <= SMALL_ROUND_JOBS) {
+        k_select_small<PASS><<<n_rounds, TAIL_THREADS, tail_lds, s>>>(X, mj, st, H);
+        RK_CHECK_LAUNCH(ctx, "k_select_small");
+        return RK_OK;
+    }
+    if (n_jobs > 0) {
         k_hist<PASS, 0><<<job_grid, JOB_THREADS, 0, s>>>(X, st, H, hist);
         RK_CHECK_LAUNCH(ctx, "k_hist<0>");
         k_hist<PASS, 1><<<job_grid, JOB_THREADS, 0, s>>>(X, st, H, hist);
@@ -945,8 +1063,16 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
         raised[ctx->device & 63] = true;
     }
+    static bool raised_small[64] = {};
+    if (mj <= SMALL_ROUND_JOBS && !raised_small[ctx->device & 63]) {   // static + dynamic LDS go beyond 64 KiB
+        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_select_small<0>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_select_small<1>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+        raised_small[ctx->device & 63] = true;
+    }
     hipStream_t s = ctx->stream;
-    {   // histograms start at zero (fill kernels, so the sequence can be captured in a graph)
+    if (mj > SMALL_ROUND_JOBS) {   // histograms start at zero (fill kernels, so the sequence can be captured in a graph)
         const size_t n32 = hist_bins, n64 = hist_bins * 2;
         k_zero_u32<<<(unsigned)((n32 + 255) / 256), 256, 0, s>>>(hist.g, n32);
         k_zero_u32<<<(unsigned)((n64 + 255) / 256), 256, 0, s>>>(reinterpret_cast<uint32_t *>(hist.c), n64);
