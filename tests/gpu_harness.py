@@ -7,7 +7,7 @@ import numpy as np
 import paper_2408_08586_amd as rk
 
 
-class GpuRun:
+class DeviceRun:
     def __init__(self, wl, device="cuda:0"):
         import torch
         self.torch = torch

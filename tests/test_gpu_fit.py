@@ -13,8 +13,8 @@ pytestmark = pytest.mark.gpu
 def gpu():
     import torch
     assert torch.cuda.is_available(), "these tests need the GPU"
-    from gpu_harness import GpuRun
-    return GpuRun
+    from gpu_harness import DeviceRun
+    return DeviceRun
 
 
 class FitCase:

@@ -19,8 +19,8 @@ def gpu():
     import torch
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    from gpu_harness import GpuRun
-    return GpuRun
+    from gpu_harness import DeviceRun
+    return DeviceRun
 
 
 def oracle_table_equal(tn, ot):
