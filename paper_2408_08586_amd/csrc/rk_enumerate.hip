@@ -147,47 +147,62 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     }
 }
 
-// exclusive scan of the per-job counts, totals and maxima (one workgroup)
+// exclusive scan of the per-job counts, totals and maxima: one workgroup walks
+// the jobs in tiles of 1024 with coalesced loads (the next tile is requested
+// before the current one is scanned); inside a tile wavefront scans by
+// shuffles, then the wavefronts' totals
 __global__ __launch_bounds__(1024) void k_scan_counts(const uint32_t *__restrict__ cnt_t,
                                                       const uint32_t *__restrict__ cnt_s, uint32_t n_jobs,
                                                       uint32_t *__restrict__ off_t, uint32_t *__restrict__ off_s,
                                                       uint32_t *__restrict__ totals) {
-    __shared__ unsigned long long part_t[1024], part_s[1024];
-    __shared__ uint32_t max_t[1024], max_s[1024];
-    const uint32_t tid = threadIdx.x;
-    const uint32_t chunk = (n_jobs + 1023u) / 1024u;
-    const uint32_t lo = tid * chunk < n_jobs ? tid * chunk : n_jobs;
-    const uint32_t hi = lo + chunk < n_jobs ? lo + chunk : n_jobs;
-    unsigned long long st = 0, ss = 0;
-    uint32_t mt = 0, ms = 0;
-    for (uint32_t j = lo; j < hi; ++j) {
-        st += cnt_t[j]; ss += cnt_s[j];
-        mt = cnt_t[j] > mt ? cnt_t[j] : mt;
-        ms = cnt_s[j] > ms ? cnt_s[j] : ms;
+    __shared__ unsigned long long wave_t[16], wave_s[16];
+    __shared__ uint32_t wave_mt[16], wave_ms[16];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    unsigned long long carry_t = 0, carry_s = 0;            // everything before the tile (same in every thread)
+    uint32_t mt = 0, ms = 0;                                // running maxima of this thread's elements
+    uint32_t nt_next = tid < n_jobs ? cnt_t[tid] : 0u, ns_next = tid < n_jobs ? cnt_s[tid] : 0u;
+    for (uint32_t base = 0; base < n_jobs; base += 1024) {
+        const uint32_t ct = nt_next, cs = ns_next;
+        const uint32_t jn = base + 1024 + tid;
+        nt_next = jn < n_jobs ? cnt_t[jn] : 0u;
+        ns_next = jn < n_jobs ? cnt_s[jn] : 0u;
+        mt = ct > mt ? ct : mt;
+        ms = cs > ms ? cs : ms;
+        unsigned long long it = ct, is = cs;                // inclusive scan inside the wavefront
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const unsigned long long at = __shfl_up(it, off, 64), as = __shfl_up(is, off, 64);
+            if ((int)lane >= off) { it += at; is += as; }
+        }
+        if (lane == 63u) { wave_t[wave] = it; wave_s[wave] = is; }
+        __syncthreads();
+        unsigned long long before_t = 0, before_s = 0, all_t = 0, all_s = 0;
+#pragma unroll
+        for (uint32_t w = 0; w < 16; ++w) {
+            if (w < wave) { before_t += wave_t[w]; before_s += wave_s[w]; }
+            all_t += wave_t[w]; all_s += wave_s[w];
+        }
+        const uint32_t j = base + tid;
+        if (j < n_jobs) {
+            off_t[j] = (uint32_t)(carry_t + before_t + it - ct);
+            off_s[j] = (uint32_t)(carry_s + before_s + is - cs);
+        }
+        carry_t += all_t; carry_s += all_s;
+        __syncthreads();                                    // the totals are read before the next tile overwrites them
     }
-    part_t[tid] = st; part_s[tid] = ss; max_t[tid] = mt; max_s[tid] = ms;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t a = __shfl_xor(mt, off, 64), b = __shfl_xor(ms, off, 64);
+        mt = a > mt ? a : mt; ms = b > ms ? b : ms;
+    }
+    if (lane == 0) { wave_mt[wave] = mt; wave_ms[wave] = ms; }
     __syncthreads();
-    for (uint32_t off = 1; off < 1024; off <<= 1) {
-        unsigned long long at = tid >= off ? part_t[tid - off] : 0ull;
-        unsigned long long as = tid >= off ? part_s[tid - off] : 0ull;
-        uint32_t xt = tid >= off ? max_t[tid - off] : 0u, xs = tid >= off ? max_s[tid - off] : 0u;
-        __syncthreads();
-        part_t[tid] += at; part_s[tid] += as;
-        max_t[tid] = max_t[tid] > xt ? max_t[tid] : xt;
-        max_s[tid] = max_s[tid] > xs ? max_s[tid] : xs;
-        __syncthreads();
-    }
-    unsigned long long rt = part_t[tid] - st, rs = part_s[tid] - ss;   // exclusive
-    for (uint32_t j = lo; j < hi; ++j) {
-        off_t[j] = (uint32_t)rt; off_s[j] = (uint32_t)rs;
-        rt += cnt_t[j]; rs += cnt_s[j];
-    }
-    if (tid == 1023) {
-        const unsigned long long tt = part_t[1023], ts = part_s[1023];
-        off_t[n_jobs] = (uint32_t)tt; off_s[n_jobs] = (uint32_t)ts;
-        totals[TOT_NT_LO] = (uint32_t)tt; totals[TOT_NT_HI] = (uint32_t)(tt >> 32);
-        totals[TOT_NS_LO] = (uint32_t)ts; totals[TOT_NS_HI] = (uint32_t)(ts >> 32);
-        totals[TOT_MAX_T] = max_t[1023]; totals[TOT_MAX_S] = max_s[1023];
+    if (tid == 0) {
+        for (uint32_t w = 0; w < 16; ++w) { mt = wave_mt[w] > mt ? wave_mt[w] : mt; ms = wave_ms[w] > ms ? wave_ms[w] : ms; }
+        off_t[n_jobs] = (uint32_t)carry_t; off_s[n_jobs] = (uint32_t)carry_s;
+        totals[TOT_NT_LO] = (uint32_t)carry_t; totals[TOT_NT_HI] = (uint32_t)(carry_t >> 32);
+        totals[TOT_NS_LO] = (uint32_t)carry_s; totals[TOT_NS_HI] = (uint32_t)(carry_s >> 32);
+        totals[TOT_MAX_T] = mt; totals[TOT_MAX_S] = ms;
     }
 }
 
