@@ -57,7 +57,7 @@ extern "C" {
 #define RK_MAX_CPU_LEVELS     64
 #define RK_MAX_MEM_LEVELS     16
 #define RK_MAX_G              65535u   /* largest g_max */
-#define RK_MAX_PP             16383u   /* largest pp_max */
+#define RK_MAX_PP             4095u    /* largest pp_max */
 #define RK_MAX_TRIPLES_PER_JOB 2048u
 #define RK_MAX_JOBS_PER_ROUND 12288u   /* limit of the greedy allocation kernel */
 
@@ -66,10 +66,12 @@ extern "C" {
 #define RK_INFEASIBLE_GPU_MEM 2u   /* estimated GPU memory above env.gpu_mem_cap */
 #define RK_INFEASIBLE_HOST_MEM 4u  /* offloaded state above the memory tier */
 
-/* packed triple: d in bits 0..15, log2(t) in bits 16..17, p in bits 18..31 */
+/* packed triple: d in bits 0..15, log2(t) in bits 16..17, p in bits 18..29,
+ * micro-batch shift v in bits 30..31 (the plan runs micro-batches of mu * 2^v samples) */
 #define RK_TRIPLE_D(x)  ((x) & 0xFFFFu)
 #define RK_TRIPLE_T(x)  (1u << (((x) >> 16) & 3u))
-#define RK_TRIPLE_P(x)  ((x) >> 18)
+#define RK_TRIPLE_P(x)  (((x) >> 18) & 0xFFFu)
+#define RK_TRIPLE_V(x)  ((x) >> 30)
 
 typedef struct rk_ctx rk_ctx;
 
@@ -93,23 +95,27 @@ typedef struct {
     const float *ref_thr;       /* reference throughput that normalises gains */
     const uint32_t *layers;     /* l */
     const uint32_t *gbatch;     /* b, global batch (kept fixed, Sec. 3) */
-    const uint32_t *mbatch;     /* micro-batch size mu; b/(d*mu) micro-batches per replica */
+    const uint32_t *mbatch;     /* micro-batch size mu; b/(d*mu*2^v) micro-batches per replica */
 } rk_jobs;
 
 /* Plan space bounds: d*t*p <= g_max, t in {1,2,4,8} and <= tp_max, p <= pp_max
- * and p | layers, (d*mu) | b.  Option masks: bit v set = value v allowed. */
+ * and p | layers, (d*mu*2^v) | b.  Option masks: bit v set = value v allowed.
+ * mu_mask: micro-batch sizes a plan may use, bit v = mu * 2^v samples (Sec. 4.1
+ * "Gradient Accumulation", Table 1: the numbers of micro-batches m and of
+ * accumulation steps a belong to the plan); 1 = only the job's own mu. */
 typedef struct {
     uint32_t g_max, tp_max, pp_max;
     uint32_t zero_mask;         /* 4 bits */
     uint32_t gc_mask;           /* 2 bits */
     uint32_t off_mask;          /* 2 bits */
+    uint32_t mu_mask;           /* 4 bits, not 0 */
 } rk_plan_bounds;
 
 /* Plan table (CSR over jobs). Buffers are caller-owned [device]; the scalar
  * fields and the optional host mirrors are written by rk_enumerate_plans. */
 typedef struct {
     uint32_t *triple_off;       /* [device] [n_jobs+1] */
-    uint32_t *triples;          /* [device] [cap_triples] packed, order g, t, p ascending */
+    uint32_t *triples;          /* [device] [cap_triples] packed, order g, t, p, v ascending */
     uint32_t *seg_off;          /* [device] [n_jobs+1] */
     uint32_t *seg_g;            /* [device] [cap_segs] GPU count of each segment */
     uint32_t *seg_first;        /* [device] [cap_segs] first triple of the segment (job-local) */

@@ -46,7 +46,7 @@ class _Grid(C.Structure):
 
 
 class _Bounds(C.Structure):
-    _fields_ = [(n, C.c_uint32) for n in ("g_max", "tp_max", "pp_max", "zero_mask", "gc_mask", "off_mask")]
+    _fields_ = [(n, C.c_uint32) for n in ("g_max", "tp_max", "pp_max", "zero_mask", "gc_mask", "off_mask", "mu_mask")]
 
 
 class _Table(C.Structure):
@@ -78,7 +78,7 @@ def _env(env):
 
 
 def _bounds(b):
-    return _Bounds(b.g_max, b.tp_max, b.pp_max, b.zero_mask, b.gc_mask, b.off_mask)
+    return _Bounds(b.g_max, b.tp_max, b.pp_max, b.zero_mask, b.gc_mask, b.off_mask, getattr(b, "mu_mask", 1))
 
 
 class _GridHolder:
@@ -122,7 +122,7 @@ def enumerate_plans(ints, bounds) -> Table:
     lib().ork_enumerate(C.c_uint32(J), _p(ints), C.byref(b), None, None, C.c_uint64(0), None, None, None,
                         C.c_uint64(0), C.byref(nt), C.byref(ns))
     triple_off = np.zeros(J + 1, np.uint32)
-    triples = np.zeros((max(nt.value, 1), 3), np.uint32)
+    triples = np.zeros((max(nt.value, 1), 4), np.uint32)
     seg_off = np.zeros(J + 1, np.uint32)
     seg_g = np.zeros(max(ns.value, 1), np.uint32)
     seg_first = np.zeros(max(ns.value, 1), np.uint32)
@@ -133,14 +133,14 @@ def enumerate_plans(ints, bounds) -> Table:
     return Table(triple_off, triples[:nt.value], seg_off, seg_g[:ns.value], seg_first[:ns.value])
 
 
-def eval_one(coef_row, ints_row, bounds, env, d, t, p, z, gc, off, c, host_bytes):
-    """One candidate -> (reason bits, dict of every intermediate term)."""
+def eval_one(coef_row, ints_row, bounds, env, d, t, p, z, gc, off, c, host_bytes, v=0):
+    """One candidate -> (reason bits, dict of every intermediate term); v = micro-batch shift of the plan."""
     cf = np.ascontiguousarray(coef_row, dtype=np.float32)
     it = np.ascontiguousarray(ints_row, dtype=np.uint32)
     terms = np.zeros(N_TERMS, np.float64)
     b, e = _bounds(bounds), _env(env)
     reason = lib().ork_eval_one(_p(cf), _p(it), C.byref(b), C.byref(e), C.c_uint32(d), C.c_uint32(t),
-                                C.c_uint32(p), C.c_uint32(z), C.c_uint32(gc), C.c_uint32(off),
+                                C.c_uint32(p), C.c_uint32(v), C.c_uint32(z), C.c_uint32(gc), C.c_uint32(off),
                                 C.c_uint32(c), C.c_float(host_bytes), _p(terms))
     return int(reason), dict(zip(TERMS, terms.tolist()))
 

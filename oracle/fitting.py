@@ -48,7 +48,7 @@ def project(theta):
     return np.where(IS_EXPONENT, np.clip(theta, 1.0, K_MAX), np.maximum(theta, 0.0))
 
 
-def predict(coef_row, ints_row, env, theta, d, t, p, option, cpus, want_t_iter=False):
+def predict(coef_row, ints_row, env, theta, d, t, p, option, cpus, want_t_iter=False, mu_shift=None):
     """Predicted throughput of the sample runs under the parameters theta (float64)."""
     cf = np.ascontiguousarray(coef_row, dtype=np.float32)
     it = np.ascontiguousarray(ints_row, dtype=np.uint32)
@@ -56,12 +56,13 @@ def predict(coef_row, ints_row, env, theta, d, t, p, option, cpus, want_t_iter=F
     assert th.shape == (N_THETA,)
     u32 = lambda a: np.ascontiguousarray(a, dtype=np.uint32)
     d, t, p, option, cpus = u32(d), u32(t), u32(p), u32(option), u32(cpus)
+    mu_shift = None if mu_shift is None else u32(mu_shift)
     n = len(d)
     thr = np.zeros(n, np.float64)
     ti = np.zeros(n, np.float64) if want_t_iter else None
     e = _env(env)
-    rc = lib().ork_predict_f64(_p(cf), _p(it), C.byref(e), _p(th), C.c_uint32(n), _p(d), _p(t), _p(p), _p(option),
-                               _p(cpus), _p(thr), _p(ti))
+    rc = lib().ork_predict_f64(_p(cf), _p(it), C.byref(e), _p(th), C.c_uint32(n), _p(d), _p(t), _p(p), _p(mu_shift),
+                               _p(option), _p(cpus), _p(thr), _p(ti))
     assert rc == 0
     return (thr, ti) if want_t_iter else thr
 

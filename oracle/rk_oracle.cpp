@@ -130,10 +130,12 @@ void memory_f32(const float *cf, const uint32_t *in, uint32_t d, uint32_t t, uin
  * varies them continuously; the float32 descriptor values convert exactly). */
 enum { TH_BWD, TH_SYNC, TH_OPT, TH_OPT_OFF, TH_OFF, TH_SWAP, TH_CONST, N_TH };
 
-uint32_t eval_candidate_th(const float *cf, const uint32_t *in, const ork_bounds *bounds,
-                           const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t z,
+uint32_t eval_candidate_th(const float *cf, const uint32_t *in_job, const ork_bounds *bounds,
+                           const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t v, uint32_t z,
                            uint32_t gc, uint32_t off, uint32_t c, float host_bytes, const double *th,
                            double *x) {
+    /* the plan's micro-batch size is the job's times 2^v */
+    const uint32_t in[N_INT] = {in_job[LAYERS], in_job[GBATCH], in_job[MBATCH] << v};
     for (int i = 0; i < ORK_N_TERMS; ++i) x[i] = 0.0;
     if (!option_valid(bounds, z, gc, off)) return 1u;
 
@@ -197,10 +199,10 @@ uint32_t eval_candidate_th(const float *cf, const uint32_t *in, const ork_bounds
 }
 
 uint32_t eval_candidate(const float *cf, const uint32_t *in, const ork_bounds *bounds,
-                        const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t z,
+                        const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t v, uint32_t z,
                         uint32_t gc, uint32_t off, uint32_t c, float host_bytes, double *x) {
     const double th[N_TH] = {cf[K_BWD], cf[K_SYNC], cf[K_OPT], cf[K_OPT_OFF], cf[K_OFF], cf[K_SWAP], cf[K_CONST]};
-    return eval_candidate_th(cf, in, bounds, env, d, t, p, z, gc, off, c, host_bytes, th, x);
+    return eval_candidate_th(cf, in, bounds, env, d, t, p, v, z, gc, off, c, host_bytes, th, x);
 }
 
 int greedy_from(uint32_t n_jobs, const float *ref_thr, const ork_table *tb, const ork_grid *grid,
@@ -264,7 +266,10 @@ double ork_f_overlap(double k, double x, double y) {
 
 /* Plan space of Sec. 3 (3D parallel sizes with d*t*p = g, Table 1) under the
  * partitioning constraints Fig. 6 alludes to: t a power of two up to tp_max,
- * p divides the layer count, d*mu divides the global batch.
+ * p divides the layer count, d*mu*2^v divides the global batch for the
+ * micro-batch shifts v that the bounds allow (Table 1 lists the number of
+ * micro-batches m and of accumulation steps a among the plan's quantities).
+ * Entries are (d, t, p, v), ordered by g, then t, p, v.
  * Pinned: brute force over [1..g]^3 in the tests; with constraints lifted the
  * count per g is the number of ordered factorisations into three factors. */
 int ork_enumerate(uint32_t n_jobs, const uint32_t *ints, const ork_bounds *bounds,
@@ -285,7 +290,9 @@ int ork_enumerate(uint32_t n_jobs, const uint32_t *ints, const ork_bounds *bound
                     if (l % p != 0) continue;
                     if (g % (t * p) != 0) continue;
                     const uint32_t d = g / (t * p);
-                    if (b % (d * mu) != 0) continue;
+                    for (uint32_t v = 0; v < 4; ++v) {
+                    if (!((bounds->mu_mask >> v) & 1u)) continue;
+                    if (mu == 0 || b % ((uint64_t)d * (mu << v)) != 0) continue;
                     if (!any) {
                         any = true;
                         if (write) {
@@ -296,10 +303,11 @@ int ork_enumerate(uint32_t n_jobs, const uint32_t *ints, const ork_bounds *bound
                     }
                     if (write) {
                         if (nt < cap_triples) {
-                            triples[nt * 3 + 0] = d; triples[nt * 3 + 1] = t; triples[nt * 3 + 2] = p;
+                            triples[nt * 4 + 0] = d; triples[nt * 4 + 1] = t; triples[nt * 4 + 2] = p; triples[nt * 4 + 3] = v;
                         } else overflow = true;
                     }
                     ++nt;
+                    }
                 }
             }
         }
@@ -311,9 +319,9 @@ int ork_enumerate(uint32_t n_jobs, const uint32_t *ints, const ork_bounds *bound
 }
 
 uint32_t ork_eval_one(const float *coef17, const uint32_t *ints3, const ork_bounds *bounds,
-                      const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t z,
+                      const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t v, uint32_t z,
                       uint32_t gc, uint32_t off, uint32_t c, float host_bytes, double *terms) {
-    return eval_candidate(coef17, ints3, bounds, env, d, t, p, z, gc, off, c, host_bytes, terms);
+    return eval_candidate(coef17, ints3, bounds, env, d, t, p, v, z, gc, off, c, host_bytes, terms);
 }
 
 /* Predicted throughput of measured runs ("samples") of one model type under
@@ -324,17 +332,19 @@ uint32_t ork_eval_one(const float *coef17, const uint32_t *ints3, const ork_boun
  * give 0.  Same arithmetic as every other evaluation here. */
 int ork_predict_f64(const float *coef17, const uint32_t *ints3, const ork_env *env, const double *th,
                     uint32_t n_samples, const uint32_t *d, const uint32_t *t, const uint32_t *p,
-                    const uint32_t *option, const uint32_t *cpus, double *thr, double *t_iter) {
-    const ork_bounds all = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xF, 0x3, 0x3};
+                    const uint32_t *mu_shift, const uint32_t *option, const uint32_t *cpus, double *thr,
+                    double *t_iter) {
+    const ork_bounds all = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xF, 0x3, 0x3, 0xF};
     double x[ORK_N_TERMS];
     for (uint32_t i = 0; i < n_samples; ++i) {
         const uint32_t o = option[i], z = o >> 2, gc = (o >> 1) & 1u, off = o & 1u;
         thr[i] = 0.0;
         if (t_iter) t_iter[i] = 0.0;
-        if (d[i] == 0 || t[i] == 0 || p[i] == 0 || o > 15u) continue;
-        if (ints3[GBATCH] % (d[i] * ints3[MBATCH]) != 0 || ints3[LAYERS] % p[i] != 0) continue;
+        const uint32_t v = mu_shift ? mu_shift[i] : 0u;
+        if (d[i] == 0 || t[i] == 0 || p[i] == 0 || o > 15u || v > 3u) continue;
+        if (ints3[GBATCH] % ((uint64_t)d[i] * (ints3[MBATCH] << v)) != 0 || ints3[LAYERS] % p[i] != 0) continue;
         if (off && cpus[i] == 0) continue;
-        const uint32_t reason = eval_candidate_th(coef17, ints3, &all, env, d[i], t[i], p[i], z, gc, off, cpus[i],
+        const uint32_t reason = eval_candidate_th(coef17, ints3, &all, env, d[i], t[i], p[i], v, z, gc, off, cpus[i],
                                                   INFINITY, th, x);
         if (reason & 1u) continue;
         thr[i] = x[X_THR];
@@ -362,13 +372,13 @@ int ork_eval_jobs(uint32_t n_jobs, const float *coef, const uint32_t *ints,
             for (uint32_t ci = 0; ci < grid->n_cpu; ++ci)
             for (uint32_t mi = 0; mi < grid->n_mem; ++mi)
             for (uint64_t tl = 0; tl < nt; ++tl) {
-                const uint32_t *tr = tb->triples + (tb->triple_off[j] + tl) * 3;
-                const uint32_t d = tr[0], t = tr[1], p = tr[2], g = d * t * p;
+                const uint32_t *tr = tb->triples + (tb->triple_off[j] + tl) * 4;
+                const uint32_t d = tr[0], t = tr[1], p = tr[2], v = tr[3], g = d * t * p;
                 for (uint32_t o = 0; o < 16; ++o) {
                     const uint32_t z = o >> 2, gc = (o >> 1) & 1u, off = o & 1u;
                     const uint32_t c = cpus_of(grid, ci, g);
                     const float hb = tier_bytes(grid, mi, g);
-                    const uint32_t reason = eval_candidate(cf, in, bounds, env, d, t, p, z, gc, off, c, hb, x);
+                    const uint32_t reason = eval_candidate(cf, in, bounds, env, d, t, p, v, z, gc, off, c, hb, x);
                     const uint64_t idx = cbase + ((ci * rows_m + mi) * nt + tl) * 16 + o;
                     thr[idx] = reason ? 0.0 : x[X_THR];
                     if (reason_out) reason_out[idx] = (uint8_t)reason;

@@ -48,11 +48,12 @@ typedef struct {
 typedef struct {
     uint32_t g_max, tp_max, pp_max;
     uint32_t zero_mask, gc_mask, off_mask;
+    uint32_t mu_mask;                 /* bit v: micro-batches of mu * 2^v samples allowed */
 } ork_bounds;
 
 typedef struct {                      /* plan table, filled by ork_enumerate */
     const uint32_t *triple_off;       /* [n_jobs+1] */
-    const uint32_t *triples;          /* [n_triples][3] = d,t,p */
+    const uint32_t *triples;          /* [n_triples][4] = d,t,p,v (v: micro-batch shift) */
     const uint32_t *seg_off;          /* [n_jobs+1] */
     const uint32_t *seg_g;            /* [n_segs] GPU count of the segment */
     const uint32_t *seg_first;        /* [n_segs] first triple (job-local) */
@@ -63,7 +64,7 @@ typedef struct { uint32_t g, c; float mem_gb; uint32_t plan; float thr; } ork_as
 /* (x^k + y^k)^(1/k), Sec. 4.3 "Modeling overlapping". */
 double ork_f_overlap(double k, double x, double y);
 
-/* Enumerate (d,t,p) triples per job in canonical order (g, then t, then p
+/* Enumerate (d,t,p,v) entries per job in canonical order (g, then t, p, v
  * ascending).  Null output buffers: only the counts are produced. Returns 0,
  * or -1 if a capacity is too small (counts still written). */
 int ork_enumerate(uint32_t n_jobs, const uint32_t *ints, const ork_bounds *bounds,
@@ -75,7 +76,7 @@ int ork_enumerate(uint32_t n_jobs, const uint32_t *ints, const ork_bounds *bound
  * (order documented in rk_oracle.cpp).  Returns the reason bits
  * (0 = feasible; 1 structural, 2 GPU memory, 4 host memory). */
 uint32_t ork_eval_one(const float *coef17, const uint32_t *ints3, const ork_bounds *bounds,
-                      const ork_env *env, uint32_t d, uint32_t t, uint32_t p,
+                      const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t v,
                       uint32_t z, uint32_t gc, uint32_t off, uint32_t c, float host_bytes,
                       double *terms);
 
@@ -85,7 +86,8 @@ uint32_t ork_eval_one(const float *coef17, const uint32_t *ints3, const ork_boun
  * coefficients come from coef17.  0 for structurally invalid samples. */
 int ork_predict_f64(const float *coef17, const uint32_t *ints3, const ork_env *env, const double *th,
                     uint32_t n_samples, const uint32_t *d, const uint32_t *t, const uint32_t *p,
-                    const uint32_t *option, const uint32_t *cpus, double *thr, double *t_iter_or_null);
+                    const uint32_t *mu_shift_or_null, const uint32_t *option, const uint32_t *cpus, double *thr,
+                    double *t_iter_or_null);
 
 /* Every candidate of jobs [job_begin, job_end): thr (0 when infeasible) and
  * optional reason bits, candidate order [job][cpu level][mem tier][plan],

@@ -36,7 +36,7 @@ class rk_jobs(C.Structure):
 
 
 class rk_plan_bounds(C.Structure):
-    _fields_ = [(n, C.c_uint32) for n in ("g_max", "tp_max", "pp_max", "zero_mask", "gc_mask", "off_mask")]
+    _fields_ = [(n, C.c_uint32) for n in ("g_max", "tp_max", "pp_max", "zero_mask", "gc_mask", "off_mask", "mu_mask")]
 
 
 class rk_plan_table(C.Structure):
@@ -122,7 +122,7 @@ def load_library():
 
 # ------------------------------------------------------------------ marshalling helpers
 def make_bounds(b) -> rk_plan_bounds:
-    return rk_plan_bounds(b.g_max, b.tp_max, b.pp_max, b.zero_mask, b.gc_mask, b.off_mask)
+    return rk_plan_bounds(b.g_max, b.tp_max, b.pp_max, b.zero_mask, b.gc_mask, b.off_mask, getattr(b, "mu_mask", 1))
 
 
 def make_grid(g) -> rk_alloc_grid:
@@ -215,7 +215,7 @@ class PlanTable:
     def unpack_triples(self) -> np.ndarray:
         """Host copy of the triples as (d, t, p) rows."""
         x = self.triples[:self.n_triples].cpu().numpy().view(np.uint32)
-        return np.stack([x & 0xFFFF, 1 << ((x >> 16) & 3), x >> 18], axis=1).astype(np.uint32)
+        return np.stack([x & 0xFFFF, 1 << ((x >> 16) & 3), (x >> 18) & 0xFFF, x >> 30], axis=1).astype(np.uint32)
 
 
 # ------------------------------------------------------------------ the C ABI, same names
@@ -350,11 +350,11 @@ def rk_schedule_round_sla(ctx, jobs: Jobs, bounds, grid, env, cluster, sla: Sla,
                                                      _ptr(total)))
 
 
-def pack_triples(d, t, p) -> np.ndarray:
-    """(d, t, p) -> the packed form of the plan table (t must be 1, 2, 4 or 8)."""
-    d, t, p = (np.asarray(a, dtype=np.uint32) for a in (d, t, p))
+def pack_triples(d, t, p, v=0) -> np.ndarray:
+    """(d, t, p, micro-batch shift v) -> the packed form of the plan table (t must be 1, 2, 4 or 8)."""
+    d, t, p, v = (np.asarray(a, dtype=np.uint32) for a in (d, t, p, v))
     log2t = np.select([t == 1, t == 2, t == 4, t == 8], [0, 1, 2, 3], default=0).astype(np.uint32)
-    return (d | (log2t << np.uint32(16)) | (p << np.uint32(18))).astype(np.uint32)
+    return (d | (log2t << np.uint32(16)) | (p << np.uint32(18)) | (v << np.uint32(30))).astype(np.uint32)
 
 
 class Samples:

@@ -3,8 +3,9 @@
 //
 // One workgroup per job.  Instead of testing every g it builds the divisor
 // lists of b/mu (data-parallel sizes) and of the layer count (pipeline sizes),
-// forms the products d*t*p <= g_max with t in {1,2,4,8}, and orders them by
-// the key (g, t, p) with a rank sort in LDS.  The counting pass also parks the
+// forms the products d*t*p <= g_max with t in {1,2,4,8} for every allowed
+// micro-batch shift v (d must divide b/(mu*2^v)), and orders them by the key
+// (g, t, p, v) with a rank sort in LDS.  The counting pass also parks the
 // sorted keys in a scratch buffer; after the exclusive scan of the counts the
 // fill pass only decodes them into place (it repeats the search only when the
 // scratch buffer was too small).
@@ -87,11 +88,18 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
         for (uint32_t c = tid; c < pairs; c += ENUM_THREADS) {
             const uint32_t p = plist[c % cp], d = dlist[c / cp];
             const uint64_t dp = (uint64_t)d * p;
+            // micro-batch shifts this d works with: mu*2^v divides b and d divides b/(mu*2^v)
+            uint32_t vmask = 0;
+            for (uint32_t v = 0; v < 4; ++v)
+                if (((bounds.mu_mask >> v) & 1u) && (n & ((1u << v) - 1u)) == 0 && ((n >> v) % d) == 0) vmask |= 1u << v;
             for (uint32_t lt = 0; lt < nlt; ++lt) {
                 const uint64_t g = dp << lt;
                 if (g <= bounds.g_max) {
-                    const uint32_t i = atomicAdd(&nk, 1u);
-                    if (i < MAX_T) keys[i] = ((uint32_t)g << 16) | (lt << 14) | p;
+                    for (uint32_t v = 0; v < 4; ++v) {
+                        if (!((vmask >> v) & 1u)) continue;
+                        const uint32_t i = atomicAdd(&nk, 1u);
+                        if (i < MAX_T) keys[i] = ((uint32_t)g << 16) | (lt << 14) | (p << 2) | v;
+                    }
                 }
             }
         }
@@ -136,9 +144,9 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     const uint32_t t0 = triple_off[j], s0 = seg_off[j];
     for (uint32_t i = lo; i < hi; ++i) {
         const uint32_t k = sorted[i];
-        const uint32_t g = k >> 16, lt = (k >> 14) & 3u, p = k & 0x3FFFu;
+        const uint32_t g = k >> 16, lt = (k >> 14) & 3u, p = (k >> 2) & 0xFFFu, v = k & 3u;
         const uint32_t d = g / (p << lt);
-        triples[t0 + i] = d | (lt << 16) | (p << 18);
+        triples[t0 + i] = d | (lt << 16) | (p << 18) | (v << 30);
         if (i == 0 || g != (sorted[i - 1] >> 16)) {
             seg_g[s0 + sidx] = g;
             seg_first[s0 + sidx] = i;
@@ -221,8 +229,9 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
     if (bounds->g_max < 1 || bounds->g_max > RK_MAX_G) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "g_max must be in 1..%u", RK_MAX_G);
     if (bounds->pp_max < 1 || bounds->pp_max > RK_MAX_PP) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "pp_max must be in 1..%u", RK_MAX_PP);
     if (bounds->tp_max < 1) return rk_fail(ctx, RK_ERR_INVALID_ARG, "tp_max below 1");
-    if (bounds->zero_mask > 0xF || bounds->gc_mask > 3 || bounds->off_mask > 3)
+    if (bounds->zero_mask > 0xF || bounds->gc_mask > 3 || bounds->off_mask > 3 || bounds->mu_mask > 0xF)
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "option mask has unknown bits");
+    if (bounds->mu_mask == 0) return rk_fail(ctx, RK_ERR_INVALID_ARG, "mu_mask allows no micro-batch size");
     RK_HIP(ctx, hipSetDevice(ctx->device));
 
     const uint32_t J = jobs->n_jobs;

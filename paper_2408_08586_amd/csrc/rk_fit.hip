@@ -62,7 +62,7 @@ __device__ Run load_run(const FitArgs &A, uint32_t j, uint32_t i) {
     const double d = RK_TRIPLE_D(packed), t = RK_TRIPLE_T(packed), p = RK_TRIPLE_P(packed);
     const uint32_t di = RK_TRIPLE_D(packed), ti = RK_TRIPLE_T(packed), pi = RK_TRIPLE_P(packed);
     const uint32_t z = o >> 2, gc = (o >> 1) & 1u, off = o & 1u;
-    const uint32_t layers = A.jobs.layers[j], gb = A.jobs.gbatch[j], mu = A.jobs.mbatch[j];
+    const uint32_t layers = A.jobs.layers[j], gb = A.jobs.gbatch[j], mu = A.jobs.mbatch[j] << RK_TRIPLE_V(packed);
     R.logy = log1p((double)A.thr[i]);
     R.valid = di > 0 && pi > 0 && o < 16u && mu > 0 && gb % (di * mu) == 0 && layers % pi == 0 && !(off && z < 2) &&
               !(off && c == 0);

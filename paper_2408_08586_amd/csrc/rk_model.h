@@ -89,9 +89,10 @@ __device__ __forceinline__ Triple triple_terms(const Job &J, const rk_env &E, ui
     const float fd = (float)T.d, ft = (float)T.t, fp = (float)T.p, ftp = (float)(T.t * T.p);
     T.fd = fd;
     T.b = (float)J.gbatch;
-    const uint32_t n = J.gbatch / (T.d * J.mbatch);          // micro-batches per replica
+    const uint32_t mb = J.mbatch << RK_TRIPLE_V(packed);     // micro-batch size of this plan
+    const uint32_t n = J.gbatch / (T.d * mb);                // micro-batches per replica
     const float fn = (float)n;
-    const float fmu = (float)J.mbatch;
+    const float fmu = (float)mb;
 
     // forward / backward of the pipeline fill + steady state, or of one accumulation step
     const float Tf_mb = fast_div(J.tfs * fmu, ftp);

@@ -494,3 +494,49 @@ def test_option_masks_and_memory_modes(gpu, orc):
     a2, t2 = run.schedule_round()
     compare_rounds(a2, t2, r)
     run.close()
+
+
+def test_micro_batch_sizes_as_a_plan_dimension(gpu, orc):
+    """Bounds that allow micro-batches of mu, 2mu, 4mu and 8mu samples (Sec. 4.1
+    "Gradient Accumulation"): table, candidates, best plans and the whole round
+    against the oracle; with only mu allowed nothing changes."""
+    import dataclasses
+    for name, mask in (("tiny", 0xF), ("paper_scale", 0xF), ("paper_scale", 0x5)):
+        base = workloads.CONFIGS[name]()
+        wl = dataclasses.replace(base, bounds=dataclasses.replace(base.bounds, mu_mask=mask))
+        ot = orc.enumerate_plans(wl.ints, wl.bounds)
+        assert np.any(ot.triples[:, 3] > 0)
+        run = gpu(wl)
+        run.enumerate()
+        oracle_table_equal(run.table_numpy(), ot)
+        je = min(wl.n_jobs, 24)
+        o_thr, o_reason = orc.eval_jobs(wl.coef, wl.ints, wl.bounds, ot, wl.grid, wl.env, 0, je, n_threads=16)
+        thr, feas, n = run.eval(0, je)
+        check_thr(run.host(thr, n), run.host(feas, n), o_thr, o_reason)
+        bt, bp, ns = run.best(thr, 0, je)
+        o_bt, o_bp = orc.best_plan(ot, wl.grid, o_thr, 0, je)
+        check_best_in_band(ot, run.n_rows, 0, je, o_thr, o_bt, o_bp, run.host(bt, ns), run.host(bp, ns).view(np.uint32))
+        fbt, fbp, fct, fcp, fcg, _ = run.fused(0, je)
+        assert np.array_equal(run.host(fbt, ns), run.host(bt, ns)) and np.array_equal(run.host(fbp, ns), run.host(bp, ns))
+        r = orc.schedule_round(wl, n_threads=16)
+        assign, total = run.schedule_round()
+        same = compare_rounds(assign, total, r)
+        # some chosen plans do use a larger micro-batch
+        sched = np.flatnonzero(assign["g"] > 0)
+        shifts = [int(ot.triples[ot.triple_off[j] + assign["plan"][j] // 16, 3]) for j in sched]
+        print(f"{name} mask {mask:#x}: assignments equal: {same}; micro-batch shifts of the chosen plans: {sorted(set(shifts))}")
+        run.close()
+    # the default mask leaves the table as it was
+    base = workloads.paper_scale()
+    wl = dataclasses.replace(base, bounds=dataclasses.replace(base.bounds, mu_mask=1))
+    run = gpu(wl)
+    run.enumerate()
+    assert np.all(run.table_numpy()["triples"][:, 3] == 0)
+    run.close()
+    import paper_2408_08586_amd as rk
+    bad = dataclasses.replace(base, bounds=dataclasses.replace(base.bounds, mu_mask=0))
+    run = gpu(bad)
+    with pytest.raises(rk.RkError) as e:
+        run.enumerate()
+    assert e.value.code == rk.RK_ERR_INVALID_ARG
+    run.close()

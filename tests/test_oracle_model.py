@@ -246,3 +246,56 @@ def test_seven_billion_on_one_gpu_needs_offload(orc):
     assert feasible and all(off == 1 for _, _, off in feasible)
     reason, x = run(orc, coef, ints, env, 1, 1, 1, z=2, gc=1, off=1, c=8, host=64 * GIB)
     assert reason == 4 and x["H_host"] == pytest.approx(7 * 14e9, rel=1e-6)
+
+
+def test_micro_batch_shift_of_a_plan(orc):
+    """Sec. 4.1 "Gradient Accumulation", Table 1 (m, a belong to the plan): a plan
+    with shift v runs micro-batches of mu * 2^v samples."""
+    env = workloads.Env(B_intra=1e11, B_inter=1e10, B_pcie=1e10, gpu_mem_cap=BIG_CAP, gpus_per_node=8)
+    spec = dict(P_bytes=4e9, seq=1024, hidden=2048, t_fwd_sample=0.002, k_bwd=2.0, k_sync=1.0, k_opt=1e-12, k_opt_off=1e-9,
+                k_off=2.0, k_swap=2.0, k_const=0.25, layers=8, gbatch=64, mbatch=2)
+    coef, ints = make_job(spec)
+    f32 = lambda x: float(np.float32(x))                    # the descriptor and the environment hold float32 values
+    tfs, k_opt, b_intra = f32(0.002), f32(1e-12), f32(1e11)
+    run_v = lambda d, t, p, v, **kw: orc.eval_one(coef, ints, BOUNDS, env, d, t, p, kw.get("z", 0), kw.get("gc", 0), 0, 1,
+                                                   BIG_CAP, v=v)[1]
+    # one GPU: a * Tf_mb is the whole batch whatever the micro-batch size, and so is the iteration time
+    for v in (0, 1, 2, 3):
+        x = run_v(1, 1, 1, v)
+        assert x["a"] == 64 / (2 * 2 ** v) and x["m"] == 1
+        assert x["Tf_mb"] == pytest.approx(tfs * 2 * 2 ** v, rel=1e-12)
+        assert x["T_iter"] == pytest.approx(64 * tfs * 3 + k_opt * 4e9 + 0.25, rel=1e-12)
+    # data parallel over 4 GPUs, no overlap (k_sync = 1): T = a*Tf + a*Tb + T_dp, again the same for every size ...
+    t_dp = 4e9 * 2 * 3 / 4 / b_intra
+    for v in (0, 1, 2):
+        x = run_v(4, 1, 1, v)
+        assert x["a"] == 16 / (2 * 2 ** v)
+        assert x["T_cc"] == pytest.approx(16 * tfs * 3 + t_dp, rel=1e-12)
+    # ... but with overlap the last backward pass hides more of the synchronisation when it is longer:
+    # T_cc = a*Tf + (a-1)*Tb + f(k; Tb, T_dp) with Tb = 2*Tf, Tf = t_fwd_sample * mu * 2^v
+    coef2, _ = make_job(dict(spec, k_sync=3.0))
+    prev = None
+    for v in (0, 1, 2):
+        x = orc.eval_one(coef2, ints, BOUNDS, env, 4, 1, 1, 0, 0, 0, 1, BIG_CAP, v=v)[1]
+        tf = tfs * 2 * 2 ** v
+        a = 16 / (2 * 2 ** v)
+        want = a * tf + (a - 1) * 2 * tf + (((2 * tf) ** 3 + t_dp ** 3) ** (1 / 3))
+        assert x["T_cc"] == pytest.approx(want, rel=1e-12)
+        assert prev is None or x["T_cc"] < prev
+        prev = x["T_cc"]
+    # pipeline: m = b / (d * mu * 2^v) micro-batches, fill + steady state (m + p - 1)
+    for v in (0, 1):
+        x = run_v(2, 1, 4, v)
+        m = 64 / (2 * 2 * 2 ** v)
+        assert x["m"] == m and x["a"] == 1
+        assert x["T_fwd"] == pytest.approx(tfs * 2 * 2 ** v / 4 * (m + 3), rel=1e-12)
+    # activations grow with the micro-batch: exact float32 bytes for powers of two (no checkpointing)
+    m0 = run_v(1, 1, 1, 0)["M_gpu"]
+    m2 = run_v(1, 1, 1, 2)["M_gpu"]
+    act0 = 34 * (2 * 1024 * 2048) * 8
+    assert m0 == 8 * 4e9 + act0 + GIB and m2 == 8 * 4e9 + 4 * act0 + GIB
+    # the shifted plan equals the unshifted plan of a job whose own micro-batch is larger, term by term
+    _, ints8 = make_job(dict(spec, mbatch=8))
+    a_ = orc.eval_one(coef, ints, BOUNDS, env, 2, 2, 2, 1, 1, 0, 1, BIG_CAP, v=2)[1]
+    b_ = orc.eval_one(coef, ints8, BOUNDS, env, 2, 2, 2, 1, 1, 0, 1, BIG_CAP, v=0)[1]
+    assert a_ == b_

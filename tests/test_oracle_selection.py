@@ -9,7 +9,7 @@ import workloads
 
 
 # ---------------------------------------------------------------- enumeration
-def brute_triples(l, b, mu, g_max, tp_max, pp_max):
+def brute_triples(l, b, mu, g_max, tp_max, pp_max, mu_mask=1):
     out = []
     for g in range(1, g_max + 1):
         found = []
@@ -20,22 +20,27 @@ def brute_triples(l, b, mu, g_max, tp_max, pp_max):
                         continue
                     if t not in (1, 2, 4, 8) or t > tp_max or p > pp_max:
                         continue
-                    if l % p or b % (d * mu):
+                    if l % p:
                         continue
-                    found.append((g, t, p, d))
+                    for v in range(4):                  # micro-batches of mu * 2^v samples
+                        if (mu_mask >> v) & 1 and b % (d * mu * 2 ** v) == 0:
+                            found.append((g, t, p, v, d))
         out += sorted(found)
-    return [(d, t, p) for g, t, p, d in out]
+    return [(d, t, p, v) for g, t, p, v, d in out]
 
 
-@pytest.mark.parametrize("g_max,tp_max,pp_max", [(8, 8, 255), (24, 4, 3), (32, 2, 255)])
-def test_enumeration_matches_brute_force(orc, g_max, tp_max, pp_max):
+@pytest.mark.parametrize("g_max,tp_max,pp_max,mu_mask", [(8, 8, 255, 1), (24, 4, 3, 1), (32, 2, 255, 1), (24, 8, 255, 0xF),
+                                                       (16, 2, 4, 0x6)])
+def test_enumeration_matches_brute_force(orc, g_max, tp_max, pp_max, mu_mask):
     ints = np.array([[12, 32, 1], [24, 64, 2], [40, 128, 4], [7, 6, 1], [32, 32, 4], [96, 48, 2]], np.uint32)
-    tb = orc.enumerate_plans(ints, workloads.Bounds(g_max=g_max, tp_max=tp_max, pp_max=pp_max))
+    tb = orc.enumerate_plans(ints, workloads.Bounds(g_max=g_max, tp_max=tp_max, pp_max=pp_max, mu_mask=mu_mask))
+    if mu_mask == 0xF:
+        assert np.any(tb.triples[:, 3] == 3) and np.any(tb.triples[:, 3] == 0)
     for j, (l, b, mu) in enumerate(ints.tolist()):
-        want = brute_triples(l, b, mu, g_max, tp_max, pp_max)
+        want = brute_triples(l, b, mu, g_max, tp_max, pp_max, mu_mask)
         got = [tuple(r) for r in tb.triples[tb.triple_off[j]:tb.triple_off[j + 1]].tolist()]
         assert got == want
-        gs = [d * t * p for d, t, p in want]
+        gs = [d * t * p for d, t, p, v in want]
         seg_g = tb.seg_g[tb.seg_off[j]:tb.seg_off[j + 1]].tolist()
         assert seg_g == sorted(set(gs))
         firsts = tb.seg_first[tb.seg_off[j]:tb.seg_off[j + 1]].tolist()
@@ -48,7 +53,7 @@ def test_enumeration_counts_ordered_factorisations(orc):
     # prod C(e_i + 2, 2) over the prime exponents -> g=1:1, 2:3, 4:6, 8:10
     ints = np.array([[840, 840 * 8, 1]], np.uint32)
     tb = orc.enumerate_plans(ints, workloads.Bounds(g_max=8))
-    g = tb.triples.prod(axis=1)
+    g = tb.triples[:, :3].prod(axis=1)
     assert [(g == v).sum() for v in (1, 2, 4, 8)] == [1, 3, 6, 10]
     # g = 6 has 9 of them, 3 of which need t in {3, 6}
     assert (g == 6).sum() == 6
@@ -71,7 +76,7 @@ def test_best_plan_matches_flat_argmax(orc, tiny_round):
         nt = int(tb.triple_off[j + 1] - tb.triple_off[j])
         ns = int(tb.seg_off[j + 1] - tb.seg_off[j])
         block = thr[16 * rows * int(tb.triple_off[j]):16 * rows * int(tb.triple_off[j + 1])].reshape(rows, nt * 16)
-        g_of_plan = np.repeat(tb.triples[tb.triple_off[j]:tb.triple_off[j + 1]].prod(axis=1), 16)
+        g_of_plan = np.repeat(tb.triples[tb.triple_off[j]:tb.triple_off[j + 1], :3].prod(axis=1), 16)
         for row in range(rows):
             for s in range(ns):
                 g = tb.seg_g[tb.seg_off[j] + s]
@@ -298,5 +303,5 @@ def test_round_invariants_on_generated_configs(orc):
         # the granted plan uses exactly the granted GPUs and is feasible there
         tb = r["table"]
         for j in np.flatnonzero(sched):
-            d, t, p = tb.triples[tb.triple_off[j] + a["plan"][j] // 16]
+            d, t, p, _ = tb.triples[tb.triple_off[j] + a["plan"][j] // 16]
             assert d * t * p == a["g"][j]

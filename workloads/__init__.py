@@ -86,6 +86,7 @@ class Bounds:
     zero_mask: int = 0xF             # bit z set: ZeRO stage z allowed
     gc_mask: int = 0x3               # bit v set: gradient checkpointing == v allowed
     off_mask: int = 0x3              # bit v set: offload == v allowed
+    mu_mask: int = 0x1               # bit v set: micro-batches of mu * 2^v samples allowed (1 = the job's own mu only)
 
 
 @dataclass
@@ -332,7 +333,7 @@ def fit_draws(n_models: int, n_samples: int = 16, n_offload: int = 5, n_restarts
 
 def fit_sample_triples(draws: FitDraws, triple_off: np.ndarray, triples: np.ndarray):
     """Map the plan positions of the draws onto a plan table (CSR offsets and
-    [n][3] unpacked triples): returns d, t, p as uint32 [J, S]."""
+    [n][3 or 4] unpacked triples): returns d, t, p as uint32 [J, S]."""
     J, S = draws.u_triple.shape
     t0 = np.asarray(triple_off[:J], np.int64)[:, None]
     nt = (np.asarray(triple_off[1:J + 1], np.int64) - np.asarray(triple_off[:J], np.int64))[:, None]
