@@ -186,6 +186,7 @@ int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bound
  * Memory estimate, float32, one rounding per operation in this order:
  *   Psi = P_bytes/(t*p); kappa = 8 | 2+6/d | 1+7/d | 8/d (ZeRO 0..3),
  *   with offload 1 (z=2) | 1/d (z=3); S = (mem_state*kappa)*Psi;
+ *   mu = the plan's micro-batch size (the job's mbatch * 2^v);
  *   tok = (mu*seq)*hidden; base = ((tok*(l/p))/t)*min(p, b/(d*mu));
  *   A = mem_act*base, or mem_act_gc*base + (mem_act*tok)/t with checkpointing;
  *   M_gpu = (S+A)+mem_const <= gpu_mem_cap;
