@@ -117,10 +117,28 @@ def what_if_batch(rk, ctx, dev, n_rounds):
         lat.append((time.perf_counter() - a) * 1e3)
     lat = np.array(lat[1:])                                     # the first call sizes the scratch buffers
     q = lambda p: float(np.percentile(lat, p))
+    # the same rounds with every distinct job listed once (nine jobs in ten are shared by all rounds)
+    swl, s_off, s_jobs, s_clusters = workloads.what_if_shared(n_rounds)
+    jobs_distinct = rk.Jobs(swl.coef, swl.ints, dev)
+    assign_s = rk.new_assign(len(s_jobs), dev)
+    totals_s = torch.zeros(n_rounds, dtype=torch.float32, device=dev)
+    shared_ms = []
+    for it in range(4):
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        rk.rk_schedule_rounds_shared(ctx, jobs_distinct, bounds, grid, env, s_off, s_jobs, clusters, assign_s, totals_s)
+        torch.cuda.synchronize()
+        if it:
+            shared_ms.append((time.perf_counter() - a) * 1e3)
+    same = bool(torch.equal(totals, totals_s)) and bool(torch.equal(assign, assign_s))
     return {"rounds": n_rounds, "jobs_per_round": rounds[0].n_jobs,
             "single_round_latency_ms": {"min": float(lat.min()), "median": q(50), "p95": q(95), "p99": q(99),
                                         "max": float(lat.max())},
-            "batch_ms": float(np.median(batch_ms)), "batch_rounds_per_s": n_rounds / (float(np.median(batch_ms)) * 1e-3)}
+            "batch_ms": float(np.median(batch_ms)), "batch_rounds_per_s": n_rounds / (float(np.median(batch_ms)) * 1e-3),
+            "shared_jobs_batch": {"entry": "rk_schedule_rounds_shared", "distinct_jobs": swl.n_jobs,
+                                  "ms": float(np.median(shared_ms)),
+                                  "rounds_per_s": n_rounds / (float(np.median(shared_ms)) * 1e-3),
+                                  "identical_to_batch": same}}
 
 
 def sla_round(rk, ctx, dev, wl, jobs, table, bounds, grid, env, cluster, best_plan, n_rows, reps):

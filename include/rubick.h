@@ -252,6 +252,19 @@ int32_t rk_schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bound
                            uint32_t n_rounds, const uint32_t *round_off, const rk_cluster *clusters,
                            rk_assign *assign, float *totals);
 
+/* Rounds that share jobs (Sec. 5.2: the curves "can be computed in parallel or
+ * even prior to the scheduling, and then cached for reuse"): round r schedules
+ * the slots [round_off[r], round_off[r+1]) and slot i stands for job
+ * round_jobs[i] of the job array (both [host]; a job may appear in any number
+ * of rounds, at most once per round).  Every job is enumerated and evaluated
+ * once.  assign [device] one record per slot, totals [device] n_rounds floats.
+ * Results per round are those of rk_schedule_round on the round's jobs in slot
+ * order. */
+int32_t rk_schedule_rounds_shared(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                                  const rk_alloc_grid *grid, const rk_env *env,
+                                  uint32_t n_rounds, const uint32_t *round_off, const uint32_t *round_jobs,
+                                  const rk_cluster *clusters, rk_assign *assign, float *totals);
+
 /* ---- service-level floors (Sec. 5.2 "Scheduling algorithm design") -------- */
 
 #define RK_MAX_TENANTS 256u

@@ -24,7 +24,7 @@ FIT_FIELDS = ("k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_con
 
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
            "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
-           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate")
+           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -415,6 +415,19 @@ def rk_simulate(ctx, ref_thr, table, grid, cluster, best_thr, best_plan, curve_t
     _check(ctx, load_library().rk_simulate(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.byref(cluster),
                                            _ptr(best_thr), _ptr(best_plan), _ptr(curve_thr), C.byref(tr), C.byref(opt),
                                            C.byref(result.c)))
+
+
+def rk_schedule_rounds_shared(ctx, jobs: Jobs, bounds, grid, env, round_off: np.ndarray, round_jobs: np.ndarray, clusters,
+                              assign, totals):
+    round_off = np.ascontiguousarray(round_off, dtype=np.uint32)
+    round_jobs = np.ascontiguousarray(round_jobs, dtype=np.uint32)
+    n_rounds = len(round_off) - 1
+    arr = (rk_cluster * n_rounds)(*clusters)
+    _check(ctx, load_library().rk_schedule_rounds_shared(ctx, C.byref(jobs.c), C.byref(bounds), C.byref(grid),
+                                                         C.byref(env), C.c_uint32(n_rounds),
+                                                         round_off.ctypes.data_as(C.c_void_p),
+                                                         round_jobs.ctypes.data_as(C.c_void_p), arr, _ptr(assign),
+                                                         _ptr(totals)))
 
 
 # ------------------------------------------------------------------ allocation helpers (no arithmetic)

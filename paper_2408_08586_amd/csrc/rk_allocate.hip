@@ -100,10 +100,14 @@ struct Ctx {                 // what every kernel of the allocation needs
     GridDev grid;
     RoundArgs R;
     uint32_t jb;             // first job of the call (origin of the segment-layout arrays)
+    const uint32_t *jmap;    // optional: the job whose curves slot j of the call uses (rounds that share jobs)
     const float *best_thr;
     const uint32_t *best_plan;
     const float *curve_thr;
 };
+
+// The job whose plan table, curves and reference throughput slot j uses.
+__device__ __forceinline__ uint32_t job_of(const Ctx &X, uint32_t j) { return X.jmap ? X.jmap[j] : j; }
 
 __device__ __forceinline__ void round_of(const RoundArgs &R, uint32_t r, uint32_t &j0, uint32_t &j1, rk_cluster &cl) {
     if (R.inline_one) { j0 = R.off0; j1 = R.off1; cl = R.cl; }
@@ -171,9 +175,10 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
     const GridDev &grid = X.grid;
     const float *__restrict__ vals = PASS == 0 ? X.curve_thr : X.best_thr;
     const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem;
-    const uint32_t s0 = X.tb.seg_off[j], ns = X.tb.seg_off[j + 1] - s0;
+    const uint32_t ju = job_of(X, j);
+    const uint32_t s0 = X.tb.seg_off[ju], ns = X.tb.seg_off[ju + 1] - s0;
     const uint64_t jbase = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]);
-    const float ref = X.ref_thr[j];
+    const float ref = X.ref_thr[ju];
 
     uint32_t npts, g_fixed = 0, c_fixed = 0;
     int32_t cur_i;
@@ -404,9 +409,10 @@ __device__ __forceinline__ Step best_step(const Ctx &X, uint32_t j, int32_t gi, 
                                           unsigned long long freeG, unsigned long long freeC) {
     const GridDev &grid = X.grid;
     const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem, m_top = n_mem - 1;
-    const uint32_t s0 = X.tb.seg_off[j], ns = X.tb.seg_off[j + 1] - s0;
+    const uint32_t ju = job_of(X, j);
+    const uint32_t s0 = X.tb.seg_off[ju], ns = X.tb.seg_off[ju + 1] - s0;
     const uint64_t jbase = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]);
-    const float ref = X.ref_thr[j];
+    const float ref = X.ref_thr[ju];
     Step out = {0.f, 0u, 0u};
     if (PASS == 0) {
         const uint32_t g_cur = gi < 0 ? 0u : X.tb.seg_g[s0 + gi];
@@ -483,7 +489,7 @@ __device__ __forceinline__ void apply_job(const Ctx &X, const JobState &st, cons
         }
         if (k == width) key = 0;
         if (PASS == 0) {
-            g_held = gi < 0 ? 0u : X.tb.seg_g[X.tb.seg_off[j] + gi];
+            g_held = gi < 0 ? 0u : X.tb.seg_g[X.tb.seg_off[job_of(X, j)] + gi];
             st.gi[jrel] = gi;
             st.g[jrel] = g_held;
         }
@@ -622,7 +628,7 @@ __device__ __forceinline__ void tail_run(const Ctx &X, const JobState &st, uint3
             if (PASS == 0) {
                 const int32_t s_i = gi[jl];
                 st.gi[jrel0 + jl] = s_i;
-                st.g[jrel0 + jl] = s_i < 0 ? 0u : X.tb.seg_g[X.tb.seg_off[J0 + jl] + s_i];
+                st.g[jrel0 + jl] = s_i < 0 ? 0u : X.tb.seg_g[X.tb.seg_off[job_of(X, J0 + jl)] + s_i];
             } else {
                 st.ci[jrel0 + jl] = ci[jl];
             }
@@ -709,7 +715,8 @@ __global__ __launch_bounds__(JOB_THREADS) void k_mem_wish(Ctx X, JobState st, rk
         const int32_t gi = st.gi[jrel];
         if (gi >= 0) {
             const uint32_t g = st.g[jrel], c_lvl = st.ci[jrel];
-            const uint32_t s0 = X.tb.seg_off[j], ns = X.tb.seg_off[j + 1] - s0;
+            const uint32_t ju = job_of(X, j);
+            const uint32_t s0 = X.tb.seg_off[ju], ns = X.tb.seg_off[ju + 1] - s0;
             const uint64_t base = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]) + (uint64_t)(c_lvl * n_mem) * ns + gi;
             float bv = 0.f;
             uint32_t bm = 0;
@@ -726,7 +733,7 @@ __global__ __launch_bounds__(JOB_THREADS) void k_mem_wish(Ctx X, JobState st, rk
                 out.plan = X.best_plan[base + (uint64_t)bm * ns];
                 out.thr = bv;
                 cost_d = (double)cost;
-                val_d = (double)bv / (double)X.ref_thr[j];
+                val_d = (double)bv / (double)X.ref_thr[job_of(X, j)];
             }
         }
         assign[jrel] = out;
@@ -781,8 +788,9 @@ __global__ __launch_bounds__(64) void k_mem_finish(Ctx X, JobState st, rk_assign
         if (have) {
             const uint32_t j = J0 + jl;
             g = st.g[jrel0 + jl]; c_lvl = st.ci[jrel0 + jl];
-            const uint32_t s0 = X.tb.seg_off[j];
-            ns = X.tb.seg_off[j + 1] - s0;
+            const uint32_t ju = job_of(X, j);
+            const uint32_t s0 = X.tb.seg_off[ju];
+            ns = X.tb.seg_off[ju + 1] - s0;
             at0 = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]) + (uint64_t)(c_lvl * n_mem) * ns + (uint32_t)st.gi[jrel0 + jl];
             float bv = 0.f;
             uint32_t bm = 0;
@@ -820,7 +828,7 @@ __global__ __launch_bounds__(64) void k_mem_finish(Ctx X, JobState st, rk_assign
                     out.mem_gb = cost;
                     out.plan = X.best_plan[at0 + (uint64_t)bm * ns];
                     out.thr = v;
-                    sum += (double)v / (double)X.ref_thr[J0 + jl];
+                    sum += (double)v / (double)X.ref_thr[job_of(X, J0 + jl)];
                 }
             }
             spent = __shfl(spent, (int)turn, 64);
@@ -1000,9 +1008,11 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
                            uint32_t n_rounds, const uint32_t *d_round_off, const rk_cluster *d_clusters,
                            const rk_cluster *one_cluster, uint32_t jb, uint32_t n_jobs, uint32_t max_jobs,
                            uint32_t max_segs_per_job, const float *best_thr, const uint32_t *best_plan,
-                           const float *curve_thr, const SlaDev *sla, const FloorsDev *given, rk_assign *assign,
-                           float *totals) {
+                           const float *curve_thr, const SlaDev *sla, const FloorsDev *given, const uint32_t *d_jmap,
+                           rk_assign *assign, float *totals) {
     if (n_rounds == 0) return RK_OK;
+    if (d_jmap && (sla || given || jb != 0))
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "rounds that share jobs take neither floors nor a job range");
     if (max_jobs > RK_MAX_JOBS_PER_ROUND)
         return rk_fail(ctx, RK_ERR_UNSUPPORTED, "a round has %u jobs, the allocation kernels take up to %u", max_jobs,
                        RK_MAX_JOBS_PER_ROUND);
@@ -1044,7 +1054,7 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
     if ((rc = scratch_typed(ctx, SL_HIST_C, hist_bins, &hist.c))) return rc;
 
     Ctx X;
-    X.ref_thr = ref_thr; X.tb = tb; X.grid = grid_dev(grid); X.jb = jb;
+    X.ref_thr = ref_thr; X.tb = tb; X.grid = grid_dev(grid); X.jb = jb; X.jmap = d_jmap;
     X.best_thr = best_thr; X.best_plan = best_plan; X.curve_thr = curve_thr;
     X.R.round_off = d_round_off; X.R.clusters = d_clusters; X.R.n_rounds = n_rounds;
     X.R.inline_one = one_cluster ? 1u : 0u;
@@ -1108,7 +1118,8 @@ extern "C" int32_t rk_allocate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
     if (table->max_segs_per_job > 32767u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 32767 segments per job");
     RK_HIP(ctx, hipSetDevice(ctx->device));
     return rk_launch_allocate(ctx, ref_thr, table_dev(table), grid, 1, nullptr, nullptr, cluster, jb, je - jb, je - jb,
-                              table->max_segs_per_job, best_thr, best_plan, curve_thr, nullptr, nullptr, assign, total);
+                              table->max_segs_per_job, best_thr, best_plan, curve_thr, nullptr, nullptr, nullptr, assign,
+                              total);
 }
 
 int32_t rk_check_sla(rk_ctx *ctx, const rk_sla *sla, bool need_request) {
@@ -1142,5 +1153,5 @@ extern "C" int32_t rk_allocate_sla(rk_ctx *ctx, const float *ref_thr, const rk_p
     if (je > jb) S = SlaDev{sla->guaranteed, sla->tenant, min_seg, min_c, sla->n_tenants, sla->quota_g, sla->quota_c};
     return rk_launch_allocate(ctx, ref_thr, table_dev(table), grid, 1, nullptr, nullptr, cluster, jb, je - jb, je - jb,
                               table->max_segs_per_job, best_thr, best_plan, curve_thr, je > jb ? &S : nullptr, nullptr,
-                              assign, total);
+                              nullptr, assign, total);
 }

@@ -38,7 +38,8 @@ enum {
     SL_PARK,                                             // enumeration: sorted keys between its two passes
     SL_FL_GI, SL_FL_CI, SL_FL_WAITS, SL_FL_CAP0,         // service-level floors of the allocation
     SL_MIN_SEG, SL_MIN_C, SL_MIN_M,                      // minimum demands of a round
-    SL_SIM_STATE, SL_SIM_ASSIGN                          // simulation: per-job state, the tick's assignment
+    SL_SIM_STATE, SL_SIM_ASSIGN,                         // simulation: per-job state, the tick's assignment
+    SL_JMAP                                              // rounds that share jobs: slot -> job
 };
 
 int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);
@@ -111,12 +112,14 @@ int32_t rk_launch_fused(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *t
 // kernel arguments; otherwise n_rounds rounds described by the device arrays.
 // sla != NULL: service-level floors first (the quotas apply to every round alike);
 // given != NULL: the floors are there already.
+// d_jmap != NULL: slot j of the call (rounds, state, results are in slots) uses the plan table, curves and
+// reference throughput of job d_jmap[j]; the curve arrays then cover the whole table from job 0.
 int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb, const rk_alloc_grid *grid,
                            uint32_t n_rounds, const uint32_t *d_round_off, const rk_cluster *d_clusters,
                            const rk_cluster *one_cluster, uint32_t jb, uint32_t n_jobs, uint32_t max_jobs,
                            uint32_t max_segs_per_job, const float *best_thr, const uint32_t *best_plan,
-                           const float *curve_thr, const SlaDev *sla, const FloorsDev *given, rk_assign *assign,
-                           float *totals);
+                           const float *curve_thr, const SlaDev *sla, const FloorsDev *given, const uint32_t *d_jmap,
+                           rk_assign *assign, float *totals);
 // minimum demands of the guaranteed jobs of [jb, je)
 int32_t rk_launch_min_res(rk_ctx *ctx, const TableDev &tb, const rk_alloc_grid *grid, uint32_t jb, uint32_t je,
                           const float *best_thr, const rk_sla *sla, int32_t *min_seg, uint32_t *min_c,

@@ -7,11 +7,12 @@
 
 namespace {
 
-// sla == NULL: every job is best-effort
+// sla == NULL: every job is best-effort.  round_jobs != NULL: the rounds are made of slots, slot i
+// schedules job round_jobs[i]; every job is enumerated and evaluated once however many slots use it.
 int32_t schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
                         const rk_alloc_grid *grid, const rk_env *env, uint32_t n_rounds,
-                        const uint32_t *round_off, const rk_cluster *clusters, const rk_sla *sla,
-                        rk_assign *assign, float *totals) {
+                        const uint32_t *round_off, const uint32_t *round_jobs, const rk_cluster *clusters,
+                        const rk_sla *sla, rk_assign *assign, float *totals) {
     int32_t rc;
     if (!jobs || !bounds || !round_off || !clusters || !totals || (!assign && jobs->n_jobs > 0))
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
@@ -21,7 +22,14 @@ int32_t schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *
     if (n_rounds == 0) return RK_OK;
     const uint32_t J = jobs->n_jobs;
     uint32_t max_jobs = 0;
-    if (round_off[0] != 0 || round_off[n_rounds] != J) return rk_fail(ctx, RK_ERR_INVALID_ARG, "round_off must run from 0 to n_jobs");
+    const uint32_t n_slots = round_off[n_rounds];
+    if (round_off[0] != 0 || (!round_jobs && n_slots != J))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "round_off must run from 0 to n_jobs");
+    if (round_jobs) {
+        if (sla) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "rounds that share jobs take no service levels");
+        for (uint32_t i = 0; i < n_slots; ++i)
+            if (round_jobs[i] >= J) return rk_fail(ctx, RK_ERR_INVALID_ARG, "round_jobs[%u] = %u is not a job", i, round_jobs[i]);
+    }
     for (uint32_t r = 0; r < n_rounds; ++r) {
         if (round_off[r + 1] < round_off[r]) return rk_fail(ctx, RK_ERR_INVALID_ARG, "round_off not ascending");
         const uint32_t n = round_off[r + 1] - round_off[r];
@@ -37,6 +45,11 @@ int32_t schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *
     // A single round travels in the kernel arguments instead.
     const size_t off_bytes = (((size_t)n_rounds + 1) * 4 + 15) & ~(size_t)15;
     char *d_meta = nullptr;
+    uint32_t *d_jmap = nullptr;
+    if (round_jobs && n_slots > 0) {
+        if ((rc = rk_scratch(ctx, SL_JMAP, (size_t)n_slots * 4, (void **)&d_jmap))) return rc;
+        RK_HIP(ctx, hipMemcpyAsync(d_jmap, round_jobs, (size_t)n_slots * 4, hipMemcpyHostToDevice, ctx->stream));
+    }
     if (n_rounds > 1) {
         if ((rc = rk_scratch(ctx, SL_ROUND_META, off_bytes + (size_t)n_rounds * sizeof(rk_cluster), (void **)&d_meta))) return rc;
         RK_HIP(ctx, hipMemcpyAsync(d_meta, round_off, ((size_t)n_rounds + 1) * 4, hipMemcpyHostToDevice, ctx->stream));
@@ -89,8 +102,9 @@ int32_t schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *
     return rk_launch_allocate(ctx, jobs->ref_thr, table_dev(&tb), grid, n_rounds,
                               reinterpret_cast<const uint32_t *>(d_meta),
                               d_meta ? reinterpret_cast<const rk_cluster *>(d_meta + off_bytes) : nullptr,
-                              n_rounds == 1 ? &clusters[0] : nullptr, 0, J, max_jobs, tb.max_segs_per_job,
-                              best_thr, best_plan, curve_thr, (sla && J > 0) ? &S : nullptr, nullptr, assign, totals);
+                              n_rounds == 1 ? &clusters[0] : nullptr, 0, round_jobs ? n_slots : J, max_jobs,
+                              tb.max_segs_per_job, best_thr, best_plan, curve_thr, (sla && J > 0) ? &S : nullptr, nullptr,
+                              d_jmap, assign, totals);
 }
 
 }  // namespace
@@ -102,7 +116,16 @@ int32_t rk_schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bound
                            const uint32_t *round_off, const rk_cluster *clusters, rk_assign *assign,
                            float *totals) {
     if (!ctx) return RK_ERR_INVALID_ARG;
-    return schedule_rounds(ctx, jobs, bounds, grid, env, n_rounds, round_off, clusters, nullptr, assign, totals);
+    return schedule_rounds(ctx, jobs, bounds, grid, env, n_rounds, round_off, nullptr, clusters, nullptr, assign, totals);
+}
+
+int32_t rk_schedule_rounds_shared(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                                  const rk_alloc_grid *grid, const rk_env *env, uint32_t n_rounds,
+                                  const uint32_t *round_off, const uint32_t *round_jobs, const rk_cluster *clusters,
+                                  rk_assign *assign, float *totals) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    if (!round_jobs) return rk_fail(ctx, RK_ERR_INVALID_ARG, "round_jobs is null");
+    return schedule_rounds(ctx, jobs, bounds, grid, env, n_rounds, round_off, round_jobs, clusters, nullptr, assign, totals);
 }
 
 int32_t rk_schedule_round(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
@@ -111,7 +134,7 @@ int32_t rk_schedule_round(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds
     if (!ctx) return RK_ERR_INVALID_ARG;
     if (!jobs || !cluster) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
     const uint32_t off[2] = {0u, jobs->n_jobs};
-    return schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, cluster, nullptr, assign, total);
+    return schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, nullptr, cluster, nullptr, assign, total);
 }
 
 int32_t rk_schedule_round_sla(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
@@ -122,7 +145,8 @@ int32_t rk_schedule_round_sla(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bo
     int32_t rc;
     if (jobs->n_jobs > 0 && (rc = rk_check_sla(ctx, sla, true))) return rc;
     const uint32_t off[2] = {0u, jobs->n_jobs};
-    return schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, cluster, jobs->n_jobs > 0 ? sla : nullptr, assign, total);
+    return schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, nullptr, cluster, jobs->n_jobs > 0 ? sla : nullptr, assign,
+                           total);
 }
 
 }  // extern "C"

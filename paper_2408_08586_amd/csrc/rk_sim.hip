@@ -237,7 +237,7 @@ extern "C" int32_t rk_simulate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
         ctx->stream = s;                                       // the allocation enqueues on the context's stream
         const int32_t r = rk_launch_allocate(ctx, ref_thr, A.tb, grid, 1, nullptr, nullptr, cluster, 0, J, J,
                                              table->max_segs_per_job, best_thr, best_plan, curve_thr, nullptr, &A.F,
-                                             assign, A.tick_total);
+                                             nullptr, assign, A.tick_total);
         ctx->stream = user;
         if (r) return r;
         k_sim_commit<<<(J + COMMIT_THREADS - 1) / COMMIT_THREADS, COMMIT_THREADS, 0, s>>>(A);

@@ -426,6 +426,54 @@ def test_schedule_rounds_batch_what_if(gpu, orc):
     run.close()
 
 
+def test_rounds_that_share_jobs(gpu, orc):
+    """The same what-if rounds with every distinct job listed once: record for
+    record what the concatenated batch gives, and the oracle's rounds."""
+    import paper_2408_08586_amd as rk
+    import torch
+    n_rounds, n_jobs = 6, 120
+    wl, round_off, round_jobs, clusters = workloads.what_if_shared(n_rounds, n_jobs=n_jobs)
+    assert wl.n_jobs == n_jobs + n_rounds * (n_jobs // 10)
+    run = gpu(wl)
+    assign = rk.new_assign(n_rounds * n_jobs)
+    totals = torch.zeros(n_rounds, dtype=torch.float32, device="cuda:0")
+    c_clusters = [rk.make_cluster(c) for c in clusters]
+    rk.rk_schedule_rounds_shared(run.ctx, run.jobs, run.bounds, run.grid, run.env, round_off, round_jobs, c_clusters,
+                                 assign, totals)
+    rk.rk_sync(run.ctx)
+    a = rk.assign_to_numpy(assign)
+    # the concatenated batch on the same context
+    rounds = [workloads.what_if(i, n_jobs=n_jobs) for i in range(n_rounds)]
+    cat = workloads.Workload("batch", np.concatenate([w.coef for w in rounds]), np.concatenate([w.ints for w in rounds]),
+                             wl.bounds, wl.grid, wl.env, wl.cluster)
+    run2 = gpu(cat)
+    assign2 = rk.new_assign(n_rounds * n_jobs)
+    totals2 = torch.zeros(n_rounds, dtype=torch.float32, device="cuda:0")
+    rk.rk_schedule_rounds(run2.ctx, run2.jobs, run2.bounds, run2.grid, run2.env, round_off, c_clusters, assign2, totals2)
+    rk.rk_sync(run2.ctx)
+    assert np.array_equal(a, rk.assign_to_numpy(assign2)) and torch.equal(totals, totals2)
+    for i, w in enumerate(rounds):
+        compare_rounds(a[i * n_jobs:(i + 1) * n_jobs], float(totals[i].item()), orc.schedule_round(w, n_threads=8))
+    # a round may be empty, a job may serve no round at all; a bad index is an error
+    off2 = np.array([0, 0, 5, 5], np.uint32)
+    jobs2 = np.array([7, 3, 150, 3 + n_jobs, 0], np.uint32)
+    assign3 = rk.new_assign(5)
+    totals3 = torch.zeros(3, dtype=torch.float32, device="cuda:0")
+    rk.rk_schedule_rounds_shared(run.ctx, run.jobs, run.bounds, run.grid, run.env, off2, jobs2, c_clusters[:3], assign3, totals3)
+    rk.rk_sync(run.ctx)
+    sub = wl.subset(jobs2)
+    sub.cluster = clusters[1]
+    r = orc.schedule_round(sub, n_threads=4)
+    compare_rounds(rk.assign_to_numpy(assign3), float(totals3[1].item()), r)
+    assert float(totals3[0].item()) == 0.0 and float(totals3[2].item()) == 0.0
+    with pytest.raises(rk.RkError) as e:
+        rk.rk_schedule_rounds_shared(run.ctx, run.jobs, run.bounds, run.grid, run.env, off2,
+                                     np.array([7, 3, wl.n_jobs, 1, 0], np.uint32), c_clusters[:3], assign3, totals3)
+    assert e.value.code == rk.RK_ERR_INVALID_ARG
+    run.close()
+    run2.close()
+
+
 def test_edge_cases(gpu, orc):
     import paper_2408_08586_amd as rk
     base = workloads.tiny()

@@ -259,7 +259,35 @@ def what_if(round_index: int, seed: int = BASE_SEED, n_jobs: int = 500) -> Workl
     C = int(round(8192 * (1.0 + (uc - 0.5) * 0.5)))
     return Workload(f"what_if[{r}]", coef, ints, Bounds(g_max=512),
                     Grid(_RATIOS.copy(), 1, np.array([2048.0], np.float32), 0),
-                    Env(), Cluster(G, C, 64 * 2048.0), {"round": r})
+                    Env(), Cluster(G, C, 64 * 2048.0), {"round": r, "redrawn": np.sort(order[:n_redraw])})
+
+
+def what_if_shared(n_rounds: int, seed: int = BASE_SEED, n_jobs: int = 500):
+    """The same what-if rounds with every distinct job listed once: the jobs that
+    a round does not redraw are the base jobs.  Returns (workload of the distinct
+    jobs, round_off, round_jobs, clusters): slot i of round r is job
+    round_jobs[round_off[r] + i], and what_if(r) equals the distinct jobs gathered
+    by that slice."""
+    ids = np.arange(n_jobs)
+    base_coef, base_ints = draw_jobs(seed, 5, 0, ids, **_BIG)
+    coefs, ints, round_jobs, clusters = [base_coef], [base_ints], [], []
+    n_distinct = n_jobs
+    first = None
+    for r in range(n_rounds):
+        w = what_if(r, seed, n_jobs)
+        first = first or w
+        red = w.meta["redrawn"]
+        slots = ids.copy()
+        slots[red] = n_distinct + np.arange(len(red))
+        n_distinct += len(red)
+        coefs.append(w.coef[red])
+        ints.append(w.ints[red])
+        round_jobs.append(slots)
+        clusters.append(w.cluster)
+    wl = Workload("what_if[shared]", np.concatenate(coefs), np.concatenate(ints), first.bounds, first.grid, first.env,
+                  first.cluster)
+    round_off = np.arange(n_rounds + 1, dtype=np.uint32) * n_jobs
+    return wl, round_off, np.concatenate(round_jobs).astype(np.uint32), clusters
 
 
 @dataclass
