@@ -118,3 +118,32 @@ def test_simulation_edge_cases(gpu, orc):
                            f64(np.ones(J)), f64(np.ones(J)), dt, 4, gate, res)
         assert e.value.code == rk.RK_ERR_INVALID_ARG
     run.close()
+
+
+def test_simulation_with_more_jobs_than_one_workgroup_selects(gpu, orc):
+    """3,000 jobs per tick: the allocation takes its multi-workgroup path, with
+    inactive and frozen jobs in it."""
+    wl = workloads.stress(n_jobs=3000)
+    wl.cluster = workloads.Cluster(1024, 128 * 128, 128 * 2048.0)
+    ot = orc.enumerate_plans(wl.ints, wl.bounds)
+    bts, bps = [], []
+    for jb in range(0, wl.n_jobs, 500):
+        thr, _ = orc.eval_jobs(wl.coef, wl.ints, wl.bounds, ot, wl.grid, wl.env, jb, jb + 500, want_reason=False, n_threads=16)
+        bt, bp = orc.best_plan(ot, wl.grid, thr, jb, jb + 500)
+        bts.append(bt.astype(np.float32))
+        bps.append(bp)
+    bt, bp = np.concatenate(bts), np.concatenate(bps)
+    ct, _, _ = orc.curves(ot, wl.grid, bt, bp)
+    r = dict(table=ot, best_thr=bt, best_plan=bp, curve_thr=ct)
+    tr = workloads.trace(wl.n_jobs, horizon_s=1800.0)
+    work = workloads.job_lengths_s(tr.u_duration) * wl.coef[:, 16] * 0.2
+    n_ticks, dt = 24, 120.0
+    want = orc.simulator.simulate(wl.coef[:, 16], ot, wl.grid, wl.cluster, bt, bp, ct, tr.arrival, work, tr.delta, dt, n_ticks)
+    run = gpu(wl)
+    run.enumerate()
+    got = run_on_gpu(run, r, tr.arrival, work, tr.delta, dt, n_ticks, 0.97)
+    same(got, want)
+    print(f"3000 jobs: {int((want['finish'] >= 0).sum())} finish, {int(want['n_reconf'].sum())} reconfigurations, "
+          f"{int(want['frozen'].sum())} frozen job-ticks, GPUs in use at the end {int(want['gpus_in_use'][-1])}")
+    assert want["frozen"].sum() > 0 and (want["finish"] >= 0).sum() > 0
+    run.close()
