@@ -218,6 +218,11 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
         return cost <= cap_c;
     };
 
+    // the first 64 amounts stay in registers over the whole walk (most jobs have no more)
+    unsigned long long cost0 = 0;
+    float val0 = 0.f;
+    if (lane < npts) { cost0 = cost_of(lane); val0 = value_of(lane); }
+
     uint32_t k = 0;
     float prev = __uint_as_float(0x7F800000u);
     while (k < H.width) {
@@ -225,9 +230,9 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
         for (uint32_t base = 0; base < npts; base += 64) {
             const uint32_t s = base + lane;
             if (s < npts && (int32_t)s > cur_i) {
-                const unsigned long long cost = cost_of(s);
+                const unsigned long long cost = base == 0 ? cost0 : cost_of(s);
                 if (affordable(cost)) {
-                    const float v = value_of(s);
+                    const float v = base == 0 ? val0 : value_of(s);
                     if (v > cur) {
                         float sl = (v - cur) / ref;
                         sl = sl / (float)(cost - cost_cur);
@@ -241,7 +246,17 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
         if (!(best >> 32)) break;
         const float top = __uint_as_float((uint32_t)(best >> 32));
         const uint32_t top_s = 0xFFFFFFFFu - (uint32_t)best;
-        const unsigned long long top_cost = cost_of(top_s);
+        // cost and value of the chosen amount: from its lane's registers when it is among the first 64
+        unsigned long long top_cost;
+        float top_val;
+        if (top_s < 64u) {
+            top_cost = ((unsigned long long)__shfl((int)(cost0 >> 32), (int)top_s, 64) << 32) |
+                       (unsigned int)__shfl((int)(uint32_t)cost0, (int)top_s, 64);
+            top_val = __shfl(val0, (int)top_s, 64);
+        } else {
+            top_cost = cost_of(top_s);
+            top_val = value_of(top_s);
+        }
         prev = top < prev ? top : prev;
         if (lane == 0) {
             const size_t e = (size_t)k * H.stride + jrel;
@@ -256,7 +271,7 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
                 H.dc[e] = top_cost - cost_cur;
             }
         }
-        cur = value_of(top_s);
+        cur = top_val;
         cur_i = (int32_t)top_s;
         cost_cur = top_cost;
         ++k;
