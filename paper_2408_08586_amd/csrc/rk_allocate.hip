@@ -22,7 +22,8 @@
 //           next step (the walk's next step if it still fits, otherwise a fresh
 //           search within the capacity that is left).
 //  k_tail   the plain step-by-step loop on the little capacity that is left:
-//           one workgroup per round, argmax over the cached steps in LDS.
+//           one workgroup per round, argmax over the cached steps, which each
+//           thread keeps in registers for the jobs it owns.
 //
 // Memory (k_mem_wish / k_mem_finish): when the tiers every job would like fit
 // with margin, all are granted in parallel; otherwise one wavefront takes the
@@ -38,7 +39,6 @@
 namespace {
 
 constexpr int TAIL_THREADS = 1024;
-constexpr int TAIL_WAVES = TAIL_THREADS / 64;
 constexpr int HULL_THREADS = 256;
 constexpr int JOB_THREADS = 256;           // kernels with one thread per job
 constexpr uint32_t BINS = 4096;            // 12 key bits per histogram level
@@ -134,6 +134,34 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
         v = o > v ? o : v;
     }
     return v;
+}
+
+template <int CTRL>
+__device__ __forceinline__ unsigned long long dpp_u64(unsigned long long v) {
+    const uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    const uint32_t l2 = (uint32_t)__builtin_amdgcn_update_dpp((int)lo, (int)lo, CTRL, 0xF, 0xF, false);
+    const uint32_t h2 = (uint32_t)__builtin_amdgcn_update_dpp((int)hi, (int)hi, CTRL, 0xF, 0xF, false);
+    return ((unsigned long long)h2 << 32) | l2;
+}
+
+// The same maximum when all 64 lanes are active: within each row of 16 lanes
+// by data-parallel-primitive moves (neighbour, neighbour pair, mirrored halves
+// of 8, mirrored halves of 16), then the four rows through scalar registers.
+__device__ __forceinline__ unsigned long long wave_max_u64_rows(unsigned long long v) {
+    unsigned long long o;
+    o = dpp_u64<0xB1>(v);  v = o > v ? o : v;                   // quad_perm [1,0,3,2]
+    o = dpp_u64<0x4E>(v);  v = o > v ? o : v;                   // quad_perm [2,3,0,1]
+    o = dpp_u64<0x141>(v); v = o > v ? o : v;                   // row_half_mirror
+    o = dpp_u64<0x140>(v); v = o > v ? o : v;                   // row_mirror
+    unsigned long long m = 0;
+#pragma unroll
+    for (int r = 0; r < 64; r += 16) {
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, r);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), r);
+        const unsigned long long row = ((unsigned long long)hi << 32) | lo;
+        m = row > m ? row : m;
+    }
+    return m;
 }
 
 __device__ __forceinline__ double wave_sum_f64(double v) {
@@ -543,50 +571,155 @@ __global__ __launch_bounds__(JOB_THREADS) void k_apply(Ctx X, JobState st, HullB
 }
 
 // ------------------------------------------------------------------ step by step on what is left
-// workgroup-wide maximum of a key; every thread gets the result
-__device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v, unsigned long long *red) {
-    v = wave_max_u64(v);
-    if ((threadIdx.x & 63u) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    unsigned long long m = red[0];
-#pragma unroll
-    for (int w = 1; w < TAIL_WAVES; ++w) m = red[w] > m ? red[w] : m;
-    __syncthreads();
-    return m;
+// The same search as best_step, by a whole wavefront: every lane passes the
+// same arguments and gets the same result.  Lanes take one candidate target
+// each, so the loads of a job's amounts and values go out together instead of
+// one after the other.
+template <int PASS>
+__device__ __forceinline__ Step best_step_wave(const Ctx &X, uint32_t j, int32_t gi, uint32_t g_held, uint32_t ci,
+                                               unsigned long long freeG, unsigned long long freeC) {
+    const GridDev &grid = X.grid;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem, m_top = n_mem - 1;
+    const uint32_t ju = job_of(X, j);
+    const uint32_t s0 = X.tb.seg_off[ju], ns = X.tb.seg_off[ju + 1] - s0;
+    const uint64_t jbase = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]);
+    const float ref = X.ref_thr[ju];
+    unsigned long long mine = 0;                                // (slope bits, inverted target): lowest target wins ties
+    uint32_t mine_dg = 0;
+    if (PASS == 0) {
+        const uint32_t g_cur = gi < 0 ? 0u : X.tb.seg_g[s0 + gi];
+        const uint64_t row = jbase + (uint64_t)(ci * n_mem + m_top) * ns;
+        const float cur = gi < 0 ? 0.f : X.curve_thr[row + gi];
+        const unsigned long long c_cur = gi < 0 ? 0ull : cpu_cost(grid, ci, g_cur);
+        for (uint32_t b = (uint32_t)(gi + 1); b < ns; b += 64) {
+            const uint32_t s = b + lane;
+            const bool in = s < ns;
+            uint32_t dg = 0;
+            float v = 0.f;
+            if (in) { dg = X.tb.seg_g[s0 + s] - g_cur; v = X.curve_thr[row + s]; }
+            const bool fits = in && dg <= freeG;
+            if (fits && v > cur && cpu_cost(grid, ci, g_cur + dg) - c_cur <= freeC) {
+                float sl = (v - cur) / ref;
+                sl = sl / (float)dg;
+                const unsigned long long key = ((unsigned long long)__float_as_uint(sl) << 32) | (0xFFFFFFFFu - s);
+                if (key > mine) { mine = key; mine_dg = dg; }
+            }
+            if (__ballot(in && !fits)) break;                   // amounts ascend: nothing further on fits
+        }
+    } else if (gi >= 0) {
+        const float cur = X.best_thr[jbase + (uint64_t)(ci * n_mem + m_top) * ns + gi];
+        const unsigned long long have = cpu_cost(grid, ci, g_held);
+        for (uint32_t b = ci + 1; b < grid.n_cpu; b += 64) {
+            const uint32_t c = b + lane;
+            const bool in = c < grid.n_cpu;
+            unsigned long long dc = 0;
+            float v = 0.f;
+            if (in) {
+                dc = cpu_cost(grid, c, g_held) - have;
+                v = X.best_thr[jbase + (uint64_t)(c * n_mem + m_top) * ns + gi];
+            }
+            const bool fits = in && dc <= freeC;
+            if (fits && v > cur) {
+                float sl = (v - cur) / ref;
+                sl = sl / (float)dc;
+                const unsigned long long key = ((unsigned long long)__float_as_uint(sl) << 32) | (0xFFFFFFFFu - c);
+                if (key > mine) mine = key;
+            }
+            if (__ballot(in && !fits)) break;                   // levels ascend
+        }
+    }
+    const unsigned long long best = wave_max_u64_rows(mine);
+    Step out = {0.f, 0u, 0u};
+    if (best >> 32) {                                           // a positive slope
+        out.slope = __uint_as_float((uint32_t)(best >> 32));
+        out.tgt = 0xFFFFFFFFu - (uint32_t)best;
+        if (PASS == 0) {
+            const unsigned long long holder = __ballot(mine == best);   // one lane: keys differ in the target
+            out.dg = (uint32_t)__builtin_amdgcn_readlane((int)mine_dg, __builtin_amdgcn_readfirstlane((int)__ffsll((long long)holder) - 1));
+        }
+    }
+    return out;
 }
 
+// LDS words tail_run needs beside its per-job scratch: the two key maxima in
+// three copies used in turn, the winner's two costs, and the CPU levels.
+constexpr int TAIL_RED_WORDS = 3 * 2 + 2 + RK_MAX_CPU_LEVELS / 2;
+
 // Workgroup of TAIL_THREADS threads; lds = max_jobs * 12 bytes of scratch, red =
-// TAIL_WAVES words.  Starts from the state k_apply / apply_job left in st.
-template <int PASS>
+// TAIL_RED_WORDS words; at most KMAX * TAIL_THREADS jobs.  Starts from the
+// state k_apply / apply_job left in st.  Thread t owns jobs t, t +
+// TAIL_THREADS, ...: their cached steps stay in its registers, and only it
+// (and, for the winner's new search, its wavefront) touches their LDS entries,
+// so a step needs two barriers: one for the maxima, one for the winner's costs.
+template <int PASS, int KMAX>
 __device__ __forceinline__ void tail_run(const Ctx &X, const JobState &st, uint32_t rnd, uint32_t J0, uint32_t J1,
                                          unsigned long long freeG, unsigned long long freeC, uint32_t max_jobs,
                                          float *lds, unsigned long long *red) {
-    float *slope = lds;                                            // cached best step of each job (0 = none)
-    uint16_t *tgt = reinterpret_cast<uint16_t *>(slope + max_jobs);   // its target (segment index or CPU level)
-    uint16_t *aux = tgt + max_jobs;                                // PASS 0: GPUs the step adds; PASS 1: GPUs held
-    int16_t *gi = reinterpret_cast<int16_t *>(aux + max_jobs);     // granted segment index, -1 = none
+    uint16_t *tgt = reinterpret_cast<uint16_t *>(lds);             // target of the cached step (segment index or CPU level)
+    int16_t *gi = reinterpret_cast<int16_t *>(tgt + max_jobs);     // granted segment index, -1 = none
     uint16_t *ci = reinterpret_cast<uint16_t *>(gi + max_jobs);    // granted CPU level
+    uint16_t *gh = ci + max_jobs;                                  // GPUs held (CPU pass); GPUs of a new step (GPU pass)
+    float *found = reinterpret_cast<float *>(gh + max_jobs);       // slope of a new step on its way to the registers
+    unsigned long long *win = red + 6;                             // GPUs and CPUs the winning step costs
+    uint32_t *lvl = reinterpret_cast<uint32_t *>(red + 8);         // CPU levels, for indexing by lane
 
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t nj = J1 - J0, jrel0 = J0 - X.jb;
     const GridDev &grid = X.grid;
 
-    for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {
-        slope[jl] = st.step_slope[jrel0 + jl];
-        tgt[jl] = st.step_tgt[jrel0 + jl];
-        gi[jl] = (int16_t)st.gi[jrel0 + jl];
-        ci[jl] = (uint16_t)st.ci[jrel0 + jl];
-        aux[jl] = PASS == 0 ? st.step_dg[jrel0 + jl] : (uint16_t)st.g[jrel0 + jl];
-    }
-    __syncthreads();
-
-    // CPUs a cached step of job jl costs
-    auto step_cpus = [&](uint32_t jl) -> unsigned long long {
-        if (PASS == 0)
-            return grid.cpu_mode ? (unsigned long long)grid.cpu_levels[ci[jl]] * aux[jl]
-                                 : (gi[jl] < 0 ? (unsigned long long)grid.cpu_levels[ci[jl]] : 0ull);
-        return cpu_cost(grid, tgt[jl], aux[jl]) - cpu_cost(grid, ci[jl], aux[jl]);
+    // CPUs a step costs (saturated to 32 bits: the free CPUs fit in 32)
+    auto need_cpus = [&](int32_t g_i, uint32_t c_i, uint32_t target, uint32_t gpus) -> uint32_t {
+        unsigned long long c;
+        if (PASS == 0) {
+            const unsigned long long times = grid.cpu_mode ? gpus : (g_i < 0 ? 1u : 0u);
+            c = (unsigned long long)lvl[c_i] * times;
+        } else {
+            const unsigned long long times = grid.cpu_mode ? gpus : 1u;
+            c = (unsigned long long)lvl[target] * times - (unsigned long long)lvl[c_i] * times;
+        }
+        return c > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)c;
     };
+
+    if (nj == 0) {                                                 // the same in all threads
+        if (PASS == 0 && tid == 0) st.free_c[rnd] = freeC;
+        return;
+    }
+    if (tid < RK_MAX_CPU_LEVELS) lvl[tid] = grid.cpu_levels[tid];
+    if (tid < 6) red[tid] = 0ull;
+    float slope[KMAX];                                             // cached best step of the thread's jobs:
+    uint32_t dg[KMAX], dc[KMAX];                                   // > 0 exact, < 0 an upper bound, 0 none; its GPUs, CPUs
+    {
+        int32_t g_i[KMAX];
+        uint32_t c_i[KMAX], target[KMAX], gpus[KMAX];
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {                           // all loads go out before the first is used
+            const uint32_t jl = tid + (uint32_t)k * TAIL_THREADS;
+            const uint32_t at = jrel0 + (jl < nj ? jl : nj - 1u);
+            g_i[k] = st.gi[at];
+            c_i[k] = st.ci[at];
+            target[k] = st.step_tgt[at];
+            gpus[k] = PASS == 0 ? st.step_dg[at] : st.g[at];
+            slope[k] = st.step_slope[at];
+        }
+        __syncthreads();                                           // the levels are in LDS
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            const uint32_t jl = tid + (uint32_t)k * TAIL_THREADS;
+            const bool have = jl < nj;
+            const uint32_t need = need_cpus(g_i[k], c_i[k], target[k], gpus[k]);
+            slope[k] = have ? slope[k] : 0.f;
+            dg[k] = PASS == 0 && have ? gpus[k] : 0u;
+            dc[k] = have ? need : 0u;
+            if (have) {
+                tgt[jl] = (uint16_t)target[k];
+                gi[jl] = (int16_t)g_i[k];
+                ci[jl] = (uint16_t)c_i[k];
+                if (PASS == 1) gh[jl] = (uint16_t)gpus[k];
+            }
+        }
+    }
+
     // A cached step that stops fitting is not searched anew at once: it is
     // kept, negated, as an upper bound of whatever the job can still do (the
     // job's state is unchanged and the capacity only shrank).  A step is
@@ -596,50 +729,91 @@ __device__ __forceinline__ void tail_run(const Ctx &X, const JobState &st, uint3
     auto key_of = [](float v, uint32_t jl) -> unsigned long long {
         return ((unsigned long long)__float_as_uint(v) << 32) | (0xFFFFFFFFu - jl);
     };
-    auto refresh = [&](uint32_t jl) {
-        const Step nx = best_step<PASS>(X, J0 + jl, gi[jl], PASS == 0 ? 0u : aux[jl], ci[jl], freeG, freeC);
-        slope[jl] = nx.slope;
-        tgt[jl] = (uint16_t)nx.tgt;
-        if (PASS == 0) aux[jl] = (uint16_t)nx.dg;
-    };
-    uint32_t steps = 0;
+    uint32_t steps = 0, turn = 0;
     for (;;) {
         if (PASS == 0 ? freeG == 0 : freeC == 0) break;         // nothing can fit any more
         unsigned long long kf = 0, ks = 0;
-        for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {
-            const float v = slope[jl];
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            const uint32_t jl = tid + (uint32_t)k * TAIL_THREADS;
+            float v = slope[k];
+            const bool stopped = v > 0.f && ((PASS == 0 && dg[k] > freeG) || dc[k] > freeC);
+            v = stopped ? -v : v;
+            slope[k] = v;
             if (v > 0.f) { const unsigned long long c = key_of(v, jl); kf = c > kf ? c : kf; }
             else if (v < 0.f) { const unsigned long long c = key_of(-v, jl); ks = c > ks ? c : ks; }
         }
-        kf = block_max_u64(kf, red);
-        ks = block_max_u64(ks, red);
+        kf = wave_max_u64_rows(kf);
+        ks = wave_max_u64_rows(ks);
+        unsigned long long *both = red + 2 * turn;              // three copies in turn: the next one is cleared meanwhile
+        turn = turn == 2 ? 0u : turn + 1u;
+        if (lane == 0) {
+            if (kf) atomicMax(&both[0], kf);
+            if (ks) atomicMax(&both[1], ks);
+        }
+        if (tid == TAIL_THREADS - 1) { red[2 * turn] = 0ull; red[2 * turn + 1] = 0ull; }
+        __syncthreads();
+        kf = both[0];
+        ks = both[1];
         if (ks > kf) {                                          // a bound could still win: make those exact
-            for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {
-                const float v = slope[jl];
-                if (v < 0.f && key_of(-v, jl) > kf) refresh(jl);
+            uint32_t todo = 0;
+#pragma unroll
+            for (int k = 0; k < KMAX; ++k) {
+                const float v = slope[k];
+                if (v < 0.f && key_of(-v, tid + (uint32_t)k * TAIL_THREADS) > kf) todo |= 1u << k;
             }
-            __syncthreads();
+            // the searches go through LDS so that the register arrays are only ever indexed by constants
+            for (uint32_t rest = todo; rest; rest &= rest - 1u) {
+                const uint32_t jl = tid + ((uint32_t)__ffs((int)rest) - 1u) * TAIL_THREADS;
+                const Step nx = best_step<PASS>(X, J0 + jl, gi[jl], PASS == 0 ? 0u : gh[jl], ci[jl], freeG, freeC);
+                found[jl] = nx.slope;
+                tgt[jl] = (uint16_t)nx.tgt;
+                if (PASS == 0) gh[jl] = (uint16_t)nx.dg;
+            }
+#pragma unroll
+            for (int k = 0; k < KMAX; ++k) {
+                if (todo >> k & 1u) {
+                    const uint32_t jl = tid + (uint32_t)k * TAIL_THREADS;
+                    slope[k] = found[jl];
+                    if (PASS == 0) dg[k] = gh[jl];
+                    dc[k] = need_cpus(gi[jl], ci[jl], tgt[jl], gh[jl]);
+                }
+            }
             continue;
         }
         if (!(kf >> 32)) break;                                 // no positive slope left
         ++steps;
         const uint32_t jw = 0xFFFFFFFFu - (uint32_t)kf;
-        if (PASS == 0) freeG -= aux[jw];
-        freeC -= step_cpus(jw);
-        __syncthreads();                                        // everyone has read the winner's state
-        if (tid == (jw % TAIL_THREADS)) {
-            if (PASS == 0) gi[jw] = (int16_t)tgt[jw]; else ci[jw] = tgt[jw];
-            refresh(jw);
-        }
-        for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {
-            if (jl == jw) continue;
-            const float v = slope[jl];
-            if (v > 0.f && ((PASS == 0 && aux[jl] > freeG) || step_cpus(jl) > freeC)) slope[jl] = -v;
+        const uint32_t owner = jw % TAIL_THREADS;
+        const uint32_t kw = (uint32_t)__builtin_amdgcn_readfirstlane((int)(jw / TAIL_THREADS));   // same in all lanes
+        if (tid == owner) {
+            uint32_t a = 0, b = 0;
+#pragma unroll
+            for (int k = 0; k < KMAX; ++k) if ((uint32_t)k == kw) { a = dg[k]; b = dc[k]; }
+            win[0] = a;
+            win[1] = b;
         }
         __syncthreads();
+        if (PASS == 0) freeG -= win[0];
+        freeC -= win[1];
+        if (wave == owner / 64u) {                              // the owner's wavefront searches the winner's next step
+            int32_t g_i = gi[jw];
+            uint32_t c_i = ci[jw];
+            if (PASS == 0) g_i = (int32_t)tgt[jw]; else c_i = tgt[jw];
+            const uint32_t held = PASS == 0 ? 0u : gh[jw];
+            const Step nx = best_step_wave<PASS>(X, J0 + jw, g_i, held, c_i, freeG, freeC);
+            if (tid == owner) {
+                if (PASS == 0) gi[jw] = (int16_t)g_i; else ci[jw] = (uint16_t)c_i;
+                tgt[jw] = (uint16_t)nx.tgt;
+                const uint32_t need = need_cpus(g_i, c_i, nx.tgt, PASS == 0 ? nx.dg : held);
+#pragma unroll
+                for (int k = 0; k < KMAX; ++k)
+                    if ((uint32_t)k == kw) { slope[k] = nx.slope; dg[k] = PASS == 0 ? nx.dg : 0u; dc[k] = need; }
+            }
+        }
     }
     if (steps) {                                                // something changed since k_apply
-        for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {
+        for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {  // the thread's own jobs
             if (PASS == 0) {
                 const int32_t s_i = gi[jl];
                 st.gi[jrel0 + jl] = s_i;
@@ -652,15 +826,17 @@ __device__ __forceinline__ void tail_run(const Ctx &X, const JobState &st, uint3
     if (PASS == 0 && tid == 0) st.free_c[rnd] = freeC;          // what the CPU pass starts from
 }
 
+constexpr int TAIL_KMAX = (RK_MAX_JOBS_PER_ROUND + TAIL_THREADS - 1) / TAIL_THREADS;
+
 template <int PASS>
 __global__ __launch_bounds__(TAIL_THREADS) void k_tail(Ctx X, uint32_t max_jobs, JobState st) {
     extern __shared__ float lds_dyn[];
-    __shared__ unsigned long long red[TAIL_WAVES];
+    __shared__ unsigned long long red[TAIL_RED_WORDS];
     const uint32_t rnd = blockIdx.x;
     uint32_t J0, J1;
     rk_cluster cl;
     round_of(X.R, rnd, J0, J1, cl);
-    tail_run<PASS>(X, st, rnd, J0, J1, st.free_g[rnd], st.free_g[X.R.n_rounds + rnd], max_jobs, lds_dyn, red);
+    tail_run<PASS, TAIL_KMAX>(X, st, rnd, J0, J1, st.free_g[rnd], st.free_g[X.R.n_rounds + rnd], max_jobs, lds_dyn, red);
 }
 
 // ------------------------------------------------------------------ small rounds: selection in one workgroup
@@ -675,7 +851,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_select_small(Ctx X, uint32_t m
     __shared__ uint32_t hg[BINS];                               // one histogram, used for level 0 and then level 1
     __shared__ unsigned long long hc[BINS];
     __shared__ CutScratch cs;
-    __shared__ unsigned long long red[TAIL_WAVES];
+    __shared__ unsigned long long red[TAIL_RED_WORDS];
     const uint32_t rnd = blockIdx.x, tid = threadIdx.x;
     uint32_t J0, J1;
     rk_cluster cl;
@@ -704,7 +880,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_select_small(Ctx X, uint32_t m
     sel.freeC = capC - usedC;
     for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) apply_job<PASS>(X, st, H, J0 + jl, sel.thr24, sel.freeG, sel.freeC);
     __syncthreads();                                            // the state in st is read back by the whole workgroup
-    tail_run<PASS>(X, st, rnd, J0, J1, sel.freeG, sel.freeC, max_jobs, lds_dyn, red);
+    tail_run<PASS, SMALL_ROUND_JOBS / TAIL_THREADS>(X, st, rnd, J0, J1, sel.freeG, sel.freeC, max_jobs, lds_dyn, red);
 }
 
 // ------------------------------------------------------------------ memory
@@ -1077,7 +1253,7 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
     X.R.cl = one_cluster ? *one_cluster : rk_cluster{0u, 0u, 0.f};
 
     const uint32_t mj = max_jobs ? ((max_jobs + 1u) & ~1u) : 2u;
-    const size_t lds = (size_t)mj * (4 + 2 + 2 + 2 + 2);
+    const size_t lds = (size_t)mj * (2 + 2 + 2 + 2 + 4);
     static bool raised[64] = {};
     if (lds > 48 * 1024 && !raised[ctx->device & 63]) {
         RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_tail<0>),
