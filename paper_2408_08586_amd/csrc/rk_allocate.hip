@@ -127,15 +127,6 @@ __device__ __forceinline__ unsigned long long cpu_cost(const GridDev &G, uint32_
     return G.cpu_mode ? (unsigned long long)G.cpu_levels[ci] * g : (unsigned long long)G.cpu_levels[ci];
 }
 
-__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const unsigned long long o = __shfl_xor(v, off, 64);
-        v = o > v ? o : v;
-    }
-    return v;
-}
-
 template <int CTRL>
 __device__ __forceinline__ unsigned long long dpp_u64(unsigned long long v) {
     const uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
@@ -144,9 +135,10 @@ __device__ __forceinline__ unsigned long long dpp_u64(unsigned long long v) {
     return ((unsigned long long)h2 << 32) | l2;
 }
 
-// The same maximum when all 64 lanes are active: within each row of 16 lanes
-// by data-parallel-primitive moves (neighbour, neighbour pair, mirrored halves
-// of 8, mirrored halves of 16), then the four rows through scalar registers.
+// Maximum over the wavefront, in every lane; all 64 lanes must be active.
+// Within each row of 16 lanes by data-parallel-primitive moves (neighbour,
+// neighbour pair, mirrored halves of 8, mirrored halves of 16), then the four
+// rows through scalar registers.
 __device__ __forceinline__ unsigned long long wave_max_u64_rows(unsigned long long v) {
     unsigned long long o;
     o = dpp_u64<0xB1>(v);  v = o > v ? o : v;                   // quad_perm [1,0,3,2]
@@ -270,7 +262,7 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
                 }
             }
         }
-        best = wave_max_u64(best);
+        best = wave_max_u64_rows(best);                   // all lanes are here: the loops above run the same number of times
         if (!(best >> 32)) break;
         const float top = __uint_as_float((uint32_t)(best >> 32));
         const uint32_t top_s = 0xFFFFFFFFu - (uint32_t)best;
@@ -278,9 +270,10 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
         unsigned long long top_cost;
         float top_val;
         if (top_s < 64u) {
-            top_cost = ((unsigned long long)__shfl((int)(cost0 >> 32), (int)top_s, 64) << 32) |
-                       (unsigned int)__shfl((int)(uint32_t)cost0, (int)top_s, 64);
-            top_val = __shfl(val0, (int)top_s, 64);
+            const int src = __builtin_amdgcn_readfirstlane((int)top_s);
+            top_cost = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(cost0 >> 32), src) << 32) |
+                       (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)cost0, src);
+            top_val = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(val0), src));
         } else {
             top_cost = cost_of(top_s);
             top_val = value_of(top_s);
