@@ -346,29 +346,44 @@ def main():
     seg_start = [n_rows * int(table.h_seg_off[a]) for a in edges[:-1]]
     seg_count = [table.n_segments(n_rows, int(a), int(b)) for a, b in zip(edges[:-1], edges[1:])]
 
-    kernel_ms = {"enumerate": [], "eval": [], "best_plan": [], "curves": [], "allocate": []}
+    # Event records cost the stream a few microseconds each, so the timed steps carry only those that the roofline
+    # needs (one before k_eval, one between k_eval and k_best_plan, one after k_best_plan, per chunk); the duration of
+    # every stage is measured in a pass of its own after the timed region, with events around every call.
+    hot_ms = {"eval": [], "best_plan": []}
+    stage_ms = {"enumerate": [], "eval": [], "best_plan": [], "curves": [], "allocate": []}
 
-    def timed(name, fn, record):
-        if not record:
-            fn()
-            return
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        fn()
-        b.record()
-        kernel_ms[name].append((a, b))
+    def mark():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record()
+        return e
 
-    def step(record):
-        timed("enumerate", lambda: rk.rk_enumerate_plans(ctx, jobs, bounds, table.c), record)
+    def step(mode):
+        """mode: None = no events, "hot" = events around the two HBM-bound kernels, "all" = around every call."""
+        every = mode == "all"
+        e0 = mark() if every else None
+        rk.rk_enumerate_plans(ctx, jobs, bounds, table.c)
+        if every:
+            e1 = mark()
+            stage_ms["enumerate"].append((e0, e1))
         for k in range(n_chunks):
             jb, je = int(edges[k]), int(edges[k + 1])
-            s0, sn = seg_start[k], seg_count[k]
-            timed("eval", lambda: rk.rk_eval_candidates(ctx, jobs, table.c, grid, env, jb, je, thr, None), record)
-            timed("best_plan", lambda: rk.rk_best_plan(ctx, table.c, grid, jb, je, thr, best_thr[s0:], best_plan[s0:]), record)
-            timed("curves", lambda: rk.rk_curves(ctx, table.c, grid, jb, je, best_thr[s0:], best_plan[s0:],
-                                                 curve_thr[s0:], curve_plan[s0:], curve_g[s0:]), record)
-        timed("allocate", lambda: rk.rk_allocate(ctx, jobs.ref_thr, table.c, grid, cluster, 0, J, best_thr, best_plan,
-                                                 curve_thr, assign, total), record)
+            s0 = seg_start[k]
+            a = mark() if mode else None
+            rk.rk_eval_candidates(ctx, jobs, table.c, grid, env, jb, je, thr, None)
+            b = mark() if mode else None
+            rk.rk_best_plan(ctx, table.c, grid, jb, je, thr, best_thr[s0:], best_plan[s0:])
+            c = mark() if mode else None
+            rk.rk_curves(ctx, table.c, grid, jb, je, best_thr[s0:], best_plan[s0:],
+                         curve_thr[s0:], curve_plan[s0:], curve_g[s0:])
+            if mode:
+                (stage_ms if every else hot_ms)["eval"].append((a, b))
+                (stage_ms if every else hot_ms)["best_plan"].append((b, c))
+            if every:
+                stage_ms["curves"].append((c, mark()))
+        e2 = mark() if every else None
+        rk.rk_allocate(ctx, jobs.ref_thr, table.c, grid, cluster, 0, J, best_thr, best_plan, curve_thr, assign, total)
+        if every:
+            stage_ms["allocate"].append((e2, mark()))
 
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -379,16 +394,22 @@ def main():
         del src, dst
 
     for _ in range(args.warmup):
-        step(False)
+        step(None)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(True)
+        step("hot")
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    avg_ms = {k: (sum(a.elapsed_time(b) for a, b in v) / len(v) if v else 0.0) for k, v in kernel_ms.items()}
-    per_step_ms = {k: avg_ms[k] * (len(v) / args.steps) for k, v in kernel_ms.items()}
+    stage_steps = min(args.steps, 5)
+    for _ in range(stage_steps):
+        step("all")
+    torch.cuda.synchronize()
+    mean_ms = lambda v: sum(a.elapsed_time(b) for a, b in v) / len(v) if v else 0.0
+    avg_ms = {k: mean_ms(v) for k, v in stage_ms.items()}
+    per_step_ms = {k: avg_ms[k] * (len(v) / stage_steps) for k, v in stage_ms.items()}
+    hot_avg_ms = {k: mean_ms(v) for k, v in hot_ms.items()}
 
     # fused round (the path a scheduler would call): latency of rk_schedule_round
     for _ in range(2):
@@ -407,11 +428,11 @@ def main():
     seg_per_launch = n_seg / n_chunks
     bytes_eval = 4.0 * cand_per_launch + 4.0 * table.n_triples / n_chunks
     bytes_best = 4.0 * cand_per_launch + 8.0 * seg_per_launch
-    gbs_eval = bytes_eval / (avg_ms["eval"] * 1e-3) / 1e9
-    gbs_best = bytes_best / (avg_ms["best_plan"] * 1e-3) / 1e9
-    dom = "eval" if per_step_ms["eval"] >= per_step_ms["best_plan"] else "best_plan"
+    gbs_eval = bytes_eval / (hot_avg_ms["eval"] * 1e-3) / 1e9            # over the launches of the timed region
+    gbs_best = bytes_best / (hot_avg_ms["best_plan"] * 1e-3) / 1e9
+    dom = "eval" if hot_avg_ms["eval"] >= hot_avg_ms["best_plan"] else "best_plan"
     achieved = gbs_eval if dom == "eval" else gbs_best
-    pair_gbs = (bytes_eval + bytes_best) / ((avg_ms["eval"] + avg_ms["best_plan"]) * 1e-3) / 1e9
+    pair_gbs = (bytes_eval + bytes_best) / ((hot_avg_ms["eval"] + hot_avg_ms["best_plan"]) * 1e-3) / 1e9
 
     digest = kernel_digest()
     traffic = None
@@ -430,10 +451,13 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": bytes_eval if dom == "eval" else bytes_best,
                      "traffic": traffic, "kernel_source_digest": digest},
-        "kernels": {"avg_launch_ms": avg_ms, "per_step_ms": per_step_ms,
+        "kernels": {"timed_region_avg_launch_ms": hot_avg_ms,
+                    "stage_pass": "separate pass after the timed region, events around every call",
+                    "avg_launch_ms": avg_ms, "per_step_ms": per_step_ms,
                     "eval_GBps": gbs_eval, "best_plan_GBps": gbs_best,
                     "eval_plus_best_plan_GBps": pair_gbs, "eval_plus_best_plan_frac_of_hbm": pair_gbs / HBM_PEAK_GBS,
-                    "eval_plus_best_plan_candidates_per_s": n_cand / ((per_step_ms["eval"] + per_step_ms["best_plan"]) * 1e-3)},
+                    "eval_plus_best_plan_candidates_per_s":
+                        n_cand / ((hot_avg_ms["eval"] + hot_avg_ms["best_plan"]) * n_chunks * 1e-3)},
         "round_latency_ms": {"entry": "rk_schedule_round (fused evaluation, host-synchronous)",
                              "min": float(lat.min()), "median": float(np.median(lat)), "max": float(lat.max())},
     }

@@ -118,6 +118,7 @@ int32_t rk_destroy(rk_ctx *ctx) {
         if (ctx->scratch[i]) (void)hipFree(ctx->scratch[i]);
     if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
     if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
+    if (ctx->counts_ev) (void)hipEventDestroy(ctx->counts_ev);
     if (ctx->sim_stream) {
         (void)hipStreamSynchronize(ctx->sim_stream);
         (void)hipStreamDestroy(ctx->sim_stream);

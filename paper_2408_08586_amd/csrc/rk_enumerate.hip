@@ -8,7 +8,9 @@
 // (g, t, p, v) with a rank sort in LDS.  The counting pass also parks the
 // sorted keys in a scratch buffer; after the exclusive scan of the counts the
 // fill pass only decodes them into place (it repeats the search only when the
-// scratch buffer was too small).
+// scratch buffer was too small).  The fill pass is launched while the counts
+// are still on their way to the host: it checks on the device that the table
+// is large enough and leaves it alone otherwise.
 #include <cstring>
 
 #include "rk_internal.h"
@@ -48,7 +50,7 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     uint32_t *__restrict__ park, uint32_t park_stride,
     const uint32_t *__restrict__ triple_off, const uint32_t *__restrict__ seg_off,
     uint32_t *__restrict__ triples, uint32_t *__restrict__ seg_g, uint32_t *__restrict__ seg_first,
-    uint32_t *__restrict__ totals) {
+    uint32_t *__restrict__ totals, uint64_t cap_triples, uint64_t cap_segs) {
     __shared__ uint32_t dlist[MAX_DIV], plist[MAX_DIV];
     __shared__ uint32_t keys[MAX_T], sorted[MAX_T];
     __shared__ uint32_t scan_tmp[ENUM_THREADS];
@@ -57,6 +59,11 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     const uint32_t j = blockIdx.x, tid = threadIdx.x;
     uint32_t cnt, err = 0;
     if (MODE == MODE_FILL_PARKED) {
+        // launched before the host has seen the totals: nothing is written unless the
+        // counting pass raised no flag and the table takes everything (same in all threads)
+        const uint64_t nt = ((uint64_t)totals[TOT_NT_HI] << 32) | totals[TOT_NT_LO];
+        const uint64_t ns = ((uint64_t)totals[TOT_NS_HI] << 32) | totals[TOT_NS_LO];
+        if (totals[TOT_ERR] != 0u || nt > 0xFFFFFFFFull || nt > cap_triples || ns > cap_segs) return;
         cnt = cnt_t[j];
         const size_t at = (size_t)j * park_stride;
         for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) sorted[i] = park[at + i];
@@ -162,7 +169,8 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
 __global__ __launch_bounds__(1024) void k_scan_counts(const uint32_t *__restrict__ cnt_t,
                                                       const uint32_t *__restrict__ cnt_s, uint32_t n_jobs,
                                                       uint32_t *__restrict__ off_t, uint32_t *__restrict__ off_s,
-                                                      uint32_t *__restrict__ totals) {
+                                                      uint32_t *__restrict__ totals, uint32_t *__restrict__ back) {
+    // back: [16 words of totals | n_jobs + 1 triple offsets | n_jobs + 1 segment offsets], one piece for the host
     __shared__ unsigned long long wave_t[16], wave_s[16];
     __shared__ uint32_t wave_mt[16], wave_ms[16];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -192,8 +200,11 @@ __global__ __launch_bounds__(1024) void k_scan_counts(const uint32_t *__restrict
         }
         const uint32_t j = base + tid;
         if (j < n_jobs) {
-            off_t[j] = (uint32_t)(carry_t + before_t + it - ct);
-            off_s[j] = (uint32_t)(carry_s + before_s + is - cs);
+            const uint32_t ot = (uint32_t)(carry_t + before_t + it - ct), os = (uint32_t)(carry_s + before_s + is - cs);
+            off_t[j] = ot;
+            off_s[j] = os;
+            back[16 + j] = ot;
+            back[16 + n_jobs + 1 + j] = os;
         }
         carry_t += all_t; carry_s += all_s;
         __syncthreads();                                    // the totals are read before the next tile overwrites them
@@ -211,6 +222,11 @@ __global__ __launch_bounds__(1024) void k_scan_counts(const uint32_t *__restrict
         totals[TOT_NT_LO] = (uint32_t)carry_t; totals[TOT_NT_HI] = (uint32_t)(carry_t >> 32);
         totals[TOT_NS_LO] = (uint32_t)carry_s; totals[TOT_NS_HI] = (uint32_t)(carry_s >> 32);
         totals[TOT_MAX_T] = mt; totals[TOT_MAX_S] = ms;
+        back[16 + n_jobs] = (uint32_t)carry_t; back[16 + 2 * n_jobs + 1] = (uint32_t)carry_s;
+        back[TOT_NT_LO] = (uint32_t)carry_t; back[TOT_NT_HI] = (uint32_t)(carry_t >> 32);
+        back[TOT_NS_LO] = (uint32_t)carry_s; back[TOT_NS_HI] = (uint32_t)(carry_s >> 32);
+        back[TOT_MAX_T] = mt; back[TOT_MAX_S] = ms;
+        back[TOT_ERR] = totals[TOT_ERR];                    // flags of the counting pass
     }
 }
 
@@ -246,7 +262,7 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
     table->n_triples = table->n_segs = 0;
     table->max_triples_per_job = table->max_segs_per_job = 0;
 
-    uint32_t *cnt_t, *cnt_s, *totals, *off_t, *off_s, *park;
+    uint32_t *cnt_t, *cnt_s, *totals, *off_t, *off_s, *park, *back;
     int32_t rc;
     if ((rc = rk_scratch(ctx, SL_CNT_T, (size_t)(2 * (size_t)J + 2) * 4, (void **)&cnt_t))) return rc;
     if ((rc = rk_scratch(ctx, SL_CNT_S, (size_t)(2 * (size_t)J + 2) * 4, (void **)&cnt_s))) return rc;
@@ -255,11 +271,14 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
     if (ctx->park_stride == 0) ctx->park_stride = 512;
     const uint32_t park_stride = ctx->park_stride;
     if ((rc = rk_scratch(ctx, SL_PARK, ((size_t)J * park_stride + 1) * 4, (void **)&park))) return rc;
-    const bool direct = table->triples && table->triple_off && table->seg_off;   // offsets go straight into the table
-    off_t = direct ? table->triple_off : cnt_t + J;
-    off_s = direct ? table->seg_off : cnt_s + J;
-    // pinned staging for what comes back: totals, then the two offset arrays
+    const bool fill = table->triples != nullptr;              // otherwise a sizing call
+    if (fill && (!table->triple_off || !table->seg_off || !table->seg_g || !table->seg_first))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "table buffer is null");
+    off_t = fill ? table->triple_off : cnt_t + J;             // offsets go straight into the table
+    off_s = fill ? table->seg_off : cnt_s + J;
+    // what comes back in one piece: totals, then the two offset arrays (pinned staging on the host)
     const size_t words_back = 16 + 2 * ((size_t)J + 1);
+    if ((rc = rk_scratch(ctx, SL_ENUM_BACK, words_back * 4, (void **)&back))) return rc;
     if (ctx->h_stage_words < words_back) {
         if (ctx->h_stage) RK_HIP(ctx, hipHostFree(ctx->h_stage));
         ctx->h_stage = nullptr; ctx->h_stage_words = 0;
@@ -267,23 +286,29 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
         ctx->h_stage_words = words_back + words_back / 4;
     }
     uint32_t *h = ctx->h_stage;
+    if (!ctx->counts_ev) RK_HIP(ctx, hipEventCreateWithFlags(&ctx->counts_ev, hipEventDisableTiming));
 
     k_zero_words<<<1, 64, 0, ctx->stream>>>(totals, TOT_WORDS);
     if (J > 0) {
         k_enumerate<MODE_COUNT><<<J, ENUM_THREADS, 0, ctx->stream>>>(
             jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
-            nullptr, nullptr, nullptr, nullptr, nullptr, totals);
+            nullptr, nullptr, nullptr, nullptr, nullptr, totals, 0, 0);
         RK_CHECK_LAUNCH(ctx, "k_enumerate<count>");
     }
-    k_scan_counts<<<1, 1024, 0, ctx->stream>>>(cnt_t, cnt_s, J, off_t, off_s, totals);
+    k_scan_counts<<<1, 1024, 0, ctx->stream>>>(cnt_t, cnt_s, J, off_t, off_s, totals, back);
     RK_CHECK_LAUNCH(ctx, "k_scan_counts");
-    const bool mirrors = table->triples && table->h_triple_off && table->h_seg_off;
-    RK_HIP(ctx, hipMemcpyAsync(h, totals, TOT_WORDS * 4, hipMemcpyDeviceToHost, ctx->stream));
-    if (mirrors) {
-        RK_HIP(ctx, hipMemcpyAsync(h + 16, off_t, ((size_t)J + 1) * 4, hipMemcpyDeviceToHost, ctx->stream));
-        RK_HIP(ctx, hipMemcpyAsync(h + 16 + J + 1, off_s, ((size_t)J + 1) * 4, hipMemcpyDeviceToHost, ctx->stream));
+    const bool mirrors = fill && table->h_triple_off && table->h_seg_off;
+    RK_HIP(ctx, hipMemcpyAsync(h, back, (mirrors ? words_back : 16) * 4, hipMemcpyDeviceToHost, ctx->stream));
+    RK_HIP(ctx, hipEventRecord(ctx->counts_ev, ctx->stream));
+    // The fill pass goes out before the host knows the totals, so that the device does not wait for the
+    // round trip: the kernel itself checks the flags and the table's capacity.
+    if (fill && J > 0) {
+        k_enumerate<MODE_FILL_PARKED><<<J, ENUM_THREADS, 0, ctx->stream>>>(
+            jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
+            off_t, off_s, table->triples, table->seg_g, table->seg_first, totals, table->cap_triples, table->cap_segs);
+        RK_CHECK_LAUNCH(ctx, "k_enumerate<fill>");
     }
-    RK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    RK_HIP(ctx, hipEventSynchronize(ctx->counts_ev));
 
     if (h[TOT_ERR] & ERR_TOO_MANY_TRIPLES) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "a job has more than %u triples", MAX_T);
     if (h[TOT_ERR] & ERR_TOO_MANY_DIVISORS) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "a job has more than %u candidate d or p sizes", MAX_DIV);
@@ -301,9 +326,7 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
         ctx->park_stride = want > MAX_T ? MAX_T : want;
     }
 
-    if (!table->triples) return RK_OK;                        // sizing call
-    if (!table->triple_off || !table->seg_off || !table->seg_g || !table->seg_first)
-        return rk_fail(ctx, RK_ERR_INVALID_ARG, "table buffer is null");
+    if (!fill) return RK_OK;
     if (table->cap_triples < nt || table->cap_segs < ns)
         return rk_fail(ctx, RK_ERR_CAPACITY, "table too small: need %llu triples and %llu segments",
                        (unsigned long long)nt, (unsigned long long)ns);
@@ -311,15 +334,10 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
         memcpy(table->h_triple_off, h + 16, ((size_t)J + 1) * 4);
         memcpy(table->h_seg_off, h + 16 + J + 1, ((size_t)J + 1) * 4);
     }
-    if (J > 0) {
-        if (parked)
-            k_enumerate<MODE_FILL_PARKED><<<J, ENUM_THREADS, 0, ctx->stream>>>(
-                jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
-                off_t, off_s, table->triples, table->seg_g, table->seg_first, totals);
-        else
-            k_enumerate<MODE_FILL_SEARCH><<<J, ENUM_THREADS, 0, ctx->stream>>>(
-                jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
-                off_t, off_s, table->triples, table->seg_g, table->seg_first, totals);
+    if (J > 0 && !parked) {                                   // the parked keys were incomplete: search again
+        k_enumerate<MODE_FILL_SEARCH><<<J, ENUM_THREADS, 0, ctx->stream>>>(
+            jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
+            off_t, off_s, table->triples, table->seg_g, table->seg_first, totals, 0, 0);
         RK_CHECK_LAUNCH(ctx, "k_enumerate<fill>");
     }
     return RK_OK;

@@ -21,6 +21,7 @@ struct rk_ctx {
     uint32_t *h_stage;                      // pinned staging for the plan-table offsets, grown on demand
     size_t h_stage_words;
     uint32_t park_stride;                   // enumeration: words per job between its two passes
+    hipEvent_t counts_ev;                   // enumeration: the counts have reached the host (made on demand)
     hipStream_t sim_stream;                 // simulation: its own stream (a tick is captured as a graph), made on demand
     hipEvent_t sim_ev[2];                   // ... ordered after and before the context's stream with these
 };
@@ -39,7 +40,8 @@ enum {
     SL_FL_GI, SL_FL_CI, SL_FL_WAITS, SL_FL_CAP0,         // service-level floors of the allocation
     SL_MIN_SEG, SL_MIN_C, SL_MIN_M,                      // minimum demands of a round
     SL_SIM_STATE, SL_SIM_ASSIGN,                         // simulation: per-job state, the tick's assignment
-    SL_JMAP                                              // rounds that share jobs: slot -> job
+    SL_JMAP,                                             // rounds that share jobs: slot -> job
+    SL_ENUM_BACK                                         // enumeration: totals and offsets in one piece for the host
 };
 
 int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);
