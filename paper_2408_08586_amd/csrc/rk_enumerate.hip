@@ -163,28 +163,55 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
 }
 
 // exclusive scan of the per-job counts, totals and maxima: one workgroup walks
-// the jobs in tiles of 1024 with coalesced loads (the next tile is requested
-// before the current one is scanned); inside a tile wavefront scans by
-// shuffles, then the wavefronts' totals
+// the jobs in tiles of 8192, every thread taking eight neighbouring jobs with
+// two 16-byte loads per array (the next tile is requested before the current
+// one is scanned); a thread sums its eight, the sums are scanned inside the
+// wavefronts by shuffles and across them through LDS, and the offsets leave
+// through LDS so that the stores are coalesced too.
+// back: [16 words of totals | n_jobs + 1 triple offsets | n_jobs + 1 segment offsets], one piece for the host
+constexpr uint32_t SCAN_PER = 8, SCAN_TILE = 1024 * SCAN_PER;
+
+struct Eight { uint32_t v[SCAN_PER]; };
+
+// counts of jobs j0 .. j0+7 (0 beyond the end); cnt + j0 is 32-byte aligned
+__device__ __forceinline__ Eight load_eight(const uint32_t *__restrict__ cnt, uint32_t j0, uint32_t n_jobs) {
+    Eight e;
+    if (j0 + SCAN_PER <= n_jobs) {
+        const uint4 a = *reinterpret_cast<const uint4 *>(cnt + j0), b = *reinterpret_cast<const uint4 *>(cnt + j0 + 4);
+        e.v[0] = a.x; e.v[1] = a.y; e.v[2] = a.z; e.v[3] = a.w;
+        e.v[4] = b.x; e.v[5] = b.y; e.v[6] = b.z; e.v[7] = b.w;
+    } else {
+#pragma unroll
+        for (uint32_t i = 0; i < SCAN_PER; ++i) e.v[i] = j0 + i < n_jobs ? cnt[j0 + i] : 0u;
+    }
+    return e;
+}
+
 __global__ __launch_bounds__(1024) void k_scan_counts(const uint32_t *__restrict__ cnt_t,
                                                       const uint32_t *__restrict__ cnt_s, uint32_t n_jobs,
                                                       uint32_t *__restrict__ off_t, uint32_t *__restrict__ off_s,
                                                       uint32_t *__restrict__ totals, uint32_t *__restrict__ back) {
-    // back: [16 words of totals | n_jobs + 1 triple offsets | n_jobs + 1 segment offsets], one piece for the host
+    __shared__ __align__(16) uint32_t buf_t[SCAN_TILE], buf_s[SCAN_TILE];
     __shared__ unsigned long long wave_t[16], wave_s[16];
     __shared__ uint32_t wave_mt[16], wave_ms[16];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     unsigned long long carry_t = 0, carry_s = 0;            // everything before the tile (same in every thread)
     uint32_t mt = 0, ms = 0;                                // running maxima of this thread's elements
-    uint32_t nt_next = tid < n_jobs ? cnt_t[tid] : 0u, ns_next = tid < n_jobs ? cnt_s[tid] : 0u;
-    for (uint32_t base = 0; base < n_jobs; base += 1024) {
-        const uint32_t ct = nt_next, cs = ns_next;
-        const uint32_t jn = base + 1024 + tid;
-        nt_next = jn < n_jobs ? cnt_t[jn] : 0u;
-        ns_next = jn < n_jobs ? cnt_s[jn] : 0u;
-        mt = ct > mt ? ct : mt;
-        ms = cs > ms ? cs : ms;
-        unsigned long long it = ct, is = cs;                // inclusive scan inside the wavefront
+    Eight nt_next = load_eight(cnt_t, tid * SCAN_PER, n_jobs), ns_next = load_eight(cnt_s, tid * SCAN_PER, n_jobs);
+    for (uint32_t base = 0; base < n_jobs; base += SCAN_TILE) {
+        const Eight ct = nt_next, cs = ns_next;
+        if (base + SCAN_TILE < n_jobs) {
+            nt_next = load_eight(cnt_t, base + SCAN_TILE + tid * SCAN_PER, n_jobs);
+            ns_next = load_eight(cnt_s, base + SCAN_TILE + tid * SCAN_PER, n_jobs);
+        }
+        unsigned long long sum_t = 0, sum_s = 0;
+#pragma unroll
+        for (uint32_t i = 0; i < SCAN_PER; ++i) {
+            sum_t += ct.v[i]; sum_s += cs.v[i];
+            mt = ct.v[i] > mt ? ct.v[i] : mt;
+            ms = cs.v[i] > ms ? cs.v[i] : ms;
+        }
+        unsigned long long it = sum_t, is = sum_s;          // inclusive scan of the threads' sums inside the wavefront
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const unsigned long long at = __shfl_up(it, off, 64), as = __shfl_up(is, off, 64);
@@ -198,16 +225,30 @@ __global__ __launch_bounds__(1024) void k_scan_counts(const uint32_t *__restrict
             if (w < wave) { before_t += wave_t[w]; before_s += wave_s[w]; }
             all_t += wave_t[w]; all_s += wave_s[w];
         }
-        const uint32_t j = base + tid;
-        if (j < n_jobs) {
-            const uint32_t ot = (uint32_t)(carry_t + before_t + it - ct), os = (uint32_t)(carry_s + before_s + is - cs);
-            off_t[j] = ot;
-            off_s[j] = os;
-            back[16 + j] = ot;
-            back[16 + n_jobs + 1 + j] = os;
+        uint32_t run_t = (uint32_t)(carry_t + before_t + it - sum_t), run_s = (uint32_t)(carry_s + before_s + is - sum_s);
+        uint32_t ot[SCAN_PER], os[SCAN_PER];
+#pragma unroll
+        for (uint32_t i = 0; i < SCAN_PER; ++i) {
+            ot[i] = run_t; os[i] = run_s;
+            run_t += ct.v[i]; run_s += cs.v[i];
+        }
+        uint4 *dt = reinterpret_cast<uint4 *>(buf_t + tid * SCAN_PER), *ds = reinterpret_cast<uint4 *>(buf_s + tid * SCAN_PER);
+        dt[0] = make_uint4(ot[0], ot[1], ot[2], ot[3]); dt[1] = make_uint4(ot[4], ot[5], ot[6], ot[7]);
+        ds[0] = make_uint4(os[0], os[1], os[2], os[3]); ds[1] = make_uint4(os[4], os[5], os[6], os[7]);
+        __syncthreads();
+#pragma unroll
+        for (uint32_t i = 0; i < SCAN_PER; ++i) {
+            const uint32_t at = i * 1024 + tid, j = base + at;
+            if (j < n_jobs) {
+                const uint32_t a = buf_t[at], b = buf_s[at];
+                off_t[j] = a;
+                off_s[j] = b;
+                back[16 + j] = a;
+                back[16 + n_jobs + 1 + j] = b;
+            }
         }
         carry_t += all_t; carry_s += all_s;
-        __syncthreads();                                    // the totals are read before the next tile overwrites them
+        __syncthreads();                                    // LDS is read before the next tile overwrites it
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
