@@ -174,47 +174,56 @@ __global__ __launch_bounds__(BEST_MAX_WAVES * 64) void k_best_plan(TableDev tb, 
 }
 
 // ------------------------------------------------------------------- curves
-// One workgroup per job.  The job's (row, segment) block is contiguous in
-// memory: it is staged through LDS in chunks of whole rows, one thread runs the
-// maximum along each row in LDS, and the results leave with contiguous stores.
+// One workgroup per job; its wavefronts split the job's rows.  A wavefront
+// walks its rows, which are contiguous in memory, 64 entries at a time: each
+// lane packs its entry into a key (throughput bits, inverted segment index,
+// GPUs of the segment), the running maximum along the row is a segmented scan
+// by shuffles (lower segment index wins among equal throughputs, as in the
+// step-by-step definition), and a row that continues from the previous 64
+// entries takes their last key along.  Only the plan of the winning segment is
+// fetched again.
 constexpr int CURVE_THREADS = 256;
-constexpr uint32_t CURVE_LDS_ENTRIES = 4096;
 
 __global__ __launch_bounds__(CURVE_THREADS) void k_curves(TableDev tb, uint32_t n_rows, uint32_t jb,
                                                           const float *__restrict__ best_thr,
                                                           const uint32_t *__restrict__ best_plan,
                                                           float *__restrict__ curve_thr, uint32_t *__restrict__ curve_plan,
                                                           uint32_t *__restrict__ curve_g) {
-    __shared__ float l_thr[CURVE_LDS_ENTRIES];
-    __shared__ uint32_t l_plan[CURVE_LDS_ENTRIES];
-    __shared__ uint32_t l_g[CURVE_LDS_ENTRIES];
-    const uint32_t j = jb + blockIdx.x, tid = threadIdx.x;
+    constexpr uint32_t WAVES = CURVE_THREADS / 64;
+    const uint32_t j = jb + blockIdx.x, lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
     if (ns == 0) return;
-    const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]);
-    const uint32_t rows_per_chunk = CURVE_LDS_ENTRIES / ns;          // ns <= 2048, so at least 2
-    for (uint32_t r0 = 0; r0 < n_rows; r0 += rows_per_chunk) {
-        const uint32_t rows = r0 + rows_per_chunk < n_rows ? rows_per_chunk : n_rows - r0;
-        const uint32_t cnt = rows * ns;
-        const uint64_t off = sbase + (uint64_t)r0 * ns;
-        for (uint32_t i = tid; i < cnt; i += CURVE_THREADS) { l_thr[i] = best_thr[off + i]; l_plan[i] = best_plan[off + i]; }
-        __syncthreads();
-        for (uint32_t r = tid; r < rows; r += CURVE_THREADS) {
-            float cur = 0.f;
-            uint32_t plan = RK_NO_PLAN, g = 0;
-            for (uint32_t s = 0; s < ns; ++s) {
-                const float v = l_thr[r * ns + s];
-                if (v > cur) { cur = v; plan = l_plan[r * ns + s]; g = tb.seg_g[s0 + s]; }
-                l_thr[r * ns + s] = cur;
-                l_plan[r * ns + s] = plan;
-                l_g[r * ns + s] = g;
-            }
+    const uint32_t per = (n_rows + WAVES - 1) / WAVES;
+    const uint32_t r_lo = wave * per < n_rows ? wave * per : n_rows;
+    const uint32_t r_hi = r_lo + per < n_rows ? r_lo + per : n_rows;
+    const uint32_t n = (r_hi - r_lo) * ns;                          // this wavefront's entries; they start a row
+    const uint64_t off = (uint64_t)n_rows * (s0 - tb.seg_off[jb]) + (uint64_t)r_lo * ns;
+    unsigned long long carry = 0;                                   // key at the end of the previous 64 entries
+    for (uint32_t base = 0; base < n; base += 64) {
+        const uint32_t i = base + lane;
+        const bool in = i < n;
+        const uint32_t s = i % ns;                                  // place in its row
+        unsigned long long key = 0;                                 // 0 = nothing feasible so far
+        if (in) {
+            const float v = best_thr[off + i];
+            if (v > 0.f)
+                key = ((unsigned long long)__float_as_uint(v) << 32) | ((0xFFFFu - s) << 16) | tb.seg_g[s0 + s];
         }
-        __syncthreads();
-        for (uint32_t i = tid; i < cnt; i += CURVE_THREADS) {
-            curve_thr[off + i] = l_thr[i]; curve_plan[off + i] = l_plan[i]; curve_g[off + i] = l_g[i];
+#pragma unroll
+        for (uint32_t d = 1; d < 64; d <<= 1) {
+            const unsigned long long o = __shfl_up(key, d, 64);
+            if (lane >= d && s >= d) key = o > key ? o : key;       // the lane d below is in the same row
         }
-        __syncthreads();
+        if (s > lane) key = carry > key ? carry : key;              // the row began before these 64 entries
+        carry = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(key >> 32), 63) << 32) |
+                (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)key, 63);
+        if (in) {
+            uint32_t plan = RK_NO_PLAN;
+            if (key) plan = best_plan[off + (i - s) + (0xFFFFu - ((uint32_t)(key >> 16) & 0xFFFFu))];
+            curve_thr[off + i] = __uint_as_float((uint32_t)(key >> 32));
+            curve_plan[off + i] = plan;
+            curve_g[off + i] = (uint32_t)key & 0xFFFFu;
+        }
     }
 }
 
