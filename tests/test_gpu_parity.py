@@ -112,6 +112,17 @@ def test_enumerate_wide_jobs_and_limits(gpu, orc):
         check_best_in_band(ot, run.n_rows, 0, wl.n_jobs, o_thr, o_bt, o_bp, run.host(bt, ns), run.host(bp, ns).view(np.uint32))
         fbt, fbp, fct, fcp, fcg, _ = run.fused()
         assert np.array_equal(run.host(fbt, ns), run.host(bt, ns)) and np.array_equal(run.host(fbp, ns), run.host(bp, ns))
+        # curves of rows far longer than a wavefront, on the oracle's best values: exact
+        assert int(np.diff(ot.seg_off).max()) > 64
+        e_bt, e_bp = orc.best_plan(ot, wl.grid, o_thr.astype(np.float32))
+        ct, cp, cg = run.curves(run.dev_f32(e_bt), run.dev_u32(e_bp))
+        e_ct, e_cp, e_cg = orc.curves(ot, wl.grid, e_bt, e_bp)
+        assert np.array_equal(run.host(ct, ns), e_ct)
+        assert np.array_equal(run.host(cp, ns).view(np.uint32), e_cp)
+        assert np.array_equal(run.host(cg, ns).view(np.uint32), e_cg)
+        ct2, cp2, cg2 = run.curves(bt, bp)
+        for a, b in ((fct, ct2), (fcp, cp2), (fcg, cg2)):
+            assert np.array_equal(run.host(a, ns), run.host(b, ns))
         run.close()
     too_wide = workloads.Workload("too_wide", coef[:1], np.array([[96, 720720, 1]], np.uint32), workloads.Bounds(g_max=4096),
                                   base.grid, workloads.Env(), workloads.Cluster(8, 8, 64.0))
