@@ -183,7 +183,12 @@ __device__ __forceinline__ void pass_caps(const RoundArgs &R, const rk_cluster &
 // (values from the per-segment maxima).  Amounts that the whole round could
 // never afford are left out.
 template <int PASS>
-__global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullBuf H) {
+__global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullBuf H, Hist zero, size_t zero_bins) {
+    // the histograms of the kernels that follow start at zero (zero_bins = 0: nothing to clear)
+    for (size_t i = (size_t)blockIdx.x * HULL_THREADS + threadIdx.x; i < zero_bins; i += (size_t)gridDim.x * HULL_THREADS) {
+        zero.g[i] = 0u;
+        zero.c[i] = 0ull;
+    }
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t jrel = blockIdx.x * (HULL_THREADS / 64) + (threadIdx.x >> 6);
     if (jrel >= H.stride) return;                         // whole wavefront
@@ -381,26 +386,37 @@ __device__ __forceinline__ uint32_t walk_width(const Ctx &X, const HullBuf &H) {
     return PASS == 0 ? H.width : (X.grid.n_cpu - 1 < H.width ? X.grid.n_cpu - 1 : H.width);
 }
 
-// Adds the steps of one job's walk to a histogram in LDS.
+// Adds the steps of one job's walk to a histogram in LDS.  The walk is read
+// four steps at a time (all twelve loads go out together; positions past the
+// walk's end are inside the buffers and ignored).
 template <int PASS, int LEVEL>
 __device__ __forceinline__ void hist_add(const Ctx &X, const HullBuf &H, uint32_t jrel, int32_t want_top, uint32_t *lg,
                                          unsigned long long *lc) {
     const uint32_t width = walk_width<PASS>(X, H);
-    for (uint32_t k = 0; k < width; ++k) {
-        const size_t e = (size_t)k * H.stride + jrel;
-        const uint32_t key = H.key[e];
-        if (!key) break;
-        uint32_t bin;
-        if (LEVEL == 0) bin = key >> 20;
-        else {
-            if ((int32_t)(key >> 20) > want_top) continue;
-            if ((int32_t)(key >> 20) < want_top) break;   // keys only decrease along a walk
-            bin = (key >> 8) & (BINS - 1);
+    for (uint32_t k0 = 0; k0 < width; k0 += 4) {
+        uint32_t key[4], dg[4];
+        unsigned long long dc[4];
+#pragma unroll
+        for (uint32_t u = 0; u < 4; ++u) {
+            const uint32_t k = k0 + u < width ? k0 + u : width - 1;
+            const size_t e = (size_t)k * H.stride + jrel;
+            key[u] = H.key[e];
+            dg[u] = PASS == 0 ? H.dg[e] : 0u;
+            dc[u] = H.dc[e];
         }
-        const uint32_t dg = H.dg[e];
-        const unsigned long long dc = H.dc[e];
-        if (dg) atomicAdd(&lg[bin], dg);
-        if (dc) atomicAdd(&lc[bin], dc);
+#pragma unroll
+        for (uint32_t u = 0; u < 4; ++u) {
+            if (k0 + u >= width || !key[u]) return;
+            uint32_t bin;
+            if (LEVEL == 0) bin = key[u] >> 20;
+            else {
+                if ((int32_t)(key[u] >> 20) > want_top) continue;
+                if ((int32_t)(key[u] >> 20) < want_top) return;   // keys only decrease along a walk
+                bin = (key[u] >> 8) & (BINS - 1);
+            }
+            if (dg[u]) atomicAdd(&lg[bin], dg[u]);
+            if (dc[u]) atomicAdd(&lc[bin], dc[u]);
+        }
     }
 }
 
@@ -439,7 +455,10 @@ __global__ __launch_bounds__(JOB_THREADS) void k_hist(Ctx X, JobState st, HullBu
 // ------------------------------------------------------------------ best step from scratch
 struct Step { float slope; uint32_t tgt, dg; };
 
-// Best step of job j from its current state under the free capacity.
+// Best step of job j from its current state under the free capacity.  The
+// candidates are read four at a time, so that their loads (and those of the
+// current state) are in flight together; positions past the end repeat the
+// last one and are ignored.
 template <int PASS>
 __device__ __forceinline__ Step best_step(const Ctx &X, uint32_t j, int32_t gi, uint32_t g_held, uint32_t ci,
                                           unsigned long long freeG, unsigned long long freeC) {
@@ -451,31 +470,55 @@ __device__ __forceinline__ Step best_step(const Ctx &X, uint32_t j, int32_t gi, 
     const float ref = X.ref_thr[ju];
     Step out = {0.f, 0u, 0u};
     if (PASS == 0) {
-        const uint32_t g_cur = gi < 0 ? 0u : X.tb.seg_g[s0 + gi];
         const uint64_t row = jbase + (uint64_t)(ci * n_mem + m_top) * ns;      // the CPU level the job holds
+        const uint32_t g_cur = gi < 0 ? 0u : X.tb.seg_g[s0 + gi];
         const float cur = gi < 0 ? 0.f : X.curve_thr[row + gi];
         const unsigned long long c_cur = gi < 0 ? 0ull : cpu_cost(grid, ci, g_cur);
-        for (uint32_t s = (uint32_t)(gi + 1); s < ns; ++s) {
-            const uint32_t dg = X.tb.seg_g[s0 + s] - g_cur;
-            if (dg > freeG) break;
-            const float v = X.curve_thr[row + s];
-            if (!(v > cur)) continue;
-            if (cpu_cost(grid, ci, g_cur + dg) - c_cur > freeC) continue;
-            float sl = (v - cur) / ref;
-            sl = sl / (float)dg;
-            if (sl > out.slope) { out.slope = sl; out.tgt = s; out.dg = dg; }
+        for (uint32_t b = (uint32_t)(gi + 1); b < ns; b += 4) {
+            uint32_t gs[4];
+            float vs[4];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                const uint32_t s = b + u < ns ? b + u : ns - 1;
+                gs[u] = X.tb.seg_g[s0 + s];
+                vs[u] = X.curve_thr[row + s];
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                const uint32_t s = b + u;
+                if (s >= ns) return out;
+                const uint32_t dg = gs[u] - g_cur;
+                if (dg > freeG) return out;                    // amounts ascend: nothing further on fits
+                const float v = vs[u];
+                if (!(v > cur)) continue;
+                if (cpu_cost(grid, ci, g_cur + dg) - c_cur > freeC) continue;
+                float sl = (v - cur) / ref;
+                sl = sl / (float)dg;
+                if (sl > out.slope) { out.slope = sl; out.tgt = s; out.dg = dg; }
+            }
         }
     } else if (gi >= 0) {
         const float cur = X.best_thr[jbase + (uint64_t)(ci * n_mem + m_top) * ns + gi];
         const unsigned long long have = cpu_cost(grid, ci, g_held);
-        for (uint32_t c = ci + 1; c < grid.n_cpu; ++c) {
-            const unsigned long long dc = cpu_cost(grid, c, g_held) - have;
-            if (dc > freeC) break;
-            const float v = X.best_thr[jbase + (uint64_t)(c * n_mem + m_top) * ns + gi];
-            if (!(v > cur)) continue;
-            float sl = (v - cur) / ref;
-            sl = sl / (float)dc;
-            if (sl > out.slope) { out.slope = sl; out.tgt = c; }
+        for (uint32_t b = ci + 1; b < grid.n_cpu; b += 4) {
+            float vs[4];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                const uint32_t c = b + u < grid.n_cpu ? b + u : grid.n_cpu - 1;
+                vs[u] = X.best_thr[jbase + (uint64_t)(c * n_mem + m_top) * ns + gi];
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                const uint32_t c = b + u;
+                if (c >= grid.n_cpu) return out;
+                const unsigned long long dc = cpu_cost(grid, c, g_held) - have;
+                if (dc > freeC) return out;                    // levels ascend
+                const float v = vs[u];
+                if (!(v > cur)) continue;
+                float sl = (v - cur) / ref;
+                sl = sl / (float)dc;
+                if (sl > out.slope) { out.slope = sl; out.tgt = c; }
+            }
         }
     }
     return out;
@@ -517,11 +560,25 @@ __device__ __forceinline__ void apply_job(const Ctx &X, const JobState &st, cons
         uint32_t ci = PASS == 0 ? fl.ci : st.ci[jrel];
         uint32_t k = 0, key = 0;
         size_t e = 0;
-        for (; k < width; ++k) {
-            e = (size_t)k * H.stride + jrel;
-            key = H.key[e];
-            if (!key || (long long)(key >> 8) <= thr24) break;
-            if (PASS == 0) gi = (int32_t)H.tgt[e]; else ci = H.tgt[e];
+        bool open_end = true;                                      // no step left out so far
+        for (uint32_t k0 = 0; k0 < width && open_end; k0 += 4) {   // four steps per round of loads
+            uint32_t keys[4], tgts[4];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                const uint32_t kk = k0 + u < width ? k0 + u : width - 1;
+                keys[u] = H.key[(size_t)kk * H.stride + jrel];
+                tgts[u] = H.tgt[(size_t)kk * H.stride + jrel];
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                if (!open_end || k0 + u >= width) continue;
+                k = k0 + u;
+                e = (size_t)k * H.stride + jrel;
+                key = keys[u];
+                if (!key || (long long)(key >> 8) <= thr24) { open_end = false; continue; }
+                if (PASS == 0) gi = (int32_t)tgts[u]; else ci = tgts[u];
+                k = k0 + u + 1;
+            }
         }
         if (k == width) key = 0;
         if (PASS == 0) {
@@ -1148,10 +1205,6 @@ __global__ __launch_bounds__(FLOOR_THREADS) void k_floors(Ctx X, JobState st, Sl
     }
 }
 
-__global__ void k_zero_u32(uint32_t *p, size_t n) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0u;
-}
 
 template <typename T>
 int32_t scratch_typed(rk_ctx *ctx, int slot, size_t count, T **out) {
@@ -1160,12 +1213,12 @@ int32_t scratch_typed(rk_ctx *ctx, int slot, size_t count, T **out) {
 
 template <int PASS>
 int32_t launch_pass(rk_ctx *ctx, const Ctx &X, const JobState &st, const HullBuf &H, const Hist &hist,
-                    uint32_t n_rounds, uint32_t n_jobs, uint32_t mj, size_t tail_lds) {
+                    uint32_t n_rounds, uint32_t n_jobs, uint32_t mj, size_t tail_lds, size_t zero_bins) {
     hipStream_t s = ctx->stream;
     const uint32_t hull_blocks = (n_jobs + (HULL_THREADS / 64) - 1) / (HULL_THREADS / 64);
     const dim3 job_grid(st.blocks_per_round, n_rounds);
     if (n_jobs > 0) {
-        k_hull<PASS><<<hull_blocks, HULL_THREADS, 0, s>>>(X, st, H);
+        k_hull<PASS><<<hull_blocks, HULL_THREADS, 0, s>>>(X, st, H, hist, zero_bins);
         RK_CHECK_LAUNCH(ctx, "k_hull");
     }
     if (mj <= SMALL_ROUND_JOBS) {
@@ -1266,18 +1319,16 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
         raised_small[ctx->device & 63] = true;
     }
     hipStream_t s = ctx->stream;
-    if (mj > SMALL_ROUND_JOBS) {   // histograms start at zero (fill kernels, so the sequence can be captured in a graph)
-        const size_t n32 = hist_bins, n64 = hist_bins * 2;
-        k_zero_u32<<<(unsigned)((n32 + 255) / 256), 256, 0, s>>>(hist.g, n32);
-        k_zero_u32<<<(unsigned)((n64 + 255) / 256), 256, 0, s>>>(reinterpret_cast<uint32_t *>(hist.c), n64);
-        RK_CHECK_LAUNCH(ctx, "k_zero_u32");
-    }
+    // Histograms start at zero: the first walk kernel clears them for both passes on its way (fill code, no
+    // memset, so the sequence can be captured in a graph).  Rounds large enough to use them have jobs, so that
+    // kernel always runs.
+    const bool hists = mj > SMALL_ROUND_JOBS;
     if (sla && !given) {
         k_floors<<<n_rounds, FLOOR_THREADS, (size_t)mj * 8, s>>>(X, st, *sla, mj);
         RK_CHECK_LAUNCH(ctx, "k_floors");
     }
-    if ((rc = launch_pass<0>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, lds))) return rc;
-    if ((rc = launch_pass<1>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, lds))) return rc;
+    if ((rc = launch_pass<0>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, lds, hists ? hist_bins : 0))) return rc;
+    if ((rc = launch_pass<1>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, lds, 0))) return rc;
     if (max_jobs > 0) {
         k_mem_wish<<<dim3(st.blocks_per_round, n_rounds), JOB_THREADS, 0, s>>>(X, st, assign);
         RK_CHECK_LAUNCH(ctx, "k_mem_wish");
