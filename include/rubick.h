@@ -170,8 +170,10 @@ const char *rk_last_error(const rk_ctx *ctx);
  * only some GPU counts are valid because of the partitioning constraints).
  * Factorises every g <= g_max on the device and writes the table.
  * With table->triples == NULL only the counts (n_triples, n_segs, maxima) are
- * produced.  Too small capacities give RK_ERR_CAPACITY with the counts set.
- * Waits for the stream (the counts come back to the host). */
+ * produced.  Too small capacities give RK_ERR_CAPACITY with the counts set and
+ * the table's triples and segments untouched (the offsets are written).
+ * Waits until the counts have come back to the host; the kernel that fills the
+ * table may still be running on the stream when the call returns. */
 int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
                            rk_plan_table *table);
 
