@@ -282,4 +282,21 @@ def frozen_round(ref_thr, table, grid, cluster, best_thr, best_idx, curve_thr, s
     return assign, total.value, gap.value
 
 
+PLACE_DTYPE = np.dtype([("node", np.uint32), ("g", np.uint32), ("c", np.uint32), ("mem_gb", np.float32)])
+
+
+def place(assign, n_nodes, gpus_per_node, cpus_per_node, mem_per_node_gb):
+    """Node-level placement of an allocation: (place_off, entries, status)."""
+    assign = np.ascontiguousarray(assign, dtype=ASSIGN_DTYPE)
+    J = assign.size
+    place_off = np.zeros(J + 1, np.uint32)
+    entries = np.zeros(max(int(assign["g"].astype(np.uint64).sum()), 1), PLACE_DTYPE)
+    status = np.zeros(J, np.uint32)
+    rc = lib().ork_place_f32(C.c_uint32(J), _p(assign), C.c_uint32(n_nodes), C.c_uint32(gpus_per_node),
+                             C.c_uint32(cpus_per_node), C.c_float(mem_per_node_gb), _p(place_off), _p(entries),
+                             _p(status))
+    assert rc == 0
+    return place_off, entries[:int(place_off[J])].copy(), status
+
+
 from . import simulator  # noqa: E402

@@ -8,6 +8,7 @@
  */
 #include "rk_oracle.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <thread>
@@ -554,6 +555,50 @@ int ork_frozen_round_f32(uint32_t n_jobs, const float *ref_thr, const ork_table 
     const uint64_t freeG = heldG < G ? G - heldG : 0, freeC = heldC < C ? C - heldC : 0;
     return greedy_from(n_jobs, ref_thr, tb, grid, freeG, freeC, host_mem_gb, best_thr, best_plan, curve_thr,
                        gi, ci, skip, assign, total, min_gap);
+}
+
+/* Sec. 5.2, Algorithm 1 (ScheduleJob): first fit over the nodes in order. */
+int ork_place_f32(uint32_t n_jobs, const ork_assign *assign, uint32_t n_nodes, uint32_t gpus_per_node,
+                  uint32_t cpus_per_node, float mem_per_node_gb, uint32_t *place_off,
+                  ork_place_entry *entries, uint32_t *status) {
+    std::vector<uint32_t> freeG(n_nodes, gpus_per_node), freeC(n_nodes, cpus_per_node);
+    std::vector<float> freeM(n_nodes, mem_per_node_gb);
+    uint32_t n_entries = 0;
+    for (uint32_t j = 0; j < n_jobs; ++j) {
+        place_off[j] = n_entries;
+        status[j] = 0;
+        const uint32_t g = assign[j].g, c = assign[j].c;
+        const float mem = assign[j].mem_gb;
+        if (g == 0) continue;
+        std::vector<ork_place_entry> parts;
+        uint32_t done = 0;
+        for (uint32_t n = 0; n < n_nodes && done < g; ++n) {
+            uint32_t k = std::min(freeG[n], g - done);
+            for (; k > 0; --k) {                      /* the most GPUs whose CPUs and memory are free here */
+                const uint64_t cpus = ((uint64_t)c * k + g - 1) / g;
+                const float m = (mem * (float)k) / (float)g;
+                if (cpus <= freeC[n] && m <= freeM[n]) break;
+            }
+            if (k == 0) continue;
+            ork_place_entry e;
+            e.node = n;
+            e.g = k;
+            e.c = (uint32_t)((uint64_t)c * (done + k) / g - (uint64_t)c * done / g);
+            e.mem_gb = (mem * (float)k) / (float)g;
+            parts.push_back(e);
+            done += k;
+        }
+        if (done < g) { status[j] = 2; continue; }    /* not enough found: the nodes stay as they were */
+        status[j] = 1;
+        for (const ork_place_entry &e : parts) {
+            freeG[e.node] -= e.g;
+            freeC[e.node] -= e.c;
+            freeM[e.node] = freeM[e.node] - e.mem_gb;
+            entries[n_entries++] = e;
+        }
+    }
+    place_off[n_jobs] = n_entries;
+    return 0;
 }
 
 }  // extern "C"

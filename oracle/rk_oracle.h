@@ -139,6 +139,20 @@ int ork_frozen_round_f32(uint32_t n_jobs, const float *ref_thr, const ork_table 
                          const uint8_t *state, const int32_t *cur_seg, const uint32_t *cur_c,
                          ork_assign *assign, double *total, double *min_gap);
 
+/* Node-level placement of an allocation (Sec. 5.2, Algorithm 1, ScheduleJob:
+ * a job walks the nodes in order, takes what each node has free and records
+ * {node, resources}; it is placed only if its whole amount is found).  Jobs
+ * in index order.  On a node a job takes the most GPUs k (up to what it still
+ * needs) such that ceil(c*k/g) CPUs and mem*k/g GiB are free there; the part
+ * is booked with CPUs floor(c*(done+k)/g) - floor(c*done/g) (done = GPUs
+ * placed on earlier nodes) and mem*k/g GiB (float32).
+ * place_off [n_jobs+1], entries [sum of g] at most, status [n_jobs]:
+ * 0 = nothing to place, 1 = placed, 2 = could not be placed (no entries). */
+typedef struct { uint32_t node, g, c; float mem_gb; } ork_place_entry;
+int ork_place_f32(uint32_t n_jobs, const ork_assign *assign, uint32_t n_nodes, uint32_t gpus_per_node,
+                  uint32_t cpus_per_node, float mem_per_node_gb, uint32_t *place_off,
+                  ork_place_entry *entries, uint32_t *status);
+
 #ifdef __cplusplus
 }
 #endif
