@@ -436,6 +436,43 @@ int32_t rk_simulate(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *tabl
                     const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
                     const rk_trace *trace, const rk_sim_options *options, const rk_sim_result *result);
 
+/* Nodes of the cluster, all alike. */
+#define RK_MAX_NODES 4096u
+typedef struct {
+    uint32_t n_nodes;           /* 1..RK_MAX_NODES */
+    uint32_t gpus_per_node;     /* 1..65535 */
+    uint32_t cpus_per_node;     /* 0..65535 */
+    float mem_per_node_gb;      /* GiB of host memory */
+} rk_nodes;
+
+/* One part of a job's placement: g GPUs, c CPUs and mem_gb GiB on a node. */
+typedef struct { uint32_t node, g, c; float mem_gb; } rk_place_entry;
+
+typedef struct {
+    uint32_t n_entries;         /* parts written */
+    uint32_t n_placed;          /* jobs with status 1 */
+    uint32_t n_failed;          /* jobs with status 2 */
+    uint32_t in_order;          /* 1: the job-by-job search ran (some node's CPUs or memory could bind) */
+} rk_place_result;
+
+/* Node-level placement of an allocation (Sec. 5.2, Algorithm 1, ScheduleJob:
+ * the job walks the nodes in order, takes what each has free and records
+ * {node, resources}; it is placed only when its whole amount has been found).
+ * Jobs are taken in index order, every node starts empty.  On a node a job
+ * of (g, c, mem) takes the most GPUs k, up to what it still lacks, such that
+ * ceil(c*k/g) CPUs and mem*k/g GiB are free there; the part is booked with
+ * floor(c*(done+k)/g) - floor(c*done/g) CPUs (done = its GPUs on earlier nodes,
+ * so the parts add up to c) and mem*k/g GiB (float32).  A job whose g GPUs
+ * are not found takes nothing.
+ *   assign     [device] n_jobs records (as rk_allocate writes them); g == 0: no parts
+ *   place_off  [device] n_jobs + 1 offsets into entries (CSR over jobs)
+ *   entries    [device] cap_entries records; cap_entries >= n_nodes * gpus_per_node
+ *   status     [device] n_jobs words: 0 nothing to place, 1 placed, 2 not placed
+ *   result     [host] or NULL; when given the call waits for the stream */
+int32_t rk_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs, const rk_assign *assign,
+                 uint32_t *place_off, rk_place_entry *entries, uint64_t cap_entries, uint32_t *status,
+                 rk_place_result *result);
+
 #ifdef __cplusplus
 }
 #endif

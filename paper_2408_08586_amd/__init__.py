@@ -24,7 +24,7 @@ FIT_FIELDS = ("k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_con
 
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
            "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
-           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared")
+           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared", "rk_place")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -438,6 +438,36 @@ def enumerate_to_table(ctx, jobs: Jobs, bounds: rk_plan_bounds, device="cuda:0")
     table = PlanTable(jobs.n_jobs, int(probe.n_triples), int(probe.n_segs), device)
     rk_enumerate_plans(ctx, jobs, bounds, table.c)
     return table
+
+
+class rk_nodes(C.Structure):
+    _fields_ = [("n_nodes", C.c_uint32), ("gpus_per_node", C.c_uint32), ("cpus_per_node", C.c_uint32),
+                ("mem_per_node_gb", C.c_float)]
+
+
+class rk_place_result(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("n_entries", "n_placed", "n_failed", "in_order")]
+
+
+PLACE_DTYPE = np.dtype([("node", np.uint32), ("g", np.uint32), ("c", np.uint32), ("mem_gb", np.float32)])
+
+
+def rk_place(ctx, nodes: rk_nodes, n_jobs, assign, place_off, entries, cap_entries, status, want_result=True):
+    """Node-level placement of the records in assign; returns rk_place_result (after a wait) or None."""
+    res = rk_place_result() if want_result else None
+    _check(ctx, load_library().rk_place(ctx, C.byref(nodes), C.c_uint32(n_jobs), _ptr(assign), _ptr(place_off),
+                                        _ptr(entries), C.c_uint64(cap_entries), _ptr(status),
+                                        C.byref(res) if want_result else None))
+    return res
+
+
+def new_place_entries(cap_entries, device="cuda:0"):
+    import torch
+    return torch.zeros(max(int(cap_entries), 1) * PLACE_DTYPE.itemsize, dtype=torch.uint8, device=device)
+
+
+def place_entries_to_numpy(t, n_entries) -> np.ndarray:
+    return t.cpu().numpy().view(PLACE_DTYPE)[:int(n_entries)]
 
 
 def new_assign(n_jobs, device="cuda:0"):

@@ -1,0 +1,290 @@
+// Node-level placement of an allocation (paper Sec. 5.2, Algorithm 1,
+// ScheduleJob: a job walks the nodes in order, takes what each node has free
+// and records {node, resources}).
+//
+// The rule is sequential: what a job finds depends on what the jobs before it
+// took.  One workgroup does it in two stages:
+//
+//  1. All jobs at once, assuming only GPUs bind.  Then first fit in node order
+//     is the jobs laid end to end on the nodes' GPU slots: job j covers slots
+//     [S_j, S_j + g_j) with S the prefix sum of the GPU counts, and its parts
+//     follow from the node boundaries inside that range.  While the parts are
+//     written, every node adds up the CPUs its parts would have needed to be
+//     free (ceil(c*k/g) each, an upper bound of what they book) and their
+//     memory.  If on every node these sums stay within the node (memory with
+//     0.1 % to spare for the rounding of the float32 remainder), no job could
+//     have met a node short of CPUs or memory, and the result stands.
+//  2. Otherwise the first wavefront redoes the round job by job: lanes take
+//     one node each, 64 nodes at a time from the first node that still has a
+//     free GPU; a lane finds the most GPUs its node can give, a prefix sum
+//     over the lanes cuts the offers at what the job still lacks, and the
+//     parts are booked only when the whole amount has been found.
+#include "rk_internal.h"
+
+namespace {
+
+constexpr int PLACE_THREADS = 1024;
+constexpr int PLACE_WAVES = PLACE_THREADS / 64;
+
+struct PlaceArgs {
+    uint32_t n_jobs, n_nodes, gpn, cpn;
+    float mpn;
+    const rk_assign *assign;
+    uint32_t *place_off;
+    rk_place_entry *entries;
+    uint32_t *status;
+    uint32_t *result;        // n_entries, n_placed, n_failed, in_order
+};
+
+__device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long long v, uint32_t lane) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const unsigned long long o = __shfl_up(v, off, 64);
+        if ((int)lane >= off) v += o;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, uint32_t lane) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_up((int)v, off, 64);
+        if ((int)lane >= off) v += o;
+    }
+    return v;
+}
+
+// exclusive prefix of one value per thread over the workgroup and the total; red = PLACE_WAVES words
+__device__ __forceinline__ unsigned long long block_excl_scan(unsigned long long v, unsigned long long *red,
+                                                              unsigned long long &total) {
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const unsigned long long incl = wave_incl_scan_u64(v, lane);
+    if (lane == 63u) red[wave] = incl;
+    __syncthreads();
+    unsigned long long before = 0, all = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < PLACE_WAVES; ++w) {
+        if (w < wave) before += red[w];
+        all += red[w];
+    }
+    __syncthreads();
+    total = all;
+    return before + incl - v;
+}
+
+// CPUs that must be free for k of the job's g GPUs, and the memory of that part
+__device__ __forceinline__ unsigned long long cpus_needed(uint32_t c, uint32_t k, uint32_t g) {
+    return ((unsigned long long)c * k + g - 1) / g;
+}
+__device__ __forceinline__ float mem_of_part(float mem, uint32_t k, uint32_t g) {
+    return (mem * (float)k) / (float)g;
+}
+// CPUs booked for k GPUs after `done` GPUs on earlier nodes
+__device__ __forceinline__ uint32_t cpus_booked(uint32_t c, uint32_t done, uint32_t k, uint32_t g) {
+    return (uint32_t)((unsigned long long)c * (done + k) / g - (unsigned long long)c * done / g);
+}
+
+__global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
+    extern __shared__ uint32_t lds[];
+    uint32_t *nodeA = lds;                               // stage 1: CPUs needed per node; stage 2: free GPUs
+    uint32_t *nodeB = nodeA + A.n_nodes;                 // stage 2: free CPUs
+    float *nodeM = reinterpret_cast<float *>(nodeB + A.n_nodes);   // stage 1: memory per node; stage 2: free memory
+    uint32_t *take = reinterpret_cast<uint32_t *>(nodeM + A.n_nodes);   // stage 2: GPUs offered by each node
+    uint32_t *before = take + A.n_nodes;                 // stage 2: the job's GPUs on earlier nodes
+    __shared__ unsigned long long red[PLACE_WAVES];
+    __shared__ uint32_t redo;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+
+    for (uint32_t n = tid; n < A.n_nodes; n += PLACE_THREADS) { nodeA[n] = 0u; nodeM[n] = 0.f; }
+    if (tid == 0) redo = 0u;
+    __syncthreads();
+
+    // ---- stage 1: the jobs end to end on the GPU slots
+    const unsigned long long slots = (unsigned long long)A.n_nodes * A.gpn;
+    unsigned long long carry_g = 0, carry_e = 0;          // GPU slots and parts before the tile
+    uint32_t n_sched = 0;
+    for (uint32_t base = 0; base < A.n_jobs; base += PLACE_THREADS) {
+        const uint32_t j = base + tid;
+        uint32_t g = 0, c = 0;
+        float mem = 0.f;
+        if (j < A.n_jobs) { g = A.assign[j].g; c = A.assign[j].c; mem = A.assign[j].mem_gb; }
+        unsigned long long tile_g, tile_e;
+        const unsigned long long start = carry_g + block_excl_scan(g, red, tile_g);
+        const bool inside = g > 0 && start + g <= slots;
+        const uint32_t n_first = inside ? (uint32_t)(start / A.gpn) : 0u;
+        const uint32_t n_last = inside ? (uint32_t)((start + g - 1) / A.gpn) : 0u;
+        const uint32_t parts = inside ? n_last - n_first + 1u : 0u;
+        const unsigned long long at = carry_e + block_excl_scan(parts, red, tile_e);
+        if (g > 0 && !inside) redo = 1u;                  // more GPUs than slots: job by job decides who fails
+        if (j < A.n_jobs) {
+            A.place_off[j] = (uint32_t)at;
+            A.status[j] = g > 0 ? 1u : 0u;
+        }
+        uint32_t done = 0;
+        for (uint32_t p = 0; p < parts; ++p) {
+            const uint32_t n = n_first + p;
+            const unsigned long long lo = p == 0 ? start : (unsigned long long)n * A.gpn;
+            const unsigned long long hi = p + 1 == parts ? start + g : (unsigned long long)(n + 1) * A.gpn;
+            const uint32_t k = (uint32_t)(hi - lo);
+            rk_place_entry e;
+            e.node = n;
+            e.g = k;
+            e.c = cpus_booked(c, done, k, g);
+            e.mem_gb = mem_of_part(mem, k, g);
+            A.entries[at + p] = e;
+            const unsigned long long need = cpus_needed(c, k, g);
+            if (need > A.cpn) redo = 1u;                  // (and the sum below cannot wrap: at most gpn parts of <= cpn)
+            else atomicAdd(&nodeA[n], (uint32_t)need);
+            atomicAdd(&nodeM[n], e.mem_gb);
+            done += k;
+        }
+        n_sched += g > 0 ? 1u : 0u;
+        carry_g += tile_g;
+        carry_e += tile_e;
+    }
+    __syncthreads();
+    for (uint32_t n = tid; n < A.n_nodes; n += PLACE_THREADS)
+        if (nodeA[n] > A.cpn || !(nodeM[n] <= 0.999f * A.mpn)) redo = 1u;
+    unsigned long long placed_all;
+    (void)block_excl_scan(n_sched, red, placed_all);      // also the barrier after the writes to redo
+    if (!redo) {
+        if (tid == 0) {
+            A.place_off[A.n_jobs] = (uint32_t)carry_e;
+            A.result[0] = (uint32_t)carry_e; A.result[1] = (uint32_t)placed_all; A.result[2] = 0u; A.result[3] = 0u;
+        }
+        return;
+    }
+
+    // ---- stage 2: job by job, by the first wavefront
+    for (uint32_t n = tid; n < A.n_nodes; n += PLACE_THREADS) { nodeA[n] = A.gpn; nodeB[n] = A.cpn; nodeM[n] = A.mpn; }
+    __syncthreads();
+    if (tid >= 64) return;
+    uint32_t cursor = 0, first = 0, n_placed = 0, n_failed = 0;
+    for (uint32_t base = 0; base < A.n_jobs; base += 64) {
+        const uint32_t j = base + lane;
+        uint32_t g = 0, c = 0;
+        float mem = 0.f;
+        if (j < A.n_jobs) { g = A.assign[j].g; c = A.assign[j].c; mem = A.assign[j].mem_gb; }
+        uint32_t my_off = 0, my_status = 0;
+        bool have_off = false;
+        unsigned long long todo = __ballot(g > 0);
+        while (todo) {
+            const int turn = (int)__ffsll((long long)todo) - 1;
+            todo &= todo - 1ull;
+            if ((int)lane <= turn && !have_off) { my_off = cursor; have_off = true; }   // jobs up to this one start here
+            const uint32_t jg = (uint32_t)__builtin_amdgcn_readlane((int)g, turn);
+            const uint32_t jc = (uint32_t)__builtin_amdgcn_readlane((int)c, turn);
+            const float jm = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mem), turn));
+            // the offers of the nodes, cut at what the job still lacks
+            uint32_t left = jg, end = first;
+            for (uint32_t nb = first; nb < A.n_nodes && left > 0; nb += 64) {
+                const uint32_t n = nb + lane;
+                uint32_t k = 0;
+                if (n < A.n_nodes) {
+                    // the most GPUs whose CPUs and memory are free here; both needs grow with k, so a bisection finds it
+                    const uint32_t fc = nodeB[n];
+                    const float fm = nodeM[n];
+                    auto fits = [&](uint32_t x) { return cpus_needed(jc, x, jg) <= fc && mem_of_part(jm, x, jg) <= fm; };
+                    uint32_t lo = 0, hi = nodeA[n] < jg ? nodeA[n] : jg;
+                    if (hi > 0 && !fits(hi)) {
+                        while (hi - lo > 1) {
+                            const uint32_t mid = lo + (hi - lo) / 2;
+                            if (fits(mid)) lo = mid; else hi = mid;
+                        }
+                        hi = lo;
+                    }
+                    k = hi;
+                }
+                const uint32_t incl = wave_incl_scan_u32(k, lane), excl = incl - k;
+                const uint32_t room = left > excl ? left - excl : 0u;
+                k = k < room ? k : room;
+                if (n < A.n_nodes) { take[n] = k; before[n] = (jg - left) + excl; }
+                const uint32_t all = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+                left -= all < left ? all : left;
+                end = nb + 64;
+            }
+            if (left > 0) {                               // not found: nothing is booked
+                if ((int)lane == turn) my_status = 2u;
+                ++n_failed;
+                continue;
+            }
+            if ((int)lane == turn) my_status = 1u;
+            ++n_placed;
+            for (uint32_t nb = first; nb < end; nb += 64) {
+                const uint32_t n = nb + lane;
+                const uint32_t k = n < A.n_nodes ? take[n] : 0u;
+                const unsigned long long with = __ballot(k > 0);
+                if (k > 0) {
+                    rk_place_entry e;
+                    e.node = n;
+                    e.g = k;
+                    e.c = cpus_booked(jc, before[n], k, jg);
+                    e.mem_gb = mem_of_part(jm, k, jg);
+                    nodeA[n] -= k;
+                    nodeB[n] -= e.c;
+                    nodeM[n] = nodeM[n] - e.mem_gb;
+                    A.entries[cursor + (uint32_t)__popcll(with & ((1ull << lane) - 1ull))] = e;
+                }
+                cursor += (uint32_t)__popcll(with);
+            }
+            // the first node that still has a free GPU
+            while (first < A.n_nodes) {
+                const uint32_t n = first + lane;
+                const unsigned long long open = __ballot(n < A.n_nodes && nodeA[n] > 0);
+                if (open) { first += (uint32_t)__ffsll((long long)open) - 1u; break; }
+                first += 64;
+            }
+            if (first > A.n_nodes) first = A.n_nodes;
+        }
+        if (!have_off) my_off = cursor;
+        if (j < A.n_jobs) { A.place_off[j] = my_off; A.status[j] = my_status; }
+    }
+    if (lane == 0) {
+        A.place_off[A.n_jobs] = cursor;
+        A.result[0] = cursor; A.result[1] = n_placed; A.result[2] = n_failed; A.result[3] = 1u;
+    }
+}
+
+}  // namespace
+
+extern "C" int32_t rk_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs, const rk_assign *assign,
+                            uint32_t *place_off, rk_place_entry *entries, uint64_t cap_entries, uint32_t *status,
+                            rk_place_result *result) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    if (!nodes || !place_off) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (n_jobs > 0 && (!assign || !status)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "assign or status is null");
+    if (nodes->n_nodes < 1 || nodes->n_nodes > RK_MAX_NODES)
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "n_nodes must be in 1..%u", RK_MAX_NODES);
+    if (nodes->gpus_per_node < 1 || nodes->gpus_per_node > 65535)
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "gpus_per_node must be in 1..65535");
+    if (nodes->cpus_per_node > 65535) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "cpus_per_node must be at most 65535");
+    if (!(nodes->mem_per_node_gb >= 0.f)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "mem_per_node_gb is negative or not a number");
+    const uint64_t need = (uint64_t)nodes->n_nodes * nodes->gpus_per_node;
+    if (cap_entries < need)
+        return rk_fail(ctx, RK_ERR_CAPACITY, "entries holds %llu parts, %llu needed (n_nodes * gpus_per_node)",
+                       (unsigned long long)cap_entries, (unsigned long long)need);
+    if (!entries) return rk_fail(ctx, RK_ERR_INVALID_ARG, "entries is null");
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    PlaceArgs A;
+    A.n_jobs = n_jobs; A.n_nodes = nodes->n_nodes; A.gpn = nodes->gpus_per_node; A.cpn = nodes->cpus_per_node;
+    A.mpn = nodes->mem_per_node_gb;
+    A.assign = assign; A.place_off = place_off; A.entries = entries; A.status = status;
+    int32_t rc;
+    if ((rc = rk_scratch(ctx, SL_PLACE_RESULT, 4 * sizeof(uint32_t), (void **)&A.result))) return rc;
+    const size_t lds = (size_t)A.n_nodes * 5 * sizeof(uint32_t);
+    static bool raised[64] = {};
+    if (lds > 48 * 1024 && !raised[ctx->device & 63]) {
+        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_place),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, RK_MAX_NODES * 5 * sizeof(uint32_t)));
+        raised[ctx->device & 63] = true;
+    }
+    k_place<<<1, PLACE_THREADS, lds, ctx->stream>>>(A);
+    RK_CHECK_LAUNCH(ctx, "k_place");
+    if (result) {
+        uint32_t *h = ctx->h_pinned;
+        RK_HIP(ctx, hipMemcpyAsync(h, A.result, 4 * sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
+        RK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        result->n_entries = h[0]; result->n_placed = h[1]; result->n_failed = h[2]; result->in_order = h[3];
+    }
+    return RK_OK;
+}

@@ -42,7 +42,7 @@ def test_header_functions_are_exported(rk):
 
 
 def test_struct_layouts_match_the_header(rk):
-    structs = ["rk_jobs", "rk_plan_bounds", "rk_plan_table", "rk_alloc_grid", "rk_env", "rk_cluster", "rk_assign", "rk_sla", "rk_samples", "rk_fit_options", "rk_fit_result", "rk_trace", "rk_sim_options", "rk_sim_result"]
+    structs = ["rk_jobs", "rk_plan_bounds", "rk_plan_table", "rk_alloc_grid", "rk_env", "rk_cluster", "rk_assign", "rk_sla", "rk_samples", "rk_fit_options", "rk_fit_result", "rk_trace", "rk_sim_options", "rk_sim_result", "rk_nodes", "rk_place_entry", "rk_place_result"]
     prog = ['#include <stdio.h>', '#include <stddef.h>', '#include "rubick.h"', 'int main(void){']
     for s in structs:
         prog.append(f'printf("{s} %zu\\n", sizeof({s}));')
@@ -55,7 +55,10 @@ def test_struct_layouts_match_the_header(rk):
               "rk_fit_options": ["refit_threshold", "n_starts", "start_offsets"],
               "rk_fit_result": ["k_const", "theta", "rmsle_after", "iters"],
               "rk_trace": ["work", "delta"], "rk_sim_options": ["n_ticks", "gate"],
-              "rk_sim_result": ["n_reconf", "held", "totals", "frozen"]}
+              "rk_sim_result": ["n_reconf", "held", "totals", "frozen"],
+              "rk_nodes": ["gpus_per_node", "cpus_per_node", "mem_per_node_gb"],
+              "rk_place_entry": ["node", "g", "c", "mem_gb"],
+              "rk_place_result": ["n_placed", "n_failed", "in_order"]}
     for s, fs in fields.items():
         for f in fs:
             prog.append(f'printf("{s}.{f} %zu\\n", offsetof({s}, {f}));')
@@ -69,11 +72,15 @@ def test_struct_layouts_match_the_header(rk):
     py = {"rk_jobs": rk.rk_jobs, "rk_plan_bounds": rk.rk_plan_bounds, "rk_plan_table": rk.rk_plan_table,
           "rk_alloc_grid": rk.rk_alloc_grid, "rk_env": rk.rk_env, "rk_cluster": rk.rk_cluster, "rk_sla": rk.rk_sla,
           "rk_samples": rk.rk_samples, "rk_fit_options": rk.rk_fit_options, "rk_fit_result": rk.rk_fit_result,
-          "rk_trace": rk.rk_trace, "rk_sim_options": rk.rk_sim_options, "rk_sim_result": rk.rk_sim_result}
+          "rk_trace": rk.rk_trace, "rk_sim_options": rk.rk_sim_options, "rk_sim_result": rk.rk_sim_result,
+          "rk_nodes": rk.rk_nodes, "rk_place_result": rk.rk_place_result}
     for s, cls in py.items():
         assert C.sizeof(cls) == int(want[s]), s
         for f in fields.get(s, []):
             assert getattr(cls, f).offset == int(want[f"{s}.{f}"]), f"{s}.{f}"
+    assert rk.PLACE_DTYPE.itemsize == int(want["rk_place_entry"])
+    for f in fields["rk_place_entry"]:
+        assert rk.PLACE_DTYPE.fields[f][1] == int(want[f"rk_place_entry.{f}"])
     assert rk.ASSIGN_DTYPE.itemsize == int(want["rk_assign"])
     for f in fields["rk_assign"]:
         assert rk.ASSIGN_DTYPE.fields[f][1] == int(want[f"rk_assign.{f}"])
