@@ -141,6 +141,35 @@ def what_if_batch(rk, ctx, dev, n_rounds):
                                   "identical_to_batch": same}}
 
 
+def placement(rk, ctx, dev, wl, assign, reps):
+    """Node-level placement (rk_place) of the round's assignment on nodes of the
+    workload's shape (the cluster's GPUs, CPUs and memory spread evenly over nodes
+    of 8 GPUs), and on nodes with only 6 CPUs (less than the one CPU per GPU the
+    round's jobs hold), where the job-by-job stage has to run and some jobs find
+    no place.  Host-synchronous latency of the call."""
+    import torch
+    J = wl.n_jobs
+    gpn = 8
+    n_nodes = max(1, wl.cluster.G // gpn)
+    cap = n_nodes * gpn
+    off = torch.zeros(J + 1, dtype=torch.int32, device=dev)
+    status = torch.zeros(J, dtype=torch.int32, device=dev)
+    ent = rk.new_place_entries(cap, dev)
+    out = {"entry": "rk_place (host-synchronous)", "nodes": n_nodes, "gpus_per_node": gpn}
+    for name, cpn in (("roomy", wl.cluster.C // n_nodes), ("tight_cpus", 6)):
+        nodes = rk.rk_nodes(n_nodes, gpn, min(int(cpn), 65535), float(wl.cluster.host_mem_gb) / n_nodes)
+        lat = []
+        for i in range(reps + 2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            res = rk.rk_place(ctx, nodes, J, assign, off, ent, cap, status)
+            if i >= 2:
+                lat.append((time.perf_counter() - t0) * 1e3)
+        out[name] = {"cpus_per_node": int(nodes.cpus_per_node), "ms": float(np.median(lat)), "placed": res.n_placed,
+                     "not_placed": res.n_failed, "parts": res.n_entries, "job_by_job_stage": bool(res.in_order)}
+    return out
+
+
 def sla_round(rk, ctx, dev, wl, jobs, table, bounds, grid, env, cluster, best_plan, n_rows, reps):
     """Service-level variant of the round on the same workload: 30 % guaranteed
     jobs of 6 tenants whose quotas sum to half the cluster.  A job's original
@@ -304,6 +333,7 @@ def main():
     ap.add_argument("--cpu-sample-jobs", type=int, default=1500)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-what-if", action="store_true")
+    ap.add_argument("--no-place", action="store_true", help="skip the node-level placement")
     ap.add_argument("--no-sla", action="store_true")
     ap.add_argument("--no-fit", action="store_true")
     ap.add_argument("--no-sim", action="store_true")
@@ -461,6 +491,9 @@ def main():
         "round_latency_ms": {"entry": "rk_schedule_round (fused evaluation, host-synchronous)",
                              "min": float(lat.min()), "median": float(np.median(lat)), "max": float(lat.max())},
     }
+    if not args.no_place:
+        rk.rk_schedule_round(ctx, jobs, bounds, grid, env, cluster, assign, total)
+        out["placement"] = placement(rk, ctx, dev, wl, assign, max(5, args.steps))
     if not args.no_sla:
         out["sla_round"] = sla_round(rk, ctx, dev, wl, jobs, table, bounds, grid, env, cluster, best_plan, n_rows,
                                      max(5, args.steps))

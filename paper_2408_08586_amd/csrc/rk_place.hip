@@ -23,7 +23,7 @@
 
 namespace {
 
-constexpr int PLACE_THREADS = 1024;
+constexpr int PLACE_THREADS = 512;
 constexpr int PLACE_WAVES = PLACE_THREADS / 64;
 
 struct PlaceArgs {
@@ -45,13 +45,23 @@ __device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long l
     return v;
 }
 
+// Inclusive prefix sum over the wavefront; all 64 lanes must be active.  Inside
+// each row of 16 lanes by data-parallel-primitive shifts (lanes shifted in from
+// outside the row read 0), then the rows' totals through scalar registers.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
 __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, uint32_t lane) {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = (uint32_t)__shfl_up((int)v, off, 64);
-        if ((int)lane >= off) v += o;
-    }
-    return v;
+    v += dpp_or_zero<0x111>(v);                             // row_shr:1
+    v += dpp_or_zero<0x112>(v);                             // row_shr:2
+    v += dpp_or_zero<0x114>(v);                             // row_shr:4
+    v += dpp_or_zero<0x118>(v);                             // row_shr:8
+    const uint32_t t0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 15);
+    const uint32_t t1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 31);
+    const uint32_t t2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 47);
+    const uint32_t row = lane >> 4;
+    return v + (row >= 1 ? t0 : 0u) + (row >= 2 ? t1 : 0u) + (row >= 3 ? t2 : 0u);
 }
 
 // exclusive prefix of one value per thread over the workgroup and the total; red = PLACE_WAVES words
@@ -72,17 +82,34 @@ __device__ __forceinline__ unsigned long long block_excl_scan(unsigned long long
     return before + incl - v;
 }
 
-// CPUs that must be free for k of the job's g GPUs, and the memory of that part
+// c*k / g and c*k % g; 32-bit arithmetic when the product cannot overflow (k <= g)
+struct DivMod { unsigned long long q; uint32_t r; };
+__device__ __forceinline__ DivMod cpus_times(uint32_t c, uint32_t k, uint32_t g) {
+    DivMod d;
+    if (((c | g) >> 16) == 0u) {
+        const uint32_t t = c * k;
+        d.q = t / g; d.r = t % g;
+    } else {
+        const unsigned long long t = (unsigned long long)c * k;
+        d.q = t / g; d.r = (uint32_t)(t % g);
+    }
+    return d;
+}
+// CPUs that must be free for k of the job's g GPUs: ceil(c*k/g); and the memory of that part
 __device__ __forceinline__ unsigned long long cpus_needed(uint32_t c, uint32_t k, uint32_t g) {
-    return ((unsigned long long)c * k + g - 1) / g;
+    const DivMod d = cpus_times(c, k, g);
+    return d.q + (d.r ? 1u : 0u);
 }
 __device__ __forceinline__ float mem_of_part(float mem, uint32_t k, uint32_t g) {
     return (mem * (float)k) / (float)g;
 }
-// CPUs booked for k GPUs after `done` GPUs on earlier nodes
+// CPUs booked for k GPUs after `done` GPUs on earlier nodes: floor(c*(done+k)/g) - floor(c*done/g)
 __device__ __forceinline__ uint32_t cpus_booked(uint32_t c, uint32_t done, uint32_t k, uint32_t g) {
-    return (uint32_t)((unsigned long long)c * (done + k) / g - (unsigned long long)c * done / g);
+    const DivMod a = cpus_times(c, done, g), b = cpus_times(c, k, g);
+    return (uint32_t)(b.q + ((unsigned long long)a.r + b.r >= g ? 1u : 0u));
 }
+
+constexpr uint32_t PLACE_PER = 8;                         // jobs per thread in the first stage
 
 __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
     extern __shared__ uint32_t lds[];
@@ -99,46 +126,112 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
     if (tid == 0) redo = 0u;
     __syncthreads();
 
-    // ---- stage 1: the jobs end to end on the GPU slots
+    // ---- stage 1: the jobs end to end on the GPU slots; a thread takes eight neighbouring jobs
     const unsigned long long slots = (unsigned long long)A.n_nodes * A.gpn;
     unsigned long long carry_g = 0, carry_e = 0;          // GPU slots and parts before the tile
     uint32_t n_sched = 0;
-    for (uint32_t base = 0; base < A.n_jobs; base += PLACE_THREADS) {
-        const uint32_t j = base + tid;
-        uint32_t g = 0, c = 0;
-        float mem = 0.f;
-        if (j < A.n_jobs) { g = A.assign[j].g; c = A.assign[j].c; mem = A.assign[j].mem_gb; }
-        unsigned long long tile_g, tile_e;
-        const unsigned long long start = carry_g + block_excl_scan(g, red, tile_g);
-        const bool inside = g > 0 && start + g <= slots;
-        const uint32_t n_first = inside ? (uint32_t)(start / A.gpn) : 0u;
-        const uint32_t n_last = inside ? (uint32_t)((start + g - 1) / A.gpn) : 0u;
-        const uint32_t parts = inside ? n_last - n_first + 1u : 0u;
-        const unsigned long long at = carry_e + block_excl_scan(parts, red, tile_e);
-        if (g > 0 && !inside) redo = 1u;                  // more GPUs than slots: job by job decides who fails
-        if (j < A.n_jobs) {
-            A.place_off[j] = (uint32_t)at;
-            A.status[j] = g > 0 ? 1u : 0u;
+    for (uint32_t base = 0; base < A.n_jobs; base += PLACE_THREADS * PLACE_PER) {
+        const uint32_t j0 = base + tid * PLACE_PER;
+        uint32_t g[PLACE_PER], c[PLACE_PER];
+        float mem[PLACE_PER];
+        unsigned long long sum_g = 0;
+        // the thread's eight records are 160 contiguous bytes: ten 16-byte loads where that is possible
+        static_assert(sizeof(rk_assign) == 20 && PLACE_PER == 8, "record layout of the vector loads");
+        if (j0 + PLACE_PER <= A.n_jobs && (reinterpret_cast<uintptr_t>(A.assign) & 15u) == 0) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(A.assign + j0);
+            uint32_t raw[40];
+#pragma unroll
+            for (uint32_t q = 0; q < 10; ++q) {
+                const uint4 v = src[q];
+                raw[4 * q] = v.x; raw[4 * q + 1] = v.y; raw[4 * q + 2] = v.z; raw[4 * q + 3] = v.w;
+            }
+#pragma unroll
+            for (uint32_t i = 0; i < PLACE_PER; ++i) { g[i] = raw[5 * i]; c[i] = raw[5 * i + 1]; mem[i] = __uint_as_float(raw[5 * i + 2]); }
+        } else {
+#pragma unroll
+            for (uint32_t i = 0; i < PLACE_PER; ++i) {
+                g[i] = 0; c[i] = 0; mem[i] = 0.f;
+                if (j0 + i < A.n_jobs) { g[i] = A.assign[j0 + i].g; c[i] = A.assign[j0 + i].c; mem[i] = A.assign[j0 + i].mem_gb; }
+            }
         }
-        uint32_t done = 0;
-        for (uint32_t p = 0; p < parts; ++p) {
-            const uint32_t n = n_first + p;
-            const unsigned long long lo = p == 0 ? start : (unsigned long long)n * A.gpn;
-            const unsigned long long hi = p + 1 == parts ? start + g : (unsigned long long)(n + 1) * A.gpn;
-            const uint32_t k = (uint32_t)(hi - lo);
+#pragma unroll
+        for (uint32_t i = 0; i < PLACE_PER; ++i) sum_g += g[i];
+        unsigned long long tile_g, tile_e;
+        unsigned long long start = carry_g + block_excl_scan(sum_g, red, tile_g);
+        uint32_t parts[PLACE_PER], k_first[PLACE_PER], node0[PLACE_PER];
+        unsigned long long sum_e = 0;
+#pragma unroll
+        for (uint32_t i = 0; i < PLACE_PER; ++i) {
+            const bool inside = g[i] > 0 && start + g[i] <= slots;      // then start fits in 32 bits (slots do)
+            if (g[i] > 0 && !inside) redo = 1u;           // more GPUs than slots: job by job decides who fails
+            const uint32_t s32 = inside ? (uint32_t)start : 0u;
+            node0[i] = s32 / A.gpn;
+            const uint32_t room = A.gpn - (s32 - node0[i] * A.gpn);      // free slots of the node the job starts on
+            k_first[i] = g[i] < room ? g[i] : room;
+            const uint32_t rest = g[i] - k_first[i], whole = rest / A.gpn;
+            parts[i] = inside ? 1u + whole + (rest - whole * A.gpn ? 1u : 0u) : 0u;
+            sum_e += parts[i];
+            start += g[i];
+            n_sched += g[i] > 0 ? 1u : 0u;
+        }
+        unsigned long long at = carry_e + block_excl_scan(sum_e, red, tile_e);
+        // one part of a job: its k GPUs after `done` GPUs on earlier nodes go to node n
+        auto write_part = [&](uint32_t jg, uint32_t jc, float jm, size_t where, uint32_t n, uint32_t done, uint32_t k) {
             rk_place_entry e;
             e.node = n;
             e.g = k;
-            e.c = cpus_booked(c, done, k, g);
-            e.mem_gb = mem_of_part(mem, k, g);
-            A.entries[at + p] = e;
-            const unsigned long long need = cpus_needed(c, k, g);
+            e.c = cpus_booked(jc, done, k, jg);
+            e.mem_gb = mem_of_part(jm, k, jg);
+            A.entries[where] = e;
+            const unsigned long long need = cpus_needed(jc, k, jg);
             if (need > A.cpn) redo = 1u;                  // (and the sum below cannot wrap: at most gpn parts of <= cpn)
             else atomicAdd(&nodeA[n], (uint32_t)need);
             atomicAdd(&nodeM[n], e.mem_gb);
-            done += k;
+        };
+        {   // offsets and status words of the thread's eight jobs: two 16-byte stores per array where that is possible
+            uint32_t offs[PLACE_PER], stat[PLACE_PER], run = (uint32_t)at;
+#pragma unroll
+            for (uint32_t i = 0; i < PLACE_PER; ++i) { offs[i] = run; stat[i] = g[i] > 0 ? 1u : 0u; run += parts[i]; }
+            const bool whole8 = j0 + PLACE_PER <= A.n_jobs &&
+                                ((reinterpret_cast<uintptr_t>(A.place_off) | reinterpret_cast<uintptr_t>(A.status)) & 15u) == 0;
+            if (whole8) {
+                uint4 *po = reinterpret_cast<uint4 *>(A.place_off + j0), *ps = reinterpret_cast<uint4 *>(A.status + j0);
+                po[0] = make_uint4(offs[0], offs[1], offs[2], offs[3]); po[1] = make_uint4(offs[4], offs[5], offs[6], offs[7]);
+                ps[0] = make_uint4(stat[0], stat[1], stat[2], stat[3]); ps[1] = make_uint4(stat[4], stat[5], stat[6], stat[7]);
+            } else {
+#pragma unroll
+                for (uint32_t i = 0; i < PLACE_PER; ++i)
+                    if (j0 + i < A.n_jobs) { A.place_off[j0 + i] = offs[i]; A.status[j0 + i] = stat[i]; }
+            }
         }
-        n_sched += g > 0 ? 1u : 0u;
+#pragma unroll
+        for (uint32_t i = 0; i < PLACE_PER; ++i) {
+            const uint32_t n0 = node0[i];
+            if (parts[i] > 0 && parts[i] <= 2) {          // short jobs: by their own thread
+                write_part(g[i], c[i], mem[i], at, n0, 0, k_first[i]);
+                if (parts[i] == 2) write_part(g[i], c[i], mem[i], at + 1, n0 + 1, k_first[i], g[i] - k_first[i]);
+            }
+            // jobs over three nodes or more: by the whole wavefront, a lane per part
+            unsigned long long todo = __ballot(parts[i] > 2);
+            while (todo) {
+                const int src = (int)__ffsll((long long)todo) - 1;
+                todo &= todo - 1ull;
+                const uint32_t jg = (uint32_t)__builtin_amdgcn_readlane((int)g[i], src);
+                const uint32_t jc = (uint32_t)__builtin_amdgcn_readlane((int)c[i], src);
+                const float jm = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mem[i]), src));
+                const uint32_t jparts = (uint32_t)__builtin_amdgcn_readlane((int)parts[i], src);
+                const uint32_t jfirst = (uint32_t)__builtin_amdgcn_readlane((int)k_first[i], src);
+                const uint32_t jn0 = (uint32_t)__builtin_amdgcn_readlane((int)n0, src);
+                const uint32_t jat = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)at, src);   // parts fit in 32 bits
+                for (uint32_t p = lane; p < jparts; p += 64) {
+                    const uint32_t done = p == 0 ? 0u : jfirst + (p - 1) * A.gpn;
+                    const uint32_t rest = jg - done;
+                    const uint32_t k = p == 0 ? jfirst : (rest < A.gpn ? rest : A.gpn);
+                    write_part(jg, jc, jm, (size_t)jat + p, jn0 + p, done, k);
+                }
+            }
+            at += parts[i];
+        }
         carry_g += tile_g;
         carry_e += tile_e;
     }
@@ -159,7 +252,9 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
     for (uint32_t n = tid; n < A.n_nodes; n += PLACE_THREADS) { nodeA[n] = A.gpn; nodeB[n] = A.cpn; nodeM[n] = A.mpn; }
     __syncthreads();
     if (tid >= 64) return;
-    uint32_t cursor = 0, first = 0, n_placed = 0, n_failed = 0;
+    uint32_t cursor = 0, n_placed = 0, n_failed = 0;
+    uint32_t first_g = 0, first_gc = 0;                  // first node with a free GPU; with a free GPU and a free CPU
+    unsigned long long free_gpus = slots;                 // of the whole cluster
     for (uint32_t base = 0; base < A.n_jobs; base += 64) {
         const uint32_t j = base + lane;
         uint32_t g = 0, c = 0;
@@ -175,9 +270,11 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
             const uint32_t jg = (uint32_t)__builtin_amdgcn_readlane((int)g, turn);
             const uint32_t jc = (uint32_t)__builtin_amdgcn_readlane((int)c, turn);
             const float jm = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mem), turn));
-            // the offers of the nodes, cut at what the job still lacks
+            // the offers of the nodes, cut at what the job still lacks (none are asked when the cluster has too few);
+            // a job that needs CPUs gets nothing from a node without a free CPU
+            const uint32_t first = jc > 0 ? first_gc : first_g;
             uint32_t left = jg, end = first;
-            for (uint32_t nb = first; nb < A.n_nodes && left > 0; nb += 64) {
+            for (uint32_t nb = first; nb < A.n_nodes && left > 0 && jg <= free_gpus; nb += 64) {
                 const uint32_t n = nb + lane;
                 uint32_t k = 0;
                 if (n < A.n_nodes) {
@@ -210,6 +307,7 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
             }
             if ((int)lane == turn) my_status = 1u;
             ++n_placed;
+            free_gpus -= jg;
             for (uint32_t nb = first; nb < end; nb += 64) {
                 const uint32_t n = nb + lane;
                 const uint32_t k = n < A.n_nodes ? take[n] : 0u;
@@ -227,14 +325,22 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
                 }
                 cursor += (uint32_t)__popcll(with);
             }
-            // the first node that still has a free GPU
-            while (first < A.n_nodes) {
-                const uint32_t n = first + lane;
+            // the first nodes that are still of use
+            while (first_g < A.n_nodes) {
+                const uint32_t n = first_g + lane;
                 const unsigned long long open = __ballot(n < A.n_nodes && nodeA[n] > 0);
-                if (open) { first += (uint32_t)__ffsll((long long)open) - 1u; break; }
-                first += 64;
+                if (open) { first_g += (uint32_t)__ffsll((long long)open) - 1u; break; }
+                first_g += 64;
             }
-            if (first > A.n_nodes) first = A.n_nodes;
+            if (first_g > A.n_nodes) first_g = A.n_nodes;
+            if (first_gc < first_g) first_gc = first_g;
+            while (first_gc < A.n_nodes) {
+                const uint32_t n = first_gc + lane;
+                const unsigned long long open = __ballot(n < A.n_nodes && nodeA[n] > 0 && nodeB[n] > 0);
+                if (open) { first_gc += (uint32_t)__ffsll((long long)open) - 1u; break; }
+                first_gc += 64;
+            }
+            if (first_gc > A.n_nodes) first_gc = A.n_nodes;
         }
         if (!have_off) my_off = cursor;
         if (j < A.n_jobs) { A.place_off[j] = my_off; A.status[j] = my_status; }
