@@ -129,6 +129,36 @@ def test_many_jobs_per_round(orc, placer, n_jobs, n_nodes, fill):
     print(f"{n_jobs} jobs on {n_nodes} nodes: {r0.n_placed}/{r0.n_failed} placed/failed roomy, {r1.n_placed}/{r1.n_failed} tight")
 
 
+def test_buffers_that_are_not_16_byte_aligned_and_no_result(orc, placer):
+    """The library reads and writes eight jobs at a time with 16-byte accesses when the
+    caller's buffers allow it; buffers that start 4 bytes off take the plain path.
+    Without a result struct the call does not wait."""
+    import torch
+    import paper_2408_08586_amd as rk
+    rng = np.random.default_rng(5)
+    J, n_nodes, gpn = 3001, 300, 8
+    g = np.where(rng.random(J) < 0.15, rng.choice([1, 2, 4, 8, 24], size=J), 0).astype(np.uint32)
+    a = jobs(orc, g, g * 2, (g * 10).astype(np.float32))
+    w_off, w_ent, w_st = orc.place(a, n_nodes, gpn, 96, 1600.0)
+    dev = "cuda:0"
+    raw = torch.zeros(4 + a.nbytes, dtype=torch.uint8, device=dev)
+    raw[4:] = torch.from_numpy(a.view(np.uint8).copy()).to(dev)
+    off = torch.full((J + 2,), -1, dtype=torch.int32, device=dev)
+    status = torch.full((J + 1,), -1, dtype=torch.int32, device=dev)
+    cap = n_nodes * gpn
+    ent = rk.new_place_entries(cap, dev)
+    assert raw[4:].data_ptr() % 16 == 4 and off[1:].data_ptr() % 16 == 4
+    res = rk.rk_place(placer.ctx, rk.rk_nodes(n_nodes, gpn, 96, 1600.0), J, raw[4:], off[1:], ent, cap, status[1:],
+                      want_result=False)
+    assert res is None
+    rk.rk_sync(placer.ctx)
+    assert np.array_equal(rk.u32(off)[1:], w_off) and np.array_equal(rk.u32(status)[1:], w_st)
+    got = rk.place_entries_to_numpy(ent, len(w_ent))
+    for f in ("node", "g", "c", "mem_gb"):
+        assert np.array_equal(got[f], w_ent[f]), f
+    assert rk.u32(off)[0] == 0xFFFFFFFF and rk.u32(status)[0] == 0xFFFFFFFF      # nothing before the buffers is touched
+
+
 def test_edge_cases(orc, placer):
     import paper_2408_08586_amd as rk
     same(orc, placer, jobs(orc, [], [], []), 4, 8, 96, 1600.0, in_order=0)                   # no jobs
