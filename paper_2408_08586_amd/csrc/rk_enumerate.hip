@@ -25,21 +25,27 @@ enum { TOT_NT_LO = 0, TOT_NT_HI, TOT_NS_LO, TOT_NS_HI, TOT_MAX_T, TOT_MAX_S, TOT
 enum { ERR_TOO_MANY_TRIPLES = 1, ERR_TOO_MANY_DIVISORS = 2, ERR_PARK_FULL = 4 };
 enum { MODE_COUNT = 0, MODE_FILL_SEARCH = 1, MODE_FILL_PARKED = 2 };
 
-// exclusive prefix sum of one value per thread over the workgroup
+// exclusive prefix sum of one value per thread over the workgroup (all threads call it): inside the
+// wavefronts by shuffles, then the wavefronts' totals through LDS (lds: one word per wavefront)
 __device__ uint32_t block_excl_scan(uint32_t v, uint32_t *lds, uint32_t *total) {
-    const uint32_t tid = threadIdx.x, nth = blockDim.x;
-    lds[tid] = v;
-    __syncthreads();
-    for (uint32_t off = 1; off < nth; off <<= 1) {
-        uint32_t add = tid >= off ? lds[tid - off] : 0u;
-        __syncthreads();
-        lds[tid] += add;
-        __syncthreads();
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_up((int)incl, off, 64);
+        if ((int)lane >= off) incl += o;
     }
-    const uint32_t incl = lds[tid];
-    *total = lds[nth - 1];
+    if (lane == 63u) lds[wave] = incl;
     __syncthreads();
-    return incl - v;
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < ENUM_THREADS / 64; ++w) {
+        if (w < wave) before += lds[w];
+        all += lds[w];
+    }
+    *total = all;
+    __syncthreads();
+    return before + incl - v;
 }
 
 template <int MODE>
@@ -52,7 +58,7 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     uint32_t *__restrict__ triples, uint32_t *__restrict__ seg_g, uint32_t *__restrict__ seg_first,
     uint32_t *__restrict__ totals, uint64_t cap_triples, uint64_t cap_segs) {
     __shared__ uint32_t dlist[MAX_DIV], plist[MAX_DIV];
-    __shared__ uint32_t keys[MAX_T], sorted[MAX_T];
+    __shared__ __align__(16) uint32_t keys[MAX_T], sorted[MAX_T];
     __shared__ uint32_t scan_tmp[ENUM_THREADS];
     __shared__ uint32_t nd, np, nk;
 
@@ -76,9 +82,15 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
         const bool any = l > 0 && b > 0 && mu > 0 && (b % mu) == 0;
         const uint32_t n = any ? b / mu : 0;
         // divisors of n (data-parallel sizes) and of l (pipeline sizes), unordered
+        // (every divisor d with d*d <= n brings n/d along, so the search stops at the square root)
         const uint32_t dmax = n < bounds.g_max ? n : bounds.g_max;
-        for (uint32_t d = tid + 1; d <= dmax; d += ENUM_THREADS)
-            if (n % d == 0) { uint32_t i = atomicAdd(&nd, 1u); if (i < MAX_DIV) dlist[i] = d; }
+        for (uint32_t d = tid + 1; (uint64_t)d * d <= n; d += ENUM_THREADS) {
+            const uint32_t e = n / d;
+            if (e * d == n) {
+                if (d <= dmax) { uint32_t i = atomicAdd(&nd, 1u); if (i < MAX_DIV) dlist[i] = d; }
+                if (e != d && e <= dmax) { uint32_t i = atomicAdd(&nd, 1u); if (i < MAX_DIV) dlist[i] = e; }
+            }
+        }
         uint32_t pmax = l < bounds.pp_max ? l : bounds.pp_max;
         pmax = pmax < bounds.g_max ? pmax : bounds.g_max;
         if (!any) pmax = 0;
@@ -114,11 +126,27 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
         if (nk > MAX_T) err |= ERR_TOO_MANY_TRIPLES;
         cnt = nk < MAX_T ? nk : MAX_T;
 
-        // rank sort: keys are distinct, the rank is the number of smaller keys
+        // rank sort: keys are distinct, the rank is the number of smaller keys.  The keys are read four at a time;
+        // the last group is filled up with the largest word, which is smaller than nothing
+        const uint32_t cnt4 = (cnt + 3u) & ~3u;                  // MAX_T is a multiple of four
+        if (tid < 4 && cnt + tid < cnt4) keys[cnt + tid] = 0xFFFFFFFFu;
+        __syncthreads();
         for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) {
             const uint32_t k = keys[i];
             uint32_t rank = 0;
-            for (uint32_t x = 0; x < cnt; ++x) rank += keys[x] < k ? 1u : 0u;
+            uint32_t x = 0;
+            for (; x + 16 <= cnt4; x += 16) {                    // four reads in flight
+                uint4 q[4];
+#pragma unroll
+                for (uint32_t u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const uint4 *>(&keys[x + 4 * u]);
+#pragma unroll
+                for (uint32_t u = 0; u < 4; ++u)
+                    rank += (q[u].x < k ? 1u : 0u) + (q[u].y < k ? 1u : 0u) + (q[u].z < k ? 1u : 0u) + (q[u].w < k ? 1u : 0u);
+            }
+            for (; x < cnt4; x += 4) {
+                const uint4 q = *reinterpret_cast<const uint4 *>(&keys[x]);
+                rank += (q.x < k ? 1u : 0u) + (q.y < k ? 1u : 0u) + (q.z < k ? 1u : 0u) + (q.w < k ? 1u : 0u);
+            }
             sorted[rank] = k;
         }
         __syncthreads();
