@@ -5,7 +5,10 @@
 // lists of b/mu (data-parallel sizes) and of the layer count (pipeline sizes),
 // forms the products d*t*p <= g_max with t in {1,2,4,8} for every allowed
 // micro-batch shift v (d must divide b/(mu*2^v)), and orders them by the key
-// (g, t, p, v) with a rank sort in LDS.  The counting pass also parks the
+// (g, t, p, v) in LDS: a bitmap of the GPU counts that occur gives every key
+// its segment (rank of its g among the distinct counts = a population count),
+// the keys are gathered by segment, and only the few keys of one segment are
+// compared with each other.  The counting pass also parks the
 // sorted keys in a scratch buffer; after the exclusive scan of the counts the
 // fill pass only decodes them into place (it repeats the search only when the
 // scratch buffer was too small).  The fill pass is launched while the counts
@@ -57,8 +60,11 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     const uint32_t *__restrict__ triple_off, const uint32_t *__restrict__ seg_off,
     uint32_t *__restrict__ triples, uint32_t *__restrict__ seg_g, uint32_t *__restrict__ seg_first,
     uint32_t *__restrict__ totals, uint64_t cap_triples, uint64_t cap_segs) {
-    __shared__ uint32_t dlist[MAX_DIV], plist[MAX_DIV];
+    extern __shared__ uint32_t gmap[];                      // counting and search modes: bitmap of the GPU counts, word prefixes
+    __shared__ uint32_t lists[2 * MAX_DIV + 1];             // the two divisor lists; later the segments' sizes and starts
+    uint32_t *dlist = lists, *plist = lists + MAX_DIV;
     __shared__ __align__(16) uint32_t keys[MAX_T], sorted[MAX_T];
+    static_assert(2 * MAX_DIV >= MAX_T, "the segment table reuses the divisor lists");
     __shared__ uint32_t scan_tmp[ENUM_THREADS];
     __shared__ uint32_t nd, np, nk;
 
@@ -126,31 +132,66 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
         if (nk > MAX_T) err |= ERR_TOO_MANY_TRIPLES;
         cnt = nk < MAX_T ? nk : MAX_T;
 
-        // rank sort: keys are distinct, the rank is the number of smaller keys.  The keys are read four at a time;
-        // the last group is filled up with the largest word, which is smaller than nothing
-        const uint32_t cnt4 = (cnt + 3u) & ~3u;                  // MAX_T is a multiple of four
-        if (tid < 4 && cnt + tid < cnt4) keys[cnt + tid] = 0xFFFFFFFFu;
+        // Sort.  Keys are distinct.  (1) bitmap of the GPU counts that occur; (2) population counts in front of
+        // every bitmap word: a key's segment is the rank of its g among the distinct counts; (3) sizes of the
+        // segments, every key takes a slot in its own; (4) starts of the segments; (5) keys gathered by segment;
+        // (6) a key's final place = start of its segment + number of smaller keys inside it.
+        constexpr uint32_t PER = MAX_T / ENUM_THREADS;          // keys per thread, at most
+        const uint32_t n_words = (bounds.g_max >> 5) + 1u;
+        uint32_t *bitmap = gmap, *before = gmap + n_words, *seg = lists;
+        for (uint32_t w = tid; w < n_words; w += ENUM_THREADS) bitmap[w] = 0u;
+        for (uint32_t i = tid; i <= cnt; i += ENUM_THREADS) seg[i] = 0u;     // there are at most cnt segments
         __syncthreads();
-        for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) {
-            const uint32_t k = keys[i];
-            uint32_t rank = 0;
-            uint32_t x = 0;
-            for (; x + 16 <= cnt4; x += 16) {                    // four reads in flight
-                uint4 q[4];
+        uint32_t mine[PER], slot[PER];
 #pragma unroll
-                for (uint32_t u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const uint4 *>(&keys[x + 4 * u]);
+        for (uint32_t r = 0; r < PER; ++r) {
+            const uint32_t i = tid + r * ENUM_THREADS;
+            mine[r] = i < cnt ? keys[i] : 0u;
+            if (i < cnt) atomicOr(&bitmap[mine[r] >> 21], 1u << ((mine[r] >> 16) & 31u));
+        }
+        __syncthreads();
+        const uint32_t wpt = (n_words + ENUM_THREADS - 1) / ENUM_THREADS;
+        const uint32_t w_lo = tid * wpt < n_words ? tid * wpt : n_words;
+        const uint32_t w_hi = w_lo + wpt < n_words ? w_lo + wpt : n_words;
+        uint32_t bits = 0;
+        for (uint32_t w = w_lo; w < w_hi; ++w) bits += (uint32_t)__popc(bitmap[w]);
+        uint32_t n_seg;
+        uint32_t run = block_excl_scan(bits, scan_tmp, &n_seg);
+        for (uint32_t w = w_lo; w < w_hi; ++w) { before[w] = run; run += (uint32_t)__popc(bitmap[w]); }
+        __syncthreads();
+        auto segment_of = [&](uint32_t key) -> uint32_t {
+            const uint32_t g = key >> 16;
+            return before[g >> 5] + (uint32_t)__popc(bitmap[g >> 5] & ((1u << (g & 31u)) - 1u));
+        };
 #pragma unroll
-                for (uint32_t u = 0; u < 4; ++u)
-                    rank += (q[u].x < k ? 1u : 0u) + (q[u].y < k ? 1u : 0u) + (q[u].z < k ? 1u : 0u) + (q[u].w < k ? 1u : 0u);
+        for (uint32_t r = 0; r < PER; ++r)
+            if (tid + r * ENUM_THREADS < cnt) slot[r] = atomicAdd(&seg[segment_of(mine[r])], 1u);
+        __syncthreads();
+        const uint32_t spt = (n_seg + ENUM_THREADS - 1) / ENUM_THREADS;
+        const uint32_t s_lo = tid * spt < n_seg ? tid * spt : n_seg;
+        const uint32_t s_hi = s_lo + spt < n_seg ? s_lo + spt : n_seg;
+        uint32_t sizes = 0, all;
+        for (uint32_t q = s_lo; q < s_hi; ++q) sizes += seg[q];
+        run = block_excl_scan(sizes, scan_tmp, &all);
+        for (uint32_t q = s_lo; q < s_hi; ++q) { const uint32_t n = seg[q]; seg[q] = run; run += n; }
+        if (tid == 0) seg[n_seg] = cnt;
+        __syncthreads();
+#pragma unroll
+        for (uint32_t r = 0; r < PER; ++r)
+            if (tid + r * ENUM_THREADS < cnt) sorted[seg[segment_of(mine[r])] + slot[r]] = mine[r];
+        __syncthreads();
+#pragma unroll
+        for (uint32_t r = 0; r < PER; ++r) {
+            if (tid + r * ENUM_THREADS < cnt) {
+                const uint32_t q = segment_of(mine[r]), a = seg[q], b = seg[q + 1];
+                uint32_t rank = a;
+                for (uint32_t x = a; x < b; ++x) rank += sorted[x] < mine[r] ? 1u : 0u;
+                keys[rank] = mine[r];                           // every thread holds its keys in registers by now
             }
-            for (; x < cnt4; x += 4) {
-                const uint4 q = *reinterpret_cast<const uint4 *>(&keys[x]);
-                rank += (q.x < k ? 1u : 0u) + (q.y < k ? 1u : 0u) + (q.z < k ? 1u : 0u) + (q.w < k ? 1u : 0u);
-            }
-            sorted[rank] = k;
         }
         __syncthreads();
     }
+    const uint32_t *fin = MODE == MODE_FILL_PARKED ? sorted : keys;      // the keys in order
 
     // segments: runs of equal g.  Each thread owns a contiguous chunk.
     const uint32_t chunk = (cnt + ENUM_THREADS - 1) / ENUM_THREADS;
@@ -158,7 +199,7 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     const uint32_t hi = lo + chunk < cnt ? lo + chunk : cnt;
     uint32_t starts = 0;
     for (uint32_t i = lo; i < hi; ++i)
-        starts += (i == 0 || (sorted[i] >> 16) != (sorted[i - 1] >> 16)) ? 1u : 0u;
+        starts += (i == 0 || (fin[i] >> 16) != (fin[i - 1] >> 16)) ? 1u : 0u;
     uint32_t nseg;
     uint32_t sidx = block_excl_scan(starts, scan_tmp, &nseg);
 
@@ -172,17 +213,17 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
         // park the sorted keys in the job's slot for the fill pass, if they fit
         if (cnt <= park_stride) {
             const size_t at = (size_t)j * park_stride;
-            for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) park[at + i] = sorted[i];
+            for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) park[at + i] = fin[i];
         }
         return;
     }
     const uint32_t t0 = triple_off[j], s0 = seg_off[j];
     for (uint32_t i = lo; i < hi; ++i) {
-        const uint32_t k = sorted[i];
+        const uint32_t k = fin[i];
         const uint32_t g = k >> 16, lt = (k >> 14) & 3u, p = (k >> 2) & 0xFFFu, v = k & 3u;
         const uint32_t d = g / (p << lt);
         triples[t0 + i] = d | (lt << 16) | (p << 18) | (v << 30);
-        if (i == 0 || g != (sorted[i - 1] >> 16)) {
+        if (i == 0 || g != (fin[i - 1] >> 16)) {
             seg_g[s0 + sidx] = g;
             seg_first[s0 + sidx] = i;
             ++sidx;
@@ -357,9 +398,10 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
     uint32_t *h = ctx->h_stage;
     if (!ctx->counts_ev) RK_HIP(ctx, hipEventCreateWithFlags(&ctx->counts_ev, hipEventDisableTiming));
 
+    const size_t gmap_bytes = (size_t)((bounds->g_max >> 5) + 1u) * 2 * sizeof(uint32_t);   // bitmap + word prefixes
     k_zero_words<<<1, 64, 0, ctx->stream>>>(totals, TOT_WORDS);
     if (J > 0) {
-        k_enumerate<MODE_COUNT><<<J, ENUM_THREADS, 0, ctx->stream>>>(
+        k_enumerate<MODE_COUNT><<<J, ENUM_THREADS, gmap_bytes, ctx->stream>>>(
             jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
             nullptr, nullptr, nullptr, nullptr, nullptr, totals, 0, 0);
         RK_CHECK_LAUNCH(ctx, "k_enumerate<count>");
@@ -404,7 +446,7 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
         memcpy(table->h_seg_off, h + 16 + J + 1, ((size_t)J + 1) * 4);
     }
     if (J > 0 && !parked) {                                   // the parked keys were incomplete: search again
-        k_enumerate<MODE_FILL_SEARCH><<<J, ENUM_THREADS, 0, ctx->stream>>>(
+        k_enumerate<MODE_FILL_SEARCH><<<J, ENUM_THREADS, gmap_bytes, ctx->stream>>>(
             jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
             off_t, off_s, table->triples, table->seg_g, table->seg_first, totals, 0, 0);
         RK_CHECK_LAUNCH(ctx, "k_enumerate<fill>");
