@@ -64,6 +64,7 @@ struct JobState {            // per job of the call, between the kernels
     float *step_slope;       // cached best next step: slope (0 = none), target, GPUs it adds
     uint16_t *step_tgt, *step_dg;
     unsigned long long *free_g, *free_c;   // per round: capacity left (after apply; after the tail)
+    uint32_t *cpu_steps;     // per round: non-zero when some job's CPU walk has a step (else the CPU pass has nothing to do)
     double *partial;         // per round and block of k_mem_wish: {sum of wish GiB, sum of thr/ref}
     uint32_t blocks_per_round;
     // floors, all null without them: the state a job starts from (segment index
@@ -188,6 +189,7 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
     for (size_t i = (size_t)blockIdx.x * HULL_THREADS + threadIdx.x; i < zero_bins; i += (size_t)gridDim.x * HULL_THREADS) {
         zero.g[i] = 0u;
         zero.c[i] = 0ull;
+        if (i < X.R.n_rounds) st.cpu_steps[i] = 0u;       // (there are more bins than rounds)
     }
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t jrel = blockIdx.x * (HULL_THREADS / 64) + (threadIdx.x >> 6);
@@ -303,6 +305,7 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
         ++k;
     }
     for (uint32_t kk = k + lane; kk < H.width; kk += 64) H.key[(size_t)kk * H.stride + jrel] = 0u;   // unused positions
+    if (PASS == 1 && k > 0 && lane == 0) st.cpu_steps[rnd] = 1u;
 }
 
 // ------------------------------------------------------------------ threshold search
@@ -428,6 +431,7 @@ __global__ __launch_bounds__(JOB_THREADS) void k_hist(Ctx X, JobState st, HullBu
     __shared__ unsigned long long lc[BINS];
     __shared__ CutScratch cs;
     const uint32_t rnd = blockIdx.y, tid = threadIdx.x;
+    if (PASS == 1 && st.cpu_steps[rnd] == 0u) return;       // no job can use more CPUs: the whole pass is empty
     uint32_t J0, J1;
     rk_cluster cl;
     round_of(X.R, rnd, J0, J1, cl);
@@ -605,6 +609,7 @@ template <int PASS>
 __global__ __launch_bounds__(JOB_THREADS) void k_apply(Ctx X, JobState st, HullBuf H, Hist hist) {
     __shared__ CutScratch cs;
     const uint32_t rnd = blockIdx.y, tid = threadIdx.x;
+    if (PASS == 1 && st.cpu_steps[rnd] == 0u) return;       // empty pass: every job keeps the CPU level it has
     uint32_t J0, J1;
     rk_cluster cl;
     round_of(X.R, rnd, J0, J1, cl);
@@ -883,6 +888,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_tail(Ctx X, uint32_t max_jobs,
     extern __shared__ float lds_dyn[];
     __shared__ unsigned long long red[TAIL_RED_WORDS];
     const uint32_t rnd = blockIdx.x;
+    if (PASS == 1 && st.cpu_steps[rnd] == 0u) return;       // empty pass
     uint32_t J0, J1;
     rk_cluster cl;
     round_of(X.R, rnd, J0, J1, cl);
@@ -1274,7 +1280,8 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
     if ((rc = scratch_typed(ctx, SL_ST_STEP_TGT, (size_t)H.stride, &st.step_tgt))) return rc;
     if ((rc = scratch_typed(ctx, SL_ST_STEP_DG, (size_t)H.stride, &st.step_dg))) return rc;
     if ((rc = scratch_typed(ctx, SL_ST_FREEG, (size_t)n_rounds * 2, &st.free_g))) return rc;   // [free G | free C] after apply
-    if ((rc = scratch_typed(ctx, SL_ST_FREEC, (size_t)n_rounds, &st.free_c))) return rc;
+    if ((rc = scratch_typed(ctx, SL_ST_FREEC, (size_t)n_rounds + ((size_t)n_rounds + 1) / 2, &st.free_c))) return rc;
+    st.cpu_steps = reinterpret_cast<uint32_t *>(st.free_c + n_rounds);
     if ((rc = scratch_typed(ctx, SL_ST_PARTIAL, (size_t)n_rounds * st.blocks_per_round * 2, &st.partial))) return rc;
     st.fl_gi = nullptr; st.fl_ci = nullptr; st.waits = nullptr; st.cap0 = nullptr;
     if (given) {
