@@ -308,6 +308,136 @@ __global__ __launch_bounds__(HULL_THREADS) void k_hull(Ctx X, JobState st, HullB
     if (PASS == 1 && k > 0 && lane == 0) st.cpu_steps[rnd] = 1u;
 }
 
+// The same walks with several jobs per wavefront, for calls in which no job has
+// more than LANES amounts (LANES = 16 or 32): a job takes LANES neighbouring
+// lanes, the wavefront loops until the last of its jobs has finished, and a
+// job's maximum is taken over its own lanes only.
+template <int LANES>
+__device__ __forceinline__ unsigned long long group_max_u64(unsigned long long v, uint32_t lane) {
+    unsigned long long o;
+    o = dpp_u64<0xB1>(v);  v = o > v ? o : v;                   // quad_perm [1,0,3,2]
+    o = dpp_u64<0x4E>(v);  v = o > v ? o : v;                   // quad_perm [2,3,0,1]
+    o = dpp_u64<0x141>(v); v = o > v ? o : v;                   // row_half_mirror
+    o = dpp_u64<0x140>(v); v = o > v ? o : v;                   // row_mirror: every row of 16 lanes holds its maximum
+    if (LANES == 16) return v;
+    unsigned long long row[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        row[r] = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), 16 * r) << 32) |
+                 (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, 16 * r);
+    const unsigned long long lo = row[0] > row[1] ? row[0] : row[1], hi = row[2] > row[3] ? row[2] : row[3];
+    return lane < 32 ? lo : hi;
+}
+
+template <int PASS, int LANES>
+__global__ __launch_bounds__(HULL_THREADS) void k_hull_groups(Ctx X, JobState st, HullBuf H, Hist zero, size_t zero_bins) {
+    for (size_t i = (size_t)blockIdx.x * HULL_THREADS + threadIdx.x; i < zero_bins; i += (size_t)gridDim.x * HULL_THREADS) {
+        zero.g[i] = 0u;
+        zero.c[i] = 0ull;
+        if (i < X.R.n_rounds) st.cpu_steps[i] = 0u;
+    }
+    constexpr uint32_t PER_WAVE = 64 / LANES;
+    const uint32_t lane = threadIdx.x & 63u, sub = lane % LANES, group_base = lane - sub;
+    const uint32_t slot = (blockIdx.x * (HULL_THREADS / 64) + (threadIdx.x >> 6)) * PER_WAVE + lane / LANES;
+    const bool valid = slot < H.stride;                    // lanes of a slot past the end stay for the shuffles
+    const uint32_t jrel = valid ? slot : H.stride - 1;
+    const uint32_t j = X.jb + jrel;
+    const uint32_t rnd = round_index_of(X.R, j);
+    uint32_t rj0, rj1;
+    rk_cluster cl;
+    round_of(X.R, rnd, rj0, rj1, cl);
+    const GridDev &grid = X.grid;
+    const float *__restrict__ vals = PASS == 0 ? X.curve_thr : X.best_thr;
+    const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem;
+    const uint32_t ju = job_of(X, j);
+    const uint32_t s0 = X.tb.seg_off[ju], ns = X.tb.seg_off[ju + 1] - s0;
+    const uint64_t jbase = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]);
+    const float ref = X.ref_thr[ju];
+
+    uint32_t npts, g_fixed = 0, c_fixed = 0;
+    int32_t cur_i;
+    unsigned long long cost_cur, cap_c, cap_g = 0;
+    float cur;
+    int32_t gi = -1;
+    if (PASS == 0) {
+        const Floor fl = floor_of(st, jrel);
+        unsigned long long startG, startC;
+        pass_caps<0>(X.R, cl, st, rnd, startG, startC);
+        c_fixed = fl.ci;
+        npts = fl.state != RK_JOB_NORMAL ? 0u : ns;
+        cur_i = fl.gi;
+        cost_cur = fl.gi < 0 ? 0ull : (unsigned long long)X.tb.seg_g[s0 + fl.gi];
+        cur = fl.gi < 0 ? 0.f : vals[jbase + (uint64_t)(c_fixed * n_mem + n_mem - 1) * ns + fl.gi];
+        cap_g = startG + cost_cur;                       // the floor is already paid for
+        cap_c = startC + (fl.gi < 0 ? 0ull : cpu_cost(grid, c_fixed, (uint32_t)cost_cur));
+    } else {
+        gi = st.gi[jrel];
+        npts = (gi < 0 || (st.waits && st.waits[jrel] != RK_JOB_NORMAL)) ? 0u : grid.n_cpu;
+        g_fixed = gi < 0 ? 0u : st.g[jrel];
+        cur_i = (int32_t)st.ci[jrel];
+        cost_cur = cpu_cost(grid, (uint32_t)cur_i, g_fixed);
+        cap_c = st.free_c[rnd] + cost_cur;               // the level held is already paid for
+        cur = gi < 0 ? 0.f : vals[jbase + (uint64_t)((uint32_t)cur_i * n_mem + n_mem - 1) * ns + gi];
+    }
+    if (!valid) npts = 0;
+    // the lane's amount: cost in the pass's resource, value, and whether the round could ever afford it
+    unsigned long long cost0 = 0;
+    float val0 = 0.f;
+    bool can = false;
+    if (sub < npts) {
+        cost0 = PASS == 0 ? (unsigned long long)X.tb.seg_g[s0 + sub] : cpu_cost(grid, sub, g_fixed);
+        val0 = PASS == 0 ? vals[jbase + (uint64_t)(c_fixed * n_mem + n_mem - 1) * ns + sub]
+                         : vals[jbase + (uint64_t)(sub * n_mem + n_mem - 1) * ns + gi];
+        can = PASS == 0 ? (cost0 <= cap_g && cpu_cost(grid, c_fixed, (uint32_t)cost0) <= cap_c) : cost0 <= cap_c;
+    }
+
+    uint32_t k = 0;
+    float prev = __uint_as_float(0x7F800000u);
+    bool walking = npts > 0;                               // the same in all lanes of a job
+    while (__ballot(walking && k < H.width)) {             // until the wavefront's last job has finished
+        unsigned long long best = 0;
+        if (walking && k < H.width && can && (int32_t)sub > cur_i && val0 > cur) {
+            float sl = (val0 - cur) / ref;
+            sl = sl / (float)(cost0 - cost_cur);
+            best = ((unsigned long long)__float_as_uint(sl) << 32) | (0xFFFFFFFFu - sub);
+        }
+        best = group_max_u64<LANES>(best, lane);
+        const bool step = walking && k < H.width && (best >> 32) != 0;
+        const float top = __uint_as_float((uint32_t)(best >> 32));
+        const uint32_t top_s = step ? 0xFFFFFFFFu - (uint32_t)best : 0u;
+        const int src = (int)(group_base + top_s);        // the lane that holds the chosen amount
+        const unsigned long long top_cost = ((unsigned long long)(uint32_t)__shfl((int)(uint32_t)(cost0 >> 32), src, 64) << 32) |
+                                            (uint32_t)__shfl((int)(uint32_t)cost0, src, 64);
+        const float top_val = __shfl(val0, src, 64);
+        if (step) {
+            prev = top < prev ? top : prev;
+            if (sub == 0) {
+                const size_t e = (size_t)k * H.stride + jrel;
+                H.key[e] = __float_as_uint(prev);
+                H.raw[e] = top;
+                H.tgt[e] = (uint16_t)top_s;
+                if (PASS == 0) {
+                    H.dg[e] = (uint32_t)(top_cost - cost_cur);
+                    H.dc[e] = cpu_cost(grid, c_fixed, (uint32_t)top_cost) - (cost_cur ? cpu_cost(grid, c_fixed, (uint32_t)cost_cur) : 0ull);
+                } else {
+                    H.dg[e] = 0u;
+                    H.dc[e] = top_cost - cost_cur;
+                }
+            }
+            cur = top_val;
+            cur_i = (int32_t)top_s;
+            cost_cur = top_cost;
+            ++k;
+        } else {
+            walking = false;
+        }
+    }
+    if (valid) {
+        for (uint32_t kk = k + sub; kk < H.width; kk += LANES) H.key[(size_t)kk * H.stride + jrel] = 0u;   // unused positions
+        if (PASS == 1 && k > 0 && sub == 0) st.cpu_steps[rnd] = 1u;
+    }
+}
+
 // ------------------------------------------------------------------ threshold search
 // Highest bin whose steps, added to everything above it, no longer fit.
 // bin = -1: all bins fit.  base*: cost of the bins above `bin`.
@@ -1219,12 +1349,21 @@ int32_t scratch_typed(rk_ctx *ctx, int slot, size_t count, T **out) {
 
 template <int PASS>
 int32_t launch_pass(rk_ctx *ctx, const Ctx &X, const JobState &st, const HullBuf &H, const Hist &hist,
-                    uint32_t n_rounds, uint32_t n_jobs, uint32_t mj, size_t tail_lds, size_t zero_bins) {
+                    uint32_t n_rounds, uint32_t n_jobs, uint32_t mj, uint32_t max_segs, size_t tail_lds, size_t zero_bins) {
     hipStream_t s = ctx->stream;
     const uint32_t hull_blocks = (n_jobs + (HULL_THREADS / 64) - 1) / (HULL_THREADS / 64);
     const dim3 job_grid(st.blocks_per_round, n_rounds);
     if (n_jobs > 0) {
-        k_hull<PASS><<<hull_blocks, HULL_THREADS, 0, s>>>(X, st, H, hist, zero_bins);
+        // amounts per job: GPU counts (at most max_segs) in the GPU pass, CPU levels in the CPU pass
+        const uint32_t amounts = PASS == 0 ? max_segs : X.grid.n_cpu;
+        const uint32_t waves = HULL_THREADS / 64;
+        if (amounts <= 16) {
+            k_hull_groups<PASS, 16><<<(n_jobs + 4 * waves - 1) / (4 * waves), HULL_THREADS, 0, s>>>(X, st, H, hist, zero_bins);
+        } else if (amounts <= 32) {
+            k_hull_groups<PASS, 32><<<(n_jobs + 2 * waves - 1) / (2 * waves), HULL_THREADS, 0, s>>>(X, st, H, hist, zero_bins);
+        } else {
+            k_hull<PASS><<<hull_blocks, HULL_THREADS, 0, s>>>(X, st, H, hist, zero_bins);
+        }
         RK_CHECK_LAUNCH(ctx, "k_hull");
     }
     if (mj <= SMALL_ROUND_JOBS) {
@@ -1334,8 +1473,8 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
         k_floors<<<n_rounds, FLOOR_THREADS, (size_t)mj * 8, s>>>(X, st, *sla, mj);
         RK_CHECK_LAUNCH(ctx, "k_floors");
     }
-    if ((rc = launch_pass<0>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, lds, hists ? hist_bins : 0))) return rc;
-    if ((rc = launch_pass<1>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, lds, 0))) return rc;
+    if ((rc = launch_pass<0>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, max_segs_per_job, lds, hists ? hist_bins : 0))) return rc;
+    if ((rc = launch_pass<1>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, max_segs_per_job, lds, 0))) return rc;
     if (max_jobs > 0) {
         k_mem_wish<<<dim3(st.blocks_per_round, n_rounds), JOB_THREADS, 0, s>>>(X, st, assign);
         RK_CHECK_LAUNCH(ctx, "k_mem_wish");
