@@ -914,7 +914,7 @@ __device__ __forceinline__ void tail_run(const Ctx &X, const JobState &st, uint3
     auto key_of = [](float v, uint32_t jl) -> unsigned long long {
         return ((unsigned long long)__float_as_uint(v) << 32) | (0xFFFFFFFFu - jl);
     };
-    uint32_t steps = 0, turn = 0;
+    uint32_t turn = 0, moved = 0;                               // moved: bit k = the thread's k-th job took a step here
     for (;;) {
         if (PASS == 0 ? freeG == 0 : freeC == 0) break;         // nothing can fit any more
         unsigned long long kf = 0, ks = 0;
@@ -967,7 +967,6 @@ __device__ __forceinline__ void tail_run(const Ctx &X, const JobState &st, uint3
             continue;
         }
         if (!(kf >> 32)) break;                                 // no positive slope left
-        ++steps;
         const uint32_t jw = 0xFFFFFFFFu - (uint32_t)kf;
         const uint32_t owner = jw % TAIL_THREADS;
         const uint32_t kw = (uint32_t)__builtin_amdgcn_readfirstlane((int)(jw / TAIL_THREADS));   // same in all lanes
@@ -989,6 +988,7 @@ __device__ __forceinline__ void tail_run(const Ctx &X, const JobState &st, uint3
             const Step nx = best_step_wave<PASS>(X, J0 + jw, g_i, held, c_i, freeG, freeC);
             if (tid == owner) {
                 if (PASS == 0) gi[jw] = (int16_t)g_i; else ci[jw] = (uint16_t)c_i;
+                moved |= 1u << kw;
                 tgt[jw] = (uint16_t)nx.tgt;
                 const uint32_t need = need_cpus(g_i, c_i, nx.tgt, PASS == 0 ? nx.dg : held);
 #pragma unroll
@@ -997,15 +997,14 @@ __device__ __forceinline__ void tail_run(const Ctx &X, const JobState &st, uint3
             }
         }
     }
-    if (steps) {                                                // something changed since k_apply
-        for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) {  // the thread's own jobs
-            if (PASS == 0) {
-                const int32_t s_i = gi[jl];
-                st.gi[jrel0 + jl] = s_i;
-                st.g[jrel0 + jl] = s_i < 0 ? 0u : X.tb.seg_g[X.tb.seg_off[job_of(X, J0 + jl)] + s_i];
-            } else {
-                st.ci[jrel0 + jl] = ci[jl];
-            }
+    for (; moved; moved &= moved - 1u) {                        // only the jobs that took a step here changed since k_apply
+        const uint32_t jl = tid + ((uint32_t)__ffs((int)moved) - 1u) * TAIL_THREADS;
+        if (PASS == 0) {
+            const int32_t s_i = gi[jl];
+            st.gi[jrel0 + jl] = s_i;
+            st.g[jrel0 + jl] = s_i < 0 ? 0u : X.tb.seg_g[X.tb.seg_off[job_of(X, J0 + jl)] + s_i];
+        } else {
+            st.ci[jrel0 + jl] = ci[jl];
         }
     }
     if (PASS == 0 && tid == 0) st.free_c[rnd] = freeC;          // what the CPU pass starts from
