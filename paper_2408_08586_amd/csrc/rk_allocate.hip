@@ -917,17 +917,23 @@ __device__ __forceinline__ void tail_run(const Ctx &X, const JobState &st, uint3
     uint32_t turn = 0, moved = 0;                               // moved: bit k = the thread's k-th job took a step here
     for (;;) {
         if (PASS == 0 ? freeG == 0 : freeC == 0) break;         // nothing can fit any more
-        unsigned long long kf = 0, ks = 0;
+        // the thread's best exact step and best bound: plain float compares (its jobs come in rising order, so the
+        // first of equal slopes is the lower job), the two keys are built once at the end
+        const uint32_t roomG = freeG > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)freeG;
+        const uint32_t roomC = freeC > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)freeC;
+        float vf = 0.f, vs = 0.f;
+        uint32_t jf = 0, js = 0;
 #pragma unroll
         for (int k = 0; k < KMAX; ++k) {
             const uint32_t jl = tid + (uint32_t)k * TAIL_THREADS;
             float v = slope[k];
-            const bool stopped = v > 0.f && ((PASS == 0 && dg[k] > freeG) || dc[k] > freeC);
+            const bool stopped = v > 0.f && ((PASS == 0 && dg[k] > roomG) || dc[k] > roomC);
             v = stopped ? -v : v;
             slope[k] = v;
-            if (v > 0.f) { const unsigned long long c = key_of(v, jl); kf = c > kf ? c : kf; }
-            else if (v < 0.f) { const unsigned long long c = key_of(-v, jl); ks = c > ks ? c : ks; }
+            if (v > vf) { vf = v; jf = jl; }
+            if (-v > vs) { vs = -v; js = jl; }
         }
+        unsigned long long kf = vf > 0.f ? key_of(vf, jf) : 0ull, ks = vs > 0.f ? key_of(vs, js) : 0ull;
         kf = wave_max_u64_rows(kf);
         ks = wave_max_u64_rows(ks);
         unsigned long long *both = red + 2 * turn;              // three copies in turn: the next one is cleared meanwhile
