@@ -295,6 +295,45 @@ def test_allocate_many_jobs_random_curves(gpu, orc, n_jobs):
     run.close()
 
 
+@pytest.mark.parametrize("g_max", [128, 1024])
+def test_allocate_jobs_with_many_gpu_counts(gpu, orc, g_max):
+    """Jobs with more than 32 (one wavefront per job) and more than 64 valid GPU
+    counts (several rounds of 64 amounts inside a walk), on drawn values."""
+    import paper_2408_08586_amd as rk
+    rng = np.random.default_rng(g_max)
+    base = workloads.tiny()
+    kinds = np.array([[96, 5040, 1], [60, 2520, 1], [12, 32, 1], [96, 1680, 1]], np.uint32)
+    ints = kinds[rng.integers(0, len(kinds), 120)]
+    coef = np.tile(base.coef[:1], (len(ints), 1))
+    coef[:, 16] = rng.uniform(0.5, 4.0, len(ints)).astype(np.float32)
+    wl = workloads.Workload("many_counts", coef, ints, workloads.Bounds(g_max=g_max), base.grid, workloads.Env(),
+                            workloads.Cluster(8, 8, 64.0))
+    ot = orc.enumerate_plans(wl.ints, wl.bounds)
+    widest = int(np.diff(ot.seg_off).max())
+    assert widest > 64 if g_max == 1024 else 32 < widest <= 64
+    n_rows = len(wl.grid.cpu_levels) * len(wl.grid.mem_levels_gb)
+    n = ot.n_segments(n_rows)
+    g_of = np.concatenate([np.tile(ot.seg_g[ot.seg_off[j]:ot.seg_off[j + 1]], n_rows) for j in range(wl.n_jobs)])
+    bt = (g_of ** rng.uniform(0.3, 1.0, n)) * rng.uniform(0.5, 1.5, n)
+    bt = np.round(bt * 8) / 8
+    bt[rng.uniform(size=n) < 0.15] = 0
+    bt = bt.astype(np.float32)
+    bp = rng.integers(0, 1000, n).astype(np.uint32)
+    bp[bt == 0] = 0xFFFFFFFF
+    ct, _, _ = orc.curves(ot, wl.grid, bt, bp)
+    run = gpu(wl)
+    run.enumerate()
+    oracle_table_equal(run.table_numpy(), ot)
+    d_bt, d_bp, d_ct = run.dev_f32(bt), run.dev_u32(bp), run.dev_f32(ct)
+    for G, Cc, M in ((3000, 50000, 1.0e6), (700, 2000, 1.0e6), (12000, 10 ** 6, 5000.0)):
+        cl = workloads.Cluster(G, Cc, M)
+        e_assign, e_total, _ = orc.greedy(wl.coef[:, 16], ot, wl.grid, cl, bt, bp, ct)
+        assign, total = run.allocate(d_bt, d_bp, d_ct, cluster=rk.make_cluster(cl))
+        assert np.array_equal(assign, e_assign), (G, Cc, M)
+        assert total == pytest.approx(e_total, rel=1e-6)
+    run.close()
+
+
 def test_allocate_on_a_job_range(gpu, orc):
     """rk_allocate on jobs [5, 23) of a larger table, arrays in the layout of that range."""
     import paper_2408_08586_amd as rk
