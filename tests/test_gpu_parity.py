@@ -79,7 +79,8 @@ def test_enumerate_odd_jobs_and_bounds(gpu, orc):
                      [1, 1, 1], [60, 360, 1], [97, 128, 1]], np.uint32)
     coef = np.tile(workloads.tiny().coef[:1], (len(ints), 1))
     for b in (workloads.Bounds(g_max=8), workloads.Bounds(g_max=24, tp_max=4, pp_max=3),
-              workloads.Bounds(g_max=720, tp_max=2), workloads.Bounds(g_max=1, tp_max=1, pp_max=1)):
+              workloads.Bounds(g_max=720, tp_max=2), workloads.Bounds(g_max=1, tp_max=1, pp_max=1),
+              workloads.Bounds(g_max=65535, tp_max=8, pp_max=4095)):        # the largest bounds the library takes
         wl = workloads.Workload("odd", coef, ints, b, workloads.tiny().grid, workloads.Env(), workloads.Cluster(8, 8, 64.0))
         run = gpu(wl)
         run.enumerate()

@@ -167,6 +167,11 @@ def test_edge_cases(orc, placer):
     same(orc, placer, jobs(orc, [8], [8], [1600.0]), 1, 8, 96, 1600.0, in_order=1)            # memory exactly full
     same(orc, placer, jobs(orc, [8], [96], [100.0]), 1, 8, 96, 1600.0, in_order=0)            # CPUs exactly full
     same(orc, placer, jobs(orc, [4, 4], [0, 0], [0.0, 0.0]), 1, 8, 0, 0.0, in_order=0)        # nodes without CPUs or memory
+    # amounts beyond 16 bits (the library switches to 64-bit products): 81,920 CPUs, 70,000 GPUs
+    same(orc, placer, jobs(orc, [5, 2048, 3], [10, 81920, 7], [0.0, 4096.0, 1.0]), 300, 8, 400, 64.0, in_order=0)
+    same(orc, placer, jobs(orc, [5, 2048, 3], [10, 81920, 7], [0.0, 4096.0, 1.0]), 300, 8, 300, 64.0, in_order=1)
+    same(orc, placer, jobs(orc, [3, 70000, 9], [3, 140001, 9], [0.0, 7.0e4, 0.0]), 4096, 32, 100, 64.0, in_order=0)
+    same(orc, placer, jobs(orc, [3, 70000, 9], [3, 140001, 9], [0.0, 7.0e4, 0.0]), 4096, 32, 60, 64.0, in_order=1)
     with pytest.raises(rk.RkError) as e:
         placer.place(jobs(orc, [1], [1], [0.0]), 4, 8, 96, 1600.0, cap=31)
     assert e.value.code == rk.RK_ERR_CAPACITY
