@@ -562,6 +562,8 @@ def test_edge_cases(gpu, orc):
     with pytest.raises(rk.RkError) as e:
         rk.rk_enumerate_plans(run.ctx, run.jobs, run.bounds, tbl.c)
     assert e.value.code == rk.RK_ERR_CAPACITY and tbl.n_triples == run.table.n_triples
+    rk.rk_sync(run.ctx)            # the fill kernel is launched before the counts are known and must have held back
+    assert not tbl.triples.any().item() and not tbl.seg_g.any().item() and not tbl.seg_first.any().item()
     bad = rk.make_grid(workloads.Grid(np.array([4, 2], np.uint32), 0, np.array([1.0], np.float32), 0))
     with pytest.raises(rk.RkError) as e:
         rk.rk_eval_candidates(run.ctx, run.jobs, run.table.c, bad, run.env, 0, wl.n_jobs, thr, None)
