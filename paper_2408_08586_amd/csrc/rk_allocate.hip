@@ -10,7 +10,9 @@
 // then CPUs):
 //
 //  k_hull   Each job's steps, were capacity never short, form a fixed walk
-//           over the upper hull of its curve (one wavefront per job).  With
+//           over the upper hull of its curve (one wavefront per job; two or
+//           four jobs per wavefront when none has more than 32 or 16 amounts:
+//           k_hull_groups).  With
 //           each slope replaced by the running minimum of the walk, the
 //           sequential order is the descending order of these keys (then job,
 //           then position in the walk).
@@ -24,6 +26,8 @@
 //  k_tail   the plain step-by-step loop on the little capacity that is left:
 //           one workgroup per round, argmax over the cached steps, which each
 //           thread keeps in registers for the jobs it owns.
+//  When no job's CPU walk has a step, the CPU pass's k_hist, k_apply and k_tail
+//  return at once (a per-round flag raised by its k_hull).
 //
 // Memory (k_mem_wish / k_mem_finish): when the tiers every job would like fit
 // with margin, all are granted in parallel; otherwise one wavefront takes the
