@@ -31,6 +31,24 @@ MEASURED_TRAFFIC = {
 }
 
 
+# Vector-ALU instructions per launch of the fused kernel on the stress workload (rocprofv3 --pmc SQ_INSTS_VALU,
+# profiles/valu_stress.txt: wavefront instructions, 64 lanes each), keyed by the digest of its sources.
+FUSED_SOURCES = ("paper_2408_08586_amd/csrc/rk_fused.hip", "paper_2408_08586_amd/csrc/rk_model.h")
+MEASURED_FUSED_VALU = {"0397e418cecff7de": 43661490}
+# 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz: vector instructions per lane and second (an FMA is one of them,
+# so this is half of the 78.6 TFLOP/s of unpacked FP32 and a quarter of the 157.3 TFLOP/s with packed FP32)
+VALU_PEAK_LANE_INSTR = 256 * 4 * 16 * 2.4e9
+
+
+def source_digest(sources):
+    import hashlib
+    h = hashlib.sha256()
+    for rel in sources:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def kernel_digest():
     import hashlib
     h = hashlib.sha256()
@@ -491,6 +509,25 @@ def main():
         "round_latency_ms": {"entry": "rk_schedule_round (fused evaluation, host-synchronous)",
                              "min": float(lat.min()), "median": float(np.median(lat)), "max": float(lat.max())},
     }
+    # the fused kernel (evaluation + best plan + curves without the candidate tensor): bound by the vector ALUs
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(max(5, args.steps) + 2)]
+    for a, b in ev:
+        a.record()
+        rk.rk_job_curves(ctx, jobs, table.c, grid, env, 0, J, best_thr, best_plan, curve_thr, curve_plan, curve_g)
+        b.record()
+    torch.cuda.synchronize()
+    fused_ms = float(np.median([a.elapsed_time(b) for a, b in ev[2:]]))
+    n_cpu = len(wl.grid.cpu_levels)
+    unique = table.n_triples * 8 * (1 + n_cpu)      # plans without offload once, offload plans once per CPU level
+    fd = source_digest(FUSED_SOURCES)
+    valu = MEASURED_FUSED_VALU.get(fd) if args.workload == "stress" else None
+    out["fused"] = {"entry": "rk_job_curves (k_fused)", "ms": fused_ms,
+                    "nominal_candidates_per_s": n_cand / (fused_ms * 1e-3),
+                    "unique_evaluations": unique, "unique_evaluations_per_s": unique / (fused_ms * 1e-3),
+                    "roofline": {"bound": "alu", "unit": "lane-instructions/s", "peak": VALU_PEAK_LANE_INSTR,
+                                 "achieved": None if valu is None else valu * 64 / (fused_ms * 1e-3),
+                                 "frac": None if valu is None else valu * 64 / (fused_ms * 1e-3) / VALU_PEAK_LANE_INSTR,
+                                 "valu_wave_instructions_per_launch": valu, "kernel_source_digest": fd}}
     if not args.no_place:
         rk.rk_schedule_round(ctx, jobs, bounds, grid, env, cluster, assign, total)
         out["placement"] = placement(rk, ctx, dev, wl, assign, max(5, args.steps))
