@@ -19,7 +19,7 @@ struct FusedLds {          // element counts of the dynamic LDS regions
 };
 
 __host__ __device__ inline size_t fused_lds_bytes(const FusedLds &L) {
-    return (size_t)L.max_ns * 8 + (size_t)L.rows_per_pass * L.max_ns * 8 + (size_t)L.max_nt * 4 * 8;
+    return (size_t)L.max_ns * 8 + (size_t)L.rows_per_pass * L.max_ns * 8 + (size_t)L.max_nt * 4 * 8 + (size_t)L.max_ns * 4;
 }
 
 __global__ __launch_bounds__(FUSED_THREADS) void k_fused(JobDev jobs, TableDev tb, GridDev grid, rk_env env,
@@ -39,6 +39,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_fused(JobDev jobs, TableDev t
     float *t_invk = t_host + L.max_nt;
     uint32_t *t_info = reinterpret_cast<uint32_t *>(t_invk + L.max_nt);      // ok bits | segment << 4
     uint32_t *t_g = t_info + L.max_nt;
+    uint32_t *l_segg = t_g + L.max_nt;                                       // [max_ns] GPUs of the job's segments
 
     const uint32_t tid = threadIdx.x;
     const uint32_t j = jb + blockIdx.x;
@@ -48,18 +49,20 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_fused(JobDev jobs, TableDev t
     const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]);
     const Job J = load_job(jobs, j);
 
-    for (uint32_t s = tid; s < ns; s += FUSED_THREADS) seg_plain[s] = 0ull;
+    // per segment: nothing found yet, its GPU count, and its number in the info word of each of its triples
+    for (uint32_t s = tid; s < ns; s += FUSED_THREADS) {
+        seg_plain[s] = 0ull;
+        l_segg[s] = tb.seg_g[s0 + s];
+        const uint32_t first = tb.seg_first[s0 + s];
+        const uint32_t last = s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt;
+        for (uint32_t t = first; t < last; ++t) t_info[t] = s << 4;
+    }
     __syncthreads();
 
     // phase 1: one thread per triple
     for (uint32_t tl = tid; tl < nt; tl += FUSED_THREADS) {
         const Triple T = triple_terms(J, env, tb.triples[t0 + tl]);
-        // segment of the triple: last s with seg_first[s] <= tl
-        uint32_t lo = 0, hi = ns;
-        while (hi - lo > 1) {
-            const uint32_t mid = (lo + hi) >> 1;
-            if (tb.seg_first[s0 + mid] <= tl) lo = mid; else hi = mid;
-        }
+        const uint32_t lo = t_info[tl] >> 4;               // segment of the triple
         unsigned long long k = 0;
 #pragma unroll
         for (uint32_t z = 0; z < 4; ++z)
@@ -127,31 +130,51 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_fused(JobDev jobs, TableDev t
         }
         __syncthreads();
 
-        // phase 3: merge with the plans without offload, write, then the running maximum
-        for (uint32_t i = tid; i < pass_rows * ns; i += FUSED_THREADS) {
-            const uint32_t rl = i / ns, s = i % ns;
-            unsigned long long k = seg_best[(size_t)rl * L.max_ns + s];
-            const unsigned long long kp = seg_plain[s];
-            k = kp > k ? kp : k;
-            seg_best[(size_t)rl * L.max_ns + s] = k;
-            if (best_thr) {
+        // phase 3: merge with the plans without offload, write, then the running maximum along each row.  The
+        // wavefronts split the pass's rows; a wavefront walks its rows 64 entries at a time: the running maximum is
+        // a segmented scan over packed keys (throughput bits, inverted segment index, GPUs of the segment: the lower
+        // segment wins among equal throughputs), a row that continues from the previous 64 entries takes their last
+        // key along, and the plan comes from the winning segment's merged key.
+        {
+            constexpr uint32_t WAVES = FUSED_THREADS / 64;
+            const uint32_t lane = tid & 63u, wave = tid >> 6;
+            const uint32_t per = (pass_rows + WAVES - 1) / WAVES;
+            const uint32_t r_lo = wave * per < pass_rows ? wave * per : pass_rows;
+            const uint32_t r_hi = r_lo + per < pass_rows ? r_lo + per : pass_rows;
+            const uint32_t n = (r_hi - r_lo) * ns;
+            unsigned long long carry = 0;
+            for (uint32_t base = 0; base < n; base += 64) {
+                const uint32_t i = base + lane;
+                const bool in = i < n;
+                const uint32_t rl = r_lo + i / ns, s = i % ns;
                 const uint64_t out = sbase + (uint64_t)(c_lo * n_mem + rl) * ns + s;
-                best_thr[out] = key_thr(k);
-                best_plan[out] = key_plan(k);
-            }
-        }
-        __syncthreads();
-        for (uint32_t rl = tid; rl < pass_rows; rl += FUSED_THREADS) {
-            const uint64_t out = sbase + (uint64_t)(c_lo * n_mem + rl) * ns;
-            float cur = 0.f;
-            uint32_t plan = RK_NO_PLAN, g = 0;
-            for (uint32_t s = 0; s < ns; ++s) {
-                const unsigned long long k = seg_best[(size_t)rl * L.max_ns + s];
-                const float v = key_thr(k);
-                if (v > cur) { cur = v; plan = key_plan(k); g = tb.seg_g[s0 + s]; }
-                curve_thr[out + s] = cur;
-                curve_plan[out + s] = plan;
-                curve_g[out + s] = g;
+                unsigned long long ck = 0;
+                if (in) {
+                    unsigned long long k = seg_best[(size_t)rl * L.max_ns + s];
+                    const unsigned long long kp = seg_plain[s];
+                    k = kp > k ? kp : k;
+                    seg_best[(size_t)rl * L.max_ns + s] = k;
+                    if (best_thr) {
+                        best_thr[out] = key_thr(k);
+                        best_plan[out] = key_plan(k);
+                    }
+                    if (k >> 32) ck = (k & 0xFFFFFFFF00000000ull) | ((0xFFFFu - s) << 16) | l_segg[s];
+                }
+#pragma unroll
+                for (uint32_t d = 1; d < 64; d <<= 1) {
+                    const unsigned long long o = __shfl_up(ck, d, 64);
+                    if (lane >= d && s >= d) ck = o > ck ? o : ck;      // the lane d below is in the same row
+                }
+                if (s > lane) ck = carry > ck ? carry : ck;             // the row began before these 64 entries
+                carry = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(ck >> 32), 63) << 32) |
+                        (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)ck, 63);
+                if (in) {
+                    uint32_t plan = RK_NO_PLAN;
+                    if (ck) plan = key_plan(seg_best[(size_t)rl * L.max_ns + (0xFFFFu - ((uint32_t)(ck >> 16) & 0xFFFFu))]);
+                    curve_thr[out] = __uint_as_float((uint32_t)(ck >> 32));
+                    curve_plan[out] = plan;
+                    curve_g[out] = (uint32_t)ck & 0xFFFFu;
+                }
             }
         }
         __syncthreads();
