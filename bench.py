@@ -34,7 +34,7 @@ MEASURED_TRAFFIC = {
 # Vector-ALU instructions per launch of the fused kernel on the stress workload (rocprofv3 --pmc SQ_INSTS_VALU,
 # profiles/valu_stress.txt: wavefront instructions, 64 lanes each), keyed by the digest of its sources.
 FUSED_SOURCES = ("paper_2408_08586_amd/csrc/rk_fused.hip", "paper_2408_08586_amd/csrc/rk_model.h")
-MEASURED_FUSED_VALU = {"0397e418cecff7de": 43661490}
+MEASURED_FUSED_VALU = {"912085237e801deb": 47817614}
 # 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz: vector instructions per lane and second (an FMA is one of them,
 # so this is half of the 78.6 TFLOP/s of unpacked FP32 and a quarter of the 157.3 TFLOP/s with packed FP32)
 VALU_PEAK_LANE_INSTR = 256 * 4 * 16 * 2.4e9
