@@ -93,7 +93,15 @@ def cpu_baseline(wl, sample_jobs, threads):
     oracle.greedy(sub.coef[:, 16], tb, sub.grid, sub.cluster, bt, bp, ct)
     t4 = time.perf_counter()
     n = thr.size
+    # one thread, on a tenth of the sample, for the per-core figure
+    one = sub.subset(np.arange(max(1, sub.n_jobs // 10)))
+    tb1 = oracle.enumerate_plans(one.ints, one.bounds)
+    t5 = time.perf_counter()
+    thr1, _ = oracle.eval_jobs(one.coef, one.ints, one.bounds, tb1, one.grid, one.env, want_reason=False, n_threads=1)
+    t6 = time.perf_counter()
     return {"value": n / (t4 - t0), "unit": "candidates/s", "cores": threads, "kind": "oracle",
+            "round_ms": (t4 - t0) * 1e3,
+            "single_thread_eval_candidates_per_s": thr1.size / (t6 - t5),
             "sample": f"first {sub.n_jobs} jobs of the workload ({n} candidates), capacities scaled by {frac:g}; "
                       f"evaluation on {threads} threads, the other stages on 1",
             "seconds": {"enumerate": t1 - t0, "evaluate": t2 - t1, "best_plan+curves": t3 - t2, "greedy": t4 - t3},
