@@ -61,10 +61,13 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     uint32_t *__restrict__ triples, uint32_t *__restrict__ seg_g, uint32_t *__restrict__ seg_first,
     uint32_t *__restrict__ totals, uint64_t cap_triples, uint64_t cap_segs) {
     extern __shared__ uint32_t gmap[];                      // counting and search modes: bitmap of the GPU counts, word prefixes
-    __shared__ uint32_t lists[2 * MAX_DIV + 1];             // the two divisor lists; later the segments' sizes and starts
+    // Two arrays serve everything (a third would cost occupancy): `lists` holds the two divisor lists and later
+    // the keys gathered by segment; `keys` holds the keys as they are found, then (once every thread has its keys
+    // in registers) the segments' sizes and starts, and at the end the keys in order.
+    __shared__ uint32_t lists[2 * MAX_DIV];
     uint32_t *dlist = lists, *plist = lists + MAX_DIV;
-    __shared__ __align__(16) uint32_t keys[MAX_T], sorted[MAX_T];
-    static_assert(2 * MAX_DIV >= MAX_T, "the segment table reuses the divisor lists");
+    __shared__ __align__(16) uint32_t keys[MAX_T + 4];
+    static_assert(2 * MAX_DIV >= MAX_T, "the gathered keys reuse the divisor lists");
     __shared__ uint32_t scan_tmp[ENUM_THREADS];
     __shared__ uint32_t nd, np, nk;
 
@@ -78,7 +81,7 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
         if (totals[TOT_ERR] != 0u || nt > 0xFFFFFFFFull || nt > cap_triples || ns > cap_segs) return;
         cnt = cnt_t[j];
         const size_t at = (size_t)j * park_stride;
-        for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) sorted[i] = park[at + i];
+        for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) keys[i] = park[at + i];
         __syncthreads();
     } else {
         const uint32_t l = layers[j], b = gbatch[j], mu = mbatch[j];
@@ -138,17 +141,19 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
         // (6) a key's final place = start of its segment + number of smaller keys inside it.
         constexpr uint32_t PER = MAX_T / ENUM_THREADS;          // keys per thread, at most
         const uint32_t n_words = (bounds.g_max >> 5) + 1u;
-        uint32_t *bitmap = gmap, *before = gmap + n_words, *seg = lists;
-        for (uint32_t w = tid; w < n_words; w += ENUM_THREADS) bitmap[w] = 0u;
-        for (uint32_t i = tid; i <= cnt; i += ENUM_THREADS) seg[i] = 0u;     // there are at most cnt segments
-        __syncthreads();
-        uint32_t mine[PER], slot[PER];
+        uint32_t *bitmap = gmap, *before = gmap + n_words, *seg = keys, *gathered = lists;
+        uint32_t mine[PER], slot[PER], place[PER];
 #pragma unroll
         for (uint32_t r = 0; r < PER; ++r) {
             const uint32_t i = tid + r * ENUM_THREADS;
             mine[r] = i < cnt ? keys[i] : 0u;
-            if (i < cnt) atomicOr(&bitmap[mine[r] >> 21], 1u << ((mine[r] >> 16) & 31u));
         }
+        for (uint32_t w = tid; w < n_words; w += ENUM_THREADS) bitmap[w] = 0u;
+        __syncthreads();                                        // every key is in a register: `keys` becomes the segment table
+        for (uint32_t i = tid; i <= cnt; i += ENUM_THREADS) seg[i] = 0u;     // there are at most cnt segments
+#pragma unroll
+        for (uint32_t r = 0; r < PER; ++r)
+            if (tid + r * ENUM_THREADS < cnt) atomicOr(&bitmap[mine[r] >> 21], 1u << ((mine[r] >> 16) & 31u));
         __syncthreads();
         const uint32_t wpt = (n_words + ENUM_THREADS - 1) / ENUM_THREADS;
         const uint32_t w_lo = tid * wpt < n_words ? tid * wpt : n_words;
@@ -178,20 +183,25 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
         __syncthreads();
 #pragma unroll
         for (uint32_t r = 0; r < PER; ++r)
-            if (tid + r * ENUM_THREADS < cnt) sorted[seg[segment_of(mine[r])] + slot[r]] = mine[r];
+            if (tid + r * ENUM_THREADS < cnt) gathered[seg[segment_of(mine[r])] + slot[r]] = mine[r];
         __syncthreads();
 #pragma unroll
         for (uint32_t r = 0; r < PER; ++r) {
+            place[r] = 0;
             if (tid + r * ENUM_THREADS < cnt) {
                 const uint32_t q = segment_of(mine[r]), a = seg[q], b = seg[q + 1];
                 uint32_t rank = a;
-                for (uint32_t x = a; x < b; ++x) rank += sorted[x] < mine[r] ? 1u : 0u;
-                keys[rank] = mine[r];                           // every thread holds its keys in registers by now
+                for (uint32_t x = a; x < b; ++x) rank += gathered[x] < mine[r] ? 1u : 0u;
+                place[r] = rank;
             }
         }
+        __syncthreads();                                        // the segment table has been read: `keys` takes the result
+#pragma unroll
+        for (uint32_t r = 0; r < PER; ++r)
+            if (tid + r * ENUM_THREADS < cnt) keys[place[r]] = mine[r];
         __syncthreads();
     }
-    const uint32_t *fin = MODE == MODE_FILL_PARKED ? sorted : keys;      // the keys in order
+    const uint32_t *fin = keys;                                 // the keys in order
 
     // segments: runs of equal g.  Each thread owns a contiguous chunk.
     const uint32_t chunk = (cnt + ENUM_THREADS - 1) / ENUM_THREADS;
