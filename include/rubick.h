@@ -464,7 +464,8 @@ typedef struct {
  * floor(c*(done+k)/g) - floor(c*done/g) CPUs (done = its GPUs on earlier nodes,
  * so the parts add up to c) and mem*k/g GiB (float32).  A job whose g GPUs
  * are not found takes nothing.
- *   assign     [device] n_jobs records (as rk_allocate writes them); g == 0: no parts
+ *   assign     [device] n_jobs records (as rk_allocate writes them); g == 0: no parts;
+ *              mem_gb must not be negative (a NaN or negative amount gives an unspecified placement)
  *   place_off  [device] n_jobs + 1 offsets into entries (CSR over jobs)
  *   entries    [device] cap_entries records; cap_entries >= n_nodes * gpus_per_node
  *   status     [device] n_jobs words: 0 nothing to place, 1 placed, 2 not placed
