@@ -221,9 +221,24 @@ def test_stress_config_sampled_jobs(gpu, orc):
     for jb, je in zip(edges[:-1], edges[1:]):
         thr, feas, n = run.eval(int(jb), int(je))
         bt, bp, ns = run.best(thr, int(jb), int(je))
+        ct, cp, cg = run.curves(bt, bp, int(jb), int(je))
         g_thr, g_feas = run.host(thr, n), run.host(feas, n)
         g_bt, g_bp = run.host(bt, ns), run.host(bp, ns).view(np.uint32)
+        g_ct, g_cp, g_cg = run.host(ct, ns), run.host(cp, ns).view(np.uint32), run.host(cg, ns).view(np.uint32)
         for j in np.sort(rng.choice(np.arange(jb, je), 12, replace=False)).tolist():
+            # curves at full size, by their definition on the library's own best values: running maximum along every
+            # row, plan and GPU count of the first segment that reaches it
+            nsj = int(tn["seg_off"][j + 1] - tn["seg_off"][j])
+            s_at = run.n_rows * int(tn["seg_off"][j] - tn["seg_off"][jb])
+            seg_g = tn["seg_g"][tn["seg_off"][j]:tn["seg_off"][j + 1]]
+            for r in range(run.n_rows):
+                row = slice(s_at + r * nsj, s_at + (r + 1) * nsj)
+                v = g_bt[row]
+                top = np.maximum.accumulate(v)
+                first = np.array([int(np.argmax(v[:k + 1] == top[k])) for k in range(nsj)])
+                assert np.array_equal(g_ct[row], top)
+                assert np.array_equal(g_cp[row], np.where(top > 0, g_bp[row][first], 0xFFFFFFFF))
+                assert np.array_equal(g_cg[row], np.where(top > 0, seg_g[first], 0))
             sub = wl.subset([j])
             ot = orc.enumerate_plans(sub.ints, sub.bounds)
             o_thr, o_reason = orc.eval_jobs(sub.coef, sub.ints, sub.bounds, ot, sub.grid, sub.env)
