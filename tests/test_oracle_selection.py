@@ -217,6 +217,36 @@ def test_greedy_optimal_on_concave_curves(orc):
         assert assign["g"].sum() <= G
 
 
+def test_greedy_is_where_unit_transfers_stop(orc):
+    # Sec. 5.2, Algorithm 1's shrinking rule written out as a loop: the job with the lowest
+    # slope gives one GPU to a job whose slope is higher, until no such pair is left.  On
+    # concave curves with distinct gains that state is unique, whatever the starting point,
+    # and it is the allocation the slope-ordered greedy computes in one go.
+    rng = np.random.default_rng(23)
+    for trial in range(20):
+        J, G = 5, 12
+        gains = np.sort(rng.uniform(0.1, 2.0, size=(J, G)).astype(np.float32), axis=1)[:, ::-1]
+        assert np.unique(gains).size == gains.size
+        pts = np.cumsum(gains.astype(np.float64), axis=1).astype(np.float32)
+        values = np.concatenate([np.zeros((J, 1), np.float32), pts], axis=1)
+        assign, total, _ = run_greedy_on(orc, pts.tolist(), G)
+        for start in range(3):
+            cuts = np.sort(rng.integers(0, G + 1, size=J - 1))
+            held = np.diff(np.concatenate([[0], cuts, [G]])).astype(int)      # a random full split
+            for _ in range(10 * G):
+                down = [values[j][held[j]] - values[j][held[j] - 1] if held[j] else np.inf for j in range(J)]
+                up = [values[j][held[j] + 1] - values[j][held[j]] if held[j] < G else -np.inf for j in range(J)]
+                shrink = int(np.argmin(down))
+                grow = int(np.argmax([up[j] if j != shrink else -np.inf for j in range(J)]))
+                if not up[grow] > down[shrink]:
+                    break
+                held[shrink] -= 1
+                held[grow] += 1
+            else:
+                raise AssertionError("the transfers did not stop")
+            assert held.tolist() == assign["g"].tolist(), (trial, start)
+
+
 def test_greedy_never_beats_optimum_and_respects_capacity(orc):
     rng = np.random.default_rng(11)
     for trial in range(20):
