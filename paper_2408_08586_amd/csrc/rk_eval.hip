@@ -180,8 +180,8 @@ __global__ __launch_bounds__(BEST_MAX_WAVES * 64) void k_best_plan(TableDev tb, 
 // GPUs of the segment), the running maximum along the row is a segmented scan
 // by shuffles (lower segment index wins among equal throughputs, as in the
 // step-by-step definition), and a row that continues from the previous 64
-// entries takes their last key along.  Only the plan of the winning segment is
-// fetched again.
+// entries takes their last key along.  The plan of an entry is loaded with its
+// throughput and moves through the scan with the key.
 constexpr int CURVE_THREADS = 256;
 
 __global__ __launch_bounds__(CURVE_THREADS) void k_curves(TableDev tb, uint32_t n_rows, uint32_t jb,
@@ -199,29 +199,40 @@ __global__ __launch_bounds__(CURVE_THREADS) void k_curves(TableDev tb, uint32_t 
     const uint32_t n = (r_hi - r_lo) * ns;                          // this wavefront's entries; they start a row
     const uint64_t off = (uint64_t)n_rows * (s0 - tb.seg_off[jb]) + (uint64_t)r_lo * ns;
     unsigned long long carry = 0;                                   // key at the end of the previous 64 entries
+    uint32_t carry_plan = RK_NO_PLAN;                               // and the plan that goes with it
     for (uint32_t base = 0; base < n; base += 64) {
         const uint32_t i = base + lane;
         const bool in = i < n;
         const uint32_t s = i % ns;                                  // place in its row
-        unsigned long long key = 0;                                 // 0 = nothing feasible so far
+        // the three loads do not depend on each other; the plan travels with the key through the scan
+        float v = 0.f;
+        uint32_t plan = RK_NO_PLAN, g = 0;
         if (in) {
-            const float v = best_thr[off + i];
-            if (v > 0.f)
-                key = ((unsigned long long)__float_as_uint(v) << 32) | ((0xFFFFu - s) << 16) | tb.seg_g[s0 + s];
+            v = best_thr[off + i];
+            plan = best_plan[off + i];
+            g = tb.seg_g[s0 + s];
         }
+        unsigned long long key = 0;                                 // 0 = nothing feasible so far
+        if (v > 0.f) key = ((unsigned long long)__float_as_uint(v) << 32) | ((0xFFFFu - s) << 16) | g;
 #pragma unroll
         for (uint32_t d = 1; d < 64; d <<= 1) {
             const unsigned long long o = __shfl_up(key, d, 64);
-            if (lane >= d && s >= d) key = o > key ? o : key;       // the lane d below is in the same row
+            const uint32_t op = __shfl_up(plan, d, 64);
+            if (lane >= d && s >= d && o > key) {                   // the lane d below is in the same row
+                key = o;
+                plan = op;
+            }
         }
-        if (s > lane) key = carry > key ? carry : key;              // the row began before these 64 entries
+        if (s > lane && carry > key) {                              // the row began before these 64 entries
+            key = carry;
+            plan = carry_plan;
+        }
         carry = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(key >> 32), 63) << 32) |
                 (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)key, 63);
+        carry_plan = (uint32_t)__builtin_amdgcn_readlane((int)plan, 63);
         if (in) {
-            uint32_t plan = RK_NO_PLAN;
-            if (key) plan = best_plan[off + (i - s) + (0xFFFFu - ((uint32_t)(key >> 16) & 0xFFFFu))];
             curve_thr[off + i] = __uint_as_float((uint32_t)(key >> 32));
-            curve_plan[off + i] = plan;
+            curve_plan[off + i] = key ? plan : RK_NO_PLAN;
             curve_g[off + i] = (uint32_t)key & 0xFFFFu;
         }
     }

@@ -218,6 +218,7 @@ def test_stress_config_sampled_jobs(gpu, orc):
     n_chunks = 3
     edges = np.linspace(0, wl.n_jobs, n_chunks + 1).astype(int)
     worst, n_mis, n_seg = 0.0, 0, 0
+    parts = []
     for jb, je in zip(edges[:-1], edges[1:]):
         thr, feas, n = run.eval(int(jb), int(je))
         bt, bp, ns = run.best(thr, int(jb), int(je))
@@ -225,6 +226,7 @@ def test_stress_config_sampled_jobs(gpu, orc):
         g_thr, g_feas = run.host(thr, n), run.host(feas, n)
         g_bt, g_bp = run.host(bt, ns), run.host(bp, ns).view(np.uint32)
         g_ct, g_cp, g_cg = run.host(ct, ns), run.host(cp, ns).view(np.uint32), run.host(cg, ns).view(np.uint32)
+        parts.append((g_bt, g_bp, g_ct, g_cp, g_cg))
         for j in np.sort(rng.choice(np.arange(jb, je), 12, replace=False)).tolist():
             # curves at full size, by their definition on the library's own best values: running maximum along every
             # row, plan and GPU count of the first segment that reaches it
@@ -251,6 +253,11 @@ def test_stress_config_sampled_jobs(gpu, orc):
             n_seg += o_bt.size
     print(f"stress: max rel err {worst:.2e}; {n_mis}/{n_seg} sampled best plans differ inside the band")
     assert n_mis <= 0.01 * n_seg
+    # the benchmark takes the curves of all jobs in one call after the last chunk: same values as chunk by chunk
+    whole = [np.concatenate([p[k] for p in parts]) for k in range(5)]
+    ct, cp, cg = run.curves(run.dev_f32(whole[0]), run.dev_u32(whole[1]))
+    for got, want in zip((ct, cp, cg), whole[2:]):
+        assert np.array_equal(run.host(got, want.size).view(want.dtype), want)
     run.close()
 
 
