@@ -292,22 +292,23 @@ int ork_enumerate(uint32_t n_jobs, const uint32_t *ints, const ork_bounds *bound
                     if (g % (t * p) != 0) continue;
                     const uint32_t d = g / (t * p);
                     for (uint32_t v = 0; v < 4; ++v) {
-                    if (!((bounds->mu_mask >> v) & 1u)) continue;
-                    if (mu == 0 || b % ((uint64_t)d * (mu << v)) != 0) continue;
-                    if (!any) {
-                        any = true;
-                        if (write) {
-                            if (ns < cap_segs) { seg_g[ns] = g; seg_first[ns] = (uint32_t)(nt - job_first); }
-                            else overflow = true;
+                        if (!((bounds->mu_mask >> v) & 1u)) continue;
+                        // n = b/(d*mu*2^v) micro-batches per replica: a whole number, at least one
+                        if (mu == 0 || b == 0 || b % ((uint64_t)d * (mu << v)) != 0) continue;
+                        if (!any) {
+                            any = true;
+                            if (write) {
+                                if (ns < cap_segs) { seg_g[ns] = g; seg_first[ns] = (uint32_t)(nt - job_first); }
+                                else overflow = true;
+                            }
+                            ++ns;
                         }
-                        ++ns;
-                    }
-                    if (write) {
-                        if (nt < cap_triples) {
-                            triples[nt * 4 + 0] = d; triples[nt * 4 + 1] = t; triples[nt * 4 + 2] = p; triples[nt * 4 + 3] = v;
-                        } else overflow = true;
-                    }
-                    ++nt;
+                        if (write) {
+                            if (nt < cap_triples) {
+                                triples[nt * 4 + 0] = d; triples[nt * 4 + 1] = t; triples[nt * 4 + 2] = p; triples[nt * 4 + 3] = v;
+                            } else overflow = true;
+                        }
+                        ++nt;
                     }
                 }
             }

@@ -47,6 +47,17 @@ def test_enumeration_matches_brute_force(orc, g_max, tp_max, pp_max, mu_mask):
         assert firsts == [gs.index(g) for g in seg_g]
 
 
+def test_enumeration_jobs_without_plans(orc):
+    # Sec. 3: a plan splits the global batch b into n = b/(d*mu) >= 1 micro-batches per replica and the l layers
+    # into p stages; no layers, an empty batch, no micro-batch size, or a micro-batch that does not divide the
+    # batch leave nothing to enumerate, whatever the neighbours are
+    ints = np.array([[12, 32, 1], [0, 8, 1], [8, 0, 1], [8, 8, 0], [5, 7, 2], [12, 32, 1]], np.uint32)
+    tb = orc.enumerate_plans(ints, workloads.Bounds(g_max=16, mu_mask=0xF))
+    n = np.diff(tb.triple_off).tolist()
+    assert n[1:5] == [0, 0, 0, 0] and n[0] == n[5] > 0
+    assert np.diff(tb.seg_off).tolist()[1:5] == [0, 0, 0, 0]
+
+
 def test_enumeration_counts_ordered_factorisations(orc):
     # with the constraints lifted (layers and batch divisible by everything)
     # the triples of g are its ordered factorisations into three factors:
