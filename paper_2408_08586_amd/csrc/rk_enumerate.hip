@@ -11,7 +11,10 @@
 // compared with each other.  The counting pass also parks the
 // sorted keys in a scratch buffer; after the exclusive scan of the counts the
 // fill pass only decodes them into place (it repeats the search only when the
-// scratch buffer was too small).  The fill pass is launched while the counts
+// scratch buffer was too small).  Jobs whose searches would be identical (same
+// layer count, same number of micro-batches per step) share one: a hash table
+// names a leader for each such group, only leaders search, the others take
+// the leader's counts and decode the leader's parked keys.  The fill pass is launched while the counts
 // are still on their way to the host: it checks on the device that the table
 // is large enough and leaves it alone otherwise.
 #include <cstring>
@@ -51,10 +54,88 @@ __device__ uint32_t block_excl_scan(uint32_t v, uint32_t *lds, uint32_t *total) 
     return before + incl - v;
 }
 
+// What the search of a job depends on (besides the bounds of the call): its layer count and b/mu; (0, 0) for a
+// job that has no plan at all.
+__device__ __forceinline__ void search_key(uint32_t l, uint32_t b, uint32_t mu, uint32_t &kl, uint32_t &kn) {
+    const bool any = l > 0 && b > 0 && mu > 0 && (b % mu) == 0;
+    kl = any ? l : 0u;
+    kn = any ? b / mu : 0u;
+}
+
+__device__ __forceinline__ uint32_t search_hash(uint32_t kl, uint32_t kn) {
+    uint32_t h = (kl * 0x9E3779B1u) ^ (kn * 0x85EBCA77u);
+    h ^= h >> 15;
+    h *= 0x2C1B3C6Du;
+    h ^= h >> 12;
+    return h;
+}
+
+// leader[j] = the job whose search job j shares (itself for the leaders).  Open addressing with linear probing,
+// an entry is a job index + 1 and never changes once set; the table has at least twice as many slots as there are
+// jobs, so every probe sequence ends at an empty slot or at the job's own kind, and nobody waits for anybody.
+// Equal jobs of a workgroup first elect one of them through a table in LDS; only that one goes to the global table.
+constexpr int LEAD_THREADS = 256;
+constexpr uint32_t SHARE_MIN_JOBS = 2048;                  // calls with fewer jobs do not look for equal ones
+
+__global__ __launch_bounds__(LEAD_THREADS) void k_enum_leaders(const uint32_t *__restrict__ layers,
+                                                               const uint32_t *__restrict__ gbatch,
+                                                               const uint32_t *__restrict__ mbatch, uint32_t n_jobs,
+                                                               uint32_t *__restrict__ tab, uint32_t tab_mask,
+                                                               uint32_t *__restrict__ leader) {
+    __shared__ uint32_t ltab[2 * LEAD_THREADS], s_kl[LEAD_THREADS], s_kn[LEAD_THREADS], s_lead[LEAD_THREADS];
+    const uint32_t tid = threadIdx.x, j = blockIdx.x * LEAD_THREADS + tid;
+    const bool valid = j < n_jobs;
+    uint32_t kl = 0, kn = 0;
+    if (valid) search_key(layers[j], gbatch[j], mbatch[j], kl, kn);
+    s_kl[tid] = kl;
+    s_kn[tid] = kn;
+    ltab[tid] = 0u;
+    ltab[tid + LEAD_THREADS] = 0u;
+    __syncthreads();
+    const uint32_t h = search_hash(kl, kn);
+    uint32_t rep = tid;                                     // the thread that speaks for this job's kind
+    if (valid) {
+        uint32_t slot = h & (2u * LEAD_THREADS - 1u);
+        for (;;) {
+            const uint32_t old = atomicCAS(&ltab[slot], 0u, tid + 1u);
+            if (old == 0u) break;
+            if (s_kl[old - 1u] == kl && s_kn[old - 1u] == kn) { rep = old - 1u; break; }
+            slot = (slot + 1u) & (2u * LEAD_THREADS - 1u);
+        }
+    }
+    if (valid && rep == tid) {
+        uint32_t slot = h & tab_mask, lead = j;
+        for (;;) {
+            const uint32_t old = atomicCAS(&tab[slot], 0u, j + 1u);
+            if (old == 0u) break;
+            const uint32_t o = old - 1u;
+            uint32_t ol, on;
+            search_key(layers[o], gbatch[o], mbatch[o], ol, on);
+            if (ol == kl && on == kn) { lead = o; break; }
+            slot = (slot + 1u) & tab_mask;
+        }
+        s_lead[tid] = lead;
+    }
+    __syncthreads();
+    if (valid) leader[j] = s_lead[rep];
+}
+
+// the counts of a job that did not search are its leader's
+__global__ __launch_bounds__(LEAD_THREADS) void k_spread_counts(const uint32_t *__restrict__ leader, uint32_t n_jobs,
+                                                                uint32_t *__restrict__ cnt_t, uint32_t *__restrict__ cnt_s) {
+    const uint32_t j = blockIdx.x * LEAD_THREADS + threadIdx.x;
+    if (j >= n_jobs) return;
+    const uint32_t l = leader[j];
+    if (l != j) {
+        cnt_t[j] = cnt_t[l];
+        cnt_s[j] = cnt_s[l];
+    }
+}
+
 template <int MODE>
 __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     const uint32_t *__restrict__ layers, const uint32_t *__restrict__ gbatch,
-    const uint32_t *__restrict__ mbatch, rk_plan_bounds bounds,
+    const uint32_t *__restrict__ mbatch, rk_plan_bounds bounds, const uint32_t *__restrict__ leader,
     uint32_t *__restrict__ cnt_t, uint32_t *__restrict__ cnt_s,
     uint32_t *__restrict__ park, uint32_t park_stride,
     const uint32_t *__restrict__ triple_off, const uint32_t *__restrict__ seg_off,
@@ -67,11 +148,13 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
     __shared__ uint32_t lists[2 * MAX_DIV];
     uint32_t *dlist = lists, *plist = lists + MAX_DIV;
     __shared__ __align__(16) uint32_t keys[MAX_T + 4];
+    static_assert(TOT_WORDS <= 16, "the totals share a block with the leaders' table");
     static_assert(2 * MAX_DIV >= MAX_T, "the gathered keys reuse the divisor lists");
     __shared__ uint32_t scan_tmp[ENUM_THREADS];
     __shared__ uint32_t nd, np, nk;
 
     const uint32_t j = blockIdx.x, tid = threadIdx.x;
+    if (MODE == MODE_COUNT && leader && leader[j] != j) return;   // (whole workgroup) the leader searches for this job
     uint32_t cnt, err = 0;
     if (MODE == MODE_FILL_PARKED) {
         // launched before the host has seen the totals: nothing is written unless the
@@ -80,7 +163,7 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
         const uint64_t ns = ((uint64_t)totals[TOT_NS_HI] << 32) | totals[TOT_NS_LO];
         if (totals[TOT_ERR] != 0u || nt > 0xFFFFFFFFull || nt > cap_triples || ns > cap_segs) return;
         cnt = cnt_t[j];
-        const size_t at = (size_t)j * park_stride;
+        const size_t at = (size_t)(leader ? leader[j] : j) * park_stride;   // the keys were parked by the job that searched
         for (uint32_t i = tid; i < cnt; i += ENUM_THREADS) keys[i] = park[at + i];
         __syncthreads();
     } else {
@@ -386,7 +469,16 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
     int32_t rc;
     if ((rc = rk_scratch(ctx, SL_CNT_T, (size_t)(2 * (size_t)J + 2) * 4, (void **)&cnt_t))) return rc;
     if ((rc = rk_scratch(ctx, SL_CNT_S, (size_t)(2 * (size_t)J + 2) * 4, (void **)&cnt_s))) return rc;
-    if ((rc = rk_scratch(ctx, SL_TOTALS, TOT_WORDS * 4, (void **)&totals))) return rc;
+    // totals (16 words) and the leaders' hash table (a power of two, at least twice the jobs) are cleared together
+    uint64_t tab_slots = 64;
+    while (tab_slots < 2 * (uint64_t)J) tab_slots <<= 1;
+    // (a call with few jobs searches for each of them: two more launches would cost more than they save)
+    const bool share = J >= SHARE_MIN_JOBS;
+    if (!share) tab_slots = 0;
+    uint32_t *tab, *leader = nullptr;
+    if ((rc = rk_scratch(ctx, SL_TOTALS, (size_t)(16 + tab_slots) * 4, (void **)&totals))) return rc;
+    tab = totals + 16;
+    if (share && (rc = rk_scratch(ctx, SL_ENUM_LEADER, ((size_t)J + 1) * 4, (void **)&leader))) return rc;
     // one slot per job for the parked keys: as wide as the widest job seen so far, or a first guess
     if (ctx->park_stride == 0) ctx->park_stride = 512;
     const uint32_t park_stride = ctx->park_stride;
@@ -409,12 +501,22 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
     if (!ctx->counts_ev) RK_HIP(ctx, hipEventCreateWithFlags(&ctx->counts_ev, hipEventDisableTiming));
 
     const size_t gmap_bytes = (size_t)((bounds->g_max >> 5) + 1u) * 2 * sizeof(uint32_t);   // bitmap + word prefixes
-    k_zero_words<<<1, 64, 0, ctx->stream>>>(totals, TOT_WORDS);
+    k_zero_words<<<(uint32_t)((16 + tab_slots + 255) / 256), 256, 0, ctx->stream>>>(totals, (uint32_t)(16 + tab_slots));
     if (J > 0) {
+        const uint32_t job_blocks = (J + LEAD_THREADS - 1) / LEAD_THREADS;
+        if (share) {
+            k_enum_leaders<<<job_blocks, LEAD_THREADS, 0, ctx->stream>>>(jobs->layers, jobs->gbatch, jobs->mbatch, J, tab,
+                                                                        (uint32_t)(tab_slots - 1), leader);
+            RK_CHECK_LAUNCH(ctx, "k_enum_leaders");
+        }
         k_enumerate<MODE_COUNT><<<J, ENUM_THREADS, gmap_bytes, ctx->stream>>>(
-            jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
+            jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, leader, cnt_t, cnt_s, park, park_stride,
             nullptr, nullptr, nullptr, nullptr, nullptr, totals, 0, 0);
         RK_CHECK_LAUNCH(ctx, "k_enumerate<count>");
+        if (share) {
+            k_spread_counts<<<job_blocks, LEAD_THREADS, 0, ctx->stream>>>(leader, J, cnt_t, cnt_s);
+            RK_CHECK_LAUNCH(ctx, "k_spread_counts");
+        }
     }
     k_scan_counts<<<1, 1024, 0, ctx->stream>>>(cnt_t, cnt_s, J, off_t, off_s, totals, back);
     RK_CHECK_LAUNCH(ctx, "k_scan_counts");
@@ -425,7 +527,7 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
     // round trip: the kernel itself checks the flags and the table's capacity.
     if (fill && J > 0) {
         k_enumerate<MODE_FILL_PARKED><<<J, ENUM_THREADS, 0, ctx->stream>>>(
-            jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
+            jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, leader, cnt_t, cnt_s, park, park_stride,
             off_t, off_s, table->triples, table->seg_g, table->seg_first, totals, table->cap_triples, table->cap_segs);
         RK_CHECK_LAUNCH(ctx, "k_enumerate<fill>");
     }
@@ -457,7 +559,7 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
     }
     if (J > 0 && !parked) {                                   // the parked keys were incomplete: search again
         k_enumerate<MODE_FILL_SEARCH><<<J, ENUM_THREADS, gmap_bytes, ctx->stream>>>(
-            jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, cnt_t, cnt_s, park, park_stride,
+            jobs->layers, jobs->gbatch, jobs->mbatch, *bounds, leader, cnt_t, cnt_s, park, park_stride,
             off_t, off_s, table->triples, table->seg_g, table->seg_first, totals, 0, 0);
         RK_CHECK_LAUNCH(ctx, "k_enumerate<fill>");
     }

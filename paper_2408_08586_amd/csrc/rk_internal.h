@@ -42,7 +42,8 @@ enum {
     SL_SIM_STATE, SL_SIM_ASSIGN,                         // simulation: per-job state, the tick's assignment
     SL_JMAP,                                             // rounds that share jobs: slot -> job
     SL_ENUM_BACK,                                        // enumeration: totals and offsets in one piece for the host
-    SL_PLACE_RESULT                                      // placement: its four summary words
+    SL_PLACE_RESULT,                                     // placement: its four summary words
+    SL_ENUM_LEADER                                       // enumeration: the job whose search a job shares
 };
 
 int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);

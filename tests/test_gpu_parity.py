@@ -88,6 +88,29 @@ def test_enumerate_odd_jobs_and_bounds(gpu, orc):
         run.close()
 
 
+def test_enumerate_jobs_that_share_a_search(gpu, orc):
+    """Equal jobs are searched once (leader election through a hash table): all jobs equal,
+    all jobs different, a few kinds in random order, equal b/mu from different (b, mu),
+    and jobs without plans among them."""
+    rng = np.random.default_rng(17)
+    base = workloads.tiny()
+    b = workloads.Bounds(g_max=64, tp_max=8, pp_max=16, mu_mask=0b11)
+    same = np.tile(np.array([[24, 64, 2]], np.uint32), (5000, 1))
+    ls, bs = np.meshgrid(np.arange(1, 71), np.arange(1, 61))
+    different = np.stack([ls.ravel(), bs.ravel(), np.ones(ls.size, np.int64)], axis=1).astype(np.uint32)   # 4,200 kinds
+    kinds = np.array([[12, 32, 1], [12, 64, 2], [12, 128, 4], [24, 32, 1], [5, 7, 2], [0, 8, 1], [8, 0, 1], [8, 8, 0],
+                      [96, 96, 1], [40, 120, 3], [40, 80, 2], [6, 9, 2]], np.uint32)
+    mixed = kinds[rng.integers(0, len(kinds), size=3001)]
+    for ints in (same, different, mixed, mixed[:1], mixed[:257]):
+        coef = np.tile(base.coef[:1], (len(ints), 1))
+        wl = workloads.Workload("shared", coef, ints, b, base.grid, workloads.Env(), workloads.Cluster(8, 8, 64.0))
+        run = gpu(wl)
+        for _ in range(2):                   # the second call finds the context's buffers in place
+            run.enumerate()
+            oracle_table_equal(run.table_numpy(), orc.enumerate_plans(ints, b))
+        run.close()
+
+
 def test_enumerate_wide_jobs_and_limits(gpu, orc):
     """Jobs with far more triples than usual (the two-pass hand-over inside the
     enumeration has to widen its slots), and a job beyond the documented limit."""
