@@ -642,6 +642,48 @@ def test_option_masks_and_memory_modes(gpu, orc):
     run.close()
 
 
+def test_largest_allocation_grid(gpu, orc):
+    """64 CPU levels x 16 host-memory tiers (the most the grid takes, 1,024 rows per job) on GPUs so small that
+    offloaded plans, which need CPUs and host memory, are chosen: every stage against the oracle."""
+    import dataclasses
+    base = workloads.paper_scale()
+    b = workloads.Bounds(g_max=16, tp_max=8, pp_max=8)
+    grid = workloads.Grid(np.arange(1, 65, dtype=np.uint32), 1, (np.arange(16) * 12.5).astype(np.float32), 0)
+    env = dataclasses.replace(base.env, gpu_mem_cap=4e9)
+    used_levels, used_tiers = set(), set()
+    for cl in (workloads.Cluster(64, 700, 300.0), workloads.Cluster(64, 20000, 1e5), workloads.Cluster(64, 700, 40.0)):
+        wl = workloads.Workload("maxgrid", base.coef[:24], base.ints[:24], b, grid, env, cl)
+        r = orc.schedule_round(wl, n_threads=16)
+        run = gpu(wl)
+        assert run.n_rows == 1024
+        run.enumerate()
+        ot = r["table"]
+        oracle_table_equal(run.table_numpy(), ot)
+        thr, feas, n = run.eval()
+        check_thr(run.host(thr, n), run.host(feas, n), r["thr"], r["reason"])
+        o32 = r["thr"].astype(np.float32)
+        bt, bp, ns = run.best(run.dev_f32(o32))
+        e_bt, e_bp = orc.best_plan(ot, wl.grid, o32)
+        assert np.array_equal(run.host(bt, ns), e_bt) and np.array_equal(run.host(bp, ns).view(np.uint32), e_bp)
+        ct, cp, cg = run.curves(bt, bp)
+        e_ct, e_cp, e_cg = orc.curves(ot, wl.grid, e_bt, e_bp)
+        for got, want in ((ct, e_ct), (cp, e_cp), (cg, e_cg)):
+            assert np.array_equal(run.host(got, ns).view(want.dtype), want)
+        bt2, bp2, _ = run.best(thr)
+        fbt, fbp, fct, fcp, fcg, _ = run.fused()
+        for a, c in zip((fbt, fbp, fct, fcp, fcg), (bt2, bp2) + run.curves(bt2, bp2)):
+            assert np.array_equal(run.host(a, ns), run.host(c, ns))
+        assign, total = run.allocate(run.dev_f32(r["best_thr"]), run.dev_u32(r["best_plan"]), run.dev_f32(r["curve_thr"]))
+        assert np.array_equal(assign, r["assign"])
+        a2, t2 = run.schedule_round()
+        compare_rounds(a2, t2, r)
+        got = r["assign"][r["assign"]["g"] > 0]
+        used_levels |= set((got["c"] // got["g"]).tolist())
+        used_tiers |= set(got["mem_gb"].tolist())
+        run.close()
+    assert len(used_levels) >= 5 and max(used_levels) == 64 and len(used_tiers) >= 3    # the case is not a trivial one
+
+
 def test_micro_batch_sizes_as_a_plan_dimension(gpu, orc):
     """Bounds that allow micro-batches of mu, 2mu, 4mu and 8mu samples (Sec. 4.1
     "Gradient Accumulation"): table, candidates, best plans and the whole round

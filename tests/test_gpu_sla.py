@@ -231,6 +231,59 @@ def test_allocate_sla_is_exact_on_shared_inputs(gpu, orc, n_jobs, n_tenants):
     run.close()
 
 
+def test_service_levels_at_the_largest_grid_and_tenant_count(gpu, orc):
+    """64 CPU levels x 16 memory tiers and 256 tenants (the most the library takes): minimum demands and the
+    allocation from the floors on inputs drawn here, identical to the oracle's."""
+    import paper_2408_08586_amd as rk
+    rng = np.random.default_rng(64016)
+    n_jobs, n_cpu, n_mem, n_tenants = 600, 64, 16, 256
+    rows = n_cpu * n_mem
+    base_wl = workloads.stress(n_jobs=n_jobs)
+    grid = workloads.Grid(np.arange(1, 65, dtype=np.uint32), 1, (np.arange(16) * 12.5).astype(np.float32), 0)
+    wl = workloads.Workload("sla_maxgrid", base_wl.coef, base_wl.ints, workloads.Bounds(g_max=16), grid, base_wl.env,
+                            workloads.Cluster(600, 6000, 1.0e5))
+    ot = orc.enumerate_plans(wl.ints, wl.bounds)
+    bt, bp, ct = random_segment_values(orc, rng, ot, n_jobs, rows, wl.grid)
+    guaranteed, req_g, req_c, req_m, base = random_requests(rng, ot, n_jobs, n_cpu, n_mem, bt, rows)
+    tenant = rng.integers(0, n_tenants + 1, n_jobs).astype(np.uint32)
+    run = gpu(wl)
+    assert run.n_rows == rows
+    run.enumerate()
+    oracle_table_equal(run.table_numpy(), ot)
+    d_bt, d_bp, d_ct = run.dev_f32(bt), run.dev_u32(bp), run.dev_f32(ct)
+    sla = rk.Sla(guaranteed, tenant, [1] * n_tenants, [1] * n_tenants, req_g, req_c, req_m, base)
+    ms, mc, mm = run.i32(n_jobs), run.i32(n_jobs), run.i32(n_jobs)
+    rk.rk_min_res(run.ctx, run.table.c, run.grid, 0, n_jobs, d_bt, sla, ms, mc, mm)
+    rk.rk_sync(run.ctx)
+    min_seg, min_c, min_m = orc.min_res(ot, wl.grid, bt, guaranteed, req_g, req_c, req_m, base)
+    assert np.array_equal(run.host(ms, n_jobs), min_seg)
+    assert np.array_equal(rk.u32(mc)[:n_jobs], min_c) and np.array_equal(rk.u32(mm)[:n_jobs], min_m)
+    assert len(set(min_c[min_seg >= 0].tolist())) > 8 and len(set(min_m[min_seg >= 0].tolist())) > 4
+    ref = wl.coef[:, 16]
+    levels = set()
+    for (G, Cc, M), share in (((600, 6000, 1.0e5), 1.0), ((600, 6000, 1.0e5), 0.3), ((300, 100000, 2000.0), 2.0)):
+        cl = workloads.Cluster(G, Cc, M)
+        w = rng.uniform(0.5, 1.5, n_tenants)
+        w = w / w.sum() * share
+        quota_g, quota_c = np.ceil(w * G).astype(np.uint32), np.ceil(w * Cc).astype(np.uint32)
+        e_assign, e_total, _ = orc.policy(ref, ot, wl.grid, cl, bt, bp, ct, guaranteed, tenant, min_seg, min_c,
+                                          quota_g, quota_c)
+        assign = rk.new_assign(n_jobs, run.device)
+        total = run.f32(1)
+        rk.rk_allocate_sla(run.ctx, run.jobs.ref_thr, run.table.c, run.grid, rk.make_cluster(cl), 0, n_jobs, d_bt, d_bp,
+                           d_ct, rk.Sla(guaranteed, tenant, quota_g, quota_c), run.torch.from_numpy(min_seg).to(run.device),
+                           run.dev_u32(min_c), assign, total)
+        rk.rk_sync(run.ctx)
+        assign = rk.assign_to_numpy(assign)
+        assert np.array_equal(assign, e_assign), (G, Cc, M, share)
+        assert float(total[0].item()) == pytest.approx(e_total, rel=1e-6, abs=1e-12)
+        got = e_assign[e_assign["g"] > 0]
+        levels |= set((got["c"] // got["g"]).tolist())
+        assert ((guaranteed != 0) & (e_assign["g"] > 0)).sum() > 0
+    assert len(levels) > 8
+    run.close()
+
+
 def test_allocate_sla_on_a_job_range(gpu, orc):
     import paper_2408_08586_amd as rk
     wl = workloads.paper_scale()
