@@ -1037,11 +1037,18 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_tail(Ctx X, uint32_t max_jobs,
 // ------------------------------------------------------------------ small rounds: selection in one workgroup
 // For rounds of at most SMALL_ROUND_JOBS jobs the histograms, the threshold,
 // the application and the step-by-step tail of a pass run in one workgroup per
-// round, with the histograms in LDS: one launch instead of six.
+// round, with the histograms in LDS: one launch instead of six.  The workgroup
+// of the CPU pass also takes the memory step that ends the round.
 constexpr uint32_t SMALL_ROUND_JOBS = 2048;
 
+__device__ __forceinline__ void mem_wish_job(const Ctx &X, const JobState &st, uint32_t j, rk_assign *__restrict__ assign,
+                                             double &cost_d, double &val_d);
+__device__ void mem_close_round(const Ctx &X, const JobState &st, uint32_t rnd, double wish, double val,
+                                rk_assign *__restrict__ assign, float *__restrict__ totals);
+
 template <int PASS>
-__global__ __launch_bounds__(TAIL_THREADS) void k_select_small(Ctx X, uint32_t max_jobs, JobState st, HullBuf H) {
+__global__ __launch_bounds__(TAIL_THREADS) void k_select_small(Ctx X, uint32_t max_jobs, JobState st, HullBuf H,
+                                                              rk_assign *__restrict__ assign, float *__restrict__ totals) {
     extern __shared__ float lds_dyn[];                          // tail scratch: max_jobs * 12 bytes
     __shared__ uint32_t hg[BINS];                               // one histogram, used for level 0 and then level 1
     __shared__ unsigned long long hc[BINS];
@@ -1076,54 +1083,75 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_select_small(Ctx X, uint32_t m
     for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) apply_job<PASS>(X, st, H, J0 + jl, sel.thr24, sel.freeG, sel.freeC);
     __syncthreads();                                            // the state in st is read back by the whole workgroup
     tail_run<PASS, SMALL_ROUND_JOBS / TAIL_THREADS>(X, st, rnd, J0, J1, sel.freeG, sel.freeC, max_jobs, lds_dyn, red);
+    if (PASS == 0) return;
+    // memory: every thread writes the wishes of its jobs, the first wavefront closes the round
+    __syncthreads();                                            // the granted amounts are in st
+    double cost_d = 0.0, val_d = 0.0;
+    for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) mem_wish_job(X, st, J0 + jl, assign, cost_d, val_d);
+    cost_d = wave_sum_f64(cost_d);
+    val_d = wave_sum_f64(val_d);
+    double *sums = reinterpret_cast<double *>(hc);              // the histograms are no longer needed
+    if ((tid & 63u) == 0) { sums[tid >> 6] = cost_d; sums[TAIL_THREADS / 64 + (tid >> 6)] = val_d; }
+    __syncthreads();                                            // also: the wishes are stored before anything replaces them
+    if (tid < 64u) {
+        const bool has = tid < TAIL_THREADS / 64;
+        const double wish = wave_sum_f64(has ? sums[tid] : 0.0), val = wave_sum_f64(has ? sums[TAIL_THREADS / 64 + tid] : 0.0);
+        mem_close_round(X, st, rnd, wish, val, assign, totals);
+    }
 }
 
 // ------------------------------------------------------------------ memory
 // Wish of a job: the smallest tier that reaches its best throughput over all
-// tiers.  The wishes are written as the result; k_mem_finish keeps them when
-// all of them together stay 1 % below the round's host memory (then every job
-// finds its wish still free when its turn comes: the float32 running remainder
-// of the in-order rule drifts by far less), and redoes the round in job order
-// otherwise.
+// tiers.  The wishes are written as the result; they are kept when all of them
+// together stay 1 % below the round's host memory (then every job finds its
+// wish still free when its turn comes: the float32 running remainder of the
+// in-order rule drifts by far less), otherwise the round is redone in job order.
+// Large rounds: k_mem_wish (a thread per job) and k_mem_finish (a wavefront per
+// round); small rounds: the workgroup of the CPU pass's selection does both.
+
+// the wish of job j, written to its record; adds its cost and its normalised throughput to the two sums
+__device__ __forceinline__ void mem_wish_job(const Ctx &X, const JobState &st, uint32_t j, rk_assign *__restrict__ assign,
+                                             double &cost_d, double &val_d) {
+    const GridDev &grid = X.grid;
+    const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem;
+    const uint32_t jrel = j - X.jb;
+    rk_assign out = {0u, 0u, 0.f, RK_NO_PLAN, 0.f};
+    const int32_t gi = st.gi[jrel];
+    if (gi >= 0) {
+        const uint32_t g = st.g[jrel], c_lvl = st.ci[jrel];
+        const uint32_t ju = job_of(X, j);
+        const uint32_t s0 = X.tb.seg_off[ju], ns = X.tb.seg_off[ju + 1] - s0;
+        const uint64_t base = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]) + (uint64_t)(c_lvl * n_mem) * ns + gi;
+        float bv = 0.f;
+        uint32_t bm = 0;
+        for (uint32_t m = 0; m < n_mem; ++m) {
+            const float v = X.best_thr[base + (uint64_t)m * ns];
+            if (v > bv) { bv = v; bm = m; }
+        }
+        if (bv > 0.f) {
+            float cost = grid.mem_levels_gb[bm];
+            if (grid.mem_mode) cost = cost * (float)g;
+            out.g = g;
+            out.c = (uint32_t)cpu_cost(grid, c_lvl, g);
+            out.mem_gb = cost;
+            out.plan = X.best_plan[base + (uint64_t)bm * ns];
+            out.thr = bv;
+            cost_d += (double)cost;
+            val_d += (double)bv / (double)X.ref_thr[job_of(X, j)];
+        }
+    }
+    assign[jrel] = out;
+}
+
 __global__ __launch_bounds__(JOB_THREADS) void k_mem_wish(Ctx X, JobState st, rk_assign *__restrict__ assign) {
     __shared__ double red[2][JOB_THREADS / 64];
     const uint32_t rnd = blockIdx.y, tid = threadIdx.x;
     uint32_t J0, J1;
     rk_cluster cl;
     round_of(X.R, rnd, J0, J1, cl);
-    const GridDev &grid = X.grid;
     const uint32_t jl = blockIdx.x * JOB_THREADS + tid;
-    const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem;
     double cost_d = 0.0, val_d = 0.0;
-    if (J0 + jl < J1) {
-        const uint32_t j = J0 + jl, jrel = j - X.jb;
-        rk_assign out = {0u, 0u, 0.f, RK_NO_PLAN, 0.f};
-        const int32_t gi = st.gi[jrel];
-        if (gi >= 0) {
-            const uint32_t g = st.g[jrel], c_lvl = st.ci[jrel];
-            const uint32_t ju = job_of(X, j);
-            const uint32_t s0 = X.tb.seg_off[ju], ns = X.tb.seg_off[ju + 1] - s0;
-            const uint64_t base = (uint64_t)n_rows * (s0 - X.tb.seg_off[X.jb]) + (uint64_t)(c_lvl * n_mem) * ns + gi;
-            float bv = 0.f;
-            uint32_t bm = 0;
-            for (uint32_t m = 0; m < n_mem; ++m) {
-                const float v = X.best_thr[base + (uint64_t)m * ns];
-                if (v > bv) { bv = v; bm = m; }
-            }
-            if (bv > 0.f) {
-                float cost = grid.mem_levels_gb[bm];
-                if (grid.mem_mode) cost = cost * (float)g;
-                out.g = g;
-                out.c = (uint32_t)cpu_cost(grid, c_lvl, g);
-                out.mem_gb = cost;
-                out.plan = X.best_plan[base + (uint64_t)bm * ns];
-                out.thr = bv;
-                cost_d = (double)cost;
-                val_d = (double)bv / (double)X.ref_thr[job_of(X, j)];
-            }
-        }
-        assign[jrel] = out;
-    }
+    if (J0 + jl < J1) mem_wish_job(X, st, J0 + jl, assign, cost_d, val_d);
     cost_d = wave_sum_f64(cost_d);
     val_d = wave_sum_f64(val_d);
     if ((tid & 63u) == 0) { red[0][tid >> 6] = cost_d; red[1][tid >> 6] = val_d; }
@@ -1136,24 +1164,16 @@ __global__ __launch_bounds__(JOB_THREADS) void k_mem_wish(Ctx X, JobState st, rk
     }
 }
 
-// One wavefront per round.
-__global__ __launch_bounds__(64) void k_mem_finish(Ctx X, JobState st, rk_assign *__restrict__ assign,
-                                                   float *__restrict__ totals) {
-    const uint32_t rnd = blockIdx.x, tid = threadIdx.x;
+// One wavefront (threadIdx.x = lane) closes a round whose wishes sum to `wish` GiB and `val` normalised throughput.
+__device__ void mem_close_round(const Ctx &X, const JobState &st, uint32_t rnd, double wish, double val,
+                                rk_assign *__restrict__ assign, float *__restrict__ totals) {
+    const uint32_t tid = threadIdx.x;
     uint32_t J0, J1;
     rk_cluster cl;
     round_of(X.R, rnd, J0, J1, cl);
     const GridDev &grid = X.grid;
     const uint32_t nj = J1 - J0, jrel0 = J0 - X.jb;
     const uint32_t n_mem = grid.n_mem, n_rows = grid.n_cpu * n_mem;
-    const uint32_t used_blocks = (nj + JOB_THREADS - 1) / JOB_THREADS;
-    double wish = 0.0, val = 0.0;
-    for (uint32_t b = tid; b < used_blocks; b += 64) {
-        wish += st.partial[((size_t)rnd * st.blocks_per_round + b) * 2 + 0];
-        val += st.partial[((size_t)rnd * st.blocks_per_round + b) * 2 + 1];
-    }
-    wish = wave_sum_f64(wish);
-    val = wave_sum_f64(val);
     if (wish <= 0.99 * (double)cl.host_mem_gb) {
         if (tid == 0) totals[rnd] = (float)val;
         return;
@@ -1224,6 +1244,24 @@ __global__ __launch_bounds__(64) void k_mem_finish(Ctx X, JobState st, rk_assign
     }
     sum = wave_sum_f64(sum);
     if (tid == 0) totals[rnd] = (float)sum;
+}
+
+// One wavefront per round.
+__global__ __launch_bounds__(64) void k_mem_finish(Ctx X, JobState st, rk_assign *__restrict__ assign,
+                                                   float *__restrict__ totals) {
+    const uint32_t rnd = blockIdx.x, tid = threadIdx.x;
+    uint32_t J0, J1;
+    rk_cluster cl;
+    round_of(X.R, rnd, J0, J1, cl);
+    const uint32_t used_blocks = (J1 - J0 + JOB_THREADS - 1) / JOB_THREADS;
+    double wish = 0.0, val = 0.0;
+    for (uint32_t b = tid; b < used_blocks; b += 64) {
+        wish += st.partial[((size_t)rnd * st.blocks_per_round + b) * 2 + 0];
+        val += st.partial[((size_t)rnd * st.blocks_per_round + b) * 2 + 1];
+    }
+    wish = wave_sum_f64(wish);
+    val = wave_sum_f64(val);
+    mem_close_round(X, st, rnd, wish, val, assign, totals);
 }
 
 // ------------------------------------------------------------------ service-level floors
@@ -1358,7 +1396,8 @@ int32_t scratch_typed(rk_ctx *ctx, int slot, size_t count, T **out) {
 
 template <int PASS>
 int32_t launch_pass(rk_ctx *ctx, const Ctx &X, const JobState &st, const HullBuf &H, const Hist &hist,
-                    uint32_t n_rounds, uint32_t n_jobs, uint32_t mj, uint32_t max_segs, size_t tail_lds, size_t zero_bins) {
+                    uint32_t n_rounds, uint32_t n_jobs, uint32_t mj, uint32_t max_segs, size_t tail_lds, size_t zero_bins,
+                    rk_assign *assign, float *totals) {
     hipStream_t s = ctx->stream;
     const uint32_t hull_blocks = (n_jobs + (HULL_THREADS / 64) - 1) / (HULL_THREADS / 64);
     const dim3 job_grid(st.blocks_per_round, n_rounds);
@@ -1376,7 +1415,7 @@ int32_t launch_pass(rk_ctx *ctx, const Ctx &X, const JobState &st, const HullBuf
         RK_CHECK_LAUNCH(ctx, "k_hull");
     }
     if (mj <= SMALL_ROUND_JOBS) {
-        k_select_small<PASS><<<n_rounds, TAIL_THREADS, tail_lds, s>>>(X, mj, st, H);
+        k_select_small<PASS><<<n_rounds, TAIL_THREADS, tail_lds, s>>>(X, mj, st, H, assign, totals);
         RK_CHECK_LAUNCH(ctx, "k_select_small");
         return RK_OK;
     }
@@ -1482,8 +1521,10 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
         k_floors<<<n_rounds, FLOOR_THREADS, (size_t)mj * 8, s>>>(X, st, *sla, mj);
         RK_CHECK_LAUNCH(ctx, "k_floors");
     }
-    if ((rc = launch_pass<0>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, max_segs_per_job, lds, hists ? hist_bins : 0))) return rc;
-    if ((rc = launch_pass<1>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, max_segs_per_job, lds, 0))) return rc;
+    if ((rc = launch_pass<0>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, max_segs_per_job, lds, hists ? hist_bins : 0, assign,
+                             totals))) return rc;
+    if ((rc = launch_pass<1>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, max_segs_per_job, lds, 0, assign, totals))) return rc;
+    if (!hists) return RK_OK;                                   // small rounds: the CPU pass's selection closed them
     if (max_jobs > 0) {
         k_mem_wish<<<dim3(st.blocks_per_round, n_rounds), JOB_THREADS, 0, s>>>(X, st, assign);
         RK_CHECK_LAUNCH(ctx, "k_mem_wish");
