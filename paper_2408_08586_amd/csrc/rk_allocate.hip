@@ -1034,63 +1034,76 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_tail(Ctx X, uint32_t max_jobs,
     tail_run<PASS, TAIL_KMAX>(X, st, rnd, J0, J1, st.free_g[rnd], st.free_g[X.R.n_rounds + rnd], max_jobs, lds_dyn, red);
 }
 
-// ------------------------------------------------------------------ small rounds: selection in one workgroup
+// ------------------------------------------------------------------ selection of a pass in one workgroup
 // For rounds of at most SMALL_ROUND_JOBS jobs the histograms, the threshold,
 // the application and the step-by-step tail of a pass run in one workgroup per
-// round, with the histograms in LDS: one launch instead of six.  The workgroup
-// of the CPU pass also takes the memory step that ends the round.
+// round, with the histograms in LDS: one launch instead of six (KMAX = jobs per
+// thread = 2).  The workgroup of the CPU pass also takes the memory step that
+// ends the round.  Larger rounds use the same kernel for their CPU pass
+// (KMAX = TAIL_KMAX, without the memory step) as long as all CPU walks together
+// are short, which the host can tell from the grid:
+// (CPU levels - 1) * jobs <= CPU_ONE_WG_STEPS.
+// The histogram (48 KiB) and the tail's scratch (12 bytes per job) share the
+// dynamic LDS: the tail starts when the threshold is known.
 constexpr uint32_t SMALL_ROUND_JOBS = 2048;
+constexpr uint64_t CPU_ONE_WG_STEPS = 65536;
+constexpr size_t SELECT_HIST_BYTES = (size_t)BINS * 12;
 
 __device__ __forceinline__ void mem_wish_job(const Ctx &X, const JobState &st, uint32_t j, rk_assign *__restrict__ assign,
                                              double &cost_d, double &val_d);
 __device__ void mem_close_round(const Ctx &X, const JobState &st, uint32_t rnd, double wish, double val,
                                 rk_assign *__restrict__ assign, float *__restrict__ totals);
 
-template <int PASS>
+template <int PASS, int KMAX>
 __global__ __launch_bounds__(TAIL_THREADS) void k_select_small(Ctx X, uint32_t max_jobs, JobState st, HullBuf H,
                                                               rk_assign *__restrict__ assign, float *__restrict__ totals) {
-    extern __shared__ float lds_dyn[];                          // tail scratch: max_jobs * 12 bytes
-    __shared__ uint32_t hg[BINS];                               // one histogram, used for level 0 and then level 1
-    __shared__ unsigned long long hc[BINS];
+    extern __shared__ unsigned long long lds_sel[];             // the histogram, then the tail's scratch
+    unsigned long long *hc = lds_sel;                           // one histogram, used for level 0 and then level 1
+    uint32_t *hg = reinterpret_cast<uint32_t *>(hc + BINS);
     __shared__ CutScratch cs;
     __shared__ unsigned long long red[TAIL_RED_WORDS];
+    __shared__ double sums[2 * (TAIL_THREADS / 64)];
     const uint32_t rnd = blockIdx.x, tid = threadIdx.x;
     uint32_t J0, J1;
     rk_cluster cl;
     round_of(X.R, rnd, J0, J1, cl);
     const uint32_t nj = J1 - J0;
-    unsigned long long capG, capC;
-    pass_caps<PASS>(X.R, cl, st, rnd, capG, capC);
-    for (uint32_t i = tid; i < BINS; i += TAIL_THREADS) { hg[i] = 0; hc[i] = 0; }
-    __syncthreads();
-    for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) hist_add<PASS, 0>(X, H, J0 + jl - X.jb, 0, hg, hc);
-    __syncthreads();
-    const Cut c0 = find_cut(hg, hc, 0, 0, capG, capC, cs);
-    Selection sel;
-    sel.thr24 = -1;
-    unsigned long long usedG = c0.baseG, usedC = c0.baseC;
-    if (c0.bin >= 0) {                                          // uniform over the workgroup
+    // a large round knows whether any job's CPU walk has a step at all (same in all threads)
+    const bool empty_pass = PASS == 1 && KMAX == TAIL_KMAX && st.cpu_steps[rnd] == 0u;
+    if (!empty_pass) {
+        unsigned long long capG, capC;
+        pass_caps<PASS>(X.R, cl, st, rnd, capG, capC);
         for (uint32_t i = tid; i < BINS; i += TAIL_THREADS) { hg[i] = 0; hc[i] = 0; }
         __syncthreads();
-        for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) hist_add<PASS, 1>(X, H, J0 + jl - X.jb, c0.bin, hg, hc);
+        for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) hist_add<PASS, 0>(X, H, J0 + jl - X.jb, 0, hg, hc);
         __syncthreads();
-        const Cut c1 = find_cut(hg, hc, c0.baseG, c0.baseC, capG, capC, cs);
-        sel.thr24 = ((long long)c0.bin << 12) + (long long)c1.bin;
-        usedG = c1.baseG; usedC = c1.baseC;
+        const Cut c0 = find_cut(hg, hc, 0, 0, capG, capC, cs);
+        Selection sel;
+        sel.thr24 = -1;
+        unsigned long long usedG = c0.baseG, usedC = c0.baseC;
+        if (c0.bin >= 0) {                                      // uniform over the workgroup
+            for (uint32_t i = tid; i < BINS; i += TAIL_THREADS) { hg[i] = 0; hc[i] = 0; }
+            __syncthreads();
+            for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) hist_add<PASS, 1>(X, H, J0 + jl - X.jb, c0.bin, hg, hc);
+            __syncthreads();
+            const Cut c1 = find_cut(hg, hc, c0.baseG, c0.baseC, capG, capC, cs);
+            sel.thr24 = ((long long)c0.bin << 12) + (long long)c1.bin;
+            usedG = c1.baseG; usedC = c1.baseC;
+        }
+        sel.freeG = capG - usedG;
+        sel.freeC = capC - usedC;
+        for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) apply_job<PASS>(X, st, H, J0 + jl, sel.thr24, sel.freeG, sel.freeC);
+        __syncthreads();                                        // the state in st is read back by the whole workgroup; the
+                                                                // histogram's LDS passes to the tail
+        tail_run<PASS, KMAX>(X, st, rnd, J0, J1, sel.freeG, sel.freeC, max_jobs, reinterpret_cast<float *>(lds_sel), red);
     }
-    sel.freeG = capG - usedG;
-    sel.freeC = capC - usedC;
-    for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) apply_job<PASS>(X, st, H, J0 + jl, sel.thr24, sel.freeG, sel.freeC);
-    __syncthreads();                                            // the state in st is read back by the whole workgroup
-    tail_run<PASS, SMALL_ROUND_JOBS / TAIL_THREADS>(X, st, rnd, J0, J1, sel.freeG, sel.freeC, max_jobs, lds_dyn, red);
-    if (PASS == 0) return;
+    if (PASS == 0 || KMAX == TAIL_KMAX) return;                 // (large rounds: a thread per job does it faster, k_mem_wish)
     // memory: every thread writes the wishes of its jobs, the first wavefront closes the round
     __syncthreads();                                            // the granted amounts are in st
     double cost_d = 0.0, val_d = 0.0;
     for (uint32_t jl = tid; jl < nj; jl += TAIL_THREADS) mem_wish_job(X, st, J0 + jl, assign, cost_d, val_d);
     cost_d = wave_sum_f64(cost_d);
     val_d = wave_sum_f64(val_d);
-    double *sums = reinterpret_cast<double *>(hc);              // the histograms are no longer needed
     if ((tid & 63u) == 0) { sums[tid >> 6] = cost_d; sums[TAIL_THREADS / 64 + (tid >> 6)] = val_d; }
     __syncthreads();                                            // also: the wishes are stored before anything replaces them
     if (tid < 64u) {
@@ -1394,13 +1407,15 @@ int32_t scratch_typed(rk_ctx *ctx, int slot, size_t count, T **out) {
     return rk_scratch(ctx, slot, count * sizeof(T), reinterpret_cast<void **>(out));
 }
 
+// *closed: the pass also took the memory step that ends the round
 template <int PASS>
 int32_t launch_pass(rk_ctx *ctx, const Ctx &X, const JobState &st, const HullBuf &H, const Hist &hist,
                     uint32_t n_rounds, uint32_t n_jobs, uint32_t mj, uint32_t max_segs, size_t tail_lds, size_t zero_bins,
-                    rk_assign *assign, float *totals) {
+                    rk_assign *assign, float *totals, bool *closed) {
     hipStream_t s = ctx->stream;
     const uint32_t hull_blocks = (n_jobs + (HULL_THREADS / 64) - 1) / (HULL_THREADS / 64);
     const dim3 job_grid(st.blocks_per_round, n_rounds);
+    *closed = false;
     if (n_jobs > 0) {
         // amounts per job: GPU counts (at most max_segs) in the GPU pass, CPU levels in the CPU pass
         const uint32_t amounts = PASS == 0 ? max_segs : X.grid.n_cpu;
@@ -1414,10 +1429,19 @@ int32_t launch_pass(rk_ctx *ctx, const Ctx &X, const JobState &st, const HullBuf
         }
         RK_CHECK_LAUNCH(ctx, "k_hull");
     }
+    const size_t sel_lds = tail_lds > SELECT_HIST_BYTES ? tail_lds : SELECT_HIST_BYTES;
     if (mj <= SMALL_ROUND_JOBS) {
-        k_select_small<PASS><<<n_rounds, TAIL_THREADS, tail_lds, s>>>(X, mj, st, H, assign, totals);
+        k_select_small<PASS, SMALL_ROUND_JOBS / TAIL_THREADS><<<n_rounds, TAIL_THREADS, sel_lds, s>>>(X, mj, st, H, assign, totals);
         RK_CHECK_LAUNCH(ctx, "k_select_small");
+        *closed = PASS == 1;
         return RK_OK;
+    }
+    if constexpr (PASS == 1) {
+        if ((uint64_t)(X.grid.n_cpu - 1u) * mj <= CPU_ONE_WG_STEPS) {
+            k_select_small<1, TAIL_KMAX><<<n_rounds, TAIL_THREADS, sel_lds, s>>>(X, mj, st, H, assign, totals);
+            RK_CHECK_LAUNCH(ctx, "k_select_small");
+            return RK_OK;
+        }
     }
     if (n_jobs > 0) {
         k_hist<PASS, 0><<<job_grid, JOB_THREADS, 0, s>>>(X, st, H, hist);
@@ -1502,13 +1526,15 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
         RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_floors),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
+        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_select_small<1, TAIL_KMAX>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
         raised[ctx->device & 63] = true;
     }
     static bool raised_small[64] = {};
     if (mj <= SMALL_ROUND_JOBS && !raised_small[ctx->device & 63]) {   // static + dynamic LDS go beyond 64 KiB
-        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_select_small<0>),
+        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_select_small<0, SMALL_ROUND_JOBS / TAIL_THREADS>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
-        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_select_small<1>),
+        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_select_small<1, SMALL_ROUND_JOBS / TAIL_THREADS>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
         raised_small[ctx->device & 63] = true;
     }
@@ -1521,10 +1547,12 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
         k_floors<<<n_rounds, FLOOR_THREADS, (size_t)mj * 8, s>>>(X, st, *sla, mj);
         RK_CHECK_LAUNCH(ctx, "k_floors");
     }
+    bool closed = false;
     if ((rc = launch_pass<0>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, max_segs_per_job, lds, hists ? hist_bins : 0, assign,
-                             totals))) return rc;
-    if ((rc = launch_pass<1>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, max_segs_per_job, lds, 0, assign, totals))) return rc;
-    if (!hists) return RK_OK;                                   // small rounds: the CPU pass's selection closed them
+                             totals, &closed))) return rc;
+    if ((rc = launch_pass<1>(ctx, X, st, H, hist, n_rounds, n_jobs, mj, max_segs_per_job, lds, 0, assign, totals,
+                             &closed))) return rc;
+    if (closed) return RK_OK;                                   // the CPU pass's selection took the memory step
     if (max_jobs > 0) {
         k_mem_wish<<<dim3(st.blocks_per_round, n_rounds), JOB_THREADS, 0, s>>>(X, st, assign);
         RK_CHECK_LAUNCH(ctx, "k_mem_wish");

@@ -305,18 +305,23 @@ def test_allocate_on_oracle_curves_is_exact(gpu, orc, name):
     run.close()
 
 
-@pytest.mark.parametrize("n_jobs", [3000, 12288])
-def test_allocate_many_jobs_random_curves(gpu, orc, n_jobs):
+@pytest.mark.parametrize("n_jobs,n_cpu", [(3000, 5), (12288, 5), (3000, 32), (12288, 7)])
+def test_allocate_many_jobs_random_curves(gpu, orc, n_jobs, n_cpu):
     """The allocation alone at its largest sizes: the per-segment values are
     drawn here (not produced by either implementation), so both sides see the
-    same float32 inputs and must return identical records."""
+    same float32 inputs and must return identical records.  With 5 CPU levels
+    one workgroup selects the CPU pass of a round; with 32 levels (3,000 jobs)
+    and 7 levels (12,288 jobs) the walks are too many for that and the
+    histogram kernels take it."""
     import paper_2408_08586_amd as rk
-    rng = np.random.default_rng(n_jobs)
+    rng = np.random.default_rng(n_jobs + n_cpu)
     base = workloads.stress(n_jobs=n_jobs)
     b = workloads.Bounds(g_max=64)
-    wl = workloads.Workload("alloc", base.coef, base.ints, b, base.grid, base.env, workloads.Cluster(4096, 30000, 2.0e5))
+    grid = base.grid if n_cpu == 5 else workloads.Grid(np.arange(1, n_cpu + 1, dtype=np.uint32), base.grid.cpu_mode,
+                                                       base.grid.mem_levels_gb, base.grid.mem_mode)
+    wl = workloads.Workload("alloc", base.coef, base.ints, b, grid, base.env, workloads.Cluster(4096, 30000, 2.0e5))
     ot = orc.enumerate_plans(wl.ints, wl.bounds)
-    n_rows = 20
+    n_rows = n_cpu * len(grid.mem_levels_gb)
     n = ot.n_segments(n_rows)
     # throughput grows roughly with g, is noisy, sometimes infeasible, sometimes exactly tied
     g_of = np.concatenate([np.tile(ot.seg_g[ot.seg_off[j]:ot.seg_off[j + 1]], n_rows) for j in range(n_jobs)])
