@@ -331,6 +331,7 @@ __global__ __launch_bounds__(ENUM_THREADS) void k_enumerate(
 // wavefronts by shuffles and across them through LDS, and the offsets leave
 // through LDS so that the stores are coalesced too.
 // back: [16 words of totals | n_jobs + 1 triple offsets | n_jobs + 1 segment offsets], one piece for the host
+// (the offsets only when the host keeps mirrors of them: back_offsets)
 constexpr uint32_t SCAN_PER = 8, SCAN_TILE = 1024 * SCAN_PER;
 
 struct Eight { uint32_t v[SCAN_PER]; };
@@ -352,7 +353,8 @@ __device__ __forceinline__ Eight load_eight(const uint32_t *__restrict__ cnt, ui
 __global__ __launch_bounds__(1024) void k_scan_counts(const uint32_t *__restrict__ cnt_t,
                                                       const uint32_t *__restrict__ cnt_s, uint32_t n_jobs,
                                                       uint32_t *__restrict__ off_t, uint32_t *__restrict__ off_s,
-                                                      uint32_t *__restrict__ totals, uint32_t *__restrict__ back) {
+                                                      uint32_t *__restrict__ totals, uint32_t *__restrict__ back,
+                                                      bool back_offsets) {
     __shared__ __align__(16) uint32_t buf_t[SCAN_TILE], buf_s[SCAN_TILE];
     __shared__ unsigned long long wave_t[16], wave_s[16];
     __shared__ uint32_t wave_mt[16], wave_ms[16];
@@ -405,8 +407,10 @@ __global__ __launch_bounds__(1024) void k_scan_counts(const uint32_t *__restrict
                 const uint32_t a = buf_t[at], b = buf_s[at];
                 off_t[j] = a;
                 off_s[j] = b;
-                back[16 + j] = a;
-                back[16 + n_jobs + 1 + j] = b;
+                if (back_offsets) {
+                    back[16 + j] = a;
+                    back[16 + n_jobs + 1 + j] = b;
+                }
             }
         }
         carry_t += all_t; carry_s += all_s;
@@ -518,9 +522,9 @@ extern "C" int32_t rk_enumerate_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk
             RK_CHECK_LAUNCH(ctx, "k_spread_counts");
         }
     }
-    k_scan_counts<<<1, 1024, 0, ctx->stream>>>(cnt_t, cnt_s, J, off_t, off_s, totals, back);
-    RK_CHECK_LAUNCH(ctx, "k_scan_counts");
     const bool mirrors = fill && table->h_triple_off && table->h_seg_off;
+    k_scan_counts<<<1, 1024, 0, ctx->stream>>>(cnt_t, cnt_s, J, off_t, off_s, totals, back, mirrors);
+    RK_CHECK_LAUNCH(ctx, "k_scan_counts");
     RK_HIP(ctx, hipMemcpyAsync(h, back, (mirrors ? words_back : 16) * 4, hipMemcpyDeviceToHost, ctx->stream));
     RK_HIP(ctx, hipEventRecord(ctx->counts_ev, ctx->stream));
     // The fill pass goes out before the host knows the totals, so that the device does not wait for the
