@@ -230,7 +230,9 @@ int32_t rk_job_curves(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *tab
 /* Greedy allocation over the curves of jobs [job_begin, job_end) (Sec. 5.2:
  * jobs that gain the most per unit of resource first, GPU slopes before CPU
  * slopes, memory from the chosen plan last).  The arrays are in segment
- * layout of the same job range.  float32 slopes ((v1-v0)/ref_thr)/delta.
+ * layout of the same job range (they may be NULL when the table has no
+ * segment at all: then no job gets anything).  float32 slopes
+ * ((v1-v0)/ref_thr)/delta.
  *   assign [device] one record per job of the range
  *   total  [device] one float: sum of thr/ref_thr over scheduled jobs */
 int32_t rk_allocate(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,

@@ -1571,7 +1571,8 @@ extern "C" int32_t rk_allocate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
     if ((rc = rk_check_table(ctx, table, jb, je))) return rc;
     if ((rc = rk_check_grid(ctx, grid))) return rc;
     if (!cluster || !total) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
-    if (je > jb && (!ref_thr || !best_thr || !best_plan || !curve_thr || !assign))
+    // (a table without any segment has empty value arrays, which may be null)
+    if (je > jb && (!ref_thr || !assign || (table->n_segs > 0 && (!best_thr || !best_plan || !curve_thr))))
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
     if (!(cluster->host_mem_gb >= 0.f)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "host_mem_gb negative or NaN");
     if (table->max_segs_per_job > 32767u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 32767 segments per job");
@@ -1602,7 +1603,8 @@ extern "C" int32_t rk_allocate_sla(rk_ctx *ctx, const float *ref_thr, const rk_p
     if ((rc = rk_check_table(ctx, table, jb, je))) return rc;
     if ((rc = rk_check_grid(ctx, grid))) return rc;
     if (!cluster || !total) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
-    if (je > jb && (!ref_thr || !best_thr || !best_plan || !curve_thr || !assign || !min_seg || !min_c))
+    if (je > jb && (!ref_thr || !assign || !min_seg || !min_c ||
+                    (table->n_segs > 0 && (!best_thr || !best_plan || !curve_thr))))
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
     if (je > jb && (rc = rk_check_sla(ctx, sla, false))) return rc;
     if (!(cluster->host_mem_gb >= 0.f)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "host_mem_gb negative or NaN");

@@ -438,8 +438,13 @@ def compare_rounds(assign, total, r):
     the oracle's greedy was clear (smallest slope gap well above float32
     noise) the assignments must be equal; otherwise the totals must agree."""
     same_g = np.array_equal(assign["g"], r["assign"]["g"]) and np.array_equal(assign["c"], r["assign"]["c"])
-    if r["min_gap"] > 1e-4:
-        assert same_g
+    if r["min_gap"] > 1e-4 and not same_g:
+        # the slopes that competed were far apart; what may still differ is whether a step of the CPU pass exists at
+        # all: a job may hold another CPU level where that changes its throughput by less than the tolerance
+        assert np.array_equal(assign["g"], r["assign"]["g"])
+        moved = assign["c"] != r["assign"]["c"]
+        want = r["assign"]["thr"][moved].astype(np.float64)
+        assert np.all(np.abs(assign["thr"][moved] - want) <= REL * want)
     if same_g:
         assert np.array_equal(assign["mem_gb"], r["assign"]["mem_gb"])
         sched = assign["g"] > 0
@@ -587,6 +592,17 @@ def test_edge_cases(gpu, orc):
     assert n == 0
     assign, total = run.schedule_round()
     assert assign.size == 0 and total == 0.0
+    run.close()
+    # jobs, none of which has a plan: the table has no segment, the value arrays are empty (null pointers are fine)
+    ints = np.array([[5, 7, 2], [0, 8, 1], [8, 0, 1]], np.uint32)
+    wl = workloads.Workload("noplans", base.coef[:3], ints, base.bounds, base.grid, base.env, base.cluster)
+    run = gpu(wl)
+    t = run.enumerate()
+    assert t.n_triples == 0 and t.n_segs == 0
+    assign, total = run.allocate(None, None, None)
+    assert (assign["g"] == 0).all() and (assign["plan"] == 0xFFFFFFFF).all() and total == 0.0
+    assign, total = run.schedule_round()
+    assert (assign["g"] == 0).all() and total == 0.0
     run.close()
     # a job without any plan among jobs that have plans; a cap nothing fits in
     ints = base.ints.copy()
