@@ -642,6 +642,41 @@ def test_edge_cases(gpu, orc):
     run.close()
 
 
+def test_two_contexts_and_a_side_stream(gpu, orc):
+    """Two contexts alive at once, one of them on a stream of its own (default priority): calls taken in turns
+    give what each context gives alone."""
+    import torch
+    wl1, wl2 = workloads.tiny(), workloads.paper_scale()
+    alone = []
+    for wl in (wl1, wl2):
+        run = gpu(wl)
+        alone.append(run.schedule_round())
+        run.close()
+    side = torch.cuda.Stream()
+    r1 = gpu(wl1)
+    with torch.cuda.stream(side):
+        r2 = gpu(wl2)                                    # the context takes the stream that is current: the side stream
+    for _ in range(3):
+        with torch.cuda.stream(side):
+            b2 = r2.schedule_round()
+            r2.enumerate()
+            thr2, _, n2 = r2.eval(want_feas=False)
+        b1 = r1.schedule_round()
+        r1.enumerate()
+        thr1, _, n1 = r1.eval(want_feas=False)
+        assert np.array_equal(b1[0], alone[0][0]) and b1[1] == alone[0][1]
+        assert np.array_equal(b2[0], alone[1][0]) and b2[1] == alone[1][1]
+        with torch.cuda.stream(side):
+            bt2, bp2, ns2 = r2.best(thr2)
+            f2 = r2.fused()
+            assert np.array_equal(r2.host(bt2, ns2), r2.host(f2[0], ns2))
+        bt1, bp1, ns1 = r1.best(thr1)
+        assert np.array_equal(r1.host(bt1, ns1), r1.host(r1.fused()[0], ns1))
+    r1.close()
+    with torch.cuda.stream(side):
+        r2.close()
+
+
 def test_option_masks_and_memory_modes(gpu, orc):
     base = workloads.paper_scale()
     b = workloads.Bounds(g_max=32, tp_max=4, pp_max=8, zero_mask=0b1101, gc_mask=0b11, off_mask=0b11)
