@@ -356,7 +356,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="stress")
     ap.add_argument("--chunks", type=int, default=3, help="job chunks streamed through one candidate buffer")
-    ap.add_argument("--cpu-sample-jobs", type=int, default=1500)
+    ap.add_argument("--cpu-sample-jobs", type=int, default=4000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-what-if", action="store_true")
     ap.add_argument("--no-place", action="store_true", help="skip the node-level placement")
