@@ -91,6 +91,25 @@ def test_simulation_end_to_end_on_device_curves(gpu, orc):
     run.close()
 
 
+def test_simulation_from_a_side_stream(gpu, orc):
+    """The context sits on a stream of its own; the simulation's internal stream is ordered after the uploads made
+    on that stream and the results are read on it afterwards."""
+    import torch
+    wl = workloads.paper_scale()
+    r = orc.schedule_round(wl, n_threads=16)
+    tr = workloads.trace(wl.n_jobs, horizon_s=3600.0)
+    work = workloads.job_lengths_s(tr.u_duration) * wl.coef[:, 16] * 2.0
+    want = orc.simulator.simulate(wl.coef[:, 16], r["table"], wl.grid, wl.cluster, r["best_thr"], r["best_plan"],
+                                  r["curve_thr"], tr.arrival, work, tr.delta, 60.0, 90)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        run = gpu(wl)
+        run.enumerate()
+        for _ in range(2):
+            same(run_on_gpu(run, r, tr.arrival, work, tr.delta, 60.0, 90, 0.97), want)
+        run.close()
+
+
 def test_simulation_edge_cases(gpu, orc):
     import paper_2408_08586_amd as rk
     wl = workloads.tiny()
