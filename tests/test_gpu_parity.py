@@ -436,7 +436,11 @@ def test_schedule_rounds_uneven_batch(gpu, orc):
 def compare_rounds(assign, total, r):
     """End-to-end result against the oracle's round.  Where every decision of
     the oracle's greedy was clear (smallest slope gap well above float32
-    noise) the assignments must be equal; otherwise the totals must agree."""
+    noise) the assignments must be equal; otherwise the totals must agree,
+    unless the near-tie changed which jobs are served at all (a job that took
+    GPUs can then lose them again in the memory step, so even the totals need
+    not be close; the allocation on the oracle's own curves is compared bit
+    for bit elsewhere)."""
     same_g = np.array_equal(assign["g"], r["assign"]["g"]) and np.array_equal(assign["c"], r["assign"]["c"])
     if r["min_gap"] > 1e-4 and not same_g:
         # the slopes that competed were far apart; what may still differ is whether a step of the CPU pass exists at
@@ -450,7 +454,8 @@ def compare_rounds(assign, total, r):
         sched = assign["g"] > 0
         rel = np.abs(assign["thr"][sched].astype(np.float64) - r["assign"]["thr"][sched]) / r["assign"]["thr"][sched]
         assert rel.size == 0 or rel.max() <= REL
-    assert total == pytest.approx(r["total"], rel=1e-4)
+    if r["min_gap"] > 1e-4 or np.array_equal(assign["g"] > 0, r["assign"]["g"] > 0):
+        assert total == pytest.approx(r["total"], rel=1e-4)
     return same_g
 
 
