@@ -23,8 +23,9 @@ def gpu():
     return DeviceRun
 
 
-def draw_workload(rng, base, wide=False):
-    """A workload of a few jobs; wide: jobs with hundreds of GPU counts, a small grid."""
+def draw_workload(rng, base, wide=False, mid=False):
+    """A workload of a few jobs; wide: jobs with hundreds of GPU counts, a small grid; mid: hundreds of jobs with
+    up to 256 GPUs each, a small grid."""
     if wide:
         n_jobs = int(rng.integers(1, 7))
         ints = np.stack([rng.choice([96, 60, 48, 120, 12, 7], n_jobs), rng.choice([5040, 2520, 1680, 720, 360, 64, 30], n_jobs),
@@ -32,15 +33,16 @@ def draw_workload(rng, base, wide=False):
         g_max, pp_max = int(rng.choice([96, 128, 256, 720, 1024])), int(rng.choice([4, 16, 255]))
         n_cpu, n_mem = int(rng.integers(1, 4)), int(rng.integers(1, 3))
     else:
-        n_jobs = int(rng.integers(1, 48))
+        n_jobs = int(rng.integers(48, 700)) if mid else int(rng.integers(1, 48))
         ints = np.stack([rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 24, 30, 32, 36, 40, 48, 60, 64, 80, 96], n_jobs),
                          rng.choice([1, 2, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 360], n_jobs),
                          rng.choice([1, 1, 1, 2, 2, 3, 4, 8], n_jobs)], 1).astype(np.uint32)
         for k in range(n_jobs):
             if rng.uniform() < 0.03:
                 ints[k, rng.integers(0, 3)] = 0                      # no layers, no batch or no micro-batch: no plan
-        g_max, pp_max = int(rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64])), int(rng.choice([1, 2, 3, 4, 8, 16]))
-        n_cpu, n_mem = int(rng.integers(1, 9)), int(rng.integers(1, 7))
+        g_max = int(rng.choice([16, 40, 64, 100, 128, 200, 256] if mid else [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64]))
+        pp_max = int(rng.choice([1, 2, 3, 4, 8, 16]))
+        n_cpu, n_mem = (int(rng.integers(1, 5)), int(rng.integers(1, 4))) if mid else (int(rng.integers(1, 9)), int(rng.integers(1, 7)))
     coef = base.coef[rng.integers(0, base.coef.shape[0], n_jobs)].copy()
     b = workloads.Bounds(g_max=g_max, tp_max=int(rng.choice([1, 2, 4, 8])), pp_max=pp_max, zero_mask=int(rng.integers(1, 16)),
                          gc_mask=int(rng.integers(1, 4)), off_mask=int(rng.integers(1, 4)), mu_mask=int(rng.integers(1, 16)))
@@ -110,6 +112,16 @@ def test_random_small_workloads(gpu, orc):
         rng = np.random.default_rng(90000 + seed)
         n += check_path(gpu, orc, draw_workload(rng, base), rng)
     print(f"300 random workloads, {n} candidates compared")
+    assert n > 10 ** 7
+
+
+def test_random_mid_size_workloads(gpu, orc):
+    base = workloads.paper_scale()
+    n = 0
+    for seed in range(60):
+        rng = np.random.default_rng(93000 + seed)
+        n += check_path(gpu, orc, draw_workload(rng, base, mid=True), rng)
+    print(f"60 random workloads of 48 to 699 jobs, {n} candidates compared")
     assert n > 10 ** 7
 
 
