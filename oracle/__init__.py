@@ -24,15 +24,26 @@ TERMS = ("n", "m", "a", "Tf_mb", "T_fwd", "T_bwd", "V_dp", "V_tp", "V_pp", "T_dp
          "B_dp", "B_tp", "B_pp")
 
 
-def build(force: bool = False) -> str:
-    """Compile the oracle with g++ (strict IEEE: no contraction, no fast-math)."""
-    stale = (not os.path.exists(_LIB)
-             or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_HDR)))
+_LIB_SAN = os.path.join(_HERE, "librk_oracle_san.so")
+
+
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile the oracle with g++ (strict IEEE: no contraction, no fast-math).
+
+    sanitize=True builds a second library with AddressSanitizer and
+    UndefinedBehaviorSanitizer (CPU only).  A process can load it only when the
+    sanitizer runtime is loaded first (LD_PRELOAD=$(g++ -print-file-name=libasan.so));
+    setting RK_ORACLE_SANITIZE=1 makes lib() pick it."""
+    out = _LIB_SAN if sanitize else _LIB
+    stale = (not os.path.exists(out)
+             or os.path.getmtime(out) < max(os.path.getmtime(_SRC), os.path.getmtime(_HDR)))
     if force or stale:
         cmd = ["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
-               "-shared", "-pthread", "-Wall", "-o", _LIB, _SRC]
-        subprocess.run(cmd, check=True, cwd=_HERE)
-    return _LIB
+               "-shared", "-pthread", "-Wall"]
+        if sanitize:
+            cmd += ["-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer"]
+        subprocess.run(cmd + ["-o", out, _SRC], check=True, cwd=_HERE)
+    return out
 
 
 class _Env(C.Structure):
@@ -62,7 +73,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        _lib = C.CDLL(build(sanitize=os.environ.get("RK_ORACLE_SANITIZE") == "1"))
+        _lib.ork_host_cores.restype = C.c_uint32
         _lib.ork_f_overlap.restype = C.c_double
         _lib.ork_f_overlap.argtypes = [C.c_double] * 3
         _lib.ork_eval_one.restype = C.c_uint32
@@ -114,13 +126,18 @@ def f_overlap(k, x, y):
     return lib().ork_f_overlap(float(k), float(x), float(y))
 
 
-def enumerate_plans(ints, bounds) -> Table:
+def host_cores() -> int:
+    """Host threads the machine offers (std::thread::hardware_concurrency)."""
+    return int(lib().ork_host_cores())
+
+
+def enumerate_plans(ints, bounds, n_threads=1) -> Table:
     ints = np.ascontiguousarray(ints, dtype=np.uint32)
     J = ints.shape[0]
     nt, ns = C.c_uint64(0), C.c_uint64(0)
     b = _bounds(bounds)
     lib().ork_enumerate(C.c_uint32(J), _p(ints), C.byref(b), None, None, C.c_uint64(0), None, None, None,
-                        C.c_uint64(0), C.byref(nt), C.byref(ns))
+                        C.c_uint64(0), C.byref(nt), C.byref(ns), C.c_uint32(n_threads))
     triple_off = np.zeros(J + 1, np.uint32)
     triples = np.zeros((max(nt.value, 1), 4), np.uint32)
     seg_off = np.zeros(J + 1, np.uint32)
@@ -128,7 +145,7 @@ def enumerate_plans(ints, bounds) -> Table:
     seg_first = np.zeros(max(ns.value, 1), np.uint32)
     rc = lib().ork_enumerate(C.c_uint32(J), _p(ints), C.byref(b), _p(triple_off), _p(triples),
                              C.c_uint64(nt.value), _p(seg_off), _p(seg_g), _p(seg_first),
-                             C.c_uint64(ns.value), C.byref(nt), C.byref(ns))
+                             C.c_uint64(ns.value), C.byref(nt), C.byref(ns), C.c_uint32(n_threads))
     assert rc == 0
     return Table(triple_off, triples[:nt.value], seg_off, seg_g[:ns.value], seg_first[:ns.value])
 
@@ -162,7 +179,7 @@ def eval_jobs(coef, ints, bounds, table, grid, env, jb=0, je=None, want_reason=T
     return thr, reason
 
 
-def best_plan(table, grid, thr, jb=0, je=None):
+def best_plan(table, grid, thr, jb=0, je=None, n_threads=1):
     """Segmented argmax; dtype of thr (float64 or float32) selects the precision."""
     je = table.n_jobs if je is None else je
     gh = _GridHolder(grid)
@@ -173,7 +190,8 @@ def best_plan(table, grid, thr, jb=0, je=None):
     best_thr = np.zeros(n, thr.dtype)
     best_idx = np.zeros(n, np.uint32)
     fn = lib().ork_best_plan_f64 if thr.dtype == np.float64 else lib().ork_best_plan_f32
-    rc = fn(C.byref(table.c), C.byref(gh.c), C.c_uint32(jb), C.c_uint32(je), _p(thr), _p(best_thr), _p(best_idx))
+    rc = fn(C.byref(table.c), C.byref(gh.c), C.c_uint32(jb), C.c_uint32(je), _p(thr), _p(best_thr), _p(best_idx),
+            C.c_uint32(n_threads))
     assert rc == 0
     return best_thr, best_idx
 
@@ -212,9 +230,9 @@ def greedy(ref_thr, table, grid, cluster, best_thr, best_idx, curve_thr):
 def schedule_round(wl, n_threads=1):
     """The whole path on a workload: enumerate -> evaluate (float64) -> argmax
     (float64) -> round to float32 -> curves -> greedy.  Returns a dict."""
-    table = enumerate_plans(wl.ints, wl.bounds)
+    table = enumerate_plans(wl.ints, wl.bounds, n_threads=n_threads)
     thr, reason = eval_jobs(wl.coef, wl.ints, wl.bounds, table, wl.grid, wl.env, n_threads=n_threads)
-    bt64, bp = best_plan(table, wl.grid, thr)
+    bt64, bp = best_plan(table, wl.grid, thr, n_threads=n_threads)
     bt = bt64.astype(np.float32)
     ct, cp, cg = curves(table, wl.grid, bt, bp)
     assign, total, gap = greedy(wl.coef[:, 16], table, wl.grid, wl.cluster, bt, bp, ct)

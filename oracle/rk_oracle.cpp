@@ -231,9 +231,11 @@ float tier_gb(const ork_grid *grid, uint32_t mi, uint32_t g) {
 
 template <typename T>
 int best_plan_impl(const ork_table *tb, const ork_grid *grid, uint32_t job_begin, uint32_t job_end,
-                   const T *thr, T *best_thr, uint32_t *best_plan) {
+                   const T *thr, T *best_thr, uint32_t *best_plan, uint32_t n_threads) {
     const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
-    for (uint32_t j = job_begin; j < job_end; ++j) {
+    if (n_threads == 0) n_threads = 1;
+    auto work = [&](uint32_t tid) {                       /* jobs are independent: threads take them in turns */
+    for (uint32_t j = job_begin + tid; j < job_end; j += n_threads) {
         const uint64_t nt = tb->triple_off[j + 1] - tb->triple_off[j];
         const uint64_t ns = tb->seg_off[j + 1] - tb->seg_off[j];
         const uint64_t cbase = 16ull * rows * (tb->triple_off[j] - tb->triple_off[job_begin]);
@@ -252,6 +254,11 @@ int best_plan_impl(const ork_table *tb, const ork_grid *grid, uint32_t job_begin
             }
         }
     }
+    };
+    if (n_threads == 1) { work(0); return 0; }
+    std::vector<std::thread> pool;
+    for (uint32_t i = 0; i < n_threads; ++i) pool.emplace_back(work, i);
+    for (auto &th : pool) th.join();
     return 0;
 }
 
@@ -276,49 +283,68 @@ double ork_f_overlap(double k, double x, double y) {
 int ork_enumerate(uint32_t n_jobs, const uint32_t *ints, const ork_bounds *bounds,
                   uint32_t *triple_off, uint32_t *triples, uint64_t cap_triples,
                   uint32_t *seg_off, uint32_t *seg_g, uint32_t *seg_first, uint64_t cap_segs,
-                  uint64_t *n_triples, uint64_t *n_segs) {
-    uint64_t nt = 0, ns = 0;
-    const bool write = triple_off && triples && seg_off && seg_g && seg_first;
-    bool overflow = false;
-    for (uint32_t j = 0; j < n_jobs; ++j) {
-        const uint32_t l = ints[j * 3 + LAYERS], b = ints[j * 3 + GBATCH], mu = ints[j * 3 + MBATCH];
-        if (write) { triple_off[j] = (uint32_t)nt; seg_off[j] = (uint32_t)ns; }
-        const uint64_t job_first = nt;
-        for (uint32_t g = 1; g <= bounds->g_max; ++g) {
-            bool any = false;
-            for (uint32_t t = 1; t <= 8 && t <= bounds->tp_max; t *= 2) {
-                for (uint32_t p = 1; p <= bounds->pp_max && p <= l; ++p) {
-                    if (l % p != 0) continue;
-                    if (g % (t * p) != 0) continue;
-                    const uint32_t d = g / (t * p);
-                    for (uint32_t v = 0; v < 4; ++v) {
-                        if (!((bounds->mu_mask >> v) & 1u)) continue;
-                        // n = b/(d*mu*2^v) micro-batches per replica: a whole number, at least one
-                        if (mu == 0 || b == 0 || b % ((uint64_t)d * (mu << v)) != 0) continue;
-                        if (!any) {
-                            any = true;
-                            if (write) {
-                                if (ns < cap_segs) { seg_g[ns] = g; seg_first[ns] = (uint32_t)(nt - job_first); }
-                                else overflow = true;
+                  uint64_t *n_triples, uint64_t *n_segs, uint32_t n_threads) {
+    /* every job on its own (the jobs are independent; threads take them in turns), then laid end to end */
+    struct JobPlans { std::vector<uint32_t> dtpv, seg_g, seg_first; };
+    std::vector<JobPlans> per_job(n_jobs);
+    auto search = [&](uint32_t tid, uint32_t step) {
+        for (uint32_t j = tid; j < n_jobs; j += step) {
+            const uint32_t l = ints[j * 3 + LAYERS], b = ints[j * 3 + GBATCH], mu = ints[j * 3 + MBATCH];
+            JobPlans &out = per_job[j];
+            for (uint32_t g = 1; g <= bounds->g_max; ++g) {
+                bool any = false;
+                for (uint32_t t = 1; t <= 8 && t <= bounds->tp_max; t *= 2) {
+                    for (uint32_t p = 1; p <= bounds->pp_max && p <= l; ++p) {
+                        if (l % p != 0) continue;
+                        if (g % (t * p) != 0) continue;
+                        const uint32_t d = g / (t * p);
+                        for (uint32_t v = 0; v < 4; ++v) {
+                            if (!((bounds->mu_mask >> v) & 1u)) continue;
+                            // n = b/(d*mu*2^v) micro-batches per replica: a whole number, at least one
+                            if (mu == 0 || b == 0 || b % ((uint64_t)d * (mu << v)) != 0) continue;
+                            if (!any) {
+                                any = true;
+                                out.seg_g.push_back(g);
+                                out.seg_first.push_back((uint32_t)(out.dtpv.size() / 4));
                             }
-                            ++ns;
+                            out.dtpv.push_back(d); out.dtpv.push_back(t); out.dtpv.push_back(p); out.dtpv.push_back(v);
                         }
-                        if (write) {
-                            if (nt < cap_triples) {
-                                triples[nt * 4 + 0] = d; triples[nt * 4 + 1] = t; triples[nt * 4 + 2] = p; triples[nt * 4 + 3] = v;
-                            } else overflow = true;
-                        }
-                        ++nt;
                     }
                 }
             }
         }
+    };
+    if (n_threads <= 1) search(0, 1);
+    else {
+        std::vector<std::thread> pool;
+        for (uint32_t i = 0; i < n_threads; ++i) pool.emplace_back(search, i, n_threads);
+        for (auto &th : pool) th.join();
+    }
+    uint64_t nt = 0, ns = 0;
+    const bool write = triple_off && triples && seg_off && seg_g && seg_first;
+    bool overflow = false;
+    for (uint32_t j = 0; j < n_jobs; ++j) {
+        const JobPlans &in = per_job[j];
+        if (write) { triple_off[j] = (uint32_t)nt; seg_off[j] = (uint32_t)ns; }
+        const uint64_t jt = in.dtpv.size() / 4, js = in.seg_g.size();
+        if (write) {
+            if (nt + jt <= cap_triples) std::copy(in.dtpv.begin(), in.dtpv.end(), triples + nt * 4);
+            else overflow = true;
+            if (ns + js <= cap_segs) {
+                std::copy(in.seg_g.begin(), in.seg_g.end(), seg_g + ns);
+                std::copy(in.seg_first.begin(), in.seg_first.end(), seg_first + ns);
+            } else overflow = true;
+        }
+        nt += jt; ns += js;
     }
     if (write) { triple_off[n_jobs] = (uint32_t)nt; seg_off[n_jobs] = (uint32_t)ns; }
     if (n_triples) *n_triples = nt;
     if (n_segs) *n_segs = ns;
     return overflow ? -1 : 0;
 }
+
+/* Host threads the machine offers (what the benchmark states beside the oracle's timings). */
+uint32_t ork_host_cores(void) { return std::thread::hardware_concurrency(); }
 
 uint32_t ork_eval_one(const float *coef17, const uint32_t *ints3, const ork_bounds *bounds,
                       const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t v, uint32_t z,
@@ -400,12 +426,12 @@ int ork_eval_jobs(uint32_t n_jobs, const float *coef, const uint32_t *ints,
  * ties; no feasible plan gives (0, ORK_NO_PLAN).
  * Pinned: numpy argmax over a flat list in the tests. */
 int ork_best_plan_f64(const ork_table *tb, const ork_grid *grid, uint32_t jb, uint32_t je,
-                      const double *thr, double *best_thr, uint32_t *best_plan) {
-    return best_plan_impl<double>(tb, grid, jb, je, thr, best_thr, best_plan);
+                      const double *thr, double *best_thr, uint32_t *best_plan, uint32_t n_threads) {
+    return best_plan_impl<double>(tb, grid, jb, je, thr, best_thr, best_plan, n_threads);
 }
 int ork_best_plan_f32(const ork_table *tb, const ork_grid *grid, uint32_t jb, uint32_t je,
-                      const float *thr, float *best_thr, uint32_t *best_plan) {
-    return best_plan_impl<float>(tb, grid, jb, je, thr, best_thr, best_plan);
+                      const float *thr, float *best_thr, uint32_t *best_plan, uint32_t n_threads) {
+    return best_plan_impl<float>(tb, grid, jb, je, thr, best_thr, best_plan, n_threads);
 }
 
 /* Resource sensitivity curve (Sec. 5.2, Fig. 6): for each GPU count the

@@ -66,11 +66,15 @@ double ork_f_overlap(double k, double x, double y);
 
 /* Enumerate (d,t,p,v) entries per job in canonical order (g, then t, p, v
  * ascending).  Null output buffers: only the counts are produced. Returns 0,
- * or -1 if a capacity is too small (counts still written). */
+ * or -1 if a capacity is too small (counts still written).  n_threads host
+ * threads share the jobs (0 or 1: the calling thread alone). */
 int ork_enumerate(uint32_t n_jobs, const uint32_t *ints, const ork_bounds *bounds,
                   uint32_t *triple_off, uint32_t *triples, uint64_t cap_triples,
                   uint32_t *seg_off, uint32_t *seg_g, uint32_t *seg_first, uint64_t cap_segs,
-                  uint64_t *n_triples, uint64_t *n_segs);
+                  uint64_t *n_triples, uint64_t *n_segs, uint32_t n_threads);
+
+/* std::thread::hardware_concurrency() of the machine. */
+uint32_t ork_host_cores(void);
 
 /* One candidate; terms[ORK_N_TERMS] receives every intermediate quantity
  * (order documented in rk_oracle.cpp).  Returns the reason bits
@@ -99,9 +103,11 @@ int ork_eval_jobs(uint32_t n_jobs, const float *coef, const uint32_t *ints,
 
 /* Per segment x cpu level x mem tier: maximum and lowest-index argmax. */
 int ork_best_plan_f64(const ork_table *table, const ork_grid *grid, uint32_t job_begin,
-                      uint32_t job_end, const double *thr, double *best_thr, uint32_t *best_plan);
+                      uint32_t job_end, const double *thr, double *best_thr, uint32_t *best_plan,
+                      uint32_t n_threads);
 int ork_best_plan_f32(const ork_table *table, const ork_grid *grid, uint32_t job_begin,
-                      uint32_t job_end, const float *thr, float *best_thr, uint32_t *best_plan);
+                      uint32_t job_end, const float *thr, float *best_thr, uint32_t *best_plan,
+                      uint32_t n_threads);
 
 /* Prefix maximum over a job's GPU counts (resource sensitivity curve). */
 int ork_curves_f32(const ork_table *table, const ork_grid *grid, uint32_t job_begin,

@@ -24,7 +24,7 @@ __host__ __device__ inline size_t fused_lds_bytes(const FusedLds &L) {
 
 __global__ __launch_bounds__(FUSED_THREADS) void k_fused(JobDev jobs, TableDev tb, GridDev grid, rk_env env,
                                                          uint32_t jb, uint32_t option_mask, FusedLds L,
-                                                         uint32_t c_per_pass,
+                                                         uint32_t c_per_pass, uint32_t m_per_pass,
                                                          float *__restrict__ best_thr, uint32_t *__restrict__ best_plan,
                                                          float *__restrict__ curve_thr, uint32_t *__restrict__ curve_plan,
                                                          uint32_t *__restrict__ curve_g) {
@@ -94,10 +94,17 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_fused(JobDev jobs, TableDev t
         }
     }
 
+    // A pass keeps the keys of some rows in LDS: several CPU levels with all their tiers, or, when the rows of one
+    // level do not fit, some tiers of one level (m_per_pass < n_mem only together with c_per_pass == 1).  Either
+    // way the rows of a pass are neighbours in the output, starting at row c_lo * n_mem + m_lo.
     const float fb = (float)J.gbatch;
-    for (uint32_t c_lo = 0; c_lo < grid.n_cpu; c_lo += c_per_pass) {
+    for (uint32_t c_lo = 0; c_lo < grid.n_cpu; c_lo += c_per_pass)
+    for (uint32_t m_lo = 0; m_lo < n_mem; m_lo += m_per_pass) {
         const uint32_t c_hi = c_lo + c_per_pass < grid.n_cpu ? c_lo + c_per_pass : grid.n_cpu;
-        const uint32_t pass_rows = (c_hi - c_lo) * n_mem;
+        const uint32_t m_hi = m_lo + m_per_pass < n_mem ? m_lo + m_per_pass : n_mem;
+        const uint32_t m_cnt = m_hi - m_lo;
+        const uint32_t pass_rows = (c_hi - c_lo) * m_cnt;
+        const uint32_t row0 = c_lo * n_mem + m_lo;
         for (uint32_t i = tid; i < pass_rows * ns; i += FUSED_THREADS) seg_best[(size_t)(i / ns) * L.max_ns + i % ns] = 0ull;
         __syncthreads();
 
@@ -124,9 +131,9 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_fused(JobDev jobs, TableDev t
                 }
             }
             const float need = t_host[tl];
-            for (uint32_t mi = 0; mi < n_mem; ++mi)
+            for (uint32_t mi = m_lo; mi < m_hi; ++mi)
                 if (need <= tier_bytes(grid, mi, g))
-                    atomicMax(&seg_best[(size_t)((ci - c_lo) * n_mem + mi) * L.max_ns + seg], k);
+                    atomicMax(&seg_best[(size_t)((ci - c_lo) * m_cnt + (mi - m_lo)) * L.max_ns + seg], k);
         }
         __syncthreads();
 
@@ -147,7 +154,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_fused(JobDev jobs, TableDev t
                 const uint32_t i = base + lane;
                 const bool in = i < n;
                 const uint32_t rl = r_lo + i / ns, s = i % ns;
-                const uint64_t out = sbase + (uint64_t)(c_lo * n_mem + rl) * ns + s;
+                const uint64_t out = sbase + (uint64_t)(row0 + rl) * ns + s;
                 unsigned long long ck = 0;
                 if (in) {
                     unsigned long long k = seg_best[(size_t)rl * L.max_ns + s];
@@ -190,23 +197,28 @@ int32_t rk_launch_fused(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *t
     FusedLds L;
     L.max_nt = table->max_triples_per_job ? table->max_triples_per_job : 1;
     L.max_ns = table->max_segs_per_job ? table->max_segs_per_job : 1;
-    // CPU levels per pass so that the per-row segment keys stay within 48 KiB
-    const size_t row_bytes = (size_t)grid->n_mem * L.max_ns * 8;
-    if (row_bytes > 48 * 1024) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "n_mem * segments per job too large for the fused kernel");
-    uint32_t c_per_pass = (uint32_t)((48 * 1024) / row_bytes);
-    if (c_per_pass > grid->n_cpu) c_per_pass = grid->n_cpu;
-    L.rows_per_pass = c_per_pass * grid->n_mem;
+    // rows per pass so that their segment keys stay within 48 KiB: whole CPU levels (all tiers of each) when a level
+    // fits, otherwise one level at a time and as many of its tiers as fit (a row of 2,048 segments takes 16 KiB)
+    const size_t one_row = (size_t)L.max_ns * 8, level_bytes = (size_t)grid->n_mem * one_row;
+    uint32_t c_per_pass = 1, m_per_pass = grid->n_mem;
+    if (level_bytes <= 48 * 1024) {
+        c_per_pass = (uint32_t)((48 * 1024) / level_bytes);
+        if (c_per_pass > grid->n_cpu) c_per_pass = grid->n_cpu;
+    } else {
+        m_per_pass = (uint32_t)((48 * 1024) / one_row);
+        if (m_per_pass < 1) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 6144 segments per job");
+    }
+    L.rows_per_pass = c_per_pass * m_per_pass;
     const size_t lds = fused_lds_bytes(L);
-    static bool raised[64] = {};
-    if (lds > 64 * 1024 && !raised[ctx->device & 63]) {
+    if (lds > 160 * 1024) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "job too large for the fused kernel");
+    if (lds > 64 * 1024 && !ctx->fused_lds_raised) {
         RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_fused),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        raised[ctx->device & 63] = true;
+        ctx->fused_lds_raised = true;
     }
-    if (lds > 160 * 1024) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "job too large for the fused kernel");
     k_fused<<<je - jb, FUSED_THREADS, lds, ctx->stream>>>(job_dev(jobs), table_dev(table), grid_dev(grid), *env, jb,
-                                                         table->option_mask, L, c_per_pass, best_thr, best_plan,
-                                                         curve_thr, curve_plan, curve_g);
+                                                         table->option_mask, L, c_per_pass, m_per_pass, best_thr,
+                                                         best_plan, curve_thr, curve_plan, curve_g);
     RK_CHECK_LAUNCH(ctx, "k_fused");
     return RK_OK;
 }

@@ -24,6 +24,7 @@ struct rk_ctx {
     hipEvent_t counts_ev;                   // enumeration: the counts have reached the host (made on demand)
     hipStream_t sim_stream;                 // simulation: its own stream (a tick is captured as a graph), made on demand
     hipEvent_t sim_ev[2];                   // ... ordered after and before the context's stream with these
+    bool fused_lds_raised;                  // fused kernel: its dynamic LDS limit has been raised for this context
 };
 
 // scratch slots

@@ -141,8 +141,10 @@ def test_noisy_fit_reaches_the_oracles_minimum(gpu, orc):
     same = np.abs(rel) <= 1e-6
     print(f"noisy data: {int(same.sum())}/{len(rel)} minima equal to the oracle's; others: worst {rel.max():+.2e}, "
           f"best {rel.min():+.2e}; iterations per model {got['iters'].mean():.0f} (max {got['iters'].max()})")
-    assert same.mean() >= 0.6
-    assert rel.max() <= 0.02
+    # observed on this seeded case: 37 of 40 equal, the others between -0.2 % and +0.009 % (a lower value means the
+    # library found a better minimum than the oracle's routine)
+    assert same.mean() >= 0.85
+    assert rel.max() <= 1e-3
 
 
 @pytest.mark.parametrize("n_samples,n_offload", [(7, 3), (24, 6), (40, 10), (64, 12)])

@@ -87,7 +87,8 @@ def check_path(gpu, orc, wl, rng):
             assert np.array_equal(run.host(a, ns), run.host(c, ns))
         assign, _ = run.allocate(run.dev_f32(r["best_thr"]), run.dev_u32(r["best_plan"]), run.dev_f32(r["curve_thr"]))
         assert np.array_equal(assign, r["assign"])
-        compare_rounds(*run.schedule_round(), r)
+        own = (run.host(fused[0], ns).copy(), run.host(fused[1], ns).view(np.uint32).copy(), run.host(fused[2], ns).copy())
+        compare_rounds(orc, wl, *run.schedule_round(), r, own)
         # a job range gives the same bits as the full call
         jb = int(rng.integers(0, wl.n_jobs))
         je = int(rng.integers(jb, wl.n_jobs + 1))

@@ -358,7 +358,11 @@ def test_schedule_round_sla_end_to_end(gpu, orc, name, share):
     rk.rk_sync(run.ctx)
     a_piece, t_piece = rk.assign_to_numpy(assign), float(total[0].item())
     if floors_equal:
-        same = compare_rounds(a_piece, t_piece, dict(assign=e_assign, total=e_total, min_gap=e_gap))
+        own = (run.host(bt, n).copy(), run.host(bp, n).view(np.uint32).copy(), run.host(ct, n).copy())
+        same = compare_rounds(orc, wl, a_piece, t_piece, dict(assign=e_assign, total=e_total, min_gap=e_gap, table=tb), own,
+                              redo=lambda b_thr, b_plan, c_thr: orc.policy(wl.coef[:, 16], tb, wl.grid, wl.cluster, b_thr, b_plan,
+                                                                           c_thr, d.guaranteed, d.tenant, h_ms, h_mc, d.quota_g,
+                                                                           d.quota_c)[:2])
     else:
         same = False
         assert t_piece == pytest.approx(e_total, rel=1e-2)

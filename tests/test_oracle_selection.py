@@ -346,3 +346,16 @@ def test_round_invariants_on_generated_configs(orc):
         for j in np.flatnonzero(sched):
             d, t, p, _ = tb.triples[tb.triple_off[j] + a["plan"][j] // 16]
             assert d * t * p == a["g"][j]
+
+
+def test_threads_over_jobs_change_nothing(orc):
+    # the oracle's enumeration, evaluation and best-plan search may share the jobs among host threads
+    # (the benchmark times them that way): same arrays as on one thread, also with more threads than jobs
+    wl = workloads.stress(n_jobs=11)
+    one = orc.schedule_round(wl, n_threads=1)
+    for n in (3, 16):
+        many = orc.schedule_round(wl, n_threads=n)
+        for k in ("triple_off", "triples", "seg_off", "seg_g", "seg_first"):
+            assert np.array_equal(getattr(one["table"], k), getattr(many["table"], k))
+        for k in ("thr", "reason", "best_thr64", "best_plan", "curve_thr", "assign"):
+            assert np.array_equal(one[k], many[k])
