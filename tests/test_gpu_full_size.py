@@ -9,7 +9,7 @@ calls give.
 
 What-if batch (rounds of 500 jobs on about 512 GPUs): whole rounds through
 rk_schedule_rounds and rk_schedule_rounds_shared against the oracle's rounds.
-RK_WHAT_IF_ROUNDS sets how many of the 256 rounds are compared (default 32)."""
+RK_WHAT_IF_ROUNDS sets how many of the 256 rounds are compared (default: all 256)."""
 import os
 import time
 
@@ -80,7 +80,7 @@ def test_stress_every_job(gpu, orc, capsys):
 def test_what_if_full_rounds(gpu, orc, capsys):
     import paper_2408_08586_amd as rk
     import torch
-    n_rounds = int(os.environ.get("RK_WHAT_IF_ROUNDS", "32"))
+    n_rounds = int(os.environ.get("RK_WHAT_IF_ROUNDS", "256"))
     t0 = time.time()
     rounds = [workloads.what_if(r) for r in range(n_rounds)]
     assert all(w.n_jobs == 500 for w in rounds)
