@@ -241,6 +241,26 @@ int32_t rk_allocate(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *tabl
                     const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
                     rk_assign *assign, float *total);
 
+/* rk_allocate for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit-identical results; the working buffers
+ * (walk steps, per-job state, histograms) are pieces of one 12 MiB array that
+ * lives in the library's image on every device instead of buffers the context
+ * allocates on demand.  The call allocates and frees nothing and copies
+ * nothing.  Limits: (je - jb) * max(longest GPU-count list of a job,
+ * grid->n_cpu) <= RK_STATIC_MAX_STEPS and je - jb <= RK_MAX_JOBS_PER_ROUND,
+ * otherwise RK_ERR_UNSUPPORTED and nothing is launched.  All calls on one
+ * device share that array, whatever their context or stream, and it keeps the
+ * last call's contents (the kernels clear what they need cleared): two calls
+ * that overlap in time on one device race; calls on one stream, or ordered by
+ * events, are fine. */
+#define RK_STATIC_MAX_STEPS 524288u
+int32_t rk_allocate_static(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                           const rk_alloc_grid *grid, const rk_cluster *cluster,
+                           uint32_t job_begin, uint32_t job_end,
+                           const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                           rk_assign *assign, float *total);
+
 /* One scheduling round end to end: enumerate -> evaluate -> best plan ->
  * curves -> greedy allocation, all on the device.  Waits once for the plan
  * counts. assign [device] n_jobs records, total [device] one float. */

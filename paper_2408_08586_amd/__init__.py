@@ -18,13 +18,14 @@ RK_OK, RK_ERR_INVALID_ARG, RK_ERR_CAPACITY, RK_ERR_DEVICE, RK_ERR_UNSUPPORTED = 
 RK_NO_PLAN = 0xFFFFFFFF
 RK_MAX_CPU_LEVELS, RK_MAX_MEM_LEVELS = 64, 16
 RK_MAX_JOBS_PER_ROUND = 12288
+RK_STATIC_MAX_STEPS = 524288
 RK_MAX_TENANTS = 256
 RK_FIT_PARAMS, RK_FIT_MAX_STARTS, RK_FIT_MAX_SAMPLES, RK_FIT_K_MAX = 7, 8, 64, 32.0
 FIT_FIELDS = ("k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_const")
 
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
            "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
-           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared", "rk_place")
+           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared", "rk_place", "rk_allocate_static")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -286,6 +287,13 @@ def rk_allocate(ctx, ref_thr, table, grid, cluster: rk_cluster, job_begin, job_e
     _check(ctx, load_library().rk_allocate(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.byref(cluster),
                                            C.c_uint32(job_begin), C.c_uint32(job_end), _ptr(best_thr),
                                            _ptr(best_plan), _ptr(curve_thr), _ptr(assign), _ptr(total)))
+
+
+def rk_allocate_static(ctx, ref_thr, table, grid, cluster: rk_cluster, job_begin, job_end, best_thr, best_plan,
+                       curve_thr, assign, total):
+    _check(ctx, load_library().rk_allocate_static(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.byref(cluster),
+                                                  C.c_uint32(job_begin), C.c_uint32(job_end), _ptr(best_thr),
+                                                  _ptr(best_plan), _ptr(curve_thr), _ptr(assign), _ptr(total)))
 
 
 def rk_schedule_round(ctx, jobs: Jobs, bounds, grid, env, cluster, assign, total):

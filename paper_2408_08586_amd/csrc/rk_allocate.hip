@@ -1402,9 +1402,29 @@ __global__ __launch_bounds__(FLOOR_THREADS) void k_floors(Ctx X, JobState st, Sl
 }
 
 
+// Scratch of rk_allocate_static: one array in the library's image, so every device the library is loaded on holds
+// its own copy at its own address for as long as the process lives.  The name is a host-side stand-in only: host
+// code uses the address that hipGetSymbolAddress returned for the context's device (rk_ctx::static_scratch).
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)12 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+// Where the working buffers of a call come from: the context's grow-only device buffers (base == nullptr), or
+// consecutive 256-byte aligned pieces of a fixed block (no allocation; a call that needs more fails).
+struct Arena {
+    unsigned char *base;
+    size_t used, cap;
+};
+
 template <typename T>
-int32_t scratch_typed(rk_ctx *ctx, int slot, size_t count, T **out) {
-    return rk_scratch(ctx, slot, count * sizeof(T), reinterpret_cast<void **>(out));
+int32_t scratch_typed(rk_ctx *ctx, Arena &arena, int slot, size_t count, T **out) {
+    if (!arena.base) return rk_scratch(ctx, slot, count * sizeof(T), reinterpret_cast<void **>(out));
+    size_t bytes = count * sizeof(T);
+    bytes = ((bytes ? bytes : 1) + 255) & ~(size_t)255;
+    if (arena.used + bytes > arena.cap)
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "the round needs more than the %zu bytes of static scratch memory", arena.cap);
+    *out = reinterpret_cast<T *>(arena.base + arena.used);
+    arena.used += bytes;
+    return RK_OK;
 }
 
 // *closed: the pass also took the memory step that ends the round
@@ -1458,13 +1478,35 @@ int32_t launch_pass(rk_ctx *ctx, const Ctx &X, const JobState &st, const HullBuf
 
 }  // namespace
 
+// Once per context, with its device current: the address of this device's copy of the static scratch array, and
+// the dynamic LDS limits of the kernels that may need more than the default (large rounds keep per-job state in LDS;
+// the single-workgroup selection adds dynamic to static LDS).  Done here so that no later call has to.
+int32_t rk_allocate_setup(rk_ctx *ctx) {
+    void *p = nullptr;
+    RK_HIP(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    ctx->static_scratch = static_cast<unsigned char *>(p);
+    const void *big[] = {reinterpret_cast<const void *>(k_tail<0>), reinterpret_cast<const void *>(k_tail<1>),
+                         reinterpret_cast<const void *>(k_floors),
+                         reinterpret_cast<const void *>(k_select_small<1, TAIL_KMAX>)};
+    for (const void *f : big) RK_HIP(ctx, hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
+    const void *small[] = {reinterpret_cast<const void *>(k_select_small<0, SMALL_ROUND_JOBS / TAIL_THREADS>),
+                           reinterpret_cast<const void *>(k_select_small<1, SMALL_ROUND_JOBS / TAIL_THREADS>)};
+    for (const void *f : small) RK_HIP(ctx, hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+    return RK_OK;
+}
+
 int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb, const rk_alloc_grid *grid,
                            uint32_t n_rounds, const uint32_t *d_round_off, const rk_cluster *d_clusters,
                            const rk_cluster *one_cluster, uint32_t jb, uint32_t n_jobs, uint32_t max_jobs,
                            uint32_t max_segs_per_job, const float *best_thr, const uint32_t *best_plan,
                            const float *curve_thr, const SlaDev *sla, const FloorsDev *given, const uint32_t *d_jmap,
-                           rk_assign *assign, float *totals) {
+                           rk_assign *assign, float *totals, bool static_scratch) {
     if (n_rounds == 0) return RK_OK;
+    Arena arena = {nullptr, 0, 0};
+    if (static_scratch) {
+        if (!ctx->static_scratch) return rk_fail(ctx, RK_ERR_DEVICE, "the static scratch memory was not set up");
+        arena = Arena{ctx->static_scratch, 0, STATIC_SCRATCH_BYTES};
+    }
     if (d_jmap && (sla || given || jb != 0))
         return rk_fail(ctx, RK_ERR_UNSUPPORTED, "rounds that share jobs take neither floors nor a job range");
     if (max_jobs > RK_MAX_JOBS_PER_ROUND)
@@ -1476,37 +1518,37 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
     H.width = max_segs_per_job > grid->n_cpu ? max_segs_per_job : grid->n_cpu;   // the longest walk of either pass
     if (H.width == 0) H.width = 1;
     const size_t entries = (size_t)H.stride * H.width;
-    if ((rc = scratch_typed(ctx, SL_HULL_KEY, entries, &H.key))) return rc;
-    if ((rc = scratch_typed(ctx, SL_HULL_RAW, entries, &H.raw))) return rc;
-    if ((rc = scratch_typed(ctx, SL_HULL_TGT, entries, &H.tgt))) return rc;
-    if ((rc = scratch_typed(ctx, SL_HULL_DG, entries, &H.dg))) return rc;
-    if ((rc = scratch_typed(ctx, SL_HULL_DC, entries, &H.dc))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_HULL_KEY, entries, &H.key))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_HULL_RAW, entries, &H.raw))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_HULL_TGT, entries, &H.tgt))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_HULL_DG, entries, &H.dg))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_HULL_DC, entries, &H.dc))) return rc;
     JobState st;
     st.blocks_per_round = (max_jobs + JOB_THREADS - 1) / JOB_THREADS;
     if (st.blocks_per_round == 0) st.blocks_per_round = 1;
-    if ((rc = scratch_typed(ctx, SL_ST_GI, (size_t)H.stride, &st.gi))) return rc;
-    if ((rc = scratch_typed(ctx, SL_ST_G, (size_t)H.stride, &st.g))) return rc;
-    if ((rc = scratch_typed(ctx, SL_ST_CI, (size_t)H.stride, &st.ci))) return rc;
-    if ((rc = scratch_typed(ctx, SL_ST_STEP_SLOPE, (size_t)H.stride, &st.step_slope))) return rc;
-    if ((rc = scratch_typed(ctx, SL_ST_STEP_TGT, (size_t)H.stride, &st.step_tgt))) return rc;
-    if ((rc = scratch_typed(ctx, SL_ST_STEP_DG, (size_t)H.stride, &st.step_dg))) return rc;
-    if ((rc = scratch_typed(ctx, SL_ST_FREEG, (size_t)n_rounds * 2, &st.free_g))) return rc;   // [free G | free C] after apply
-    if ((rc = scratch_typed(ctx, SL_ST_FREEC, (size_t)n_rounds + ((size_t)n_rounds + 1) / 2, &st.free_c))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_GI, (size_t)H.stride, &st.gi))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_G, (size_t)H.stride, &st.g))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_CI, (size_t)H.stride, &st.ci))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_STEP_SLOPE, (size_t)H.stride, &st.step_slope))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_STEP_TGT, (size_t)H.stride, &st.step_tgt))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_STEP_DG, (size_t)H.stride, &st.step_dg))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_FREEG, (size_t)n_rounds * 2, &st.free_g))) return rc;   // [free G | free C] after apply
+    if ((rc = scratch_typed(ctx, arena, SL_ST_FREEC, (size_t)n_rounds + ((size_t)n_rounds + 1) / 2, &st.free_c))) return rc;
     st.cpu_steps = reinterpret_cast<uint32_t *>(st.free_c + n_rounds);
-    if ((rc = scratch_typed(ctx, SL_ST_PARTIAL, (size_t)n_rounds * st.blocks_per_round * 2, &st.partial))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_PARTIAL, (size_t)n_rounds * st.blocks_per_round * 2, &st.partial))) return rc;
     st.fl_gi = nullptr; st.fl_ci = nullptr; st.waits = nullptr; st.cap0 = nullptr;
     if (given) {
         st.fl_gi = given->gi; st.fl_ci = given->ci; st.waits = given->state; st.cap0 = given->cap0;
     } else if (sla) {
-        if ((rc = scratch_typed(ctx, SL_FL_GI, (size_t)H.stride, &st.fl_gi))) return rc;
-        if ((rc = scratch_typed(ctx, SL_FL_CI, (size_t)H.stride, &st.fl_ci))) return rc;
-        if ((rc = scratch_typed(ctx, SL_FL_WAITS, (size_t)H.stride, &st.waits))) return rc;
-        if ((rc = scratch_typed(ctx, SL_FL_CAP0, (size_t)n_rounds * 2, &st.cap0))) return rc;
+        if ((rc = scratch_typed(ctx, arena, SL_FL_GI, (size_t)H.stride, &st.fl_gi))) return rc;
+        if ((rc = scratch_typed(ctx, arena, SL_FL_CI, (size_t)H.stride, &st.fl_ci))) return rc;
+        if ((rc = scratch_typed(ctx, arena, SL_FL_WAITS, (size_t)H.stride, &st.waits))) return rc;
+        if ((rc = scratch_typed(ctx, arena, SL_FL_CAP0, (size_t)n_rounds * 2, &st.cap0))) return rc;
     }
     Hist hist;
     const size_t hist_bins = (size_t)n_rounds * 4 * BINS;
-    if ((rc = scratch_typed(ctx, SL_HIST_G, hist_bins, &hist.g))) return rc;
-    if ((rc = scratch_typed(ctx, SL_HIST_C, hist_bins, &hist.c))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_HIST_G, hist_bins, &hist.g))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_HIST_C, hist_bins, &hist.c))) return rc;
 
     Ctx X;
     X.ref_thr = ref_thr; X.tb = tb; X.grid = grid_dev(grid); X.jb = jb; X.jmap = d_jmap;
@@ -1518,26 +1560,7 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
 
     const uint32_t mj = max_jobs ? ((max_jobs + 1u) & ~1u) : 2u;
     const size_t lds = (size_t)mj * (2 + 2 + 2 + 2 + 4);
-    static bool raised[64] = {};
-    if (lds > 48 * 1024 && !raised[ctx->device & 63]) {
-        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_tail<0>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
-        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_tail<1>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
-        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_floors),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
-        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_select_small<1, TAIL_KMAX>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
-        raised[ctx->device & 63] = true;
-    }
-    static bool raised_small[64] = {};
-    if (mj <= SMALL_ROUND_JOBS && !raised_small[ctx->device & 63]) {   // static + dynamic LDS go beyond 64 KiB
-        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_select_small<0, SMALL_ROUND_JOBS / TAIL_THREADS>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
-        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_select_small<1, SMALL_ROUND_JOBS / TAIL_THREADS>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
-        raised_small[ctx->device & 63] = true;
-    }
+    // (the kernels' dynamic LDS limits were raised when the context was made: rk_allocate_setup)
     hipStream_t s = ctx->stream;
     // Histograms start at zero: the first walk kernel clears them for both passes on its way (fill code, no
     // memset, so the sequence can be captured in a graph).  Rounds large enough to use them have jobs, so that
@@ -1562,10 +1585,10 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
     return RK_OK;
 }
 
-extern "C" int32_t rk_allocate(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
-                               const rk_alloc_grid *grid, const rk_cluster *cluster, uint32_t jb, uint32_t je,
-                               const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
-                               rk_assign *assign, float *total) {
+static int32_t allocate_one_round(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                                  const rk_alloc_grid *grid, const rk_cluster *cluster, uint32_t jb, uint32_t je,
+                                  const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                                  rk_assign *assign, float *total, bool static_scratch) {
     if (!ctx) return RK_ERR_INVALID_ARG;
     int32_t rc;
     if ((rc = rk_check_table(ctx, table, jb, je))) return rc;
@@ -1576,10 +1599,32 @@ extern "C" int32_t rk_allocate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
     if (!(cluster->host_mem_gb >= 0.f)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "host_mem_gb negative or NaN");
     if (table->max_segs_per_job > 32767u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 32767 segments per job");
+    if (static_scratch) {
+        const uint64_t width = table->max_segs_per_job > grid->n_cpu ? table->max_segs_per_job : grid->n_cpu;
+        if ((uint64_t)(je - jb) * width > RK_STATIC_MAX_STEPS)
+            return rk_fail(ctx, RK_ERR_UNSUPPORTED, "%u jobs x %llu amounts per job: rk_allocate_static takes up to %u",
+                           je - jb, (unsigned long long)width, RK_STATIC_MAX_STEPS);
+    }
     RK_HIP(ctx, hipSetDevice(ctx->device));
     return rk_launch_allocate(ctx, ref_thr, table_dev(table), grid, 1, nullptr, nullptr, cluster, jb, je - jb, je - jb,
                               table->max_segs_per_job, best_thr, best_plan, curve_thr, nullptr, nullptr, nullptr, assign,
-                              total);
+                              total, static_scratch);
+}
+
+extern "C" int32_t rk_allocate(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                               const rk_alloc_grid *grid, const rk_cluster *cluster, uint32_t jb, uint32_t je,
+                               const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                               rk_assign *assign, float *total) {
+    return allocate_one_round(ctx, ref_thr, table, grid, cluster, jb, je, best_thr, best_plan, curve_thr, assign, total,
+                              false);
+}
+
+extern "C" int32_t rk_allocate_static(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                                      const rk_alloc_grid *grid, const rk_cluster *cluster, uint32_t jb, uint32_t je,
+                                      const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                                      rk_assign *assign, float *total) {
+    return allocate_one_round(ctx, ref_thr, table, grid, cluster, jb, je, best_thr, best_plan, curve_thr, assign, total,
+                              true);
 }
 
 int32_t rk_check_sla(rk_ctx *ctx, const rk_sla *sla, bool need_request) {
@@ -1614,5 +1659,5 @@ extern "C" int32_t rk_allocate_sla(rk_ctx *ctx, const float *ref_thr, const rk_p
     if (je > jb) S = SlaDev{sla->guaranteed, sla->tenant, min_seg, min_c, sla->n_tenants, sla->quota_g, sla->quota_c};
     return rk_launch_allocate(ctx, ref_thr, table_dev(table), grid, 1, nullptr, nullptr, cluster, jb, je - jb, je - jb,
                               table->max_segs_per_job, best_thr, best_plan, curve_thr, je > jb ? &S : nullptr, nullptr,
-                              nullptr, assign, total);
+                              nullptr, assign, total, false);
 }

@@ -106,6 +106,11 @@ int32_t rk_create(rk_ctx **out, int32_t device_id, void *hip_stream) {
         free(ctx);
         return RK_ERR_DEVICE;
     }
+    if (rk_allocate_setup(ctx) != RK_OK) {
+        (void)hipHostFree(ctx->h_pinned);
+        free(ctx);
+        return RK_ERR_DEVICE;
+    }
     *out = ctx;
     return RK_OK;
 }

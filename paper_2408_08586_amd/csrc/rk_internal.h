@@ -25,6 +25,7 @@ struct rk_ctx {
     hipStream_t sim_stream;                 // simulation: its own stream (a tick is captured as a graph), made on demand
     hipEvent_t sim_ev[2];                   // ... ordered after and before the context's stream with these
     bool fused_lds_raised;                  // fused kernel: its dynamic LDS limit has been raised for this context
+    unsigned char *static_scratch;          // this device's copy of the static scratch array (rk_allocate_static)
 };
 
 // scratch slots
@@ -124,7 +125,12 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
                            const rk_cluster *one_cluster, uint32_t jb, uint32_t n_jobs, uint32_t max_jobs,
                            uint32_t max_segs_per_job, const float *best_thr, const uint32_t *best_plan,
                            const float *curve_thr, const SlaDev *sla, const FloorsDev *given, const uint32_t *d_jmap,
-                           rk_assign *assign, float *totals);
+                           rk_assign *assign, float *totals, bool static_scratch = false);
+// static_scratch: the working buffers are pieces of the library's static device array (nothing is allocated; a
+// round that needs more than the array holds is refused) instead of the context's grow-only buffers.
+// Once per context, device current: finds this device's copy of that array and raises the LDS limits of the
+// allocation kernels.
+int32_t rk_allocate_setup(rk_ctx *ctx);
 // minimum demands of the guaranteed jobs of [jb, je)
 int32_t rk_launch_min_res(rk_ctx *ctx, const TableDev &tb, const rk_alloc_grid *grid, uint32_t jb, uint32_t je,
                           const float *best_thr, const rk_sla *sla, int32_t *min_seg, uint32_t *min_c,
