@@ -38,6 +38,15 @@ MEASURED_FUSED_VALU = {"912085237e801deb": 47817614}
 # 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz: vector instructions per lane and second (an FMA is one of them,
 # so this is half of the 78.6 TFLOP/s of unpacked FP32 and a quarter of the 157.3 TFLOP/s with packed FP32)
 VALU_PEAK_LANE_INSTR = 256 * 4 * 16 * 2.4e9
+# log2 / exp2 / reciprocal issue at a quarter of that rate
+TRANS_PEAK_LANE_INSTR = VALU_PEAK_LANE_INSTR / 4
+# Arithmetic the model needs once everything shared is computed once (counted from the formulas of Sec. 4 as the fused
+# kernel factors them; float32 operations / quarter-rate operations, a correctly rounded division = 10 + 1):
+#   per triple:                      terms shared by its 16 options (times, volumes, two overlaps, activations)
+#   per plan without offload:        memory verdict + optimizer term + throughput
+#   per triple with offload allowed: PCIe term, one overlap, host bytes, four memory verdicts
+#   per (CPU level, such a triple):  swap overlap, two throughputs, keys, tier tests
+ALGO_OPS = {"triple": (120, 18), "plain_plan": (20, 2.25), "offload_triple": (90, 14), "offload_level": (34, 8)}
 
 
 def source_digest(sources):
@@ -72,40 +81,66 @@ def build_workload(name):
     raise SystemExit(f"unknown workload {name}")
 
 
-def cpu_baseline(wl, sample_jobs, threads):
-    """The oracle, as it stands, on the first `sample_jobs` jobs of the workload."""
+def oracle_round(oracle, wl, threads):
+    """One whole round of the oracle, as it stands, on `threads` host threads (enumeration, evaluation and best-plan
+    search share the jobs among them; curves and greedy are plain loops on one).  Returns (candidates, seconds per stage)."""
+    t0 = time.perf_counter()
+    tb = oracle.enumerate_plans(wl.ints, wl.bounds, n_threads=threads)
+    t1 = time.perf_counter()
+    thr, _ = oracle.eval_jobs(wl.coef, wl.ints, wl.bounds, tb, wl.grid, wl.env, want_reason=False, n_threads=threads)
+    t2 = time.perf_counter()
+    bt64, bp = oracle.best_plan(tb, wl.grid, thr, n_threads=threads)
+    bt = bt64.astype(np.float32)
+    ct, cp, cg = oracle.curves(tb, wl.grid, bt, bp)
+    t3 = time.perf_counter()
+    oracle.greedy(wl.coef[:, 16], tb, wl.grid, wl.cluster, bt, bp, ct)
+    t4 = time.perf_counter()
+    return thr.size, {"enumerate": t1 - t0, "evaluate": t2 - t1, "best_plan+curves": t3 - t2, "greedy": t4 - t3,
+                      "round": t4 - t0}
+
+
+def cpu_baseline(wl, sample_jobs):
+    """The oracle, as it stands, timed on this machine's host cores: the benchmark's workload (a stated sample of its
+    jobs) and the other configurations, each on all the cores this process may use and on one."""
     import oracle
     import workloads
-    sub = wl.subset(np.arange(min(sample_jobs, wl.n_jobs)))
-    frac = sub.n_jobs / wl.n_jobs
-    sub.cluster = workloads.Cluster(max(1, int(wl.cluster.G * frac)), max(1, int(wl.cluster.C * frac)),
-                                    wl.cluster.host_mem_gb * frac)
-    t0 = time.perf_counter()
-    tb = oracle.enumerate_plans(sub.ints, sub.bounds)
-    t1 = time.perf_counter()
-    thr, _ = oracle.eval_jobs(sub.coef, sub.ints, sub.bounds, tb, sub.grid, sub.env, want_reason=False,
-                              n_threads=threads)
-    t2 = time.perf_counter()
-    bt64, bp = oracle.best_plan(tb, sub.grid, thr)
-    bt = bt64.astype(np.float32)
-    ct, cp, cg = oracle.curves(tb, sub.grid, bt, bp)
-    t3 = time.perf_counter()
-    oracle.greedy(sub.coef[:, 16], tb, sub.grid, sub.cluster, bt, bp, ct)
-    t4 = time.perf_counter()
-    n = thr.size
-    # one thread, on a tenth of the sample, for the per-core figure
-    one = sub.subset(np.arange(max(1, sub.n_jobs // 10)))
-    tb1 = oracle.enumerate_plans(one.ints, one.bounds)
-    t5 = time.perf_counter()
-    thr1, _ = oracle.eval_jobs(one.coef, one.ints, one.bounds, tb1, one.grid, one.env, want_reason=False, n_threads=1)
-    t6 = time.perf_counter()
-    return {"value": n / (t4 - t0), "unit": "candidates/s", "cores": threads, "kind": "oracle",
-            "round_ms": (t4 - t0) * 1e3,
-            "single_thread_eval_candidates_per_s": thr1.size / (t6 - t5),
-            "sample": f"first {sub.n_jobs} jobs of the workload ({n} candidates), capacities scaled by {frac:g}; "
-                      f"evaluation on {threads} threads, the other stages on 1",
-            "seconds": {"enumerate": t1 - t0, "evaluate": t2 - t1, "best_plan+curves": t3 - t2, "greedy": t4 - t3},
-            "eval_only_candidates_per_s": n / (t2 - t1)}
+    host_cores = oracle.host_cores()
+    # the box gives one GPU's share of its cores to a job: 16 threads (OMP_NUM_THREADS), whatever the machine has
+    threads = max(1, min(host_cores, int(os.environ.get("OMP_NUM_THREADS", "16"))))
+
+    def sample(w, n):
+        sub = w.subset(np.arange(min(n, w.n_jobs)))
+        frac = sub.n_jobs / w.n_jobs
+        sub.cluster = workloads.Cluster(max(1, int(w.cluster.G * frac)), max(1, int(w.cluster.C * frac)),
+                                        w.cluster.host_mem_gb * frac)
+        return sub
+
+    def both(w, n_all, n_one):
+        a, b = sample(w, n_all), sample(w, n_one)
+        n_a, s_a = oracle_round(oracle, a, threads)
+        n_b, s_b = oracle_round(oracle, b, 1)
+        return {"all_cores": {"jobs": a.n_jobs, "candidates": n_a, "candidates_per_s": n_a / s_a["round"],
+                              "round_ms": s_a["round"] * 1e3, "eval_only_candidates_per_s": n_a / s_a["evaluate"],
+                              "seconds": s_a},
+                "one_thread": {"jobs": b.n_jobs, "candidates": n_b, "candidates_per_s": n_b / s_b["round"],
+                               "round_ms": s_b["round"] * 1e3, "eval_only_candidates_per_s": n_b / s_b["evaluate"],
+                               "seconds": s_b}}
+
+    main = both(wl, sample_jobs, max(1, sample_jobs // 8))
+    others = {}
+    for name, w, n_all, n_one in (("tiny", workloads.tiny(), 8, 8), ("paper_scale", workloads.paper_scale(), 64, 64),
+                                  ("large", workloads.large(), 1000, 250), ("what_if[0]", workloads.what_if(0), 500, 250)):
+        if w.name != wl.name:
+            others[name] = both(w, n_all, n_one)
+    a = main["all_cores"]
+    return {"value": a["candidates_per_s"], "unit": "candidates/s", "cores": threads, "host_cores": host_cores,
+            "kind": "oracle", "round_ms": a["round_ms"],
+            "sample": f"first {a['jobs']} of the workload's {wl.n_jobs} jobs ({a['candidates']} candidates), capacities "
+                      f"scaled to the sample; whole path (enumerate, evaluate, best plan, curves, greedy); enumeration, "
+                      f"evaluation and best-plan search on {threads} threads, curves and greedy on 1; one-thread figures "
+                      f"on the first {main['one_thread']['jobs']} jobs",
+            "seconds": a["seconds"], "eval_only_candidates_per_s": a["eval_only_candidates_per_s"],
+            "one_thread": main["one_thread"], "other_configurations": others}
 
 
 def what_if_batch(rk, ctx, dev, n_rounds):
@@ -356,7 +391,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="stress")
     ap.add_argument("--chunks", type=int, default=3, help="job chunks streamed through one candidate buffer")
-    ap.add_argument("--cpu-sample-jobs", type=int, default=4000)
+    ap.add_argument("--cpu-sample-jobs", type=int, default=4000,
+                    help="jobs of the workload the oracle is timed on (4,000 jobs of the stress workload: about 2.7e8 "
+                         "candidates, 2.2 GB of float64 throughputs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-what-if", action="store_true")
     ap.add_argument("--no-place", action="store_true", help="skip the node-level placement")
@@ -385,6 +422,14 @@ def main():
     cluster = rk.make_cluster(wl.cluster)
     n_rows = len(wl.grid.cpu_levels) * len(wl.grid.mem_levels_gb)
 
+    # host <-> device copies of a round's inputs and outputs, apart from the kernels (inputs stay resident afterwards)
+    torch.cuda.synchronize()
+    h2d = []
+    for _ in range(5):
+        a = time.perf_counter()
+        jobs = rk.Jobs(wl.coef, wl.ints, dev)
+        torch.cuda.synchronize()
+        h2d.append((time.perf_counter() - a) * 1e3)
     table = rk.enumerate_to_table(ctx, jobs, bounds, dev)      # sizes the buffers; enumeration is re-run per step
     J = wl.n_jobs
     n_chunks = max(1, min(args.chunks, J))
@@ -492,6 +537,12 @@ def main():
             lat_cached.append((time.perf_counter() - a) * 1e3)
     lat_cached = np.array(lat_cached)
 
+    d2h = []
+    for _ in range(5):
+        a = time.perf_counter()
+        rk.assign_to_numpy(assign)
+        d2h.append((time.perf_counter() - a) * 1e3)
+
     # roofline of the dominant kernel (algorithmic bytes per launch / average launch duration)
     cand_per_launch = n_cand / n_chunks
     seg_per_launch = n_seg / n_chunks
@@ -507,6 +558,10 @@ def main():
     traffic = None
     if args.workload == "stress" and n_chunks == 3:
         traffic = MEASURED_TRAFFIC.get(digest, {}).get("k_eval" if dom == "eval" else "k_best_plan")
+        if traffic is None:
+            print(f"bench.py: the evaluation kernels' sources (digest {digest}) have changed since the HBM counters of "
+                  f"profiles/hbm_traffic_stress.txt were taken: roofline.traffic is null until they are taken again",
+                  file=sys.stderr)
 
     out = {
         "metric": "candidate plan evaluations/sec (whole path: enumerate + evaluate + best plan + curves + greedy), 1 GPU",
@@ -519,7 +574,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "k_eval" if dom == "eval" else "k_best_plan",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": bytes_eval if dom == "eval" else bytes_best,
-                     "traffic": traffic, "kernel_source_digest": digest},
+                     "traffic": traffic, "traffic_source": "profiles/hbm_traffic_stress.txt (rocprofv3 --pmc FETCH_SIZE / "
+                                                            "WRITE_SIZE, scaled by a plain copy's counters)",
+                     "kernel_source_digest": digest},
         "kernels": {"timed_region_avg_launch_ms": hot_avg_ms,
                     "stage_pass": "separate pass after the timed region, events around every call",
                     "avg_launch_ms": avg_ms, "per_step_ms": per_step_ms,
@@ -533,6 +590,9 @@ def main():
                                                     "min": float(lat_cached.min()), "median": float(np.median(lat_cached)),
                                                     "max": float(lat_cached.max())}},
     }
+    out["transfers_ms"] = {"h2d_job_descriptors": float(np.median(h2d)), "h2d_bytes": int(wl.coef.nbytes + wl.ints.nbytes),
+                           "d2h_assignment": float(np.median(d2h)), "d2h_bytes": int(J * 20),
+                           "note": "pageable host arrays through torch; not part of any timed region"}
     # the fused kernel (evaluation + best plan + curves without the candidate tensor): bound by the vector ALUs
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(max(5, args.steps) + 2)]
     for a, b in ev:
@@ -542,16 +602,37 @@ def main():
     torch.cuda.synchronize()
     fused_ms = float(np.median([a.elapsed_time(b) for a, b in ev[2:]]))
     n_cpu = len(wl.grid.cpu_levels)
-    unique = table.n_triples * 8 * (1 + n_cpu)      # plans without offload once, offload plans once per CPU level
+    # plans without offload once (8 per triple), the 4 offload plans that ZeRO stage >= 2 allows once per CPU level;
+    # memory tiers only mask
+    nt_all = table.n_triples
+    unique = nt_all * (8 + 4 * n_cpu)
     fd = source_digest(FUSED_SOURCES)
     valu = MEASURED_FUSED_VALU.get(fd) if args.workload == "stress" else None
+    if args.workload == "stress" and valu is None:
+        print(f"bench.py: no instruction count on record for the fused kernel's sources (digest {fd}); its issue-slot "
+              f"figure is reported as null until profiles/valu_stress.txt is taken again", file=sys.stderr)
+    ops = sum(ALGO_OPS[k][0] * n for k, n in (("triple", nt_all), ("plain_plan", 8 * nt_all), ("offload_triple", nt_all),
+                                              ("offload_level", n_cpu * nt_all)))
+    trans = sum(ALGO_OPS[k][1] * n for k, n in (("triple", nt_all), ("plain_plan", 8 * nt_all), ("offload_triple", nt_all),
+                                                ("offload_level", n_cpu * nt_all)))
+    sec = fused_ms * 1e-3
     out["fused"] = {"entry": "rk_job_curves (k_fused)", "ms": fused_ms,
-                    "nominal_candidates_per_s": n_cand / (fused_ms * 1e-3),
-                    "unique_evaluations": unique, "unique_evaluations_per_s": unique / (fused_ms * 1e-3),
+                    "nominal_candidates_per_s": n_cand / sec,
+                    "unique_evaluations": unique, "unique_evaluations_per_s": unique / sec,
+                    # algorithmic arithmetic against the vector-ALU ceilings: issue slots the model's own operations
+                    # need (a quarter-rate operation takes four) over the slots the chip has in that time
+                    "roofline_algorithmic": {"bound": "alu", "unit": "lane-operations/s",
+                                             "float_ops_per_launch": ops, "quarter_rate_ops_per_launch": trans,
+                                             "float_ops_per_s": ops / sec, "quarter_rate_ops_per_s": trans / sec,
+                                             "peak_float": VALU_PEAK_LANE_INSTR, "peak_quarter_rate": TRANS_PEAK_LANE_INSTR,
+                                             "frac_quarter_rate": trans / sec / TRANS_PEAK_LANE_INSTR,
+                                             "frac": (ops + 4 * trans) / sec / VALU_PEAK_LANE_INSTR},
+                    # every vector instruction the kernel issues (address arithmetic, keys and LDS traffic included)
                     "roofline": {"bound": "alu", "unit": "lane-instructions/s", "peak": VALU_PEAK_LANE_INSTR,
-                                 "achieved": None if valu is None else valu * 64 / (fused_ms * 1e-3),
-                                 "frac": None if valu is None else valu * 64 / (fused_ms * 1e-3) / VALU_PEAK_LANE_INSTR,
-                                 "valu_wave_instructions_per_launch": valu, "kernel_source_digest": fd}}
+                                 "achieved": None if valu is None else valu * 64 / sec,
+                                 "frac": None if valu is None else valu * 64 / sec / VALU_PEAK_LANE_INSTR,
+                                 "valu_wave_instructions_per_launch": valu, "kernel_source_digest": fd,
+                                 "count_source": "profiles/valu_stress.txt"}}
     if not args.no_place:
         rk.rk_schedule_round(ctx, jobs, bounds, grid, env, cluster, assign, total)
         out["placement"] = placement(rk, ctx, dev, wl, assign, max(5, args.steps))
@@ -565,8 +646,7 @@ def main():
     if not args.no_what_if:
         out["what_if"] = what_if_batch(rk, ctx, dev, args.what_if_rounds)
     if not args.no_cpu_baseline:
-        threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
-        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_jobs, threads)
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_jobs)
     rk.rk_destroy(ctx)
     print(json.dumps(out))
 
