@@ -317,4 +317,43 @@ def place(assign, n_nodes, gpus_per_node, cpus_per_node, mem_per_node_gb):
     return place_off, entries[:int(place_off[J])].copy(), status
 
 
+def eval_one_placed(coef_row, ints_row, bounds, env, d, t, p, z, gc, off, c, host_bytes, parts, v=0):
+    """One candidate on a placement: parts = GPUs on the consecutive nodes the job sits on."""
+    cf = np.ascontiguousarray(coef_row, dtype=np.float32)
+    it = np.ascontiguousarray(ints_row, dtype=np.uint32)
+    parts = np.ascontiguousarray(parts, dtype=np.uint32)
+    assert int(parts.sum()) == d * t * p
+    terms = np.zeros(N_TERMS, np.float64)
+    b, e = _bounds(bounds), _env(env)
+    lib().ork_eval_one_placed.restype = C.c_uint32
+    reason = lib().ork_eval_one_placed(_p(cf), _p(it), C.byref(b), C.byref(e), C.c_uint32(d), C.c_uint32(t),
+                                       C.c_uint32(p), C.c_uint32(v), C.c_uint32(z), C.c_uint32(gc), C.c_uint32(off),
+                                       C.c_uint32(c), C.c_float(host_bytes), C.c_uint32(len(parts)), _p(parts), _p(terms))
+    return int(reason), dict(zip(TERMS, terms.tolist()))
+
+
+def place_plans(coef, ints, bounds, table, grid, env, best_thr, assign, n_nodes, gpus_per_node, cpus_per_node,
+                mem_per_node_gb, min_seg=None):
+    """Placement that feeds the plan -> (placed records, place_off, entries, status, total)."""
+    coef = np.ascontiguousarray(coef, dtype=np.float32)
+    ints = np.ascontiguousarray(ints, dtype=np.uint32)
+    best_thr = np.ascontiguousarray(best_thr, dtype=np.float32)
+    assign = np.ascontiguousarray(assign, dtype=ASSIGN_DTYPE)
+    J = assign.size
+    gh = _GridHolder(grid)
+    ms = None if min_seg is None else np.ascontiguousarray(min_seg, dtype=np.int32)
+    out = np.zeros(J, ASSIGN_DTYPE)
+    place_off = np.zeros(J + 1, np.uint32)
+    entries = np.zeros(max(int(assign["g"].astype(np.uint64).sum()), 1), PLACE_DTYPE)
+    status = np.zeros(J, np.uint32)
+    total = C.c_double(0)
+    b, e = _bounds(bounds), _env(env)
+    rc = lib().ork_place_plans(C.c_uint32(J), _p(coef), _p(ints), C.byref(b), C.byref(table.c), C.byref(gh.c), C.byref(e),
+                               _p(best_thr), _p(assign), _p(ms), C.c_uint32(n_nodes), C.c_uint32(gpus_per_node),
+                               C.c_uint32(cpus_per_node), C.c_float(mem_per_node_gb), _p(out), _p(place_off), _p(entries),
+                               _p(status), C.byref(total))
+    assert rc == 0, "the records are not an allocation on this table and grid"
+    return out, place_off, entries[:int(place_off[J])].copy(), status, total.value
+
+
 from . import simulator  # noqa: E402

@@ -55,6 +55,30 @@ void bandwidths(const ork_env *env, uint32_t d, uint32_t t, uint32_t p,
     *B_pp = bx;
 }
 
+/* The same rule for a job whose GPUs are known: parts[i] GPUs on the i-th node
+ * of its placement, in placement order.  Ranks are laid over these GPU slots
+ * with tensor-parallel ranks adjacent, then data-parallel, then pipeline
+ * stages.  A communication group uses the intra-node links only if all its
+ * ranks landed on one node (Sec. 4.1: the bottleneck bandwidth decides), which
+ * for groups of w adjacent-block ranks means that every node boundary inside
+ * the job falls on a multiple of w: w = t for tensor parallelism, w = t*d for
+ * data parallelism (its groups interleave over a whole pipeline stage);
+ * pipeline neighbours share a node only when the whole job does. */
+void bandwidths_placed(const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t n_parts,
+                       const uint32_t *parts, double *B_dp, double *B_tp, double *B_pp) {
+    const double bi = env->B_intra, bx = env->B_inter;
+    bool tp_in = true, dp_in = true;
+    uint64_t edge = 0;
+    for (uint32_t i = 0; i + 1 < n_parts; ++i) {          /* the boundaries between consecutive parts */
+        edge += parts[i];
+        if (edge % t != 0) tp_in = false;
+        if (edge % ((uint64_t)t * d) != 0) dp_in = false;
+    }
+    *B_tp = tp_in ? bi : bx;
+    *B_dp = dp_in ? bi : bx;
+    *B_pp = (n_parts <= 1) ? bi : bx;
+}
+
 /* GPU and host memory of a plan, float32, one rounding per operation, in
  * exactly this order.  The paper leaves the estimate to the training
  * frameworks (Sec. 6); this is the mixed-precision Adam accounting of the
@@ -134,7 +158,7 @@ enum { TH_BWD, TH_SYNC, TH_OPT, TH_OPT_OFF, TH_OFF, TH_SWAP, TH_CONST, N_TH };
 uint32_t eval_candidate_th(const float *cf, const uint32_t *in_job, const ork_bounds *bounds,
                            const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t v, uint32_t z,
                            uint32_t gc, uint32_t off, uint32_t c, float host_bytes, const double *th,
-                           double *x) {
+                           double *x, uint32_t n_parts = 0, const uint32_t *parts = nullptr) {
     /* the plan's micro-batch size is the job's times 2^v */
     const uint32_t in[N_INT] = {in_job[LAYERS], in_job[GBATCH], in_job[MBATCH] << v};
     for (int i = 0; i < ORK_N_TERMS; ++i) x[i] = 0.0;
@@ -161,7 +185,8 @@ uint32_t eval_candidate_th(const float *cf, const uint32_t *in_job, const ork_bo
     const double V_tp = (t > 1) ? eb * 4.0 * 2.0 * (t - 1.0) * b * s * h * l / ((double)d * t) : 0.0;
     const double V_pp = (p > 1) ? eb * 2.0 * p * b * s * h / ((double)d * t) : 0.0;
     double B_dp, B_tp, B_pp;
-    bandwidths(env, d, t, p, &B_dp, &B_tp, &B_pp);
+    if (parts) bandwidths_placed(env, d, t, p, n_parts, parts, &B_dp, &B_tp, &B_pp);   /* the job's actual nodes */
+    else bandwidths(env, d, t, p, &B_dp, &B_tp, &B_pp);                                 /* packed placement */
     const double T_dp = V_dp / B_dp, T_tp = V_tp / B_tp, T_pp = V_pp / B_pp;
 
     /* computation + communication; the accumulation form reduces to the 3D
@@ -201,9 +226,10 @@ uint32_t eval_candidate_th(const float *cf, const uint32_t *in_job, const ork_bo
 
 uint32_t eval_candidate(const float *cf, const uint32_t *in, const ork_bounds *bounds,
                         const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t v, uint32_t z,
-                        uint32_t gc, uint32_t off, uint32_t c, float host_bytes, double *x) {
+                        uint32_t gc, uint32_t off, uint32_t c, float host_bytes, double *x,
+                        uint32_t n_parts = 0, const uint32_t *parts = nullptr) {
     const double th[N_TH] = {cf[K_BWD], cf[K_SYNC], cf[K_OPT], cf[K_OPT_OFF], cf[K_OFF], cf[K_SWAP], cf[K_CONST]};
-    return eval_candidate_th(cf, in, bounds, env, d, t, p, v, z, gc, off, c, host_bytes, th, x);
+    return eval_candidate_th(cf, in, bounds, env, d, t, p, v, z, gc, off, c, host_bytes, th, x, n_parts, parts);
 }
 
 int greedy_from(uint32_t n_jobs, const float *ref_thr, const ork_table *tb, const ork_grid *grid,
@@ -261,6 +287,45 @@ int best_plan_impl(const ork_table *tb, const ork_grid *grid, uint32_t job_begin
     for (auto &th : pool) th.join();
     return 0;
 }
+
+/* Free resources of the nodes and one job's first fit over them in node order
+ * (Sec. 5.2, Algorithm 1, ScheduleJob): on each node the most GPUs k, up to
+ * what the job still lacks, for which ceil(c*k/g) CPUs and mem*k/g GiB are free
+ * there; the part is booked with floor(c*(done+k)/g) - floor(c*done/g) CPUs. */
+struct NodeState {
+    std::vector<uint32_t> freeG, freeC;
+    std::vector<float> freeM;
+    NodeState(uint32_t n, uint32_t g, uint32_t c, float m) : freeG(n, g), freeC(n, c), freeM(n, m) {}
+    /* true and the parts when all g GPUs are found; nothing is booked */
+    bool first_fit(uint32_t g, uint32_t c, float mem, std::vector<ork_place_entry> &parts) const {
+        parts.clear();
+        uint32_t done = 0;
+        for (uint32_t n = 0; n < freeG.size() && done < g; ++n) {
+            uint32_t k = std::min(freeG[n], g - done);
+            for (; k > 0; --k) {                      /* the most GPUs whose CPUs and memory are free here */
+                const uint64_t cpus = ((uint64_t)c * k + g - 1) / g;
+                const float m = (mem * (float)k) / (float)g;
+                if (cpus <= freeC[n] && m <= freeM[n]) break;
+            }
+            if (k == 0) continue;
+            ork_place_entry e;
+            e.node = n;
+            e.g = k;
+            e.c = (uint32_t)((uint64_t)c * (done + k) / g - (uint64_t)c * done / g);
+            e.mem_gb = (mem * (float)k) / (float)g;
+            parts.push_back(e);
+            done += k;
+        }
+        return done == g;
+    }
+    void book(const std::vector<ork_place_entry> &parts) {
+        for (const ork_place_entry &e : parts) {
+            freeG[e.node] -= e.g;
+            freeC[e.node] -= e.c;
+            freeM[e.node] = freeM[e.node] - e.mem_gb;
+        }
+    }
+};
 
 }  // namespace
 
@@ -350,6 +415,16 @@ uint32_t ork_eval_one(const float *coef17, const uint32_t *ints3, const ork_boun
                       const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t v, uint32_t z,
                       uint32_t gc, uint32_t off, uint32_t c, float host_bytes, double *terms) {
     return eval_candidate(coef17, ints3, bounds, env, d, t, p, v, z, gc, off, c, host_bytes, terms);
+}
+
+/* One candidate whose GPUs are parts[0..n_parts) on consecutive nodes of its
+ * placement (sum = d*t*p): the bandwidth of every communication group follows
+ * where its ranks landed.  Pinned: hand cases of the bandwidth classes. */
+uint32_t ork_eval_one_placed(const float *coef17, const uint32_t *ints3, const ork_bounds *bounds,
+                             const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t v, uint32_t z,
+                             uint32_t gc, uint32_t off, uint32_t c, float host_bytes, uint32_t n_parts,
+                             const uint32_t *parts, double *terms) {
+    return eval_candidate(coef17, ints3, bounds, env, d, t, p, v, z, gc, off, c, host_bytes, terms, n_parts, parts);
 }
 
 /* Predicted throughput of measured runs ("samples") of one model type under
@@ -588,43 +663,104 @@ int ork_frozen_round_f32(uint32_t n_jobs, const float *ref_thr, const ork_table 
 int ork_place_f32(uint32_t n_jobs, const ork_assign *assign, uint32_t n_nodes, uint32_t gpus_per_node,
                   uint32_t cpus_per_node, float mem_per_node_gb, uint32_t *place_off,
                   ork_place_entry *entries, uint32_t *status) {
-    std::vector<uint32_t> freeG(n_nodes, gpus_per_node), freeC(n_nodes, cpus_per_node);
-    std::vector<float> freeM(n_nodes, mem_per_node_gb);
+    NodeState nodes(n_nodes, gpus_per_node, cpus_per_node, mem_per_node_gb);
     uint32_t n_entries = 0;
     for (uint32_t j = 0; j < n_jobs; ++j) {
         place_off[j] = n_entries;
         status[j] = 0;
-        const uint32_t g = assign[j].g, c = assign[j].c;
-        const float mem = assign[j].mem_gb;
-        if (g == 0) continue;
+        if (assign[j].g == 0) continue;
         std::vector<ork_place_entry> parts;
-        uint32_t done = 0;
-        for (uint32_t n = 0; n < n_nodes && done < g; ++n) {
-            uint32_t k = std::min(freeG[n], g - done);
-            for (; k > 0; --k) {                      /* the most GPUs whose CPUs and memory are free here */
-                const uint64_t cpus = ((uint64_t)c * k + g - 1) / g;
-                const float m = (mem * (float)k) / (float)g;
-                if (cpus <= freeC[n] && m <= freeM[n]) break;
-            }
-            if (k == 0) continue;
-            ork_place_entry e;
-            e.node = n;
-            e.g = k;
-            e.c = (uint32_t)((uint64_t)c * (done + k) / g - (uint64_t)c * done / g);
-            e.mem_gb = (mem * (float)k) / (float)g;
-            parts.push_back(e);
-            done += k;
-        }
-        if (done < g) { status[j] = 2; continue; }    /* not enough found: the nodes stay as they were */
+        if (!nodes.first_fit(assign[j].g, assign[j].c, assign[j].mem_gb, parts)) { status[j] = 2; continue; }
         status[j] = 1;
-        for (const ork_place_entry &e : parts) {
-            freeG[e.node] -= e.g;
-            freeC[e.node] -= e.c;
-            freeM[e.node] = freeM[e.node] - e.mem_gb;
-            entries[n_entries++] = e;
-        }
+        nodes.book(parts);
+        for (const ork_place_entry &e : parts) entries[n_entries++] = e;
     }
     place_off[n_jobs] = n_entries;
+    return 0;
+}
+
+/* Placement that feeds the plan (Sec. 5.2, Algorithm 1, ScheduleJob from the
+ * placement record to the return: the job walks the nodes, and if what it
+ * found satisfies at least its minimum demand the plan is selected given the
+ * found placement, then memory is allocated from that plan's estimate; last
+ * paragraph of Sec. 5.2: a job placed on several nodes is predicted with the
+ * inter-node bandwidth).
+ *  Jobs in index order, every node starts empty.  A job comes with the
+ *  amounts an allocation decided (assign[j]: g GPUs = one of its valid counts,
+ *  c CPUs = a CPU level at that count, mem_gb = a memory tier at that count).
+ *  It tries first fit with these; when the nodes do not hold them it tries its
+ *  next smaller valid GPU count (same CPU level and memory tier, so the
+ *  amounts shrink with the grid's modes) that has a feasible plan there, and
+ *  so on, but never below its floor (min_seg[j], -1 = none): Algorithm 1
+ *  accepts what the search found as long as the minimum demand is met.
+ *  A placed job's plan is searched again among the plans of its GPU count that
+ *  are feasible at its CPUs and memory tier, each evaluated with the bandwidths
+ *  of the actual node split (bandwidths_placed); best throughput, lowest plan
+ *  index on ties.
+ * out[j] = the amounts placed, the plan and its throughput (zeros / no plan
+ * when the job got nothing); status 0 nothing to place, 1 placed, 2 placed
+ * with fewer GPUs than asked, 3 not placed.  total = sum of thr / ref_thr.
+ * best_thr (segment layout of all jobs) says which (count, level, tier) have a
+ * feasible plan at all.  PARITY UNPINNED as a reading; pinned by hand cases
+ * (a 3+1 split that flips the best plan, a retry at a smaller count, the
+ * floor) and by brute force over the plans on generated rounds. */
+int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, const ork_bounds *bounds,
+                    const ork_table *tb, const ork_grid *grid, const ork_env *env, const float *best_thr,
+                    const ork_assign *assign, const int32_t *min_seg, uint32_t n_nodes, uint32_t gpus_per_node,
+                    uint32_t cpus_per_node, float mem_per_node_gb, ork_assign *out, uint32_t *place_off,
+                    ork_place_entry *entries, uint32_t *status, double *total) {
+    const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    NodeState nodes(n_nodes, gpus_per_node, cpus_per_node, mem_per_node_gb);
+    uint32_t n_entries = 0;
+    double sum = 0.0;
+    double x[ORK_N_TERMS];
+    for (uint32_t j = 0; j < n_jobs; ++j) {
+        place_off[j] = n_entries;
+        status[j] = 0;
+        out[j] = ork_assign{0, 0, 0.0f, ORK_NO_PLAN, 0.0f};
+        const uint32_t g0 = assign[j].g;
+        if (g0 == 0) continue;
+        const uint32_t s_off = tb->seg_off[j], ns = tb->seg_off[j + 1] - s_off;
+        /* where the amounts sit in the grid: the GPU count among the job's counts, the CPU level and the tier */
+        int64_t s0 = -1, ci = -1, mi = -1;
+        for (uint32_t s = 0; s < ns; ++s) if (tb->seg_g[s_off + s] == g0) s0 = s;
+        for (uint32_t c = 0; c < grid->n_cpu; ++c) if (cpus_of(grid, c, g0) == assign[j].c) ci = c;
+        for (uint32_t m = 0; m < grid->n_mem; ++m) if (tier_gb(grid, m, g0) == assign[j].mem_gb) mi = m;
+        if (s0 < 0 || ci < 0 || mi < 0) return -1;          /* not an allocation on this table and grid */
+        const int64_t s_min = (min_seg && min_seg[j] >= 0) ? min_seg[j] : 0;
+        std::vector<ork_place_entry> parts;
+        int64_t s = s0;
+        for (; s >= s_min; --s) {                           /* the amounts asked for, then smaller valid counts */
+            if (!(best_thr[rows * s_off + ((uint64_t)ci * grid->n_mem + mi) * ns + s] > 0.0f)) continue;
+            const uint32_t g = tb->seg_g[s_off + s];
+            if (nodes.first_fit(g, cpus_of(grid, (uint32_t)ci, g), tier_gb(grid, (uint32_t)mi, g), parts)) break;
+        }
+        if (s < s_min) { status[j] = 3; continue; }
+        status[j] = (s == s0) ? 1 : 2;
+        nodes.book(parts);
+        std::vector<uint32_t> split;
+        for (const ork_place_entry &e : parts) { entries[n_entries++] = e; split.push_back(e.g); }
+        /* GetBestPlan(j, placement): the plans of this GPU count with the bandwidths of this split */
+        const uint32_t g = tb->seg_g[s_off + s], c = cpus_of(grid, (uint32_t)ci, g);
+        const float hb = tier_bytes(grid, (uint32_t)mi, g);
+        const uint32_t t_off = tb->triple_off[j], nt = tb->triple_off[j + 1] - t_off;
+        const uint32_t first = tb->seg_first[s_off + s];
+        const uint32_t last = ((uint32_t)s + 1 < ns) ? tb->seg_first[s_off + s + 1] : nt;
+        double bv = 0.0; uint32_t bp = ORK_NO_PLAN;
+        for (uint32_t tl = first; tl < last; ++tl) {
+            const uint32_t *tr = tb->triples + (uint64_t)(t_off + tl) * 4;
+            for (uint32_t o = 0; o < 16; ++o) {
+                const uint32_t reason = eval_candidate(coef + (uint64_t)j * N_COEF, ints + (uint64_t)j * N_INT, bounds, env,
+                                                       tr[0], tr[1], tr[2], tr[3], o >> 2, (o >> 1) & 1u, o & 1u, c, hb, x,
+                                                       (uint32_t)split.size(), split.data());
+                if (!reason && x[X_THR] > bv) { bv = x[X_THR]; bp = tl * 16 + o; }   /* strict: lowest index on ties */
+            }
+        }
+        out[j] = ork_assign{g, c, tier_gb(grid, (uint32_t)mi, g), bp, (float)bv};
+        sum += (double)(float)bv / (double)coef[(uint64_t)j * N_COEF + REF_THR];
+    }
+    place_off[n_jobs] = n_entries;
+    if (total) *total = sum;
     return 0;
 }
 

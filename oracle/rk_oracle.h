@@ -159,6 +159,25 @@ int ork_place_f32(uint32_t n_jobs, const ork_assign *assign, uint32_t n_nodes, u
                   uint32_t cpus_per_node, float mem_per_node_gb, uint32_t *place_off,
                   ork_place_entry *entries, uint32_t *status);
 
+/* ork_eval_one for a job whose GPUs are parts[0..n_parts) on the consecutive
+ * nodes of its placement: every communication group gets the intra-node
+ * bandwidth only if all its ranks are on one node. */
+uint32_t ork_eval_one_placed(const float *coef17, const uint32_t *ints3, const ork_bounds *bounds,
+                             const ork_env *env, uint32_t d, uint32_t t, uint32_t p, uint32_t v,
+                             uint32_t z, uint32_t gc, uint32_t off, uint32_t c, float host_bytes,
+                             uint32_t n_parts, const uint32_t *parts, double *terms);
+
+/* Placement of an allocation that feeds the plan: first fit per job with a
+ * fall-back to smaller valid GPU counts (not below min_seg[j], NULL or -1 = no
+ * floor), then the best plan of the placed count under the bandwidths of the
+ * actual node split.  out[n_jobs] = placed amounts, plan, throughput; status
+ * 0 nothing to place, 1 placed as asked, 2 placed with fewer GPUs, 3 not placed. */
+int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, const ork_bounds *bounds,
+                    const ork_table *table, const ork_grid *grid, const ork_env *env, const float *best_thr,
+                    const ork_assign *assign, const int32_t *min_seg, uint32_t n_nodes, uint32_t gpus_per_node,
+                    uint32_t cpus_per_node, float mem_per_node_gb, ork_assign *out, uint32_t *place_off,
+                    ork_place_entry *entries, uint32_t *status, double *total);
+
 #ifdef __cplusplus
 }
 #endif
