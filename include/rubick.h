@@ -496,6 +496,50 @@ int32_t rk_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs, const rk_a
                  uint32_t *place_off, rk_place_entry *entries, uint64_t cap_entries, uint32_t *status,
                  rk_place_result *result);
 
+/* Placement that feeds the plan (Sec. 5.2, Algorithm 1, ScheduleJob: after the
+ * walk over the nodes the plan is selected given the found placement and memory
+ * is allocated from its estimate; last paragraph of Sec. 5.2: a job placed on
+ * several nodes is predicted with the inter-node bandwidth; Sec. 4.1: the
+ * bottleneck bandwidth of a communication group decides).  Over all jobs of the
+ * table, in index order, every node starts empty:
+ *  - a job tries first fit (as rk_place) with the amounts of assign[j], which
+ *    must be a valid GPU count of the job, a CPU level and a memory tier of the
+ *    grid at that count, with a feasible plan there (what rk_allocate and its
+ *    relatives write; anything else is not placed);
+ *  - if the nodes do not hold them it falls back to its next smaller GPU count
+ *    that has a feasible plan at the same CPU level and memory tier (CPUs and
+ *    GiB follow the grid's modes), and so on, but not below its floor
+ *    (min_seg[j] = segment index, NULL or -1 = none): what the search found is
+ *    accepted as long as the minimum demand is met;
+ *  - the plan of a placed job is searched again among the plans of its GPU
+ *    count, each evaluated (Sec. 4, Eq. 1, arithmetic of rk_eval_candidates)
+ *    with bandwidths from the actual node split: ranks fill the job's GPU slots
+ *    in placement order, tensor-parallel ranks adjacent, then data-parallel,
+ *    then pipeline stages, and a kind of group uses B_intra only if every group
+ *    of that kind has all its ranks on one node.
+ *   best_thr  [device] segment layout of all jobs (tells which counts have a feasible plan)
+ *   placed    [device] n_jobs records: the amounts placed, the plan and its throughput
+ *             (zeros and RK_NO_PLAN for a job that got nothing)
+ *   place_off, entries, cap_entries, result: as rk_place
+ *   status    [device] 0 nothing to place, 1 placed as asked, 2 placed with fewer GPUs, 3 not placed
+ *   total     [device] one float: sum of thr/ref_thr over the placed jobs */
+int32_t rk_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table, const rk_alloc_grid *grid,
+                       const rk_env *env, const rk_nodes *nodes, const float *best_thr, const rk_assign *assign,
+                       const int32_t *min_seg_or_null, rk_assign *placed, uint32_t *place_off,
+                       rk_place_entry *entries, uint64_t cap_entries, uint32_t *status, float *total,
+                       rk_place_result *result);
+
+/* A whole round on nodes (Sec. 5.2, Algorithm 1): rk_schedule_round (with sla ==
+ * NULL) or rk_schedule_round_sla against what the nodes hold together, then
+ * rk_place_plans with the floors of the guaranteed jobs.  assign [device]
+ * n_jobs records receives the amounts the allocation decided, placed what
+ * came of them on the nodes; total is that of the placed jobs. */
+int32_t rk_schedule_round_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                                 const rk_alloc_grid *grid, const rk_env *env, const rk_nodes *nodes,
+                                 const rk_sla *sla_or_null, rk_assign *assign, rk_assign *placed,
+                                 uint32_t *place_off, rk_place_entry *entries, uint64_t cap_entries,
+                                 uint32_t *status, float *total, rk_place_result *result);
+
 #ifdef __cplusplus
 }
 #endif

@@ -729,13 +729,16 @@ int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, co
         if (s0 < 0 || ci < 0 || mi < 0) return -1;          /* not an allocation on this table and grid */
         const int64_t s_min = (min_seg && min_seg[j] >= 0) ? min_seg[j] : 0;
         std::vector<ork_place_entry> parts;
-        int64_t s = s0;
-        for (; s >= s_min; --s) {                           /* the amounts asked for, then smaller valid counts */
-            if (!(best_thr[rows * s_off + ((uint64_t)ci * grid->n_mem + mi) * ns + s] > 0.0f)) continue;
-            const uint32_t g = tb->seg_g[s_off + s];
-            if (nodes.first_fit(g, cpus_of(grid, (uint32_t)ci, g), tier_gb(grid, (uint32_t)mi, g), parts)) break;
+        int64_t s = -1;
+        for (int64_t s2 = s0; s2 >= 0 && s < 0; --s2) {     /* the amounts asked for, then smaller valid counts */
+            if (s2 != s0) {
+                if (s2 < s_min) break;                      /* never below the floor */
+                if (!(best_thr[rows * s_off + ((uint64_t)ci * grid->n_mem + mi) * ns + s2] > 0.0f)) continue;
+            }
+            const uint32_t g = tb->seg_g[s_off + s2];
+            if (nodes.first_fit(g, cpus_of(grid, (uint32_t)ci, g), tier_gb(grid, (uint32_t)mi, g), parts)) s = s2;
         }
-        if (s < s_min) { status[j] = 3; continue; }
+        if (s < 0) { status[j] = 3; continue; }
         status[j] = (s == s0) ? 1 : 2;
         nodes.book(parts);
         std::vector<uint32_t> split;

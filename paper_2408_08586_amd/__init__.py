@@ -25,7 +25,8 @@ FIT_FIELDS = ("k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_con
 
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
            "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
-           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared", "rk_place", "rk_allocate_static")
+           "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared", "rk_place", "rk_allocate_static", "rk_place_plans",
+           "rk_schedule_round_placed")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -466,6 +467,29 @@ def rk_place(ctx, nodes: rk_nodes, n_jobs, assign, place_off, entries, cap_entri
     _check(ctx, load_library().rk_place(ctx, C.byref(nodes), C.c_uint32(n_jobs), _ptr(assign), _ptr(place_off),
                                         _ptr(entries), C.c_uint64(cap_entries), _ptr(status),
                                         C.byref(res) if want_result else None))
+    return res
+
+
+def rk_place_plans(ctx, jobs: Jobs, table, grid, env, nodes: rk_nodes, best_thr, assign, min_seg, placed, place_off, entries,
+                   cap_entries, status, total, want_result=True):
+    """Placement that feeds the plan; min_seg may be None.  Returns rk_place_result (after a wait) or None."""
+    res = rk_place_result() if want_result else None
+    _check(ctx, load_library().rk_place_plans(ctx, C.byref(jobs.c), C.byref(table), C.byref(grid), C.byref(env), C.byref(nodes),
+                                              _ptr(best_thr), _ptr(assign), _ptr(min_seg), _ptr(placed), _ptr(place_off),
+                                              _ptr(entries), C.c_uint64(cap_entries), _ptr(status), _ptr(total),
+                                              C.byref(res) if want_result else None))
+    return res
+
+
+def rk_schedule_round_placed(ctx, jobs: Jobs, bounds, grid, env, nodes: rk_nodes, sla, assign, placed, place_off, entries,
+                             cap_entries, status, total, want_result=True):
+    """A whole round on nodes; sla may be None."""
+    res = rk_place_result() if want_result else None
+    _check(ctx, load_library().rk_schedule_round_placed(ctx, C.byref(jobs.c), C.byref(bounds), C.byref(grid), C.byref(env),
+                                                        C.byref(nodes), C.byref(sla.c) if sla is not None else None,
+                                                        _ptr(assign), _ptr(placed), _ptr(place_off), _ptr(entries),
+                                                        C.c_uint64(cap_entries), _ptr(status), _ptr(total),
+                                                        C.byref(res) if want_result else None))
     return res
 
 

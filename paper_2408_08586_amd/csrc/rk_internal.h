@@ -26,6 +26,7 @@ struct rk_ctx {
     hipEvent_t sim_ev[2];                   // ... ordered after and before the context's stream with these
     bool fused_lds_raised;                  // fused kernel: its dynamic LDS limit has been raised for this context
     unsigned char *static_scratch;          // this device's copy of the static scratch array (rk_allocate_static)
+    bool place_lds_raised;                  // placement kernel: its dynamic LDS limit has been raised for this context
 };
 
 // scratch slots
@@ -135,3 +136,9 @@ int32_t rk_allocate_setup(rk_ctx *ctx);
 int32_t rk_launch_min_res(rk_ctx *ctx, const TableDev &tb, const rk_alloc_grid *grid, uint32_t jb, uint32_t je,
                           const float *best_thr, const rk_sla *sla, int32_t *min_seg, uint32_t *min_c,
                           uint32_t *min_m);
+
+// placement that feeds the plan, over all jobs of the table (arguments as rk_place_plans, already validated)
+int32_t rk_launch_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table, const rk_alloc_grid *grid,
+                              const rk_env *env, const rk_nodes *nodes, const float *best_thr, const rk_assign *assign,
+                              const int32_t *min_seg, rk_assign *placed, uint32_t *place_off, rk_place_entry *entries,
+                              uint64_t cap_entries, uint32_t *status, float *total, rk_place_result *result);

@@ -82,7 +82,37 @@ struct Triple {
     float b;             // global batch
 };
 
-__device__ __forceinline__ Triple triple_terms(const Job &J, const rk_env &E, uint32_t packed) {
+// Bandwidths of the three kinds of communication groups.
+struct Links { float dp, tp, pp; };
+
+// Bottleneck bandwidths under a packed placement (TP ranks adjacent, then DP, then PP stages; the job starts at
+// a node boundary and fills whole nodes): inside one node everything is intra-node; over several nodes a kind of
+// group stays on the intra-node links only when whole groups tile a node.
+__device__ __forceinline__ Links packed_links(const rk_env &E, uint32_t d, uint32_t t, uint32_t g) {
+    const uint32_t N = E.gpus_per_node;
+    Links L = {E.B_intra, E.B_intra, E.B_intra};
+    if (g > N) {
+        L.tp = (N % t == 0) ? E.B_intra : E.B_inter;
+        L.dp = (N % (t * d) == 0) ? E.B_intra : E.B_inter;
+        L.pp = E.B_inter;
+    }
+    return L;
+}
+
+// The same for a job whose nodes are known: edge_gcd = greatest common divisor of the GPU counts at which the
+// job's slots cross from one node to the next (0 when it sits on one node).  Groups of w adjacent ranks all lie
+// inside a node exactly when w divides every such count: w = t for tensor parallelism, t*d for data parallelism
+// (its groups interleave over a whole pipeline stage); pipeline neighbours share a node only when the job does.
+__device__ __forceinline__ Links placed_links(const rk_env &E, uint32_t d, uint32_t t, uint32_t edge_gcd) {
+    Links L;
+    L.tp = (edge_gcd % t == 0) ? E.B_intra : E.B_inter;
+    L.dp = (edge_gcd % (t * d) == 0) ? E.B_intra : E.B_inter;
+    L.pp = edge_gcd == 0 ? E.B_intra : E.B_inter;
+    return L;
+}
+
+template <bool PLACED>
+__device__ __forceinline__ Triple triple_terms_on(const Job &J, const rk_env &E, uint32_t packed, uint32_t edge_gcd) {
     Triple T;
     T.d = RK_TRIPLE_D(packed); T.t = RK_TRIPLE_T(packed); T.p = RK_TRIPLE_P(packed);
     T.g = T.d * T.t * T.p;
@@ -101,14 +131,8 @@ __device__ __forceinline__ Triple triple_terms(const Job &J, const rk_env &E, ui
     const float Tbwd0 = J.k_bwd * Tfwd;
     const float Tbwd1 = Tbwd0 + Tfwd;                        // checkpointing recomputes a forward
 
-    // bottleneck bandwidths under a packed placement (TP ranks adjacent, then DP, then PP)
-    const uint32_t N = E.gpus_per_node;
-    float Bdp = E.B_intra, Btp = E.B_intra, Bpp = E.B_intra;
-    if (T.g > N) {
-        Btp = (N % T.t == 0) ? E.B_intra : E.B_inter;
-        Bdp = (N % (T.t * T.d) == 0) ? E.B_intra : E.B_inter;
-        Bpp = E.B_inter;
-    }
+    const Links L = PLACED ? placed_links(E, T.d, T.t, edge_gcd) : packed_links(E, T.d, T.t, T.g);
+    const float Bdp = L.dp, Btp = L.tp, Bpp = L.pp;
     const float bsh = (T.b * J.seq) * J.hidden;
     const float dt = fd * ft;
     T.Tdp = T.d > 1 ? fast_div(J.P * (2.f * (fd - 1.f)), (fd * ftp) * Bdp) : 0.f;
@@ -145,6 +169,11 @@ __device__ __forceinline__ Triple triple_terms(const Job &J, const rk_env &E, ui
     return T;
 }
 
+// terms of a triple under the packed placement every candidate is evaluated with
+__device__ __forceinline__ Triple triple_terms(const Job &J, const rk_env &E, uint32_t packed) {
+    return triple_terms_on<false>(J, E, packed, 0u);
+}
+
 // GPU-memory verdict of a plan: true if it fits.
 __device__ __forceinline__ bool gpu_mem_fits(const Job &J, const rk_env &E, const Triple &T,
                                              uint32_t z, uint32_t gc, uint32_t off) {
@@ -178,6 +207,13 @@ __device__ __forceinline__ float host_bytes_needed(const Job &J, const Triple &T
 
 __device__ __forceinline__ float tier_bytes(const GridDev &G, uint32_t mi, uint32_t g) {
     float v = G.mem_levels_gb[mi] * 1073741824.0f;
+    if (G.mem_mode) v = v * (float)g;
+    return v;
+}
+
+// GiB a job of g GPUs books at memory tier mi
+__device__ __forceinline__ float tier_gib(const GridDev &G, uint32_t mi, uint32_t g) {
+    float v = G.mem_levels_gb[mi];
     if (G.mem_mode) v = v * (float)g;
     return v;
 }

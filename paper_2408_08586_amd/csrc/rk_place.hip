@@ -19,12 +19,29 @@
 //     free GPU; a lane finds the most GPUs its node can give, a prefix sum
 //     over the lanes cuts the offers at what the job still lacks, and the
 //     parts are booked only when the whole amount has been found.
+//
+// rk_place_plans adds what Algorithm 1 does with a placement: a job that does
+// not find its amount falls back to its next smaller valid GPU count (k_place
+// with a Retry), and the plan of every placed job is searched again among the
+// plans of its GPU count under the bandwidths of the actual node split
+// (k_replan).
 #include "rk_internal.h"
+#include "rk_model.h"
 
 namespace {
 
 constexpr int PLACE_THREADS = 512;
 constexpr int PLACE_WAVES = PLACE_THREADS / 64;
+
+// Fall-back of a job that does not find its amount (on != 0): the next smaller GPU count of its list, not below
+// its floor, that has a feasible plan at the job's CPU level and memory tier; CPUs and memory follow the grid.
+struct Retry {
+    uint32_t on;
+    const uint32_t *seg_off, *seg_g;
+    const float *best_thr;   // segment layout of all jobs
+    const int32_t *min_seg;  // per job, may be null; -1 = no floor
+    GridDev grid;
+};
 
 struct PlaceArgs {
     uint32_t n_jobs, n_nodes, gpn, cpn;
@@ -34,7 +51,26 @@ struct PlaceArgs {
     rk_place_entry *entries;
     uint32_t *status;
     uint32_t *result;        // n_entries, n_placed, n_failed, in_order
+    Retry retry;
 };
+
+// Where a record's amounts sit in the job's lists: segment of the GPU count, CPU level, memory tier (-1: not
+// found).  Evaluated by a whole wavefront, the result is uniform.
+struct GridPos { int32_t s, ci, mi; };
+__device__ __forceinline__ GridPos locate(const GridDev &G, const uint32_t *seg_g, uint32_t s_off, uint32_t ns, uint32_t g,
+                                          uint32_t c, float mem, uint32_t lane) {
+    GridPos P = {-1, -1, -1};
+    for (uint32_t base = 0; base < ns && P.s < 0; base += 64) {
+        const uint32_t s = base + lane;
+        const unsigned long long hit = __ballot(s < ns && seg_g[s_off + s] == g);
+        if (hit) P.s = (int32_t)(base + (uint32_t)__ffsll((long long)hit) - 1u);
+    }
+    const unsigned long long hc = __ballot(lane < G.n_cpu && cpus_of(G, lane, g) == c);
+    if (hc) P.ci = (int32_t)__ffsll((long long)hc) - 1;
+    const unsigned long long hm = __ballot(lane < G.n_mem && tier_gib(G, lane, g) == mem);
+    if (hm) P.mi = (int32_t)__ffsll((long long)hm) - 1;
+    return P;
+}
 
 __device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long long v, uint32_t lane) {
 #pragma unroll
@@ -267,13 +303,17 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
             const int turn = (int)__ffsll((long long)todo) - 1;
             todo &= todo - 1ull;
             if ((int)lane <= turn && !have_off) { my_off = cursor; have_off = true; }   // jobs up to this one start here
-            const uint32_t jg = (uint32_t)__builtin_amdgcn_readlane((int)g, turn);
-            const uint32_t jc = (uint32_t)__builtin_amdgcn_readlane((int)c, turn);
-            const float jm = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mem), turn));
+            uint32_t jg = (uint32_t)__builtin_amdgcn_readlane((int)g, turn);
+            uint32_t jc = (uint32_t)__builtin_amdgcn_readlane((int)c, turn);
+            float jm = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mem), turn));
+            GridPos pos = {-2, -1, -1};                    // -2: not looked up yet
+            uint32_t tries = 0, first, left, end;
+            for (;;) {                                     // the amount asked for, then smaller ones if allowed
             // the offers of the nodes, cut at what the job still lacks (none are asked when the cluster has too few);
             // a job that needs CPUs gets nothing from a node without a free CPU
-            const uint32_t first = jc > 0 ? first_gc : first_g;
-            uint32_t left = jg, end = first;
+            first = jc > 0 ? first_gc : first_g;
+            left = jg;
+            end = first;
             for (uint32_t nb = first; nb < A.n_nodes && left > 0 && jg <= free_gpus; nb += 64) {
                 const uint32_t n = nb + lane;
                 uint32_t k = 0;
@@ -300,12 +340,37 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
                 left -= all < left ? all : left;
                 end = nb + 64;
             }
+            if (left == 0 || !A.retry.on) break;
+            {                                             // not found: the next smaller count the job may run on
+                const Retry &R = A.retry;
+                const uint32_t jj = base + (uint32_t)turn;
+                const uint32_t s_off = R.seg_off[jj], ns = R.seg_off[jj + 1] - s_off;
+                if (pos.s == -2) pos = locate(R.grid, R.seg_g, s_off, ns, jg, jc, jm, lane);
+                int32_t next = -1;
+                if (pos.s >= 0 && pos.ci >= 0 && pos.mi >= 0) {
+                    const int32_t floor_s = R.min_seg && R.min_seg[jj] > 0 ? R.min_seg[jj] : 0;
+                    const uint64_t row = (uint64_t)R.grid.n_cpu * R.grid.n_mem * s_off +
+                                         ((uint64_t)pos.ci * R.grid.n_mem + pos.mi) * ns;
+                    for (int32_t hi = pos.s - 1; hi >= floor_s && next < 0; hi -= 64) {
+                        const int32_t s = hi - (int32_t)lane;                 // lane 0 looks at the nearest count
+                        const unsigned long long ok = __ballot(s >= floor_s && R.best_thr[row + (uint32_t)(s < 0 ? 0 : s)] > 0.f);
+                        if (ok) next = hi - ((int32_t)__ffsll((long long)ok) - 1);
+                    }
+                }
+                if (next < 0) break;
+                pos.s = next;
+                jg = R.seg_g[s_off + (uint32_t)next];
+                jc = cpus_of(R.grid, (uint32_t)pos.ci, jg);
+                jm = tier_gib(R.grid, (uint32_t)pos.mi, jg);
+                ++tries;
+            }
+            }
             if (left > 0) {                               // not found: nothing is booked
-                if ((int)lane == turn) my_status = 2u;
+                if ((int)lane == turn) my_status = A.retry.on ? 3u : 2u;
                 ++n_failed;
                 continue;
             }
-            if ((int)lane == turn) my_status = 1u;
+            if ((int)lane == turn) my_status = tries ? 2u : 1u;
             ++n_placed;
             free_gpus -= jg;
             for (uint32_t nb = first; nb < end; nb += 64) {
@@ -351,12 +416,129 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
     }
 }
 
-}  // namespace
+// ------------------------------------------------------------ the plan of a placed job
+// GetBestPlan(j, placement): a wavefront per job.  The job's parts give its GPU count and the greatest common
+// divisor of the counts at which its slots cross a node boundary, which decides the bandwidth of every kind of
+// communication group (placed_links); its lanes then take the triples of that GPU count, all sixteen options each,
+// with the arithmetic of the candidate evaluation, and the best (throughput, lowest plan index) wins.
+constexpr int REPLAN_THREADS = 256;
 
-extern "C" int32_t rk_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs, const rk_assign *assign,
-                            uint32_t *place_off, rk_place_entry *entries, uint64_t cap_entries, uint32_t *status,
-                            rk_place_result *result) {
-    if (!ctx) return RK_ERR_INVALID_ARG;
+struct ReplanArgs {
+    JobDev jobs;
+    TableDev tb;
+    GridDev grid;
+    rk_env env;
+    uint32_t n_jobs, option_mask;
+    const rk_assign *assign;         // what was asked for: fixes the CPU level and the memory tier
+    const uint32_t *place_off;
+    const rk_place_entry *entries;
+    const uint32_t *status;
+    rk_assign *placed;
+};
+
+__device__ __forceinline__ uint32_t gcd_u32(uint32_t a, uint32_t b) {
+    while (b) { const uint32_t r = a % b; a = b; b = r; }
+    return a;
+}
+
+__global__ __launch_bounds__(REPLAN_THREADS) void k_replan(ReplanArgs A) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t j = blockIdx.x * (REPLAN_THREADS / 64) + (threadIdx.x >> 6);
+    if (j >= A.n_jobs) return;
+    rk_assign out = {0u, 0u, 0.f, RK_NO_PLAN, 0.f};
+    const uint32_t st = A.status[j];
+    if (st == 1u || st == 2u) {
+        const uint32_t e0 = A.place_off[j], e1 = A.place_off[j + 1];
+        uint32_t run = 0, ge = 0;                          // GPUs so far; gcd of the boundaries this lane has seen
+        for (uint32_t base = e0; base < e1; base += 64) {
+            const uint32_t i = base + lane;
+            const uint32_t k = i < e1 ? A.entries[i].g : 0u;
+            uint32_t incl = k;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t o = __shfl_up(incl, off, 64);
+                if ((int)lane >= off) incl += o;
+            }
+            incl += run;
+            if (i + 1 < e1) ge = gcd_u32(ge, incl);       // the end of the last part is not a boundary inside the job
+            run = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) ge = gcd_u32(ge, __shfl_xor(ge, off, 64));
+        const uint32_t g = run;
+        const uint32_t s_off = A.tb.seg_off[j], ns = A.tb.seg_off[j + 1] - s_off;
+        const rk_assign asked = A.assign[j];
+        const GridPos lv = locate(A.grid, A.tb.seg_g, s_off, ns, asked.g, asked.c, asked.mem_gb, lane);
+        const GridPos at = locate(A.grid, A.tb.seg_g, s_off, ns, g, 0u, 0.f, lane);
+        if (lv.ci >= 0 && lv.mi >= 0 && at.s >= 0) {
+            const uint32_t ci = (uint32_t)lv.ci, mi = (uint32_t)lv.mi, s = (uint32_t)at.s;
+            const uint32_t c = cpus_of(A.grid, ci, g);
+            const float tier = tier_bytes(A.grid, mi, g);
+            const uint32_t t0 = A.tb.triple_off[j], nt = A.tb.triple_off[j + 1] - t0;
+            const uint32_t first = A.tb.seg_first[s_off + s];
+            const uint32_t last = s + 1 < ns ? A.tb.seg_first[s_off + s + 1] : nt;
+            const Job J = load_job(A.jobs, j);
+            unsigned long long key = 0;
+            for (uint32_t tl = first + lane; tl < last; tl += 64) {
+                const Triple T = triple_terms_on<true>(J, A.env, A.tb.triples[t0 + tl], ge);
+                bool any_off = false;
+#pragma unroll
+                for (uint32_t z = 0; z < 4; ++z)
+#pragma unroll
+                    for (uint32_t gc = 0; gc < 2; ++gc) {
+                        const uint32_t o = z * 4 + gc * 2;
+                        if (((A.option_mask >> o) & 1u) && gpu_mem_fits(J, A.env, T, z, gc, 0)) {
+                            const unsigned long long k2 = make_key(thr_plain(J, T, z, gc), tl * 16 + o);
+                            key = k2 > key ? k2 : key;
+                        }
+                        if (z >= 2 && ((A.option_mask >> (o + 1)) & 1u)) any_off = true;
+                    }
+                if (any_off && host_bytes_needed(J, T) <= tier) {
+                    const Offload O = offload_terms(J, A.env, T);
+                    const float sw = swap_term(J, O, c);
+#pragma unroll
+                    for (uint32_t z = 2; z < 4; ++z)
+#pragma unroll
+                        for (uint32_t gc = 0; gc < 2; ++gc) {
+                            const uint32_t o = z * 4 + gc * 2 + 1;
+                            if (((A.option_mask >> o) & 1u) && gpu_mem_fits(J, A.env, T, z, gc, 1)) {
+                                const unsigned long long k2 = make_key(thr_offload(T, O, gc, sw), tl * 16 + o);
+                                key = k2 > key ? k2 : key;
+                            }
+                        }
+                }
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const unsigned long long o = __shfl_xor(key, off, 64);
+                key = o > key ? o : key;
+            }
+            out.g = g; out.c = c; out.mem_gb = tier_gib(A.grid, mi, g);
+            out.plan = key_plan(key); out.thr = key_thr(key);
+        }
+    }
+    if (lane == 0) A.placed[j] = out;
+}
+
+// total = sum of thr / ref_thr over the records, in float64, in a fixed order (thread t takes the jobs t, t + 1024, ...)
+__global__ __launch_bounds__(1024) void k_place_total(uint32_t n_jobs, const rk_assign *placed, const float *ref_thr,
+                                                      float *total) {
+    __shared__ double part[1024];
+    double sum = 0.0;
+    for (uint32_t j = threadIdx.x; j < n_jobs; j += 1024)
+        if (placed[j].g > 0) sum += (double)placed[j].thr / (double)ref_thr[j];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (uint32_t w = 512; w >= 1; w >>= 1) {
+        if (threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *total = (float)part[0];
+}
+
+int32_t launch_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs, const rk_assign *assign, uint32_t *place_off,
+                     rk_place_entry *entries, uint64_t cap_entries, uint32_t *status, const Retry &retry,
+                     rk_place_result *result) {
     if (!nodes || !place_off) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
     if (n_jobs > 0 && (!assign || !status)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "assign or status is null");
     if (nodes->n_nodes < 1 || nodes->n_nodes > RK_MAX_NODES)
@@ -375,22 +557,81 @@ extern "C" int32_t rk_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs,
     A.n_jobs = n_jobs; A.n_nodes = nodes->n_nodes; A.gpn = nodes->gpus_per_node; A.cpn = nodes->cpus_per_node;
     A.mpn = nodes->mem_per_node_gb;
     A.assign = assign; A.place_off = place_off; A.entries = entries; A.status = status;
+    A.retry = retry;
     int32_t rc;
     if ((rc = rk_scratch(ctx, SL_PLACE_RESULT, 4 * sizeof(uint32_t), (void **)&A.result))) return rc;
     const size_t lds = (size_t)A.n_nodes * 5 * sizeof(uint32_t);
-    static bool raised[64] = {};
-    if (lds > 48 * 1024 && !raised[ctx->device & 63]) {
+    if (lds > 48 * 1024 && !ctx->place_lds_raised) {
         RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_place),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, RK_MAX_NODES * 5 * sizeof(uint32_t)));
-        raised[ctx->device & 63] = true;
+        ctx->place_lds_raised = true;
     }
     k_place<<<1, PLACE_THREADS, lds, ctx->stream>>>(A);
     RK_CHECK_LAUNCH(ctx, "k_place");
-    if (result) {
-        uint32_t *h = ctx->h_pinned;
-        RK_HIP(ctx, hipMemcpyAsync(h, A.result, 4 * sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
-        RK_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        result->n_entries = h[0]; result->n_placed = h[1]; result->n_failed = h[2]; result->in_order = h[3];
-    }
+    (void)result;
     return RK_OK;
+}
+
+int32_t fetch_place_result(rk_ctx *ctx, rk_place_result *result) {
+    uint32_t *d_result = static_cast<uint32_t *>(ctx->scratch[SL_PLACE_RESULT]);
+    uint32_t *h = ctx->h_pinned;
+    RK_HIP(ctx, hipMemcpyAsync(h, d_result, 4 * sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
+    RK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    result->n_entries = h[0]; result->n_placed = h[1]; result->n_failed = h[2]; result->in_order = h[3];
+    return RK_OK;
+}
+
+}  // namespace
+
+extern "C" int32_t rk_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs, const rk_assign *assign,
+                            uint32_t *place_off, rk_place_entry *entries, uint64_t cap_entries, uint32_t *status,
+                            rk_place_result *result) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    Retry none = {};
+    int32_t rc;
+    if ((rc = launch_place(ctx, nodes, n_jobs, assign, place_off, entries, cap_entries, status, none, result))) return rc;
+    return result ? fetch_place_result(ctx, result) : RK_OK;
+}
+
+int32_t rk_launch_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table, const rk_alloc_grid *grid,
+                              const rk_env *env, const rk_nodes *nodes, const float *best_thr, const rk_assign *assign,
+                              const int32_t *min_seg, rk_assign *placed, uint32_t *place_off, rk_place_entry *entries,
+                              uint64_t cap_entries, uint32_t *status, float *total, rk_place_result *result) {
+    const uint32_t n_jobs = table->n_jobs;
+    Retry retry = {};
+    retry.on = 1u;
+    retry.seg_off = table->seg_off; retry.seg_g = table->seg_g;
+    retry.best_thr = best_thr; retry.min_seg = min_seg;
+    retry.grid = grid_dev(grid);
+    int32_t rc;
+    if ((rc = launch_place(ctx, nodes, n_jobs, assign, place_off, entries, cap_entries, status, retry, result))) return rc;
+    if (n_jobs > 0) {
+        ReplanArgs R;
+        R.jobs = job_dev(jobs); R.tb = table_dev(table); R.grid = retry.grid; R.env = *env;
+        R.n_jobs = n_jobs; R.option_mask = table->option_mask;
+        R.assign = assign; R.place_off = place_off; R.entries = entries; R.status = status; R.placed = placed;
+        const uint32_t per = REPLAN_THREADS / 64;
+        k_replan<<<(n_jobs + per - 1) / per, REPLAN_THREADS, 0, ctx->stream>>>(R);
+        RK_CHECK_LAUNCH(ctx, "k_replan");
+    }
+    k_place_total<<<1, 1024, 0, ctx->stream>>>(n_jobs, placed, jobs->ref_thr, total);
+    RK_CHECK_LAUNCH(ctx, "k_place_total");
+    return result ? fetch_place_result(ctx, result) : RK_OK;
+}
+
+extern "C" int32_t rk_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table, const rk_alloc_grid *grid,
+                                  const rk_env *env, const rk_nodes *nodes, const float *best_thr, const rk_assign *assign,
+                                  const int32_t *min_seg, rk_assign *placed, uint32_t *place_off, rk_place_entry *entries,
+                                  uint64_t cap_entries, uint32_t *status, float *total, rk_place_result *result) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if (!jobs || !total) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if ((rc = rk_check_table(ctx, table, 0, table ? table->n_jobs : 0))) return rc;
+    if (jobs->n_jobs != table->n_jobs) return rk_fail(ctx, RK_ERR_INVALID_ARG, "jobs and table disagree on n_jobs");
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    if ((rc = rk_check_env(ctx, env))) return rc;
+    if (table->n_jobs > 0 && (!placed || !jobs->ref_thr || (table->n_segs > 0 && !best_thr)))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    return rk_launch_place_plans(ctx, jobs, table, grid, env, nodes, best_thr, assign, min_seg, placed, place_off, entries,
+                                 cap_entries, status, total, result);
 }

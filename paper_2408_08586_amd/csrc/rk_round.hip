@@ -7,12 +7,19 @@
 
 namespace {
 
+// what a round leaves in the context's buffers for a step that follows it
+struct RoundKeep {
+    rk_plan_table tb;
+    float *best_thr;
+    int32_t *min_seg;        // null without service levels
+};
+
 // sla == NULL: every job is best-effort.  round_jobs != NULL: the rounds are made of slots, slot i
 // schedules job round_jobs[i]; every job is enumerated and evaluated once however many slots use it.
 int32_t schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
                         const rk_alloc_grid *grid, const rk_env *env, uint32_t n_rounds,
                         const uint32_t *round_off, const uint32_t *round_jobs, const rk_cluster *clusters,
-                        const rk_sla *sla, rk_assign *assign, float *totals) {
+                        const rk_sla *sla, rk_assign *assign, float *totals, RoundKeep *keep = nullptr) {
     int32_t rc;
     if (!jobs || !bounds || !round_off || !clusters || !totals || (!assign && jobs->n_jobs > 0))
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
@@ -89,6 +96,7 @@ int32_t schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *
     if ((rc = rk_scratch(ctx, SL_CURVE_G, n_out * 4, (void **)&curve_g))) return rc;
 
     if ((rc = rk_launch_fused(ctx, jobs, &tb, grid, env, 0, J, best_thr, best_plan, curve_thr, curve_plan, curve_g))) return rc;
+    if (keep) { keep->tb = tb; keep->best_thr = best_thr; keep->min_seg = nullptr; }
     SlaDev S = {};
     if (sla && J > 0) {
         int32_t *min_seg;
@@ -98,6 +106,7 @@ int32_t schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *
         if ((rc = rk_scratch(ctx, SL_MIN_M, (size_t)J * 4, (void **)&min_m))) return rc;
         if ((rc = rk_launch_min_res(ctx, table_dev(&tb), grid, 0, J, best_thr, sla, min_seg, min_c, min_m))) return rc;
         S = SlaDev{sla->guaranteed, sla->tenant, min_seg, min_c, sla->n_tenants, sla->quota_g, sla->quota_c};
+        if (keep) keep->min_seg = min_seg;
     }
     return rk_launch_allocate(ctx, jobs->ref_thr, table_dev(&tb), grid, n_rounds,
                               reinterpret_cast<const uint32_t *>(d_meta),
@@ -147,6 +156,27 @@ int32_t rk_schedule_round_sla(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bo
     const uint32_t off[2] = {0u, jobs->n_jobs};
     return schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, nullptr, cluster, jobs->n_jobs > 0 ? sla : nullptr, assign,
                            total);
+}
+
+int32_t rk_schedule_round_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                                 const rk_alloc_grid *grid, const rk_env *env, const rk_nodes *nodes, const rk_sla *sla,
+                                 rk_assign *assign, rk_assign *placed, uint32_t *place_off, rk_place_entry *entries,
+                                 uint64_t cap_entries, uint32_t *status, float *total, rk_place_result *result) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    if (!jobs || !nodes || !total) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (jobs->n_jobs > 0 && !placed) return rk_fail(ctx, RK_ERR_INVALID_ARG, "placed is null");
+    int32_t rc;
+    if (sla && jobs->n_jobs > 0 && (rc = rk_check_sla(ctx, sla, true))) return rc;
+    // the amounts are decided against what the nodes hold together, then the nodes are walked
+    const uint64_t G = (uint64_t)nodes->n_nodes * nodes->gpus_per_node, Cc = (uint64_t)nodes->n_nodes * nodes->cpus_per_node;
+    if (G > 0xFFFFFFFFull || Cc > 0xFFFFFFFFull) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "cluster too large");
+    const rk_cluster cluster = {(uint32_t)G, (uint32_t)Cc, (float)nodes->n_nodes * nodes->mem_per_node_gb};
+    const uint32_t off[2] = {0u, jobs->n_jobs};
+    RoundKeep keep;
+    if ((rc = schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, nullptr, &cluster, jobs->n_jobs > 0 ? sla : nullptr, assign,
+                              total, &keep))) return rc;
+    return rk_launch_place_plans(ctx, jobs, &keep.tb, grid, env, nodes, keep.best_thr, assign, keep.min_seg, placed, place_off,
+                                 entries, cap_entries, status, total, result);
 }
 
 }  // extern "C"
