@@ -300,6 +300,29 @@ def frozen_round(ref_thr, table, grid, cluster, best_thr, best_idx, curve_thr, s
     return assign, total.value, gap.value
 
 
+def reschedule(ref_thr, table, grid, cluster, best_thr, best_idx, curve_thr, cur_seg, cur_c, floor_seg=None, floor_c=None,
+               state=None):
+    """Algorithm 1's Schedule as a loop from the jobs' present state -> (records, total, steps committed)."""
+    gh = _GridHolder(grid)
+    J = table.n_jobs
+    f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    ref_thr, best_thr, curve_thr = f(ref_thr), f(best_thr), f(curve_thr)
+    best_idx = np.ascontiguousarray(best_idx, dtype=np.uint32)
+    cur_seg = np.ascontiguousarray(cur_seg, dtype=np.int32)
+    cur_c = np.ascontiguousarray(cur_c, dtype=np.uint32)
+    state = None if state is None else np.ascontiguousarray(state, dtype=np.uint8)
+    floor_seg = None if floor_seg is None else np.ascontiguousarray(floor_seg, dtype=np.int32)
+    floor_c = None if floor_c is None else np.ascontiguousarray(floor_c, dtype=np.uint32)
+    assign = np.zeros(J, ASSIGN_DTYPE)
+    total, moves = C.c_double(0), C.c_uint32(0)
+    rc = lib().ork_reschedule_f32(C.c_uint32(J), _p(ref_thr), C.byref(table.c), C.byref(gh.c), C.c_uint32(cluster.G),
+                                  C.c_uint32(cluster.C), C.c_float(cluster.host_mem_gb), _p(best_thr), _p(best_idx),
+                                  _p(curve_thr), _p(state), _p(cur_seg), _p(cur_c), _p(floor_seg), _p(floor_c), _p(assign),
+                                  C.byref(total), C.byref(moves))
+    assert rc == 0
+    return assign, total.value, moves.value
+
+
 PLACE_DTYPE = np.dtype([("node", np.uint32), ("g", np.uint32), ("c", np.uint32), ("mem_gb", np.float32)])
 
 

@@ -238,6 +238,10 @@ int greedy_from(uint32_t n_jobs, const float *ref_thr, const ork_table *tb, cons
                 std::vector<uint32_t> &ci, const std::vector<uint8_t> &waits, ork_assign *assign,
                 double *total, double *min_gap);
 
+int memory_step(uint32_t n_jobs, const float *ref_thr, const ork_table *tb, const ork_grid *grid, float host_mem_gb,
+                const float *best_thr, const uint32_t *best_plan, const std::vector<int64_t> &gi,
+                const std::vector<uint32_t> &ci, ork_assign *assign, double *total);
+
 uint32_t cpus_of(const ork_grid *grid, uint32_t ci, uint32_t g) {
     return grid->cpu_mode ? grid->cpu_levels[ci] * g : grid->cpu_levels[ci];
 }
@@ -767,6 +771,188 @@ int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, co
     return 0;
 }
 
+/* Algorithm 1's Schedule as the loop it is written as (Sec. 5.2, "Scheduling
+ * algorithm design" and the paragraph on shrinking), from the state the jobs
+ * are in: running jobs keep what they hold unless another job takes it.
+ *   - Privileged jobs first, in job order: the jobs that have a floor
+ *     (floor_seg >= 0) and hold fewer GPUs than it.  Then all other jobs that
+ *     take part, sorted once by their GPU slope, then their CPU slope (both
+ *     descending), then their index.
+ *   - ScheduleJob(j), for GPUs and then for CPUs: while j has a next step (for
+ *     a job below its floor: the step to the floor with the floor's CPU level;
+ *     otherwise the larger amount with the highest slope, as in the greedy,
+ *     whatever is free), the amount the step needs is gathered from what is
+ *     free and then from the other jobs, always from the one with the lowest
+ *     slope among those above their own floor (GetLowestSlopeOverMinJob; ties:
+ *     lower index).  The reallocation unit of a job is the distance to its
+ *     next useful amount: a job that gives steps down to the largest amount
+ *     with a lower throughput (to the smallest amount with the same throughput
+ *     when it holds more than it uses), never below its floor; its slope is
+ *     the normalised throughput it loses per unit it gives.  A job may be
+ *     shrunk when j's slope is higher than its slope, or when j is below its
+ *     floor.  The step is committed when everything was found and, unless j is
+ *     below its floor, j's gain exceeds what the others lose together;
+ *     otherwise every job is put back and j's search in this resource ends.
+ *     A GPU step must find its CPUs (at j's CPU level) free or freed by the
+ *     same shrinks.
+ *   - A job shrunk to nothing is preempted (best-effort jobs only: a job with
+ *     a floor stops there).  Memory last, as in the greedy.
+ * state[j] = 1: the job takes no part and holds nothing.  n_moves = steps
+ * committed.  PARITY UNPINNED as a reading (the paper gives the outline);
+ * pinned by hand cases for every rule above, by the greedy and the exhaustive
+ * optimum on concave curves from an empty cluster, and by invariants. */
+int ork_reschedule_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb, const ork_grid *grid,
+                       uint32_t G, uint32_t C, float host_mem_gb, const float *best_thr,
+                       const uint32_t *best_plan, const float *curve_thr, const uint8_t *state,
+                       const int32_t *cur_seg, const uint32_t *cur_c, const int32_t *floor_seg,
+                       const uint32_t *floor_c, ork_assign *assign, double *total, uint32_t *n_moves) {
+    const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    const uint32_t m_top = grid->n_mem - 1;
+    std::vector<int64_t> gi(n_jobs, -1);
+    std::vector<uint32_t> ci(n_jobs, 0);
+    auto ns_of = [&](uint32_t j) { return (int64_t)(tb->seg_off[j + 1] - tb->seg_off[j]); };
+    auto g_at = [&](uint32_t j, int64_t s) -> uint64_t { return s < 0 ? 0 : tb->seg_g[tb->seg_off[j] + s]; };
+    auto c_at = [&](uint32_t j, uint32_t c, int64_t s) -> uint64_t { return s < 0 ? 0 : cpus_of(grid, c, (uint32_t)g_at(j, s)); };
+    auto at = [&](const float *arr, uint32_t j, uint32_t c, int64_t s) -> float {
+        return s < 0 ? 0.0f : arr[rows * tb->seg_off[j] + ((uint64_t)c * grid->n_mem + m_top) * ns_of(j) + s];
+    };
+    auto part = [&](uint32_t j) { return !state || state[j] == 0; };
+    auto fl_s = [&](uint32_t j) -> int64_t { return floor_seg ? floor_seg[j] : -1; };
+    auto fl_c = [&](uint32_t j) -> uint32_t { return (floor_seg && floor_seg[j] >= 0 && floor_c) ? floor_c[j] : 0u; };
+
+    uint64_t heldG = 0, heldC = 0;
+    for (uint32_t j = 0; j < n_jobs; ++j) {
+        if (!part(j) || cur_seg[j] < 0 || cur_seg[j] >= ns_of(j) || cur_c[j] >= grid->n_cpu) continue;
+        gi[j] = cur_seg[j]; ci[j] = cur_c[j];
+        heldG += g_at(j, gi[j]); heldC += c_at(j, ci[j], gi[j]);
+    }
+    uint64_t freeG = heldG < G ? G - heldG : 0, freeC = heldC < C ? C - heldC : 0;
+    uint32_t moves = 0;
+
+    struct Step { bool any; int64_t tgt; uint32_t lvl; float slope, gain; uint64_t dg, dc; };
+    /* the next GPU step of job j: to its floor while below it, else the larger count with the highest slope */
+    auto up_gpu = [&](uint32_t j) {
+        Step st = {false, -1, ci[j], 0.0f, 0.0f, 0, 0};
+        const float cur = at(curve_thr, j, ci[j], gi[j]);
+        if (fl_s(j) >= 0 && gi[j] < fl_s(j)) {
+            const uint32_t lvl = std::max(ci[j], fl_c(j));
+            const float v = at(curve_thr, j, lvl, fl_s(j));
+            st.any = true; st.tgt = fl_s(j); st.lvl = lvl;
+            st.dg = g_at(j, fl_s(j)) - g_at(j, gi[j]);
+            st.dc = c_at(j, lvl, fl_s(j)) - c_at(j, ci[j], gi[j]);
+            st.gain = (v - cur) / ref_thr[j];
+            st.slope = st.gain / (float)st.dg;
+            return st;
+        }
+        for (int64_t s = gi[j] + 1; s < ns_of(j); ++s) {
+            const uint64_t dg = g_at(j, s) - g_at(j, gi[j]);
+            if (g_at(j, s) > G) break;
+            const float v = at(curve_thr, j, ci[j], s);
+            if (!(v > cur)) continue;
+            const float gain = (v - cur) / ref_thr[j];
+            const float sl = gain / (float)dg;
+            if (sl > st.slope) {
+                st.any = true; st.tgt = s; st.slope = sl; st.gain = gain; st.dg = dg;
+                st.dc = c_at(j, ci[j], s) - c_at(j, ci[j], gi[j]);
+            }
+        }
+        return st;
+    };
+    auto up_cpu = [&](uint32_t j) {
+        Step st = {false, gi[j], ci[j], 0.0f, 0.0f, 0, 0};
+        if (gi[j] < 0) return st;
+        const float cur = at(best_thr, j, ci[j], gi[j]);
+        for (uint32_t c = ci[j] + 1; c < grid->n_cpu; ++c) {
+            const uint64_t dc = c_at(j, c, gi[j]) - c_at(j, ci[j], gi[j]);
+            const float v = at(best_thr, j, c, gi[j]);
+            if (!(v > cur)) continue;
+            const float gain = (v - cur) / ref_thr[j];
+            const float sl = gain / (float)dc;
+            if (sl > st.slope) { st.any = true; st.lvl = c; st.slope = sl; st.gain = gain; st.dc = dc; }
+        }
+        return st;
+    };
+    /* what job v gives when it steps down in GPUs: target segment (-1 = everything), loss, units */
+    struct Give { bool any; int64_t tgt; float loss, slope; uint64_t dg, dc; };
+    auto down_gpu = [&](uint32_t v) {
+        Give gv = {false, -1, 0.0f, 0.0f, 0, 0};
+        if (gi[v] < 0 || (fl_s(v) >= 0 && gi[v] <= fl_s(v))) return gv;
+        const float V = at(curve_thr, v, ci[v], gi[v]);
+        /* down to where the curve's value just below begins: the largest amount with a lower throughput, or, when
+           the job holds more than it uses (same value just below), the smallest amount with the same throughput */
+        const float want = at(curve_thr, v, ci[v], gi[v] - 1);
+        int64_t t = -1;
+        if (want > 0.0f) for (t = 0; at(curve_thr, v, ci[v], t) != want; ++t) {}
+        if (fl_s(v) >= 0 && t < fl_s(v)) t = fl_s(v);
+        gv.any = true; gv.tgt = t;
+        gv.loss = (V - at(curve_thr, v, ci[v], t)) / ref_thr[v];
+        gv.dg = g_at(v, gi[v]) - g_at(v, t);
+        gv.dc = c_at(v, ci[v], gi[v]) - c_at(v, ci[v], t);
+        gv.slope = gv.loss / (float)gv.dg;
+        return gv;
+    };
+    auto down_cpu = [&](uint32_t v) {
+        Give gv = {false, gi[v], 0.0f, 0.0f, 0, 0};
+        const uint32_t lowest = (fl_s(v) >= 0) ? fl_c(v) : 0u;
+        if (gi[v] < 0 || ci[v] == 0 || ci[v] <= lowest) return gv;
+        gv.any = true;
+        gv.loss = (at(best_thr, v, ci[v], gi[v]) - at(best_thr, v, ci[v] - 1, gi[v])) / ref_thr[v];
+        gv.dc = c_at(v, ci[v], gi[v]) - c_at(v, ci[v] - 1, gi[v]);
+        gv.slope = gv.loss / (float)gv.dc;
+        return gv;
+    };
+
+    auto schedule_job = [&](uint32_t j) {
+        for (int res = 0; res < 2; ++res) {                 /* GPUs, then CPUs */
+            for (;;) {
+                const Step st = res == 0 ? up_gpu(j) : up_cpu(j);
+                if (!st.any) break;
+                const bool below_min = res == 0 && fl_s(j) >= 0 && gi[j] < fl_s(j);
+                uint64_t availG = freeG, availC = freeC;
+                std::vector<int64_t> keep_gi(gi);
+                std::vector<uint32_t> keep_ci(ci);
+                float lost = 0.0f;
+                bool ok = true;
+                while (res == 0 ? availG < st.dg : availC < st.dc) {
+                    int64_t pick = -1; Give best = {false, -1, 0.0f, 0.0f, 0, 0};
+                    for (uint32_t v = 0; v < n_jobs; ++v) {  /* GetLowestSlopeOverMinJob */
+                        if (v == j || !part(v)) continue;
+                        const Give gv = res == 0 ? down_gpu(v) : down_cpu(v);
+                        if (!gv.any) continue;
+                        if (pick < 0 || gv.slope < best.slope) { pick = v; best = gv; }
+                    }
+                    if (pick < 0 || !(below_min || st.slope > best.slope)) { ok = false; break; }
+                    availG += best.dg; availC += best.dc; lost = lost + best.loss;
+                    if (res == 0) { gi[pick] = best.tgt; if (best.tgt < 0) ci[pick] = 0; }
+                    else ci[pick] -= 1;
+                }
+                if (ok && (availG < st.dg || availC < st.dc)) ok = false;
+                if (ok && !below_min && !(st.gain > lost)) ok = false;
+                if (!ok) { gi = keep_gi; ci = keep_ci; break; }
+                freeG = availG - st.dg; freeC = availC - st.dc;
+                if (res == 0) gi[j] = st.tgt;
+                ci[j] = st.lvl;
+                ++moves;
+            }
+        }
+    };
+
+    std::vector<uint8_t> first(n_jobs, 0);
+    for (uint32_t j = 0; j < n_jobs; ++j)
+        if (part(j) && fl_s(j) >= 0 && fl_s(j) < ns_of(j) && gi[j] < fl_s(j)) { first[j] = 1; schedule_job(j); }
+    std::vector<uint32_t> order;
+    std::vector<float> sg(n_jobs, 0.0f), sc(n_jobs, 0.0f);
+    for (uint32_t j = 0; j < n_jobs; ++j)
+        if (part(j) && !first[j]) { order.push_back(j); sg[j] = up_gpu(j).slope; sc[j] = up_cpu(j).slope; }
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+        if (sg[a] != sg[b]) return sg[a] > sg[b];
+        return sc[a] > sc[b];
+    });
+    for (uint32_t j : order) schedule_job(j);
+    if (n_moves) *n_moves = moves;
+    return memory_step(n_jobs, ref_thr, tb, grid, host_mem_gb, best_thr, best_plan, gi, ci, assign, total);
+}
+
 }  // extern "C"
 
 namespace {
@@ -841,24 +1027,34 @@ int greedy_from(uint32_t n_jobs, const float *ref_thr, const ork_table *tb, cons
         freeC -= cpu_cost(tj, (uint32_t)tc, gi[tj]) - cpu_cost(tj, ci[tj], gi[tj]);
         ci[tj] = (uint32_t)tc;
     }
-    /* memory, then output */
+    if (min_gap) *min_gap = gap_min;
+    return memory_step(n_jobs, ref_thr, tb, grid, host_mem_gb, best_thr, best_plan, gi, ci, assign, total);
+}
+
+/* Memory, then output (Sec. 5.2: memory is allocated last, from the chosen plan's estimate): in job order, among the
+ * tiers that still fit, the one with the highest throughput (smallest such tier); none feasible: the job is dropped. */
+int memory_step(uint32_t n_jobs, const float *ref_thr, const ork_table *tb, const ork_grid *grid, float host_mem_gb,
+                const float *best_thr, const uint32_t *best_plan, const std::vector<int64_t> &gi,
+                const std::vector<uint32_t> &ci, ork_assign *assign, double *total) {
+    const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
     float freeM = host_mem_gb;
     double sum = 0.0;
     for (uint32_t j = 0; j < n_jobs; ++j) {
         ork_assign out = {0, 0, 0.0f, ORK_NO_PLAN, 0.0f};
         if (gi[j] >= 0) {
-            const uint32_t g = (uint32_t)g_of(j, gi[j]);
+            const uint64_t ns = tb->seg_off[j + 1] - tb->seg_off[j];
+            const uint32_t g = tb->seg_g[tb->seg_off[j] + gi[j]];
             float bv = 0.0f; int64_t bm = -1;
             for (uint32_t m = 0; m < grid->n_mem; ++m) {
                 if (!(tier_gb(grid, m, g) <= freeM)) continue;
-                const float v = at(best_thr, j, ci[j], m, gi[j]);
+                const float v = best_thr[rows * tb->seg_off[j] + ((uint64_t)ci[j] * grid->n_mem + m) * ns + gi[j]];
                 if (v > bv) { bv = v; bm = m; }
             }
             if (bm >= 0) {
                 const float cost = tier_gb(grid, (uint32_t)bm, g);
                 freeM = freeM - cost;
-                out.g = g; out.c = (uint32_t)cpu_cost(j, ci[j], gi[j]); out.mem_gb = cost;
-                out.plan = best_plan[rows * tb->seg_off[j] + ((uint64_t)ci[j] * grid->n_mem + bm) * ns_of(j) + gi[j]];
+                out.g = g; out.c = cpus_of(grid, ci[j], g); out.mem_gb = cost;
+                out.plan = best_plan[rows * tb->seg_off[j] + ((uint64_t)ci[j] * grid->n_mem + bm) * ns + gi[j]];
                 out.thr = bv;
                 sum += (double)bv / (double)ref_thr[j];
             }
@@ -866,7 +1062,6 @@ int greedy_from(uint32_t n_jobs, const float *ref_thr, const ork_table *tb, cons
         assign[j] = out;
     }
     if (total) *total = sum;
-    if (min_gap) *min_gap = gap_min;
     return 0;
 }
 

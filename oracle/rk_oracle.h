@@ -145,6 +145,18 @@ int ork_frozen_round_f32(uint32_t n_jobs, const float *ref_thr, const ork_table 
                          const uint8_t *state, const int32_t *cur_seg, const uint32_t *cur_c,
                          ork_assign *assign, double *total, double *min_gap);
 
+/* Algorithm 1's Schedule as a loop from the jobs' present state: privileged
+ * jobs (below their floor) first, the others by slope; every job takes what is
+ * free and shrinks the jobs with the lowest slope while that is permitted
+ * (rules at the definition).  state[j] = 1: takes no part (may be NULL);
+ * cur_seg / cur_c: what the job holds (-1: nothing); floor_seg / floor_c: its
+ * minimum demand (-1 or NULL: none). */
+int ork_reschedule_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *table, const ork_grid *grid,
+                       uint32_t G, uint32_t C, float host_mem_gb, const float *best_thr,
+                       const uint32_t *best_plan, const float *curve_thr, const uint8_t *state,
+                       const int32_t *cur_seg, const uint32_t *cur_c, const int32_t *floor_seg,
+                       const uint32_t *floor_c, ork_assign *assign, double *total, uint32_t *n_moves);
+
 /* Node-level placement of an allocation (Sec. 5.2, Algorithm 1, ScheduleJob:
  * a job walks the nodes in order, takes what each node has free and records
  * {node, resources}; it is placed only if its whole amount is found).  Jobs
