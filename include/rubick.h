@@ -261,6 +261,51 @@ int32_t rk_allocate_static(rk_ctx *ctx, const float *ref_thr, const rk_plan_tabl
                            const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
                            rk_assign *assign, float *total);
 
+/* What the jobs of the table hold and are guaranteed, all [device], one entry
+ * per job.  state: 0 the job takes part, 1 it takes no part and holds nothing
+ * (NULL: all take part).  cur_seg: index of the GPU count it holds in its
+ * list, -1 nothing; cur_c: the CPU level it holds.  floor_seg / floor_c: its
+ * minimum demand as rk_min_res gives it (-1, or NULL: none). */
+typedef struct {
+    const uint8_t *state;
+    const int32_t *cur_seg;
+    const uint32_t *cur_c;
+    const int32_t *floor_seg;
+    const uint32_t *floor_c;
+} rk_job_state;
+
+/* Algorithm 1's Schedule as the loop it is written as, from the state the jobs
+ * are in (Sec. 5.2 "Scheduling algorithm design" and the paragraph on shrinking:
+ * running jobs keep what they hold unless a job with a higher slope, or one
+ * below its minimum demand, takes it).  Over all jobs of the table, arrays in
+ * segment layout as for rk_allocate.
+ *  - Privileged jobs first, in job order: those with a floor that hold fewer
+ *    GPUs than it.  Then all others that take part, sorted once by their GPU
+ *    slope, then CPU slope (descending), then index.
+ *  - ScheduleJob(j), for GPUs and then CPUs: while j has a next step (below its
+ *    floor: to the floor with the floor's CPU level; otherwise the larger
+ *    amount with the highest float32 slope ((v1-v0)/ref_thr)/delta, the smaller
+ *    amount among equal slopes), what the step needs is gathered from what is
+ *    free, then from the other jobs, always the one with the lowest slope among
+ *    those above their own floor (GetLowestSlopeOverMinJob; lower index on
+ *    ties).  A job that gives steps down to the largest amount with a lower
+ *    throughput (the smallest with the same throughput if it holds more than
+ *    it uses), not below its floor; its slope is the normalised throughput it
+ *    loses per unit given.  It may be shrunk when j's slope is higher than its
+ *    own or j is below its floor.  The step is committed when all was found
+ *    (a GPU step needs its CPUs at j's level free or freed by the same shrinks)
+ *    and, unless j is below its floor, j gains more than the others lose;
+ *    otherwise every job is put back and j's search in that resource ends.
+ *  - Memory last, as in rk_allocate.  A job shrunk to nothing is preempted.
+ *   assign  [device] n_jobs records; total [device] one float
+ *   n_moves [device] one word or NULL: steps committed
+ * Limits: at most RK_MAX_JOBS_PER_ROUND jobs.  One workgroup runs the loop: the
+ * rule is sequential. */
+int32_t rk_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                      const rk_alloc_grid *grid, const rk_cluster *cluster,
+                      const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                      const rk_job_state *jobs_state, rk_assign *assign, float *total, uint32_t *n_moves);
+
 /* One scheduling round end to end: enumerate -> evaluate -> best plan ->
  * curves -> greedy allocation, all on the device.  Waits once for the plan
  * counts. assign [device] n_jobs records, total [device] one float. */

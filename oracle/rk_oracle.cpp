@@ -817,8 +817,13 @@ int ork_reschedule_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *t
         return s < 0 ? 0.0f : arr[rows * tb->seg_off[j] + ((uint64_t)c * grid->n_mem + m_top) * ns_of(j) + s];
     };
     auto part = [&](uint32_t j) { return !state || state[j] == 0; };
-    auto fl_s = [&](uint32_t j) -> int64_t { return floor_seg ? floor_seg[j] : -1; };
-    auto fl_c = [&](uint32_t j) -> uint32_t { return (floor_seg && floor_seg[j] >= 0 && floor_c) ? floor_c[j] : 0u; };
+    /* the job's floor: a segment the job does not have counts as none, the CPU level is clamped to the grid */
+    auto fl_s = [&](uint32_t j) -> int64_t {
+        return (floor_seg && floor_seg[j] >= 0 && floor_seg[j] < ns_of(j)) ? floor_seg[j] : -1;
+    };
+    auto fl_c = [&](uint32_t j) -> uint32_t {
+        return (fl_s(j) >= 0 && floor_c) ? std::min(floor_c[j], grid->n_cpu - 1) : 0u;
+    };
 
     uint64_t heldG = 0, heldC = 0;
     for (uint32_t j = 0; j < n_jobs; ++j) {
@@ -939,7 +944,7 @@ int ork_reschedule_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *t
 
     std::vector<uint8_t> first(n_jobs, 0);
     for (uint32_t j = 0; j < n_jobs; ++j)
-        if (part(j) && fl_s(j) >= 0 && fl_s(j) < ns_of(j) && gi[j] < fl_s(j)) { first[j] = 1; schedule_job(j); }
+        if (part(j) && fl_s(j) >= 0 && gi[j] < fl_s(j)) { first[j] = 1; schedule_job(j); }
     std::vector<uint32_t> order;
     std::vector<float> sg(n_jobs, 0.0f), sc(n_jobs, 0.0f);
     for (uint32_t j = 0; j < n_jobs; ++j)

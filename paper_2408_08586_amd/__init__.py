@@ -26,7 +26,7 @@ FIT_FIELDS = ("k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_con
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
            "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
            "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared", "rk_place", "rk_allocate_static", "rk_place_plans",
-           "rk_schedule_round_placed")
+           "rk_schedule_round_placed", "rk_reschedule")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -295,6 +295,19 @@ def rk_allocate_static(ctx, ref_thr, table, grid, cluster: rk_cluster, job_begin
     _check(ctx, load_library().rk_allocate_static(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.byref(cluster),
                                                   C.c_uint32(job_begin), C.c_uint32(job_end), _ptr(best_thr),
                                                   _ptr(best_plan), _ptr(curve_thr), _ptr(assign), _ptr(total)))
+
+
+class rk_job_state(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("state", "cur_seg", "cur_c", "floor_seg", "floor_c")]
+
+
+def rk_reschedule(ctx, ref_thr, table, grid, cluster: rk_cluster, best_thr, best_plan, curve_thr, cur_seg, cur_c, assign,
+                  total, state=None, floor_seg=None, floor_c=None, n_moves=None):
+    """Algorithm 1's Schedule loop from the jobs' present state (device tensors; state is uint8, cur_seg / floor_seg int32)."""
+    js = rk_job_state(_ptr(state), _ptr(cur_seg), _ptr(cur_c), _ptr(floor_seg), _ptr(floor_c))
+    _check(ctx, load_library().rk_reschedule(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.byref(cluster),
+                                             _ptr(best_thr), _ptr(best_plan), _ptr(curve_thr), C.byref(js), _ptr(assign),
+                                             _ptr(total), _ptr(n_moves)))
 
 
 def rk_schedule_round(ctx, jobs: Jobs, bounds, grid, env, cluster, assign, total):

@@ -1402,6 +1402,380 @@ __global__ __launch_bounds__(FLOOR_THREADS) void k_floors(Ctx X, JobState st, Sl
 }
 
 
+// ------------------------------------------------------------------ Algorithm 1's Schedule as a loop
+// From the state the jobs are in (paper Sec. 5.2, Algorithm 1 and the paragraph on shrinking): privileged jobs
+// (below their floor) first in job order, then the others sorted once by GPU slope, CPU slope, index.  A job takes
+// its next step (to its floor while below it, else the larger amount with the highest slope) when the amount can be
+// gathered from what is free and from the jobs with the lowest slope among those above their own floor, each of
+// which steps down to its next useful amount; a job may be shrunk when the taker's slope is higher than its own or
+// the taker is below its floor, and the step is committed when all was found and (unless the taker is below its
+// floor) the taker gains more than the others lose; otherwise everything is put back.
+//
+// One workgroup: the rule is sequential.  What is parallel is the search for a job's next step (a wavefront over
+// its amounts), the search for the job to shrink (all threads over cached slopes) and the order of the jobs (a
+// rank sort).  Control flow is the same for all threads; the first thread takes the decisions, LDS and barriers
+// carry them.
+constexpr int RS_THREADS = 1024;
+
+struct RsArgs {
+    Ctx X;
+    JobState st;                 // gi, g, ci: the state the loop works on (and the memory step reads)
+    uint32_t n_jobs;
+    unsigned long long G, C;
+    const uint8_t *state;        // may be null
+    const int32_t *cur_seg;
+    const uint32_t *cur_c;
+    const int32_t *floor_seg;    // may be null
+    const uint32_t *floor_c;     // may be null
+    float *ds_g, *ds_c;          // per job: what it loses per GPU / CPU it gives (infinite: gives nothing)
+    float *sg, *sc;              // per job: slopes the order is taken from
+    uint32_t *order, *touched, *stamp, *first;
+    int32_t *keep_gi;
+    uint32_t *keep_ci;
+    uint32_t *n_moves;           // may be null
+};
+
+struct RsStep { uint32_t any; int32_t tgt; uint32_t lvl; float slope, gain; unsigned long long dg, dc; };
+struct RsGive { uint32_t any; int32_t tgt; float loss, slope; unsigned long long dg, dc; };
+
+__device__ __forceinline__ uint32_t rs_ns(const RsArgs &A, uint32_t j) { return A.X.tb.seg_off[j + 1] - A.X.tb.seg_off[j]; }
+__device__ __forceinline__ unsigned long long rs_g(const RsArgs &A, uint32_t j, int32_t s) {
+    return s < 0 ? 0ull : A.X.tb.seg_g[A.X.tb.seg_off[j] + (uint32_t)s];
+}
+__device__ __forceinline__ unsigned long long rs_c(const RsArgs &A, uint32_t j, uint32_t c, int32_t s) {
+    return s < 0 ? 0ull : cpu_cost(A.X.grid, c, (uint32_t)rs_g(A, j, s));
+}
+// value of job j at CPU level c, top memory tier, segment s (0 below the first segment)
+__device__ __forceinline__ float rs_at(const RsArgs &A, const float *arr, uint32_t j, uint32_t c, int32_t s) {
+    if (s < 0) return 0.f;
+    const uint32_t n_mem = A.X.grid.n_mem, ns = rs_ns(A, j);
+    return arr[(uint64_t)A.X.grid.n_cpu * n_mem * A.X.tb.seg_off[j] + ((uint64_t)c * n_mem + (n_mem - 1)) * ns + (uint32_t)s];
+}
+__device__ __forceinline__ bool rs_part(const RsArgs &A, uint32_t j) { return !A.state || A.state[j] == 0; }
+// the job's floor: segment (-1: none; a segment the job does not have counts as none) and CPU level (clamped)
+__device__ __forceinline__ int32_t rs_fl_s(const RsArgs &A, uint32_t j) {
+    if (!A.floor_seg) return -1;
+    const int32_t f = A.floor_seg[j];
+    return (f >= 0 && (uint32_t)f < rs_ns(A, j)) ? f : -1;
+}
+__device__ __forceinline__ uint32_t rs_fl_c(const RsArgs &A, uint32_t j) {
+    if (rs_fl_s(A, j) < 0 || !A.floor_c) return 0u;
+    const uint32_t c = A.floor_c[j];
+    return c < A.X.grid.n_cpu ? c : A.X.grid.n_cpu - 1u;
+}
+
+// Next GPU step of job j.  `lanes` threads share the candidates (1: the calling thread alone; 64: a wavefront, all
+// lanes get the result).  Highest slope, the smaller amount among equal slopes.
+__device__ RsStep rs_up_gpu(const RsArgs &A, uint32_t j, uint32_t lane, uint32_t lanes) {
+    RsStep st = {0u, -1, A.st.ci[j], 0.f, 0.f, 0ull, 0ull};
+    const int32_t gi = A.st.gi[j];
+    const uint32_t ci = A.st.ci[j];
+    const float ref = A.X.ref_thr[j];
+    const float cur = rs_at(A, A.X.curve_thr, j, ci, gi);
+    const int32_t fl = rs_fl_s(A, j);
+    if (fl >= 0 && gi < fl) {
+        const uint32_t lvl = ci > rs_fl_c(A, j) ? ci : rs_fl_c(A, j);
+        const float v = rs_at(A, A.X.curve_thr, j, lvl, fl);
+        st.any = 1u; st.tgt = fl; st.lvl = lvl;
+        st.dg = rs_g(A, j, fl) - rs_g(A, j, gi);
+        st.dc = rs_c(A, j, lvl, fl) - rs_c(A, j, ci, gi);
+        st.gain = (v - cur) / ref;
+        st.slope = st.gain / (float)st.dg;
+        return st;
+    }
+    const int32_t ns = (int32_t)rs_ns(A, j);
+    unsigned long long key = 0;                            // slope bits, then the inverted segment index
+    for (int32_t s = gi + 1 + (int32_t)lane; s < ns; s += (int32_t)lanes) {
+        if (rs_g(A, j, s) > A.G) break;
+        const float v = rs_at(A, A.X.curve_thr, j, ci, s);
+        if (!(v > cur)) continue;
+        const unsigned long long dg = rs_g(A, j, s) - rs_g(A, j, gi);
+        const float gain = (v - cur) / ref;
+        const float sl = gain / (float)dg;
+        if (!(sl > 0.f)) continue;
+        const unsigned long long k = ((unsigned long long)__float_as_uint(sl) << 32) | (0xFFFFFFFFu - (uint32_t)s);
+        key = k > key ? k : key;
+    }
+    if (lanes > 1) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const unsigned long long o = __shfl_xor(key, off, 64);
+            key = o > key ? o : key;
+        }
+    }
+    if (key) {
+        const int32_t s = (int32_t)(0xFFFFFFFFu - (uint32_t)key);
+        const float v = rs_at(A, A.X.curve_thr, j, ci, s);
+        st.any = 1u; st.tgt = s;
+        st.dg = rs_g(A, j, s) - rs_g(A, j, gi);
+        st.dc = rs_c(A, j, ci, s) - rs_c(A, j, ci, gi);
+        st.gain = (v - cur) / ref;
+        st.slope = st.gain / (float)st.dg;
+    }
+    return st;
+}
+
+__device__ RsStep rs_up_cpu(const RsArgs &A, uint32_t j, uint32_t lane, uint32_t lanes) {
+    const int32_t gi = A.st.gi[j];
+    const uint32_t ci = A.st.ci[j];
+    RsStep st = {0u, gi, ci, 0.f, 0.f, 0ull, 0ull};
+    if (gi < 0) return st;
+    const float ref = A.X.ref_thr[j];
+    const float cur = rs_at(A, A.X.best_thr, j, ci, gi);
+    unsigned long long key = 0;
+    for (uint32_t c = ci + 1 + lane; c < A.X.grid.n_cpu; c += lanes) {
+        const float v = rs_at(A, A.X.best_thr, j, c, gi);
+        if (!(v > cur)) continue;
+        const unsigned long long dc = rs_c(A, j, c, gi) - rs_c(A, j, ci, gi);
+        const float gain = (v - cur) / ref;
+        const float sl = gain / (float)dc;
+        if (!(sl > 0.f)) continue;
+        const unsigned long long k = ((unsigned long long)__float_as_uint(sl) << 32) | (0xFFFFFFFFu - c);
+        key = k > key ? k : key;
+    }
+    if (lanes > 1) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const unsigned long long o = __shfl_xor(key, off, 64);
+            key = o > key ? o : key;
+        }
+    }
+    if (key) {
+        const uint32_t c = 0xFFFFFFFFu - (uint32_t)key;
+        const float v = rs_at(A, A.X.best_thr, j, c, gi);
+        st.any = 1u; st.lvl = c;
+        st.dc = rs_c(A, j, c, gi) - rs_c(A, j, ci, gi);
+        st.gain = (v - cur) / ref;
+        st.slope = st.gain / (float)st.dc;
+    }
+    return st;
+}
+
+// What job v gives when it steps down in GPUs: to where the curve's value just below its amount begins (the largest
+// amount with a lower throughput, or the smallest with the same one when it holds more than it uses), not below
+// its floor.  The curve does not fall along a row, so that place is found by bisection.
+__device__ RsGive rs_down_gpu(const RsArgs &A, uint32_t v) {
+    RsGive gv = {0u, -1, 0.f, 0.f, 0ull, 0ull};
+    const int32_t gi = A.st.gi[v];
+    const int32_t fl = rs_fl_s(A, v);
+    if (!rs_part(A, v) || gi < 0 || (fl >= 0 && gi <= fl)) return gv;
+    const uint32_t ci = A.st.ci[v];
+    const float V = rs_at(A, A.X.curve_thr, v, ci, gi);
+    const float want = rs_at(A, A.X.curve_thr, v, ci, gi - 1);
+    int32_t t = -1;
+    if (want > 0.f) {
+        int32_t lo = 0, hi = gi - 1;                       // first segment whose value reaches `want`
+        while (lo < hi) {
+            const int32_t mid = (lo + hi) >> 1;
+            if (rs_at(A, A.X.curve_thr, v, ci, mid) >= want) hi = mid; else lo = mid + 1;
+        }
+        t = lo;
+    }
+    if (fl >= 0 && t < fl) t = fl;
+    gv.any = 1u; gv.tgt = t;
+    gv.loss = (V - rs_at(A, A.X.curve_thr, v, ci, t)) / A.X.ref_thr[v];
+    gv.dg = rs_g(A, v, gi) - rs_g(A, v, t);
+    gv.dc = rs_c(A, v, ci, gi) - rs_c(A, v, ci, t);
+    gv.slope = gv.loss / (float)gv.dg;
+    return gv;
+}
+
+__device__ RsGive rs_down_cpu(const RsArgs &A, uint32_t v) {
+    const int32_t gi = A.st.gi[v];
+    RsGive gv = {0u, gi, 0.f, 0.f, 0ull, 0ull};
+    const uint32_t ci = A.st.ci[v];
+    const uint32_t lowest = rs_fl_s(A, v) >= 0 ? rs_fl_c(A, v) : 0u;
+    if (!rs_part(A, v) || gi < 0 || ci == 0 || ci <= lowest) return gv;
+    gv.any = 1u;
+    gv.loss = (rs_at(A, A.X.best_thr, v, ci, gi) - rs_at(A, A.X.best_thr, v, ci - 1, gi)) / A.X.ref_thr[v];
+    gv.dc = rs_c(A, v, ci, gi) - rs_c(A, v, ci - 1, gi);
+    gv.slope = gv.loss / (float)gv.dc;
+    return gv;
+}
+
+// the cached slopes of job v after its state changed
+__device__ __forceinline__ void rs_refresh(const RsArgs &A, uint32_t v) {
+    const RsGive a = rs_down_gpu(A, v), b = rs_down_cpu(A, v);
+    A.ds_g[v] = a.any ? a.slope : __int_as_float(0x7F800000);
+    A.ds_c[v] = b.any ? b.slope : __int_as_float(0x7F800000);
+}
+
+__global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
+    __shared__ RsStep sh_step;
+    __shared__ unsigned long long sh_free[2], sh_avail[2], sh_held[2][RS_THREADS / 64];
+    __shared__ float sh_lost, sh_wmin[RS_THREADS / 64];
+    __shared__ uint32_t sh_widx[RS_THREADS / 64];
+    __shared__ uint32_t sh_ok, sh_go, sh_touched, sh_epoch, sh_moves, sh_nb;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t J = A.n_jobs;
+    const float INF = __int_as_float(0x7F800000);
+
+    // the state the jobs are in, and what they hold together
+    unsigned long long hg = 0, hc = 0;
+    for (uint32_t j = tid; j < J; j += RS_THREADS) {
+        int32_t gi = -1;
+        uint32_t ci = 0;
+        if (rs_part(A, j) && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < rs_ns(A, j) && A.cur_c[j] < A.X.grid.n_cpu) {
+            gi = A.cur_seg[j]; ci = A.cur_c[j];
+            hg += rs_g(A, j, gi); hc += rs_c(A, j, ci, gi);
+        }
+        A.st.gi[j] = gi; A.st.ci[j] = ci;
+        A.stamp[j] = 0u; A.first[j] = 0u;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) { hg += __shfl_xor(hg, off, 64); hc += __shfl_xor(hc, off, 64); }
+    if (lane == 0) { sh_held[0][wave] = hg; sh_held[1][wave] = hc; }
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long g = 0, c = 0;
+        for (uint32_t w = 0; w < RS_THREADS / 64; ++w) { g += sh_held[0][w]; c += sh_held[1][w]; }
+        sh_free[0] = g < A.G ? A.G - g : 0ull;
+        sh_free[1] = c < A.C ? A.C - c : 0ull;
+        sh_epoch = 0u; sh_moves = 0u;
+    }
+    for (uint32_t j = tid; j < J; j += RS_THREADS) rs_refresh(A, j);
+    __syncthreads();
+
+    // ScheduleJob(j); the same code path for all threads
+    auto schedule_job = [&](uint32_t j) {
+        for (uint32_t res = 0; res < 2; ++res) {
+            for (;;) {
+                if (wave == 0) {
+                    const RsStep st = res == 0 ? rs_up_gpu(A, j, lane, 64) : rs_up_cpu(A, j, lane, 64);
+                    if (lane == 0) {
+                        sh_step = st;
+                        sh_avail[0] = sh_free[0]; sh_avail[1] = sh_free[1];
+                        sh_lost = 0.f; sh_ok = 1u; sh_touched = 0u; sh_epoch += 1u;
+                    }
+                }
+                __syncthreads();
+                const RsStep st = sh_step;
+                if (!st.any) { __syncthreads(); break; }
+                const bool below_min = res == 0 && rs_fl_s(A, j) >= 0 && A.st.gi[j] < rs_fl_s(A, j);
+                const unsigned long long need = res == 0 ? st.dg : st.dc;
+                while (sh_ok && sh_avail[res] < need) {
+                    // the job with the lowest slope among those that can give (GetLowestSlopeOverMinJob); ties: lower index
+                    const float *ds = res == 0 ? A.ds_g : A.ds_c;
+                    float best = INF;
+                    uint32_t who = 0xFFFFFFFFu;
+                    for (uint32_t v = tid; v < J; v += RS_THREADS) {
+                        const float s = ds[v];
+                        if (v != j && s < best) { best = s; who = v; }
+                    }
+#pragma unroll
+                    for (int off = 32; off >= 1; off >>= 1) {
+                        const float ob = __shfl_xor(best, off, 64);
+                        const uint32_t ow = __shfl_xor(who, off, 64);
+                        if (ob < best || (ob == best && ow < who)) { best = ob; who = ow; }
+                    }
+                    if (lane == 0) { sh_wmin[wave] = best; sh_widx[wave] = who; }
+                    __syncthreads();
+                    if (tid == 0) {
+                        float b2 = INF;
+                        uint32_t w2 = 0xFFFFFFFFu;
+                        for (uint32_t w = 0; w < RS_THREADS / 64; ++w)
+                            if (sh_wmin[w] < b2 || (sh_wmin[w] == b2 && sh_widx[w] < w2)) { b2 = sh_wmin[w]; w2 = sh_widx[w]; }
+                        if (w2 == 0xFFFFFFFFu || !(b2 < INF) || !(below_min || st.slope > b2)) {
+                            sh_ok = 0u;
+                        } else {
+                            const RsGive gv = res == 0 ? rs_down_gpu(A, w2) : rs_down_cpu(A, w2);
+                            if (A.stamp[w2] != sh_epoch) {          // first time this job gives in this step: remember its state
+                                A.stamp[w2] = sh_epoch;
+                                A.keep_gi[w2] = A.st.gi[w2]; A.keep_ci[w2] = A.st.ci[w2];
+                                A.touched[sh_touched++] = w2;
+                            }
+                            sh_avail[0] += gv.dg; sh_avail[1] += gv.dc;
+                            sh_lost = sh_lost + gv.loss;
+                            if (res == 0) { A.st.gi[w2] = gv.tgt; if (gv.tgt < 0) A.st.ci[w2] = 0u; }
+                            else A.st.ci[w2] -= 1u;
+                            rs_refresh(A, w2);
+                        }
+                    }
+                    __syncthreads();
+                }
+                if (tid == 0) {
+                    bool ok = sh_ok != 0u;
+                    if (ok && (sh_avail[0] < st.dg || sh_avail[1] < st.dc)) ok = false;
+                    if (ok && !below_min && !(st.gain > sh_lost)) ok = false;
+                    if (!ok) {
+                        for (uint32_t i = 0; i < sh_touched; ++i) {
+                            const uint32_t v = A.touched[i];
+                            A.st.gi[v] = A.keep_gi[v]; A.st.ci[v] = A.keep_ci[v];
+                            rs_refresh(A, v);
+                        }
+                    } else {
+                        sh_free[0] = sh_avail[0] - st.dg; sh_free[1] = sh_avail[1] - st.dc;
+                        if (res == 0) A.st.gi[j] = st.tgt;
+                        A.st.ci[j] = st.lvl;
+                        rs_refresh(A, j);
+                        sh_moves += 1u;
+                    }
+                    sh_go = ok ? 1u : 0u;
+                }
+                __syncthreads();
+                const uint32_t go = sh_go;
+                __syncthreads();
+                if (!go) break;
+            }
+        }
+    };
+
+    // privileged jobs, in job order.  Who they are is known from the start: a job never gives below its floor, so
+    // only a job that begins below it can be below it.
+    for (uint32_t j = tid; j < J; j += RS_THREADS) {
+        const int32_t fl = rs_fl_s(A, j);
+        A.first[j] = (rs_part(A, j) && fl >= 0 && A.st.gi[j] < fl) ? 1u : 0u;
+    }
+    if (tid == 0) sh_nb = 0u;
+    __syncthreads();
+    {
+        uint32_t mine = 0;
+        for (uint32_t j = tid; j < J; j += RS_THREADS) {
+            if (!A.first[j]) continue;
+            uint32_t pos = 0;
+            for (uint32_t i = 0; i < j; ++i) pos += A.first[i];
+            A.order[pos] = j;
+            ++mine;
+        }
+        atomicAdd(&sh_nb, mine);
+    }
+    __syncthreads();
+    const uint32_t na = sh_nb;
+    for (uint32_t k = 0; k < na; ++k) schedule_job(A.order[k]);
+    __syncthreads();
+    // the others, sorted once by GPU slope, CPU slope (descending), index
+    for (uint32_t j = tid; j < J; j += RS_THREADS) {
+        const bool in = rs_part(A, j) && !A.first[j];
+        A.sg[j] = in ? rs_up_gpu(A, j, 0, 1).slope : -1.f;      // -1: not in the list
+        A.sc[j] = in ? rs_up_cpu(A, j, 0, 1).slope : -1.f;
+    }
+    __syncthreads();
+    for (uint32_t j = tid; j < J; j += RS_THREADS) {
+        const float gj = A.sg[j], cj = A.sc[j];
+        if (gj < 0.f) continue;
+        uint32_t rank = 0;
+        for (uint32_t i = 0; i < J; ++i) {
+            const float gi2 = A.sg[i], ci2 = A.sc[i];
+            if (gi2 < 0.f) continue;
+            rank += (gi2 > gj || (gi2 == gj && (ci2 > cj || (ci2 == cj && i < j)))) ? 1u : 0u;
+        }
+        A.order[rank] = j;
+    }
+    if (tid == 0) sh_nb = 0u;
+    __syncthreads();
+    {
+        uint32_t mine = 0;
+        for (uint32_t j = tid; j < J; j += RS_THREADS) mine += A.sg[j] >= 0.f ? 1u : 0u;
+        atomicAdd(&sh_nb, mine);
+    }
+    __syncthreads();
+    const uint32_t nb = sh_nb;
+    for (uint32_t k = 0; k < nb; ++k) schedule_job(A.order[k]);
+    __syncthreads();
+    for (uint32_t j = tid; j < J; j += RS_THREADS) A.st.g[j] = (uint32_t)rs_g(A, j, A.st.gi[j]);
+    if (tid == 0 && A.n_moves) *A.n_moves = sh_moves;
+}
+
 // Scratch of rk_allocate_static: one array in the library's image, so every device the library is loaded on holds
 // its own copy at its own address for as long as the process lives.  The name is a host-side stand-in only: host
 // code uses the address that hipGetSymbolAddress returned for the context's device (rk_ctx::static_scratch).
@@ -1581,6 +1955,63 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
         RK_CHECK_LAUNCH(ctx, "k_mem_wish");
     }
     k_mem_finish<<<n_rounds, 64, 0, s>>>(X, st, assign, totals);
+    RK_CHECK_LAUNCH(ctx, "k_mem_finish");
+    return RK_OK;
+}
+
+extern "C" int32_t rk_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                                 const rk_alloc_grid *grid, const rk_cluster *cluster, const float *best_thr,
+                                 const uint32_t *best_plan, const float *curve_thr, const rk_job_state *jobs_state,
+                                 rk_assign *assign, float *total, uint32_t *n_moves) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if ((rc = rk_check_table(ctx, table, 0, table ? table->n_jobs : 0))) return rc;
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    if (!cluster || !total || !jobs_state) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    const uint32_t J = table->n_jobs;
+    if (J > 0 && (!ref_thr || !assign || !jobs_state->cur_seg || !jobs_state->cur_c ||
+                  (table->n_segs > 0 && (!best_thr || !best_plan || !curve_thr))))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (!(cluster->host_mem_gb >= 0.f)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "host_mem_gb negative or NaN");
+    if (table->max_segs_per_job > 32767u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 32767 segments per job");
+    if (J > RK_MAX_JOBS_PER_ROUND)
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "%u jobs, the allocation kernels take up to %u", J, RK_MAX_JOBS_PER_ROUND);
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    Arena arena = {nullptr, 0, 0};
+    const size_t n = J ? J : 1;
+    RsArgs A;
+    JobState &st = A.st;
+    st = JobState{};
+    st.blocks_per_round = (J + JOB_THREADS - 1) / JOB_THREADS;
+    if (st.blocks_per_round == 0) st.blocks_per_round = 1;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_GI, n, &st.gi))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_G, n, &st.g))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_CI, n, &st.ci))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_PARTIAL, (size_t)st.blocks_per_round * 2, &st.partial))) return rc;
+    float *f32;
+    uint32_t *u32;
+    if ((rc = scratch_typed(ctx, arena, SL_RS_F32, n * 4, &f32))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_RS_U32, n * 6, &u32))) return rc;
+    A.ds_g = f32; A.ds_c = f32 + n; A.sg = f32 + 2 * n; A.sc = f32 + 3 * n;
+    A.order = u32; A.touched = u32 + n; A.stamp = u32 + 2 * n; A.first = u32 + 3 * n;
+    A.keep_gi = reinterpret_cast<int32_t *>(u32 + 4 * n); A.keep_ci = u32 + 5 * n;
+    Ctx &X = A.X;
+    X.ref_thr = ref_thr; X.tb = table_dev(table); X.grid = grid_dev(grid); X.jb = 0; X.jmap = nullptr;
+    X.best_thr = best_thr; X.best_plan = best_plan; X.curve_thr = curve_thr;
+    X.R.round_off = nullptr; X.R.clusters = nullptr; X.R.n_rounds = 1; X.R.inline_one = 1u;
+    X.R.off0 = 0; X.R.off1 = J; X.R.cl = *cluster;
+    A.n_jobs = J; A.G = cluster->G; A.C = cluster->C;
+    A.state = jobs_state->state; A.cur_seg = jobs_state->cur_seg; A.cur_c = jobs_state->cur_c;
+    A.floor_seg = jobs_state->floor_seg; A.floor_c = jobs_state->floor_c;
+    A.n_moves = n_moves;
+    hipStream_t s = ctx->stream;
+    k_reschedule<<<1, RS_THREADS, 0, s>>>(A);
+    RK_CHECK_LAUNCH(ctx, "k_reschedule");
+    if (J > 0) {
+        k_mem_wish<<<dim3(st.blocks_per_round, 1), JOB_THREADS, 0, s>>>(X, st, assign);
+        RK_CHECK_LAUNCH(ctx, "k_mem_wish");
+    }
+    k_mem_finish<<<1, 64, 0, s>>>(X, st, assign, total);
     RK_CHECK_LAUNCH(ctx, "k_mem_finish");
     return RK_OK;
 }

@@ -9,7 +9,7 @@
 
 #include "rubick.h"
 
-enum { RK_SCRATCH_SLOTS = 48 };
+enum { RK_SCRATCH_SLOTS = 56 };
 
 struct rk_ctx {
     int device;
@@ -46,7 +46,8 @@ enum {
     SL_JMAP,                                             // rounds that share jobs: slot -> job
     SL_ENUM_BACK,                                        // enumeration: totals and offsets in one piece for the host
     SL_PLACE_RESULT,                                     // placement: its four summary words
-    SL_ENUM_LEADER                                       // enumeration: the job whose search a job shares
+    SL_ENUM_LEADER,                                      // enumeration: the job whose search a job shares
+    SL_RS_F32, SL_RS_U32                                 // the Schedule loop: cached slopes; order, marks and saved states
 };
 
 int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);

@@ -42,7 +42,7 @@ def test_header_functions_are_exported(rk):
 
 
 def test_struct_layouts_match_the_header(rk):
-    structs = ["rk_jobs", "rk_plan_bounds", "rk_plan_table", "rk_alloc_grid", "rk_env", "rk_cluster", "rk_assign", "rk_sla", "rk_samples", "rk_fit_options", "rk_fit_result", "rk_trace", "rk_sim_options", "rk_sim_result", "rk_nodes", "rk_place_entry", "rk_place_result"]
+    structs = ["rk_jobs", "rk_plan_bounds", "rk_plan_table", "rk_alloc_grid", "rk_env", "rk_cluster", "rk_assign", "rk_sla", "rk_samples", "rk_fit_options", "rk_fit_result", "rk_trace", "rk_sim_options", "rk_sim_result", "rk_nodes", "rk_place_entry", "rk_place_result", "rk_job_state"]
     prog = ['#include <stdio.h>', '#include <stddef.h>', '#include "rubick.h"', 'int main(void){']
     for s in structs:
         prog.append(f'printf("{s} %zu\\n", sizeof({s}));')
@@ -58,7 +58,8 @@ def test_struct_layouts_match_the_header(rk):
               "rk_sim_result": ["n_reconf", "held", "totals", "frozen"],
               "rk_nodes": ["gpus_per_node", "cpus_per_node", "mem_per_node_gb"],
               "rk_place_entry": ["node", "g", "c", "mem_gb"],
-              "rk_place_result": ["n_placed", "n_failed", "in_order"]}
+              "rk_place_result": ["n_placed", "n_failed", "in_order"],
+              "rk_job_state": ["cur_seg", "cur_c", "floor_seg", "floor_c"]}
     for s, fs in fields.items():
         for f in fs:
             prog.append(f'printf("{s}.{f} %zu\\n", offsetof({s}, {f}));')
@@ -73,7 +74,7 @@ def test_struct_layouts_match_the_header(rk):
           "rk_alloc_grid": rk.rk_alloc_grid, "rk_env": rk.rk_env, "rk_cluster": rk.rk_cluster, "rk_sla": rk.rk_sla,
           "rk_samples": rk.rk_samples, "rk_fit_options": rk.rk_fit_options, "rk_fit_result": rk.rk_fit_result,
           "rk_trace": rk.rk_trace, "rk_sim_options": rk.rk_sim_options, "rk_sim_result": rk.rk_sim_result,
-          "rk_nodes": rk.rk_nodes, "rk_place_result": rk.rk_place_result}
+          "rk_nodes": rk.rk_nodes, "rk_place_result": rk.rk_place_result, "rk_job_state": rk.rk_job_state}
     for s, cls in py.items():
         assert C.sizeof(cls) == int(want[s]), s
         for f in fields.get(s, []):

@@ -1,0 +1,176 @@
+"""GPU parity of rk_reschedule (Algorithm 1's Schedule as a loop from the jobs'
+present state) against the oracle's ork_reschedule_f32 on shared float32
+inputs: records, totals and the number of committed steps must be identical."""
+import numpy as np
+import pytest
+
+import workloads
+from test_oracle_reschedule import table_for
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from gpu_harness import DeviceRun
+    return DeviceRun
+
+
+def on_gpu(run, bt, bp, ct, cluster, cur_seg, cur_c, floor_seg, floor_c, state):
+    import torch
+    import paper_2408_08586_amd as rk
+    J = run.wl.n_jobs
+    dev = run.device
+    i32 = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    u8 = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint8)).to(dev)
+    assign, total = rk.new_assign(J, dev), run.f32(1)
+    moves = torch.zeros(4, dtype=torch.int32, device=dev)
+    rk.rk_reschedule(run.ctx, run.jobs.ref_thr, run.table.c, run.grid, rk.make_cluster(cluster), run.dev_f32(bt), run.dev_u32(bp),
+                     run.dev_f32(ct), i32(cur_seg), run.dev_u32(cur_c), assign, total, state=u8(state), floor_seg=i32(floor_seg),
+                     floor_c=None if floor_c is None else run.dev_u32(floor_c), n_moves=moves)
+    rk.rk_sync(run.ctx)
+    return rk.assign_to_numpy(assign), float(total[0].item()), int(moves[0].item())
+
+
+def same(got, want):
+    assert np.array_equal(got[0], want[0]), np.flatnonzero(got[0] != want[0])[:5]
+    assert got[1] == pytest.approx(want[1], rel=1e-6, abs=1e-12)
+    assert got[2] == want[2]
+
+
+def random_round(rng, orc):
+    """A round on drawn values: every GPU count 1..g_max is a segment, some counts are not valid (value 0), several CPU
+    levels and memory tiers in either mode, a random present state with floors and jobs that take no part."""
+    J, g_max = int(rng.integers(1, 41)), int(rng.integers(2, 17))
+    n_cpu, n_mem = int(rng.integers(1, 5)), int(rng.integers(1, 4))
+    tb = table_for(orc, J, g_max)
+    grid = workloads.Grid(np.sort(rng.choice(np.arange(1, 9), n_cpu, replace=False)).astype(np.uint32), int(rng.integers(0, 2)),
+                          np.sort(rng.choice(np.array([0, 4, 16, 64], np.float32), n_mem, replace=False)).astype(np.float32),
+                          int(rng.integers(0, 2)))
+    bt = np.zeros((J, n_cpu, n_mem, g_max), np.float32)
+    for j in range(J):
+        valid = np.unique(np.concatenate([[1], rng.choice(np.arange(1, g_max + 1), int(rng.integers(1, 6)))]))
+        base = np.zeros(g_max)
+        base[valid - 1] = np.cumsum(np.sort(rng.uniform(0.2, 2.0, len(valid)))[::-1] * rng.uniform(0.5, 1.5, len(valid)))
+        base = np.round(base * 16) / 16                                      # coarse: exact ties do occur
+        for c in range(n_cpu):
+            for m in range(n_mem):
+                v = base * (1 + 0.25 * c * rng.uniform(0, 1)) * (1.0 if m == n_mem - 1 else rng.choice([0.0, 0.8, 1.0]))
+                bt[j, c, m] = np.round(v * 16) / 16
+        bt[j] = np.maximum.accumulate(np.maximum.accumulate(bt[j], axis=0), axis=1)   # more CPUs or memory never hurt
+    flat = bt.reshape(-1)
+    bp = rng.integers(0, 1000, flat.size).astype(np.uint32)
+    bp[flat == 0] = orc.NO_PLAN
+    ct, _, _ = orc.curves(tb, grid, flat, bp)
+    ref = rng.uniform(0.5, 2.0, J).astype(np.float32)
+    G = int(rng.integers(0, 3 * g_max + 1))
+    cl = workloads.Cluster(G, int(rng.integers(0, 12 * max(G, 1))), float(rng.choice([0.0, 16.0, 200.0, 1e6])))
+    cur_seg, cur_c = np.full(J, -1, np.int32), np.zeros(J, np.uint32)
+    floor_seg, floor_c = np.full(J, -1, np.int32), np.zeros(J, np.uint32)
+    left = G
+    for j in rng.permutation(J).tolist():
+        ok = np.flatnonzero(bt[j, 0, n_mem - 1] > 0)
+        if rng.uniform() < 0.3:
+            floor_seg[j], floor_c[j] = int(rng.choice(ok)), int(rng.integers(0, n_cpu))
+        if rng.uniform() < 0.5:
+            fit = ok[(ok + 1 <= left) & (ok >= floor_seg[j])] if rng.uniform() < 0.9 else ok[ok + 1 <= left]
+            if fit.size:
+                cur_seg[j], cur_c[j] = int(rng.choice(fit)), int(rng.integers(0, n_cpu))
+                left -= cur_seg[j] + 1
+    state = (rng.uniform(size=J) < 0.1).astype(np.uint8)
+    coef = np.tile(workloads.tiny().coef[:1], (J, 1))
+    coef[:, 16] = ref
+    ints = np.tile(np.array([[1, 720720, 1]], np.uint32), (J, 1))
+    wl = workloads.Workload("drawn", coef, ints, workloads.Bounds(g_max=g_max, tp_max=1), grid, workloads.Env(), cl)
+    return wl, tb, flat, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state
+
+
+def test_random_rounds_on_drawn_values(gpu, orc):
+    n_moves = n_priv = 0
+    for seed in range(400):
+        rng = np.random.default_rng(95000 + seed)
+        wl, tb, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state = random_round(rng, orc)
+        use_floor = seed % 4 != 0
+        use_state = seed % 3 != 0
+        want = orc.reschedule(wl.coef[:, 16], tb, wl.grid, wl.cluster, bt, bp, ct, cur_seg, cur_c,
+                              floor_seg if use_floor else None, floor_c if use_floor else None, state=state if use_state else None)
+        run = gpu(wl)
+        run.enumerate()
+        assert np.array_equal(run.table_numpy()["seg_g"], tb.seg_g)
+        got = on_gpu(run, bt, bp, ct, wl.cluster, cur_seg, cur_c, floor_seg if use_floor else None,
+                     floor_c if use_floor else None, state if use_state else None)
+        run.close()
+        same(got, want)
+        n_moves += want[2]
+        n_priv += int(use_floor and np.any((floor_seg >= 0) & (cur_seg < floor_seg)))
+    print(f"400 rounds, {n_moves} steps committed, {n_priv} rounds with privileged jobs")
+    assert n_moves > 1500 and n_priv > 100
+
+
+@pytest.mark.parametrize("name", ["paper_scale", "what_if", "stress"])
+def test_generated_rounds_from_a_running_state(gpu, orc, name):
+    """The state a from-scratch round leaves, then the cluster loses a tenth of its GPUs and CPUs, a tenth of the
+    jobs leave and their slots are new arrivals, some jobs are guaranteed: the loop on the library's own curves,
+    given to both sides."""
+    import paper_2408_08586_amd as rk
+    wl = {"paper_scale": workloads.paper_scale, "what_if": lambda: workloads.what_if(7), "stress": workloads.stress}[name]()
+    J = wl.n_jobs
+    rng = np.random.default_rng(J)
+    run = gpu(wl)
+    run.enumerate()
+    bt, bp, ct, _, _, n = run.fused()
+    bt, bp, ct = run.host(bt, n).copy(), run.host(bp, n).view(np.uint32).copy(), run.host(ct, n).copy()
+    tn = run.table_numpy()
+    tb = orc.Table(tn["triple_off"], tn["triples"], tn["seg_off"], tn["seg_g"], tn["seg_first"])
+    a0, _, _ = orc.greedy(wl.coef[:, 16], tb, wl.grid, wl.cluster, bt, bp, ct)
+    cur_seg, cur_c = np.full(J, -1, np.int32), np.zeros(J, np.uint32)
+    levels = np.asarray(wl.grid.cpu_levels)
+    for j in np.flatnonzero(a0["g"] > 0).tolist():
+        seg_g = tb.seg_g[tb.seg_off[j]:tb.seg_off[j + 1]]
+        cur_seg[j] = int(np.flatnonzero(seg_g == a0["g"][j])[0])
+        per = a0["c"][j] // a0["g"][j] if wl.grid.cpu_mode else a0["c"][j]
+        cur_c[j] = int(np.flatnonzero(levels == per)[0])
+    gone = rng.uniform(size=J) < 0.1
+    cur_seg[gone] = -1                                                       # left; the slot is a new arrival
+    floor_seg, floor_c = np.full(J, -1, np.int32), np.zeros(J, np.uint32)
+    ns = np.diff(tb.seg_off)
+    guaranteed = (rng.uniform(size=J) < 0.05) & (ns > 0)
+    floor_seg[guaranteed] = np.minimum(rng.integers(0, 3, guaranteed.sum()), ns[guaranteed] - 1)
+    floor_seg[(cur_seg >= 0) & (floor_seg > cur_seg)] = -1                  # running jobs sit at or above their floor
+    state = (rng.uniform(size=J) < 0.02).astype(np.uint8)
+    cl = workloads.Cluster(int(wl.cluster.G * 0.9), int(wl.cluster.C * 0.9), wl.cluster.host_mem_gb)
+    # the jobs that stayed hold more than the smaller cluster has only if the greedy had filled it; make room first
+    held = sum(int(tb.seg_g[tb.seg_off[j] + cur_seg[j]]) for j in np.flatnonzero((cur_seg >= 0) & (state == 0)))
+    if held > cl.G:
+        cl = workloads.Cluster(held, cl.C, cl.host_mem_gb)
+    want = orc.reschedule(wl.coef[:, 16], tb, wl.grid, cl, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state=state)
+    got = on_gpu(run, bt, bp, ct, cl, cur_seg, cur_c, floor_seg, floor_c, state)
+    same(got, want)
+    a = got[0]
+    print(f"{name}: {int((a0['g'] > 0).sum())} jobs ran, {int(gone.sum())} slots changed hands, {got[2]} steps committed, "
+          f"{int((a['g'] > 0).sum())} jobs run now")
+    assert got[2] > 0 and a["g"].sum() <= cl.G
+    run.close()
+
+
+def test_argument_errors(gpu, orc):
+    import paper_2408_08586_amd as rk
+    wl = workloads.tiny()
+    run = gpu(wl)
+    run.enumerate()
+    bt, bp, ct, _, _, n = run.fused()
+    J = wl.n_jobs
+    assign, total = rk.new_assign(J, run.device), run.f32(1)
+    with pytest.raises(rk.RkError) as e:
+        rk.rk_reschedule(run.ctx, run.jobs.ref_thr, run.table.c, run.grid, run.cluster, bt, bp, ct, None, None, assign, total)
+    assert e.value.code == rk.RK_ERR_INVALID_ARG
+    # nobody holds anything, no floors: every job is a newcomer
+    cur = run.torch.full((J,), -1, dtype=run.torch.int32, device=run.device)
+    rk.rk_reschedule(run.ctx, run.jobs.ref_thr, run.table.c, run.grid, run.cluster, bt, bp, ct, cur, run.i32(J).zero_(), assign,
+                     total)
+    rk.rk_sync(run.ctx)
+    a = rk.assign_to_numpy(assign)
+    assert 0 < a["g"].sum() <= wl.cluster.G
+    run.close()
