@@ -231,6 +231,71 @@ def placement(rk, ctx, dev, wl, assign, reps):
     return out
 
 
+def algorithm1_bench(rk, ctx, dev, wl, jobs, table, grid, env, best_thr, best_plan, curve_thr, assign, reps):
+    """Algorithm 1 as a loop and on nodes, on the same workload: the state the from-scratch round leaves, then a tenth
+    of the jobs leave (their slots are new arrivals) and the cluster loses a tenth of its GPUs and CPUs:
+    rk_reschedule from that state; then rk_place_plans of its result on nodes of 8 GPUs, roomy and with 6 CPUs each
+    (fall-back to smaller GPU counts, plans chosen again on the actual node split)."""
+    import torch
+    J = wl.n_jobs
+    a0 = rk.assign_to_numpy(assign)
+    seg_off = np.asarray(table.h_seg_off[:J + 1], dtype=np.int64)
+    seg_g = rk.u32(table.seg_g)
+    levels = np.asarray(wl.grid.cpu_levels)
+    cur_seg, cur_c = np.full(J, -1, np.int32), np.zeros(J, np.uint32)
+    for j in np.flatnonzero(a0["g"] > 0).tolist():
+        cur_seg[j] = int(np.flatnonzero(seg_g[seg_off[j]:seg_off[j + 1]] == a0["g"][j])[0])
+        per = a0["c"][j] // a0["g"][j] if wl.grid.cpu_mode else a0["c"][j]
+        cur_c[j] = int(np.flatnonzero(levels == per)[0])
+    rng = np.random.default_rng(J)
+    cur_seg[rng.uniform(size=J) < 0.1] = -1
+    held = int(sum(int(seg_g[seg_off[j] + cur_seg[j]]) for j in np.flatnonzero(cur_seg >= 0)))
+    small = rk.make_cluster(type(wl.cluster)(max(held, int(wl.cluster.G * 0.9)), int(wl.cluster.C * 0.9), wl.cluster.host_mem_gb))
+    d_seg = torch.from_numpy(cur_seg).to(dev)
+    d_c = torch.from_numpy(cur_c.view(np.int32)).to(dev)
+    out, total = rk.new_assign(J, dev), torch.zeros(1, dtype=torch.float32, device=dev)
+    moves = torch.zeros(4, dtype=torch.int32, device=dev)
+    ms = []
+    for i in range(reps + 2):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        rk.rk_reschedule(ctx, jobs.ref_thr, table.c, grid, small, best_thr, best_plan, curve_thr, d_seg, d_c, out, total,
+                         n_moves=moves)
+        b.record()
+        torch.cuda.synchronize()
+        if i >= 2:
+            ms.append(a.elapsed_time(b))
+    res = rk.assign_to_numpy(out)
+    info = {"entry": "rk_reschedule (one workgroup; sequential by definition)", "jobs": J,
+            "jobs_running_before": int((cur_seg >= 0).sum()), "steps_committed": int(moves[0].item()), "jobs_on_the_full_path": int(moves[1].item()),
+            "shrinks_applied": int(moves[2].item()), "steps_taken_back": int(moves[3].item()),
+            "jobs_running_after": int((res["g"] > 0).sum()), "ms": float(np.median(ms))}
+    gpn, n_nodes = 8, max(1, wl.cluster.G // 8)
+    cap = n_nodes * gpn
+    placed = rk.new_assign(J, dev)
+    off = torch.zeros(J + 1, dtype=torch.int32, device=dev)
+    status = torch.zeros(J, dtype=torch.int32, device=dev)
+    ent = rk.new_place_entries(cap, dev)
+    info["place_plans"] = {"entry": "rk_place_plans (host-synchronous)", "nodes": n_nodes, "gpus_per_node": gpn}
+    for name, cpn in (("roomy", wl.cluster.C // n_nodes), ("tight_cpus", 6)):
+        nodes = rk.rk_nodes(n_nodes, gpn, min(int(cpn), 65535), float(wl.cluster.host_mem_gb) / n_nodes)
+        lat = []
+        for i in range(reps + 2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            r = rk.rk_place_plans(ctx, jobs, table.c, grid, env, nodes, best_thr, out, None, placed, off, ent, cap, status, total)
+            if i >= 2:
+                lat.append((time.perf_counter() - t0) * 1e3)
+        st = rk.u32(status)[:J]
+        p = rk.assign_to_numpy(placed)
+        info["place_plans"][name] = {"cpus_per_node": int(nodes.cpus_per_node), "ms": float(np.median(lat)),
+                                     "placed_as_asked": int((st == 1).sum()), "placed_with_fewer_gpus": int((st == 2).sum()),
+                                     "not_placed": int((st == 3).sum()), "parts": r.n_entries,
+                                     "plans_changed_by_the_split": int(((p["plan"] != res["plan"]) & (st == 1)).sum()),
+                                     "job_by_job_stage": bool(r.in_order)}
+    return info
+
+
 def sla_round(rk, ctx, dev, wl, jobs, table, bounds, grid, env, cluster, best_plan, n_rows, reps):
     """Service-level variant of the round on the same workload: 30 % guaranteed
     jobs of 6 tenants whose quotas sum to half the cluster.  A job's original
@@ -636,6 +701,11 @@ def main():
     if not args.no_place:
         rk.rk_schedule_round(ctx, jobs, bounds, grid, env, cluster, assign, total)
         out["placement"] = placement(rk, ctx, dev, wl, assign, max(5, args.steps))
+    if not args.no_place:
+        rk.rk_job_curves(ctx, jobs, table.c, grid, env, 0, J, best_thr, best_plan, curve_thr, curve_plan, curve_g)
+        rk.rk_allocate(ctx, jobs.ref_thr, table.c, grid, cluster, 0, J, best_thr, best_plan, curve_thr, assign, total)
+        out["algorithm1"] = algorithm1_bench(rk, ctx, dev, wl, jobs, table, grid, env, best_thr, best_plan, curve_thr, assign,
+                                             max(5, args.steps))
     if not args.no_sla:
         out["sla_round"] = sla_round(rk, ctx, dev, wl, jobs, table, bounds, grid, env, cluster, best_plan, n_rows,
                                      max(5, args.steps))

@@ -298,13 +298,15 @@ typedef struct {
  *    otherwise every job is put back and j's search in that resource ends.
  *  - Memory last, as in rk_allocate.  A job shrunk to nothing is preempted.
  *   assign  [device] n_jobs records; total [device] one float
- *   n_moves [device] one word or NULL: steps committed
+ *   stats   [device] four words or NULL: steps committed, jobs that needed more
+ *           than a look (a step that was free to take, or a job it might shrink),
+ *           shrinks applied, steps taken back
  * Limits: at most RK_MAX_JOBS_PER_ROUND jobs.  One workgroup runs the loop: the
  * rule is sequential. */
 int32_t rk_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
                       const rk_alloc_grid *grid, const rk_cluster *cluster,
                       const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
-                      const rk_job_state *jobs_state, rk_assign *assign, float *total, uint32_t *n_moves);
+                      const rk_job_state *jobs_state, rk_assign *assign, float *total, uint32_t *stats);
 
 /* One scheduling round end to end: enumerate -> evaluate -> best plan ->
  * curves -> greedy allocation, all on the device.  Waits once for the plan

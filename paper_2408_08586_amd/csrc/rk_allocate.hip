@@ -1429,10 +1429,14 @@ struct RsArgs {
     const uint32_t *floor_c;     // may be null
     float *ds_g, *ds_c;          // per job: what it loses per GPU / CPU it gives (infinite: gives nothing)
     float *sg, *sc;              // per job: slopes the order is taken from
+    float *ug, *uc;              // per job, kept current: slope of its next GPU / CPU step (0: none)
+    uint32_t *udg;               // ... GPUs its next GPU step adds
+    unsigned long long *udc_g, *udc_c;   // ... CPUs its next GPU step / CPU step adds
     uint32_t *order, *touched, *stamp, *first;
     int32_t *keep_gi;
     uint32_t *keep_ci;
-    uint32_t *n_moves;           // may be null
+    float *keep_ds;              // the two give-slopes of a job before a step touched it
+    uint32_t *stats;             // may be null: steps committed, jobs on the full path, shrinks applied, steps taken back
 };
 
 struct RsStep { uint32_t any; int32_t tgt; uint32_t lvl; float slope, gain; unsigned long long dg, dc; };
@@ -1593,11 +1597,29 @@ __device__ RsGive rs_down_cpu(const RsArgs &A, uint32_t v) {
     return gv;
 }
 
-// the cached slopes of job v after its state changed
-__device__ __forceinline__ void rs_refresh(const RsArgs &A, uint32_t v) {
+// the cached slopes of job v after its state changed: what it loses per unit it gives ...
+__device__ __forceinline__ void rs_refresh_give(const RsArgs &A, uint32_t v) {
     const RsGive a = rs_down_gpu(A, v), b = rs_down_cpu(A, v);
     A.ds_g[v] = a.any ? a.slope : __int_as_float(0x7F800000);
     A.ds_c[v] = b.any ? b.slope : __int_as_float(0x7F800000);
+}
+// ... and its own next steps as well
+__device__ __forceinline__ void rs_refresh(const RsArgs &A, uint32_t v) {
+    rs_refresh_give(A, v);
+    const RsStep ug = rs_up_gpu(A, v, 0, 1), uc = rs_up_cpu(A, v, 0, 1);
+    A.ug[v] = ug.any ? ug.slope : 0.f; A.udg[v] = (uint32_t)ug.dg; A.udc_g[v] = ug.dc;
+    A.uc[v] = uc.any ? uc.slope : 0.f; A.udc_c[v] = uc.dc;
+}
+
+// the two lowest values of ds over all jobs and the job of the lowest (lower index among equal values)
+struct RsMin { float m1, m2; uint32_t i1; };
+__device__ __forceinline__ RsMin rs_min_merge(const RsMin &a, const RsMin &b) {
+    RsMin r;
+    const bool a_first = a.m1 < b.m1 || (a.m1 == b.m1 && a.i1 <= b.i1);
+    const RsMin &lo = a_first ? a : b, &hi = a_first ? b : a;
+    r.m1 = lo.m1; r.i1 = lo.i1;
+    r.m2 = lo.m2 < hi.m1 ? lo.m2 : hi.m1;
+    return r;
 }
 
 __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
@@ -1605,7 +1627,9 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
     __shared__ unsigned long long sh_free[2], sh_avail[2], sh_held[2][RS_THREADS / 64];
     __shared__ float sh_lost, sh_wmin[RS_THREADS / 64];
     __shared__ uint32_t sh_widx[RS_THREADS / 64];
-    __shared__ uint32_t sh_ok, sh_go, sh_touched, sh_epoch, sh_moves, sh_nb;
+    __shared__ uint32_t sh_ok, sh_go, sh_touched, sh_epoch, sh_moves, sh_nb, sh_full, sh_shrinks, sh_undone;
+    __shared__ RsMin sh_min[2], sh_wm[2][RS_THREADS / 64];
+    __shared__ float sh_wc[RS_THREADS / 64];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t J = A.n_jobs;
     const float INF = __int_as_float(0x7F800000);
@@ -1631,7 +1655,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
         for (uint32_t w = 0; w < RS_THREADS / 64; ++w) { g += sh_held[0][w]; c += sh_held[1][w]; }
         sh_free[0] = g < A.G ? A.G - g : 0ull;
         sh_free[1] = c < A.C ? A.C - c : 0ull;
-        sh_epoch = 0u; sh_moves = 0u;
+        sh_epoch = 0u; sh_moves = 0u; sh_full = 0u; sh_shrinks = 0u; sh_undone = 0u;
     }
     for (uint32_t j = tid; j < J; j += RS_THREADS) rs_refresh(A, j);
     __syncthreads();
@@ -1682,13 +1706,15 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
                             if (A.stamp[w2] != sh_epoch) {          // first time this job gives in this step: remember its state
                                 A.stamp[w2] = sh_epoch;
                                 A.keep_gi[w2] = A.st.gi[w2]; A.keep_ci[w2] = A.st.ci[w2];
+                                A.keep_ds[2 * w2] = A.ds_g[w2]; A.keep_ds[2 * w2 + 1] = A.ds_c[w2];
                                 A.touched[sh_touched++] = w2;
                             }
                             sh_avail[0] += gv.dg; sh_avail[1] += gv.dc;
                             sh_lost = sh_lost + gv.loss;
                             if (res == 0) { A.st.gi[w2] = gv.tgt; if (gv.tgt < 0) A.st.ci[w2] = 0u; }
                             else A.st.ci[w2] -= 1u;
-                            rs_refresh(A, w2);
+                            rs_refresh_give(A, w2);             // (its own next steps are brought up to date on commit)
+                            sh_shrinks += 1u;
                         }
                     }
                     __syncthreads();
@@ -1698,22 +1724,26 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
                     if (ok && (sh_avail[0] < st.dg || sh_avail[1] < st.dc)) ok = false;
                     if (ok && !below_min && !(st.gain > sh_lost)) ok = false;
                     if (!ok) {
-                        for (uint32_t i = 0; i < sh_touched; ++i) {
+                        for (uint32_t i = 0; i < sh_touched; ++i) {         // everything back as it was
                             const uint32_t v = A.touched[i];
                             A.st.gi[v] = A.keep_gi[v]; A.st.ci[v] = A.keep_ci[v];
-                            rs_refresh(A, v);
+                            A.ds_g[v] = A.keep_ds[2 * v]; A.ds_c[v] = A.keep_ds[2 * v + 1];
                         }
+                        sh_undone += sh_touched ? 1u : 0u;
                     } else {
                         sh_free[0] = sh_avail[0] - st.dg; sh_free[1] = sh_avail[1] - st.dc;
                         if (res == 0) A.st.gi[j] = st.tgt;
                         A.st.ci[j] = st.lvl;
-                        rs_refresh(A, j);
                         sh_moves += 1u;
                     }
                     sh_go = ok ? 1u : 0u;
                 }
                 __syncthreads();
                 const uint32_t go = sh_go;
+                if (go) {                                       // the jobs whose state changed: all their cached values
+                    const uint32_t n_changed = sh_touched + 1u;
+                    for (uint32_t i = tid; i < n_changed; i += RS_THREADS) rs_refresh(A, i < sh_touched ? A.touched[i] : j);
+                }
                 __syncthreads();
                 if (!go) break;
             }
@@ -1728,52 +1758,108 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
     }
     if (tid == 0) sh_nb = 0u;
     __syncthreads();
-    {
-        uint32_t mine = 0;
-        for (uint32_t j = tid; j < J; j += RS_THREADS) {
-            if (!A.first[j]) continue;
-            uint32_t pos = 0;
-            for (uint32_t i = 0; i < j; ++i) pos += A.first[i];
-            A.order[pos] = j;
-            ++mine;
+    for (uint32_t base = 0; base < J; base += RS_THREADS) {       // their list, in job order: 1,024 jobs at a time
+        const uint32_t j = base + tid;
+        const bool is = j < J && A.first[j] != 0u;
+        const unsigned long long in_wave = __ballot(is);
+        if (lane == 0) sh_widx[wave] = (uint32_t)__popcll(in_wave);
+        __syncthreads();
+        uint32_t before = sh_nb, all = 0;
+        for (uint32_t w = 0; w < RS_THREADS / 64; ++w) {
+            if (w < wave) before += sh_widx[w];
+            all += sh_widx[w];
         }
-        atomicAdd(&sh_nb, mine);
+        if (is) A.order[before + (uint32_t)__popcll(in_wave & ((1ull << lane) - 1ull))] = j;
+        __syncthreads();
+        if (tid == 0) sh_nb += all;
     }
     __syncthreads();
     const uint32_t na = sh_nb;
     for (uint32_t k = 0; k < na; ++k) schedule_job(A.order[k]);
     __syncthreads();
-    // the others, sorted once by GPU slope, CPU slope (descending), index
+    // the others: their order is fixed once, by GPU slope, then CPU slope (both descending), then index
     for (uint32_t j = tid; j < J; j += RS_THREADS) {
         const bool in = rs_part(A, j) && !A.first[j];
         A.sg[j] = in ? rs_up_gpu(A, j, 0, 1).slope : -1.f;      // -1: not in the list
         A.sc[j] = in ? rs_up_cpu(A, j, 0, 1).slope : -1.f;
     }
     __syncthreads();
-    for (uint32_t j = tid; j < J; j += RS_THREADS) {
-        const float gj = A.sg[j], cj = A.sc[j];
-        if (gj < 0.f) continue;
-        uint32_t rank = 0;
-        for (uint32_t i = 0; i < J; ++i) {
-            const float gi2 = A.sg[i], ci2 = A.sc[i];
-            if (gi2 < 0.f) continue;
-            rank += (gi2 > gj || (gi2 == gj && (ci2 > cj || (ci2 == cj && i < j)))) ? 1u : 0u;
+    // Most jobs of a large round find nothing to do when their turn comes: no step, or a step that needs more than is
+    // free while no other job's slope is lower than theirs.  Whether that is so follows from values that change only
+    // when a step is committed: the job's own next steps (kept current for every job), what is free, and the two
+    // lowest slopes among the jobs that can give.  Passing over such a job changes nothing, so the jobs need not be
+    // sorted: all threads look for the first job in the order, after the one served last, that is not of that kind,
+    // it is served in full, and the search starts again from the new state.
+    auto comes_before = [&](float ga, float ca, uint32_t a, float gb, float cb, uint32_t b) {
+        return ga > gb || (ga == gb && (ca > cb || (ca == cb && a < b)));
+    };
+    float last_g = INF, last_c = INF;                     // key of the job served last (before every job at first)
+    uint32_t last_j = 0u;
+    for (;;) {
+        __syncthreads();
+        for (uint32_t res = 0; res < 2; ++res) {
+            const float *ds = res == 0 ? A.ds_g : A.ds_c;
+            RsMin m = {INF, INF, 0xFFFFFFFFu};
+            for (uint32_t v = tid; v < J; v += RS_THREADS) {
+                const RsMin one = {ds[v], INF, v};
+                m = rs_min_merge(m, one);
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                RsMin o;
+                o.m1 = __shfl_xor(m.m1, off, 64); o.m2 = __shfl_xor(m.m2, off, 64); o.i1 = __shfl_xor(m.i1, off, 64);
+                m = rs_min_merge(m, o);
+            }
+            if (lane == 0) sh_wm[res][wave] = m;
         }
-        A.order[rank] = j;
+        __syncthreads();
+        if (tid < 2) {
+            RsMin m = sh_wm[tid][0];
+            for (uint32_t w = 1; w < RS_THREADS / 64; ++w) m = rs_min_merge(m, sh_wm[tid][w]);
+            sh_min[tid] = m;
+        }
+        __syncthreads();
+        const unsigned long long free_g = sh_free[0], free_c = sh_free[1];
+        const RsMin mg = sh_min[0], mc = sh_min[1];
+        float best_g = -1.f, best_c = -1.f;                // -1: none found
+        uint32_t best_j = 0xFFFFFFFFu;
+        for (uint32_t j = tid; j < J; j += RS_THREADS) {
+            const float kg = A.sg[j], kc = A.sc[j];
+            if (kg < 0.f || !comes_before(last_g, last_c, last_j, kg, kc, j)) continue;       // not in the list, or served
+            const float lowest_g = j == mg.i1 ? mg.m2 : mg.m1, lowest_c = j == mc.i1 ? mc.m2 : mc.m1;
+            const float ug = A.ug[j], uc = A.uc[j];
+            // GPU step: none; or GPUs are short and nobody may be shrunk for it; or the GPUs are there and its CPUs are not
+            const bool gpu_idle = !(ug > 0.f) || (free_g < A.udg[j] ? !(ug > lowest_g) : free_c < A.udc_g[j]);
+            const bool cpu_idle = !(uc > 0.f) || (free_c < A.udc_c[j] && !(uc > lowest_c));
+            if (gpu_idle && cpu_idle) continue;
+            if (best_j == 0xFFFFFFFFu || comes_before(kg, kc, j, best_g, best_c, best_j)) { best_g = kg; best_c = kc; best_j = j; }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float og = __shfl_xor(best_g, off, 64), oc = __shfl_xor(best_c, off, 64);
+            const uint32_t oj = __shfl_xor(best_j, off, 64);
+            if (oj != 0xFFFFFFFFu && (best_j == 0xFFFFFFFFu || comes_before(og, oc, oj, best_g, best_c, best_j))) {
+                best_g = og; best_c = oc; best_j = oj;
+            }
+        }
+        if (lane == 0) { sh_wmin[wave] = best_g; sh_wc[wave] = best_c; sh_widx[wave] = best_j; }
+        __syncthreads();
+        best_g = sh_wmin[0]; best_c = sh_wc[0]; best_j = sh_widx[0];
+        for (uint32_t w = 1; w < RS_THREADS / 64; ++w) {
+            const uint32_t oj = sh_widx[w];
+            if (oj != 0xFFFFFFFFu && (best_j == 0xFFFFFFFFu || comes_before(sh_wmin[w], sh_wc[w], oj, best_g, best_c, best_j))) {
+                best_g = sh_wmin[w]; best_c = sh_wc[w]; best_j = oj;
+            }
+        }
+        __syncthreads();
+        if (best_j == 0xFFFFFFFFu) break;
+        if (tid == 0) sh_full += 1u;
+        schedule_job(best_j);
+        last_g = best_g; last_c = best_c; last_j = best_j;
     }
-    if (tid == 0) sh_nb = 0u;
-    __syncthreads();
-    {
-        uint32_t mine = 0;
-        for (uint32_t j = tid; j < J; j += RS_THREADS) mine += A.sg[j] >= 0.f ? 1u : 0u;
-        atomicAdd(&sh_nb, mine);
-    }
-    __syncthreads();
-    const uint32_t nb = sh_nb;
-    for (uint32_t k = 0; k < nb; ++k) schedule_job(A.order[k]);
     __syncthreads();
     for (uint32_t j = tid; j < J; j += RS_THREADS) A.st.g[j] = (uint32_t)rs_g(A, j, A.st.gi[j]);
-    if (tid == 0 && A.n_moves) *A.n_moves = sh_moves;
+    if (tid == 0 && A.stats) { A.stats[0] = sh_moves; A.stats[1] = sh_full; A.stats[2] = sh_shrinks; A.stats[3] = sh_undone; }
 }
 
 // Scratch of rk_allocate_static: one array in the library's image, so every device the library is loaded on holds
@@ -1962,7 +2048,7 @@ int32_t rk_launch_allocate(rk_ctx *ctx, const float *ref_thr, const TableDev &tb
 extern "C" int32_t rk_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
                                  const rk_alloc_grid *grid, const rk_cluster *cluster, const float *best_thr,
                                  const uint32_t *best_plan, const float *curve_thr, const rk_job_state *jobs_state,
-                                 rk_assign *assign, float *total, uint32_t *n_moves) {
+                                 rk_assign *assign, float *total, uint32_t *stats) {
     if (!ctx) return RK_ERR_INVALID_ARG;
     int32_t rc;
     if ((rc = rk_check_table(ctx, table, 0, table ? table->n_jobs : 0))) return rc;
@@ -1990,11 +2076,15 @@ extern "C" int32_t rk_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_pla
     if ((rc = scratch_typed(ctx, arena, SL_ST_PARTIAL, (size_t)st.blocks_per_round * 2, &st.partial))) return rc;
     float *f32;
     uint32_t *u32;
-    if ((rc = scratch_typed(ctx, arena, SL_RS_F32, n * 4, &f32))) return rc;
-    if ((rc = scratch_typed(ctx, arena, SL_RS_U32, n * 6, &u32))) return rc;
-    A.ds_g = f32; A.ds_c = f32 + n; A.sg = f32 + 2 * n; A.sc = f32 + 3 * n;
+    unsigned long long *u64;
+    if ((rc = scratch_typed(ctx, arena, SL_RS_F32, n * 8, &f32))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_RS_U32, n * 7, &u32))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_RS_U64, n * 2, &u64))) return rc;
+    A.ds_g = f32; A.ds_c = f32 + n; A.sg = f32 + 2 * n; A.sc = f32 + 3 * n; A.ug = f32 + 4 * n; A.uc = f32 + 5 * n;
+    A.keep_ds = f32 + 6 * n;
     A.order = u32; A.touched = u32 + n; A.stamp = u32 + 2 * n; A.first = u32 + 3 * n;
-    A.keep_gi = reinterpret_cast<int32_t *>(u32 + 4 * n); A.keep_ci = u32 + 5 * n;
+    A.keep_gi = reinterpret_cast<int32_t *>(u32 + 4 * n); A.keep_ci = u32 + 5 * n; A.udg = u32 + 6 * n;
+    A.udc_g = u64; A.udc_c = u64 + n;
     Ctx &X = A.X;
     X.ref_thr = ref_thr; X.tb = table_dev(table); X.grid = grid_dev(grid); X.jb = 0; X.jmap = nullptr;
     X.best_thr = best_thr; X.best_plan = best_plan; X.curve_thr = curve_thr;
@@ -2003,7 +2093,7 @@ extern "C" int32_t rk_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_pla
     A.n_jobs = J; A.G = cluster->G; A.C = cluster->C;
     A.state = jobs_state->state; A.cur_seg = jobs_state->cur_seg; A.cur_c = jobs_state->cur_c;
     A.floor_seg = jobs_state->floor_seg; A.floor_c = jobs_state->floor_c;
-    A.n_moves = n_moves;
+    A.stats = stats;
     hipStream_t s = ctx->stream;
     k_reschedule<<<1, RS_THREADS, 0, s>>>(A);
     RK_CHECK_LAUNCH(ctx, "k_reschedule");

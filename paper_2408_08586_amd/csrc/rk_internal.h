@@ -47,7 +47,7 @@ enum {
     SL_ENUM_BACK,                                        // enumeration: totals and offsets in one piece for the host
     SL_PLACE_RESULT,                                     // placement: its four summary words
     SL_ENUM_LEADER,                                      // enumeration: the job whose search a job shares
-    SL_RS_F32, SL_RS_U32                                 // the Schedule loop: cached slopes; order, marks and saved states
+    SL_RS_F32, SL_RS_U32, SL_RS_U64                      // the Schedule loop: cached slopes; order, marks and saved states; CPU needs
 };
 
 int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);
