@@ -466,6 +466,9 @@ def main():
     ap.add_argument("--no-fit", action="store_true")
     ap.add_argument("--no-sim", action="store_true")
     ap.add_argument("--what-if-rounds", type=int, default=256)
+    ap.add_argument("--stream-calibration", action="store_true",
+                    help="also run, five times each, a strided read of a chunk's candidate buffer and the evaluation with "
+                         "the feasibility output (for profiles)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (reads 1 GiB, writes 1 GiB) three times, "
                          "to scale the profiler's FETCH_SIZE / WRITE_SIZE counters")
@@ -552,6 +555,32 @@ def main():
         if every:
             stage_ms["allocate"].append((e2, mark()))
 
+    # What the chip gives kernels that do nothing but fill, then read, the candidate buffer of one chunk: the measured
+    # ceiling of the k_eval + k_best_plan pair.  A read that follows a write of the same buffer is slower than the same
+    # read after another read (the written lines are still on their way to HBM), so both positions are timed.
+    n_probe = (max(chunk_cands) // 4) * 4
+    probe = {"fill": [], "read_after_fill": [], "read_after_read": []}
+    for i in range(7):
+        e = [mark()]
+        rk.rk_probe_stream(ctx, thr, n_probe, 1, 1.0)
+        e.append(mark())
+        rk.rk_probe_stream(ctx, thr, n_probe, 0, out=total)
+        e.append(mark())
+        rk.rk_probe_stream(ctx, thr, n_probe, 0, out=total)
+        e.append(mark())
+        if i >= 2:
+            for k, (x, y) in zip(probe, zip(e[:-1], e[1:])):
+                probe[k].append((x, y))
+    torch.cuda.synchronize()
+    probe_ms = {k: sum(x.elapsed_time(y) for x, y in v) / len(v) for k, v in probe.items()}
+    if args.stream_calibration:
+        # for profiles: the strided read, and k_eval with the feasibility output, which the timed steps do not ask for
+        feas = torch.empty(max(chunk_cands) + 16, dtype=torch.uint8, device=dev)
+        for _ in range(5):
+            rk.rk_probe_stream(ctx, thr, n_probe, 2, out=total)
+            rk.rk_eval_candidates(ctx, jobs, table.c, grid, env, 0, int(edges[1]), thr, feas)
+        torch.cuda.synchronize()
+        del feas
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -647,6 +676,10 @@ def main():
                     "avg_launch_ms": avg_ms, "per_step_ms": per_step_ms,
                     "eval_GBps": gbs_eval, "best_plan_GBps": gbs_best,
                     "eval_plus_best_plan_GBps": pair_gbs, "eval_plus_best_plan_frac_of_hbm": pair_gbs / HBM_PEAK_GBS,
+                    # kernels that only fill and only read the same buffer (4 bytes per candidate each way)
+                    "plain_stream_ms": probe_ms,
+                    "eval_plus_best_plan_over_plain_fill_plus_read":
+                        (hot_avg_ms["eval"] + hot_avg_ms["best_plan"]) / (probe_ms["fill"] + probe_ms["read_after_fill"]),
                     "eval_plus_best_plan_candidates_per_s":
                         n_cand / ((hot_avg_ms["eval"] + hot_avg_ms["best_plan"]) * n_chunks * 1e-3)},
         "round_latency_ms": {"entry": "rk_schedule_round (fused evaluation, host-synchronous)",

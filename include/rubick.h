@@ -587,6 +587,16 @@ int32_t rk_schedule_round_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan
                                  uint32_t *place_off, rk_place_entry *entries, uint64_t cap_entries,
                                  uint32_t *status, float *total, rk_place_result *result);
 
+/* ---- measurement helper (no part of the method) --------------------------- */
+
+/* Streams a buffer and nothing else, for the benchmark's roofline context:
+ * mode 0 reads the first n_floats (rounded down to a multiple of 4) floats of
+ * buf [device, 16-byte aligned] with 16-byte streaming loads (out [device]: one
+ * float the kernel may add to), a tile of 64 KiB per workgroup; mode 2 reads
+ * them with 4,096 workgroups that stride through the buffer together; mode 1
+ * fills them with `value`. */
+int32_t rk_probe_stream(rk_ctx *ctx, float *buf, uint64_t n_floats, int32_t mode, float value, float *out);
+
 #ifdef __cplusplus
 }
 #endif

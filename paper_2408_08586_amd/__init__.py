@@ -26,7 +26,7 @@ FIT_FIELDS = ("k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_con
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
            "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
            "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared", "rk_place", "rk_allocate_static", "rk_place_plans",
-           "rk_schedule_round_placed", "rk_reschedule")
+           "rk_schedule_round_placed", "rk_reschedule", "rk_probe_stream")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -308,6 +308,12 @@ def rk_reschedule(ctx, ref_thr, table, grid, cluster: rk_cluster, best_thr, best
     _check(ctx, load_library().rk_reschedule(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.byref(cluster),
                                              _ptr(best_thr), _ptr(best_plan), _ptr(curve_thr), C.byref(js), _ptr(assign),
                                              _ptr(total), _ptr(n_moves)))
+
+
+def rk_probe_stream(ctx, buf, n_floats, mode, value=0.0, out=None):
+    """Measurement helper: stream-read (mode 0) or fill (mode 1) the first n_floats floats of buf."""
+    _check(ctx, load_library().rk_probe_stream(ctx, _ptr(buf), C.c_uint64(n_floats), C.c_int32(mode), C.c_float(value),
+                                               _ptr(out)))
 
 
 def rk_schedule_round(ctx, jobs: Jobs, bounds, grid, env, cluster, assign, total):
