@@ -592,9 +592,12 @@ int32_t rk_schedule_round_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan
 /* Streams a buffer and nothing else, for the benchmark's roofline context:
  * mode 0 reads the first n_floats (rounded down to a multiple of 4) floats of
  * buf [device, 16-byte aligned] with 16-byte streaming loads (out [device]: one
- * float the kernel may add to), a tile of 64 KiB per workgroup; mode 2 reads
- * them with 4,096 workgroups that stride through the buffer together; mode 1
- * fills them with `value`. */
+ * float the kernel may add to), a tile of 64 KiB per workgroup; mode 3 is the
+ * same read under a second kernel name (a profile then tells a read that
+ * follows a fill from one that follows a read); mode 2 reads them with 4,096
+ * workgroups that stride through the buffer together; mode 1 fills them with
+ * `value`.  Any other mode, a null or misaligned buf, or fewer than 4 floats:
+ * RK_ERR_INVALID_ARG. */
 int32_t rk_probe_stream(rk_ctx *ctx, float *buf, uint64_t n_floats, int32_t mode, float value, float *out);
 
 #ifdef __cplusplus

@@ -14,7 +14,9 @@ constexpr uint64_t PROBE_TILE = (uint64_t)PROBE_THREADS * PROBE_UNROLL * 4;     
 
 // every workgroup streams one contiguous tile with 16-byte streaming loads, four in flight per lane, and compares the
 // sum of what it read with a value it practically never has (so the loads cannot be dropped; *out is only touched in
-// that case)
+// that case).  TAG only gives the kernel two names, so that a profile tells the read that follows a fill of the same
+// buffer (0) from the read that follows another read (1).
+template <int TAG>
 __global__ __launch_bounds__(PROBE_THREADS) void k_probe_read(const v4f *__restrict__ buf, uint64_t n_vec,
                                                               float *__restrict__ out) {
     const uint64_t base = (uint64_t)blockIdx.x * PROBE_TILE;
@@ -70,14 +72,16 @@ __global__ __launch_bounds__(PROBE_THREADS) void k_probe_fill(v4f *__restrict__ 
 
 extern "C" int32_t rk_probe_stream(rk_ctx *ctx, float *buf, uint64_t n_floats, int32_t mode, float value, float *out) {
     if (!ctx) return RK_ERR_INVALID_ARG;
-    if (!buf || n_floats < 4 || ((uintptr_t)buf & 15u) || (mode != 1 && !out) || mode < 0 || mode > 2)
+    if (!buf || n_floats < 4 || ((uintptr_t)buf & 15u) || (mode != 1 && !out) || mode < 0 || mode > 3)
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "rk_probe_stream: bad argument");
     RK_HIP(ctx, hipSetDevice(ctx->device));
     const uint64_t n_vec = n_floats / 4;
     const uint64_t blocks = (n_vec + PROBE_TILE - 1) / PROBE_TILE;
     if (blocks > 0x7FFFFFFFull) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "buffer too large");
     if (mode == 0)
-        k_probe_read<<<(uint32_t)blocks, PROBE_THREADS, 0, ctx->stream>>>(reinterpret_cast<const v4f *>(buf), n_vec, out);
+        k_probe_read<0><<<(uint32_t)blocks, PROBE_THREADS, 0, ctx->stream>>>(reinterpret_cast<const v4f *>(buf), n_vec, out);
+    else if (mode == 3)
+        k_probe_read<1><<<(uint32_t)blocks, PROBE_THREADS, 0, ctx->stream>>>(reinterpret_cast<const v4f *>(buf), n_vec, out);
     else if (mode == 2)
         k_probe_read_strided<<<4096, PROBE_THREADS, 0, ctx->stream>>>(reinterpret_cast<const v4f *>(buf), n_vec, out);
     else
