@@ -1,6 +1,8 @@
 """GPU parity of rk_reschedule (Algorithm 1's Schedule as a loop from the jobs'
 present state) against the oracle's ork_reschedule_f32 on shared float32
 inputs: records, totals and the number of committed steps must be identical."""
+import math
+
 import numpy as np
 import pytest
 
@@ -40,10 +42,12 @@ def same(got, want):
     assert got[2] == want[2]
 
 
-def random_round(rng, orc):
+def random_round(rng, orc, J=None, g_max=None):
     """A round on drawn values: every GPU count 1..g_max is a segment, some counts are not valid (value 0), several CPU
     levels and memory tiers in either mode, a random present state with floors and jobs that take no part."""
-    J, g_max = int(rng.integers(1, 41)), int(rng.integers(2, 17))
+    if J is None:
+        J, g_max = int(rng.integers(1, 41)), int(rng.integers(2, 17))
+    big = J > 64
     n_cpu, n_mem = int(rng.integers(1, 5)), int(rng.integers(1, 4))
     tb = table_for(orc, J, g_max)
     grid = workloads.Grid(np.sort(rng.choice(np.arange(1, 9), n_cpu, replace=False)).astype(np.uint32), int(rng.integers(0, 2)),
@@ -65,8 +69,8 @@ def random_round(rng, orc):
     bp[flat == 0] = orc.NO_PLAN
     ct, _, _ = orc.curves(tb, grid, flat, bp)
     ref = rng.uniform(0.5, 2.0, J).astype(np.float32)
-    G = int(rng.integers(0, 3 * g_max + 1))
-    cl = workloads.Cluster(G, int(rng.integers(0, 12 * max(G, 1))), float(rng.choice([0.0, 16.0, 200.0, 1e6])))
+    G = int(rng.integers(J // 4, 2 * J + 1)) if big else int(rng.integers(0, 3 * g_max + 1))
+    cl = workloads.Cluster(G, int(rng.integers(G if big else 0, 12 * max(G, 1))), float(rng.choice([0.0, 16.0, 200.0, 1e6])))
     cur_seg, cur_c = np.full(J, -1, np.int32), np.zeros(J, np.uint32)
     floor_seg, floor_c = np.full(J, -1, np.int32), np.zeros(J, np.uint32)
     left = G
@@ -82,7 +86,7 @@ def random_round(rng, orc):
     state = (rng.uniform(size=J) < 0.1).astype(np.uint8)
     coef = np.tile(workloads.tiny().coef[:1], (J, 1))
     coef[:, 16] = ref
-    ints = np.tile(np.array([[1, 720720, 1]], np.uint32), (J, 1))
+    ints = np.tile(np.array([[1, math.lcm(*range(1, g_max + 1)), 1]], np.uint32), (J, 1))   # as table_for builds its table
     wl = workloads.Workload("drawn", coef, ints, workloads.Bounds(g_max=g_max, tp_max=1), grid, workloads.Env(), cl)
     return wl, tb, flat, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state
 
@@ -107,6 +111,25 @@ def test_random_rounds_on_drawn_values(gpu, orc):
         n_priv += int(use_floor and np.any((floor_seg >= 0) & (cur_seg < floor_seg)))
     print(f"400 rounds, {n_moves} steps committed, {n_priv} rounds with privileged jobs")
     assert n_moves > 1500 and n_priv > 100
+
+
+def test_larger_drawn_rounds(gpu, orc):
+    """Rounds of hundreds to thousands of jobs with hundreds of committed steps each: a thread of the kernel then owns
+    several jobs, the privileged list and the search for the next job to serve run over many wavefronts."""
+    n_moves = 0
+    for seed, J in enumerate([300, 1000, 1024, 1025, 2049, 3000] * 3):
+        rng = np.random.default_rng(96000 + seed)
+        wl, tb, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state = random_round(rng, orc, J, int(rng.integers(2, 23)))
+        want = orc.reschedule(wl.coef[:, 16], tb, wl.grid, wl.cluster, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state=state)
+        run = gpu(wl)
+        run.enumerate()
+        assert np.array_equal(run.table_numpy()["seg_g"], tb.seg_g)
+        got = on_gpu(run, bt, bp, ct, wl.cluster, cur_seg, cur_c, floor_seg, floor_c, state)
+        run.close()
+        same(got, want)
+        n_moves += want[2]
+    print(f"18 rounds, {n_moves} steps committed")
+    assert n_moves > 3000
 
 
 @pytest.mark.parametrize("name", ["paper_scale", "what_if", "stress"])
