@@ -552,7 +552,8 @@ int32_t rk_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs, const rk_a
  *  - a job tries first fit (as rk_place) with the amounts of assign[j], which
  *    must be a valid GPU count of the job, a CPU level and a memory tier of the
  *    grid at that count, with a feasible plan there (what rk_allocate and its
- *    relatives write; anything else is not placed);
+ *    relatives write; any other record gets status 3, books nothing and counts
+ *    among result->n_failed);
  *  - if the nodes do not hold them it falls back to its next smaller GPU count
  *    that has a feasible plan at the same CPU level and memory tier (CPUs and
  *    GiB follow the grid's modes), and so on, but not below its floor

@@ -731,6 +731,7 @@ int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, co
         for (uint32_t c = 0; c < grid->n_cpu; ++c) if (cpus_of(grid, c, g0) == assign[j].c) ci = c;
         for (uint32_t m = 0; m < grid->n_mem; ++m) if (tier_gb(grid, m, g0) == assign[j].mem_gb) mi = m;
         if (s0 < 0 || ci < 0 || mi < 0) return -1;          /* not an allocation on this table and grid */
+        if (!(best_thr[rows * s_off + ((uint64_t)ci * grid->n_mem + mi) * ns + s0] > 0.0f)) return -1;   /* no plan there */
         const int64_t s_min = (min_seg && min_seg[j] >= 0) ? min_seg[j] : 0;
         std::vector<ork_place_entry> parts;
         int64_t s = -1;

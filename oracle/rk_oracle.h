@@ -183,7 +183,10 @@ uint32_t ork_eval_one_placed(const float *coef17, const uint32_t *ints3, const o
  * fall-back to smaller valid GPU counts (not below min_seg[j], NULL or -1 = no
  * floor), then the best plan of the placed count under the bandwidths of the
  * actual node split.  out[n_jobs] = placed amounts, plan, throughput; status
- * 0 nothing to place, 1 placed as asked, 2 placed with fewer GPUs, 3 not placed. */
+ * 0 nothing to place, 1 placed as asked, 2 placed with fewer GPUs, 3 not placed.
+ * Returns -1 for a record that is no allocation on this table and grid (its
+ * GPU count, CPU level or memory tier is not one of the job's, or no plan is
+ * feasible there). */
 int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, const ork_bounds *bounds,
                     const ork_table *table, const ork_grid *grid, const ork_env *env, const float *best_thr,
                     const ork_assign *assign, const int32_t *min_seg, uint32_t n_nodes, uint32_t gpus_per_node,

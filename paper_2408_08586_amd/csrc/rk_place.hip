@@ -72,6 +72,24 @@ __device__ __forceinline__ GridPos locate(const GridDev &G, const uint32_t *seg_
     return P;
 }
 
+// Whether a record is an allocation on this table and grid: a GPU count of the job, a CPU level and a memory tier of
+// the grid at that count, with a feasible plan there.  By one thread (the counts of a job ascend: bisection).
+__device__ inline bool on_the_grid(const Retry &R, uint32_t j, uint32_t g, uint32_t c, float mem) {
+    const uint32_t s_off = R.seg_off[j], ns = R.seg_off[j + 1] - s_off;
+    uint32_t lo = 0, hi = ns;
+    while (lo < hi) {
+        const uint32_t mid = lo + (hi - lo) / 2;
+        if (R.seg_g[s_off + mid] < g) lo = mid + 1; else hi = mid;
+    }
+    if (lo >= ns || R.seg_g[s_off + lo] != g) return false;
+    int32_t ci = -1, mi = -1;
+    for (uint32_t k = 0; k < R.grid.n_cpu && ci < 0; ++k) if (cpus_of(R.grid, k, g) == c) ci = (int32_t)k;
+    for (uint32_t k = 0; k < R.grid.n_mem && mi < 0; ++k) if (tier_gib(R.grid, k, g) == mem) mi = (int32_t)k;
+    if (ci < 0 || mi < 0) return false;
+    const uint64_t at = (uint64_t)R.grid.n_cpu * R.grid.n_mem * s_off + ((uint64_t)ci * R.grid.n_mem + (uint32_t)mi) * ns + lo;
+    return R.best_thr[at] > 0.f;
+}
+
 __device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long long v, uint32_t lane) {
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
@@ -165,7 +183,7 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
     // ---- stage 1: the jobs end to end on the GPU slots; a thread takes eight neighbouring jobs
     const unsigned long long slots = (unsigned long long)A.n_nodes * A.gpn;
     unsigned long long carry_g = 0, carry_e = 0;          // GPU slots and parts before the tile
-    uint32_t n_sched = 0;
+    uint32_t n_sched = 0, n_off = 0;                      // jobs with parts; records that are no allocation here
     for (uint32_t base = 0; base < A.n_jobs; base += PLACE_THREADS * PLACE_PER) {
         const uint32_t j0 = base + tid * PLACE_PER;
         uint32_t g[PLACE_PER], c[PLACE_PER];
@@ -189,6 +207,13 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
                 g[i] = 0; c[i] = 0; mem[i] = 0.f;
                 if (j0 + i < A.n_jobs) { g[i] = A.assign[j0 + i].g; c[i] = A.assign[j0 + i].c; mem[i] = A.assign[j0 + i].mem_gb; }
             }
+        }
+        uint32_t off_grid = 0;                             // bit i: the record is no allocation here (not placed, status 3)
+        if (A.retry.on) {
+#pragma unroll
+            for (uint32_t i = 0; i < PLACE_PER; ++i)
+                if (g[i] > 0 && !on_the_grid(A.retry, j0 + i, g[i], c[i], mem[i])) { off_grid |= 1u << i; g[i] = 0; }
+            n_off += (uint32_t)__popc(off_grid);
         }
 #pragma unroll
         for (uint32_t i = 0; i < PLACE_PER; ++i) sum_g += g[i];
@@ -227,7 +252,11 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
         {   // offsets and status words of the thread's eight jobs: two 16-byte stores per array where that is possible
             uint32_t offs[PLACE_PER], stat[PLACE_PER], run = (uint32_t)at;
 #pragma unroll
-            for (uint32_t i = 0; i < PLACE_PER; ++i) { offs[i] = run; stat[i] = g[i] > 0 ? 1u : 0u; run += parts[i]; }
+            for (uint32_t i = 0; i < PLACE_PER; ++i) {
+                offs[i] = run;
+                stat[i] = g[i] > 0 ? 1u : ((off_grid >> i) & 1u) ? 3u : 0u;
+                run += parts[i];
+            }
             const bool whole8 = j0 + PLACE_PER <= A.n_jobs &&
                                 ((reinterpret_cast<uintptr_t>(A.place_off) | reinterpret_cast<uintptr_t>(A.status)) & 15u) == 0;
             if (whole8) {
@@ -275,11 +304,12 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
     for (uint32_t n = tid; n < A.n_nodes; n += PLACE_THREADS)
         if (nodeA[n] > A.cpn || !(nodeM[n] <= 0.999f * A.mpn)) redo = 1u;
     unsigned long long placed_all;
-    (void)block_excl_scan(n_sched, red, placed_all);      // also the barrier after the writes to redo
+    (void)block_excl_scan(((unsigned long long)n_off << 32) | n_sched, red, placed_all);   // also the barrier after the writes to redo
     if (!redo) {
         if (tid == 0) {
             A.place_off[A.n_jobs] = (uint32_t)carry_e;
-            A.result[0] = (uint32_t)carry_e; A.result[1] = (uint32_t)placed_all; A.result[2] = 0u; A.result[3] = 0u;
+            A.result[0] = (uint32_t)carry_e; A.result[1] = (uint32_t)placed_all; A.result[2] = (uint32_t)(placed_all >> 32);
+            A.result[3] = 0u;
         }
         return;
     }
@@ -297,6 +327,8 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
         float mem = 0.f;
         if (j < A.n_jobs) { g = A.assign[j].g; c = A.assign[j].c; mem = A.assign[j].mem_gb; }
         uint32_t my_off = 0, my_status = 0;
+        if (A.retry.on && g > 0 && !on_the_grid(A.retry, j, g, c, mem)) { g = 0; my_status = 3u; }   // no allocation here
+        n_failed += (uint32_t)__popcll(__ballot(my_status == 3u));
         bool have_off = false;
         unsigned long long todo = __ballot(g > 0);
         while (todo) {

@@ -240,3 +240,65 @@ def test_whole_round_on_nodes_is_its_pieces(gpu, orc, with_sla):
     compare(orc, wl, ot, want, got)
     assert res1.n_placed > 3
     run.close()
+
+
+def test_argument_errors_and_amounts_off_the_grid(gpu, orc):
+    """Error codes of rk_place_plans, and records that are not an allocation on this table and grid: such a job is
+    not placed (status 3), books nothing, and the others are placed as if it had asked for nothing."""
+    import torch
+    import paper_2408_08586_amd as rk
+    wl = dataclasses.replace(workloads.paper_scale(), bounds=workloads.Bounds(g_max=6))
+    r = orc.schedule_round(wl, n_threads=8)
+    J = wl.n_jobs
+    run = gpu(wl)
+    run.enumerate()
+    dev = run.device
+    a = r["assign"].copy()
+    served = np.flatnonzero(a["g"] > 0)
+    assert served.size >= 6
+    bad = a.copy()
+    j0, j1, j2 = (int(x) for x in served[:3])
+    counts = r["table"].seg_g[r["table"].seg_off[j0]:r["table"].seg_off[j0 + 1]].tolist()
+    bad["g"][j0] = next(g for g in range(2, 64) if g not in counts)          # not a GPU count of the job
+    bad["c"][j1] += 1000                                                     # not a CPU level of the grid
+    bad["mem_gb"][j2] = 3.0                                                  # not a memory tier of the grid
+    gone = a.copy()
+    for j in (j0, j1, j2):
+        gone[j] = (0, 0, 0.0, orc.NO_PLAN, 0.0)
+    want = orc.place_plans(wl.coef, wl.ints, wl.bounds, r["table"], wl.grid, wl.env, r["best_thr"], gone, 8, 8, 64, 4096.0)
+    got = place_on_gpu(run, r["best_thr"], bad, None, 8, 8, 64, 4096.0)
+    st = got[3].copy()
+    assert st[j0] == 3 and st[j1] == 3 and st[j2] == 3 and got[5].n_failed == 3
+    st[[j0, j1, j2]] = 0
+    assert np.array_equal(st, want[3]) and np.array_equal(got[1], want[1])
+    for f in ("node", "g", "c", "mem_gb"):
+        assert np.array_equal(got[2][f], want[2][f])
+    for f in ("g", "c", "mem_gb", "plan"):
+        assert np.array_equal(got[0][f], want[0][f]), f
+
+    d_assign = torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).copy()).to(dev)
+    cap = 64
+    mk = lambda: (rk.new_assign(J, dev), torch.zeros(J + 1, dtype=torch.int32, device=dev), rk.new_place_entries(cap, dev),
+                  torch.zeros(J, dtype=torch.int32, device=dev), run.f32(1))
+    bt = run.dev_f32(r["best_thr"])
+
+    def call(nodes=None, placed="ok", cap_entries=cap, total="ok", best="ok", jobs=None):
+        p, o, e, s, t = mk()
+        return rk.rk_place_plans(run.ctx, jobs or run.jobs, run.table.c, run.grid, run.env, nodes or rk.rk_nodes(8, 8, 64, 4096.0),
+                                 bt if best == "ok" else None, d_assign, None, p if placed == "ok" else None, o, e, cap_entries, s,
+                                 t if total == "ok" else None)
+
+    assert call().n_placed == served.size
+    for kwargs, code in (({"placed": None}, rk.RK_ERR_INVALID_ARG), ({"total": None}, rk.RK_ERR_INVALID_ARG),
+                         ({"best": None}, rk.RK_ERR_INVALID_ARG), ({"cap_entries": 63}, rk.RK_ERR_CAPACITY),
+                         ({"nodes": rk.rk_nodes(5000, 8, 64, 4096.0)}, rk.RK_ERR_UNSUPPORTED),
+                         ({"nodes": rk.rk_nodes(8, 0, 64, 4096.0)}, rk.RK_ERR_UNSUPPORTED)):
+        with pytest.raises(rk.RkError) as e:
+            call(**kwargs)
+        assert e.value.code == code, kwargs
+    other = rk.Jobs(wl.coef[:5], wl.ints[:5], dev)
+    with pytest.raises(rk.RkError) as e:
+        call(jobs=other)
+    assert e.value.code == rk.RK_ERR_INVALID_ARG
+    assert call().n_placed == served.size                                   # the context works on after the errors
+    run.close()
