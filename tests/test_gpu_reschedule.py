@@ -113,6 +113,34 @@ def test_random_rounds_on_drawn_values(gpu, orc):
     assert n_moves > 1500 and n_priv > 100
 
 
+def test_states_outside_their_ranges(gpu, orc):
+    """What a caller may get wrong without an error: a held GPU count or CPU level the job does not have (the job then
+    holds nothing), a floor that is no index of its list (no floor), a floor's CPU level beyond the grid (clamped), a
+    state byte other than 0 (takes no part), jobs that hold more than the cluster has.  Both sides read them alike."""
+    n_moves = 0
+    for seed in range(60):
+        rng = np.random.default_rng(97000 + seed)
+        wl, tb, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state = random_round(rng, orc)
+        J, g_max, n_cpu = wl.n_jobs, wl.bounds.g_max, len(wl.grid.cpu_levels)
+        for j in range(J):
+            u = rng.uniform()
+            if u < 0.10: cur_seg[j] = g_max + int(rng.integers(0, 3))
+            elif u < 0.20: cur_c[j] = n_cpu + int(rng.integers(0, 3))
+            elif u < 0.30: floor_seg[j] = g_max + int(rng.integers(0, 100))
+            elif u < 0.40: floor_c[j] = n_cpu + int(rng.integers(0, 1000))
+            elif u < 0.45: state[j] = int(rng.choice([2, 7, 255]))
+            elif u < 0.50: cur_seg[j], floor_seg[j] = -5, -7
+        cl = wl.cluster if seed % 3 else workloads.Cluster(wl.cluster.G // 3, wl.cluster.C // 3, wl.cluster.host_mem_gb)
+        want = orc.reschedule(wl.coef[:, 16], tb, wl.grid, cl, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state=state)
+        run = gpu(wl)
+        run.enumerate()
+        got = on_gpu(run, bt, bp, ct, cl, cur_seg, cur_c, floor_seg, floor_c, state)
+        run.close()
+        same(got, want)
+        n_moves += want[2]
+    assert n_moves > 100
+
+
 def test_larger_drawn_rounds(gpu, orc):
     """Rounds of hundreds to thousands of jobs with hundreds of committed steps each: a thread of the kernel then owns
     several jobs, the privileged list and the search for the next job to serve run over many wavefronts."""
