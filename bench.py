@@ -143,6 +143,36 @@ def cpu_baseline(wl, sample_jobs):
             "one_thread": main["one_thread"], "other_configurations": others}
 
 
+def other_rounds(rk, ctx, dev, skip, reps):
+    """rk_schedule_round on the small configurations (the oracle's times for the same rounds are in cpu_baseline):
+    latency of the whole round, host-synchronous, inputs resident."""
+    import torch
+    import workloads
+    out = {}
+    for name, make in (("tiny", workloads.tiny), ("paper_scale", workloads.paper_scale), ("large", workloads.large)):
+        if name == skip:
+            continue
+        w = make()
+        jobs = rk.Jobs(w.coef, w.ints, dev)
+        bounds, grid, env, cluster = rk.make_bounds(w.bounds), rk.make_grid(w.grid), rk.make_env(w.env), rk.make_cluster(w.cluster)
+        table = rk.enumerate_to_table(ctx, jobs, bounds, dev)
+        n_rows = len(w.grid.cpu_levels) * len(w.grid.mem_levels_gb)
+        assign, total = rk.new_assign(w.n_jobs, dev), torch.zeros(1, dtype=torch.float32, device=dev)
+        lat = []
+        for i in range(reps + 3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            rk.rk_schedule_round(ctx, jobs, bounds, grid, env, cluster, assign, total)
+            torch.cuda.synchronize()
+            if i >= 3:
+                lat.append((time.perf_counter() - t0) * 1e3)
+        n = table.n_candidates(n_rows)
+        out[name] = {"jobs": w.n_jobs, "candidates": n, "round_ms": {"min": float(np.min(lat)), "median": float(np.median(lat)),
+                                                                     "max": float(np.max(lat))},
+                     "nominal_candidates_per_s": n / (float(np.median(lat)) * 1e-3)}
+    return out
+
+
 def what_if_batch(rk, ctx, dev, n_rounds):
     """What-if configuration: independent rounds of 500 jobs on about 512 GPUs.  Latency of each round run on
     its own (rk_schedule_round, host-synchronous) and time of all rounds as one rk_schedule_rounds batch."""
@@ -516,8 +546,8 @@ def main():
     seg_count = [table.n_segments(n_rows, int(a), int(b)) for a, b in zip(edges[:-1], edges[1:])]
 
     # Event records cost the stream a few microseconds each, so the timed steps carry only those that the roofline
-    # needs (one before k_eval, one between k_eval and k_best_plan, one after k_best_plan, per chunk); the duration of
-    # every stage is measured in a pass of its own after the timed region, with events around every call.
+    # needs (one before the first k_eval, then one after every k_eval and every k_best_plan: 7 per step of 3 chunks);
+    # the duration of every stage is measured in a pass of its own after the timed region, with events around every call.
     hot_ms = {"eval": [], "best_plan": []}
     stage_ms = {"enumerate": [], "eval": [], "best_plan": [], "curves": [], "allocate": []}
 
@@ -534,10 +564,11 @@ def main():
         if every:
             e1 = mark()
             stage_ms["enumerate"].append((e0, e1))
+        c = None
         for k in range(n_chunks):
             jb, je = int(edges[k]), int(edges[k + 1])
             s0 = seg_start[k]
-            a = mark() if mode else None
+            a = (c or mark()) if mode else None           # the event after a chunk's best plan also opens the next chunk
             rk.rk_eval_candidates(ctx, jobs, table.c, grid, env, jb, je, thr, None)
             b = mark() if mode else None
             rk.rk_best_plan(ctx, table.c, grid, jb, je, thr, best_thr[s0:], best_plan[s0:])
@@ -747,6 +778,8 @@ def main():
     if not args.no_sim:
         out["simulation"] = sim_bench(rk, ctx, dev, 3)
     if not args.no_what_if:
+        out["other_configurations"] = {"entry": "rk_schedule_round (fused evaluation, host-synchronous)",
+                                       **other_rounds(rk, ctx, dev, args.workload, 20)}
         out["what_if"] = what_if_batch(rk, ctx, dev, args.what_if_rounds)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_jobs)
