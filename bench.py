@@ -568,7 +568,7 @@ def main():
         for k in range(n_chunks):
             jb, je = int(edges[k]), int(edges[k + 1])
             s0 = seg_start[k]
-            a = (c or mark()) if mode else None           # the event after a chunk's best plan also opens the next chunk
+            a = (mark() if c is None else c) if mode else None   # the event after a chunk's best plan also opens the next
             rk.rk_eval_candidates(ctx, jobs, table.c, grid, env, jb, je, thr, None)
             b = mark() if mode else None
             rk.rk_best_plan(ctx, table.c, grid, jb, je, thr, best_thr[s0:], best_plan[s0:])
