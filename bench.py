@@ -2,8 +2,9 @@
 """Benchmark of the plan-evaluation path on one MI355X.
 
 A step is one pass of the whole path over one synthetic scheduling problem:
-enumerate plans -> (per job chunk) evaluate candidates, best plan per segment
--> curves -> greedy allocation.  Inputs are resident in HBM before the timed
+enumerate plans -> (per job chunk) evaluate candidates into the candidate
+tensor and take the best plan per segment, in one kernel -> curves -> greedy
+allocation.  Inputs are resident in HBM before the timed
 region.  Prints one JSON line.
 """
 from __future__ import annotations
@@ -546,10 +547,12 @@ def main():
     seg_count = [table.n_segments(n_rows, int(a), int(b)) for a, b in zip(edges[:-1], edges[1:])]
 
     # Event records cost the stream a few microseconds each, so the timed steps carry only those that the roofline
-    # needs (one before the first k_eval, then one after every k_eval and every k_best_plan: 7 per step of 3 chunks);
-    # the duration of every stage is measured in a pass of its own after the timed region, with events around every call.
-    hot_ms = {"eval": [], "best_plan": []}
-    stage_ms = {"enumerate": [], "eval": [], "best_plan": [], "curves": [], "allocate": []}
+    # needs (one before the first chunk's kernel, then one after every chunk's: 4 per step of 3 chunks); the duration
+    # of every stage is measured in a pass of its own after the timed region, with events around every call, and so
+    # is the same path with the evaluation and the best plan as two kernels (rk_eval_candidates, rk_best_plan).
+    hot_ms = {"eval_best": []}
+    stage_ms = {"enumerate": [], "eval_best": [], "curves": [], "allocate": []}
+    pair_ms = {"eval": [], "best_plan": []}
 
     def mark():
         e = torch.cuda.Event(enable_timing=True)
@@ -557,7 +560,8 @@ def main():
         return e
 
     def step(mode):
-        """mode: None = no events, "hot" = events around the two HBM-bound kernels, "all" = around every call."""
+        """mode: None = no events, "hot" = events around the HBM-bound kernel, "all" = around every call, "pair" = the
+        evaluation and the best plan as two kernels, events around both."""
         every = mode == "all"
         e0 = mark() if every else None
         rk.rk_enumerate_plans(ctx, jobs, bounds, table.c)
@@ -568,14 +572,20 @@ def main():
         for k in range(n_chunks):
             jb, je = int(edges[k]), int(edges[k + 1])
             s0 = seg_start[k]
-            a = (mark() if c is None else c) if mode else None   # the event after a chunk's best plan also opens the next
-            rk.rk_eval_candidates(ctx, jobs, table.c, grid, env, jb, je, thr, None)
-            b = mark() if mode else None
-            rk.rk_best_plan(ctx, table.c, grid, jb, je, thr, best_thr[s0:], best_plan[s0:])
+            a = (mark() if c is None else c) if mode else None   # the event after a chunk's kernel also opens the next
+            if mode == "pair":
+                rk.rk_eval_candidates(ctx, jobs, table.c, grid, env, jb, je, thr, None)
+                b = mark()
+                rk.rk_best_plan(ctx, table.c, grid, jb, je, thr, best_thr[s0:], best_plan[s0:])
+                c = mark()
+                pair_ms["eval"].append((a, b))
+                pair_ms["best_plan"].append((b, c))
+                continue
+            # candidates of the chunk to thr, their per-segment maxima and plans to best_thr / best_plan, in one pass
+            rk.rk_eval_best_plan(ctx, jobs, table.c, grid, env, jb, je, thr, best_thr[s0:], best_plan[s0:])
             if mode:
                 c = mark()
-                (stage_ms if every else hot_ms)["eval"].append((a, b))
-                (stage_ms if every else hot_ms)["best_plan"].append((b, c))
+                (stage_ms if every else hot_ms)["eval_best"].append((a, c))
         # the curves need only the per-segment maxima, which are small: one launch for all jobs
         e15 = mark() if every else None
         rk.rk_curves(ctx, table.c, grid, 0, J, best_thr, best_plan, curve_thr, curve_plan, curve_g)
@@ -587,7 +597,7 @@ def main():
             stage_ms["allocate"].append((e2, mark()))
 
     # What the chip gives kernels that do nothing but fill, then read, the candidate buffer of one chunk: the measured
-    # ceiling of the k_eval + k_best_plan pair.  A read that follows a write of the same buffer is slower than the same
+    # ceiling of the one-pass kernel (the fill) and of the k_eval + k_best_plan pair (fill, then read).  A read that follows a write of the same buffer is slower than the same
     # read after another read (the written lines are still on their way to HBM), so both positions are timed.
     n_probe = (max(chunk_cands) // 4) * 4
     probe = {"fill": [], "read_after_fill": [], "read_after_read": []}
@@ -632,11 +642,14 @@ def main():
     stage_steps = min(args.steps, 5)
     for _ in range(stage_steps):
         step("all")
+    for _ in range(stage_steps):
+        step("pair")
     torch.cuda.synchronize()
     mean_ms = lambda v: sum(a.elapsed_time(b) for a, b in v) / len(v) if v else 0.0
     avg_ms = {k: mean_ms(v) for k, v in stage_ms.items()}
     per_step_ms = {k: avg_ms[k] * (len(v) / stage_steps) for k, v in stage_ms.items()}
     hot_avg_ms = {k: mean_ms(v) for k, v in hot_ms.items()}
+    pair_avg_ms = {k: mean_ms(v) for k, v in pair_ms.items()}
 
     # fused round (the path a scheduler would call): latency of rk_schedule_round
     for _ in range(2):
@@ -673,16 +686,18 @@ def main():
     seg_per_launch = n_seg / n_chunks
     bytes_eval = 4.0 * cand_per_launch + 4.0 * table.n_triples / n_chunks
     bytes_best = 4.0 * cand_per_launch + 8.0 * seg_per_launch
-    gbs_eval = bytes_eval / (hot_avg_ms["eval"] * 1e-3) / 1e9            # over the launches of the timed region
-    gbs_best = bytes_best / (hot_avg_ms["best_plan"] * 1e-3) / 1e9
-    dom = "eval" if hot_avg_ms["eval"] >= hot_avg_ms["best_plan"] else "best_plan"
-    achieved = gbs_eval if dom == "eval" else gbs_best
-    pair_gbs = (bytes_eval + bytes_best) / ((hot_avg_ms["eval"] + hot_avg_ms["best_plan"]) * 1e-3) / 1e9
+    # the one-pass kernel writes every candidate once (4 B), reads the plan table (4 B per triple) and writes the
+    # per-segment results (8 B per entry); it does not read the candidates back
+    bytes_one = 4.0 * cand_per_launch + 4.0 * table.n_triples / n_chunks + 8.0 * seg_per_launch
+    achieved = bytes_one / (hot_avg_ms["eval_best"] * 1e-3) / 1e9         # over the launches of the timed region
+    gbs_eval = bytes_eval / (pair_avg_ms["eval"] * 1e-3) / 1e9
+    gbs_best = bytes_best / (pair_avg_ms["best_plan"] * 1e-3) / 1e9
+    pair_gbs = (bytes_eval + bytes_best) / ((pair_avg_ms["eval"] + pair_avg_ms["best_plan"]) * 1e-3) / 1e9
 
     digest = kernel_digest()
     traffic = None
     if args.workload == "stress" and n_chunks == 3:
-        traffic = MEASURED_TRAFFIC.get(digest, {}).get("k_eval" if dom == "eval" else "k_best_plan")
+        traffic = MEASURED_TRAFFIC.get(digest, {}).get("k_eval_best")
         if traffic is None:
             print(f"bench.py: the evaluation kernels' sources (digest {digest}) have changed since the HBM counters of "
                   f"profiles/hbm_traffic_stress.txt were taken: roofline.traffic is null until they are taken again",
@@ -696,23 +711,29 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": desc, "n_jobs": J, "n_candidates": n_cand, "n_segment_rows": n_seg,
                    "n_triples": table.n_triples, "job_chunks": n_chunks},
-        "roofline": {"bound": "hbm", "kernel": "k_eval" if dom == "eval" else "k_best_plan",
+        "roofline": {"bound": "hbm", "kernel": "k_eval_best",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "algorithmic_bytes_per_launch": bytes_eval if dom == "eval" else bytes_best,
+                     "algorithmic_bytes_per_launch": bytes_one,
                      "traffic": traffic, "traffic_source": "profiles/hbm_traffic_stress.txt (rocprofv3 --pmc FETCH_SIZE / "
                                                             "WRITE_SIZE, scaled by a plain copy's counters)",
                      "kernel_source_digest": digest},
         "kernels": {"timed_region_avg_launch_ms": hot_avg_ms,
                     "stage_pass": "separate pass after the timed region, events around every call",
                     "avg_launch_ms": avg_ms, "per_step_ms": per_step_ms,
-                    "eval_GBps": gbs_eval, "best_plan_GBps": gbs_best,
-                    "eval_plus_best_plan_GBps": pair_gbs, "eval_plus_best_plan_frac_of_hbm": pair_gbs / HBM_PEAK_GBS,
+                    "eval_best_candidates_per_s": n_cand / (hot_avg_ms["eval_best"] * n_chunks * 1e-3),
                     # kernels that only fill and only read the same buffer (4 bytes per candidate each way)
                     "plain_stream_ms": probe_ms,
-                    "eval_plus_best_plan_over_plain_fill_plus_read":
-                        (hot_avg_ms["eval"] + hot_avg_ms["best_plan"]) / (probe_ms["fill"] + probe_ms["read_after_fill"]),
-                    "eval_plus_best_plan_candidates_per_s":
-                        n_cand / ((hot_avg_ms["eval"] + hot_avg_ms["best_plan"]) * n_chunks * 1e-3)},
+                    "eval_best_over_plain_fill": hot_avg_ms["eval_best"] / probe_ms["fill"],
+                    # the same path with the candidates read back: rk_eval_candidates, then rk_best_plan
+                    "two_kernels": {"pass": "separate pass after the timed region, events around both kernels",
+                                    "avg_launch_ms": pair_avg_ms, "eval_GBps": gbs_eval, "best_plan_GBps": gbs_best,
+                                    "eval_plus_best_plan_GBps": pair_gbs,
+                                    "eval_plus_best_plan_frac_of_hbm": pair_gbs / HBM_PEAK_GBS,
+                                    "eval_plus_best_plan_over_plain_fill_plus_read":
+                                        (pair_avg_ms["eval"] + pair_avg_ms["best_plan"]) /
+                                        (probe_ms["fill"] + probe_ms["read_after_fill"]),
+                                    "eval_plus_best_plan_candidates_per_s":
+                                        n_cand / ((pair_avg_ms["eval"] + pair_avg_ms["best_plan"]) * n_chunks * 1e-3)}},
         "round_latency_ms": {"entry": "rk_schedule_round (fused evaluation, host-synchronous)",
                              "min": float(lat.min()), "median": float(np.median(lat)), "max": float(lat.max()),
                              "with_cached_curves": {"entry": "rk_allocate on curves kept from an earlier round",

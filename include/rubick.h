@@ -209,6 +209,21 @@ int32_t rk_best_plan(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_gri
                      uint32_t job_begin, uint32_t job_end, const float *thr,
                      float *best_thr, uint32_t *best_plan, uint64_t cap_segs, uint64_t *n_needed);
 
+/* rk_eval_candidates and rk_best_plan in one pass over jobs [job_begin,
+ * job_end) (Sec. 4, Eq. 1 and GetBestPlan, Sec. 5.2): thr (and feas, if given)
+ * receive exactly what rk_eval_candidates writes, best_thr / best_plan exactly
+ * what rk_best_plan then gives on that thr, but the candidates are reduced
+ * while they are still in registers, so the tensor is written once and not
+ * read back.  cap = capacity of thr (and feas) in candidates, cap_segs = of the
+ * two segment outputs in entries; RK_ERR_CAPACITY when either is too small.
+ * When the keys of one CPU level's rows (n_mem * longest segment list * 8
+ * bytes) do not fit in LDS the two kernels run one after the other instead. */
+int32_t rk_eval_best_plan(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table,
+                          const rk_alloc_grid *grid, const rk_env *env,
+                          uint32_t job_begin, uint32_t job_end,
+                          float *thr, uint8_t *feas_or_null, uint64_t cap,
+                          float *best_thr, uint32_t *best_plan, uint64_t cap_segs);
+
 /* Resource sensitivity curves from the per-segment maxima (Sec. 5.2, Fig. 6):
  * per job and row, over the job's GPU counts in ascending order, the best
  * throughput achievable within that many GPUs, its plan and the smallest GPU

@@ -26,7 +26,7 @@ FIT_FIELDS = ("k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_con
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
            "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
            "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared", "rk_place", "rk_allocate_static", "rk_place_plans",
-           "rk_schedule_round_placed", "rk_reschedule", "rk_probe_stream")
+           "rk_schedule_round_placed", "rk_reschedule", "rk_probe_stream", "rk_eval_best_plan")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -267,6 +267,14 @@ def rk_best_plan(ctx, table: rk_plan_table, grid: rk_alloc_grid, job_begin, job_
                                             C.c_uint32(job_end), _ptr(thr), _ptr(best_thr), _ptr(best_plan),
                                             C.c_uint64(0 if best_thr is None else best_thr.numel()), C.byref(need)))
     return need.value
+
+
+def rk_eval_best_plan(ctx, jobs: Jobs, table: rk_plan_table, grid: rk_alloc_grid, env: rk_env, job_begin, job_end, thr,
+                      best_thr, best_plan, feas=None):
+    _check(ctx, load_library().rk_eval_best_plan(ctx, C.byref(jobs.c), C.byref(table), C.byref(grid), C.byref(env),
+                                                 C.c_uint32(job_begin), C.c_uint32(job_end), _ptr(thr), _ptr(feas),
+                                                 C.c_uint64(0 if thr is None else thr.numel()), _ptr(best_thr),
+                                                 _ptr(best_plan), C.c_uint64(0 if best_thr is None else best_thr.numel())))
 
 
 def rk_curves(ctx, table, grid, job_begin, job_end, best_thr, best_plan, curve_thr, curve_plan, curve_g):

@@ -173,6 +173,156 @@ __global__ __launch_bounds__(BEST_MAX_WAVES * 64) void k_best_plan(TableDev tb, 
     }
 }
 
+// ------------------------------------------- evaluation and best plan in one pass
+// The evaluation kernel's thread mapping and stores (a thread owns (triple, ZeRO stage), a wavefront writes 1 KiB
+// contiguous per row), with one workgroup per (job, group of CPU levels) whose wavefronts walk the job's triples, 16
+// per wavefront at a time, and keep, per row and segment, the packed key of the best plan in LDS: the candidate tensor
+// is written once and never read back.  The workgroup is as large as the longest job of the call needs to take all its
+// triples at once (at most 1,024 threads = 256 triples per round), so that a call has about as many wavefronts in
+// flight as the plain evaluation kernel.  The options without offload are the same in every row and the offload options depend on the
+// CPU level only (the memory tier masks them), so the four lanes of a triple reduce their keys once per tile and
+// once per CPU level (two DPP steps each); a row then costs the quad leader a select and one LDS atomic maximum.
+// The keys are those of k_best_plan on the values stored, so the results are the same bits.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+
+constexpr int EVAL_BEST_MAX_THREADS = 1024;
+
+// A workgroup barrier that orders LDS traffic only: every wavefront waits for its own LDS operations (lgkmcnt 0), not
+// for its global loads and stores, which __syncthreads() would also drain.  Enough where the data exchanged is in LDS.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_s_waitcnt(0xC07F);          // vmcnt 63, expcnt 7, lgkmcnt 0
+    __builtin_amdgcn_s_barrier();
+}
+
+template <bool WITH_FEAS>
+__global__ __launch_bounds__(EVAL_BEST_MAX_THREADS) void k_eval_best(JobDev jobs, TableDev tb, GridDev grid, rk_env env, uint32_t jb,
+                                                            uint32_t option_mask, uint32_t c_per_block, uint32_t max_nt,
+                                                            uint32_t max_ns, float *__restrict__ thr,
+                                                            uint8_t *__restrict__ feas, float *__restrict__ best_thr,
+                                                            uint32_t *__restrict__ best_plan) {
+    extern __shared__ unsigned long long lds64[];
+    const uint32_t rows_here = c_per_block * grid.n_mem;
+    unsigned long long *seg_key = lds64;                                               // [rows_here][ns]
+    uint16_t *seg_of = reinterpret_cast<uint16_t *>(seg_key + (size_t)rows_here * max_ns);   // [max_nt]
+    const uint32_t tid = threadIdx.x, n_thr = blockDim.x;
+    const uint32_t j = jb + blockIdx.x;
+    const uint32_t t0 = tb.triple_off[j], nt = tb.triple_off[j + 1] - t0;
+    const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
+    if (nt == 0) return;                                                               // no plan: no candidates, no segments
+    const uint32_t z = tid & 3u;
+    const uint32_t n_rows = grid.n_cpu * grid.n_mem;
+    const uint64_t cbase = 16ull * n_rows * (uint64_t)(t0 - tb.triple_off[jb]);
+    const uint32_t c_lo = blockIdx.y * c_per_block;
+    const uint32_t c_hi = c_lo + c_per_block < grid.n_cpu ? c_lo + c_per_block : grid.n_cpu;
+    const Job J = load_job(jobs, j);
+
+    // The thread's triples are fetched before the loop (at most eight: 2,048 triples over 256 quads, and a smaller
+    // workgroup covers its longest job in one round).  Inside the loop nothing is loaded from global memory, so no
+    // wavefront ever waits for its earlier stores on the way to its next triple: the memory counter it would wait on
+    // counts loads and stores alike, in order.
+    constexpr uint32_t MAX_ROUNDS = RK_MAX_TRIPLES_PER_JOB / (EVAL_BEST_MAX_THREADS / 4);
+    uint32_t mine[MAX_ROUNDS];
+#pragma unroll
+    for (uint32_t k = 0; k < MAX_ROUNDS; ++k) {
+        const uint32_t tl = (tid >> 2) + k * (n_thr >> 2);
+        mine[k] = tl < nt ? tb.triples[t0 + tl] : 0u;
+    }
+    // the triple -> segment map and the empty keys, while those loads are on their way
+    for (uint32_t s = tid; s < ns; s += n_thr) {
+        const uint32_t first = tb.seg_first[s0 + s];
+        const uint32_t last = s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt;
+        for (uint32_t t = first; t < last; ++t) seg_of[t] = (uint16_t)s;
+    }
+    for (uint32_t i = tid; i < rows_here * ns; i += n_thr) seg_key[i] = 0ull;
+    lds_barrier();
+
+    for (uint32_t tl = tid >> 2; tl < nt; tl += n_thr >> 2) {                          // the four lanes of a quad share tl
+        const Triple T = triple_terms(J, env, mine[0]);
+#pragma unroll
+        for (uint32_t k = 0; k + 1 < MAX_ROUNDS; ++k) mine[k] = mine[k + 1];
+        const uint32_t plan0 = tl * 16 + z * 4;
+        float plain[2];
+        uint32_t why_plain[2];
+#pragma unroll
+        for (uint32_t gc = 0; gc < 2; ++gc) {
+            const bool allowed = (option_mask >> (z * 4 + gc * 2)) & 1u;
+            const bool fits = gpu_mem_fits(J, env, T, z, gc, 0);
+            why_plain[gc] = allowed ? (fits ? 0u : RK_INFEASIBLE_GPU_MEM) : RK_INFEASIBLE_STRUCT;
+            plain[gc] = why_plain[gc] ? 0.f : thr_plain(J, T, z, gc);
+        }
+        uint32_t why_off[2];
+#pragma unroll
+        for (uint32_t gc = 0; gc < 2; ++gc) {
+            const bool allowed = z >= 2 && ((option_mask >> (z * 4 + gc * 2 + 1)) & 1u);
+            why_off[gc] = allowed ? (gpu_mem_fits(J, env, T, z, gc, 1) ? 0u : RK_INFEASIBLE_GPU_MEM)
+                                  : RK_INFEASIBLE_STRUCT;
+        }
+        const bool any_off = z >= 2 && (!(why_off[0] & RK_INFEASIBLE_STRUCT) || !(why_off[1] & RK_INFEASIBLE_STRUCT));
+        Offload O = {};
+        float need_host = 0.f;
+        if (any_off) {
+            O = offload_terms(J, env, T);
+            need_host = host_bytes_needed(J, T);
+        }
+        // what the quad knows together: the best option without offload, and the host bytes of the triple (the same
+        // in every lane that offloads, 0 in the others; not negative, so the float maximum picks it)
+        unsigned long long k_plain = max_u64(make_key(plain[0], plan0), make_key(plain[1], plan0 + 2));
+        k_plain = max_u64(k_plain, dpp_u64<0xB1>(k_plain));                            // quad_perm [1,0,3,2]
+        k_plain = max_u64(k_plain, dpp_u64<0x4E>(k_plain));                            // quad_perm [2,3,0,1]
+        float quad_host = fmaxf(need_host, dpp_f32<0xB1>(need_host));
+        quad_host = fmaxf(quad_host, dpp_f32<0x4E>(quad_host));
+        const uint32_t seg = seg_of[tl];
+
+        for (uint32_t ci = c_lo; ci < c_hi; ++ci) {
+            float off_thr[2] = {0.f, 0.f};
+            if (any_off) {
+                const float sw = swap_term(J, O, cpus_of(grid, ci, T.g));
+                off_thr[0] = thr_offload(T, O, 0, sw);
+                off_thr[1] = thr_offload(T, O, 1, sw);
+            }
+            // the best of all options when the tier holds the offloaded state
+            unsigned long long k_all = max_u64(make_key(why_off[0] ? 0.f : off_thr[0], plan0 + 1),
+                                               make_key(why_off[1] ? 0.f : off_thr[1], plan0 + 3));
+            k_all = max_u64(k_all, dpp_u64<0xB1>(k_all));
+            k_all = max_u64(k_all, dpp_u64<0x4E>(k_all));
+            k_all = max_u64(k_all, k_plain);
+            unsigned long long *keys = seg_key + (size_t)(ci - c_lo) * grid.n_mem * ns + seg;
+            for (uint32_t mi = 0; mi < grid.n_mem; ++mi) {
+                const float tier = tier_bytes(grid, mi, T.g);
+                uint32_t w0 = why_off[0], w1 = why_off[1];
+                if (any_off && !(need_host <= tier)) {
+                    if (!(w0 & RK_INFEASIBLE_STRUCT)) w0 |= RK_INFEASIBLE_HOST_MEM;
+                    if (!(w1 & RK_INFEASIBLE_STRUCT)) w1 |= RK_INFEASIBLE_HOST_MEM;
+                }
+                v4f v;
+                v.x = plain[0];
+                v.y = w0 ? 0.f : off_thr[0];
+                v.z = plain[1];
+                v.w = w1 ? 0.f : off_thr[1];
+                const uint64_t idx = cbase + ((uint64_t)(ci * grid.n_mem + mi) * nt + tl) * 16 + z * 4;
+                *reinterpret_cast<v4f *>(thr + idx) = v;
+                if (WITH_FEAS) {
+                    const uint32_t packed = why_plain[0] | (w0 << 8) | (why_plain[1] << 16) | (w1 << 24);
+                    *reinterpret_cast<uint32_t *>(feas + idx) = packed;
+                }
+                const unsigned long long k = quad_host <= tier ? k_all : k_plain;
+                if (z == 0 && (k >> 32)) atomicMax(keys + (size_t)mi * ns, k);
+            }
+        }
+    }
+    lds_barrier();                                                                     // the stores above need not have landed
+    const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]) + (uint64_t)c_lo * grid.n_mem * ns;
+    const uint32_t n_out = (c_hi - c_lo) * grid.n_mem * ns;                            // this workgroup's rows are contiguous
+    for (uint32_t i = tid; i < n_out; i += n_thr) {
+        const unsigned long long k = seg_key[i];
+        best_thr[sbase + i] = key_thr(k);
+        best_plan[sbase + i] = key_plan(k);
+    }
+}
+
 // ------------------------------------------------------------------- curves
 // One workgroup per job; its wavefronts split the job's rows.  A wavefront
 // walks its rows, which are contiguous in memory, 64 entries at a time: each
@@ -320,6 +470,66 @@ int32_t rk_best_plan(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_gri
     k_best_plan<<<(uint32_t)blocks, wpb * 64, lds, ctx->stream>>>(table_dev(table), (uint32_t)n_rows, jb, wpb, groups,
                                                                  max_nt, max_ns, thr, best_thr, best_plan);
     RK_CHECK_LAUNCH(ctx, "k_best_plan");
+    return RK_OK;
+}
+
+int32_t rk_eval_best_plan(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table, const rk_alloc_grid *grid,
+                          const rk_env *env, uint32_t jb, uint32_t je, float *thr, uint8_t *feas, uint64_t cap,
+                          float *best_thr, uint32_t *best_plan, uint64_t cap_segs) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if (!jobs) return rk_fail(ctx, RK_ERR_INVALID_ARG, "jobs is null");
+    if ((rc = rk_check_table(ctx, table, jb, je))) return rc;
+    if (jobs->n_jobs != table->n_jobs) return rk_fail(ctx, RK_ERR_INVALID_ARG, "jobs and table disagree on n_jobs");
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    if ((rc = rk_check_env(ctx, env))) return rc;
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    uint64_t nt, ns;
+    if ((rc = rk_range_offsets(ctx, table, jb, je, &nt, &ns))) return rc;
+    const uint64_t n_rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    const uint64_t need = 16ull * n_rows * nt, need_segs = n_rows * ns;
+    if (need == 0) return RK_OK;
+    if (!thr || !best_thr || !best_plan) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null buffer");
+    if (cap < need) return rk_fail(ctx, RK_ERR_CAPACITY, "thr holds %llu candidates, %llu needed",
+                                   (unsigned long long)cap, (unsigned long long)need);
+    if (cap_segs < need_segs) return rk_fail(ctx, RK_ERR_CAPACITY, "outputs hold %llu entries, %llu needed",
+                                             (unsigned long long)cap_segs, (unsigned long long)need_segs);
+    if (((uintptr_t)thr & 15u) || ((uintptr_t)feas & 15u)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "output not 16-byte aligned");
+
+    const uint32_t nj = je - jb;
+    const uint32_t max_nt = table->max_triples_per_job ? table->max_triples_per_job : 1;
+    const uint32_t max_ns = table->max_segs_per_job ? table->max_segs_per_job : 1;
+    const size_t map_bytes = ((size_t)max_nt * 2 + 7) & ~(size_t)7;
+    const size_t level_bytes = (size_t)grid->n_mem * max_ns * 8;                // keys of one CPU level's rows
+    const size_t c_fit = (56 * 1024 - map_bytes) / level_bytes;
+    if (c_fit == 0) {
+        // the keys of one CPU level do not fit in LDS together: evaluate, then reduce from the tensor (same results)
+        if ((rc = rk_eval_candidates(ctx, jobs, table, grid, env, jb, je, thr, feas, cap, nullptr))) return rc;
+        return rk_best_plan(ctx, table, grid, jb, je, thr, best_thr, best_plan, cap_segs, nullptr);
+    }
+    // a workgroup per job; with few jobs the CPU levels are split over blockIdx.y so that the chip is filled
+    uint32_t split = 1;
+    if (nj < 2048) {
+        split = (2048 + nj - 1) / nj;
+        if (split > grid->n_cpu) split = grid->n_cpu;
+    }
+    uint32_t c_per_block = (grid->n_cpu + split - 1) / split;
+    if (c_per_block > c_fit) c_per_block = (uint32_t)c_fit;
+    split = (grid->n_cpu + c_per_block - 1) / c_per_block;
+    const size_t lds = (size_t)c_per_block * level_bytes + map_bytes;
+    const dim3 g2(nj, split);
+    uint32_t threads = ((max_nt + 15) / 16) * 64;                               // a wavefront per 16 triples of the longest job
+    if (threads > (uint32_t)EVAL_BEST_MAX_THREADS) threads = EVAL_BEST_MAX_THREADS;
+    const JobDev jd = job_dev(jobs);
+    const TableDev td = table_dev(table);
+    const GridDev gd = grid_dev(grid);
+    if (feas)
+        k_eval_best<true><<<g2, threads, lds, ctx->stream>>>(jd, td, gd, *env, jb, table->option_mask, c_per_block, max_nt,
+                                                                 max_ns, thr, feas, best_thr, best_plan);
+    else
+        k_eval_best<false><<<g2, threads, lds, ctx->stream>>>(jd, td, gd, *env, jb, table->option_mask, c_per_block, max_nt,
+                                                                  max_ns, thr, nullptr, best_thr, best_plan);
+    RK_CHECK_LAUNCH(ctx, "k_eval_best");
     return RK_OK;
 }
 

@@ -57,6 +57,16 @@ class DeviceRun:
         assert need == n
         return bt, bp, n
 
+    def eval_best(self, jb=0, je=None, want_feas=True):
+        """Evaluation and best plan in one pass: (thr, feas, best_thr, best_plan, candidates, segment entries)."""
+        je = self.wl.n_jobs if je is None else je
+        n = self.table.n_candidates(self.n_rows, jb, je)
+        ns = self.table.n_segments(self.n_rows, jb, je)
+        thr, bt, bp = self.f32(n), self.f32(ns), self.i32(ns)
+        feas = self.torch.empty(max(n, 16), dtype=self.torch.uint8, device=self.device) if want_feas else None
+        rk.rk_eval_best_plan(self.ctx, self.jobs, self.table.c, self.grid, self.env, jb, je, thr, bt, bp, feas=feas)
+        return thr, feas, bt, bp, n, ns
+
     def curves(self, bt, bp, jb=0, je=None):
         je = self.wl.n_jobs if je is None else je
         n = self.table.n_segments(self.n_rows, jb, je)
