@@ -216,8 +216,9 @@ int32_t rk_best_plan(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_gri
  * while they are still in registers, so the tensor is written once and not
  * read back.  cap = capacity of thr (and feas) in candidates, cap_segs = of the
  * two segment outputs in entries; RK_ERR_CAPACITY when either is too small.
- * When the keys of one CPU level's rows (n_mem * longest segment list * 8
- * bytes) do not fit in LDS the two kernels run one after the other instead. */
+ * A segment whose plans lie in more than one 64-triple tile is finished by a
+ * second, small kernel from keys kept in a buffer the context owns (it grows
+ * on first use: 16 bytes per tile and row).  At most 65535 jobs per call. */
 int32_t rk_eval_best_plan(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table,
                           const rk_alloc_grid *grid, const rk_env *env,
                           uint32_t job_begin, uint32_t job_end,

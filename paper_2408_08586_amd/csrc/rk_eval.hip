@@ -174,21 +174,20 @@ __global__ __launch_bounds__(BEST_MAX_WAVES * 64) void k_best_plan(TableDev tb, 
 }
 
 // ------------------------------------------- evaluation and best plan in one pass
-// The evaluation kernel's thread mapping and stores (a thread owns (triple, ZeRO stage), a wavefront writes 1 KiB
-// contiguous per row), with one workgroup per (job, group of CPU levels) whose wavefronts walk the job's triples, 16
-// per wavefront at a time, and keep, per row and segment, the packed key of the best plan in LDS: the candidate tensor
-// is written once and never read back.  The workgroup is as large as the longest job of the call needs to take all its
-// triples at once (at most 1,024 threads = 256 triples per round), so that a call has about as many wavefronts in
-// flight as the plain evaluation kernel.  The options without offload are the same in every row and the offload options depend on the
+// The evaluation kernel's grid, thread mapping and stores (a workgroup takes 64 triples of a job, a thread owns
+// (triple, ZeRO stage), a wavefront writes 1 KiB contiguous per row); in addition the workgroup keeps, per row and
+// per segment that its tile touches, the packed key of the best plan in LDS: the candidate tensor is written once
+// and never read back.  The options without offload are the same in every row and the offload options depend on the
 // CPU level only (the memory tier masks them), so the four lanes of a triple reduce their keys once per tile and
 // once per CPU level (two DPP steps each); a row then costs the quad leader a select and one LDS atomic maximum.
-// The keys are those of k_best_plan on the values stored, so the results are the same bits.
+// The triples of a job are ordered by segment, so only the first and the last segment of a tile can continue in a
+// neighbouring tile: the segments that lie inside the tile are written out as results, the (at most two) others as
+// partial keys, which k_merge_spanning combines.  The keys are those of k_best_plan on the values stored, so the
+// results are the same bits.
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xF, 0xF, false));
 }
-
-constexpr int EVAL_BEST_MAX_THREADS = 1024;
 
 // A workgroup barrier that orders LDS traffic only: every wavefront waits for its own LDS operations (lgkmcnt 0), not
 // for its global loads and stores, which __syncthreads() would also drain.  Enough where the data exchanged is in LDS.
@@ -197,55 +196,67 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_s_barrier();
 }
 
+// index of a (job, tile) among the tiles of a call: tiles of different jobs never share an index (a job adds at
+// least its own number of tiles: floor(a + b) >= floor(a) + floor(b), and the job's own 1 covers a last partial tile)
+__device__ __forceinline__ uint32_t tile_index(const TableDev &tb, uint32_t jb, uint32_t j, uint32_t tile) {
+    return (tb.triple_off[j] - tb.triple_off[jb]) / TRIPLES_PER_BLOCK + (j - jb) + tile;
+}
+
 template <bool WITH_FEAS>
-__global__ __launch_bounds__(EVAL_BEST_MAX_THREADS) void k_eval_best(JobDev jobs, TableDev tb, GridDev grid, rk_env env, uint32_t jb,
-                                                            uint32_t option_mask, uint32_t c_per_block, uint32_t max_nt,
-                                                            uint32_t max_ns, float *__restrict__ thr,
-                                                            uint8_t *__restrict__ feas, float *__restrict__ best_thr,
-                                                            uint32_t *__restrict__ best_plan) {
-    extern __shared__ unsigned long long lds64[];
-    const uint32_t rows_here = c_per_block * grid.n_mem;
-    unsigned long long *seg_key = lds64;                                               // [rows_here][ns]
-    uint16_t *seg_of = reinterpret_cast<uint16_t *>(seg_key + (size_t)rows_here * max_ns);   // [max_nt]
-    const uint32_t tid = threadIdx.x, n_thr = blockDim.x;
-    const uint32_t j = jb + blockIdx.x;
+__global__ __launch_bounds__(EVAL_THREADS) void k_eval_best(JobDev jobs, TableDev tb, GridDev grid, rk_env env, uint32_t jb,
+                                                            uint32_t option_mask, uint32_t c_per_block, uint32_t key_stride,
+                                                            float *__restrict__ thr, uint8_t *__restrict__ feas,
+                                                            float *__restrict__ best_thr, uint32_t *__restrict__ best_plan,
+                                                            unsigned long long *__restrict__ partial) {
+    // [rows of this workgroup][key_stride local segments]; key_stride = min(64, longest segment list of the table)
+    extern __shared__ unsigned long long seg_key[];
+    __shared__ uint16_t seg_of[TRIPLES_PER_BLOCK];                   // segment of each triple of the tile
+    __shared__ uint32_t seg_lo_sh;                                   // segment of the tile's first triple
+    const uint32_t tid = threadIdx.x;
+    const uint32_t j = jb + blockIdx.y;
     const uint32_t t0 = tb.triple_off[j], nt = tb.triple_off[j + 1] - t0;
+    const uint32_t tile_lo = blockIdx.x * TRIPLES_PER_BLOCK;
+    if (tile_lo >= nt) return;
+    const uint32_t tile_hi = tile_lo + TRIPLES_PER_BLOCK < nt ? tile_lo + TRIPLES_PER_BLOCK : nt;
     const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
-    if (nt == 0) return;                                                               // no plan: no candidates, no segments
+    const uint32_t tl = tile_lo + (tid >> 2);                        // the four lanes of a quad share tl
+    const bool active = tl < tile_hi;
+    const uint32_t packed_triple = active ? tb.triples[t0 + tl] : 0u;
     const uint32_t z = tid & 3u;
     const uint32_t n_rows = grid.n_cpu * grid.n_mem;
     const uint64_t cbase = 16ull * n_rows * (uint64_t)(t0 - tb.triple_off[jb]);
-    const uint32_t c_lo = blockIdx.y * c_per_block;
+    const uint32_t c_lo = blockIdx.z * c_per_block;
     const uint32_t c_hi = c_lo + c_per_block < grid.n_cpu ? c_lo + c_per_block : grid.n_cpu;
+    const uint32_t rows_here = (c_hi - c_lo) * grid.n_mem;
+    // Where the results go.  Read here and not where they are used: a load after the candidate stores would make the
+    // wavefront wait for all of them (the counter it waits on counts loads and stores alike, in order).
+    const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]);
+    const uint64_t pbase = (uint64_t)tile_index(tb, jb, j, blockIdx.x) * 2 * n_rows;
     const Job J = load_job(jobs, j);
 
-    // The thread's triples are fetched before the loop (at most eight: 2,048 triples over 256 quads, and a smaller
-    // workgroup covers its longest job in one round).  Inside the loop nothing is loaded from global memory, so no
-    // wavefront ever waits for its earlier stores on the way to its next triple: the memory counter it would wait on
-    // counts loads and stores alike, in order.
-    constexpr uint32_t MAX_ROUNDS = RK_MAX_TRIPLES_PER_JOB / (EVAL_BEST_MAX_THREADS / 4);
-    uint32_t mine[MAX_ROUNDS];
-#pragma unroll
-    for (uint32_t k = 0; k < MAX_ROUNDS; ++k) {
-        const uint32_t tl = (tid >> 2) + k * (n_thr >> 2);
-        mine[k] = tl < nt ? tb.triples[t0 + tl] : 0u;
+    // Which segments the tile touches; whether its first and its last segment go on in a neighbouring tile.  The loads
+    // of this part are issued before the arithmetic below and used after it.
+    __shared__ uint32_t first_open_sh, last_open_sh;
+    uint32_t my_first[2] = {0u, 0u}, my_end[2] = {0u, 0u};           // a thread looks at segments tid and tid + 256 here,
+    for (uint32_t k = 0; k < 2; ++k) {                               // at the others (jobs with more than 512) below
+        const uint32_t s = tid + k * EVAL_THREADS;
+        if (s < ns) {
+            my_first[k] = tb.seg_first[s0 + s];
+            my_end[k] = s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt;
+        }
     }
-    // the triple -> segment map and the empty keys, while those loads are on their way
-    for (uint32_t s = tid; s < ns; s += n_thr) {
-        const uint32_t first = tb.seg_first[s0 + s];
-        const uint32_t last = s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt;
-        for (uint32_t t = first; t < last; ++t) seg_of[t] = (uint16_t)s;
-    }
-    for (uint32_t i = tid; i < rows_here * ns; i += n_thr) seg_key[i] = 0ull;
-    lds_barrier();
 
-    for (uint32_t tl = tid >> 2; tl < nt; tl += n_thr >> 2) {                          // the four lanes of a quad share tl
-        const Triple T = triple_terms(J, env, mine[0]);
-#pragma unroll
-        for (uint32_t k = 0; k + 1 < MAX_ROUNDS; ++k) mine[k] = mine[k + 1];
-        const uint32_t plan0 = tl * 16 + z * 4;
-        float plain[2];
-        uint32_t why_plain[2];
+    // everything that does not depend on the row (as in k_eval)
+    Triple T = {};
+    float plain[2] = {0.f, 0.f};
+    uint32_t why_plain[2] = {0u, 0u}, why_off[2] = {0u, 0u};
+    bool any_off = false;
+    Offload O = {};
+    float need_host = 0.f, quad_host = 0.f;
+    unsigned long long k_plain = 0ull;
+    const uint32_t plan0 = tl * 16 + z * 4;
+    if (active) {
+        T = triple_terms(J, env, packed_triple);
 #pragma unroll
         for (uint32_t gc = 0; gc < 2; ++gc) {
             const bool allowed = (option_mask >> (z * 4 + gc * 2)) & 1u;
@@ -253,29 +264,49 @@ __global__ __launch_bounds__(EVAL_BEST_MAX_THREADS) void k_eval_best(JobDev jobs
             why_plain[gc] = allowed ? (fits ? 0u : RK_INFEASIBLE_GPU_MEM) : RK_INFEASIBLE_STRUCT;
             plain[gc] = why_plain[gc] ? 0.f : thr_plain(J, T, z, gc);
         }
-        uint32_t why_off[2];
 #pragma unroll
         for (uint32_t gc = 0; gc < 2; ++gc) {
             const bool allowed = z >= 2 && ((option_mask >> (z * 4 + gc * 2 + 1)) & 1u);
             why_off[gc] = allowed ? (gpu_mem_fits(J, env, T, z, gc, 1) ? 0u : RK_INFEASIBLE_GPU_MEM)
                                   : RK_INFEASIBLE_STRUCT;
         }
-        const bool any_off = z >= 2 && (!(why_off[0] & RK_INFEASIBLE_STRUCT) || !(why_off[1] & RK_INFEASIBLE_STRUCT));
-        Offload O = {};
-        float need_host = 0.f;
+        any_off = z >= 2 && (!(why_off[0] & RK_INFEASIBLE_STRUCT) || !(why_off[1] & RK_INFEASIBLE_STRUCT));
         if (any_off) {
             O = offload_terms(J, env, T);
             need_host = host_bytes_needed(J, T);
         }
         // what the quad knows together: the best option without offload, and the host bytes of the triple (the same
         // in every lane that offloads, 0 in the others; not negative, so the float maximum picks it)
-        unsigned long long k_plain = max_u64(make_key(plain[0], plan0), make_key(plain[1], plan0 + 2));
+        k_plain = max_u64(make_key(plain[0], plan0), make_key(plain[1], plan0 + 2));
         k_plain = max_u64(k_plain, dpp_u64<0xB1>(k_plain));                            // quad_perm [1,0,3,2]
         k_plain = max_u64(k_plain, dpp_u64<0x4E>(k_plain));                            // quad_perm [2,3,0,1]
-        float quad_host = fmaxf(need_host, dpp_f32<0xB1>(need_host));
+        quad_host = fmaxf(need_host, dpp_f32<0xB1>(need_host));
         quad_host = fmaxf(quad_host, dpp_f32<0x4E>(quad_host));
-        const uint32_t seg = seg_of[tl];
+    }
 
+    // the triple -> segment map of the tile, and empty keys
+    auto note_segment = [&](uint32_t s, uint32_t first, uint32_t end) {
+        if (first < tile_hi && end > tile_lo) {
+            if (first <= tile_lo) {                                  // it holds the tile's first triple
+                seg_lo_sh = s;
+                first_open_sh = (first < tile_lo || end > tile_hi) ? 1u : 0u;
+            }
+            if (end >= tile_hi) last_open_sh = end > tile_hi ? 1u : 0u;   // it holds the tile's last triple
+            const uint32_t a = first > tile_lo ? first : tile_lo, b = end < tile_hi ? end : tile_hi;
+            for (uint32_t t = a; t < b; ++t) seg_of[t - tile_lo] = (uint16_t)s;
+        }
+    };
+    for (uint32_t k = 0; k < 2; ++k)
+        if (tid + k * EVAL_THREADS < ns) note_segment(tid + k * EVAL_THREADS, my_first[k], my_end[k]);
+    for (uint32_t s = tid + 2 * EVAL_THREADS; s < ns; s += EVAL_THREADS)
+        note_segment(s, tb.seg_first[s0 + s], s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt);
+    for (uint32_t i = tid; i < rows_here * key_stride; i += EVAL_THREADS) seg_key[i] = 0ull;
+    lds_barrier();
+    const uint32_t seg_lo = seg_lo_sh;
+    const uint32_t n_seg_here = seg_of[tile_hi - 1 - tile_lo] - seg_lo + 1;
+
+    if (active) {
+        unsigned long long *keys = seg_key + (seg_of[tl - tile_lo] - seg_lo);
         for (uint32_t ci = c_lo; ci < c_hi; ++ci) {
             float off_thr[2] = {0.f, 0.f};
             if (any_off) {
@@ -289,7 +320,6 @@ __global__ __launch_bounds__(EVAL_BEST_MAX_THREADS) void k_eval_best(JobDev jobs
             k_all = max_u64(k_all, dpp_u64<0xB1>(k_all));
             k_all = max_u64(k_all, dpp_u64<0x4E>(k_all));
             k_all = max_u64(k_all, k_plain);
-            unsigned long long *keys = seg_key + (size_t)(ci - c_lo) * grid.n_mem * ns + seg;
             for (uint32_t mi = 0; mi < grid.n_mem; ++mi) {
                 const float tier = tier_bytes(grid, mi, T.g);
                 uint32_t w0 = why_off[0], w1 = why_off[1];
@@ -309,17 +339,54 @@ __global__ __launch_bounds__(EVAL_BEST_MAX_THREADS) void k_eval_best(JobDev jobs
                     *reinterpret_cast<uint32_t *>(feas + idx) = packed;
                 }
                 const unsigned long long k = quad_host <= tier ? k_all : k_plain;
-                if (z == 0 && (k >> 32)) atomicMax(keys + (size_t)mi * ns, k);
+                if (z == 0 && (k >> 32)) atomicMax(keys + ((ci - c_lo) * grid.n_mem + mi) * key_stride, k);
             }
         }
     }
     lds_barrier();                                                                     // the stores above need not have landed
-    const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]) + (uint64_t)c_lo * grid.n_mem * ns;
-    const uint32_t n_out = (c_hi - c_lo) * grid.n_mem * ns;                            // this workgroup's rows are contiguous
-    for (uint32_t i = tid; i < n_out; i += n_thr) {
-        const unsigned long long k = seg_key[i];
-        best_thr[sbase + i] = key_thr(k);
-        best_plan[sbase + i] = key_plan(k);
+
+    // a segment that lies inside the tile is finished; one that goes on in a neighbouring tile leaves its key: in
+    // slot 0 if it holds the tile's first triple, else (it then holds the last one) in slot 1
+    const bool first_open = first_open_sh != 0u, last_open = last_open_sh != 0u;
+    for (uint32_t i = tid; i < rows_here * n_seg_here; i += EVAL_THREADS) {
+        const uint32_t r_l = i / n_seg_here, q = i - r_l * n_seg_here, s = seg_lo + q;
+        const uint32_t r = c_lo * grid.n_mem + r_l;
+        const unsigned long long k = seg_key[r_l * key_stride + q];
+        const bool open = q == 0 ? first_open : (q + 1 == n_seg_here && last_open);
+        if (!open) {
+            best_thr[sbase + (uint64_t)r * ns + s] = key_thr(k);
+            best_plan[sbase + (uint64_t)r * ns + s] = key_plan(k);
+        } else {
+            partial[pbase + (q == 0 ? 0u : 1u) * n_rows + r] = k;
+        }
+    }
+}
+
+// The segments of a job that span tiles: the maximum of the keys their tiles left.  A workgroup per job.
+constexpr int MERGE_THREADS = 128;
+__global__ __launch_bounds__(MERGE_THREADS) void k_merge_spanning(TableDev tb, uint32_t n_rows, uint32_t jb,
+                                                                  const unsigned long long *__restrict__ partial,
+                                                                  float *__restrict__ best_thr,
+                                                                  uint32_t *__restrict__ best_plan) {
+    const uint32_t j = jb + blockIdx.x;
+    const uint32_t t0 = tb.triple_off[j], nt = tb.triple_off[j + 1] - t0;
+    const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
+    if (nt <= TRIPLES_PER_BLOCK) return;                             // one tile: nothing spans
+    const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]);
+    const uint64_t tile0 = tile_index(tb, jb, j, 0);
+    for (uint32_t i = threadIdx.x; i < ns * n_rows; i += MERGE_THREADS) {
+        const uint32_t s = i / n_rows, r = i - s * n_rows;
+        const uint32_t first = tb.seg_first[s0 + s];
+        const uint32_t end = s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt;
+        const uint32_t ta = first / TRIPLES_PER_BLOCK, tz = (end - 1) / TRIPLES_PER_BLOCK;
+        if (ta == tz) continue;
+        unsigned long long k = 0;
+        for (uint32_t t = ta; t <= tz; ++t) {
+            const uint32_t slot = first <= t * TRIPLES_PER_BLOCK ? 0u : 1u;            // it holds that tile's first triple
+            k = max_u64(k, partial[((tile0 + t) * 2 + slot) * n_rows + r]);
+        }
+        best_thr[sbase + (uint64_t)r * ns + s] = key_thr(k);
+        best_plan[sbase + (uint64_t)r * ns + s] = key_plan(k);
     }
 }
 
@@ -497,39 +564,46 @@ int32_t rk_eval_best_plan(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table 
     if (((uintptr_t)thr & 15u) || ((uintptr_t)feas & 15u)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "output not 16-byte aligned");
 
     const uint32_t nj = je - jb;
-    const uint32_t max_nt = table->max_triples_per_job ? table->max_triples_per_job : 1;
+    if (nj > 65535u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 65535 jobs in one call; use job ranges");
+    const uint32_t bx = (table->max_triples_per_job + TRIPLES_PER_BLOCK - 1) / TRIPLES_PER_BLOCK;
+    // a tile of 64 triples touches at most 64 segments, and no more than the longest segment list of the table; the
+    // keys of a workgroup's rows stay within 8 KiB of LDS, so that LDS never limits how many workgroups a compute
+    // unit holds: as many CPU levels per workgroup as that allows, the others over blockIdx.z; with few jobs the
+    // levels are split further so that the chip is filled
     const uint32_t max_ns = table->max_segs_per_job ? table->max_segs_per_job : 1;
-    const size_t map_bytes = ((size_t)max_nt * 2 + 7) & ~(size_t)7;
-    const size_t level_bytes = (size_t)grid->n_mem * max_ns * 8;                // keys of one CPU level's rows
-    const size_t c_fit = (56 * 1024 - map_bytes) / level_bytes;
-    if (c_fit == 0) {
-        // the keys of one CPU level do not fit in LDS together: evaluate, then reduce from the tensor (same results)
-        if ((rc = rk_eval_candidates(ctx, jobs, table, grid, env, jb, je, thr, feas, cap, nullptr))) return rc;
-        return rk_best_plan(ctx, table, grid, jb, je, thr, best_thr, best_plan, cap_segs, nullptr);
-    }
-    // a workgroup per job; with few jobs the CPU levels are split over blockIdx.y so that the chip is filled
-    uint32_t split = 1;
-    if (nj < 2048) {
-        split = (2048 + nj - 1) / nj;
+    const uint32_t key_stride = max_ns < (uint32_t)TRIPLES_PER_BLOCK ? max_ns : (uint32_t)TRIPLES_PER_BLOCK;
+    const size_t level_bytes = (size_t)grid->n_mem * key_stride * 8;             // at most 16 * 64 * 8 = 8 KiB
+    uint32_t c_per_block = (uint32_t)((8 * 1024) / level_bytes);
+    if (c_per_block < 1) c_per_block = 1;
+    if (c_per_block > grid->n_cpu) c_per_block = grid->n_cpu;
+    const uint64_t blocks = (uint64_t)bx * nj;
+    if (blocks < 2048) {
+        uint32_t split = (uint32_t)((2048 + blocks - 1) / blocks);
         if (split > grid->n_cpu) split = grid->n_cpu;
+        const uint32_t c2 = (grid->n_cpu + split - 1) / split;
+        if (c2 < c_per_block) c_per_block = c2;
     }
-    uint32_t c_per_block = (grid->n_cpu + split - 1) / split;
-    if (c_per_block > c_fit) c_per_block = (uint32_t)c_fit;
-    split = (grid->n_cpu + c_per_block - 1) / c_per_block;
-    const size_t lds = (size_t)c_per_block * level_bytes + map_bytes;
-    const dim3 g2(nj, split);
-    uint32_t threads = ((max_nt + 15) / 16) * 64;                               // a wavefront per 16 triples of the longest job
-    if (threads > (uint32_t)EVAL_BEST_MAX_THREADS) threads = EVAL_BEST_MAX_THREADS;
+    const uint32_t split = (grid->n_cpu + c_per_block - 1) / c_per_block;
+    const size_t lds = (size_t)c_per_block * level_bytes;
+    // partial keys of the segments that span tiles: two per (tile, row)
+    const uint64_t n_tiles = nt / TRIPLES_PER_BLOCK + nj + bx;
+    unsigned long long *partial = nullptr;
+    if ((rc = rk_scratch(ctx, SL_EVAL_PARTIAL, (size_t)(n_tiles * 2 * n_rows * 8), (void **)&partial))) return rc;
+    const dim3 g3(bx, nj, split);
     const JobDev jd = job_dev(jobs);
     const TableDev td = table_dev(table);
     const GridDev gd = grid_dev(grid);
     if (feas)
-        k_eval_best<true><<<g2, threads, lds, ctx->stream>>>(jd, td, gd, *env, jb, table->option_mask, c_per_block, max_nt,
-                                                                 max_ns, thr, feas, best_thr, best_plan);
+        k_eval_best<true><<<g3, EVAL_THREADS, lds, ctx->stream>>>(jd, td, gd, *env, jb, table->option_mask, c_per_block,
+                                                                 key_stride, thr, feas, best_thr, best_plan, partial);
     else
-        k_eval_best<false><<<g2, threads, lds, ctx->stream>>>(jd, td, gd, *env, jb, table->option_mask, c_per_block, max_nt,
-                                                                  max_ns, thr, nullptr, best_thr, best_plan);
+        k_eval_best<false><<<g3, EVAL_THREADS, lds, ctx->stream>>>(jd, td, gd, *env, jb, table->option_mask, c_per_block,
+                                                                  key_stride, thr, nullptr, best_thr, best_plan, partial);
     RK_CHECK_LAUNCH(ctx, "k_eval_best");
+    if (bx > 1) {
+        k_merge_spanning<<<nj, MERGE_THREADS, 0, ctx->stream>>>(td, (uint32_t)n_rows, jb, partial, best_thr, best_plan);
+        RK_CHECK_LAUNCH(ctx, "k_merge_spanning");
+    }
     return RK_OK;
 }
 

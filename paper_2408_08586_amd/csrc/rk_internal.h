@@ -47,8 +47,11 @@ enum {
     SL_ENUM_BACK,                                        // enumeration: totals and offsets in one piece for the host
     SL_PLACE_RESULT,                                     // placement: its four summary words
     SL_ENUM_LEADER,                                      // enumeration: the job whose search a job shares
-    SL_RS_F32, SL_RS_U32, SL_RS_U64                      // the Schedule loop: cached slopes; order, marks and saved states; CPU needs
+    SL_RS_F32, SL_RS_U32, SL_RS_U64,                     // the Schedule loop: cached slopes; order, marks and saved states; CPU needs
+    SL_EVAL_PARTIAL,                                     // evaluation with best plan: keys of the segments that span tiles
+    SL_COUNT
 };
+static_assert(SL_COUNT <= RK_SCRATCH_SLOTS, "more scratch slots than the context holds");
 
 int32_t rk_fail(rk_ctx *ctx, int32_t code, const char *fmt, ...);
 int32_t rk_scratch(rk_ctx *ctx, int slot, size_t bytes, void **out);

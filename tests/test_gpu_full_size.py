@@ -4,8 +4,8 @@ Stress (10,000 jobs, 6.8e8 candidates): every job, 1,000 at a time - the plan
 table bit for bit, every throughput within 1e-5 relative, every feasibility
 mask bit for bit, every best plan equal to the oracle's or inside the 1e-5
 band of its maximum, the best-plan and curve kernels bit for bit on the
-oracle's own float32 values, the fused entry point bit for bit what the three
-calls give.
+oracle's own float32 values, the one-pass and the fused entry points bit for
+bit what the separate calls give.
 
 What-if batch (rounds of 500 jobs on about 512 GPUs): whole rounds through
 rk_schedule_rounds and rk_schedule_rounds_shared against the oracle's rounds.
@@ -33,6 +33,7 @@ def gpu():
 
 
 def test_stress_every_job(gpu, orc, capsys):
+    import torch
     wl = workloads.stress()
     t0 = time.time()
     ot = orc.enumerate_plans(wl.ints, wl.bounds, n_threads=THREADS)
@@ -54,6 +55,12 @@ def test_stress_every_job(gpu, orc, capsys):
         o_bt, o_bp = orc.best_plan(ot, wl.grid, o_thr, jb, je, n_threads=THREADS)
         g_bt, g_bp = run.host(bt, ns), run.host(bp, ns).view(np.uint32)
         n_mis += check_best_in_band(ot, run.n_rows, jb, je, o_thr, o_bt, o_bp, g_bt, g_bp)
+        # evaluation and best plan in one pass: the same bits as the two calls
+        t1, f1, b1, p1, n1, ns1 = run.eval_best(jb, je)
+        assert (n1, ns1) == (n, ns)
+        assert torch.equal(t1[:n], thr[:n]) and torch.equal(f1[:n], feas[:n])
+        assert torch.equal(b1[:ns].view(torch.int32), bt[:ns].view(torch.int32)) and torch.equal(p1[:ns], bp[:ns])
+        del t1, f1, b1, p1
         # the fused entry point gives the same bits as evaluation -> best plan -> curves
         ct, cp, cg = run.curves(bt, bp, jb, je)
         fused = run.fused(jb, je)
