@@ -597,13 +597,16 @@ def main():
             stage_ms["allocate"].append((e2, mark()))
 
     # What the chip gives kernels that do nothing but fill, then read, the candidate buffer of one chunk: the measured
-    # ceiling of the one-pass kernel (the fill) and of the k_eval + k_best_plan pair (fill, then read).  A read that follows a write of the same buffer is slower than the same
+    # ceiling of the one-pass kernel, whose launches follow each other (a fill that follows a fill), and of the k_eval +
+    # k_best_plan pair (fill, then read).  A read that follows a write of the same buffer is slower than the same
     # read after another read (the written lines are still on their way to HBM), so both positions are timed.
     n_probe = (max(chunk_cands) // 4) * 4
-    probe = {"fill": [], "read_after_fill": [], "read_after_read": []}
+    probe = {"fill": [], "fill_after_fill": [], "read_after_fill": [], "read_after_read": []}
     for i in range(7):
         e = [mark()]
         rk.rk_probe_stream(ctx, thr, n_probe, 1, 1.0)
+        e.append(mark())
+        rk.rk_probe_stream(ctx, thr, n_probe, 4, 2.0)
         e.append(mark())
         rk.rk_probe_stream(ctx, thr, n_probe, 0, out=total)
         e.append(mark())
@@ -723,7 +726,7 @@ def main():
                     "eval_best_candidates_per_s": n_cand / (hot_avg_ms["eval_best"] * n_chunks * 1e-3),
                     # kernels that only fill and only read the same buffer (4 bytes per candidate each way)
                     "plain_stream_ms": probe_ms,
-                    "eval_best_over_plain_fill": hot_avg_ms["eval_best"] / probe_ms["fill"],
+                    "eval_best_over_plain_fill_after_fill": hot_avg_ms["eval_best"] / probe_ms["fill_after_fill"],
                     # the same path with the candidates read back: rk_eval_candidates, then rk_best_plan
                     "two_kernels": {"pass": "separate pass after the timed region, events around both kernels",
                                     "avg_launch_ms": pair_avg_ms, "eval_GBps": gbs_eval, "best_plan_GBps": gbs_best,

@@ -613,8 +613,9 @@ int32_t rk_schedule_round_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan
  * same read under a second kernel name (a profile then tells a read that
  * follows a fill from one that follows a read); mode 2 reads them with 4,096
  * workgroups that stride through the buffer together; mode 1 fills them with
- * `value`.  Any other mode, a null or misaligned buf, or fewer than 4 floats:
- * RK_ERR_INVALID_ARG. */
+ * `value`, mode 4 is the same fill under a second kernel name (a fill that
+ * follows a fill).  Any other mode, a null or misaligned buf, or fewer than 4
+ * floats: RK_ERR_INVALID_ARG. */
 int32_t rk_probe_stream(rk_ctx *ctx, float *buf, uint64_t n_floats, int32_t mode, float value, float *out);
 
 #ifdef __cplusplus

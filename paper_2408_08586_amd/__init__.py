@@ -319,7 +319,7 @@ def rk_reschedule(ctx, ref_thr, table, grid, cluster: rk_cluster, best_thr, best
 
 
 def rk_probe_stream(ctx, buf, n_floats, mode, value=0.0, out=None):
-    """Measurement helper: stream-read (modes 0, 3; strided: 2) or fill (mode 1) the first n_floats floats of buf."""
+    """Measurement helper: stream-read (modes 0, 3; strided: 2) or fill (modes 1, 4) the first n_floats floats of buf."""
     _check(ctx, load_library().rk_probe_stream(ctx, _ptr(buf), C.c_uint64(n_floats), C.c_int32(mode), C.c_float(value),
                                                _ptr(out)))
 

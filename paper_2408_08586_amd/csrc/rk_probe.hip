@@ -58,6 +58,8 @@ __global__ __launch_bounds__(PROBE_THREADS) void k_probe_read_strided(const v4f 
     if ((threadIdx.x & 63) == 0 && acc == 12345.678f) atomicAdd(out, acc);
 }
 
+// TAG as for k_probe_read: 0 = the fill that follows a read, 1 = the fill that follows another fill
+template <int TAG>
 __global__ __launch_bounds__(PROBE_THREADS) void k_probe_fill(v4f *__restrict__ buf, uint64_t n_vec, float value) {
     const uint64_t base = (uint64_t)blockIdx.x * PROBE_TILE;
     const v4f v = {value, value, value, value};
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(PROBE_THREADS) void k_probe_fill(v4f *__restrict__ 
 
 extern "C" int32_t rk_probe_stream(rk_ctx *ctx, float *buf, uint64_t n_floats, int32_t mode, float value, float *out) {
     if (!ctx) return RK_ERR_INVALID_ARG;
-    if (!buf || n_floats < 4 || ((uintptr_t)buf & 15u) || (mode != 1 && !out) || mode < 0 || mode > 3)
+    if (!buf || n_floats < 4 || ((uintptr_t)buf & 15u) || ((mode == 0 || mode == 2 || mode == 3) && !out) || mode < 0 || mode > 4)
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "rk_probe_stream: bad argument");
     RK_HIP(ctx, hipSetDevice(ctx->device));
     const uint64_t n_vec = n_floats / 4;
@@ -84,8 +86,10 @@ extern "C" int32_t rk_probe_stream(rk_ctx *ctx, float *buf, uint64_t n_floats, i
         k_probe_read<1><<<(uint32_t)blocks, PROBE_THREADS, 0, ctx->stream>>>(reinterpret_cast<const v4f *>(buf), n_vec, out);
     else if (mode == 2)
         k_probe_read_strided<<<4096, PROBE_THREADS, 0, ctx->stream>>>(reinterpret_cast<const v4f *>(buf), n_vec, out);
+    else if (mode == 4)
+        k_probe_fill<1><<<(uint32_t)blocks, PROBE_THREADS, 0, ctx->stream>>>(reinterpret_cast<v4f *>(buf), n_vec, value);
     else
-        k_probe_fill<<<(uint32_t)blocks, PROBE_THREADS, 0, ctx->stream>>>(reinterpret_cast<v4f *>(buf), n_vec, value);
+        k_probe_fill<0><<<(uint32_t)blocks, PROBE_THREADS, 0, ctx->stream>>>(reinterpret_cast<v4f *>(buf), n_vec, value);
     RK_CHECK_LAUNCH(ctx, "k_probe");
     return RK_OK;
 }
