@@ -184,6 +184,11 @@ __global__ __launch_bounds__(BEST_MAX_WAVES * 64) void k_best_plan(TableDev tb, 
 // neighbouring tile: the segments that lie inside the tile are written out as results, the (at most two) others as
 // partial keys, which k_merge_spanning combines.  The keys are those of k_best_plan on the values stored, so the
 // results are the same bits.
+#ifndef EB_TILE
+#define EB_TILE 64                               // triples per workgroup of the one-pass kernel
+#endif
+constexpr int EB_THREADS = 4 * EB_TILE;
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xF, 0xF, false));
@@ -199,25 +204,25 @@ __device__ __forceinline__ void lds_barrier() {
 // index of a (job, tile) among the tiles of a call: tiles of different jobs never share an index (a job adds at
 // least its own number of tiles: floor(a + b) >= floor(a) + floor(b), and the job's own 1 covers a last partial tile)
 __device__ __forceinline__ uint32_t tile_index(const TableDev &tb, uint32_t jb, uint32_t j, uint32_t tile) {
-    return (tb.triple_off[j] - tb.triple_off[jb]) / TRIPLES_PER_BLOCK + (j - jb) + tile;
+    return (tb.triple_off[j] - tb.triple_off[jb]) / EB_TILE + (j - jb) + tile;
 }
 
 template <bool WITH_FEAS>
-__global__ __launch_bounds__(EVAL_THREADS) void k_eval_best(JobDev jobs, TableDev tb, GridDev grid, rk_env env, uint32_t jb,
+__global__ __launch_bounds__(EB_THREADS) void k_eval_best(JobDev jobs, TableDev tb, GridDev grid, rk_env env, uint32_t jb,
                                                             uint32_t option_mask, uint32_t c_per_block, uint32_t key_stride,
                                                             float *__restrict__ thr, uint8_t *__restrict__ feas,
                                                             float *__restrict__ best_thr, uint32_t *__restrict__ best_plan,
                                                             unsigned long long *__restrict__ partial) {
     // [rows of this workgroup][key_stride local segments]; key_stride = min(64, longest segment list of the table)
     extern __shared__ unsigned long long seg_key[];
-    __shared__ uint16_t seg_of[TRIPLES_PER_BLOCK];                   // segment of each triple of the tile
+    __shared__ uint16_t seg_of[EB_TILE];                   // segment of each triple of the tile
     __shared__ uint32_t seg_lo_sh;                                   // segment of the tile's first triple
     const uint32_t tid = threadIdx.x;
     const uint32_t j = jb + blockIdx.y;
     const uint32_t t0 = tb.triple_off[j], nt = tb.triple_off[j + 1] - t0;
-    const uint32_t tile_lo = blockIdx.x * TRIPLES_PER_BLOCK;
+    const uint32_t tile_lo = blockIdx.x * EB_TILE;
     if (tile_lo >= nt) return;
-    const uint32_t tile_hi = tile_lo + TRIPLES_PER_BLOCK < nt ? tile_lo + TRIPLES_PER_BLOCK : nt;
+    const uint32_t tile_hi = tile_lo + EB_TILE < nt ? tile_lo + EB_TILE : nt;
     const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
     const uint32_t tl = tile_lo + (tid >> 2);                        // the four lanes of a quad share tl
     const bool active = tl < tile_hi;
@@ -239,7 +244,7 @@ __global__ __launch_bounds__(EVAL_THREADS) void k_eval_best(JobDev jobs, TableDe
     __shared__ uint32_t first_open_sh, last_open_sh;
     uint32_t my_first[2] = {0u, 0u}, my_end[2] = {0u, 0u};           // a thread looks at segments tid and tid + 256 here,
     for (uint32_t k = 0; k < 2; ++k) {                               // at the others (jobs with more than 512) below
-        const uint32_t s = tid + k * EVAL_THREADS;
+        const uint32_t s = tid + k * EB_THREADS;
         if (s < ns) {
             my_first[k] = tb.seg_first[s0 + s];
             my_end[k] = s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt;
@@ -297,10 +302,10 @@ __global__ __launch_bounds__(EVAL_THREADS) void k_eval_best(JobDev jobs, TableDe
         }
     };
     for (uint32_t k = 0; k < 2; ++k)
-        if (tid + k * EVAL_THREADS < ns) note_segment(tid + k * EVAL_THREADS, my_first[k], my_end[k]);
-    for (uint32_t s = tid + 2 * EVAL_THREADS; s < ns; s += EVAL_THREADS)
+        if (tid + k * EB_THREADS < ns) note_segment(tid + k * EB_THREADS, my_first[k], my_end[k]);
+    for (uint32_t s = tid + 2 * EB_THREADS; s < ns; s += EB_THREADS)
         note_segment(s, tb.seg_first[s0 + s], s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt);
-    for (uint32_t i = tid; i < rows_here * key_stride; i += EVAL_THREADS) seg_key[i] = 0ull;
+    for (uint32_t i = tid; i < rows_here * key_stride; i += EB_THREADS) seg_key[i] = 0ull;
     lds_barrier();
     const uint32_t seg_lo = seg_lo_sh;
     const uint32_t n_seg_here = seg_of[tile_hi - 1 - tile_lo] - seg_lo + 1;
@@ -348,7 +353,7 @@ __global__ __launch_bounds__(EVAL_THREADS) void k_eval_best(JobDev jobs, TableDe
     // a segment that lies inside the tile is finished; one that goes on in a neighbouring tile leaves its key: in
     // slot 0 if it holds the tile's first triple, else (it then holds the last one) in slot 1
     const bool first_open = first_open_sh != 0u, last_open = last_open_sh != 0u;
-    for (uint32_t i = tid; i < rows_here * n_seg_here; i += EVAL_THREADS) {
+    for (uint32_t i = tid; i < rows_here * n_seg_here; i += EB_THREADS) {
         const uint32_t r_l = i / n_seg_here, q = i - r_l * n_seg_here, s = seg_lo + q;
         const uint32_t r = c_lo * grid.n_mem + r_l;
         const unsigned long long k = seg_key[r_l * key_stride + q];
@@ -371,18 +376,18 @@ __global__ __launch_bounds__(MERGE_THREADS) void k_merge_spanning(TableDev tb, u
     const uint32_t j = jb + blockIdx.x;
     const uint32_t t0 = tb.triple_off[j], nt = tb.triple_off[j + 1] - t0;
     const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
-    if (nt <= TRIPLES_PER_BLOCK) return;                             // one tile: nothing spans
+    if (nt <= EB_TILE) return;                             // one tile: nothing spans
     const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]);
     const uint64_t tile0 = tile_index(tb, jb, j, 0);
     for (uint32_t i = threadIdx.x; i < ns * n_rows; i += MERGE_THREADS) {
         const uint32_t s = i / n_rows, r = i - s * n_rows;
         const uint32_t first = tb.seg_first[s0 + s];
         const uint32_t end = s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt;
-        const uint32_t ta = first / TRIPLES_PER_BLOCK, tz = (end - 1) / TRIPLES_PER_BLOCK;
+        const uint32_t ta = first / EB_TILE, tz = (end - 1) / EB_TILE;
         if (ta == tz) continue;
         unsigned long long k = 0;
         for (uint32_t t = ta; t <= tz; ++t) {
-            const uint32_t slot = first <= t * TRIPLES_PER_BLOCK ? 0u : 1u;            // it holds that tile's first triple
+            const uint32_t slot = first <= t * EB_TILE ? 0u : 1u;            // it holds that tile's first triple
             k = max_u64(k, partial[((tile0 + t) * 2 + slot) * n_rows + r]);
         }
         best_thr[sbase + (uint64_t)r * ns + s] = key_thr(k);
@@ -565,13 +570,13 @@ int32_t rk_eval_best_plan(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table 
 
     const uint32_t nj = je - jb;
     if (nj > 65535u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 65535 jobs in one call; use job ranges");
-    const uint32_t bx = (table->max_triples_per_job + TRIPLES_PER_BLOCK - 1) / TRIPLES_PER_BLOCK;
+    const uint32_t bx = (table->max_triples_per_job + EB_TILE - 1) / EB_TILE;
     // a tile of 64 triples touches at most 64 segments, and no more than the longest segment list of the table; the
     // keys of a workgroup's rows stay within 8 KiB of LDS, so that LDS never limits how many workgroups a compute
     // unit holds: as many CPU levels per workgroup as that allows, the others over blockIdx.z; with few jobs the
     // levels are split further so that the chip is filled
     const uint32_t max_ns = table->max_segs_per_job ? table->max_segs_per_job : 1;
-    const uint32_t key_stride = max_ns < (uint32_t)TRIPLES_PER_BLOCK ? max_ns : (uint32_t)TRIPLES_PER_BLOCK;
+    const uint32_t key_stride = max_ns < (uint32_t)EB_TILE ? max_ns : (uint32_t)EB_TILE;
     const size_t level_bytes = (size_t)grid->n_mem * key_stride * 8;             // at most 16 * 64 * 8 = 8 KiB
     uint32_t c_per_block = (uint32_t)((8 * 1024) / level_bytes);
     if (c_per_block < 1) c_per_block = 1;
@@ -586,7 +591,7 @@ int32_t rk_eval_best_plan(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table 
     const uint32_t split = (grid->n_cpu + c_per_block - 1) / c_per_block;
     const size_t lds = (size_t)c_per_block * level_bytes;
     // partial keys of the segments that span tiles: two per (tile, row)
-    const uint64_t n_tiles = nt / TRIPLES_PER_BLOCK + nj + bx;
+    const uint64_t n_tiles = nt / EB_TILE + nj + bx;
     unsigned long long *partial = nullptr;
     if ((rc = rk_scratch(ctx, SL_EVAL_PARTIAL, (size_t)(n_tiles * 2 * n_rows * 8), (void **)&partial))) return rc;
     const dim3 g3(bx, nj, split);
@@ -594,10 +599,10 @@ int32_t rk_eval_best_plan(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table 
     const TableDev td = table_dev(table);
     const GridDev gd = grid_dev(grid);
     if (feas)
-        k_eval_best<true><<<g3, EVAL_THREADS, lds, ctx->stream>>>(jd, td, gd, *env, jb, table->option_mask, c_per_block,
+        k_eval_best<true><<<g3, EB_THREADS, lds, ctx->stream>>>(jd, td, gd, *env, jb, table->option_mask, c_per_block,
                                                                  key_stride, thr, feas, best_thr, best_plan, partial);
     else
-        k_eval_best<false><<<g3, EVAL_THREADS, lds, ctx->stream>>>(jd, td, gd, *env, jb, table->option_mask, c_per_block,
+        k_eval_best<false><<<g3, EB_THREADS, lds, ctx->stream>>>(jd, td, gd, *env, jb, table->option_mask, c_per_block,
                                                                   key_stride, thr, nullptr, best_thr, best_plan, partial);
     RK_CHECK_LAUNCH(ctx, "k_eval_best");
     if (bx > 1) {
