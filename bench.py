@@ -716,6 +716,9 @@ def main():
                    "n_triples": table.n_triples, "job_chunks": n_chunks},
         "roofline": {"bound": "hbm", "kernel": "k_eval_best",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "duration_covers": "one rk_eval_best_plan call between two events: k_eval_best and the small "
+                                        "k_merge_spanning that finishes the segments spanning tiles (rocprofv3 per kernel: "
+                                        "profiles/whole_path_stress.txt)",
                      "algorithmic_bytes_per_launch": bytes_one,
                      "traffic": traffic, "traffic_source": "profiles/hbm_traffic_stress.txt (rocprofv3 --pmc FETCH_SIZE / "
                                                             "WRITE_SIZE, scaled by a plain copy's counters)",
