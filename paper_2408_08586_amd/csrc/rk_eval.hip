@@ -367,31 +367,51 @@ __global__ __launch_bounds__(EB_THREADS) void k_eval_best(JobDev jobs, TableDev 
     }
 }
 
-// The segments of a job that span tiles: the maximum of the keys their tiles left.  A workgroup per job.
-constexpr int MERGE_THREADS = 128;
-__global__ __launch_bounds__(MERGE_THREADS) void k_merge_spanning(TableDev tb, uint32_t n_rows, uint32_t jb,
+// The segments of a job that span tiles: the maximum of the keys their tiles left.  Half a wavefront per job: its
+// 32 lanes look at 32 segments at a time, and for every one of them that spans tiles the lanes take a row each.
+constexpr int MERGE_THREADS = 256;
+constexpr int MERGE_LANES = 32;
+__global__ __launch_bounds__(MERGE_THREADS) void k_merge_spanning(TableDev tb, uint32_t n_rows, uint32_t jb, uint32_t n_jobs,
                                                                   const unsigned long long *__restrict__ partial,
                                                                   float *__restrict__ best_thr,
                                                                   uint32_t *__restrict__ best_plan) {
-    const uint32_t j = jb + blockIdx.x;
+    const uint32_t lane = threadIdx.x % MERGE_LANES;
+    const uint32_t slot_in_block = threadIdx.x / MERGE_LANES;
+    const uint32_t jl = blockIdx.x * (MERGE_THREADS / MERGE_LANES) + slot_in_block;
+    if (jl >= n_jobs) return;
+    const uint32_t j = jb + jl;
     const uint32_t t0 = tb.triple_off[j], nt = tb.triple_off[j + 1] - t0;
+    if (nt <= (uint32_t)EB_TILE) return;                             // one tile: nothing spans
     const uint32_t s0 = tb.seg_off[j], ns = tb.seg_off[j + 1] - s0;
-    if (nt <= EB_TILE) return;                             // one tile: nothing spans
     const uint64_t sbase = (uint64_t)n_rows * (s0 - tb.seg_off[jb]);
     const uint64_t tile0 = tile_index(tb, jb, j, 0);
-    for (uint32_t i = threadIdx.x; i < ns * n_rows; i += MERGE_THREADS) {
-        const uint32_t s = i / n_rows, r = i - s * n_rows;
-        const uint32_t first = tb.seg_first[s0 + s];
-        const uint32_t end = s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt;
-        const uint32_t ta = first / EB_TILE, tz = (end - 1) / EB_TILE;
-        if (ta == tz) continue;
-        unsigned long long k = 0;
-        for (uint32_t t = ta; t <= tz; ++t) {
-            const uint32_t slot = first <= t * EB_TILE ? 0u : 1u;            // it holds that tile's first triple
-            k = max_u64(k, partial[((tile0 + t) * 2 + slot) * n_rows + r]);
+    // the half of the wavefront this job has: shuffles and ballots stay inside it
+    const uint32_t half = (threadIdx.x & 63u) / MERGE_LANES;
+    for (uint32_t sb = 0; sb < ns; sb += MERGE_LANES) {
+        const uint32_t s = sb + lane;
+        uint32_t first = 0, end = 0;
+        if (s < ns) {
+            first = tb.seg_first[s0 + s];
+            end = s + 1 < ns ? tb.seg_first[s0 + s + 1] : nt;
         }
-        best_thr[sbase + (uint64_t)r * ns + s] = key_thr(k);
-        best_plan[sbase + (uint64_t)r * ns + s] = key_plan(k);
+        const bool spans = s < ns && first / EB_TILE != (end - 1) / EB_TILE;
+        uint32_t todo = (uint32_t)(__ballot(spans) >> (half * MERGE_LANES));
+        while (todo) {
+            const uint32_t src = (uint32_t)__ffs((int)todo) - 1u;
+            todo &= todo - 1u;
+            const uint32_t f = (uint32_t)__shfl((int)first, (int)(half * MERGE_LANES + src), 64);
+            const uint32_t e = (uint32_t)__shfl((int)end, (int)(half * MERGE_LANES + src), 64);
+            const uint32_t ta = f / EB_TILE, tz = (e - 1) / EB_TILE;
+            for (uint32_t r = lane; r < n_rows; r += MERGE_LANES) {
+                unsigned long long k = 0;
+                for (uint32_t t = ta; t <= tz; ++t) {
+                    const uint32_t slot = f <= t * EB_TILE ? 0u : 1u;                  // it holds that tile's first triple
+                    k = max_u64(k, partial[((tile0 + t) * 2 + slot) * n_rows + r]);
+                }
+                best_thr[sbase + (uint64_t)r * ns + sb + src] = key_thr(k);
+                best_plan[sbase + (uint64_t)r * ns + sb + src] = key_plan(k);
+            }
+        }
     }
 }
 
@@ -606,7 +626,9 @@ int32_t rk_eval_best_plan(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table 
                                                                   key_stride, thr, nullptr, best_thr, best_plan, partial);
     RK_CHECK_LAUNCH(ctx, "k_eval_best");
     if (bx > 1) {
-        k_merge_spanning<<<nj, MERGE_THREADS, 0, ctx->stream>>>(td, (uint32_t)n_rows, jb, partial, best_thr, best_plan);
+        const uint32_t per_block = MERGE_THREADS / MERGE_LANES;
+        k_merge_spanning<<<(nj + per_block - 1) / per_block, MERGE_THREADS, 0, ctx->stream>>>(td, (uint32_t)n_rows, jb, nj, partial,
+                                                                                           best_thr, best_plan);
         RK_CHECK_LAUNCH(ctx, "k_merge_spanning");
     }
     return RK_OK;
