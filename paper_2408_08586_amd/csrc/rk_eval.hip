@@ -197,8 +197,10 @@ __device__ __forceinline__ float dpp_f32(float v) {
 // A workgroup barrier that orders LDS traffic only: every wavefront waits for its own LDS operations (lgkmcnt 0), not
 // for its global loads and stores, which __syncthreads() would also drain.  Enough where the data exchanged is in LDS.
 __device__ __forceinline__ void lds_barrier() {
+    asm volatile("" ::: "memory");               // the compiler keeps memory accesses on their side of the barrier
     __builtin_amdgcn_s_waitcnt(0xC07F);          // vmcnt 63, expcnt 7, lgkmcnt 0
     __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
 // index of a (job, tile) among the tiles of a call: tiles of different jobs never share an index (a job adds at
