@@ -356,8 +356,9 @@ def eval_one_placed(coef_row, ints_row, bounds, env, d, t, p, z, gc, off, c, hos
 
 
 def place_plans(coef, ints, bounds, table, grid, env, best_thr, assign, n_nodes, gpus_per_node, cpus_per_node,
-                mem_per_node_gb, min_seg=None):
-    """Placement that feeds the plan -> (placed records, place_off, entries, status, total)."""
+                mem_per_node_gb, min_seg=None, prev=None):
+    """Placement that feeds the plan -> (placed records, place_off, entries, status, total).
+    prev = (place_off, entries) of an earlier placement: jobs whose amounts are unchanged stay on their nodes."""
     coef = np.ascontiguousarray(coef, dtype=np.float32)
     ints = np.ascontiguousarray(ints, dtype=np.uint32)
     best_thr = np.ascontiguousarray(best_thr, dtype=np.float32)
@@ -371,11 +372,17 @@ def place_plans(coef, ints, bounds, table, grid, env, best_thr, assign, n_nodes,
     status = np.zeros(J, np.uint32)
     total = C.c_double(0)
     b, e = _bounds(bounds), _env(env)
+    p_off = None if prev is None else np.ascontiguousarray(prev[0], dtype=np.uint32)
+    p_ent = None if prev is None else np.ascontiguousarray(prev[1], dtype=PLACE_DTYPE)
+    if prev is not None:
+        assert p_off.size == J + 1 and int(p_off[J]) <= max(p_ent.size, 0) and np.all(np.diff(p_off.astype(np.int64)) >= 0)
+        if p_ent.size == 0:
+            p_ent = np.zeros(1, PLACE_DTYPE)
     rc = lib().ork_place_plans(C.c_uint32(J), _p(coef), _p(ints), C.byref(b), C.byref(table.c), C.byref(gh.c), C.byref(e),
-                               _p(best_thr), _p(assign), _p(ms), C.c_uint32(n_nodes), C.c_uint32(gpus_per_node),
+                               _p(best_thr), _p(assign), _p(ms), _p(p_off), _p(p_ent), C.c_uint32(n_nodes), C.c_uint32(gpus_per_node),
                                C.c_uint32(cpus_per_node), C.c_float(mem_per_node_gb), _p(out), _p(place_off), _p(entries),
                                _p(status), C.byref(total))
-    assert rc == 0, "the records are not an allocation on this table and grid"
+    assert rc == 0, "the records are not an allocation on this table and grid, or the kept parts do not fit the nodes"
     return out, place_off, entries[:int(place_off[J])].copy(), status, total.value
 
 

@@ -705,12 +705,22 @@ int ork_place_f32(uint32_t n_jobs, const ork_assign *assign, uint32_t n_nodes, u
  * when the job got nothing); status 0 nothing to place, 1 placed, 2 placed
  * with fewer GPUs than asked, 3 not placed.  total = sum of thr / ref_thr.
  * best_thr (segment layout of all jobs) says which (count, level, tier) have a
- * feasible plan at all.  PARITY UNPINNED as a reading; pinned by hand cases
- * (a 3+1 split that flips the best plan, a retry at a smaller count, the
- * floor) and by brute force over the plans on generated rounds. */
+ * feasible plan at all.
+ *  With an earlier placement (prev_off, prev_entries; NULL: none) running jobs
+ *  stay where they are (Algorithm 1's ScheduleJob adds to what a job holds): a
+ *  job whose amounts are the ones its earlier parts add up to - the same GPUs
+ *  and CPUs, and every part is what first fit books for these amounts on that
+ *  split - keeps those parts; all kept jobs are booked before any other job
+ *  looks for room, the others then take their turns in index order as above.
+ *  Returns -1 when the kept parts do not fit the nodes (prev is then not a
+ *  placement on these nodes).
+ * PARITY UNPINNED as a reading; pinned by hand cases (a 3+1 split that flips
+ * the best plan, a retry at a smaller count, the floor, jobs that stay) and by
+ * brute force over the plans on generated rounds. */
 int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, const ork_bounds *bounds,
                     const ork_table *tb, const ork_grid *grid, const ork_env *env, const float *best_thr,
-                    const ork_assign *assign, const int32_t *min_seg, uint32_t n_nodes, uint32_t gpus_per_node,
+                    const ork_assign *assign, const int32_t *min_seg, const uint32_t *prev_off,
+                    const ork_place_entry *prev_entries, uint32_t n_nodes, uint32_t gpus_per_node,
                     uint32_t cpus_per_node, float mem_per_node_gb, ork_assign *out, uint32_t *place_off,
                     ork_place_entry *entries, uint32_t *status, double *total) {
     const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
@@ -718,6 +728,37 @@ int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, co
     uint32_t n_entries = 0;
     double sum = 0.0;
     double x[ORK_N_TERMS];
+    /* the jobs that stay: booked first, whatever their index */
+    std::vector<uint8_t> kept(n_jobs, 0);
+    if (prev_off && prev_entries) {
+        for (uint32_t j = 0; j < n_jobs; ++j) {
+            const uint32_t g = assign[j].g, c = assign[j].c;
+            const float mem = assign[j].mem_gb;
+            const uint32_t a = prev_off[j], b = prev_off[j + 1];
+            if (g == 0 || a == b) continue;
+            uint64_t done = 0;
+            bool same = true;
+            for (uint32_t i = a; i < b && same; ++i) {
+                const ork_place_entry &e = prev_entries[i];
+                if (e.node >= n_nodes || e.g == 0 || done + e.g > g) { same = false; break; }
+                const uint32_t cpus = (uint32_t)((uint64_t)c * (done + e.g) / g - (uint64_t)c * done / g);
+                const float m = (mem * (float)e.g) / (float)g;
+                if (e.c != cpus || !(e.mem_gb == m)) same = false;
+                done += e.g;
+            }
+            kept[j] = same && done == g;
+        }
+        for (uint32_t j = 0; j < n_jobs; ++j) {
+            if (!kept[j]) continue;
+            for (uint32_t i = prev_off[j]; i < prev_off[j + 1]; ++i) {
+                const ork_place_entry &e = prev_entries[i];
+                if (nodes.freeG[e.node] < e.g || nodes.freeC[e.node] < e.c || !(e.mem_gb <= nodes.freeM[e.node])) return -1;
+                nodes.freeG[e.node] -= e.g;
+                nodes.freeC[e.node] -= e.c;
+                nodes.freeM[e.node] = nodes.freeM[e.node] - e.mem_gb;
+            }
+        }
+    }
     for (uint32_t j = 0; j < n_jobs; ++j) {
         place_off[j] = n_entries;
         status[j] = 0;
@@ -735,6 +776,10 @@ int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, co
         const int64_t s_min = (min_seg && min_seg[j] >= 0) ? min_seg[j] : 0;
         std::vector<ork_place_entry> parts;
         int64_t s = -1;
+        if (kept[j]) {                                      /* stays where it is; its parts are booked already */
+            parts.assign(prev_entries + prev_off[j], prev_entries + prev_off[j + 1]);
+            s = s0;
+        }
         for (int64_t s2 = s0; s2 >= 0 && s < 0; --s2) {     /* the amounts asked for, then smaller valid counts */
             if (s2 != s0) {
                 if (s2 < s_min) break;                      /* never below the floor */
@@ -745,7 +790,7 @@ int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, co
         }
         if (s < 0) { status[j] = 3; continue; }
         status[j] = (s == s0) ? 1 : 2;
-        nodes.book(parts);
+        if (!kept[j]) nodes.book(parts);
         std::vector<uint32_t> split;
         for (const ork_place_entry &e : parts) { entries[n_entries++] = e; split.push_back(e.g); }
         /* GetBestPlan(j, placement): the plans of this GPU count with the bandwidths of this split */

@@ -184,12 +184,16 @@ uint32_t ork_eval_one_placed(const float *coef17, const uint32_t *ints3, const o
  * floor), then the best plan of the placed count under the bandwidths of the
  * actual node split.  out[n_jobs] = placed amounts, plan, throughput; status
  * 0 nothing to place, 1 placed as asked, 2 placed with fewer GPUs, 3 not placed.
+ * prev_off [n_jobs+1] / prev_entries (or NULL): an earlier placement; a job
+ * whose amounts are what its earlier parts add up to keeps them, and the
+ * kept jobs are booked before the others look for room.
  * Returns -1 for a record that is no allocation on this table and grid (its
  * GPU count, CPU level or memory tier is not one of the job's, or no plan is
  * feasible there). */
 int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, const ork_bounds *bounds,
                     const ork_table *table, const ork_grid *grid, const ork_env *env, const float *best_thr,
-                    const ork_assign *assign, const int32_t *min_seg, uint32_t n_nodes, uint32_t gpus_per_node,
+                    const ork_assign *assign, const int32_t *min_seg, const uint32_t *prev_off,
+                    const ork_place_entry *prev_entries, uint32_t n_nodes, uint32_t gpus_per_node,
                     uint32_t cpus_per_node, float mem_per_node_gb, ork_assign *out, uint32_t *place_off,
                     ork_place_entry *entries, uint32_t *status, double *total);
 

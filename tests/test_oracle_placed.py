@@ -229,3 +229,174 @@ def test_generated_round_against_first_fit_and_brute_force(cpn, mpn):
         assert n_retried + int((st == 3).sum()) >= 1
     print(f"cpn={cpn} mpn={mpn}: {int(((st == 1) | (st == 2)).sum())} placed, {n_multi} over several nodes, {n_changed} plans "
           f"changed by the split, {n_retried} with fewer GPUs, {int((st == 3).sum())} not placed")
+
+
+# ---------------------------------------------------------------- jobs that stay where they are
+def stay_jobs(n):
+    """n copies of the hand job (counts 1, 2, 3, 4, 6, 8; 1 CPU and 64 GiB per job) with their maxima on a one-row grid."""
+    coef, ints = make_job(**HAND_JOB)
+    coef_n, ints_n = np.stack([coef] * n), np.stack([ints] * n)
+    tb = orc.enumerate_plans(ints_n, PLAIN)
+    grid = workloads.Grid(np.array([1], np.uint32), 0, np.array([64.0], np.float32), 0)
+    thr, _ = orc.eval_jobs(coef_n, ints_n, PLAIN, tb, grid, HAND_ENV)
+    bt = orc.best_plan(tb, grid, thr)[0].astype(np.float32)
+    return coef_n, ints_n, tb, grid, bt
+
+
+def stay_round(jobs, gs, prev=None, n_nodes=2, cpn=8):
+    coef, ints, tb, grid, bt = jobs
+    a = np.zeros(len(gs), orc.ASSIGN_DTYPE)
+    a["g"] = gs
+    a["c"] = [1 if g else 0 for g in gs]
+    a["mem_gb"] = [64.0 if g else 0.0 for g in gs]
+    out, off, ent, st, total = orc.place_plans(coef, ints, PLAIN, tb, grid, HAND_ENV, bt, a, n_nodes, 4, cpn, 1000.0, prev=prev)
+    parts = [[(int(e["node"]), int(e["g"])) for e in ent[off[j]:off[j + 1]]] for j in range(len(gs))]
+    return out, off, ent, st.tolist(), parts
+
+
+def test_running_jobs_stay_on_their_nodes():
+    jobs = stay_jobs(4)
+    # first round: A takes 3 GPUs of node 0, B 1 + 3, C the last GPU of node 1; D is not there yet
+    out1, off1, ent1, st1, parts1 = stay_round(jobs, [3, 4, 1, 0])
+    assert parts1 == [[(0, 3)], [(0, 1), (1, 3)], [(1, 1)], []] and st1 == [1, 1, 1, 0]
+    # A leaves, D arrives with 3 GPUs.  Laid out anew B would move to node 0; with the earlier placement B and C stay
+    # and D takes the three GPUs that A left
+    _, _, _, st_new, parts_new = stay_round(jobs, [0, 4, 1, 3])
+    assert parts_new == [[], [(0, 4)], [(1, 1)], [(1, 3)]]
+    out2, _, _, st2, parts2 = stay_round(jobs, [0, 4, 1, 3], prev=(off1, ent1))
+    assert parts2 == [[], [(0, 1), (1, 3)], [(1, 1)], [(0, 3)]] and st2 == [0, 1, 1, 1]
+    # B's plan is the one of its split 1 + 3 (every group crosses the nodes: four pipeline stages), as in round one
+    assert out2["plan"][1] == out1["plan"][1] and out2["thr"][1] == out1["thr"][1]
+    assert out2["thr"][1] == pytest.approx(32 / (0.58 + 0.02147483648), rel=1e-6)
+
+
+def test_a_newcomer_with_a_lower_index_does_not_take_a_kept_jobs_gpus():
+    jobs = stay_jobs(2)
+    _, off1, ent1, _, parts1 = stay_round(jobs, [0, 4])
+    assert parts1 == [[], [(0, 4)]]
+    # job 0 arrives and asks for 4: in index order from empty nodes it would take node 0; job 1 is booked first
+    _, _, _, st2, parts2 = stay_round(jobs, [4, 4], prev=(off1, ent1))
+    assert parts2 == [[(1, 4)], [(0, 4)]] and st2 == [1, 1]
+    # and falls back to a smaller count when what is left is less than it asks for
+    _, _, _, st3, parts3 = stay_round(jobs, [8, 4], prev=(off1, ent1))
+    assert parts3 == [[(1, 4)], [(0, 4)]] and st3 == [2, 1]
+
+
+def test_a_job_whose_amounts_changed_is_placed_again():
+    jobs = stay_jobs(3)
+    _, off1, ent1, _, parts1 = stay_round(jobs, [2, 3, 2])
+    assert parts1 == [[(0, 2)], [(0, 2), (1, 1)], [(1, 2)]]
+    # job 1 shrinks to 2 GPUs: its parts are released, jobs 0 and 2 stay, job 1 first-fits into what is free (node 0)
+    _, _, _, st2, parts2 = stay_round(jobs, [2, 2, 2], prev=(off1, ent1))
+    assert parts2 == [[(0, 2)], [(0, 2)], [(1, 2)]] and st2 == [1, 1, 1]
+    # job 0 grows to 4: released and placed again in its turn, after the kept jobs were booked: node 0 has 2 free,
+    # node 1 has 1 free -> 3 GPUs at most: it falls back to 3
+    out3, _, _, st3, parts3 = stay_round(jobs, [4, 3, 2], prev=(off1, ent1))
+    assert parts3 == [[(0, 2), (1, 1)], [(0, 2), (1, 1)], [(1, 2)]] and st3 == [2, 1, 1] and out3["g"][0] == 3
+    # the same GPUs with another CPU amount is a change as well (the parts' CPUs would differ)
+    coef, ints, tb, grid, bt = jobs
+    a = np.zeros(3, orc.ASSIGN_DTYPE)
+    a["g"], a["c"], a["mem_gb"] = [2, 3, 2], [1, 1, 1], [64.0, 64.0, 64.0]
+    ent_c = ent1.copy()
+    ent_c["c"][off1[1]] += 1                                         # job 1's first part claims one CPU more than first fit books
+    out, off, ent, st, _ = orc.place_plans(coef, ints, PLAIN, tb, grid, HAND_ENV, bt, a, 2, 4, 8, 1000.0, prev=(off1, ent_c))
+    assert [(int(e["node"]), int(e["g"])) for e in ent[off[1]:off[2]]] == [(0, 2), (1, 1)] and st.tolist() == [1, 1, 1]
+    assert int(ent["c"][off[1]]) + int(ent["c"][off[1] + 1]) == 1    # placed again with what first fit books
+
+
+def test_a_job_that_grew_is_not_kept_on_its_smaller_parts():
+    """One CPU per GPU and no host memory: the parts of 3 GPUs are exactly the first parts that 4 GPUs would get, so
+    only the GPU total tells that the job has changed."""
+    coef, ints, tb, _, _ = stay_jobs(2)
+    grid = workloads.Grid(np.array([1], np.uint32), 1, np.array([0.0], np.float32), 1)
+    thr, _ = orc.eval_jobs(coef, ints, PLAIN, tb, grid, HAND_ENV)
+    bt = orc.best_plan(tb, grid, thr)[0].astype(np.float32)
+
+    def round_(gs, prev=None):
+        a = np.zeros(2, orc.ASSIGN_DTYPE)
+        a["g"], a["c"] = gs, gs
+        out, off, ent, st, _ = orc.place_plans(coef, ints, PLAIN, tb, grid, HAND_ENV, bt, a, 2, 4, 8, 1000.0, prev=prev)
+        return off, ent, st.tolist(), [[(int(e["node"]), int(e["g"]), int(e["c"])) for e in ent[off[j]:off[j + 1]]] for j in range(2)]
+
+    off1, ent1, st1, parts1 = round_([2, 3])
+    assert parts1 == [[(0, 2, 2)], [(0, 2, 2), (1, 1, 1)]]
+    _, _, st2, parts2 = round_([2, 4], prev=(off1, ent1))
+    assert parts2 == [[(0, 2, 2)], [(0, 2, 2), (1, 2, 2)]] and st2 == [1, 1]
+
+
+def test_an_earlier_placement_that_does_not_fit_is_refused():
+    jobs = stay_jobs(2)
+    _, off1, ent1, _, _ = stay_round(jobs, [4, 4])
+    both_on_node_0 = ent1.copy()
+    both_on_node_0["node"][:] = 0
+    with pytest.raises(AssertionError):
+        stay_round(jobs, [4, 4], prev=(off1, both_on_node_0))
+    off_node = ent1.copy()
+    off_node["node"][1] = 7                                          # a node the cluster does not have: the job does not stay
+    _, _, _, st, parts = stay_round(jobs, [4, 4], prev=(off1, off_node))
+    assert parts == [[(0, 4)], [(1, 4)]] and st == [1, 1]
+
+
+def test_generated_rounds_with_an_earlier_placement():
+    """paper_scale jobs of at most 6 GPUs on 8 nodes x 8 GPUs: a round, then a quarter of the running jobs leave, the
+    others keep their amounts, newcomers take the free slots of the job list.  Every job that kept its amounts keeps
+    its parts, nothing exceeds a node, the newcomers are placed by first fit into what the kept jobs leave."""
+    import dataclasses
+    wl = dataclasses.replace(workloads.paper_scale(), bounds=workloads.Bounds(g_max=6))
+    r = orc.schedule_round(wl, n_threads=4)
+    tb, grid = r["table"], wl.grid
+    args = (wl.coef, wl.ints, wl.bounds, tb, grid, wl.env, r["best_thr"])
+    a1 = r["assign"]
+    out1, off1, ent1, st1, _ = orc.place_plans(*args, a1, 8, 8, 64, 4096.0)
+    running = np.flatnonzero(st1 == 1)
+    assert running.size >= 10
+    n_kept = n_new = 0
+    for seed in range(20):
+        rng = np.random.default_rng(seed)
+        a2 = out1.copy()                                             # what the jobs hold after round one
+        leave = running[rng.uniform(size=running.size) < 0.25]
+        a2[leave] = (0, 0, 0.0, orc.NO_PLAN, 0.0)
+        idle = np.flatnonzero(a2["g"] == 0)
+        arrive = idle[rng.uniform(size=idle.size) < 0.3]
+        for j in arrive:                                             # a newcomer asks for what the round gave some running job
+            src = int(rng.choice(running))
+            seg_g = tb.seg_g[tb.seg_off[j]:tb.seg_off[j + 1]]
+            rows = len(grid.cpu_levels) * len(grid.mem_levels_gb)
+            row0 = r["best_thr"][rows * int(tb.seg_off[j]):][:seg_g.size]       # lowest CPU level, first tier
+            ok = [s for s in range(seg_g.size) if row0[s] > 0]
+            if not ok:
+                continue
+            s = int(rng.choice(ok))
+            a2[j] = (int(seg_g[s]), int(grid.cpu_levels[0]), float(grid.mem_levels_gb[0]), 0, 0.0)
+        out2, off2, ent2, st2, _ = orc.place_plans(*args, a2, 8, 8, 64, 4096.0, prev=(off1, ent1))
+        stay = np.flatnonzero((a2["g"] > 0) & (a2["g"] == out1["g"]) & (a2["c"] == out1["c"]) & (a2["mem_gb"] == out1["mem_gb"])
+                              & (st1 > 0))
+        for j in stay:
+            assert np.array_equal(ent2[off2[j]:off2[j + 1]], ent1[off1[j]:off1[j + 1]]) and st2[j] == 1
+        n_kept += stay.size
+        used_g = np.bincount(ent2["node"], weights=ent2["g"], minlength=8)
+        used_c = np.bincount(ent2["node"], weights=ent2["c"], minlength=8)
+        assert used_g.max() <= 8 and used_c.max() <= 64
+        # the others, given to the pinned first fit on nodes that hold the kept parts already, get the same parts:
+        # replay them one by one in index order
+        freeG = np.full(8, 8, np.int64)
+        for j in stay:
+            for e in ent1[off1[j]:off1[j + 1]]:
+                freeG[e["node"]] -= int(e["g"])
+        for j in np.flatnonzero((a2["g"] > 0) & ~np.isin(np.arange(wl.n_jobs), stay)):
+            n_new += 1
+            if st2[j] == 3:
+                continue
+            g = int(out2["g"][j])
+            need, want = g, []
+            for n in range(8):                                       # GPUs bind alone here (64 CPUs, 4 TiB per node)
+                k = int(min(freeG[n], need))
+                if k:
+                    want.append((n, k))
+                    need -= k
+                if need == 0:
+                    break
+            assert need == 0 and [(int(e["node"]), int(e["g"])) for e in ent2[off2[j]:off2[j + 1]]] == want
+            for n, k in want:
+                freeG[n] -= k
+    assert n_kept > 100 and n_new > 30
