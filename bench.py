@@ -266,7 +266,8 @@ def algorithm1_bench(rk, ctx, dev, wl, jobs, table, grid, env, best_thr, best_pl
     """Algorithm 1 as a loop and on nodes, on the same workload: the state the from-scratch round leaves, then a tenth
     of the jobs leave (their slots are new arrivals) and the cluster loses a tenth of its GPUs and CPUs:
     rk_reschedule from that state; then rk_place_plans of its result on nodes of 8 GPUs, roomy and with 6 CPUs each
-    (fall-back to smaller GPU counts, plans chosen again on the actual node split)."""
+    (fall-back to smaller GPU counts, plans chosen again on the actual node split), with the placement of the state
+    before as the earlier placement: jobs whose amounts the loop left alone stay on their nodes."""
     import torch
     J = wl.n_jobs
     a0 = rk.assign_to_numpy(assign)
@@ -308,21 +309,32 @@ def algorithm1_bench(rk, ctx, dev, wl, jobs, table, grid, env, best_thr, best_pl
     status = torch.zeros(J, dtype=torch.int32, device=dev)
     ent = rk.new_place_entries(cap, dev)
     info["place_plans"] = {"entry": "rk_place_plans (host-synchronous)", "nodes": n_nodes, "gpus_per_node": gpn}
+    # where the jobs sat before the loop: the from-scratch round's amounts on the same nodes (the earlier placement)
+    before = rk.new_assign(J, dev)
+    off0 = torch.zeros(J + 1, dtype=torch.int32, device=dev)
+    ent0 = rk.new_place_entries(cap, dev)
     for name, cpn in (("roomy", wl.cluster.C // n_nodes), ("tight_cpus", 6)):
         nodes = rk.rk_nodes(n_nodes, gpn, min(int(cpn), 65535), float(wl.cluster.host_mem_gb) / n_nodes)
+        rk.rk_place_plans(ctx, jobs, table.c, grid, env, nodes, best_thr, assign, None, before, off0, ent0, cap, status, total)
         lat = []
         for i in range(reps + 2):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            r = rk.rk_place_plans(ctx, jobs, table.c, grid, env, nodes, best_thr, out, None, placed, off, ent, cap, status, total)
+            r = rk.rk_place_plans(ctx, jobs, table.c, grid, env, nodes, best_thr, out, None, placed, off, ent, cap, status, total,
+                                  prev_off=off0, prev_entries=ent0)
             if i >= 2:
                 lat.append((time.perf_counter() - t0) * 1e3)
+        o0, o1 = rk.u32(off0)[:J + 1].astype(np.int64), rk.u32(off)[:J + 1].astype(np.int64)
+        e0, e1 = rk.place_entries_to_numpy(ent0, int(o0[J])), rk.place_entries_to_numpy(ent, r.n_entries)
+        stayed = sum(1 for j in np.flatnonzero((np.diff(o0) > 0) & (np.diff(o1) > 0)).tolist()
+                     if np.array_equal(e0[o0[j]:o0[j + 1]], e1[o1[j]:o1[j + 1]]))
         st = rk.u32(status)[:J]
         p = rk.assign_to_numpy(placed)
         info["place_plans"][name] = {"cpus_per_node": int(nodes.cpus_per_node), "ms": float(np.median(lat)),
                                      "placed_as_asked": int((st == 1).sum()), "placed_with_fewer_gpus": int((st == 2).sum()),
                                      "not_placed": int((st == 3).sum()), "parts": r.n_entries,
                                      "plans_changed_by_the_split": int(((p["plan"] != res["plan"]) & (st == 1)).sum()),
+                                     "jobs_that_stayed_on_their_nodes": int(stayed),
                                      "job_by_job_stage": bool(r.in_order)}
     return info
 

@@ -581,6 +581,15 @@ int32_t rk_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs, const rk_a
  *    in placement order, tensor-parallel ranks adjacent, then data-parallel,
  *    then pipeline stages, and a kind of group uses B_intra only if every group
  *    of that kind has all its ranks on one node.
+ *  - with an earlier placement of the same jobs (prev_off, prev_entries, in
+ *    the layout this call writes; both NULL: every node starts empty) running
+ *    jobs stay where they are (ScheduleJob adds to what a job holds): a job
+ *    whose amounts are what its earlier parts add up to - the same GPUs and
+ *    CPUs, every part what first fit books for these amounts on that split -
+ *    keeps those parts (status 1); all kept jobs are booked, in index order,
+ *    before any other job looks for room.  If the kept parts do not fit the
+ *    nodes the earlier placement is ignored as a whole.  Must not alias the
+ *    output buffers.
  *   best_thr  [device] segment layout of all jobs (tells which counts have a feasible plan)
  *   placed    [device] n_jobs records: the amounts placed, the plan and its throughput
  *             (zeros and RK_NO_PLAN for a job that got nothing)
@@ -589,7 +598,8 @@ int32_t rk_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs, const rk_a
  *   total     [device] one float: sum of thr/ref_thr over the placed jobs */
 int32_t rk_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table, const rk_alloc_grid *grid,
                        const rk_env *env, const rk_nodes *nodes, const float *best_thr, const rk_assign *assign,
-                       const int32_t *min_seg_or_null, rk_assign *placed, uint32_t *place_off,
+                       const int32_t *min_seg_or_null, const uint32_t *prev_off_or_null,
+                       const rk_place_entry *prev_entries_or_null, rk_assign *placed, uint32_t *place_off,
                        rk_place_entry *entries, uint64_t cap_entries, uint32_t *status, float *total,
                        rk_place_result *result);
 

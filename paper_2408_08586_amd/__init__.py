@@ -498,11 +498,13 @@ def rk_place(ctx, nodes: rk_nodes, n_jobs, assign, place_off, entries, cap_entri
 
 
 def rk_place_plans(ctx, jobs: Jobs, table, grid, env, nodes: rk_nodes, best_thr, assign, min_seg, placed, place_off, entries,
-                   cap_entries, status, total, want_result=True):
-    """Placement that feeds the plan; min_seg may be None.  Returns rk_place_result (after a wait) or None."""
+                   cap_entries, status, total, want_result=True, prev_off=None, prev_entries=None):
+    """Placement that feeds the plan; min_seg may be None; prev_off / prev_entries: an earlier placement whose
+    unchanged jobs stay on their nodes.  Returns rk_place_result (after a wait) or None."""
     res = rk_place_result() if want_result else None
     _check(ctx, load_library().rk_place_plans(ctx, C.byref(jobs.c), C.byref(table), C.byref(grid), C.byref(env), C.byref(nodes),
-                                              _ptr(best_thr), _ptr(assign), _ptr(min_seg), _ptr(placed), _ptr(place_off),
+                                              _ptr(best_thr), _ptr(assign), _ptr(min_seg), _ptr(prev_off), _ptr(prev_entries),
+                                              _ptr(placed), _ptr(place_off),
                                               _ptr(entries), C.c_uint64(cap_entries), _ptr(status), _ptr(total),
                                               C.byref(res) if want_result else None))
     return res

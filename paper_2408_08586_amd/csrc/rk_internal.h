@@ -49,6 +49,7 @@ enum {
     SL_ENUM_LEADER,                                      // enumeration: the job whose search a job shares
     SL_RS_F32, SL_RS_U32, SL_RS_U64,                     // the Schedule loop: cached slopes; order, marks and saved states; CPU needs
     SL_EVAL_PARTIAL,                                     // evaluation with best plan: keys of the segments that span tiles
+    SL_PLACE_KEEP,                                       // placement: which jobs keep their earlier parts
     SL_COUNT
 };
 static_assert(SL_COUNT <= RK_SCRATCH_SLOTS, "more scratch slots than the context holds");
@@ -144,5 +145,6 @@ int32_t rk_launch_min_res(rk_ctx *ctx, const TableDev &tb, const rk_alloc_grid *
 // placement that feeds the plan, over all jobs of the table (arguments as rk_place_plans, already validated)
 int32_t rk_launch_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table, const rk_alloc_grid *grid,
                               const rk_env *env, const rk_nodes *nodes, const float *best_thr, const rk_assign *assign,
-                              const int32_t *min_seg, rk_assign *placed, uint32_t *place_off, rk_place_entry *entries,
+                              const int32_t *min_seg, const uint32_t *prev_off, const rk_place_entry *prev_entries,
+                              rk_assign *placed, uint32_t *place_off, rk_place_entry *entries,
                               uint64_t cap_entries, uint32_t *status, float *total, rk_place_result *result);

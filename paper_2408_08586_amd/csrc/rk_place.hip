@@ -43,6 +43,13 @@ struct Retry {
     GridDev grid;
 };
 
+// An earlier placement of the same jobs: a job whose amounts are what its earlier parts add up to keeps them.
+struct Keep {
+    const uint32_t *prev_off;            // n_jobs + 1 offsets into prev_entries; null: every node starts empty
+    const rk_place_entry *prev_entries;
+    uint8_t *flag;                       // scratch, per job: keeps its parts
+};
+
 struct PlaceArgs {
     uint32_t n_jobs, n_nodes, gpn, cpn;
     float mpn;
@@ -52,6 +59,7 @@ struct PlaceArgs {
     uint32_t *status;
     uint32_t *result;        // n_entries, n_placed, n_failed, in_order
     Retry retry;
+    Keep keep;
 };
 
 // Where a record's amounts sit in the job's lists: segment of the GPU count, CPU level, memory tier (-1: not
@@ -180,11 +188,14 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
     if (tid == 0) redo = 0u;
     __syncthreads();
 
-    // ---- stage 1: the jobs end to end on the GPU slots; a thread takes eight neighbouring jobs
+    // ---- stage 1: the jobs end to end on the GPU slots; a thread takes eight neighbouring jobs.  Not with an earlier
+    // placement to respect: the kept jobs sit where they sat, so the others go job by job into what is left.
+    const bool keeping = A.keep.prev_off != nullptr;
     const unsigned long long slots = (unsigned long long)A.n_nodes * A.gpn;
     unsigned long long carry_g = 0, carry_e = 0;          // GPU slots and parts before the tile
     uint32_t n_sched = 0, n_off = 0;                      // jobs with parts; records that are no allocation here
-    for (uint32_t base = 0; base < A.n_jobs; base += PLACE_THREADS * PLACE_PER) {
+    if (keeping && tid == 0) redo = 1u;
+    for (uint32_t base = 0; base < (keeping ? 0u : A.n_jobs); base += PLACE_THREADS * PLACE_PER) {
         const uint32_t j0 = base + tid * PLACE_PER;
         uint32_t g[PLACE_PER], c[PLACE_PER];
         float mem[PLACE_PER];
@@ -316,11 +327,64 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
 
     // ---- stage 2: job by job, by the first wavefront
     for (uint32_t n = tid; n < A.n_nodes; n += PLACE_THREADS) { nodeA[n] = A.gpn; nodeB[n] = A.cpn; nodeM[n] = A.mpn; }
+    if (keeping) {
+        // which jobs stay: the amounts asked are an allocation here and every earlier part is what first fit books
+        // for these amounts on that split (all threads, a job each)
+        for (uint32_t j = tid; j < A.n_jobs; j += PLACE_THREADS) {
+            const uint32_t g = A.assign[j].g, c = A.assign[j].c;
+            const float mem = A.assign[j].mem_gb;
+            const uint32_t a = A.keep.prev_off[j], b = A.keep.prev_off[j + 1];
+            bool same = g > 0 && b > a && (!A.retry.on || on_the_grid(A.retry, j, g, c, mem));
+            uint32_t done = 0;
+            for (uint32_t i = a; i < b && same; ++i) {
+                const rk_place_entry e = A.keep.prev_entries[i];
+                if (e.node >= A.n_nodes || e.g == 0 || e.g > g - done) { same = false; break; }
+                if (e.c != cpus_booked(c, done, e.g, g) || !(e.mem_gb == mem_of_part(mem, e.g, g))) same = false;
+                done += e.g;
+            }
+            A.keep.flag[j] = (same && done == g) ? 1 : 0;
+        }
+    }
     __syncthreads();
     if (tid >= 64) return;
     uint32_t cursor = 0, n_placed = 0, n_failed = 0;
     uint32_t first_g = 0, first_gc = 0;                  // first node with a free GPU; with a free GPU and a free CPU
     unsigned long long free_gpus = slots;                 // of the whole cluster
+    if (keeping) {
+        // the kept jobs are booked first, in job order (a node's free memory is a float32 running remainder, so the
+        // order of the subtractions is part of the result); a job's parts sit on different nodes: a lane each
+        bool fits = true;
+        for (uint32_t base = 0; base < A.n_jobs && fits; base += 64) {
+            const uint32_t j = base + lane;
+            unsigned long long todo = __ballot(j < A.n_jobs && A.keep.flag[j] != 0);
+            while (todo && fits) {
+                const uint32_t jj = base + (uint32_t)__ffsll((long long)todo) - 1u;
+                todo &= todo - 1ull;
+                const uint32_t a = A.keep.prev_off[jj], b = A.keep.prev_off[jj + 1];
+                for (uint32_t ib = a; ib < b && fits; ib += 64) {
+                    const uint32_t i = ib + lane;
+                    bool ok = true;
+                    if (i < b) {
+                        const rk_place_entry e = A.keep.prev_entries[i];
+                        ok = nodeA[e.node] >= e.g && nodeB[e.node] >= e.c && e.mem_gb <= nodeM[e.node];
+                        if (ok) {
+                            nodeA[e.node] -= e.g;
+                            nodeB[e.node] -= e.c;
+                            nodeM[e.node] = nodeM[e.node] - e.mem_gb;
+                        }
+                    }
+                    fits = __ballot(!ok) == 0ull;
+                }
+                free_gpus -= A.assign[jj].g;
+            }
+        }
+        if (!fits) {
+            // the earlier placement is no placement on these nodes: it is ignored, everything is placed anew
+            for (uint32_t n = lane; n < A.n_nodes; n += 64) { nodeA[n] = A.gpn; nodeB[n] = A.cpn; nodeM[n] = A.mpn; }
+            for (uint32_t j = lane; j < A.n_jobs; j += 64) A.keep.flag[j] = 0;
+            free_gpus = slots;
+        }
+    }
     for (uint32_t base = 0; base < A.n_jobs; base += 64) {
         const uint32_t j = base + lane;
         uint32_t g = 0, c = 0;
@@ -338,6 +402,15 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_place(PlaceArgs A) {
             uint32_t jg = (uint32_t)__builtin_amdgcn_readlane((int)g, turn);
             uint32_t jc = (uint32_t)__builtin_amdgcn_readlane((int)c, turn);
             float jm = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mem), turn));
+            if (keeping && A.keep.flag[base + (uint32_t)turn]) {           // stays: its earlier parts, booked above
+                const uint32_t jj = base + (uint32_t)turn;
+                const uint32_t a = A.keep.prev_off[jj], b = A.keep.prev_off[jj + 1];
+                for (uint32_t i = a + lane; i < b; i += 64) A.entries[cursor + (i - a)] = A.keep.prev_entries[i];
+                cursor += b - a;
+                if ((int)lane == turn) my_status = 1u;
+                ++n_placed;
+                continue;
+            }
             GridPos pos = {-2, -1, -1};                    // -2: not looked up yet
             uint32_t tries = 0, first, left, end;
             for (;;) {                                     // the amount asked for, then smaller ones if allowed
@@ -570,7 +643,7 @@ __global__ __launch_bounds__(1024) void k_place_total(uint32_t n_jobs, const rk_
 
 int32_t launch_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs, const rk_assign *assign, uint32_t *place_off,
                      rk_place_entry *entries, uint64_t cap_entries, uint32_t *status, const Retry &retry,
-                     rk_place_result *result) {
+                     const uint32_t *prev_off, const rk_place_entry *prev_entries, rk_place_result *result) {
     if (!nodes || !place_off) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
     if (n_jobs > 0 && (!assign || !status)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "assign or status is null");
     if (nodes->n_nodes < 1 || nodes->n_nodes > RK_MAX_NODES)
@@ -590,7 +663,15 @@ int32_t launch_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs, const 
     A.mpn = nodes->mem_per_node_gb;
     A.assign = assign; A.place_off = place_off; A.entries = entries; A.status = status;
     A.retry = retry;
+    A.keep = Keep{nullptr, nullptr, nullptr};
     int32_t rc;
+    if (prev_off && n_jobs > 0) {
+        if (!prev_entries) return rk_fail(ctx, RK_ERR_INVALID_ARG, "prev_off without prev_entries");
+        if (prev_entries == entries || prev_off == place_off)
+            return rk_fail(ctx, RK_ERR_INVALID_ARG, "the earlier placement must not be the output buffers");
+        A.keep.prev_off = prev_off; A.keep.prev_entries = prev_entries;
+        if ((rc = rk_scratch(ctx, SL_PLACE_KEEP, (size_t)n_jobs, (void **)&A.keep.flag))) return rc;
+    }
     if ((rc = rk_scratch(ctx, SL_PLACE_RESULT, 4 * sizeof(uint32_t), (void **)&A.result))) return rc;
     const size_t lds = (size_t)A.n_nodes * 5 * sizeof(uint32_t);
     if (lds > 48 * 1024 && !ctx->place_lds_raised) {
@@ -621,13 +702,15 @@ extern "C" int32_t rk_place(rk_ctx *ctx, const rk_nodes *nodes, uint32_t n_jobs,
     if (!ctx) return RK_ERR_INVALID_ARG;
     Retry none = {};
     int32_t rc;
-    if ((rc = launch_place(ctx, nodes, n_jobs, assign, place_off, entries, cap_entries, status, none, result))) return rc;
+    if ((rc = launch_place(ctx, nodes, n_jobs, assign, place_off, entries, cap_entries, status, none, nullptr, nullptr,
+                           result))) return rc;
     return result ? fetch_place_result(ctx, result) : RK_OK;
 }
 
 int32_t rk_launch_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table, const rk_alloc_grid *grid,
                               const rk_env *env, const rk_nodes *nodes, const float *best_thr, const rk_assign *assign,
-                              const int32_t *min_seg, rk_assign *placed, uint32_t *place_off, rk_place_entry *entries,
+                              const int32_t *min_seg, const uint32_t *prev_off, const rk_place_entry *prev_entries,
+                              rk_assign *placed, uint32_t *place_off, rk_place_entry *entries,
                               uint64_t cap_entries, uint32_t *status, float *total, rk_place_result *result) {
     const uint32_t n_jobs = table->n_jobs;
     Retry retry = {};
@@ -636,7 +719,8 @@ int32_t rk_launch_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_ta
     retry.best_thr = best_thr; retry.min_seg = min_seg;
     retry.grid = grid_dev(grid);
     int32_t rc;
-    if ((rc = launch_place(ctx, nodes, n_jobs, assign, place_off, entries, cap_entries, status, retry, result))) return rc;
+    if ((rc = launch_place(ctx, nodes, n_jobs, assign, place_off, entries, cap_entries, status, retry, prev_off, prev_entries,
+                           result))) return rc;
     if (n_jobs > 0) {
         ReplanArgs R;
         R.jobs = job_dev(jobs); R.tb = table_dev(table); R.grid = retry.grid; R.env = *env;
@@ -653,7 +737,8 @@ int32_t rk_launch_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_ta
 
 extern "C" int32_t rk_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table, const rk_alloc_grid *grid,
                                   const rk_env *env, const rk_nodes *nodes, const float *best_thr, const rk_assign *assign,
-                                  const int32_t *min_seg, rk_assign *placed, uint32_t *place_off, rk_place_entry *entries,
+                                  const int32_t *min_seg, const uint32_t *prev_off, const rk_place_entry *prev_entries,
+                                  rk_assign *placed, uint32_t *place_off, rk_place_entry *entries,
                                   uint64_t cap_entries, uint32_t *status, float *total, rk_place_result *result) {
     if (!ctx) return RK_ERR_INVALID_ARG;
     int32_t rc;
@@ -664,6 +749,6 @@ extern "C" int32_t rk_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_pla
     if ((rc = rk_check_env(ctx, env))) return rc;
     if (table->n_jobs > 0 && (!placed || !jobs->ref_thr || (table->n_segs > 0 && !best_thr)))
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
-    return rk_launch_place_plans(ctx, jobs, table, grid, env, nodes, best_thr, assign, min_seg, placed, place_off, entries,
-                                 cap_entries, status, total, result);
+    return rk_launch_place_plans(ctx, jobs, table, grid, env, nodes, best_thr, assign, min_seg, prev_off, prev_entries, placed,
+                                 place_off, entries, cap_entries, status, total, result);
 }

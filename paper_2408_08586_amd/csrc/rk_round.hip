@@ -175,8 +175,8 @@ int32_t rk_schedule_round_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan
     RoundKeep keep;
     if ((rc = schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, nullptr, &cluster, jobs->n_jobs > 0 ? sla : nullptr, assign,
                               total, &keep))) return rc;
-    return rk_launch_place_plans(ctx, jobs, &keep.tb, grid, env, nodes, keep.best_thr, assign, keep.min_seg, placed, place_off,
-                                 entries, cap_entries, status, total, result);
+    return rk_launch_place_plans(ctx, jobs, &keep.tb, grid, env, nodes, keep.best_thr, assign, keep.min_seg, nullptr, nullptr,
+                                 placed, place_off, entries, cap_entries, status, total, result);
 }
 
 }  // extern "C"

@@ -26,13 +26,19 @@ def gpu():
     return DeviceRun
 
 
-def place_on_gpu(run, best_thr, assign, floors, n_nodes, gpn, cpn, mpn):
+def place_on_gpu(run, best_thr, assign, floors, n_nodes, gpn, cpn, mpn, prev=None):
+    """prev = (place_off, entries) of an earlier placement as numpy arrays, or None."""
     import torch
     import paper_2408_08586_amd as rk
     J = run.wl.n_jobs
     dev = run.device
     d_assign = torch.from_numpy(np.ascontiguousarray(assign).view(np.uint8).copy()).to(dev)
     d_floor = None if floors is None else torch.from_numpy(np.ascontiguousarray(floors, dtype=np.int32)).to(dev)
+    p_off = p_ent = None
+    if prev is not None:
+        p_off = torch.from_numpy(np.ascontiguousarray(prev[0], dtype=np.uint32).view(np.int32).copy()).to(dev)
+        ent = np.ascontiguousarray(prev[1], dtype=rk.PLACE_DTYPE)
+        p_ent = torch.from_numpy((ent if ent.size else np.zeros(1, rk.PLACE_DTYPE)).view(np.uint8).copy()).to(dev)
     placed = rk.new_assign(J, dev)
     cap = n_nodes * gpn
     off = torch.full((J + 1,), -1, dtype=torch.int32, device=dev)
@@ -40,7 +46,8 @@ def place_on_gpu(run, best_thr, assign, floors, n_nodes, gpn, cpn, mpn):
     ent = rk.new_place_entries(cap, dev)
     total = run.f32(1)
     res = rk.rk_place_plans(run.ctx, run.jobs, run.table.c, run.grid, run.env, rk.rk_nodes(n_nodes, gpn, cpn, mpn),
-                            run.dev_f32(best_thr), d_assign, d_floor, placed, off, ent, cap, status, total)
+                            run.dev_f32(best_thr), d_assign, d_floor, placed, off, ent, cap, status, total,
+                            prev_off=p_off, prev_entries=p_ent)
     return (rk.assign_to_numpy(placed), rk.u32(off), rk.place_entries_to_numpy(ent, res.n_entries), rk.u32(status)[:J],
             float(total[0].item()), res)
 
@@ -182,6 +189,19 @@ def test_stress_round_on_its_nodes(gpu, orc):
               f"{int((st == 3).sum())} not placed; job-by-job stage: {bool(got[5].in_order)}")
         assert bool(got[5].in_order) == (cpn == 6)
     assert (st == 2).sum() + (st == 3).sum() > 0
+    # a second round on roomy nodes: a tenth of the running jobs leave, the others stay where they are
+    first = orc.place_plans(wl.coef, wl.ints, wl.bounds, ot, wl.grid, wl.env, bt, assign, 512, 8, 128, 2048.0)
+    rng = np.random.default_rng(7)
+    a2 = first[0].copy()
+    gone = np.flatnonzero(a2["g"] > 0)[rng.uniform(size=int((a2["g"] > 0).sum())) < 0.1]
+    a2[gone] = (0, 0, 0.0, orc.NO_PLAN, 0.0)
+    prev = (first[1], first[2])
+    want = orc.place_plans(wl.coef, wl.ints, wl.bounds, ot, wl.grid, wl.env, bt, a2, 512, 8, 128, 2048.0, prev=prev)
+    got = place_on_gpu(run, bt, a2, None, 512, 8, 128, 2048.0, prev=prev)
+    compare(orc, wl, ot, want, got)
+    stay = np.flatnonzero(a2["g"] > 0)
+    assert gone.size > 5 and all(np.array_equal(want[2][want[1][j]:want[1][j + 1]], first[2][first[1][j]:first[1][j + 1]])
+                                 for j in stay)
     run.close()
 
 
@@ -302,3 +322,102 @@ def test_argument_errors_and_amounts_off_the_grid(gpu, orc):
     assert e.value.code == rk.RK_ERR_INVALID_ARG
     assert call().n_placed == served.size                                   # the context works on after the errors
     run.close()
+
+
+def test_running_jobs_stay_on_their_nodes(gpu, orc):
+    """The hand cases of the oracle's pins on the device: jobs that stay, a newcomer with a lower index, changed
+    amounts, and an earlier placement that does not fit (the library then places everything anew)."""
+    from test_oracle_placed import stay_jobs
+    coef, ints, tb, grid, bt = stay_jobs(4)
+    wl = workloads.Workload("stay", coef, ints, PLAIN, grid, HAND_ENV, workloads.Cluster(8, 16, 1000.0))
+    run = gpu(wl)
+    run.enumerate()
+
+    def records(gs):
+        a = np.zeros(4, orc.ASSIGN_DTYPE)
+        a["g"], a["c"], a["mem_gb"] = gs, [1 if g else 0 for g in gs], [64.0 if g else 0.0 for g in gs]
+        return a
+
+    def both(gs, prev=None, cpn=8):
+        a = records(gs)
+        want = orc.place_plans(coef, ints, PLAIN, tb, grid, HAND_ENV, bt, a, 2, 4, cpn, 1000.0, prev=prev)
+        got = place_on_gpu(run, bt, a, None, 2, 4, cpn, 1000.0, prev=prev)
+        assert compare(orc, wl, tb, want, got) == 0
+        return want, got
+
+    w1, g1 = both([3, 4, 1, 0])
+    prev = (g1[1], g1[2])                                            # the library's own earlier placement
+    w2, g2 = both([0, 4, 1, 3], prev=prev)
+    assert [(int(e["node"]), int(e["g"])) for e in g2[2]] == [(0, 1), (1, 3), (1, 1), (0, 3)] and bool(g2[5].in_order)
+    both([0, 4, 1, 3])                                               # and without it job 1 moves to node 0
+    both([0, 3, 1, 3], prev=prev)                                    # job 1 shrank: placed again
+    both([4, 4, 0, 0], prev=(w2[1], w2[2]))                          # job 0 arrives ahead of the kept job 1
+    both([8, 4, 0, 0], prev=(w2[1], w2[2]))                          # ... and falls back to what is left
+    # an earlier placement that claims both 4-GPU jobs on node 0: the oracle refuses, the library ignores it
+    w, g = both([4, 4, 0, 0])
+    bad = g[2].copy()
+    bad["node"][:] = 0
+    with pytest.raises(AssertionError):
+        orc.place_plans(coef, ints, PLAIN, tb, grid, HAND_ENV, bt, records([4, 4, 0, 0]), 2, 4, 8, 1000.0, prev=(g[1], bad))
+    again = place_on_gpu(run, bt, records([4, 4, 0, 0]), None, 2, 4, 8, 1000.0, prev=(g[1], bad))
+    assert compare(orc, wl, tb, w, again) == 0
+    run.close()
+
+
+def test_random_second_rounds_with_an_earlier_placement(gpu, orc):
+    """Seeded random workloads on random nodes, two rounds each: the first placement, then some jobs leave, some change
+    their amounts, some arrive (amounts of other valid points of their grid), and the second placement keeps what it can."""
+    base = workloads.paper_scale()
+    done = n_kept = n_moved = n_failed = 0
+    for seed in range(200):
+        rng = np.random.default_rng(99000 + seed)
+        wl = draw_workload(rng, base, mid=seed % 4 == 0)
+        r = orc.schedule_round(wl, n_threads=8)
+        ot = r["table"]
+        if ot.triple_off[-1] == 0 or int(np.diff(ot.triple_off).max()) > 2048:
+            continue
+        a1 = r["assign"]
+        gpn = int(rng.choice([2, 4, 8]))
+        n_nodes = int(max(1, -(-int(a1["g"].sum()) // gpn) + rng.integers(0, 3)))
+        cpn = int(min(65535, rng.choice([4 * gpn, 16 * gpn, 40 * gpn])))
+        mpn = float(rng.choice([64.0, 512.0, 1e5]))
+        wl = dataclasses.replace(wl, env=dataclasses.replace(wl.env, gpus_per_node=gpn))
+        args = (wl.coef, wl.ints, wl.bounds, ot, wl.grid, wl.env, r["best_thr"])
+        w1 = orc.place_plans(*args, a1, n_nodes, gpn, cpn, mpn)
+        run = gpu(wl)
+        run.enumerate()
+        g1 = place_on_gpu(run, r["best_thr"], a1, None, n_nodes, gpn, cpn, mpn)
+        compare(orc, wl, ot, w1, g1)
+        # second round: what the jobs hold, minus those that leave, with some amounts changed to other feasible points
+        a2 = w1[0].copy()
+        rows = len(wl.grid.cpu_levels) * len(wl.grid.mem_levels_gb)
+        n_mem = len(wl.grid.mem_levels_gb)
+        for j in range(wl.n_jobs):
+            u = rng.uniform()
+            if a2["g"][j] > 0 and u < 0.2:
+                a2[j] = (0, 0, 0.0, orc.NO_PLAN, 0.0)
+            elif u < 0.45:
+                ns = int(ot.seg_off[j + 1] - ot.seg_off[j])
+                bt_j = r["best_thr"][rows * int(ot.seg_off[j]):rows * int(ot.seg_off[j + 1])].reshape(rows, ns) if ns else None
+                ok = np.argwhere(bt_j > 0) if ns else np.zeros((0, 2), int)
+                if len(ok):
+                    row, s = (int(x) for x in ok[rng.integers(0, len(ok))])
+                    g = int(ot.seg_g[ot.seg_off[j] + s])
+                    ci, mi = row // n_mem, row % n_mem
+                    c = int(wl.grid.cpu_levels[ci]) * (g if wl.grid.cpu_mode else 1)
+                    m = np.float32(wl.grid.mem_levels_gb[mi]) * (np.float32(g) if wl.grid.mem_mode else np.float32(1))
+                    a2[j] = (g, c, float(m), 0, 0.0)
+        prev = (g1[1], g1[2])
+        w2 = orc.place_plans(*args, a2, n_nodes, gpn, cpn, mpn, prev=prev)
+        g2 = place_on_gpu(run, r["best_thr"], a2, None, n_nodes, gpn, cpn, mpn, prev=prev)
+        compare(orc, wl, ot, w2, g2)
+        run.close()
+        same = (a2["g"] > 0) & (a2["g"] == w1[0]["g"]) & (a2["c"] == w1[0]["c"]) & (a2["mem_gb"] == w1[0]["mem_gb"])
+        for j in np.flatnonzero(same):
+            assert np.array_equal(w2[2][w2[1][j]:w2[1][j + 1]], w1[2][w1[1][j]:w1[1][j + 1]])
+        n_kept += int(same.sum())
+        n_moved += int(((a2["g"] > 0) & ~same & (w2[3] > 0) & (w2[3] < 3)).sum())
+        n_failed += int((w2[3] == 3).sum())
+        done += 1
+    print(f"{done} workloads: {n_kept} jobs stayed, {n_moved} placed again or new, {n_failed} not placed")
+    assert done > 150 and n_kept > 100 and n_moved > 150 and n_failed > 100
