@@ -386,4 +386,41 @@ def place_plans(coef, ints, bounds, table, grid, env, best_thr, assign, n_nodes,
     return out, place_off, entries[:int(place_off[J])].copy(), status, total.value
 
 
+def reschedule_nodes(ref_thr, table, grid, n_nodes, gpus_per_node, cpus_per_node, mem_per_node_gb, best_thr, best_idx,
+                     curve_thr, cur_seg, cur_c, prev, floor_seg=None, floor_c=None, state=None):
+    """Algorithm 1's Schedule with the node-by-node search of ScheduleJob, from the jobs' present state and
+    placement prev = (place_off, entries) -> (records, place_off, entries, total, steps committed), or None when
+    the state is not a placement on these nodes."""
+    gh = _GridHolder(grid)
+    J = table.n_jobs
+    f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    ref_thr, best_thr, curve_thr = f(ref_thr), f(best_thr), f(curve_thr)
+    best_idx = np.ascontiguousarray(best_idx, dtype=np.uint32)
+    cur_seg = np.ascontiguousarray(cur_seg, dtype=np.int32)
+    cur_c = np.ascontiguousarray(cur_c, dtype=np.uint32)
+    state = None if state is None else np.ascontiguousarray(state, dtype=np.uint8)
+    floor_seg = None if floor_seg is None else np.ascontiguousarray(floor_seg, dtype=np.int32)
+    floor_c = None if floor_c is None else np.ascontiguousarray(floor_c, dtype=np.uint32)
+    p_off = None if prev is None else np.ascontiguousarray(prev[0], dtype=np.uint32)
+    p_ent = None if prev is None else np.ascontiguousarray(prev[1], dtype=PLACE_DTYPE)
+    if prev is not None:
+        assert p_off.size == J + 1 and int(p_off[J]) <= p_ent.size and np.all(np.diff(p_off.astype(np.int64)) >= 0)
+        if p_ent.size == 0:
+            p_ent = np.zeros(1, PLACE_DTYPE)
+    assign = np.zeros(J, ASSIGN_DTYPE)
+    place_off = np.zeros(J + 1, np.uint32)
+    entries = np.zeros(max(n_nodes * gpus_per_node, 1), PLACE_DTYPE)
+    total, moves = C.c_double(0), C.c_uint32(0)
+    rc = lib().ork_reschedule_nodes_f32(C.c_uint32(J), _p(ref_thr), C.byref(table.c), C.byref(gh.c), C.c_uint32(n_nodes),
+                                        C.c_uint32(gpus_per_node), C.c_uint32(cpus_per_node), C.c_float(mem_per_node_gb),
+                                        _p(best_thr), _p(best_idx), _p(curve_thr), _p(state), _p(cur_seg), _p(cur_c),
+                                        _p(floor_seg), _p(floor_c), _p(p_off), _p(p_ent), _p(assign), _p(place_off),
+                                        _p(entries), C.byref(total), C.byref(moves))
+    assert rc != -2, "the grid's CPU levels must be CPUs per GPU"
+    if rc == -1:
+        return None
+    assert rc == 0
+    return assign, place_off, entries[:int(place_off[J])].copy(), total.value, moves.value
+
+
 from . import simulator  # noqa: E402

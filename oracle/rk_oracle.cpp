@@ -12,6 +12,8 @@
 #include <cmath>
 #include <cstring>
 #include <thread>
+#include <map>
+#include <set>
 #include <vector>
 
 namespace {
@@ -328,6 +330,119 @@ struct NodeState {
             freeC[e.node] -= e.c;
             freeM[e.node] = freeM[e.node] - e.mem_gb;
         }
+    }
+};
+
+/* What Algorithm 1's loop asks of a job's curves (Sec. 5.2, the paragraphs on slopes and on shrinking): the state the
+ * jobs are in and, from it, a job's next step up and what it gives when it steps down, in GPUs and in CPU levels.
+ * Shared by the loop over the cluster's totals and the loop over its nodes. */
+struct Loop {
+    uint32_t n_jobs;
+    const float *ref_thr;
+    const ork_table *tb;
+    const ork_grid *grid;
+    uint64_t G;                         /* GPUs of the cluster: no step goes beyond */
+    const float *best_thr, *curve_thr;
+    const uint8_t *state;
+    const int32_t *floor_seg;
+    const uint32_t *floor_c;
+    std::vector<int64_t> gi;            /* what every job holds: index of its GPU count (-1 nothing) ... */
+    std::vector<uint32_t> ci;           /* ... and its CPU level */
+
+    Loop(uint32_t n, const float *ref, const ork_table *t, const ork_grid *g, uint64_t gpus, const float *best,
+         const float *curve, const uint8_t *st, const int32_t *fs, const uint32_t *fc)
+        : n_jobs(n), ref_thr(ref), tb(t), grid(g), G(gpus), best_thr(best), curve_thr(curve), state(st),
+          floor_seg(fs), floor_c(fc), gi(n, -1), ci(n, 0) {}
+
+    int64_t ns_of(uint32_t j) const { return (int64_t)(tb->seg_off[j + 1] - tb->seg_off[j]); }
+    uint64_t g_at(uint32_t j, int64_t s) const { return s < 0 ? 0 : tb->seg_g[tb->seg_off[j] + s]; }
+    uint64_t c_at(uint32_t j, uint32_t c, int64_t s) const { return s < 0 ? 0 : cpus_of(grid, c, (uint32_t)g_at(j, s)); }
+    /* value of job j at CPU level c, highest memory tier, GPU count s (0 below the first) */
+    float at(const float *arr, uint32_t j, uint32_t c, int64_t s) const {
+        const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
+        const uint32_t m_top = grid->n_mem - 1;
+        return s < 0 ? 0.0f : arr[rows * tb->seg_off[j] + ((uint64_t)c * grid->n_mem + m_top) * ns_of(j) + s];
+    }
+    bool part(uint32_t j) const { return !state || state[j] == 0; }
+    /* the job's floor: a segment the job does not have counts as none, the CPU level is clamped to the grid */
+    int64_t fl_s(uint32_t j) const {
+        return (floor_seg && floor_seg[j] >= 0 && floor_seg[j] < ns_of(j)) ? floor_seg[j] : -1;
+    }
+    uint32_t fl_c(uint32_t j) const {
+        return (fl_s(j) >= 0 && floor_c) ? std::min(floor_c[j], grid->n_cpu - 1) : 0u;
+    }
+
+    struct Step { bool any; int64_t tgt; uint32_t lvl; float slope, gain; uint64_t dg, dc; };
+    /* the next GPU step of job j: to its floor while below it, else the larger count with the highest slope */
+    Step up_gpu(uint32_t j) const {
+        Step st = {false, -1, ci[j], 0.0f, 0.0f, 0, 0};
+        const float cur = at(curve_thr, j, ci[j], gi[j]);
+        if (fl_s(j) >= 0 && gi[j] < fl_s(j)) {
+            const uint32_t lvl = std::max(ci[j], fl_c(j));
+            const float v = at(curve_thr, j, lvl, fl_s(j));
+            st.any = true; st.tgt = fl_s(j); st.lvl = lvl;
+            st.dg = g_at(j, fl_s(j)) - g_at(j, gi[j]);
+            st.dc = c_at(j, lvl, fl_s(j)) - c_at(j, ci[j], gi[j]);
+            st.gain = (v - cur) / ref_thr[j];
+            st.slope = st.gain / (float)st.dg;
+            return st;
+        }
+        for (int64_t s = gi[j] + 1; s < ns_of(j); ++s) {
+            const uint64_t dg = g_at(j, s) - g_at(j, gi[j]);
+            if (g_at(j, s) > G) break;
+            const float v = at(curve_thr, j, ci[j], s);
+            if (!(v > cur)) continue;
+            const float gain = (v - cur) / ref_thr[j];
+            const float sl = gain / (float)dg;
+            if (sl > st.slope) {
+                st.any = true; st.tgt = s; st.slope = sl; st.gain = gain; st.dg = dg;
+                st.dc = c_at(j, ci[j], s) - c_at(j, ci[j], gi[j]);
+            }
+        }
+        return st;
+    }
+    Step up_cpu(uint32_t j) const {
+        Step st = {false, gi[j], ci[j], 0.0f, 0.0f, 0, 0};
+        if (gi[j] < 0) return st;
+        const float cur = at(best_thr, j, ci[j], gi[j]);
+        for (uint32_t c = ci[j] + 1; c < grid->n_cpu; ++c) {
+            const uint64_t dc = c_at(j, c, gi[j]) - c_at(j, ci[j], gi[j]);
+            const float v = at(best_thr, j, c, gi[j]);
+            if (!(v > cur)) continue;
+            const float gain = (v - cur) / ref_thr[j];
+            const float sl = gain / (float)dc;
+            if (sl > st.slope) { st.any = true; st.lvl = c; st.slope = sl; st.gain = gain; st.dc = dc; }
+        }
+        return st;
+    }
+    /* what job v gives when it steps down in GPUs: target segment (-1 = everything), loss, units */
+    struct Give { bool any; int64_t tgt; float loss, slope; uint64_t dg, dc; };
+    Give down_gpu(uint32_t v) const {
+        Give gv = {false, -1, 0.0f, 0.0f, 0, 0};
+        if (gi[v] < 0 || (fl_s(v) >= 0 && gi[v] <= fl_s(v))) return gv;
+        const float V = at(curve_thr, v, ci[v], gi[v]);
+        /* down to where the curve's value just below begins: the largest amount with a lower throughput, or, when
+           the job holds more than it uses (same value just below), the smallest amount with the same throughput */
+        const float want = at(curve_thr, v, ci[v], gi[v] - 1);
+        int64_t t = -1;
+        if (want > 0.0f) for (t = 0; at(curve_thr, v, ci[v], t) != want; ++t) {}
+        if (fl_s(v) >= 0 && t < fl_s(v)) t = fl_s(v);
+        gv.any = true; gv.tgt = t;
+        gv.loss = (V - at(curve_thr, v, ci[v], t)) / ref_thr[v];
+        gv.dg = g_at(v, gi[v]) - g_at(v, t);
+        gv.dc = c_at(v, ci[v], gi[v]) - c_at(v, ci[v], t);
+        gv.slope = gv.loss / (float)gv.dg;
+        return gv;
+    }
+    Give down_cpu(uint32_t v) const {
+        Give gv = {false, gi[v], 0.0f, 0.0f, 0, 0};
+        const uint32_t lowest = (fl_s(v) >= 0) ? fl_c(v) : 0u;
+        if (gi[v] < 0 || ci[v] == 0 || ci[v] <= lowest) return gv;
+        gv.any = true;
+        gv.loss = (at(best_thr, v, ci[v], gi[v]) - at(best_thr, v, ci[v] - 1, gi[v])) / ref_thr[v];
+        gv.dc = c_at(v, ci[v], gi[v]) - c_at(v, ci[v] - 1, gi[v]);
+        gv.slope = gv.loss / (float)gv.dc;
+        return gv;
     }
 };
 
@@ -852,25 +967,20 @@ int ork_reschedule_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *t
                        const uint32_t *best_plan, const float *curve_thr, const uint8_t *state,
                        const int32_t *cur_seg, const uint32_t *cur_c, const int32_t *floor_seg,
                        const uint32_t *floor_c, ork_assign *assign, double *total, uint32_t *n_moves) {
-    const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
-    const uint32_t m_top = grid->n_mem - 1;
-    std::vector<int64_t> gi(n_jobs, -1);
-    std::vector<uint32_t> ci(n_jobs, 0);
-    auto ns_of = [&](uint32_t j) { return (int64_t)(tb->seg_off[j + 1] - tb->seg_off[j]); };
-    auto g_at = [&](uint32_t j, int64_t s) -> uint64_t { return s < 0 ? 0 : tb->seg_g[tb->seg_off[j] + s]; };
-    auto c_at = [&](uint32_t j, uint32_t c, int64_t s) -> uint64_t { return s < 0 ? 0 : cpus_of(grid, c, (uint32_t)g_at(j, s)); };
-    auto at = [&](const float *arr, uint32_t j, uint32_t c, int64_t s) -> float {
-        return s < 0 ? 0.0f : arr[rows * tb->seg_off[j] + ((uint64_t)c * grid->n_mem + m_top) * ns_of(j) + s];
-    };
-    auto part = [&](uint32_t j) { return !state || state[j] == 0; };
-    /* the job's floor: a segment the job does not have counts as none, the CPU level is clamped to the grid */
-    auto fl_s = [&](uint32_t j) -> int64_t {
-        return (floor_seg && floor_seg[j] >= 0 && floor_seg[j] < ns_of(j)) ? floor_seg[j] : -1;
-    };
-    auto fl_c = [&](uint32_t j) -> uint32_t {
-        return (fl_s(j) >= 0 && floor_c) ? std::min(floor_c[j], grid->n_cpu - 1) : 0u;
-    };
-
+    Loop L(n_jobs, ref_thr, tb, grid, G, best_thr, curve_thr, state, floor_seg, floor_c);
+    std::vector<int64_t> &gi = L.gi;
+    std::vector<uint32_t> &ci = L.ci;
+    typedef Loop::Step Step;
+    typedef Loop::Give Give;
+    auto ns_of = [&](uint32_t j) { return L.ns_of(j); };
+    auto g_at = [&](uint32_t j, int64_t s) { return L.g_at(j, s); };
+    auto c_at = [&](uint32_t j, uint32_t c, int64_t s) { return L.c_at(j, c, s); };
+    auto part = [&](uint32_t j) { return L.part(j); };
+    auto fl_s = [&](uint32_t j) { return L.fl_s(j); };
+    auto up_gpu = [&](uint32_t j) { return L.up_gpu(j); };
+    auto up_cpu = [&](uint32_t j) { return L.up_cpu(j); };
+    auto down_gpu = [&](uint32_t v) { return L.down_gpu(v); };
+    auto down_cpu = [&](uint32_t v) { return L.down_cpu(v); };
     uint64_t heldG = 0, heldC = 0;
     for (uint32_t j = 0; j < n_jobs; ++j) {
         if (!part(j) || cur_seg[j] < 0 || cur_seg[j] >= ns_of(j) || cur_c[j] >= grid->n_cpu) continue;
@@ -879,79 +989,6 @@ int ork_reschedule_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *t
     }
     uint64_t freeG = heldG < G ? G - heldG : 0, freeC = heldC < C ? C - heldC : 0;
     uint32_t moves = 0;
-
-    struct Step { bool any; int64_t tgt; uint32_t lvl; float slope, gain; uint64_t dg, dc; };
-    /* the next GPU step of job j: to its floor while below it, else the larger count with the highest slope */
-    auto up_gpu = [&](uint32_t j) {
-        Step st = {false, -1, ci[j], 0.0f, 0.0f, 0, 0};
-        const float cur = at(curve_thr, j, ci[j], gi[j]);
-        if (fl_s(j) >= 0 && gi[j] < fl_s(j)) {
-            const uint32_t lvl = std::max(ci[j], fl_c(j));
-            const float v = at(curve_thr, j, lvl, fl_s(j));
-            st.any = true; st.tgt = fl_s(j); st.lvl = lvl;
-            st.dg = g_at(j, fl_s(j)) - g_at(j, gi[j]);
-            st.dc = c_at(j, lvl, fl_s(j)) - c_at(j, ci[j], gi[j]);
-            st.gain = (v - cur) / ref_thr[j];
-            st.slope = st.gain / (float)st.dg;
-            return st;
-        }
-        for (int64_t s = gi[j] + 1; s < ns_of(j); ++s) {
-            const uint64_t dg = g_at(j, s) - g_at(j, gi[j]);
-            if (g_at(j, s) > G) break;
-            const float v = at(curve_thr, j, ci[j], s);
-            if (!(v > cur)) continue;
-            const float gain = (v - cur) / ref_thr[j];
-            const float sl = gain / (float)dg;
-            if (sl > st.slope) {
-                st.any = true; st.tgt = s; st.slope = sl; st.gain = gain; st.dg = dg;
-                st.dc = c_at(j, ci[j], s) - c_at(j, ci[j], gi[j]);
-            }
-        }
-        return st;
-    };
-    auto up_cpu = [&](uint32_t j) {
-        Step st = {false, gi[j], ci[j], 0.0f, 0.0f, 0, 0};
-        if (gi[j] < 0) return st;
-        const float cur = at(best_thr, j, ci[j], gi[j]);
-        for (uint32_t c = ci[j] + 1; c < grid->n_cpu; ++c) {
-            const uint64_t dc = c_at(j, c, gi[j]) - c_at(j, ci[j], gi[j]);
-            const float v = at(best_thr, j, c, gi[j]);
-            if (!(v > cur)) continue;
-            const float gain = (v - cur) / ref_thr[j];
-            const float sl = gain / (float)dc;
-            if (sl > st.slope) { st.any = true; st.lvl = c; st.slope = sl; st.gain = gain; st.dc = dc; }
-        }
-        return st;
-    };
-    /* what job v gives when it steps down in GPUs: target segment (-1 = everything), loss, units */
-    struct Give { bool any; int64_t tgt; float loss, slope; uint64_t dg, dc; };
-    auto down_gpu = [&](uint32_t v) {
-        Give gv = {false, -1, 0.0f, 0.0f, 0, 0};
-        if (gi[v] < 0 || (fl_s(v) >= 0 && gi[v] <= fl_s(v))) return gv;
-        const float V = at(curve_thr, v, ci[v], gi[v]);
-        /* down to where the curve's value just below begins: the largest amount with a lower throughput, or, when
-           the job holds more than it uses (same value just below), the smallest amount with the same throughput */
-        const float want = at(curve_thr, v, ci[v], gi[v] - 1);
-        int64_t t = -1;
-        if (want > 0.0f) for (t = 0; at(curve_thr, v, ci[v], t) != want; ++t) {}
-        if (fl_s(v) >= 0 && t < fl_s(v)) t = fl_s(v);
-        gv.any = true; gv.tgt = t;
-        gv.loss = (V - at(curve_thr, v, ci[v], t)) / ref_thr[v];
-        gv.dg = g_at(v, gi[v]) - g_at(v, t);
-        gv.dc = c_at(v, ci[v], gi[v]) - c_at(v, ci[v], t);
-        gv.slope = gv.loss / (float)gv.dg;
-        return gv;
-    };
-    auto down_cpu = [&](uint32_t v) {
-        Give gv = {false, gi[v], 0.0f, 0.0f, 0, 0};
-        const uint32_t lowest = (fl_s(v) >= 0) ? fl_c(v) : 0u;
-        if (gi[v] < 0 || ci[v] == 0 || ci[v] <= lowest) return gv;
-        gv.any = true;
-        gv.loss = (at(best_thr, v, ci[v], gi[v]) - at(best_thr, v, ci[v] - 1, gi[v])) / ref_thr[v];
-        gv.dc = c_at(v, ci[v], gi[v]) - c_at(v, ci[v] - 1, gi[v]);
-        gv.slope = gv.loss / (float)gv.dc;
-        return gv;
-    };
 
     auto schedule_job = [&](uint32_t j) {
         for (int res = 0; res < 2; ++res) {                 /* GPUs, then CPUs */
@@ -1002,6 +1039,219 @@ int ork_reschedule_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *t
     for (uint32_t j : order) schedule_job(j);
     if (n_moves) *n_moves = moves;
     return memory_step(n_jobs, ref_thr, tb, grid, host_mem_gb, best_thr, best_plan, gi, ci, assign, total);
+}
+
+/* Algorithm 1 as printed: ScheduleJob searches the cluster node by node, and on each node the job to shrink is the one
+ * with the lowest slope among the jobs on THAT node (GetLowestSlopeOverMinJob(n, resType)).  State, order, steps,
+ * slopes, permit cases and commit rule are those of ork_reschedule_f32; what is new is where things are:
+ *   - Every job that holds something has parts (node, GPUs), at most one per node, in ascending node order; they come
+ *     in as an earlier placement (prev_off, prev_entries) and must add up to what the job holds.  The CPU levels must
+ *     be CPUs per GPU (cpu_mode 1; otherwise -2): a part of k GPUs at level l holds cpu_levels[l] * k CPUs of its node.
+ *   - A GPU step of job j walks the nodes in order.  On a node it first takes what is free (a GPU only together with
+ *     its CPUs at the step's level), then, while it still lacks GPUs, asks for the job with the lowest slope among
+ *     the other jobs with a part on this node that are above their own floor (lower index on ties); if that job may
+ *     be shrunk (j's slope is higher, or j is below its floor) it steps down to its next useful amount, giving up
+ *     GPUs of its part on this node first and, if its step is larger than that part, the rest from its other parts,
+ *     the last one first (those become free where they are); j takes again.  No such job, or not permitted: next node.
+ *     A step that raises the CPU level of a job that already holds parts (a step to a floor with a higher level)
+ *     needs the additional CPUs of those parts free on their nodes.
+ *   - A CPU step raises the level on every node the job is on: per node, what is free first, then the jobs on that
+ *     node by lowest CPU slope, each giving one level (on all its nodes).
+ *   - A step is committed when all of it was found and (unless j is below its floor) j gains more than the others
+ *     lose; otherwise jobs and nodes are put back as they were and j's search in that resource ends.
+ *   - Memory last, in job order: a tier costs every part its share (tier * k / g, float32) of its node's memory; among
+ *     the tiers every part can pay, the highest throughput, the smallest such tier; none: the job is dropped.
+ * Returns -1 when the state is not a placement on these nodes (parts that do not add up, a node that does not exist
+ * or holds more than it has, parts out of order, CPUs that are not level * GPUs).
+ * PARITY UNPINNED as a reading; pinned by the loop over totals (one node that holds the whole cluster), by hand cases
+ * for every rule above and by invariants on generated rounds. */
+int ork_reschedule_nodes_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb, const ork_grid *grid,
+                             uint32_t n_nodes, uint32_t gpus_per_node, uint32_t cpus_per_node, float mem_per_node_gb,
+                             const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                             const uint8_t *state, const int32_t *cur_seg, const uint32_t *cur_c,
+                             const int32_t *floor_seg, const uint32_t *floor_c, const uint32_t *prev_off,
+                             const ork_place_entry *prev_entries, ork_assign *assign, uint32_t *place_off,
+                             ork_place_entry *entries, double *total, uint32_t *n_moves) {
+    if (grid->cpu_mode != 1) return -2;
+    Loop L(n_jobs, ref_thr, tb, grid, (uint64_t)n_nodes * gpus_per_node, best_thr, curve_thr, state, floor_seg, floor_c);
+    auto cpl = [&](uint32_t lvl) -> uint64_t { return grid->cpu_levels[lvl]; };
+    /* where everything is: a job's parts (node -> GPUs), who is on a node, what a node has free */
+    struct Where {
+        std::vector<std::map<uint32_t, uint64_t>> parts;
+        std::vector<std::set<uint32_t>> on_node;
+        std::vector<uint64_t> freeG, freeC;
+    } W;
+    W.parts.resize(n_jobs); W.on_node.resize(n_nodes);
+    W.freeG.assign(n_nodes, gpus_per_node); W.freeC.assign(n_nodes, cpus_per_node);
+    auto add = [&](uint32_t j, uint32_t n, uint64_t k, uint64_t per_gpu) {          /* j gets k GPUs of node n */
+        W.freeG[n] -= k; W.freeC[n] -= k * per_gpu;
+        W.parts[j][n] += k; W.on_node[n].insert(j);
+    };
+    auto drop = [&](uint32_t v, uint32_t n, uint64_t k, uint64_t per_gpu) {         /* v gives k GPUs of node n back */
+        W.freeG[n] += k; W.freeC[n] += k * per_gpu;
+        if ((W.parts[v][n] -= k) == 0) { W.parts[v].erase(n); W.on_node[n].erase(v); }
+    };
+
+    for (uint32_t j = 0; j < n_jobs; ++j) {
+        if (!L.part(j) || cur_seg[j] < 0 || cur_seg[j] >= L.ns_of(j) || cur_c[j] >= grid->n_cpu) continue;
+        L.gi[j] = cur_seg[j]; L.ci[j] = cur_c[j];
+        if (!prev_off || !prev_entries) return -1;          /* a running job is somewhere */
+        uint64_t sum = 0;
+        int64_t last = -1;
+        for (uint32_t i = prev_off[j]; i < prev_off[j + 1]; ++i) {
+            const ork_place_entry &e = prev_entries[i];
+            if (e.node >= n_nodes || (int64_t)e.node <= last || e.g == 0 || e.c != cpl(L.ci[j]) * e.g) return -1;
+            if (e.g > W.freeG[e.node] || e.c > W.freeC[e.node]) return -1;
+            add(j, e.node, e.g, cpl(L.ci[j]));
+            last = e.node; sum += e.g;
+        }
+        if (sum != L.g_at(j, L.gi[j])) return -1;
+    }
+    uint32_t moves = 0;
+
+    /* the most GPUs of node n that j can take now, up to what it lacks: a GPU comes with per_gpu CPUs */
+    auto take = [&](uint32_t j, uint32_t n, uint64_t per_gpu, uint64_t &lack) {
+        const uint64_t k = std::min(std::min(lack, W.freeG[n]), W.freeC[n] / per_gpu);
+        if (k) { add(j, n, k, per_gpu); lack -= k; }
+    };
+    auto schedule_job = [&](uint32_t j) {
+        for (;;) {                                          /* GPUs */
+            const Loop::Step st = L.up_gpu(j);
+            if (!st.any) break;
+            const bool below_min = L.fl_s(j) >= 0 && L.gi[j] < L.fl_s(j);
+            const Where keepW = W;
+            const std::vector<int64_t> keep_gi(L.gi);
+            const std::vector<uint32_t> keep_ci(L.ci);
+            const uint64_t per_gpu = cpl(st.lvl);
+            uint64_t lack = st.dg;
+            float lost = 0.0f;
+            bool ok = true;
+            if (L.gi[j] >= 0 && st.lvl != L.ci[j]) {        /* its parts go to the step's level: their CPUs must be free */
+                const uint64_t more = per_gpu - cpl(L.ci[j]);
+                for (const auto &pk : W.parts[j]) {
+                    if (W.freeC[pk.first] < more * pk.second) { ok = false; break; }
+                    W.freeC[pk.first] -= more * pk.second;
+                }
+            }
+            for (uint32_t n = 0; n < n_nodes && ok && lack > 0; ++n) {
+                take(j, n, per_gpu, lack);
+                while (lack > 0) {
+                    int64_t pick = -1; Loop::Give best = {false, -1, 0.0f, 0.0f, 0, 0};
+                    for (uint32_t v : W.on_node[n]) {       /* GetLowestSlopeOverMinJob(n, GPU); ascending index */
+                        if (v == j || !L.part(v)) continue;
+                        const Loop::Give gv = L.down_gpu(v);
+                        if (!gv.any) continue;
+                        if (pick < 0 || gv.slope < best.slope) { pick = v; best = gv; }
+                    }
+                    if (pick < 0 || !(below_min || st.slope > best.slope)) break;
+                    const uint64_t per_v = cpl(L.ci[pick]);
+                    uint64_t rest = best.dg;
+                    const uint64_t here = std::min(rest, W.parts[pick][n]);
+                    drop((uint32_t)pick, n, here, per_v); rest -= here;
+                    while (rest > 0) {                      /* the rest from its other parts, the last one first */
+                        auto it = W.parts[pick].end();
+                        do { --it; } while (it->first == n);
+                        const uint32_t m = it->first;
+                        const uint64_t k = std::min(rest, it->second);
+                        drop((uint32_t)pick, m, k, per_v); rest -= k;
+                    }
+                    lost = lost + best.loss;
+                    L.gi[pick] = best.tgt; if (best.tgt < 0) L.ci[pick] = 0;
+                    take(j, n, per_gpu, lack);
+                }
+            }
+            if (ok && lack > 0) ok = false;
+            if (ok && !below_min && !(st.gain > lost)) ok = false;
+            if (!ok) { W = keepW; L.gi = keep_gi; L.ci = keep_ci; break; }
+            L.gi[j] = st.tgt; L.ci[j] = st.lvl;
+            ++moves;
+        }
+        for (;;) {                                          /* CPUs */
+            const Loop::Step st = L.up_cpu(j);
+            if (!st.any) break;
+            const Where keepW = W;
+            const std::vector<uint32_t> keep_ci(L.ci);
+            const uint64_t more = cpl(st.lvl) - cpl(L.ci[j]);
+            float lost = 0.0f;
+            bool ok = true;
+            for (const auto &pk : W.parts[j]) {
+                const uint32_t n = pk.first;
+                const uint64_t need = more * pk.second;
+                while (ok && W.freeC[n] < need) {
+                    int64_t pick = -1; Loop::Give best = {false, -1, 0.0f, 0.0f, 0, 0};
+                    for (uint32_t v : W.on_node[n]) {       /* GetLowestSlopeOverMinJob(n, CPU) */
+                        if (v == j || !L.part(v)) continue;
+                        const Loop::Give gv = L.down_cpu(v);
+                        if (!gv.any) continue;
+                        if (pick < 0 || gv.slope < best.slope) { pick = v; best = gv; }
+                    }
+                    if (pick < 0 || !(st.slope > best.slope)) { ok = false; break; }
+                    const uint64_t less = cpl(L.ci[pick]) - cpl(L.ci[pick] - 1);
+                    for (const auto &qk : W.parts[pick]) W.freeC[qk.first] += less * qk.second;
+                    L.ci[pick] -= 1;
+                    lost = lost + best.loss;
+                }
+                if (!ok) break;
+                W.freeC[n] -= need;
+            }
+            if (ok && !(st.gain > lost)) ok = false;
+            if (!ok) { W = keepW; L.ci = keep_ci; break; }
+            L.ci[j] = st.lvl;
+            ++moves;
+        }
+    };
+
+    std::vector<uint8_t> first(n_jobs, 0);
+    for (uint32_t j = 0; j < n_jobs; ++j)
+        if (L.part(j) && L.fl_s(j) >= 0 && L.gi[j] < L.fl_s(j)) { first[j] = 1; schedule_job(j); }
+    std::vector<uint32_t> order;
+    std::vector<float> sg(n_jobs, 0.0f), sc(n_jobs, 0.0f);
+    for (uint32_t j = 0; j < n_jobs; ++j)
+        if (L.part(j) && !first[j]) { order.push_back(j); sg[j] = L.up_gpu(j).slope; sc[j] = L.up_cpu(j).slope; }
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+        if (sg[a] != sg[b]) return sg[a] > sg[b];
+        return sc[a] > sc[b];
+    });
+    for (uint32_t j : order) schedule_job(j);
+    if (n_moves) *n_moves = moves;
+
+    /* memory, then the records */
+    const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    std::vector<float> freeM(n_nodes, mem_per_node_gb);
+    uint32_t n_entries = 0;
+    double sum = 0.0;
+    for (uint32_t j = 0; j < n_jobs; ++j) {
+        place_off[j] = n_entries;
+        assign[j] = ork_assign{0, 0, 0.0f, ORK_NO_PLAN, 0.0f};
+        if (L.gi[j] < 0) continue;
+        const uint64_t ns = L.ns_of(j);
+        const uint32_t g = (uint32_t)L.g_at(j, L.gi[j]);
+        float bv = 0.0f; int64_t bm = -1;
+        for (uint32_t m = 0; m < grid->n_mem; ++m) {
+            bool fits = true;
+            for (const auto &pk : W.parts[j])
+                if (!((tier_gb(grid, m, g) * (float)pk.second) / (float)g <= freeM[pk.first])) fits = false;
+            if (!fits) continue;
+            const float v = best_thr[rows * tb->seg_off[j] + ((uint64_t)L.ci[j] * grid->n_mem + m) * ns + L.gi[j]];
+            if (v > bv) { bv = v; bm = m; }
+        }
+        if (bm < 0) continue;
+        const float cost = tier_gb(grid, (uint32_t)bm, g);
+        for (const auto &pk : W.parts[j]) {
+            ork_place_entry e;
+            e.node = pk.first; e.g = (uint32_t)pk.second; e.c = (uint32_t)(cpl(L.ci[j]) * pk.second);
+            e.mem_gb = (cost * (float)pk.second) / (float)g;
+            freeM[e.node] = freeM[e.node] - e.mem_gb;
+            entries[n_entries++] = e;
+        }
+        assign[j].g = g; assign[j].c = cpus_of(grid, L.ci[j], g); assign[j].mem_gb = cost;
+        assign[j].plan = best_plan[rows * tb->seg_off[j] + ((uint64_t)L.ci[j] * grid->n_mem + bm) * ns + L.gi[j]];
+        assign[j].thr = bv;
+        sum += (double)bv / (double)ref_thr[j];
+    }
+    place_off[n_jobs] = n_entries;
+    if (total) *total = sum;
+    return 0;
 }
 
 }  // extern "C"

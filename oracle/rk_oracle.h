@@ -197,6 +197,22 @@ int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, co
                     uint32_t cpus_per_node, float mem_per_node_gb, ork_assign *out, uint32_t *place_off,
                     ork_place_entry *entries, uint32_t *status, double *total);
 
+/* Algorithm 1's Schedule with ScheduleJob searching node by node: the job to
+ * shrink on a node is the one with the lowest slope among the jobs on that
+ * node.  State as ork_reschedule_f32 plus the earlier placement of the jobs
+ * that hold something (parts in ascending node order, CPUs = level * GPUs; the
+ * grid's CPU levels must be per GPU).  Results: assign [n_jobs], the new
+ * placement (place_off [n_jobs+1], entries at most the cluster's GPUs).
+ * Returns 0, -1 when the state is no placement on these nodes, -2 when the
+ * CPU levels are not per GPU. */
+int ork_reschedule_nodes_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *table, const ork_grid *grid,
+                             uint32_t n_nodes, uint32_t gpus_per_node, uint32_t cpus_per_node, float mem_per_node_gb,
+                             const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                             const uint8_t *state, const int32_t *cur_seg, const uint32_t *cur_c,
+                             const int32_t *floor_seg, const uint32_t *floor_c, const uint32_t *prev_off,
+                             const ork_place_entry *prev_entries, ork_assign *assign, uint32_t *place_off,
+                             ork_place_entry *entries, double *total, uint32_t *n_moves);
+
 #ifdef __cplusplus
 }
 #endif
