@@ -614,6 +614,64 @@ int32_t rk_schedule_round_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan
                                  uint32_t *place_off, rk_place_entry *entries, uint64_t cap_entries,
                                  uint32_t *status, float *total, rk_place_result *result);
 
+/* Algorithm 1's Schedule with ScheduleJob searching the cluster node by node
+ * (Sec. 5.2, Algorithm 1: "for n in cluster.nodes", GetLowestSlopeOverMinJob(n,
+ * resType), and the paragraph on shrinking).  State, order of the jobs, steps,
+ * slopes, permit cases and commit rule are those of rk_reschedule; here every
+ * job that holds something is somewhere, and the job to shrink on a node is
+ * the one with the lowest slope among the jobs on THAT node.
+ *  - The grid's CPU levels must be CPUs per GPU (cpu_mode 1, otherwise
+ *    RK_ERR_UNSUPPORTED): a part of k GPUs at level l holds cpu_levels[l] * k
+ *    CPUs of its node.
+ *  - prev_off [device] n_jobs + 1 offsets, prev_entries [device]
+ *    n_prev_entries records: where the jobs are now.  The parts of a job that
+ *    holds something (jobs_state) must add up to its GPU count, lie on nodes in
+ *    strictly ascending order and carry c = cpu_levels[cur_c] * g; no node may
+ *    hold more than it has (mem_gb is not read: memory is allocated anew).
+ *    Parts of a job that holds nothing are ignored.  Both NULL: nobody holds
+ *    anything.  A state that is no such placement schedules nothing: all
+ *    records and offsets are zero and stats[4] is 1.
+ *  - A GPU step of job j walks the nodes in order.  On a node it takes what is
+ *    free (a GPU only with its CPUs at the step's level); while it still lacks
+ *    GPUs, the job with the lowest slope among the other jobs on this node
+ *    that are above their own floor (lower index on ties) is shrunk if that is
+ *    permitted (j's slope is higher, or j is below its floor): it steps down
+ *    to its next useful amount, giving up GPUs of its part on this node first
+ *    and, if its step is larger than that part, the rest from its other parts,
+ *    the last one first; j takes again.  Nobody, or not permitted: next node.
+ *    A step to a floor with a higher CPU level needs the additional CPUs of
+ *    the parts j already has free on their nodes.
+ *  - A CPU step raises the level on every node the job is on: per node what is
+ *    free first, then the jobs on that node by lowest CPU slope, each giving
+ *    one level (on all its nodes).
+ *  - A step is committed when all of it was found and (unless j is below its
+ *    floor) j gains more than the others lose; otherwise jobs and nodes are
+ *    put back and j's search in that resource ends.
+ *  - Memory last, in job order: a tier costs every part its share
+ *    (tier * k / g, float32) of its node's memory; among the tiers every part
+ *    can pay, the highest throughput, the smallest such tier; none: the job is
+ *    dropped and has no parts in the result.
+ *   assign     [device] n_jobs records (plan and throughput from best_plan / best_thr)
+ *   place_off  [device] n_jobs + 1 offsets; entries [device] cap_entries records,
+ *              cap_entries >= n_nodes * gpus_per_node; a job's parts in ascending
+ *              node order, c = CPUs, mem_gb = its share of the tier
+ *   total      [device] one float: sum of thr / ref_thr
+ *   stats      [device] five words or NULL: steps committed, jobs that needed
+ *              more than a look, shrinks applied, steps taken back, 1 when the
+ *              state was no placement
+ * The result is what rk_place_plans keeps when it is given as the earlier
+ * placement (every part is what first fit books for these amounts on that
+ * split), which chooses the plan under the bandwidths of the actual split.
+ * Limits: RK_MAX_JOBS_PER_ROUND jobs, n_nodes * gpus_per_node <= 2^20.  One
+ * workgroup runs the loop: the rule is sequential. */
+int32_t rk_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                            const rk_alloc_grid *grid, const rk_nodes *nodes, const float *best_thr,
+                            const uint32_t *best_plan, const float *curve_thr,
+                            const rk_job_state *jobs_state, const uint32_t *prev_off_or_null,
+                            const rk_place_entry *prev_entries_or_null, uint64_t n_prev_entries,
+                            rk_assign *assign, uint32_t *place_off, rk_place_entry *entries,
+                            uint64_t cap_entries, float *total, uint32_t *stats_or_null);
+
 /* ---- measurement helper (no part of the method) --------------------------- */
 
 /* Streams a buffer and nothing else, for the benchmark's roofline context:

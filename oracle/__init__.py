@@ -404,7 +404,9 @@ def reschedule_nodes(ref_thr, table, grid, n_nodes, gpus_per_node, cpus_per_node
     p_off = None if prev is None else np.ascontiguousarray(prev[0], dtype=np.uint32)
     p_ent = None if prev is None else np.ascontiguousarray(prev[1], dtype=PLACE_DTYPE)
     if prev is not None:
-        assert p_off.size == J + 1 and int(p_off[J]) <= p_ent.size and np.all(np.diff(p_off.astype(np.int64)) >= 0)
+        assert p_off.size == J + 1
+        if np.any(np.diff(p_off.astype(np.int64)) < 0) or int(p_off.max()) > p_ent.size:
+            return None                                      # offsets that are no index into the entries
         if p_ent.size == 0:
             p_ent = np.zeros(1, PLACE_DTYPE)
     assign = np.zeros(J, ASSIGN_DTYPE)

@@ -50,6 +50,7 @@ enum {
     SL_RS_F32, SL_RS_U32, SL_RS_U64,                     // the Schedule loop: cached slopes; order, marks and saved states; CPU needs
     SL_EVAL_PARTIAL,                                     // evaluation with best plan: keys of the segments that span tiles
     SL_PLACE_KEEP,                                       // placement: which jobs keep their earlier parts
+    SL_ND_NODES, SL_ND_U32, SL_ND_F32, SL_ND_U64,        // the Schedule loop over nodes: node tables and their copy; per-job words
     SL_COUNT
 };
 static_assert(SL_COUNT <= RK_SCRATCH_SLOTS, "more scratch slots than the context holds");

@@ -1,0 +1,803 @@
+// Algorithm 1's Schedule with ScheduleJob searching the cluster node by node (paper Sec. 5.2, Algorithm 1 and the
+// paragraph on shrinking): on each node the job first takes what is free, then the job with the lowest slope among
+// the jobs ON THAT NODE that are above their own minimum is shrunk while that is permitted, then the next node.
+// State, order of the jobs, steps, slopes, permit cases and commit rule are those of the loop over the cluster's
+// totals (k_reschedule); this kernel adds where things are.
+//
+// Nodes: per node what is free (GPUs, CPUs) and the list of its residents (job, GPUs of that job here); a node of n
+// GPUs has at most n residents, so the lists are a fixed table.  The CPU levels are CPUs per GPU: a part of k GPUs at
+// level l holds cpu_levels[l] * k CPUs of its node.  A job's parts are not stored per job; they are found by looking
+// the job up on every node (all threads, a node or a few per thread) in the few places that need them.
+//
+// One workgroup: the rule is sequential.  Parallel are: the search for a job's next step (a wavefront over its
+// amounts), the walk over the nodes as long as nobody has to be asked (the first wavefront takes 64 nodes at a time:
+// what each offers, a prefix sum that cuts the offers at what the job lacks, and the first node where the job still
+// lacks GPUs and somebody may be shrunk), the parts a shrunk job gives up elsewhere (a suffix sum over the nodes),
+// the look-ahead that passes over jobs with nothing to do, and everything about memory and the records.
+// Before a step touches anything the node tables are copied; a step that is not committed copies them back.
+#include "rk_internal.h"
+#include "rk_model.h"
+#include "rk_loop.h"
+
+namespace {
+
+constexpr int ND_THREADS = 1024;
+constexpr int ND_WAVES = ND_THREADS / 64;
+constexpr uint32_t ND_NONE = 0xFFFFFFFFu;
+constexpr uint32_t ND_PER = (RK_MAX_NODES + ND_THREADS - 1) / ND_THREADS;   // nodes per thread, at most
+constexpr uint32_t ND_MAX_GPUS = 1u << 20;                                   // nodes x GPUs per node
+
+struct NdCurves {
+    const float *ref_thr;
+    TableDev tb;
+    GridDev grid;
+    const float *best_thr;
+    const uint32_t *best_plan;
+    const float *curve_thr;
+};
+struct NdHold { int32_t *gi; uint32_t *ci; };
+
+struct NdArgs {
+    NdCurves X;
+    NdHold st;                       // what every job holds: index of its GPU count (-1 nothing), CPU level
+    unsigned long long G;            // GPUs of the cluster
+    uint32_t n_jobs, n_nodes, gpn, cpn;
+    float mem_gb;                    // host memory of a node
+    const uint8_t *state;            // may be null
+    const int32_t *cur_seg;
+    const uint32_t *cur_c;
+    const int32_t *floor_seg;        // may be null
+    const uint32_t *floor_c;         // may be null
+    const uint32_t *prev_off;        // may be null (then nobody may hold anything)
+    const rk_place_entry *prev_entries;
+    uint64_t n_prev;                 // records in prev_entries
+    // nodes: one block of words [free_g | free_c | cnt | res_job | res_k], and its copy
+    uint32_t *free_g, *free_c, *cnt, *res_job, *res_k;
+    uint32_t *keep_nodes;
+    uint32_t nodes_words;
+    // per job: cached slopes (see rk_loop.h), the order, what a step touched
+    float *ds_g, *ds_c, *ug, *uc, *sg, *sc, *keep_ds;
+    uint32_t *udg, *touched, *stamp, *first, *keep_ci, *np, *tmp_off, *tier;
+    int32_t *keep_gi;
+    unsigned long long *udc_g, *udc_c;
+    uint32_t *plist;                 // parts of one job: (node, GPUs) pairs, ascending node
+    uint32_t *tmp_parts;             // parts of all jobs, grouped by job, in no order
+    rk_assign *assign;
+    uint32_t *place_off;
+    rk_place_entry *entries;
+    float *total;
+    uint32_t *stats;                 // may be null
+};
+
+__device__ __forceinline__ uint32_t nd_cpl(const NdArgs &A, uint32_t lvl) { return A.X.grid.cpu_levels[lvl]; }
+
+// where job `job` is in node n's list, -1: not there
+__device__ __forceinline__ int nd_find(const NdArgs &A, uint32_t n, uint32_t job) {
+    const uint32_t c = A.cnt[n];
+    const uint32_t *rj = A.res_job + (size_t)n * A.gpn;
+    for (uint32_t i = 0; i < c; ++i)
+        if (rj[i] == job) return (int)i;
+    return -1;
+}
+__device__ __forceinline__ uint32_t nd_part(const NdArgs &A, uint32_t n, uint32_t job) {
+    const int i = nd_find(A, n, job);
+    return i < 0 ? 0u : A.res_k[(size_t)n * A.gpn + (uint32_t)i];
+}
+// job takes k free GPUs of node n, each with per_gpu CPUs (the caller has checked that they are free)
+__device__ __forceinline__ void nd_add(const NdArgs &A, uint32_t n, uint32_t job, uint32_t k, uint32_t per_gpu) {
+    A.free_g[n] -= k; A.free_c[n] -= k * per_gpu;
+    const size_t base = (size_t)n * A.gpn;
+    const int i = nd_find(A, n, job);
+    if (i >= 0) { A.res_k[base + (uint32_t)i] += k; return; }
+    const uint32_t c = A.cnt[n];
+    if (c < A.gpn) { A.res_job[base + c] = job; A.res_k[base + c] = k; A.cnt[n] = c + 1u; }   // (always: a resident holds a GPU)
+}
+// job gives k GPUs of node n back, each with per_gpu CPUs
+__device__ __forceinline__ void nd_drop(const NdArgs &A, uint32_t n, uint32_t job, uint32_t k, uint32_t per_gpu) {
+    const int i = nd_find(A, n, job);
+    if (i < 0) return;
+    const size_t base = (size_t)n * A.gpn;
+    A.free_g[n] += k; A.free_c[n] += k * per_gpu;
+    const uint32_t left = A.res_k[base + (uint32_t)i] - k;
+    if (left) { A.res_k[base + (uint32_t)i] = left; return; }
+    const uint32_t c = A.cnt[n] - 1u;
+    A.res_job[base + (uint32_t)i] = A.res_job[base + c]; A.res_k[base + (uint32_t)i] = A.res_k[base + c];
+    A.cnt[n] = c;
+}
+// GetLowestSlopeOverMinJob(n, resType): lowest cached slope among the residents of n other than j (infinite: gives
+// nothing); lower job index among equal slopes; who = ND_NONE when nobody can give
+__device__ __forceinline__ float nd_lowest_on(const NdArgs &A, uint32_t n, uint32_t j, const float *ds, uint32_t &who) {
+    const float INF = __int_as_float(0x7F800000);
+    float best = INF;
+    who = ND_NONE;
+    const uint32_t c = A.cnt[n];
+    const uint32_t *rj = A.res_job + (size_t)n * A.gpn;
+    for (uint32_t i = 0; i < c; ++i) {
+        const uint32_t v = rj[i];
+        if (v == j) continue;
+        const float s = ds[v];
+        if (s < best || (s == best && s < INF && v < who)) { best = s; who = v; }
+    }
+    return best;
+}
+
+__global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
+    __shared__ RsStep sh_step;
+    __shared__ float sh_lost, sh_wmin[ND_WAVES], sh_wc[ND_WAVES];
+    __shared__ uint32_t sh_widx[ND_WAVES], sh_scan[ND_WAVES];
+    __shared__ uint32_t sh_lack, sh_ok, sh_go, sh_touched, sh_epoch, sh_moves, sh_full, sh_shrinks, sh_undone;
+    __shared__ uint32_t sh_vnode, sh_next, sh_v, sh_rest, sh_per_v, sh_flag, sh_np, sh_bad, sh_fit;
+    __shared__ unsigned long long sh_take[RK_MAX_CPU_LEVELS], sh_free_c;
+    __shared__ RsMin sh_min[2], sh_wm[2][ND_WAVES];
+    __shared__ double sh_sum[ND_WAVES];
+    __shared__ float sh_mem[RK_MAX_NODES];                  // memory of the nodes: sums of wishes, then what is left
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t J = A.n_jobs, N = A.n_nodes;
+    const float INF = __int_as_float(0x7F800000);
+    const uint32_t per_thread = (N + ND_THREADS - 1) / ND_THREADS;          // <= ND_PER
+
+    // exclusive prefix sum over the threads of the workgroup (thread order); all threads call it
+    auto block_scan = [&](uint32_t val, uint32_t &all) {
+        uint32_t inc = val;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t o = __shfl_up(inc, off, 64);
+            if ((int)lane >= off) inc += o;
+        }
+        if (lane == 63) sh_scan[wave] = inc;
+        __syncthreads();
+        uint32_t base = 0;
+        all = 0;
+        for (uint32_t w = 0; w < ND_WAVES; ++w) { if (w < wave) base += sh_scan[w]; all += sh_scan[w]; }
+        __syncthreads();
+        return base + inc - val;
+    };
+
+    // ---- the state the jobs are in
+    if (tid == 0) { sh_bad = 0u; sh_epoch = 0u; sh_moves = 0u; sh_full = 0u; sh_shrinks = 0u; sh_undone = 0u; }
+    for (uint32_t n = tid; n < N; n += ND_THREADS) { A.free_g[n] = A.gpn; A.free_c[n] = A.cpn; A.cnt[n] = 0u; }
+    for (uint32_t j = tid; j < J; j += ND_THREADS) {
+        int32_t gi = -1;
+        uint32_t ci = 0;
+        if (rs_part(A, j) && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < rs_ns(A, j) && A.cur_c[j] < A.X.grid.n_cpu) {
+            gi = A.cur_seg[j]; ci = A.cur_c[j];
+        }
+        A.st.gi[j] = gi; A.st.ci[j] = ci;
+        A.stamp[j] = 0u; A.first[j] = 0u;
+    }
+    __syncthreads();
+    // its parts: every job checks its own list; the nodes are booked with atomics and checked afterwards
+    for (uint32_t j = tid; j < J; j += ND_THREADS) {
+        if (A.st.gi[j] < 0) continue;
+        bool good = A.prev_off != nullptr && A.prev_entries != nullptr;
+        if (good) {
+            const uint32_t per_gpu = nd_cpl(A, A.st.ci[j]);
+            const uint32_t a = A.prev_off[j], b = A.prev_off[j + 1];
+            if (a > b || b > A.n_prev) good = false;
+            unsigned long long sum = 0;
+            long long last = -1;
+            for (uint32_t i = a; i < b && good; ++i) {
+                const rk_place_entry e = A.prev_entries[i];
+                if (e.node >= N || (long long)e.node <= last || e.g == 0u || e.g > A.gpn ||
+                    (unsigned long long)e.c != (unsigned long long)per_gpu * e.g) { good = false; break; }
+                last = e.node; sum += e.g;
+            }
+            if (good && sum != rs_g(A, j, A.st.gi[j])) good = false;
+            for (uint32_t i = a; i < b && good; ++i) {
+                const rk_place_entry e = A.prev_entries[i];
+                const uint32_t slot = atomicAdd(&A.cnt[e.node], 1u);
+                if (slot < A.gpn) {
+                    A.res_job[(size_t)e.node * A.gpn + slot] = j; A.res_k[(size_t)e.node * A.gpn + slot] = e.g;
+                }
+                // (wraps below zero when the node holds more than it has; seen by the check below)
+                atomicSub(&A.free_g[e.node], e.g);
+                atomicSub(&A.free_c[e.node], e.c);
+            }
+        }
+        if (!good) atomicOr(&sh_bad, 1u);
+    }
+    __syncthreads();
+    for (uint32_t n = tid; n < N; n += ND_THREADS)
+        if (A.cnt[n] > A.gpn || A.free_g[n] > A.gpn || A.free_c[n] > A.cpn) atomicOr(&sh_bad, 1u);
+    __syncthreads();
+    if (sh_bad) {                                            // not a placement on these nodes: nothing is scheduled
+        for (uint32_t j = tid; j < J; j += ND_THREADS) {
+            A.assign[j] = rk_assign{0u, 0u, 0.f, RK_NO_PLAN, 0.f};
+            A.place_off[j] = 0u;
+        }
+        if (tid == 0) {
+            A.place_off[J] = 0u; *A.total = 0.f;
+            if (A.stats) { A.stats[0] = 0u; A.stats[1] = 0u; A.stats[2] = 0u; A.stats[3] = 0u; A.stats[4] = 1u; }
+        }
+        return;
+    }
+    for (uint32_t j = tid; j < J; j += ND_THREADS) rs_refresh(A, j);
+    __syncthreads();
+
+    auto keep_nodes = [&]() { for (uint32_t i = tid; i < A.nodes_words; i += ND_THREADS) A.keep_nodes[i] = A.free_g[i]; };
+    auto restore_nodes = [&]() { for (uint32_t i = tid; i < A.nodes_words; i += ND_THREADS) A.free_g[i] = A.keep_nodes[i]; };
+    // first thread: remember job v as it is before this step changes it
+    auto remember = [&](uint32_t v) {
+        if (A.stamp[v] == sh_epoch) return;
+        A.stamp[v] = sh_epoch;
+        A.keep_gi[v] = A.st.gi[v]; A.keep_ci[v] = A.st.ci[v];
+        A.keep_ds[2 * v] = A.ds_g[v]; A.keep_ds[2 * v + 1] = A.ds_c[v];
+        A.touched[sh_touched++] = v;
+    };
+    auto put_jobs_back = [&]() {
+        for (uint32_t i = 0; i < sh_touched; ++i) {
+            const uint32_t v = A.touched[i];
+            A.st.gi[v] = A.keep_gi[v]; A.st.ci[v] = A.keep_ci[v];
+            A.ds_g[v] = A.keep_ds[2 * v]; A.ds_c[v] = A.keep_ds[2 * v + 1];
+        }
+        sh_undone += sh_touched ? 1u : 0u;
+    };
+
+    // ScheduleJob(j); the same code path for all threads
+    auto schedule_job = [&](uint32_t j) {
+        for (;;) {                                           // ---- GPUs
+            if (wave == 0) {
+                const RsStep up = rs_up_gpu(A, j, lane, 64);
+                if (lane == 0) {
+                    sh_step = up;
+                    sh_lack = (uint32_t)up.dg; sh_lost = 0.f; sh_ok = 1u; sh_touched = 0u; sh_epoch += 1u;
+                }
+            }
+            __syncthreads();
+            const RsStep st = sh_step;
+            if (!st.any) { __syncthreads(); break; }
+            const bool below_min = rs_fl_s(A, j) >= 0 && A.st.gi[j] < rs_fl_s(A, j);
+            const uint32_t per_gpu = nd_cpl(A, st.lvl);
+            keep_nodes();
+            __syncthreads();
+            if (A.st.gi[j] >= 0 && st.lvl != A.st.ci[j]) {   // its parts go to the step's level: their CPUs must be free
+                const uint32_t more = per_gpu - nd_cpl(A, A.st.ci[j]);
+                for (uint32_t n = tid; n < N; n += ND_THREADS) {
+                    const uint32_t k = nd_part(A, n, j);
+                    if (!k) continue;
+                    if (A.free_c[n] < more * k) atomicAnd(&sh_ok, 0u);
+                    else A.free_c[n] -= more * k;
+                }
+                __syncthreads();
+            }
+            uint32_t n0 = 0;
+            bool walking = sh_ok && sh_lack > 0;             // (read here, written again only behind the next barrier)
+            __syncthreads();
+            while (walking && n0 < N) {                      // the walk over the nodes, 64 at a time
+                if (wave == 0) {
+                    const uint32_t lack = sh_lack;
+                    const uint32_t n = n0 + lane;
+                    const bool in = n < N;
+                    uint32_t offer = 0;
+                    bool ask = false;                        // somebody here may be shrunk
+                    if (in) {
+                        const uint32_t by_cpu = A.free_c[n] / per_gpu;
+                        offer = A.free_g[n] < by_cpu ? A.free_g[n] : by_cpu;
+                        uint32_t who;
+                        const float low = nd_lowest_on(A, n, j, A.ds_g, who);
+                        ask = who != ND_NONE && (below_min || st.slope > low);
+                    }
+                    uint32_t cum = offer;
+#pragma unroll
+                    for (int off = 1; off < 64; off <<= 1) {
+                        const uint32_t o = __shfl_up(cum, off, 64);
+                        if ((int)lane >= off) cum += o;
+                    }
+                    const unsigned long long done_at = __ballot(in && cum >= lack);
+                    const unsigned long long ask_at = __ballot(in && ask && cum < lack);
+                    const int done_l = done_at ? __ffsll((long long)done_at) - 1 : 64;
+                    const int ask_l = ask_at ? __ffsll((long long)ask_at) - 1 : 64;
+                    const int last = done_l < ask_l ? done_l : ask_l;
+                    if (in && (int)lane <= last && offer) {
+                        const uint32_t before = cum - offer;                 // < lack for these lanes
+                        const uint32_t t = offer < lack - before ? offer : lack - before;
+                        nd_add(A, n, j, t, per_gpu);
+                    }
+                    const uint32_t upto = __shfl(cum, last < 64 ? last : 63, 64);
+                    if (lane == 0) {
+                        sh_lack = lack - (upto < lack ? upto : lack);
+                        sh_vnode = ask_l < done_l ? n0 + (uint32_t)ask_l : ND_NONE;
+                        sh_next = ask_l < done_l ? n0 + (uint32_t)ask_l + 1u : n0 + 64u;
+                    }
+                }
+                __syncthreads();
+                const uint32_t f = sh_vnode;
+                if (f != ND_NONE) {                          // node f: the job still lacks GPUs and somebody may be shrunk
+                    for (;;) {
+                        if (tid == 0) {
+                            uint32_t who;
+                            const float low = nd_lowest_on(A, f, j, A.ds_g, who);
+                            if (who == ND_NONE || !(below_min || st.slope > low)) {
+                                sh_v = ND_NONE;
+                            } else {
+                                const RsGive gv = rs_down_gpu(A, who);
+                                remember(who);
+                                const uint32_t per_v = nd_cpl(A, A.st.ci[who]);
+                                const uint32_t here_has = nd_part(A, f, who);
+                                const uint32_t here = (uint32_t)gv.dg < here_has ? (uint32_t)gv.dg : here_has;
+                                nd_drop(A, f, who, here, per_v);
+                                sh_rest = (uint32_t)gv.dg - here; sh_per_v = per_v; sh_v = who;
+                                sh_lost = sh_lost + gv.loss;
+                                A.st.gi[who] = gv.tgt; if (gv.tgt < 0) A.st.ci[who] = 0u;
+                                rs_refresh_give(A, who);
+                                sh_shrinks += 1u;
+                            }
+                        }
+                        __syncthreads();
+                        const uint32_t v = sh_v, rest = sh_rest, per_v = sh_per_v;
+                        if (v == ND_NONE) break;
+                        if (rest > 0) {                      // the rest from its other parts, the last one first
+                            uint32_t k[ND_PER], local = 0;
+#pragma unroll
+                            for (uint32_t i = 0; i < ND_PER; ++i) {
+                                const uint32_t r = tid * per_thread + i;     // position from the last node
+                                k[i] = (i < per_thread && r < N && N - 1u - r != f) ? nd_part(A, N - 1u - r, v) : 0u;
+                                local += k[i];
+                            }
+                            uint32_t all;
+                            uint32_t running = block_scan(local, all);
+#pragma unroll
+                            for (uint32_t i = 0; i < ND_PER; ++i) {
+                                if (k[i] && rest > running) {
+                                    const uint32_t give = k[i] < rest - running ? k[i] : rest - running;
+                                    nd_drop(A, N - 1u - (tid * per_thread + i), v, give, per_v);
+                                }
+                                running += k[i];
+                            }
+                            __syncthreads();
+                        }
+                        if (tid == 0) {
+                            const uint32_t by_cpu = A.free_c[f] / per_gpu;
+                            const uint32_t offer = A.free_g[f] < by_cpu ? A.free_g[f] : by_cpu;
+                            const uint32_t t = offer < sh_lack ? offer : sh_lack;
+                            if (t) nd_add(A, f, j, t, per_gpu);
+                            sh_lack -= t;
+                        }
+                        __syncthreads();
+                        if (sh_lack == 0) break;
+                    }
+                }
+                n0 = sh_next;
+                walking = sh_lack > 0;
+                __syncthreads();
+            }
+            if (tid == 0) {
+                bool ok = sh_ok != 0u && sh_lack == 0u;
+                if (ok && !below_min && !(st.gain > sh_lost)) ok = false;
+                if (!ok) put_jobs_back();
+                else { A.st.gi[j] = st.tgt; A.st.ci[j] = st.lvl; sh_moves += 1u; }
+                sh_go = ok ? 1u : 0u;
+            }
+            __syncthreads();
+            const uint32_t go = sh_go;
+            if (go) {
+                const uint32_t n_changed = sh_touched + 1u;
+                for (uint32_t i = tid; i < n_changed; i += ND_THREADS) rs_refresh(A, i < sh_touched ? A.touched[i] : j);
+            } else {
+                restore_nodes();
+            }
+            __syncthreads();
+            if (!go) break;
+        }
+        for (;;) {                                           // ---- CPUs: on every node the job is on
+            if (wave == 0) {
+                const RsStep up = rs_up_cpu(A, j, lane, 64);
+                if (lane == 0) { sh_step = up; sh_lost = 0.f; sh_ok = 1u; sh_touched = 0u; sh_epoch += 1u; }
+            }
+            __syncthreads();
+            const RsStep st = sh_step;
+            if (!st.any) { __syncthreads(); break; }
+            const uint32_t more = nd_cpl(A, st.lvl) - nd_cpl(A, A.st.ci[j]);
+            keep_nodes();
+            {                                                // its parts, in node order
+                uint32_t k[ND_PER], local = 0;
+#pragma unroll
+                for (uint32_t i = 0; i < ND_PER; ++i) {
+                    const uint32_t n = tid * per_thread + i;
+                    k[i] = (i < per_thread && n < N) ? nd_part(A, n, j) : 0u;
+                    local += k[i] ? 1u : 0u;
+                }
+                uint32_t all;
+                uint32_t at = block_scan(local, all);
+#pragma unroll
+                for (uint32_t i = 0; i < ND_PER; ++i)
+                    if (k[i]) { A.plist[2 * at] = tid * per_thread + i; A.plist[2 * at + 1] = k[i]; ++at; }
+                if (tid == 0) sh_np = all;
+                __syncthreads();
+            }
+            const uint32_t np = sh_np;
+            bool found = true;                               // every part so far has its CPUs
+            for (uint32_t p = 0; p < np && found; ++p) {
+                const uint32_t n = A.plist[2 * p], need = more * A.plist[2 * p + 1];
+                for (;;) {
+                    if (tid == 0) {
+                        if (A.free_c[n] >= need) { A.free_c[n] -= need; sh_flag = 0u; }
+                        else {
+                            uint32_t who;
+                            const float low = nd_lowest_on(A, n, j, A.ds_c, who);
+                            if (who == ND_NONE || !(st.slope > low)) { sh_ok = 0u; sh_flag = 0u; }
+                            else {
+                                const RsGive gv = rs_down_cpu(A, who);
+                                remember(who);
+                                sh_per_v = nd_cpl(A, A.st.ci[who]) - nd_cpl(A, A.st.ci[who] - 1u);
+                                sh_v = who; sh_flag = 1u;
+                                sh_lost = sh_lost + gv.loss;
+                                A.st.ci[who] -= 1u;
+                                rs_refresh_give(A, who);
+                                sh_shrinks += 1u;
+                            }
+                        }
+                    }
+                    __syncthreads();
+                    const uint32_t flag = sh_flag, v = sh_v, less = sh_per_v;
+                    found = sh_ok != 0u;
+                    if (flag)                                 // the job that gives a level gives it on all its nodes
+                        for (uint32_t m = tid; m < N; m += ND_THREADS) A.free_c[m] += less * nd_part(A, m, v);
+                    __syncthreads();
+                    if (!flag) break;
+                }
+            }
+            if (tid == 0) {
+                bool ok = sh_ok != 0u;
+                if (ok && !(st.gain > sh_lost)) ok = false;
+                if (!ok) put_jobs_back();
+                else { A.st.ci[j] = st.lvl; sh_moves += 1u; }
+                sh_go = ok ? 1u : 0u;
+            }
+            __syncthreads();
+            const uint32_t go = sh_go;
+            if (go) {
+                const uint32_t n_changed = sh_touched + 1u;
+                for (uint32_t i = tid; i < n_changed; i += ND_THREADS) rs_refresh(A, i < sh_touched ? A.touched[i] : j);
+            } else {
+                restore_nodes();
+            }
+            __syncthreads();
+            if (!go) break;
+        }
+    };
+
+    // ---- privileged jobs (below their floor), in job order
+    for (uint32_t j = tid; j < J; j += ND_THREADS) {
+        const int32_t fl = rs_fl_s(A, j);
+        A.first[j] = (rs_part(A, j) && fl >= 0 && A.st.gi[j] < fl) ? 1u : 0u;
+    }
+    __syncthreads();
+    for (uint32_t base = 0; base < J; base += ND_THREADS) {  // their list: 1,024 jobs at a time (tmp_off serves as the list)
+        const uint32_t j = base + tid;
+        const bool is = j < J && A.first[j] != 0u;
+        uint32_t all;
+        const uint32_t at = block_scan(is ? 1u : 0u, all);
+        if (is) A.tmp_off[at] = j;
+        __syncthreads();
+        for (uint32_t k = 0; k < all; ++k) schedule_job(A.tmp_off[k]);
+        __syncthreads();
+    }
+    // ---- the others: their order is fixed once, by GPU slope, then CPU slope (both descending), then index
+    for (uint32_t j = tid; j < J; j += ND_THREADS) {
+        const bool in = rs_part(A, j) && !A.first[j];
+        A.sg[j] = in ? rs_up_gpu(A, j, 0, 1).slope : -1.f;   // -1: not in the list
+        A.sc[j] = in ? rs_up_cpu(A, j, 0, 1).slope : -1.f;
+    }
+    __syncthreads();
+    // Most jobs find nothing to do when their turn comes, and whether that is so follows from values that change
+    // only when a step is committed.  A GPU step does nothing when there is none, or when what the nodes can give
+    // a job at its level (GPUs with their CPUs) is less than the step needs and no job anywhere has a slope below
+    // this job's (then nobody on any node may be shrunk).  A CPU step does nothing when there is none, or when no
+    // job anywhere has a lower CPU slope and all free CPUs together are fewer than the step needs.  Passing over
+    // such a job changes nothing, so the jobs are not sorted: all threads look for the first job in the order, after
+    // the one served last, that is not of that kind; it is served in full and the search starts again.
+    auto comes_before = [&](float ga, float ca, uint32_t a, float gb, float cb, uint32_t b) {
+        return ga > gb || (ga == gb && (ca > cb || (ca == cb && a < b)));
+    };
+    float last_g = INF, last_c = INF;
+    uint32_t last_j = 0u;
+    for (;;) {
+        __syncthreads();
+        if (tid < RK_MAX_CPU_LEVELS) sh_take[tid] = 0ull;
+        if (tid == 0) sh_free_c = 0ull;
+        for (uint32_t res = 0; res < 2; ++res) {
+            const float *ds = res == 0 ? A.ds_g : A.ds_c;
+            RsMin m = {INF, INF, ND_NONE};
+            for (uint32_t v = tid; v < J; v += ND_THREADS) {
+                const RsMin one = {ds[v], INF, v};
+                m = rs_min_merge(m, one);
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                RsMin o;
+                o.m1 = __shfl_xor(m.m1, off, 64); o.m2 = __shfl_xor(m.m2, off, 64); o.i1 = __shfl_xor(m.i1, off, 64);
+                m = rs_min_merge(m, o);
+            }
+            if (lane == 0) sh_wm[res][wave] = m;
+        }
+        __syncthreads();
+        if (tid < 2) {
+            RsMin m = sh_wm[tid][0];
+            for (uint32_t w = 1; w < ND_WAVES; ++w) m = rs_min_merge(m, sh_wm[tid][w]);
+            sh_min[tid] = m;
+        }
+        {                                                    // what the nodes can give at every CPU level
+            unsigned long long fc = 0;
+            for (uint32_t n = tid; n < N; n += ND_THREADS) fc += A.free_c[n];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) fc += __shfl_xor(fc, off, 64);
+            if (lane == 0 && fc) atomicAdd(&sh_free_c, fc);
+            for (uint32_t l = 0; l < A.X.grid.n_cpu; ++l) {
+                const uint32_t per_gpu = nd_cpl(A, l);
+                unsigned long long t = 0;
+                for (uint32_t n = tid; n < N; n += ND_THREADS) {
+                    const uint32_t by_cpu = A.free_c[n] / per_gpu;
+                    t += A.free_g[n] < by_cpu ? A.free_g[n] : by_cpu;
+                }
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off, 64);
+                if (lane == 0 && t) atomicAdd(&sh_take[l], t);
+            }
+        }
+        __syncthreads();
+        const RsMin mg = sh_min[0], mc = sh_min[1];
+        const unsigned long long free_c = sh_free_c;
+        float best_g = -1.f, best_c = -1.f;
+        uint32_t best_j = ND_NONE;
+        for (uint32_t j = tid; j < J; j += ND_THREADS) {
+            const float kg = A.sg[j], kc = A.sc[j];
+            if (kg < 0.f || !comes_before(last_g, last_c, last_j, kg, kc, j)) continue;
+            const float lowest_g = j == mg.i1 ? mg.m2 : mg.m1, lowest_c = j == mc.i1 ? mc.m2 : mc.m1;
+            const float ug = A.ug[j], uc = A.uc[j];
+            const bool gpu_idle = !(ug > 0.f) || (sh_take[A.st.ci[j]] < A.udg[j] && !(ug > lowest_g));
+            const bool cpu_idle = !(uc > 0.f) || (free_c < A.udc_c[j] && !(uc > lowest_c));
+            if (gpu_idle && cpu_idle) continue;
+            if (best_j == ND_NONE || comes_before(kg, kc, j, best_g, best_c, best_j)) { best_g = kg; best_c = kc; best_j = j; }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float og = __shfl_xor(best_g, off, 64), oc = __shfl_xor(best_c, off, 64);
+            const uint32_t oj = __shfl_xor(best_j, off, 64);
+            if (oj != ND_NONE && (best_j == ND_NONE || comes_before(og, oc, oj, best_g, best_c, best_j))) {
+                best_g = og; best_c = oc; best_j = oj;
+            }
+        }
+        if (lane == 0) { sh_wmin[wave] = best_g; sh_wc[wave] = best_c; sh_widx[wave] = best_j; }
+        __syncthreads();
+        best_g = sh_wmin[0]; best_c = sh_wc[0]; best_j = sh_widx[0];
+        for (uint32_t w = 1; w < ND_WAVES; ++w) {
+            const uint32_t oj = sh_widx[w];
+            if (oj != ND_NONE && (best_j == ND_NONE || comes_before(sh_wmin[w], sh_wc[w], oj, best_g, best_c, best_j))) {
+                best_g = sh_wmin[w]; best_c = sh_wc[w]; best_j = oj;
+            }
+        }
+        __syncthreads();
+        if (best_j == ND_NONE) break;
+        if (tid == 0) sh_full += 1u;
+        schedule_job(best_j);
+        last_g = best_g; last_c = best_c; last_j = best_j;
+    }
+    __syncthreads();
+
+    // ---- memory, then the records.  Parts of all jobs, grouped by job (in no order yet)
+    for (uint32_t j = tid; j < J; j += ND_THREADS) A.np[j] = 0u;
+    __syncthreads();
+    for (uint32_t n = tid; n < N; n += ND_THREADS)
+        for (uint32_t i = 0; i < A.cnt[n]; ++i) atomicAdd(&A.np[A.res_job[(size_t)n * A.gpn + i]], 1u);
+    __syncthreads();
+    const uint32_t jobs_per_thread = (J + ND_THREADS - 1) / ND_THREADS;
+    auto scan_jobs = [&](const uint32_t *count, bool only_kept, uint32_t *off) {       // off[J] = the sum
+        uint32_t local = 0;
+        for (uint32_t i = 0; i < jobs_per_thread; ++i) {
+            const uint32_t j = tid * jobs_per_thread + i;
+            if (j < J && (!only_kept || A.tier[j] != ND_NONE)) local += count[j];
+        }
+        uint32_t all;
+        uint32_t at = block_scan(local, all);
+        for (uint32_t i = 0; i < jobs_per_thread; ++i) {
+            const uint32_t j = tid * jobs_per_thread + i;
+            if (j >= J) break;
+            off[j] = at;
+            if (!only_kept || A.tier[j] != ND_NONE) at += count[j];
+        }
+        if (tid == 0) off[J] = all;
+    };
+    scan_jobs(A.np, false, A.tmp_off);
+    for (uint32_t j = tid; j < J; j += ND_THREADS) A.stamp[j] = 0u;          // (cursor of the job's parts)
+    __syncthreads();
+    for (uint32_t n = tid; n < N; n += ND_THREADS)
+        for (uint32_t i = 0; i < A.cnt[n]; ++i) {
+            const uint32_t job = A.res_job[(size_t)n * A.gpn + i];
+            const uint32_t at = A.tmp_off[job] + atomicAdd(&A.stamp[job], 1u);
+            A.tmp_parts[2 * (size_t)at] = n; A.tmp_parts[2 * (size_t)at + 1] = A.res_k[(size_t)n * A.gpn + i];
+        }
+    for (uint32_t n = tid; n < N; n += ND_THREADS) sh_mem[n] = 0.f;
+    if (tid == 0) sh_fit = A.gpn <= 4096u ? 1u : 0u;
+    __syncthreads();
+    const uint64_t rows = (uint64_t)A.X.grid.n_cpu * A.X.grid.n_mem;
+    auto tier_cost = [&](uint32_t m, uint32_t g) {
+        float v = A.X.grid.mem_levels_gb[m];
+        if (A.X.grid.mem_mode) v = v * (float)g;
+        return v;
+    };
+    auto value_at = [&](uint32_t j, uint32_t m) {
+        return A.X.best_thr[rows * A.X.tb.seg_off[j] + ((uint64_t)A.st.ci[j] * A.X.grid.n_mem + m) * rs_ns(A, j) + (uint32_t)A.st.gi[j]];
+    };
+    // the tier every job would like (highest throughput, smallest such tier), and what that asks of the nodes
+    for (uint32_t j = tid; j < J; j += ND_THREADS) {
+        uint32_t bm = ND_NONE;
+        if (A.st.gi[j] >= 0) {
+            float bv = 0.f;
+            for (uint32_t m = 0; m < A.X.grid.n_mem; ++m) {
+                const float v = value_at(j, m);
+                if (v > bv) { bv = v; bm = m; }
+            }
+            if (bm != ND_NONE) {
+                const uint32_t g = (uint32_t)rs_g(A, j, A.st.gi[j]);
+                const float cost = tier_cost(bm, g);
+                for (uint32_t i = 0; i < A.np[j]; ++i) {
+                    const size_t at = 2 * (size_t)(A.tmp_off[j] + i);
+                    atomicAdd(&sh_mem[A.tmp_parts[at]], (cost * (float)A.tmp_parts[at + 1]) / (float)g);
+                }
+            }
+        }
+        A.tier[j] = bm;
+    }
+    __syncthreads();
+    for (uint32_t n = tid; n < N; n += ND_THREADS)
+        if (!(sh_mem[n] <= A.mem_gb * 0.999f)) atomicAnd(&sh_fit, 0u);
+    __syncthreads();
+    if (!sh_fit) {                                           // some node's memory can bind: job by job, in order
+        for (uint32_t n = tid; n < N; n += ND_THREADS) sh_mem[n] = A.mem_gb;
+        __syncthreads();
+        if (wave == 0) {
+            for (uint32_t j = 0; j < J; ++j) {
+                if (A.st.gi[j] < 0) continue;
+                const uint32_t g = (uint32_t)rs_g(A, j, A.st.gi[j]);
+                const uint32_t a = A.tmp_off[j], P = A.np[j];
+                float bv = 0.f;
+                uint32_t bm = ND_NONE;
+                for (uint32_t m = 0; m < A.X.grid.n_mem; ++m) {
+                    const float cost = tier_cost(m, g);
+                    bool bad = false;
+                    for (uint32_t i = lane; i < P; i += 64u) {
+                        const size_t at = 2 * (size_t)(a + i);
+                        if (!((cost * (float)A.tmp_parts[at + 1]) / (float)g <= sh_mem[A.tmp_parts[at]])) bad = true;
+                    }
+                    if (__ballot(bad)) continue;
+                    const float v = value_at(j, m);
+                    if (v > bv) { bv = v; bm = m; }
+                }
+                if (bm != ND_NONE) {
+                    const float cost = tier_cost(bm, g);
+                    for (uint32_t i = lane; i < P; i += 64u) {
+                        const size_t at = 2 * (size_t)(a + i);
+                        sh_mem[A.tmp_parts[at]] = sh_mem[A.tmp_parts[at]] - (cost * (float)A.tmp_parts[at + 1]) / (float)g;
+                    }
+                }
+                if (lane == 0) A.tier[j] = bm;
+            }
+        }
+        __syncthreads();
+    }
+    // the records: a job's parts in node order
+    scan_jobs(A.np, true, A.place_off);
+    if (tid == 0) sh_np = 0u;                                // jobs with many parts (their list: `touched`)
+    __syncthreads();
+    double sum = 0.0;
+    for (uint32_t j = tid; j < J; j += ND_THREADS) {
+        rk_assign out = {0u, 0u, 0.f, RK_NO_PLAN, 0.f};
+        const uint32_t m = A.tier[j];
+        if (m != ND_NONE) {
+            const uint32_t g = (uint32_t)rs_g(A, j, A.st.gi[j]);
+            const uint32_t per_gpu = nd_cpl(A, A.st.ci[j]);
+            const float cost = tier_cost(m, g);
+            out.g = g; out.c = per_gpu * g; out.mem_gb = cost;
+            out.plan = A.X.best_plan[rows * A.X.tb.seg_off[j] + ((uint64_t)A.st.ci[j] * A.X.grid.n_mem + m) * rs_ns(A, j) + (uint32_t)A.st.gi[j]];
+            out.thr = value_at(j, m);
+            sum += (double)out.thr / (double)A.X.ref_thr[j];
+            const uint32_t P = A.np[j], a = A.tmp_off[j], to = A.place_off[j];
+            if (P <= 8u) {                                   // few parts: this thread ranks them
+                for (uint32_t i = 0; i < P; ++i) {
+                    const uint32_t node = A.tmp_parts[2 * (size_t)(a + i)], k = A.tmp_parts[2 * (size_t)(a + i) + 1];
+                    uint32_t rank = 0;
+                    for (uint32_t q = 0; q < P; ++q) rank += A.tmp_parts[2 * (size_t)(a + q)] < node ? 1u : 0u;
+                    A.entries[to + rank] = rk_place_entry{node, k, per_gpu * k, (cost * (float)k) / (float)g};
+                }
+            } else {
+                A.touched[atomicAdd(&sh_np, 1u)] = j;
+            }
+        }
+        A.assign[j] = out;
+    }
+    __syncthreads();
+    const uint32_t n_wide = sh_np;
+    for (uint32_t w = wave; w < n_wide; w += ND_WAVES) {      // many parts: a wavefront ranks them
+        const uint32_t j = A.touched[w];
+        const uint32_t m = A.tier[j], P = A.np[j];
+        const uint32_t g = (uint32_t)rs_g(A, j, A.st.gi[j]);
+        const uint32_t per_gpu = nd_cpl(A, A.st.ci[j]);
+        const float cost = tier_cost(m, g);
+        const uint32_t a = A.tmp_off[j], to = A.place_off[j];
+        for (uint32_t i = lane; i < P; i += 64u) {
+            const uint32_t node = A.tmp_parts[2 * (size_t)(a + i)], k = A.tmp_parts[2 * (size_t)(a + i) + 1];
+            uint32_t rank = 0;
+            for (uint32_t q = 0; q < P; ++q) rank += A.tmp_parts[2 * (size_t)(a + q)] < node ? 1u : 0u;
+            A.entries[to + rank] = rk_place_entry{node, k, per_gpu * k, (cost * (float)k) / (float)g};
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    if (lane == 0) sh_sum[wave] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        double s = 0.0;
+        for (uint32_t w = 0; w < ND_WAVES; ++w) s += sh_sum[w];
+        *A.total = (float)s;
+        if (A.stats) { A.stats[0] = sh_moves; A.stats[1] = sh_full; A.stats[2] = sh_shrinks; A.stats[3] = sh_undone; A.stats[4] = 0u; }
+    }
+}
+
+}  // namespace
+
+extern "C" int32_t rk_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                                       const rk_alloc_grid *grid, const rk_nodes *nodes, const float *best_thr,
+                                       const uint32_t *best_plan, const float *curve_thr,
+                                       const rk_job_state *jobs_state, const uint32_t *prev_off,
+                                       const rk_place_entry *prev_entries, uint64_t n_prev_entries,
+                                       rk_assign *assign, uint32_t *place_off,
+                                       rk_place_entry *entries, uint64_t cap_entries, float *total, uint32_t *stats) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if ((rc = rk_check_table(ctx, table, 0, table ? table->n_jobs : 0))) return rc;
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    if (!nodes || !total || !jobs_state || !place_off) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    const uint32_t J = table->n_jobs;
+    if (J > 0 && (!ref_thr || !assign || !jobs_state->cur_seg || !jobs_state->cur_c ||
+                  (table->n_segs > 0 && (!best_thr || !best_plan || !curve_thr))))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if ((prev_off == nullptr) != (prev_entries == nullptr))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "the earlier placement needs both its offsets and its entries");
+    if (nodes->n_nodes == 0 || nodes->n_nodes > RK_MAX_NODES || nodes->gpus_per_node == 0 ||
+        nodes->gpus_per_node > 65535u || nodes->cpus_per_node > 65535u || !(nodes->mem_per_node_gb >= 0.f))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "nodes: 1..%u nodes of 1..65535 GPUs, at most 65535 CPUs, memory >= 0", RK_MAX_NODES);
+    if (grid->cpu_mode != 1u)
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "the search over nodes needs CPU levels per GPU (cpu_mode 1)");
+    const uint64_t gpus = (uint64_t)nodes->n_nodes * nodes->gpus_per_node;
+    if (gpus > ND_MAX_GPUS) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "%llu GPUs, the search over nodes takes up to %u", (unsigned long long)gpus, ND_MAX_GPUS);
+    if (table->max_segs_per_job > 32767u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 32767 segments per job");
+    if (J > RK_MAX_JOBS_PER_ROUND)
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "%u jobs, the allocation kernels take up to %u", J, RK_MAX_JOBS_PER_ROUND);
+    if (cap_entries < gpus && J > 0) return rk_fail(ctx, RK_ERR_CAPACITY, "entries: %llu records, %llu may be needed", (unsigned long long)cap_entries, (unsigned long long)gpus);
+    if (J > 0 && !entries) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    const size_t n = J ? J : 1, N = nodes->n_nodes;
+    const size_t nodes_words = 3 * N + 2 * (size_t)gpus;
+    uint32_t *w_nodes, *w_jobs;
+    float *f_jobs;
+    unsigned long long *u64;
+    if ((rc = rk_scratch(ctx, SL_ND_NODES, (2 * nodes_words + 2 * N + 2 * (size_t)gpus) * sizeof(uint32_t), (void **)&w_nodes))) return rc;
+    if ((rc = rk_scratch(ctx, SL_ND_U32, (11 * n + 1) * sizeof(uint32_t), (void **)&w_jobs))) return rc;
+    if ((rc = rk_scratch(ctx, SL_ND_F32, 8 * n * sizeof(float), (void **)&f_jobs))) return rc;
+    if ((rc = rk_scratch(ctx, SL_ND_U64, 2 * n * sizeof(unsigned long long), (void **)&u64))) return rc;
+    NdArgs A;
+    A.X.ref_thr = ref_thr; A.X.tb = table_dev(table); A.X.grid = grid_dev(grid);
+    A.X.best_thr = best_thr; A.X.best_plan = best_plan; A.X.curve_thr = curve_thr;
+    A.G = gpus;
+    A.n_jobs = J; A.n_nodes = nodes->n_nodes; A.gpn = nodes->gpus_per_node; A.cpn = nodes->cpus_per_node;
+    A.mem_gb = nodes->mem_per_node_gb;
+    A.state = jobs_state->state; A.cur_seg = jobs_state->cur_seg; A.cur_c = jobs_state->cur_c;
+    A.floor_seg = jobs_state->floor_seg; A.floor_c = jobs_state->floor_c;
+    A.prev_off = prev_off; A.prev_entries = prev_entries; A.n_prev = n_prev_entries;
+    A.free_g = w_nodes; A.free_c = w_nodes + N; A.cnt = w_nodes + 2 * N; A.res_job = w_nodes + 3 * N;
+    A.res_k = A.res_job + gpus;
+    A.keep_nodes = w_nodes + nodes_words; A.nodes_words = (uint32_t)nodes_words;
+    A.plist = w_nodes + 2 * nodes_words; A.tmp_parts = A.plist + 2 * N;
+    A.st.gi = reinterpret_cast<int32_t *>(w_jobs); A.st.ci = w_jobs + n; A.udg = w_jobs + 2 * n; A.touched = w_jobs + 3 * n;
+    A.stamp = w_jobs + 4 * n; A.first = w_jobs + 5 * n; A.keep_ci = w_jobs + 6 * n;
+    A.keep_gi = reinterpret_cast<int32_t *>(w_jobs + 7 * n); A.np = w_jobs + 8 * n; A.tier = w_jobs + 9 * n;
+    A.tmp_off = w_jobs + 10 * n;                             // n + 1 words
+    A.ds_g = f_jobs; A.ds_c = f_jobs + n; A.ug = f_jobs + 2 * n; A.uc = f_jobs + 3 * n; A.sg = f_jobs + 4 * n;
+    A.sc = f_jobs + 5 * n; A.keep_ds = f_jobs + 6 * n;
+    A.udc_g = u64; A.udc_c = u64 + n;
+    A.assign = assign; A.place_off = place_off; A.entries = entries; A.total = total; A.stats = stats;
+    k_reschedule_nodes<<<1, ND_THREADS, 0, ctx->stream>>>(A);
+    RK_CHECK_LAUNCH(ctx, "k_reschedule_nodes");
+    return RK_OK;
+}

@@ -1,0 +1,199 @@
+"""GPU parity of rk_reschedule_nodes (Algorithm 1's Schedule with ScheduleJob
+searching node by node) against the oracle's ork_reschedule_nodes_f32 on shared
+float32 inputs: records, the new placement part by part, totals and the number
+of committed steps must be identical; a state that is no placement on the
+nodes must be refused by both."""
+import numpy as np
+import pytest
+
+import workloads
+from test_gpu_reschedule import random_round
+from test_oracle_reschedule_nodes import first_fit
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from gpu_harness import DeviceRun
+    return DeviceRun
+
+
+def on_gpu(run, bt, bp, ct, nodes, cur_seg, cur_c, prev, floor_seg, floor_c, state):
+    import torch
+    import paper_2408_08586_amd as rk
+    J = run.wl.n_jobs
+    dev = run.device
+    i32 = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    u8 = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint8)).to(dev)
+    p_off = p_ent = None
+    n_prev = 0
+    if prev is not None:
+        p_off = torch.from_numpy(np.ascontiguousarray(prev[0], dtype=np.uint32).view(np.int32).copy()).to(dev)
+        ent = np.ascontiguousarray(prev[1], dtype=rk.PLACE_DTYPE)
+        n_prev = int(ent.size)
+        p_ent = torch.from_numpy((ent if ent.size else np.zeros(1, rk.PLACE_DTYPE)).view(np.uint8).copy()).to(dev)
+    n_nodes, gpn, cpn, mem = nodes
+    cap = n_nodes * gpn
+    assign, total = rk.new_assign(J, dev), run.f32(1)
+    off = torch.full((J + 1,), -1, dtype=torch.int32, device=dev)
+    ent = rk.new_place_entries(cap, dev)
+    stats = torch.full((5,), -1, dtype=torch.int32, device=dev)
+    rk.rk_reschedule_nodes(run.ctx, run.jobs.ref_thr, run.table.c, run.grid, rk.rk_nodes(n_nodes, gpn, cpn, mem),
+                           run.dev_f32(bt), run.dev_u32(bp), run.dev_f32(ct), i32(cur_seg), run.dev_u32(cur_c), assign, off,
+                           ent, cap, total, prev_off=p_off, prev_entries=p_ent, n_prev_entries=n_prev, state=u8(state),
+                           floor_seg=i32(floor_seg), floor_c=None if floor_c is None else run.dev_u32(floor_c), stats=stats)
+    rk.rk_sync(run.ctx)
+    off = rk.u32(off)
+    stats = stats.cpu().numpy()
+    return rk.assign_to_numpy(assign), off, rk.place_entries_to_numpy(ent, int(off[J])), float(total[0].item()), stats
+
+
+def same(got, want):
+    """want = the oracle's (records, offsets, entries, total, steps), or None for a state that is no placement."""
+    g_a, g_off, g_ent, g_total, stats = got
+    if want is None:
+        assert stats[4] == 1 and not g_a["g"].any() and not g_off.any() and g_total == 0
+        return
+    w_a, w_off, w_ent, w_total, w_moves = want
+    assert stats[4] == 0
+    assert np.array_equal(g_a, w_a), np.flatnonzero(g_a != w_a)[:5]
+    assert np.array_equal(g_off, w_off)
+    assert np.array_equal(g_ent, w_ent), np.flatnonzero(g_ent != w_ent)[:5]
+    assert g_total == pytest.approx(w_total, rel=1e-6, abs=1e-12)
+    assert stats[0] == w_moves
+
+
+def node_round(rng, orc, J=None, g_max=None, roomy=None):
+    """A drawn round (as for the loop over totals) with CPU levels per GPU, nodes that hold the cluster's GPUs, and the
+    jobs that hold something laid out by first fit (a job that finds no room holds nothing)."""
+    wl, tb, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state = random_round(rng, orc, J, g_max)
+    grid = workloads.Grid(wl.grid.cpu_levels, 1, wl.grid.mem_levels_gb, wl.grid.mem_mode)
+    ct, _, _ = orc.curves(tb, grid, bt, bp)
+    wl = workloads.Workload("drawn", wl.coef, wl.ints, wl.bounds, grid, wl.env, wl.cluster)
+    J = wl.n_jobs
+    gpn = int(rng.choice([1, 2, 4, 8]))
+    n_nodes = max(1, -(-wl.cluster.G // gpn))
+    top = int(grid.cpu_levels[-1])
+    roomy = rng.uniform() < 0.5 if roomy is None else roomy
+    cpn = gpn * top if roomy else int(rng.integers(gpn, gpn * top + 1))
+    mem = float(rng.choice([8.0, 64.0, 1e6]))
+    free_g, free_c = [gpn] * n_nodes, [cpn] * n_nodes
+    off, ent = [0], []
+    cur_seg[state != 0] = -1                                 # (they hold nothing, also when the states are not passed)
+    for j in range(J):
+        if cur_seg[j] >= 0:
+            parts = first_fit(free_g, free_c, int(cur_seg[j]) + 1, int(grid.cpu_levels[cur_c[j]]))
+            if parts is None:
+                cur_seg[j] = -1
+            else:
+                ent += [(n, k, int(grid.cpu_levels[cur_c[j]]) * k, 0.0) for n, k in sorted(parts.items())]
+        off.append(len(ent))
+    prev = (np.array(off, np.uint32), np.array(ent, orc.PLACE_DTYPE) if ent else np.zeros(0, orc.PLACE_DTYPE))
+    return wl, tb, bt, bp, ct, (n_nodes, gpn, cpn, mem), cur_seg, cur_c, prev, floor_seg, floor_c, state
+
+
+def run_both(gpu, orc, case, use_floor=True, use_state=True):
+    wl, tb, bt, bp, ct, nodes, cur_seg, cur_c, prev, floor_seg, floor_c, state = case
+    fs, fc, st = (floor_seg, floor_c) if use_floor else (None, None), None, state if use_state else None
+    fs, fc = fs
+    want = orc.reschedule_nodes(wl.coef[:, 16], tb, wl.grid, *nodes, bt, bp, ct, cur_seg, cur_c, prev, fs, fc, state=st)
+    run = gpu(wl)
+    run.enumerate()
+    assert np.array_equal(run.table_numpy()["seg_g"], tb.seg_g)
+    got = on_gpu(run, bt, bp, ct, nodes, cur_seg, cur_c, prev, fs, fc, st)
+    run.close()
+    same(got, want)
+    return want
+
+
+def test_random_rounds_on_drawn_values(gpu, orc):
+    n_moves = n_spread = n_dropped = 0
+    for seed in range(400):
+        rng = np.random.default_rng(81000 + seed)
+        case = node_round(rng, orc)
+        print("seed", 81000 + seed, "jobs", case[0].n_jobs, "nodes", case[5], flush=True)
+        want = run_both(gpu, orc, case, use_floor=seed % 4 != 0, use_state=seed % 3 != 0)
+        assert want is not None
+        a, off, ent, _, moves = want
+        n_moves += moves
+        n_spread += int(np.any(np.diff(off.astype(np.int64)) > 1))
+        n_dropped += int(np.any((a["g"] == 0) & (case[6] >= 0)))
+    print(f"400 rounds, {n_moves} steps committed, {n_spread} rounds with a job on several nodes, {n_dropped} with a job that left")
+    assert n_moves > 1500 and n_spread > 100
+
+
+def test_larger_drawn_rounds(gpu, orc):
+    n_moves = 0
+    for seed, J in enumerate([300, 1000, 1024, 1025, 2049, 3000] * 2):
+        rng = np.random.default_rng(82000 + seed)
+        case = node_round(rng, orc, J, int(rng.integers(2, 23)))
+        print("seed", 82000 + seed, "jobs", J, "nodes", case[5], flush=True)
+        want = run_both(gpu, orc, case)
+        n_moves += want[4]
+    print(f"12 rounds, {n_moves} steps committed")
+    assert n_moves > 1000
+
+
+def test_states_that_are_no_placement(gpu, orc):
+    n_bad = 0
+    for seed in range(40):
+        rng = np.random.default_rng(83000 + seed)
+        case = list(node_round(rng, orc, roomy=True))
+        off, ent = case[8][0].copy(), case[8][1].copy()
+        kind = seed % 5
+        if len(ent) == 0:
+            continue
+        i = int(rng.integers(0, len(ent)))
+        if kind == 0: ent["g"][i] += 1                        # parts that do not add up (and CPUs that do not match)
+        elif kind == 1: ent["node"][i] = case[5][0] + int(rng.integers(0, 3))     # a node the cluster does not have
+        elif kind == 2: ent["c"][i] += 1                      # CPUs that are not level * GPUs
+        elif kind == 3: off[1:] = off[1:][::-1]               # offsets that do not ascend (unless all jobs are alike)
+        elif kind == 4: case[5] = (case[5][0], case[5][1], max(1, case[5][2] // 8), case[5][3])   # nodes with too few CPUs
+        case[8] = (off, ent)
+        print("seed", 83000 + seed, "kind", kind, flush=True)
+        want = run_both(gpu, orc, tuple(case))
+        n_bad += want is None
+    assert n_bad > 20
+
+
+def test_argument_errors(gpu, orc):
+    import paper_2408_08586_amd as rk
+    rng = np.random.default_rng(5)
+    wl, tb, bt, bp, ct, nodes, cur_seg, cur_c, prev, floor_seg, floor_c, state = node_round(rng, orc)
+    run = gpu(wl)
+    run.enumerate()
+    J = wl.n_jobs
+    dev = run.device
+    assign, total = rk.new_assign(J, dev), run.f32(1)
+    off = run.i32(J + 1)
+    n_nodes, gpn, cpn, mem = nodes
+    ent = rk.new_place_entries(n_nodes * gpn, dev)
+    cur = run.torch.full((J,), -1, dtype=run.torch.int32, device=dev)
+    args = (run.dev_f32(bt), run.dev_u32(bp), run.dev_f32(ct), cur, run.i32(J).zero_(), assign, off, ent)
+
+    def call(grid=run.grid, nd=rk.rk_nodes(n_nodes, gpn, cpn, mem), cap=n_nodes * gpn, **kw):
+        rk.rk_reschedule_nodes(run.ctx, run.jobs.ref_thr, run.table.c, grid, nd, *args, cap, total, **kw)
+
+    with pytest.raises(rk.RkError) as e:
+        call(grid=rk.make_grid(workloads.Grid(wl.grid.cpu_levels, 0, wl.grid.mem_levels_gb, wl.grid.mem_mode)))
+    assert e.value.code == rk.RK_ERR_UNSUPPORTED              # CPU levels of the job, not per GPU
+    with pytest.raises(rk.RkError) as e:
+        call(cap=n_nodes * gpn - 1)
+    assert e.value.code == rk.RK_ERR_CAPACITY
+    with pytest.raises(rk.RkError) as e:
+        call(nd=rk.rk_nodes(0, gpn, cpn, mem))
+    assert e.value.code == rk.RK_ERR_INVALID_ARG
+    with pytest.raises(rk.RkError) as e:
+        call(prev_off=off)                                   # offsets without entries
+    assert e.value.code == rk.RK_ERR_INVALID_ARG
+    # nobody holds anything and there is no earlier placement: every job is a newcomer
+    call()
+    rk.rk_sync(run.ctx)
+    a = rk.assign_to_numpy(assign)
+    assert 0 <= a["g"].sum() <= n_nodes * gpn
+    want = orc.reschedule_nodes(wl.coef[:, 16], tb, wl.grid, *nodes, bt, bp, ct, np.full(J, -1), np.zeros(J), None)
+    assert np.array_equal(a, want[0])
+    run.close()
