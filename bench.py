@@ -336,6 +336,35 @@ def algorithm1_bench(rk, ctx, dev, wl, jobs, table, grid, env, best_thr, best_pl
                                      "plans_changed_by_the_split": int(((p["plan"] != res["plan"]) & (st == 1)).sum()),
                                      "jobs_that_stayed_on_their_nodes": int(stayed),
                                      "job_by_job_stage": bool(r.in_order)}
+    if wl.grid.cpu_mode == 1:
+        # the same loop with ScheduleJob searching node by node: the jobs start where the from-scratch round's amounts
+        # were placed (roomy nodes), those of the departed slots hold nothing
+        nodes = rk.rk_nodes(n_nodes, gpn, min(int(wl.cluster.C // n_nodes), 65535), float(wl.cluster.host_mem_gb) / n_nodes)
+        r0 = rk.rk_place_plans(ctx, jobs, table.c, grid, env, nodes, best_thr, assign, None, before, off0, ent0, cap, status, total)
+        seg_n = cur_seg.copy()
+        seg_n[rk.u32(status)[:J] != 1] = -1
+        d_seg_n = torch.from_numpy(seg_n).to(dev)
+        stats = torch.zeros(5, dtype=torch.int32, device=dev)
+        ms = []
+        for i in range(reps + 2):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            rk.rk_reschedule_nodes(ctx, jobs.ref_thr, table.c, grid, nodes, best_thr, best_plan, curve_thr, d_seg_n, d_c, out, off,
+                                   ent, cap, total, prev_off=off0, prev_entries=ent0, n_prev_entries=r0.n_entries, stats=stats)
+            b.record()
+            torch.cuda.synchronize()
+            if i >= 2:
+                ms.append(a.elapsed_time(b))
+        res_n = rk.assign_to_numpy(out)
+        o1 = rk.u32(off)[:J + 1].astype(np.int64)
+        st5 = stats.cpu().numpy()
+        info["over_nodes"] = {"entry": "rk_reschedule_nodes (one workgroup; the job to shrink is one of the node under search)",
+                              "nodes": n_nodes, "gpus_per_node": gpn, "cpus_per_node": int(nodes.cpus_per_node),
+                              "jobs_running_before": int((seg_n >= 0).sum()), "steps_committed": int(st5[0]),
+                              "jobs_on_the_full_path": int(st5[1]), "shrinks_applied": int(st5[2]),
+                              "steps_taken_back": int(st5[3]), "jobs_running_after": int((res_n["g"] > 0).sum()),
+                              "jobs_on_several_nodes": int((np.diff(o1) > 1).sum()), "parts": int(o1[J]),
+                              "total": float(total[0].item()), "ms": float(np.median(ms))}
     return info
 
 

@@ -159,6 +159,67 @@ def test_states_that_are_no_placement(gpu, orc):
     assert n_bad > 20
 
 
+@pytest.mark.parametrize("name", ["what_if", "stress"])
+def test_generated_rounds_from_a_running_state(gpu, orc, name):
+    """The state a from-scratch round leaves, laid out on the nodes by first fit; then a tenth of the jobs leave and
+    their slots are new arrivals, some jobs are guaranteed: the loop over the nodes on the library's own curves, given
+    to both sides.  What comes out is a placement that rk_place_plans keeps part by part."""
+    import time
+    import paper_2408_08586_amd as rk
+    from test_gpu_placed import place_on_gpu
+    wl = {"what_if": lambda: workloads.what_if(7), "stress": workloads.stress}[name]()
+    assert wl.grid.cpu_mode == 1
+    J = wl.n_jobs
+    rng = np.random.default_rng(J + 1)
+    run = gpu(wl)
+    run.enumerate()
+    bt, bp, ct, _, _, n = run.fused()
+    bt, bp, ct = run.host(bt, n).copy(), run.host(bp, n).view(np.uint32).copy(), run.host(ct, n).copy()
+    tn = run.table_numpy()
+    tb = orc.Table(tn["triple_off"], tn["triples"], tn["seg_off"], tn["seg_g"], tn["seg_first"])
+    a0, _, _ = orc.greedy(wl.coef[:, 16], tb, wl.grid, wl.cluster, bt, bp, ct)
+    gpn = wl.env.gpus_per_node
+    n_nodes = wl.cluster.G // gpn
+    nodes = (n_nodes, gpn, int(wl.grid.cpu_levels[-1]) * gpn, wl.cluster.host_mem_gb / n_nodes)
+    off0, ent0, status0 = orc.place(a0, *nodes)
+    cur_seg, cur_c = np.full(J, -1, np.int32), np.zeros(J, np.uint32)
+    levels = np.asarray(wl.grid.cpu_levels)
+    for j in np.flatnonzero(status0 == 1).tolist():
+        seg_g = tb.seg_g[tb.seg_off[j]:tb.seg_off[j + 1]]
+        cur_seg[j] = int(np.flatnonzero(seg_g == a0["g"][j])[0])
+        cur_c[j] = int(np.flatnonzero(levels == a0["c"][j] // a0["g"][j])[0])
+    gone = rng.uniform(size=J) < 0.1
+    cur_seg[gone] = -1                                                       # left; the slot is a new arrival
+    floor_seg, floor_c = np.full(J, -1, np.int32), np.zeros(J, np.uint32)
+    ns = np.diff(tb.seg_off)
+    guaranteed = (rng.uniform(size=J) < 0.05) & (ns > 0)
+    floor_seg[guaranteed] = np.minimum(rng.integers(0, 3, guaranteed.sum()), ns[guaranteed] - 1)
+    floor_seg[(cur_seg >= 0) & (floor_seg > cur_seg)] = -1                  # running jobs sit at or above their floor
+    state = (rng.uniform(size=J) < 0.02).astype(np.uint8)
+    cur_seg[state != 0] = -1
+    prev = (off0, ent0)
+    t0 = time.time()
+    want = orc.reschedule_nodes(wl.coef[:, 16], tb, wl.grid, *nodes, bt, bp, ct, cur_seg, cur_c, prev, floor_seg, floor_c,
+                                state=state)
+    t1 = time.time()
+    got = on_gpu(run, bt, bp, ct, nodes, cur_seg, cur_c, prev, floor_seg, floor_c, state)
+    same(got, want)
+    a, off, ent, total, stats = got
+    print(f"{name}: {int((status0 == 1).sum())} jobs ran on {n_nodes} nodes, {int(gone.sum())} slots changed hands, "
+          f"{stats[0]} steps committed ({stats[1]} jobs served in full, {stats[2]} shrinks, {stats[3]} steps taken back), "
+          f"{int((a['g'] > 0).sum())} jobs run now, {int((np.diff(off.astype(np.int64)) > 1).sum())} on several nodes; "
+          f"oracle {t1 - t0:.1f} s", flush=True)
+    assert stats[0] > 0
+    used = np.zeros(n_nodes, np.int64)
+    np.add.at(used, ent["node"], ent["g"])
+    assert used.max() <= gpn
+    # GetBestPlan(j, placement): given as the earlier placement, every job keeps its parts and only the plan is chosen again
+    placed, p_off, p_ent, p_status, _, res = place_on_gpu(run, bt, a, floor_seg, *nodes, prev=(off, ent))
+    assert np.array_equal(p_off, off) and np.array_equal(p_ent, ent)
+    assert np.array_equal(p_status, (a["g"] > 0).astype(np.uint32)) and res.in_order == 1
+    run.close()
+
+
 def test_argument_errors(gpu, orc):
     import paper_2408_08586_amd as rk
     rng = np.random.default_rng(5)
