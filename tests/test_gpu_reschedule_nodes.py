@@ -66,7 +66,7 @@ def same(got, want):
     assert stats[0] == w_moves
 
 
-def node_round(rng, orc, J=None, g_max=None, roomy=None):
+def node_round(rng, orc, J=None, g_max=None, roomy=None, gpn=None, n_nodes=None):
     """A drawn round (as for the loop over totals) with CPU levels per GPU, nodes that hold the cluster's GPUs, and the
     jobs that hold something laid out by first fit (a job that finds no room holds nothing)."""
     wl, tb, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state = random_round(rng, orc, J, g_max)
@@ -74,8 +74,8 @@ def node_round(rng, orc, J=None, g_max=None, roomy=None):
     ct, _, _ = orc.curves(tb, grid, bt, bp)
     wl = workloads.Workload("drawn", wl.coef, wl.ints, wl.bounds, grid, wl.env, wl.cluster)
     J = wl.n_jobs
-    gpn = int(rng.choice([1, 2, 4, 8]))
-    n_nodes = max(1, -(-wl.cluster.G // gpn))
+    gpn = int(rng.choice([1, 2, 4, 8])) if gpn is None else gpn
+    n_nodes = max(1, -(-wl.cluster.G // gpn)) if n_nodes is None else n_nodes
     top = int(grid.cpu_levels[-1])
     roomy = rng.uniform() < 0.5 if roomy is None else roomy
     cpn = gpn * top if roomy else int(rng.integers(gpn, gpn * top + 1))
@@ -135,6 +135,20 @@ def test_larger_drawn_rounds(gpu, orc):
         n_moves += want[4]
     print(f"12 rounds, {n_moves} steps committed")
     assert n_moves > 1000
+
+
+def test_shapes_at_the_limits(gpu, orc):
+    """The most nodes the library takes (four per thread of the kernel), nodes of more GPUs than a wavefront has lanes,
+    the most jobs a round may have, and the smallest cluster there is."""
+    import time
+    for seed, (J, g_max, gpn, n_nodes) in enumerate([(2000, 4, 1, 4096), (500, 22, 128, 8), (12288, 3, 8, 512), (1, 2, 1, 1),
+                                                      (700, 16, 3, 1365)]):
+        rng = np.random.default_rng(84000 + seed)
+        case = node_round(rng, orc, J, g_max, gpn=gpn, n_nodes=n_nodes)
+        t0 = time.time()
+        want = run_both(gpu, orc, case)
+        print("seed", 84000 + seed, "jobs", J, "nodes", case[5], "steps", want[4], f"{time.time() - t0:.1f} s", flush=True)
+        assert want is not None
 
 
 def test_states_that_are_no_placement(gpu, orc):
