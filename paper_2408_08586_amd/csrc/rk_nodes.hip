@@ -67,6 +67,7 @@ struct NdArgs {
     rk_place_entry *entries;
     float *total;
     uint32_t *stats;                 // may be null
+    uint32_t *flags;                 // one word: non-zero when some job's parts are no placement
 };
 
 __device__ __forceinline__ uint32_t nd_cpl(const NdArgs &A, uint32_t lvl) { return A.X.grid.cpu_levels[lvl]; }
@@ -121,6 +122,59 @@ __device__ __forceinline__ float nd_lowest_on(const NdArgs &A, uint32_t n, uint3
     return best;
 }
 
+// The nodes, all free and empty.
+__global__ void k_nd_init(NdArgs A) {
+    const uint32_t n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n < A.n_nodes) { A.free_g[n] = A.gpn; A.free_c[n] = A.cpn; A.cnt[n] = 0u; }
+    if (n == 0) A.flags[0] = 0u;
+}
+
+// Every job on its own, any number of workgroups: what it holds, whether it comes first, its parts booked on the
+// nodes (atomics; a node that ends up holding more than it has is seen by the main kernel), its cached slopes.
+__global__ void k_nd_prepare(NdArgs A) {
+    const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= A.n_jobs) return;
+    const uint32_t N = A.n_nodes;
+    int32_t gi = -1;
+    uint32_t ci = 0;
+    if (rs_part(A, j) && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < rs_ns(A, j) && A.cur_c[j] < A.X.grid.n_cpu) {
+        gi = A.cur_seg[j]; ci = A.cur_c[j];
+    }
+    A.st.gi[j] = gi; A.st.ci[j] = ci;
+    A.stamp[j] = 0u;
+    const int32_t fl = rs_fl_s(A, j);
+    A.first[j] = (rs_part(A, j) && fl >= 0 && gi < fl) ? 1u : 0u;
+    if (gi >= 0) {
+        bool good = A.prev_off != nullptr && A.prev_entries != nullptr;
+        if (good) {
+            const uint32_t per_gpu = nd_cpl(A, ci);
+            const uint32_t a = A.prev_off[j], b = A.prev_off[j + 1];
+            if (a > b || b > A.n_prev) good = false;
+            unsigned long long sum = 0;
+            long long last = -1;
+            for (uint32_t i = a; i < b && good; ++i) {
+                const rk_place_entry e = A.prev_entries[i];
+                if (e.node >= N || (long long)e.node <= last || e.g == 0u || e.g > A.gpn || e.c > A.cpn ||
+                    (unsigned long long)e.c != (unsigned long long)per_gpu * e.g) { good = false; break; }
+                last = e.node; sum += e.g;
+            }
+            if (good && sum != rs_g(A, j, gi)) good = false;
+            for (uint32_t i = a; i < b && good; ++i) {
+                const rk_place_entry e = A.prev_entries[i];
+                const uint32_t slot = atomicAdd(&A.cnt[e.node], 1u);
+                if (slot < A.gpn) {
+                    A.res_job[(size_t)e.node * A.gpn + slot] = j; A.res_k[(size_t)e.node * A.gpn + slot] = e.g;
+                }
+                // (wraps below zero when the node holds more than it has; the main kernel sees that)
+                atomicSub(&A.free_g[e.node], e.g);
+                atomicSub(&A.free_c[e.node], e.c);
+            }
+        }
+        if (!good) atomicOr(&A.flags[0], 1u);
+    }
+    rs_refresh(A, j);
+}
+
 __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
     __shared__ RsStep sh_step;
     __shared__ float sh_lost, sh_wmin[ND_WAVES], sh_wc[ND_WAVES];
@@ -153,49 +207,8 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
         return base + inc - val;
     };
 
-    // ---- the state the jobs are in
-    if (tid == 0) { sh_bad = 0u; sh_epoch = 0u; sh_moves = 0u; sh_full = 0u; sh_shrinks = 0u; sh_undone = 0u; }
-    for (uint32_t n = tid; n < N; n += ND_THREADS) { A.free_g[n] = A.gpn; A.free_c[n] = A.cpn; A.cnt[n] = 0u; }
-    for (uint32_t j = tid; j < J; j += ND_THREADS) {
-        int32_t gi = -1;
-        uint32_t ci = 0;
-        if (rs_part(A, j) && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < rs_ns(A, j) && A.cur_c[j] < A.X.grid.n_cpu) {
-            gi = A.cur_seg[j]; ci = A.cur_c[j];
-        }
-        A.st.gi[j] = gi; A.st.ci[j] = ci;
-        A.stamp[j] = 0u; A.first[j] = 0u;
-    }
-    __syncthreads();
-    // its parts: every job checks its own list; the nodes are booked with atomics and checked afterwards
-    for (uint32_t j = tid; j < J; j += ND_THREADS) {
-        if (A.st.gi[j] < 0) continue;
-        bool good = A.prev_off != nullptr && A.prev_entries != nullptr;
-        if (good) {
-            const uint32_t per_gpu = nd_cpl(A, A.st.ci[j]);
-            const uint32_t a = A.prev_off[j], b = A.prev_off[j + 1];
-            if (a > b || b > A.n_prev) good = false;
-            unsigned long long sum = 0;
-            long long last = -1;
-            for (uint32_t i = a; i < b && good; ++i) {
-                const rk_place_entry e = A.prev_entries[i];
-                if (e.node >= N || (long long)e.node <= last || e.g == 0u || e.g > A.gpn ||
-                    (unsigned long long)e.c != (unsigned long long)per_gpu * e.g) { good = false; break; }
-                last = e.node; sum += e.g;
-            }
-            if (good && sum != rs_g(A, j, A.st.gi[j])) good = false;
-            for (uint32_t i = a; i < b && good; ++i) {
-                const rk_place_entry e = A.prev_entries[i];
-                const uint32_t slot = atomicAdd(&A.cnt[e.node], 1u);
-                if (slot < A.gpn) {
-                    A.res_job[(size_t)e.node * A.gpn + slot] = j; A.res_k[(size_t)e.node * A.gpn + slot] = e.g;
-                }
-                // (wraps below zero when the node holds more than it has; seen by the check below)
-                atomicSub(&A.free_g[e.node], e.g);
-                atomicSub(&A.free_c[e.node], e.c);
-            }
-        }
-        if (!good) atomicOr(&sh_bad, 1u);
-    }
+    // ---- the state the jobs are in has been loaded (k_nd_init, k_nd_prepare); no node may hold more than it has
+    if (tid == 0) { sh_bad = A.flags[0]; sh_epoch = 0u; sh_moves = 0u; sh_full = 0u; sh_shrinks = 0u; sh_undone = 0u; }
     __syncthreads();
     for (uint32_t n = tid; n < N; n += ND_THREADS)
         if (A.cnt[n] > A.gpn || A.free_g[n] > A.gpn || A.free_c[n] > A.cpn) atomicOr(&sh_bad, 1u);
@@ -211,9 +224,6 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
         }
         return;
     }
-    for (uint32_t j = tid; j < J; j += ND_THREADS) rs_refresh(A, j);
-    __syncthreads();
-
     auto keep_nodes = [&]() { for (uint32_t i = tid; i < A.nodes_words; i += ND_THREADS) A.keep_nodes[i] = A.free_g[i]; };
     auto restore_nodes = [&]() { for (uint32_t i = tid; i < A.nodes_words; i += ND_THREADS) A.free_g[i] = A.keep_nodes[i]; };
     // first thread: remember job v as it is before this step changes it
@@ -458,11 +468,6 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
     };
 
     // ---- privileged jobs (below their floor), in job order
-    for (uint32_t j = tid; j < J; j += ND_THREADS) {
-        const int32_t fl = rs_fl_s(A, j);
-        A.first[j] = (rs_part(A, j) && fl >= 0 && A.st.gi[j] < fl) ? 1u : 0u;
-    }
-    __syncthreads();
     for (uint32_t base = 0; base < J; base += ND_THREADS) {  // their list: 1,024 jobs at a time (tmp_off serves as the list)
         const uint32_t j = base + tid;
         const bool is = j < J && A.first[j] != 0u;
@@ -476,8 +481,8 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
     // ---- the others: their order is fixed once, by GPU slope, then CPU slope (both descending), then index
     for (uint32_t j = tid; j < J; j += ND_THREADS) {
         const bool in = rs_part(A, j) && !A.first[j];
-        A.sg[j] = in ? rs_up_gpu(A, j, 0, 1).slope : -1.f;   // -1: not in the list
-        A.sc[j] = in ? rs_up_cpu(A, j, 0, 1).slope : -1.f;
+        A.sg[j] = in ? A.ug[j] : -1.f;                       // the cached slopes are current; -1: not in the list
+        A.sc[j] = in ? A.uc[j] : -1.f;
     }
     __syncthreads();
     // Most jobs find nothing to do when their turn comes, and whether that is so follows from values that change
@@ -773,7 +778,7 @@ extern "C" int32_t rk_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const 
     float *f_jobs;
     unsigned long long *u64;
     if ((rc = rk_scratch(ctx, SL_ND_NODES, (2 * nodes_words + 2 * N + 2 * (size_t)gpus) * sizeof(uint32_t), (void **)&w_nodes))) return rc;
-    if ((rc = rk_scratch(ctx, SL_ND_U32, (11 * n + 1) * sizeof(uint32_t), (void **)&w_jobs))) return rc;
+    if ((rc = rk_scratch(ctx, SL_ND_U32, (11 * n + 2) * sizeof(uint32_t), (void **)&w_jobs))) return rc;
     if ((rc = rk_scratch(ctx, SL_ND_F32, 8 * n * sizeof(float), (void **)&f_jobs))) return rc;
     if ((rc = rk_scratch(ctx, SL_ND_U64, 2 * n * sizeof(unsigned long long), (void **)&u64))) return rc;
     NdArgs A;
@@ -793,10 +798,17 @@ extern "C" int32_t rk_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const 
     A.stamp = w_jobs + 4 * n; A.first = w_jobs + 5 * n; A.keep_ci = w_jobs + 6 * n;
     A.keep_gi = reinterpret_cast<int32_t *>(w_jobs + 7 * n); A.np = w_jobs + 8 * n; A.tier = w_jobs + 9 * n;
     A.tmp_off = w_jobs + 10 * n;                             // n + 1 words
+    A.flags = w_jobs + 11 * n + 1;
     A.ds_g = f_jobs; A.ds_c = f_jobs + n; A.ug = f_jobs + 2 * n; A.uc = f_jobs + 3 * n; A.sg = f_jobs + 4 * n;
     A.sc = f_jobs + 5 * n; A.keep_ds = f_jobs + 6 * n;
     A.udc_g = u64; A.udc_c = u64 + n;
     A.assign = assign; A.place_off = place_off; A.entries = entries; A.total = total; A.stats = stats;
+    k_nd_init<<<(uint32_t)((N + 255) / 256), 256, 0, ctx->stream>>>(A);
+    RK_CHECK_LAUNCH(ctx, "k_nd_init");
+    if (J > 0) {
+        k_nd_prepare<<<(J + 255) / 256, 256, 0, ctx->stream>>>(A);
+        RK_CHECK_LAUNCH(ctx, "k_nd_prepare");
+    }
     k_reschedule_nodes<<<1, ND_THREADS, 0, ctx->stream>>>(A);
     RK_CHECK_LAUNCH(ctx, "k_reschedule_nodes");
     return RK_OK;
