@@ -57,6 +57,9 @@ struct NdArgs {
     uint32_t nodes_words;
     // per job: cached slopes (see rk_loop.h), the order, what a step touched
     float *ds_g, *ds_c, *ug, *uc, *sg, *sc, *keep_ds;
+    float *gain_g, *gain_c;          // ... and of a job's next GPU / CPU step: its gain,
+    int32_t *tgt_g;                  // the GPU step's target amount,
+    uint32_t *lvl_g, *lvl_c, *any;   // the CPU level each step ends on, bit 0 / 1: there is a GPU / CPU step
     uint32_t *udg, *touched, *stamp, *first, *keep_ci, *np, *tmp_off, *tier;
     int32_t *keep_gi;
     unsigned long long *udc_g, *udc_c;
@@ -122,6 +125,32 @@ __device__ __forceinline__ float nd_lowest_on(const NdArgs &A, uint32_t n, uint3
     return best;
 }
 
+// All cached values of job v from its present state: what it gives (rs_refresh_give) and its next steps in full, so
+// that ScheduleJob need not search them again.  `lanes` threads share the search (1, or the 64 of a wavefront).
+__device__ __forceinline__ void nd_refresh(const NdArgs &A, uint32_t v, uint32_t lane, uint32_t lanes) {
+    const RsGive a = rs_down_gpu(A, v), b = rs_down_cpu(A, v);
+    const RsStep ug = rs_up_gpu(A, v, lane, lanes), uc = rs_up_cpu(A, v, lane, lanes);
+    if (lane != 0) return;
+    A.ds_g[v] = a.any ? a.slope : __int_as_float(0x7F800000);
+    A.ds_c[v] = b.any ? b.slope : __int_as_float(0x7F800000);
+    A.ug[v] = ug.any ? ug.slope : 0.f; A.udg[v] = (uint32_t)ug.dg; A.udc_g[v] = ug.dc;   // (a step that exists has its slope here)
+    A.uc[v] = uc.any ? uc.slope : 0.f; A.udc_c[v] = uc.dc;
+    A.gain_g[v] = ug.gain; A.gain_c[v] = uc.gain; A.tgt_g[v] = ug.tgt; A.lvl_g[v] = ug.lvl; A.lvl_c[v] = uc.lvl;
+    A.any[v] = (ug.any ? 1u : 0u) | (uc.any ? 2u : 0u);
+}
+// the cached next step of job j: res 0 GPUs, 1 CPU level
+__device__ __forceinline__ RsStep nd_cached_step(const NdArgs &A, uint32_t j, uint32_t res) {
+    RsStep st;
+    if (res == 0) {
+        st.any = A.any[j] & 1u; st.tgt = A.tgt_g[j]; st.lvl = A.lvl_g[j]; st.slope = A.ug[j]; st.gain = A.gain_g[j];
+        st.dg = A.udg[j]; st.dc = A.udc_g[j];
+    } else {
+        st.any = (A.any[j] >> 1) & 1u; st.tgt = A.st.gi[j]; st.lvl = A.lvl_c[j]; st.slope = A.uc[j]; st.gain = A.gain_c[j];
+        st.dg = 0ull; st.dc = A.udc_c[j];
+    }
+    return st;
+}
+
 // The nodes, all free and empty.
 __global__ void k_nd_init(NdArgs A) {
     const uint32_t n = blockIdx.x * blockDim.x + threadIdx.x;
@@ -172,7 +201,7 @@ __global__ void k_nd_prepare(NdArgs A) {
         }
         if (!good) atomicOr(&A.flags[0], 1u);
     }
-    rs_refresh(A, j);
+    nd_refresh(A, j, 0, 1);
 }
 
 __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
@@ -180,7 +209,7 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
     __shared__ float sh_lost, sh_wmin[ND_WAVES], sh_wc[ND_WAVES];
     __shared__ uint32_t sh_widx[ND_WAVES], sh_scan[ND_WAVES];
     __shared__ uint32_t sh_lack, sh_ok, sh_go, sh_touched, sh_epoch, sh_moves, sh_full, sh_shrinks, sh_undone;
-    __shared__ uint32_t sh_vnode, sh_next, sh_v, sh_rest, sh_per_v, sh_flag, sh_np, sh_bad, sh_fit;
+    __shared__ uint32_t sh_vnode, sh_next, sh_v, sh_rest, sh_per_v, sh_flag, sh_np, sh_bad, sh_fit, sh_done, sh_ask;
     __shared__ unsigned long long sh_take[RK_MAX_CPU_LEVELS], sh_free_c;
     __shared__ RsMin sh_min[2], sh_wm[2][ND_WAVES];
     __shared__ double sh_sum[ND_WAVES];
@@ -246,12 +275,10 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
     // ScheduleJob(j); the same code path for all threads
     auto schedule_job = [&](uint32_t j) {
         for (;;) {                                           // ---- GPUs
-            if (wave == 0) {
-                const RsStep up = rs_up_gpu(A, j, lane, 64);
-                if (lane == 0) {
-                    sh_step = up;
-                    sh_lack = (uint32_t)up.dg; sh_lost = 0.f; sh_ok = 1u; sh_touched = 0u; sh_epoch += 1u;
-                }
+            if (tid == 0) {
+                const RsStep up = nd_cached_step(A, j, 0);
+                sh_step = up;
+                sh_lack = (uint32_t)up.dg; sh_lost = 0.f; sh_ok = 1u; sh_touched = 0u; sh_epoch += 1u;
             }
             __syncthreads();
             const RsStep st = sh_step;
@@ -273,42 +300,33 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
             uint32_t n0 = 0;
             bool walking = sh_ok && sh_lack > 0;             // (read here, written again only behind the next barrier)
             __syncthreads();
-            while (walking && n0 < N) {                      // the walk over the nodes, 64 at a time
-                if (wave == 0) {
-                    const uint32_t lack = sh_lack;
-                    const uint32_t n = n0 + lane;
-                    const bool in = n < N;
-                    uint32_t offer = 0;
-                    bool ask = false;                        // somebody here may be shrunk
-                    if (in) {
-                        const uint32_t by_cpu = A.free_c[n] / per_gpu;
-                        offer = A.free_g[n] < by_cpu ? A.free_g[n] : by_cpu;
-                        uint32_t who;
-                        const float low = nd_lowest_on(A, n, j, A.ds_g, who);
-                        ask = who != ND_NONE && (below_min || st.slope > low);
-                    }
-                    uint32_t cum = offer;
-#pragma unroll
-                    for (int off = 1; off < 64; off <<= 1) {
-                        const uint32_t o = __shfl_up(cum, off, 64);
-                        if ((int)lane >= off) cum += o;
-                    }
-                    const unsigned long long done_at = __ballot(in && cum >= lack);
-                    const unsigned long long ask_at = __ballot(in && ask && cum < lack);
-                    const int done_l = done_at ? __ffsll((long long)done_at) - 1 : 64;
-                    const int ask_l = ask_at ? __ffsll((long long)ask_at) - 1 : 64;
-                    const int last = done_l < ask_l ? done_l : ask_l;
-                    if (in && (int)lane <= last && offer) {
-                        const uint32_t before = cum - offer;                 // < lack for these lanes
-                        const uint32_t t = offer < lack - before ? offer : lack - before;
-                        nd_add(A, n, j, t, per_gpu);
-                    }
-                    const uint32_t upto = __shfl(cum, last < 64 ? last : 63, 64);
-                    if (lane == 0) {
-                        sh_lack = lack - (upto < lack ? upto : lack);
-                        sh_vnode = ask_l < done_l ? n0 + (uint32_t)ask_l : ND_NONE;
-                        sh_next = ask_l < done_l ? n0 + (uint32_t)ask_l + 1u : n0 + 64u;
-                    }
+            while (walking && n0 < N) {                      // the walk over the nodes, a node per thread at a time
+                const uint32_t lack = sh_lack;
+                const uint32_t n = n0 + tid;
+                const bool in = n < N;
+                uint32_t offer = 0;
+                bool ask = false;                            // somebody here may be shrunk
+                if (in) {
+                    const uint32_t by_cpu = A.free_c[n] / per_gpu;
+                    offer = A.free_g[n] < by_cpu ? A.free_g[n] : by_cpu;
+                    uint32_t who;
+                    const float low = nd_lowest_on(A, n, j, A.ds_g, who);
+                    ask = who != ND_NONE && (below_min || st.slope > low);
+                }
+                if (tid == 0) { sh_done = ND_THREADS; sh_ask = ND_THREADS; }
+                uint32_t all;
+                const uint32_t before = block_scan(offer, all);          // (its barriers order the two lines around it)
+                if (in && before + offer >= lack) atomicMin(&sh_done, tid);
+                if (in && ask && before + offer < lack) atomicMin(&sh_ask, tid);
+                __syncthreads();
+                const uint32_t done_t = sh_done, ask_t = sh_ask;
+                const uint32_t last = done_t < ask_t ? done_t : ask_t;   // the nodes up to here give what they offer
+                if (in && tid <= last && offer) nd_add(A, n, j, offer < lack - before ? offer : lack - before, per_gpu);
+                if (tid == (last < ND_THREADS ? last : 0u)) {
+                    const uint32_t upto = last < ND_THREADS ? before + offer : all;
+                    sh_lack = lack - (upto < lack ? upto : lack);
+                    sh_vnode = ask_t < done_t ? n0 + ask_t : ND_NONE;
+                    sh_next = ask_t < done_t ? n0 + ask_t + 1u : n0 + ND_THREADS;
                 }
                 __syncthreads();
                 const uint32_t f = sh_vnode;
@@ -381,8 +399,8 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
             __syncthreads();
             const uint32_t go = sh_go;
             if (go) {
-                const uint32_t n_changed = sh_touched + 1u;
-                for (uint32_t i = tid; i < n_changed; i += ND_THREADS) rs_refresh(A, i < sh_touched ? A.touched[i] : j);
+                const uint32_t n_changed = sh_touched + 1u;      // a wavefront per job whose state changed
+                for (uint32_t i = wave; i < n_changed; i += ND_WAVES) nd_refresh(A, i < sh_touched ? A.touched[i] : j, lane, 64);
             } else {
                 restore_nodes();
             }
@@ -390,10 +408,7 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
             if (!go) break;
         }
         for (;;) {                                           // ---- CPUs: on every node the job is on
-            if (wave == 0) {
-                const RsStep up = rs_up_cpu(A, j, lane, 64);
-                if (lane == 0) { sh_step = up; sh_lost = 0.f; sh_ok = 1u; sh_touched = 0u; sh_epoch += 1u; }
-            }
+            if (tid == 0) { sh_step = nd_cached_step(A, j, 1); sh_lost = 0.f; sh_ok = 1u; sh_touched = 0u; sh_epoch += 1u; }
             __syncthreads();
             const RsStep st = sh_step;
             if (!st.any) { __syncthreads(); break; }
@@ -457,8 +472,8 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
             __syncthreads();
             const uint32_t go = sh_go;
             if (go) {
-                const uint32_t n_changed = sh_touched + 1u;
-                for (uint32_t i = tid; i < n_changed; i += ND_THREADS) rs_refresh(A, i < sh_touched ? A.touched[i] : j);
+                const uint32_t n_changed = sh_touched + 1u;      // a wavefront per job whose state changed
+                for (uint32_t i = wave; i < n_changed; i += ND_WAVES) nd_refresh(A, i < sh_touched ? A.touched[i] : j, lane, 64);
             } else {
                 restore_nodes();
             }
@@ -504,9 +519,15 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
         for (uint32_t res = 0; res < 2; ++res) {
             const float *ds = res == 0 ? A.ds_g : A.ds_c;
             RsMin m = {INF, INF, ND_NONE};
-            for (uint32_t v = tid; v < J; v += ND_THREADS) {
-                const RsMin one = {ds[v], INF, v};
-                m = rs_min_merge(m, one);
+            for (uint32_t v0 = tid; v0 < J; v0 += 4 * ND_THREADS) {      // four loads in flight
+                float x[4];
+#pragma unroll
+                for (uint32_t k = 0; k < 4; ++k) x[k] = v0 + k * ND_THREADS < J ? ds[v0 + k * ND_THREADS] : INF;
+#pragma unroll
+                for (uint32_t k = 0; k < 4; ++k) {
+                    const RsMin one = {x[k], INF, v0 + k * ND_THREADS};
+                    m = rs_min_merge(m, one);
+                }
             }
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) {
@@ -545,15 +566,28 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
         const unsigned long long free_c = sh_free_c;
         float best_g = -1.f, best_c = -1.f;
         uint32_t best_j = ND_NONE;
-        for (uint32_t j = tid; j < J; j += ND_THREADS) {
-            const float kg = A.sg[j], kc = A.sc[j];
-            if (kg < 0.f || !comes_before(last_g, last_c, last_j, kg, kc, j)) continue;
-            const float lowest_g = j == mg.i1 ? mg.m2 : mg.m1, lowest_c = j == mc.i1 ? mc.m2 : mc.m1;
-            const float ug = A.ug[j], uc = A.uc[j];
-            const bool gpu_idle = !(ug > 0.f) || (sh_take[A.st.ci[j]] < A.udg[j] && !(ug > lowest_g));
-            const bool cpu_idle = !(uc > 0.f) || (free_c < A.udc_c[j] && !(uc > lowest_c));
-            if (gpu_idle && cpu_idle) continue;
-            if (best_j == ND_NONE || comes_before(kg, kc, j, best_g, best_c, best_j)) { best_g = kg; best_c = kc; best_j = j; }
+        for (uint32_t j0 = tid; j0 < J; j0 += 4 * ND_THREADS) {          // four jobs' values in flight
+            float kg[4], kc[4], ug[4], uc[4];
+            uint32_t dg[4], lv[4];
+            unsigned long long dc[4];
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                const uint32_t j = j0 + k * ND_THREADS;
+                const bool in = j < J;
+                kg[k] = in ? A.sg[j] : -1.f; kc[k] = in ? A.sc[j] : -1.f;
+                ug[k] = in ? A.ug[j] : 0.f; uc[k] = in ? A.uc[j] : 0.f;
+                dg[k] = in ? A.udg[j] : 0u; lv[k] = in ? A.st.ci[j] : 0u; dc[k] = in ? A.udc_c[j] : 0ull;
+            }
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                const uint32_t j = j0 + k * ND_THREADS;
+                if (kg[k] < 0.f || !comes_before(last_g, last_c, last_j, kg[k], kc[k], j)) continue;
+                const float lowest_g = j == mg.i1 ? mg.m2 : mg.m1, lowest_c = j == mc.i1 ? mc.m2 : mc.m1;
+                const bool gpu_idle = !(ug[k] > 0.f) || (sh_take[lv[k]] < dg[k] && !(ug[k] > lowest_g));
+                const bool cpu_idle = !(uc[k] > 0.f) || (free_c < dc[k] && !(uc[k] > lowest_c));
+                if (gpu_idle && cpu_idle) continue;
+                if (best_j == ND_NONE || comes_before(kg[k], kc[k], j, best_g, best_c, best_j)) { best_g = kg[k]; best_c = kc[k]; best_j = j; }
+            }
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
@@ -778,8 +812,8 @@ extern "C" int32_t rk_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const 
     float *f_jobs;
     unsigned long long *u64;
     if ((rc = rk_scratch(ctx, SL_ND_NODES, (2 * nodes_words + 2 * N + 2 * (size_t)gpus) * sizeof(uint32_t), (void **)&w_nodes))) return rc;
-    if ((rc = rk_scratch(ctx, SL_ND_U32, (11 * n + 2) * sizeof(uint32_t), (void **)&w_jobs))) return rc;
-    if ((rc = rk_scratch(ctx, SL_ND_F32, 8 * n * sizeof(float), (void **)&f_jobs))) return rc;
+    if ((rc = rk_scratch(ctx, SL_ND_U32, (15 * n + 2) * sizeof(uint32_t), (void **)&w_jobs))) return rc;
+    if ((rc = rk_scratch(ctx, SL_ND_F32, 10 * n * sizeof(float), (void **)&f_jobs))) return rc;
     if ((rc = rk_scratch(ctx, SL_ND_U64, 2 * n * sizeof(unsigned long long), (void **)&u64))) return rc;
     NdArgs A;
     A.X.ref_thr = ref_thr; A.X.tb = table_dev(table); A.X.grid = grid_dev(grid);
@@ -799,8 +833,10 @@ extern "C" int32_t rk_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const 
     A.keep_gi = reinterpret_cast<int32_t *>(w_jobs + 7 * n); A.np = w_jobs + 8 * n; A.tier = w_jobs + 9 * n;
     A.tmp_off = w_jobs + 10 * n;                             // n + 1 words
     A.flags = w_jobs + 11 * n + 1;
+    uint32_t *more = w_jobs + 11 * n + 2;
+    A.tgt_g = reinterpret_cast<int32_t *>(more); A.lvl_g = more + n; A.lvl_c = more + 2 * n; A.any = more + 3 * n;
     A.ds_g = f_jobs; A.ds_c = f_jobs + n; A.ug = f_jobs + 2 * n; A.uc = f_jobs + 3 * n; A.sg = f_jobs + 4 * n;
-    A.sc = f_jobs + 5 * n; A.keep_ds = f_jobs + 6 * n;
+    A.sc = f_jobs + 5 * n; A.keep_ds = f_jobs + 6 * n; A.gain_g = f_jobs + 8 * n; A.gain_c = f_jobs + 9 * n;
     A.udc_g = u64; A.udc_c = u64 + n;
     A.assign = assign; A.place_off = place_off; A.entries = entries; A.total = total; A.stats = stats;
     k_nd_init<<<(uint32_t)((N + 255) / 256), 256, 0, ctx->stream>>>(A);
