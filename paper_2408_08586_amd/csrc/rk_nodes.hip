@@ -511,54 +511,59 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
         return ga > gb || (ga == gb && (ca > cb || (ca == cb && a < b)));
     };
     float last_g = INF, last_c = INF;
-    uint32_t last_j = 0u;
+    uint32_t last_j = 0u, moves_seen = ND_NONE;
     for (;;) {
         __syncthreads();
-        if (tid < RK_MAX_CPU_LEVELS) sh_take[tid] = 0ull;
-        if (tid == 0) sh_free_c = 0ull;
-        for (uint32_t res = 0; res < 2; ++res) {
-            const float *ds = res == 0 ? A.ds_g : A.ds_c;
-            RsMin m = {INF, INF, ND_NONE};
-            for (uint32_t v0 = tid; v0 < J; v0 += 4 * ND_THREADS) {      // four loads in flight
-                float x[4];
-#pragma unroll
-                for (uint32_t k = 0; k < 4; ++k) x[k] = v0 + k * ND_THREADS < J ? ds[v0 + k * ND_THREADS] : INF;
-#pragma unroll
-                for (uint32_t k = 0; k < 4; ++k) {
-                    const RsMin one = {x[k], INF, v0 + k * ND_THREADS};
-                    m = rs_min_merge(m, one);
-                }
-            }
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                RsMin o;
-                o.m1 = __shfl_xor(m.m1, off, 64); o.m2 = __shfl_xor(m.m2, off, 64); o.i1 = __shfl_xor(m.i1, off, 64);
-                m = rs_min_merge(m, o);
-            }
-            if (lane == 0) sh_wm[res][wave] = m;
-        }
+        const bool fresh = sh_moves != moves_seen;          // a step was committed since the last look (or this is the first)
+        moves_seen = sh_moves;
         __syncthreads();
-        if (tid < 2) {
-            RsMin m = sh_wm[tid][0];
-            for (uint32_t w = 1; w < ND_WAVES; ++w) m = rs_min_merge(m, sh_wm[tid][w]);
-            sh_min[tid] = m;
-        }
-        {                                                    // what the nodes can give at every CPU level
-            unsigned long long fc = 0;
-            for (uint32_t n = tid; n < N; n += ND_THREADS) fc += A.free_c[n];
+        if (fresh) {
+            if (tid < RK_MAX_CPU_LEVELS) sh_take[tid] = 0ull;
+            if (tid == 0) sh_free_c = 0ull;
+            for (uint32_t res = 0; res < 2; ++res) {
+                const float *ds = res == 0 ? A.ds_g : A.ds_c;
+                RsMin m = {INF, INF, ND_NONE};
+                for (uint32_t v0 = tid; v0 < J; v0 += 4 * ND_THREADS) {      // four loads in flight
+                    float x[4];
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) fc += __shfl_xor(fc, off, 64);
-            if (lane == 0 && fc) atomicAdd(&sh_free_c, fc);
-            for (uint32_t l = 0; l < A.X.grid.n_cpu; ++l) {
-                const uint32_t per_gpu = nd_cpl(A, l);
-                unsigned long long t = 0;
-                for (uint32_t n = tid; n < N; n += ND_THREADS) {
-                    const uint32_t by_cpu = A.free_c[n] / per_gpu;
-                    t += A.free_g[n] < by_cpu ? A.free_g[n] : by_cpu;
+                    for (uint32_t k = 0; k < 4; ++k) x[k] = v0 + k * ND_THREADS < J ? ds[v0 + k * ND_THREADS] : INF;
+#pragma unroll
+                    for (uint32_t k = 0; k < 4; ++k) {
+                        const RsMin one = {x[k], INF, v0 + k * ND_THREADS};
+                        m = rs_min_merge(m, one);
+                    }
                 }
 #pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off, 64);
-                if (lane == 0 && t) atomicAdd(&sh_take[l], t);
+                for (int off = 32; off >= 1; off >>= 1) {
+                    RsMin o;
+                    o.m1 = __shfl_xor(m.m1, off, 64); o.m2 = __shfl_xor(m.m2, off, 64); o.i1 = __shfl_xor(m.i1, off, 64);
+                    m = rs_min_merge(m, o);
+                }
+                if (lane == 0) sh_wm[res][wave] = m;
+            }
+            __syncthreads();
+            if (tid < 2) {
+                RsMin m = sh_wm[tid][0];
+                for (uint32_t w = 1; w < ND_WAVES; ++w) m = rs_min_merge(m, sh_wm[tid][w]);
+                sh_min[tid] = m;
+            }
+            {                                                    // what the nodes can give at every CPU level
+                unsigned long long fc = 0;
+                for (uint32_t n = tid; n < N; n += ND_THREADS) fc += A.free_c[n];
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) fc += __shfl_xor(fc, off, 64);
+                if (lane == 0 && fc) atomicAdd(&sh_free_c, fc);
+                for (uint32_t l = 0; l < A.X.grid.n_cpu; ++l) {
+                    const uint32_t per_gpu = nd_cpl(A, l);
+                    unsigned long long t = 0;
+                    for (uint32_t n = tid; n < N; n += ND_THREADS) {
+                        const uint32_t by_cpu = A.free_c[n] / per_gpu;
+                        t += A.free_g[n] < by_cpu ? A.free_g[n] : by_cpu;
+                    }
+#pragma unroll
+                    for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off, 64);
+                    if (lane == 0 && t) atomicAdd(&sh_take[l], t);
+                }
             }
         }
         __syncthreads();
