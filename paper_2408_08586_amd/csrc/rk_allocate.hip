@@ -1437,6 +1437,23 @@ struct RsArgs {
     uint32_t *stats;             // may be null: steps committed, jobs on the full path, shrinks applied, steps taken back
 };
 
+// Every job on its own, any number of workgroups: what it holds, whether it comes first (a floor it is below), its
+// cached slopes and steps.
+__global__ void k_rs_prepare(RsArgs A) {
+    const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= A.n_jobs) return;
+    int32_t gi = -1;
+    uint32_t ci = 0;
+    if (rs_part(A, j) && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < rs_ns(A, j) && A.cur_c[j] < A.X.grid.n_cpu) {
+        gi = A.cur_seg[j]; ci = A.cur_c[j];
+    }
+    A.st.gi[j] = gi; A.st.ci[j] = ci; A.st.g[j] = (uint32_t)rs_g(A, j, gi);
+    A.stamp[j] = 0u;
+    const int32_t fl = rs_fl_s(A, j);
+    A.first[j] = (rs_part(A, j) && fl >= 0 && gi < fl) ? 1u : 0u;
+    rs_refresh(A, j);
+}
+
 __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
     __shared__ RsStep sh_step;
     __shared__ unsigned long long sh_free[2], sh_avail[2], sh_held[2][RS_THREADS / 64];
@@ -1449,17 +1466,11 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
     const uint32_t J = A.n_jobs;
     const float INF = __int_as_float(0x7F800000);
 
-    // the state the jobs are in, and what they hold together
+    // the state the jobs are in has been loaded (k_rs_prepare); what they hold together
     unsigned long long hg = 0, hc = 0;
     for (uint32_t j = tid; j < J; j += RS_THREADS) {
-        int32_t gi = -1;
-        uint32_t ci = 0;
-        if (rs_part(A, j) && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < rs_ns(A, j) && A.cur_c[j] < A.X.grid.n_cpu) {
-            gi = A.cur_seg[j]; ci = A.cur_c[j];
-            hg += rs_g(A, j, gi); hc += rs_c(A, j, ci, gi);
-        }
-        A.st.gi[j] = gi; A.st.ci[j] = ci;
-        A.stamp[j] = 0u; A.first[j] = 0u;
+        const uint32_t g = A.st.g[j];
+        if (g) { hg += g; hc += cpu_cost(A.X.grid, A.st.ci[j], g); }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) { hg += __shfl_xor(hg, off, 64); hc += __shfl_xor(hc, off, 64); }
@@ -1472,7 +1483,6 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
         sh_free[1] = c < A.C ? A.C - c : 0ull;
         sh_epoch = 0u; sh_moves = 0u; sh_full = 0u; sh_shrinks = 0u; sh_undone = 0u;
     }
-    for (uint32_t j = tid; j < J; j += RS_THREADS) rs_refresh(A, j);
     __syncthreads();
 
     // ScheduleJob(j); the same code path for all threads
@@ -1556,8 +1566,8 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
                 __syncthreads();
                 const uint32_t go = sh_go;
                 if (go) {                                       // the jobs whose state changed: all their cached values
-                    const uint32_t n_changed = sh_touched + 1u;
-                    for (uint32_t i = tid; i < n_changed; i += RS_THREADS) rs_refresh(A, i < sh_touched ? A.touched[i] : j);
+                    const uint32_t n_changed = sh_touched + 1u;      // a wavefront per job
+                    for (uint32_t i = wave; i < n_changed; i += RS_THREADS / 64) rs_refresh_lanes(A, i < sh_touched ? A.touched[i] : j, lane, 64);
                 }
                 __syncthreads();
                 if (!go) break;
@@ -1567,10 +1577,6 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
 
     // privileged jobs, in job order.  Who they are is known from the start: a job never gives below its floor, so
     // only a job that begins below it can be below it.
-    for (uint32_t j = tid; j < J; j += RS_THREADS) {
-        const int32_t fl = rs_fl_s(A, j);
-        A.first[j] = (rs_part(A, j) && fl >= 0 && A.st.gi[j] < fl) ? 1u : 0u;
-    }
     if (tid == 0) sh_nb = 0u;
     __syncthreads();
     for (uint32_t base = 0; base < J; base += RS_THREADS) {       // their list, in job order: 1,024 jobs at a time
@@ -1595,8 +1601,8 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
     // the others: their order is fixed once, by GPU slope, then CPU slope (both descending), then index
     for (uint32_t j = tid; j < J; j += RS_THREADS) {
         const bool in = rs_part(A, j) && !A.first[j];
-        A.sg[j] = in ? rs_up_gpu(A, j, 0, 1).slope : -1.f;      // -1: not in the list
-        A.sc[j] = in ? rs_up_cpu(A, j, 0, 1).slope : -1.f;
+        A.sg[j] = in ? A.ug[j] : -1.f;                          // the cached slopes are current; -1: not in the list
+        A.sc[j] = in ? A.uc[j] : -1.f;
     }
     __syncthreads();
     // Most jobs of a large round find nothing to do when their turn comes: no step, or a step that needs more than is
@@ -1609,45 +1615,69 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
         return ga > gb || (ga == gb && (ca > cb || (ca == cb && a < b)));
     };
     float last_g = INF, last_c = INF;                     // key of the job served last (before every job at first)
-    uint32_t last_j = 0u;
+    uint32_t last_j = 0u, moves_seen = 0xFFFFFFFFu;
     for (;;) {
         __syncthreads();
-        for (uint32_t res = 0; res < 2; ++res) {
-            const float *ds = res == 0 ? A.ds_g : A.ds_c;
-            RsMin m = {INF, INF, 0xFFFFFFFFu};
-            for (uint32_t v = tid; v < J; v += RS_THREADS) {
-                const RsMin one = {ds[v], INF, v};
-                m = rs_min_merge(m, one);
-            }
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                RsMin o;
-                o.m1 = __shfl_xor(m.m1, off, 64); o.m2 = __shfl_xor(m.m2, off, 64); o.i1 = __shfl_xor(m.i1, off, 64);
-                m = rs_min_merge(m, o);
-            }
-            if (lane == 0) sh_wm[res][wave] = m;
-        }
+        const bool fresh = sh_moves != moves_seen;        // a step was committed since the last look (or this is the first)
+        moves_seen = sh_moves;
         __syncthreads();
-        if (tid < 2) {
-            RsMin m = sh_wm[tid][0];
-            for (uint32_t w = 1; w < RS_THREADS / 64; ++w) m = rs_min_merge(m, sh_wm[tid][w]);
-            sh_min[tid] = m;
+        if (fresh) {                                      // otherwise the lowest slopes are what they were
+            for (uint32_t res = 0; res < 2; ++res) {
+                const float *ds = res == 0 ? A.ds_g : A.ds_c;
+                RsMin m = {INF, INF, 0xFFFFFFFFu};
+                for (uint32_t v0 = tid; v0 < J; v0 += 4 * RS_THREADS) {      // four loads in flight
+                    float x[4];
+#pragma unroll
+                    for (uint32_t k = 0; k < 4; ++k) x[k] = v0 + k * RS_THREADS < J ? ds[v0 + k * RS_THREADS] : INF;
+#pragma unroll
+                    for (uint32_t k = 0; k < 4; ++k) {
+                        const RsMin one = {x[k], INF, v0 + k * RS_THREADS};
+                        m = rs_min_merge(m, one);
+                    }
+                }
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) {
+                    RsMin o;
+                    o.m1 = __shfl_xor(m.m1, off, 64); o.m2 = __shfl_xor(m.m2, off, 64); o.i1 = __shfl_xor(m.i1, off, 64);
+                    m = rs_min_merge(m, o);
+                }
+                if (lane == 0) sh_wm[res][wave] = m;
+            }
+            __syncthreads();
+            if (tid < 2) {
+                RsMin m = sh_wm[tid][0];
+                for (uint32_t w = 1; w < RS_THREADS / 64; ++w) m = rs_min_merge(m, sh_wm[tid][w]);
+                sh_min[tid] = m;
+            }
         }
         __syncthreads();
         const unsigned long long free_g = sh_free[0], free_c = sh_free[1];
         const RsMin mg = sh_min[0], mc = sh_min[1];
         float best_g = -1.f, best_c = -1.f;                // -1: none found
         uint32_t best_j = 0xFFFFFFFFu;
-        for (uint32_t j = tid; j < J; j += RS_THREADS) {
-            const float kg = A.sg[j], kc = A.sc[j];
-            if (kg < 0.f || !comes_before(last_g, last_c, last_j, kg, kc, j)) continue;       // not in the list, or served
-            const float lowest_g = j == mg.i1 ? mg.m2 : mg.m1, lowest_c = j == mc.i1 ? mc.m2 : mc.m1;
-            const float ug = A.ug[j], uc = A.uc[j];
-            // GPU step: none; or GPUs are short and nobody may be shrunk for it; or the GPUs are there and its CPUs are not
-            const bool gpu_idle = !(ug > 0.f) || (free_g < A.udg[j] ? !(ug > lowest_g) : free_c < A.udc_g[j]);
-            const bool cpu_idle = !(uc > 0.f) || (free_c < A.udc_c[j] && !(uc > lowest_c));
-            if (gpu_idle && cpu_idle) continue;
-            if (best_j == 0xFFFFFFFFu || comes_before(kg, kc, j, best_g, best_c, best_j)) { best_g = kg; best_c = kc; best_j = j; }
+        for (uint32_t j0 = tid; j0 < J; j0 += 4 * RS_THREADS) {      // four jobs' values in flight
+            float kg[4], kc[4], ug[4], uc[4];
+            uint32_t dg[4];
+            unsigned long long dcg[4], dcc[4];
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                const uint32_t j = j0 + k * RS_THREADS;
+                const bool in = j < J;
+                kg[k] = in ? A.sg[j] : -1.f; kc[k] = in ? A.sc[j] : -1.f;
+                ug[k] = in ? A.ug[j] : 0.f; uc[k] = in ? A.uc[j] : 0.f;
+                dg[k] = in ? A.udg[j] : 0u; dcg[k] = in ? A.udc_g[j] : 0ull; dcc[k] = in ? A.udc_c[j] : 0ull;
+            }
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                const uint32_t j = j0 + k * RS_THREADS;
+                if (kg[k] < 0.f || !comes_before(last_g, last_c, last_j, kg[k], kc[k], j)) continue;   // not in the list, or served
+                const float lowest_g = j == mg.i1 ? mg.m2 : mg.m1, lowest_c = j == mc.i1 ? mc.m2 : mc.m1;
+                // GPU step: none; or GPUs are short and nobody may be shrunk for it; or the GPUs are there and its CPUs are not
+                const bool gpu_idle = !(ug[k] > 0.f) || (free_g < dg[k] ? !(ug[k] > lowest_g) : free_c < dcg[k]);
+                const bool cpu_idle = !(uc[k] > 0.f) || (free_c < dcc[k] && !(uc[k] > lowest_c));
+                if (gpu_idle && cpu_idle) continue;
+                if (best_j == 0xFFFFFFFFu || comes_before(kg[k], kc[k], j, best_g, best_c, best_j)) { best_g = kg[k]; best_c = kc[k]; best_j = j; }
+            }
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
@@ -1910,6 +1940,10 @@ extern "C" int32_t rk_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_pla
     A.floor_seg = jobs_state->floor_seg; A.floor_c = jobs_state->floor_c;
     A.stats = stats;
     hipStream_t s = ctx->stream;
+    if (J > 0) {
+        k_rs_prepare<<<(J + 255) / 256, 256, 0, s>>>(A);
+        RK_CHECK_LAUNCH(ctx, "k_rs_prepare");
+    }
     k_reschedule<<<1, RS_THREADS, 0, s>>>(A);
     RK_CHECK_LAUNCH(ctx, "k_reschedule");
     if (J > 0) {

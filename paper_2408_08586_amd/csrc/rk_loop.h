@@ -190,14 +190,19 @@ __device__ __forceinline__ void rs_refresh_give(const Args &A, uint32_t v) {
     A.ds_g[v] = a.any ? a.slope : __int_as_float(0x7F800000);
     A.ds_c[v] = b.any ? b.slope : __int_as_float(0x7F800000);
 }
-// ... and its own next steps as well
+// ... and its own next steps as well; `lanes` threads share the search for them (1, or the 64 of a wavefront)
 template <class Args>
-__device__ __forceinline__ void rs_refresh(const Args &A, uint32_t v) {
-    rs_refresh_give(A, v);
-    const RsStep ug = rs_up_gpu(A, v, 0, 1), uc = rs_up_cpu(A, v, 0, 1);
+__device__ __forceinline__ void rs_refresh_lanes(const Args &A, uint32_t v, uint32_t lane, uint32_t lanes) {
+    const RsGive a = rs_down_gpu(A, v), b = rs_down_cpu(A, v);
+    const RsStep ug = rs_up_gpu(A, v, lane, lanes), uc = rs_up_cpu(A, v, lane, lanes);
+    if (lane != 0) return;
+    A.ds_g[v] = a.any ? a.slope : __int_as_float(0x7F800000);
+    A.ds_c[v] = b.any ? b.slope : __int_as_float(0x7F800000);
     A.ug[v] = ug.any ? ug.slope : 0.f; A.udg[v] = (uint32_t)ug.dg; A.udc_g[v] = ug.dc;
     A.uc[v] = uc.any ? uc.slope : 0.f; A.udc_c[v] = uc.dc;
 }
+template <class Args>
+__device__ __forceinline__ void rs_refresh(const Args &A, uint32_t v) { rs_refresh_lanes(A, v, 0, 1); }
 
 // the two lowest values of ds over all jobs and the job of the lowest (lower index among equal values)
 struct RsMin { float m1, m2; uint32_t i1; };

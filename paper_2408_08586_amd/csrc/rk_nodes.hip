@@ -9,11 +9,13 @@
 // level l holds cpu_levels[l] * k CPUs of its node.  A job's parts are not stored per job; they are found by looking
 // the job up on every node (all threads, a node or a few per thread) in the few places that need them.
 //
-// One workgroup: the rule is sequential.  Parallel are: the search for a job's next step (a wavefront over its
-// amounts), the walk over the nodes as long as nobody has to be asked (the first wavefront takes 64 nodes at a time:
-// what each offers, a prefix sum that cuts the offers at what the job lacks, and the first node where the job still
-// lacks GPUs and somebody may be shrunk), the parts a shrunk job gives up elsewhere (a suffix sum over the nodes),
-// the look-ahead that passes over jobs with nothing to do, and everything about memory and the records.
+// k_nd_init clears the nodes and k_nd_prepare loads every job on its own, over the whole chip: what it holds, its parts
+// booked on the nodes, its cached slopes and next steps.  The loop itself is one workgroup: the rule is sequential.
+// Parallel are: the refresh of the jobs a committed step changed (a wavefront per job), the walk over the nodes as
+// long as nobody has to be asked (a node per thread: what each offers, a prefix sum that cuts the offers at what the
+// job lacks, and the first node where the job still lacks GPUs and somebody may be shrunk), the parts a shrunk job
+// gives up elsewhere (a suffix sum over the nodes), the look-ahead that passes over jobs with nothing to do, and
+// everything about memory and the records.
 // Before a step touches anything the node tables are copied; a step that is not committed copies them back.
 #include "rk_internal.h"
 #include "rk_model.h"
