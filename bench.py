@@ -357,6 +357,17 @@ def algorithm1_bench(rk, ctx, dev, wl, jobs, table, grid, env, best_thr, best_pl
                 ms.append(a.elapsed_time(b))
         res_n = rk.assign_to_numpy(out)
         o1 = rk.u32(off)[:J + 1].astype(np.int64)
+        # GetBestPlan(j, placement) on what the loop left: the plans under the bandwidths of the actual node splits
+        ms_plan = []
+        for i in range(reps + 2):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            rk.rk_best_plan_placed(ctx, jobs, table.c, grid, env, out, off, ent, placed, total)
+            b.record()
+            torch.cuda.synchronize()
+            if i >= 2:
+                ms_plan.append(a.elapsed_time(b))
+        p_n = rk.assign_to_numpy(placed)
         st5 = stats.cpu().numpy()
         info["over_nodes"] = {"entry": "rk_reschedule_nodes (one workgroup; the job to shrink is one of the node under search)",
                               "nodes": n_nodes, "gpus_per_node": gpn, "cpus_per_node": int(nodes.cpus_per_node),
@@ -364,7 +375,10 @@ def algorithm1_bench(rk, ctx, dev, wl, jobs, table, grid, env, best_thr, best_pl
                               "jobs_on_the_full_path": int(st5[1]), "shrinks_applied": int(st5[2]),
                               "steps_taken_back": int(st5[3]), "jobs_running_after": int((res_n["g"] > 0).sum()),
                               "jobs_on_several_nodes": int((np.diff(o1) > 1).sum()), "parts": int(o1[J]),
-                              "total": float(total[0].item()), "ms": float(np.median(ms))}
+                              "ms": float(np.median(ms)),
+                              "best_plan_placed": {"entry": "rk_best_plan_placed (k_replan + k_place_total)",
+                                                   "plans_changed_by_the_split": int(((p_n["plan"] != res_n["plan"]) & (res_n["g"] > 0)).sum()),
+                                                   "total": float(total[0].item()), "ms": float(np.median(ms_plan))}}
     return info
 
 
@@ -763,7 +777,12 @@ def main():
                      "algorithmic_bytes_per_launch": bytes_one,
                      "traffic": traffic, "traffic_source": "profiles/hbm_traffic_stress.txt (rocprofv3 --pmc FETCH_SIZE / "
                                                             "WRITE_SIZE, scaled by a plain copy's counters)",
-                     "kernel_source_digest": digest},
+                     "kernel_source_digest": digest,
+                     # the same result with the candidates read back (rk_eval_candidates + rk_best_plan): twice the
+                     # bytes at a higher rate, and a slower step; measured in a pass of its own (kernels.two_kernels)
+                     "eval_then_best_plan": {"achieved": pair_gbs, "frac": pair_gbs / HBM_PEAK_GBS,
+                                             "ms_per_chunk": pair_avg_ms["eval"] + pair_avg_ms["best_plan"],
+                                             "one_pass_ms_per_chunk": hot_avg_ms["eval_best"]}},
         "kernels": {"timed_region_avg_launch_ms": hot_avg_ms,
                     "stage_pass": "separate pass after the timed region, events around every call",
                     "avg_launch_ms": avg_ms, "per_step_ms": per_step_ms,

@@ -603,6 +603,25 @@ int32_t rk_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *ta
                        rk_place_entry *entries, uint64_t cap_entries, uint32_t *status, float *total,
                        rk_place_result *result);
 
+/* GetBestPlan(j, placement) for a placement that is there already (Sec. 5.2,
+ * Algorithm 1, ScheduleJob after the search; Sec. 4.1: the bottleneck
+ * bandwidth of a communication group decides): for every job with parts in
+ * (place_off, entries) the best plan of the GPU count its parts add up to, at
+ * the CPU level and memory tier of assign[j], evaluated with the bandwidths of
+ * the actual node split - the selection rk_place_plans makes after placing,
+ * without placing anything and without waiting for the stream.  The parts must
+ * be in the order the job's ranks fill them (ascending nodes for the library's
+ * own placements).
+ *   assign     [device] n_jobs records: g, c, mem_gb locate the CPU level and tier
+ *              (amounts that are not on the grid give an empty record)
+ *   place_off  [device] n_jobs + 1 offsets into entries [device]
+ *   placed     [device] n_jobs records: the amounts placed, plan and throughput
+ *   total      [device] one float: sum of thr / ref_thr */
+int32_t rk_best_plan_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table,
+                            const rk_alloc_grid *grid, const rk_env *env, const rk_assign *assign,
+                            const uint32_t *place_off, const rk_place_entry *entries, rk_assign *placed,
+                            float *total);
+
 /* A whole round on nodes (Sec. 5.2, Algorithm 1): rk_schedule_round (with sla ==
  * NULL) or rk_schedule_round_sla against what the nodes hold together, then
  * rk_place_plans with the floors of the guaranteed jobs.  assign [device]
@@ -659,9 +678,9 @@ int32_t rk_schedule_round_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan
  *   stats      [device] five words or NULL: steps committed, jobs that needed
  *              more than a look, shrinks applied, steps taken back, 1 when the
  *              state was no placement
- * The result is what rk_place_plans keeps when it is given as the earlier
- * placement (every part is what first fit books for these amounts on that
- * split), which chooses the plan under the bandwidths of the actual split.
+ * GetBestPlan(j, placement) on the result: rk_best_plan_placed (rk_place_plans,
+ * given the result as the earlier placement, keeps it part by part and chooses
+ * the same plans).
  * Limits: RK_MAX_JOBS_PER_ROUND jobs, n_nodes * gpus_per_node <= 2^20.  One
  * workgroup runs the loop: the rule is sequential. */
 int32_t rk_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,

@@ -26,7 +26,7 @@ FIT_FIELDS = ("k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_con
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
            "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
            "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared", "rk_place", "rk_allocate_static", "rk_place_plans",
-           "rk_schedule_round_placed", "rk_reschedule", "rk_probe_stream", "rk_eval_best_plan", "rk_reschedule_nodes")
+           "rk_schedule_round_placed", "rk_reschedule", "rk_probe_stream", "rk_eval_best_plan", "rk_reschedule_nodes", "rk_best_plan_placed")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -329,6 +329,12 @@ def rk_reschedule_nodes(ctx, ref_thr, table, grid, nodes: "rk_nodes", best_thr, 
                                                    _ptr(prev_off), _ptr(prev_entries), C.c_uint64(n_prev_entries),
                                                    _ptr(assign), _ptr(place_off), _ptr(entries), C.c_uint64(cap_entries),
                                                    _ptr(total), _ptr(stats)))
+
+
+def rk_best_plan_placed(ctx, jobs: Jobs, table, grid, env, assign, place_off, entries, placed, total):
+    """GetBestPlan(j, placement) for a placement that is there already (device tensors)."""
+    _check(ctx, load_library().rk_best_plan_placed(ctx, C.byref(jobs.c), C.byref(table), C.byref(grid), C.byref(env),
+                                                   _ptr(assign), _ptr(place_off), _ptr(entries), _ptr(placed), _ptr(total)))
 
 
 def rk_probe_stream(ctx, buf, n_floats, mode, value=0.0, out=None):

@@ -537,7 +537,7 @@ struct ReplanArgs {
     const rk_assign *assign;         // what was asked for: fixes the CPU level and the memory tier
     const uint32_t *place_off;
     const rk_place_entry *entries;
-    const uint32_t *status;
+    const uint32_t *status;          // null: a job is placed when it has parts
     rk_assign *placed;
 };
 
@@ -551,7 +551,7 @@ __global__ __launch_bounds__(REPLAN_THREADS) void k_replan(ReplanArgs A) {
     const uint32_t j = blockIdx.x * (REPLAN_THREADS / 64) + (threadIdx.x >> 6);
     if (j >= A.n_jobs) return;
     rk_assign out = {0u, 0u, 0.f, RK_NO_PLAN, 0.f};
-    const uint32_t st = A.status[j];
+    const uint32_t st = A.status ? A.status[j] : (A.place_off[j + 1] > A.place_off[j] ? 1u : 0u);
     if (st == 1u || st == 2u) {
         const uint32_t e0 = A.place_off[j], e1 = A.place_off[j + 1];
         uint32_t run = 0, ge = 0;                          // GPUs so far; gcd of the boundaries this lane has seen
@@ -751,4 +751,33 @@ extern "C" int32_t rk_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_pla
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
     return rk_launch_place_plans(ctx, jobs, table, grid, env, nodes, best_thr, assign, min_seg, prev_off, prev_entries, placed,
                                  place_off, entries, cap_entries, status, total, result);
+}
+
+extern "C" int32_t rk_best_plan_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table,
+                                       const rk_alloc_grid *grid, const rk_env *env, const rk_assign *assign,
+                                       const uint32_t *place_off, const rk_place_entry *entries, rk_assign *placed,
+                                       float *total) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if (!jobs || !total || !place_off) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if ((rc = rk_check_table(ctx, table, 0, table ? table->n_jobs : 0))) return rc;
+    if (jobs->n_jobs != table->n_jobs) return rk_fail(ctx, RK_ERR_INVALID_ARG, "jobs and table disagree on n_jobs");
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    if ((rc = rk_check_env(ctx, env))) return rc;
+    const uint32_t n_jobs = table->n_jobs;
+    if (n_jobs > 0 && (!placed || !assign || !entries || !jobs->ref_thr)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (placed == assign) return rk_fail(ctx, RK_ERR_INVALID_ARG, "placed must not be the records it is chosen from");
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    if (n_jobs > 0) {
+        ReplanArgs R;
+        R.jobs = job_dev(jobs); R.tb = table_dev(table); R.grid = grid_dev(grid); R.env = *env;
+        R.n_jobs = n_jobs; R.option_mask = table->option_mask;
+        R.assign = assign; R.place_off = place_off; R.entries = entries; R.status = nullptr; R.placed = placed;
+        const uint32_t per = REPLAN_THREADS / 64;
+        k_replan<<<(n_jobs + per - 1) / per, REPLAN_THREADS, 0, ctx->stream>>>(R);
+        RK_CHECK_LAUNCH(ctx, "k_replan");
+    }
+    k_place_total<<<1, 1024, 0, ctx->stream>>>(n_jobs, placed, jobs->ref_thr, total);
+    RK_CHECK_LAUNCH(ctx, "k_place_total");
+    return RK_OK;
 }

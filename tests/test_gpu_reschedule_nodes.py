@@ -227,10 +227,29 @@ def test_generated_rounds_from_a_running_state(gpu, orc, name):
     used = np.zeros(n_nodes, np.int64)
     np.add.at(used, ent["node"], ent["g"])
     assert used.max() <= gpn
-    # GetBestPlan(j, placement): given as the earlier placement, every job keeps its parts and only the plan is chosen again
-    placed, p_off, p_ent, p_status, _, res = place_on_gpu(run, bt, a, floor_seg, *nodes, prev=(off, ent))
-    assert np.array_equal(p_off, off) and np.array_equal(p_ent, ent)
-    assert np.array_equal(p_status, (a["g"] > 0).astype(np.uint32)) and res.in_order == 1
+    # GetBestPlan(j, placement).  The oracle's placement that feeds the plan, given this placement as the earlier one,
+    # keeps every part and chooses the plans for the actual splits; so does rk_place_plans, and rk_best_plan_placed
+    # chooses them without placing anything
+    from types import SimpleNamespace
+    from test_gpu_placed import compare
+    w_placed = orc.place_plans(wl.coef, wl.ints, wl.bounds, tb, wl.grid, wl.env, bt, a, *nodes, min_seg=floor_seg, prev=(off, ent))
+    assert np.array_equal(w_placed[1], off) and np.array_equal(w_placed[2], ent)
+    got_pp = place_on_gpu(run, bt, a, floor_seg, *nodes, prev=(off, ent))
+    n_band = compare(orc, wl, tb, w_placed, got_pp)
+    assert got_pp[5].in_order == 1
+    import torch
+    dev = run.device
+    d_a = torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).copy()).to(dev)
+    d_off = torch.from_numpy(off.view(np.int32).copy()).to(dev)
+    d_ent = torch.from_numpy((ent if ent.size else np.zeros(1, rk.PLACE_DTYPE)).view(np.uint8).copy()).to(dev)
+    placed, total2 = rk.new_assign(J, dev), run.f32(1)
+    rk.rk_best_plan_placed(run.ctx, run.jobs, run.table.c, run.grid, run.env, d_a, d_off, d_ent, placed, total2)
+    rk.rk_sync(run.ctx)
+    on = (a["g"] > 0)
+    res = SimpleNamespace(n_entries=len(ent), n_placed=int(on.sum()), n_failed=0)
+    compare(orc, wl, tb, w_placed, (rk.assign_to_numpy(placed), off, ent, on.astype(np.uint32), float(total2[0].item()), res))
+    changed = int(((rk.assign_to_numpy(placed)["plan"] != a["plan"]) & on).sum())
+    print(f"{name}: the actual splits change the plan of {changed} of {int(on.sum())} jobs ({n_band} inside the tie band)", flush=True)
     run.close()
 
 

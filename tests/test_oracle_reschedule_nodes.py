@@ -322,6 +322,12 @@ def test_invariants_on_random_rounds_over_nodes():
             if moves == 0:
                 assert parts[j] == where[j]                    # nothing committed: nobody moved
         assert max(used_g) <= gpn and max(used_c) <= cpn       # no node holds more than it has
+        if not any(floors[j] and hold[j] < floors[j] and not state[j] for j in range(J)):
+            # nobody had to be served at a loss: every committed step raised the total (memory is plentiful here)
+            v = np.array(vals, np.float32)[:, :, 0, :]
+            best = [np.maximum.accumulate(np.concatenate([[0.0], np.maximum.accumulate(v[j], axis=0)[cur_c[j]]])) for j in range(J)]
+            before = sum(float(best[j][hold[j]]) for j in range(J))
+            assert total >= before * (1 - 1e-6), (trial, total, before)
         n += 1
         moved += moves > 0
         spread += any(len(p) > 1 for p in parts)
