@@ -278,8 +278,9 @@ int32_t rk_allocate_static(rk_ctx *ctx, const float *ref_thr, const rk_plan_tabl
                            rk_assign *assign, float *total);
 
 /* What the jobs of the table hold and are guaranteed, all [device], one entry
- * per job.  state: 0 the job takes part, 1 it takes no part and holds nothing
- * (NULL: all take part).  cur_seg: index of the GPU count it holds in its
+ * per job.  state: 0 the job takes part; 2 it keeps exactly what it holds (it
+ * takes no step and gives nothing: a job that must not be reconfigured now);
+ * any other value: it takes no part and holds nothing (NULL: all take part).  cur_seg: index of the GPU count it holds in its
  * list, -1 nothing; cur_c: the CPU level it holds.  floor_seg / floor_c: its
  * minimum demand as rk_min_res gives it (-1, or NULL: none). */
 typedef struct {
@@ -481,6 +482,10 @@ typedef struct {
 typedef struct {
     double dt;                  /* tick length, seconds, > 0 */
     uint32_t n_ticks;
+    uint32_t policy;            /* the round of every tick: 0 the greedy from scratch (as rk_allocate) with the
+                                   frozen jobs charged first; 1 Algorithm 1's Schedule loop from what the jobs
+                                   hold (as rk_reschedule: running jobs keep it unless a job with a higher
+                                   slope takes it; frozen jobs in state 2) */
     double gate;                /* threshold of the reconfiguration rule (the paper uses 0.97) */
 } rk_sim_options;
 
@@ -506,8 +511,11 @@ typedef struct {
  *   - a job is active when arrival <= t and it has not finished;
  *   - an active job holding GPUs is frozen unless T - (N+1)*delta > gate*T, with
  *     T the seconds it has held resources and N its reconfigurations so far;
- *   - one greedy round (as rk_allocate): inactive jobs take no part, frozen jobs
- *     keep their GPUs and CPUs and are charged for them first;
+ *   - one round: inactive jobs take no part, frozen jobs keep their GPUs and
+ *     CPUs.  Policy 0: the greedy from scratch (as rk_allocate), the frozen jobs
+ *     charged first.  Policy 1 (Sec. 5.2: the policy is triggered whenever jobs
+ *     are submitted or completed; here every tick): the Schedule loop from what
+ *     the jobs hold (as rk_reschedule, no floors);
  *   - a job that keeps running with different (GPUs, CPUs, plan) is reconfigured:
  *     N += 1 and delta seconds are owed; starting from or stopping at zero is free;
  *   - a job holding GPUs pays owed seconds out of the tick, then trains at the

@@ -363,7 +363,10 @@ struct Loop {
         const uint32_t m_top = grid->n_mem - 1;
         return s < 0 ? 0.0f : arr[rows * tb->seg_off[j] + ((uint64_t)c * grid->n_mem + m_top) * ns_of(j) + s];
     }
+    /* state 0: the job takes part; 2: it keeps exactly what it holds (it takes no step and gives nothing); anything
+       else: it takes no part and holds nothing */
     bool part(uint32_t j) const { return !state || state[j] == 0; }
+    bool holds(uint32_t j) const { return !state || state[j] == 0 || state[j] == 2; }
     /* the job's floor: a segment the job does not have counts as none, the CPU level is clamped to the grid */
     int64_t fl_s(uint32_t j) const {
         return (floor_seg && floor_seg[j] >= 0 && floor_seg[j] < ns_of(j)) ? floor_seg[j] : -1;
@@ -958,8 +961,10 @@ int ork_place_plans(uint32_t n_jobs, const float *coef, const uint32_t *ints, co
  *     same shrinks.
  *   - A job shrunk to nothing is preempted (best-effort jobs only: a job with
  *     a floor stops there).  Memory last, as in the greedy.
- * state[j] = 1: the job takes no part and holds nothing.  n_moves = steps
- * committed.  PARITY UNPINNED as a reading (the paper gives the outline);
+ * state[j] = 1 (or anything but 0 and 2): the job takes no part and holds
+ * nothing; 2: it keeps exactly what it holds, takes no step and gives nothing
+ * (a job that must not be reconfigured now, Sec. 5.2 "Incorporating
+ * reconfiguration penalty").  n_moves = steps committed.  PARITY UNPINNED as a reading (the paper gives the outline);
  * pinned by hand cases for every rule above, by the greedy and the exhaustive
  * optimum on concave curves from an empty cluster, and by invariants. */
 int ork_reschedule_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *tb, const ork_grid *grid,
@@ -983,7 +988,7 @@ int ork_reschedule_f32(uint32_t n_jobs, const float *ref_thr, const ork_table *t
     auto down_cpu = [&](uint32_t v) { return L.down_cpu(v); };
     uint64_t heldG = 0, heldC = 0;
     for (uint32_t j = 0; j < n_jobs; ++j) {
-        if (!part(j) || cur_seg[j] < 0 || cur_seg[j] >= ns_of(j) || cur_c[j] >= grid->n_cpu) continue;
+        if (!L.holds(j) || cur_seg[j] < 0 || cur_seg[j] >= ns_of(j) || cur_c[j] >= grid->n_cpu) continue;
         gi[j] = cur_seg[j]; ci[j] = cur_c[j];
         heldG += g_at(j, gi[j]); heldC += c_at(j, ci[j], gi[j]);
     }
@@ -1093,7 +1098,7 @@ int ork_reschedule_nodes_f32(uint32_t n_jobs, const float *ref_thr, const ork_ta
     };
 
     for (uint32_t j = 0; j < n_jobs; ++j) {
-        if (!L.part(j) || cur_seg[j] < 0 || cur_seg[j] >= L.ns_of(j) || cur_c[j] >= grid->n_cpu) continue;
+        if (!L.holds(j) || cur_seg[j] < 0 || cur_seg[j] >= L.ns_of(j) || cur_c[j] >= grid->n_cpu) continue;
         L.gi[j] = cur_seg[j]; L.ci[j] = cur_c[j];
         if (!prev_off || !prev_entries) return -1;          /* a running job is somewhere */
         uint64_t sum = 0;

@@ -11,9 +11,12 @@ Every tick of length dt, at time t = k*dt:
      reconfiguration keeps (T - (N+1)*delta) > gate*T, with T the time it has
      held resources and N its reconfigurations so far (the division-free form
      of the paper's ratio);
-  3. one greedy round over the resource sensitivity curves (computed once:
-     they do not depend on the cluster's state): inactive jobs take no part,
-     frozen jobs keep their GPUs and CPUs;
+  3. one round over the resource sensitivity curves (computed once: they do
+     not depend on the cluster's state): inactive jobs take no part, frozen
+     jobs keep their GPUs and CPUs.  policy "greedy": the from-scratch greedy
+     with the frozen jobs charged first; policy "loop": Algorithm 1's Schedule
+     loop from what the jobs hold (running jobs keep it unless a job with a
+     higher slope takes it; the policy is triggered every tick);
   4. a running job whose (GPUs, CPUs, plan) changed while it keeps running is
      reconfigured: N += 1 and delta seconds of checkpoint-resume are owed;
      starting from or stopping at zero GPUs is free;
@@ -31,7 +34,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import frozen_round
+from . import frozen_round, reschedule
 
 
 def level_of(grid, c, g):
@@ -43,7 +46,7 @@ def level_of(grid, c, g):
 
 
 def simulate(ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, arrival, work, delta, dt, n_ticks,
-             gate=0.97, trace=False):
+             gate=0.97, trace=False, policy="greedy"):
     J = table.n_jobs
     arrival, work, delta = (np.asarray(a, np.float64) for a in (arrival, work, delta))
     dt, gate = float(dt), float(gate)
@@ -68,8 +71,12 @@ def simulate(ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, arri
             may_move = held - (n_reconf.astype(np.float64) + 1.0) * delta > gate * held
         frozen = running & ~may_move
         state = np.where(~active, 1, np.where(frozen, 2, 0)).astype(np.uint8)
-        assign, total, _ = frozen_round(ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, state, seg_prev,
-                                        lvl_prev)
+        if policy == "loop":
+            assign, total, _ = reschedule(ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, seg_prev, lvl_prev,
+                                          state=state)
+        else:
+            assign, total, _ = frozen_round(ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, state, seg_prev,
+                                            lvl_prev)
         gpus_in_use[k] = assign["g"].sum()
         totals[k] = total
         frozen_count[k] = frozen.sum()

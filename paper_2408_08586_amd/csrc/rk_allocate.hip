@@ -1444,7 +1444,7 @@ __global__ void k_rs_prepare(RsArgs A) {
     if (j >= A.n_jobs) return;
     int32_t gi = -1;
     uint32_t ci = 0;
-    if (rs_part(A, j) && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < rs_ns(A, j) && A.cur_c[j] < A.X.grid.n_cpu) {
+    if (rs_holds(A, j) && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < rs_ns(A, j) && A.cur_c[j] < A.X.grid.n_cpu) {
         gi = A.cur_seg[j]; ci = A.cur_c[j];
     }
     A.st.gi[j] = gi; A.st.ci[j] = ci; A.st.g[j] = (uint32_t)rs_g(A, j, gi);
@@ -1908,6 +1908,16 @@ extern "C" int32_t rk_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_pla
     if (J > RK_MAX_JOBS_PER_ROUND)
         return rk_fail(ctx, RK_ERR_UNSUPPORTED, "%u jobs, the allocation kernels take up to %u", J, RK_MAX_JOBS_PER_ROUND);
     RK_HIP(ctx, hipSetDevice(ctx->device));
+    return rk_launch_reschedule(ctx, ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, jobs_state, assign, total,
+                                stats);
+}
+
+int32_t rk_launch_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table, const rk_alloc_grid *grid,
+                             const rk_cluster *cluster, const float *best_thr, const uint32_t *best_plan,
+                             const float *curve_thr, const rk_job_state *jobs_state, rk_assign *assign, float *total,
+                             uint32_t *stats) {
+    const uint32_t J = table->n_jobs;
+    int32_t rc;
     Arena arena = {nullptr, 0, 0};
     const size_t n = J ? J : 1;
     RsArgs A;

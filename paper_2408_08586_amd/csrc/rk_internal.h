@@ -149,3 +149,9 @@ int32_t rk_launch_place_plans(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_ta
                               const int32_t *min_seg, const uint32_t *prev_off, const rk_place_entry *prev_entries,
                               rk_assign *placed, uint32_t *place_off, rk_place_entry *entries,
                               uint64_t cap_entries, uint32_t *status, float *total, rk_place_result *result);
+
+// Algorithm 1's Schedule loop over the cluster's totals (arguments as rk_reschedule, already validated, device current)
+int32_t rk_launch_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table, const rk_alloc_grid *grid,
+                             const rk_cluster *cluster, const float *best_thr, const uint32_t *best_plan,
+                             const float *curve_thr, const rk_job_state *jobs_state, rk_assign *assign, float *total,
+                             uint32_t *stats);

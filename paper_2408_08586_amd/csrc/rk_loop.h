@@ -36,6 +36,10 @@ __device__ __forceinline__ float rs_at(const Args &A, const float *arr, uint32_t
 }
 template <class Args>
 __device__ __forceinline__ bool rs_part(const Args &A, uint32_t j) { return !A.state || A.state[j] == 0; }
+// state 2: the job keeps exactly what it holds (it takes no step and gives nothing); any other non-zero state: it takes
+// no part and holds nothing
+template <class Args>
+__device__ __forceinline__ bool rs_holds(const Args &A, uint32_t j) { return !A.state || A.state[j] == 0 || A.state[j] == 2; }
 // the job's floor: segment (-1: none; a segment the job does not have counts as none) and CPU level (clamped)
 template <class Args>
 __device__ __forceinline__ int32_t rs_fl_s(const Args &A, uint32_t j) {

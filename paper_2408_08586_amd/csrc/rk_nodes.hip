@@ -168,7 +168,7 @@ __global__ void k_nd_prepare(NdArgs A) {
     const uint32_t N = A.n_nodes;
     int32_t gi = -1;
     uint32_t ci = 0;
-    if (rs_part(A, j) && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < rs_ns(A, j) && A.cur_c[j] < A.X.grid.n_cpu) {
+    if (rs_holds(A, j) && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < rs_ns(A, j) && A.cur_c[j] < A.X.grid.n_cpu) {
         gi = A.cur_seg[j]; ci = A.cur_c[j];
     }
     A.st.gi[j] = gi; A.st.ci[j] = ci;

@@ -185,6 +185,7 @@ extern "C" int32_t rk_simulate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
     if (!(options->dt > 0.0)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "dt must be positive");
     if (options->gate != options->gate) return rk_fail(ctx, RK_ERR_INVALID_ARG, "gate is NaN");
+    if (options->policy > 1u) return rk_fail(ctx, RK_ERR_INVALID_ARG, "policy must be 0 (greedy round) or 1 (Schedule loop)");
     if (!(cluster->host_mem_gb >= 0.f)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "host_mem_gb negative or NaN");
     if (J > RK_MAX_JOBS_PER_ROUND)
         return rk_fail(ctx, RK_ERR_UNSUPPORTED, "%u jobs, the allocation kernels take up to %u", J, RK_MAX_JOBS_PER_ROUND);
@@ -235,9 +236,16 @@ extern "C" int32_t rk_simulate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
         k_sim_begin<<<1, SIM_THREADS, 0, s>>>(A);
         RK_CHECK_LAUNCH(ctx, "k_sim_begin");
         ctx->stream = s;                                       // the allocation enqueues on the context's stream
-        const int32_t r = rk_launch_allocate(ctx, ref_thr, A.tb, grid, 1, nullptr, nullptr, cluster, 0, J, J,
-                                             table->max_segs_per_job, best_thr, best_plan, curve_thr, nullptr, &A.F,
-                                             nullptr, assign, A.tick_total);
+        int32_t r;
+        if (options->policy == 1u) {                           // Algorithm 1's loop from what the jobs hold
+            const rk_job_state held = {A.F.state, A.S.seg, A.S.lvl, nullptr, nullptr};
+            r = rk_launch_reschedule(ctx, ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, &held, assign,
+                                     A.tick_total, nullptr);
+        } else {
+            r = rk_launch_allocate(ctx, ref_thr, A.tb, grid, 1, nullptr, nullptr, cluster, 0, J, J,
+                                   table->max_segs_per_job, best_thr, best_plan, curve_thr, nullptr, &A.F,
+                                   nullptr, assign, A.tick_total);
+        }
         ctx->stream = user;
         if (r) return r;
         k_sim_commit<<<(J + COMMIT_THREADS - 1) / COMMIT_THREADS, COMMIT_THREADS, 0, s>>>(A);

@@ -84,6 +84,7 @@ def random_round(rng, orc, J=None, g_max=None):
                 cur_seg[j], cur_c[j] = int(rng.choice(fit)), int(rng.integers(0, n_cpu))
                 left -= cur_seg[j] + 1
     state = (rng.uniform(size=J) < 0.1).astype(np.uint8)
+    state[rng.uniform(size=J) < 0.1] = 2                    # jobs that keep exactly what they hold
     coef = np.tile(workloads.tiny().coef[:1], (J, 1))
     coef[:, 16] = ref
     ints = np.tile(np.array([[1, math.lcm(*range(1, g_max + 1)), 1]], np.uint32), (J, 1))   # as table_for builds its table
@@ -116,7 +117,7 @@ def test_random_rounds_on_drawn_values(gpu, orc):
 def test_states_outside_their_ranges(gpu, orc):
     """What a caller may get wrong without an error: a held GPU count or CPU level the job does not have (the job then
     holds nothing), a floor that is no index of its list (no floor), a floor's CPU level beyond the grid (clamped), a
-    state byte other than 0 (takes no part), jobs that hold more than the cluster has.  Both sides read them alike."""
+    state byte other than 0 (2: keeps what it holds; anything else: takes no part), jobs that hold more than the cluster has.  Both sides read them alike."""
     n_moves = 0
     for seed in range(60):
         rng = np.random.default_rng(97000 + seed)
@@ -128,7 +129,7 @@ def test_states_outside_their_ranges(gpu, orc):
             elif u < 0.20: cur_c[j] = n_cpu + int(rng.integers(0, 3))
             elif u < 0.30: floor_seg[j] = g_max + int(rng.integers(0, 100))
             elif u < 0.40: floor_c[j] = n_cpu + int(rng.integers(0, 1000))
-            elif u < 0.45: state[j] = int(rng.choice([2, 7, 255]))
+            elif u < 0.45: state[j] = int(rng.choice([2, 3, 7, 255]))
             elif u < 0.50: cur_seg[j], floor_seg[j] = -5, -7
         cl = wl.cluster if seed % 3 else workloads.Cluster(wl.cluster.G // 3, wl.cluster.C // 3, wl.cluster.host_mem_gb)
         want = orc.reschedule(wl.coef[:, 16], tb, wl.grid, cl, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state=state)

@@ -82,7 +82,7 @@ def node_round(rng, orc, J=None, g_max=None, roomy=None, gpn=None, n_nodes=None)
     mem = float(rng.choice([8.0, 64.0, 1e6]))
     free_g, free_c = [gpn] * n_nodes, [cpn] * n_nodes
     off, ent = [0], []
-    cur_seg[state != 0] = -1                                 # (they hold nothing, also when the states are not passed)
+    cur_seg[(state != 0) & (state != 2)] = -1                # (they hold nothing, also when the states are not passed)
     for j in range(J):
         if cur_seg[j] >= 0:
             parts = first_fit(free_g, free_c, int(cur_seg[j]) + 1, int(grid.cpu_levels[cur_c[j]]))

@@ -17,7 +17,7 @@ def gpu():
     return DeviceRun
 
 
-def run_on_gpu(run, r, arrival, work, delta, dt, n_ticks, gate, cluster=None, curves=None):
+def run_on_gpu(run, r, arrival, work, delta, dt, n_ticks, gate, cluster=None, curves=None, policy=0):
     import paper_2408_08586_amd as rk
     torch = run.torch
     J = run.wl.n_jobs
@@ -26,7 +26,7 @@ def run_on_gpu(run, r, arrival, work, delta, dt, n_ticks, gate, cluster=None, cu
     bt, bp, ct = curves if curves is not None else (run.dev_f32(r["best_thr"]), run.dev_u32(r["best_plan"]),
                                                     run.dev_f32(r["curve_thr"]))
     rk.rk_simulate(run.ctx, run.jobs.ref_thr, run.table.c, run.grid, run.cluster if cluster is None else cluster, bt, bp, ct,
-                   f64(arrival), f64(work), f64(delta), dt, n_ticks, gate, res)
+                   f64(arrival), f64(work), f64(delta), dt, n_ticks, gate, res, policy=policy)
     rk.rk_sync(run.ctx)
     return dict(finish=res.finish.cpu().numpy()[:J], n_reconf=res.n_reconf.cpu().numpy()[:J].view(np.uint32),
                 progress=res.progress.cpu().numpy()[:J], held=res.held.cpu().numpy()[:J],
@@ -62,6 +62,36 @@ def test_simulation_is_identical_on_shared_curves(gpu, orc, name, hours, dt, n_t
     # a second run on the same context starts from a clean state
     got2 = run_on_gpu(run, r, tr.arrival, work, tr.delta, dt, n_ticks, 1.0)
     same(got2, got)
+    run.close()
+
+
+@pytest.mark.parametrize("name,hours,dt,n_ticks,scale", [("tiny", 0.5, 30.0, 200, 1.0), ("paper_scale", 2.0, 60.0, 300, 4.0),
+                                                         ("large", 4.0, 120.0, 150, 2.0)])
+def test_simulation_with_the_loop_as_its_policy(gpu, orc, name, hours, dt, n_ticks, scale):
+    """Algorithm 1's Schedule loop every tick (frozen jobs in state 2) instead of the greedy from scratch."""
+    wl = workloads.CONFIGS[name]()
+    r = orc.schedule_round(wl, n_threads=16)
+    tr = workloads.trace(wl.n_jobs, horizon_s=hours * 3600.0)
+    work = workloads.job_lengths_s(tr.u_duration) * wl.coef[:, 16] * scale
+    run = gpu(wl)
+    run.enumerate()
+    for gate in (0.97, -np.inf, 1.0):
+        want = orc.simulator.simulate(wl.coef[:, 16], r["table"], wl.grid, wl.cluster, r["best_thr"], r["best_plan"],
+                                      r["curve_thr"], tr.arrival, work, tr.delta, dt, n_ticks, gate=gate, policy="loop")
+        got = run_on_gpu(run, r, tr.arrival, work, tr.delta, dt, n_ticks, gate, policy=1)
+        same(got, want)
+        if gate == 0.97:
+            fin = want["finish"] >= 0
+            print(f"{name}, loop: {int(fin.sum())}/{wl.n_jobs} jobs finish, {int(want['n_reconf'].sum())} reconfigurations, "
+                  f"{int(want['frozen'].sum())} frozen job-ticks, mean JCT {np.mean((want['finish'] - tr.arrival)[fin]):.0f} s")
+            assert fin.sum() > 0
+    # the two policies on one context, one after the other: neither leaves anything behind for the other
+    a = run_on_gpu(run, r, tr.arrival, work, tr.delta, dt, n_ticks, 0.97, policy=0)
+    b = run_on_gpu(run, r, tr.arrival, work, tr.delta, dt, n_ticks, 0.97, policy=1)
+    same(a, orc.simulator.simulate(wl.coef[:, 16], r["table"], wl.grid, wl.cluster, r["best_thr"], r["best_plan"], r["curve_thr"],
+                                   tr.arrival, work, tr.delta, dt, n_ticks))
+    same(b, orc.simulator.simulate(wl.coef[:, 16], r["table"], wl.grid, wl.cluster, r["best_thr"], r["best_plan"], r["curve_thr"],
+                                   tr.arrival, work, tr.delta, dt, n_ticks, policy="loop"))
     run.close()
 
 

@@ -152,6 +152,25 @@ def test_jobs_are_taken_by_slope():
     assert a["g"].tolist() == [1, 0]
 
 
+def test_a_job_that_keeps_what_it_holds():
+    import oracle as orc
+    # state 2: the flat job keeps its four GPUs whatever the newcomer's slope (without the state it would give three)
+    a, _, moves = loop(orc, [FLAT, STEEP], 4, [4, 0], state=[2, 0])
+    assert a["g"].tolist() == [4, 0] and moves == 0
+    # ... it does not grow either, with a GPU free and a step worth taking
+    a, _, moves = loop(orc, [STEEP, FLAT], 4, [1, 0], state=[2, 0])
+    assert a["g"].tolist() == [1, 3] and moves == 3
+    # ... what it holds is not there for the others: three of four GPUs held, one left
+    a, _, _ = loop(orc, [FLAT, STEEP], 4, [3, 0], state=[2, 0])
+    assert a["g"].tolist() == [3, 1]
+    # ... not even for a job below its minimum
+    a, _, _ = loop(orc, [FLAT, STEEP], 4, [4, 0], floors=[0, 2], state=[2, 0])
+    assert a["g"].tolist() == [4, 0]
+    # any other state byte: the job takes no part and holds nothing
+    a, _, _ = loop(orc, [FLAT, STEEP], 4, [4, 0], state=[3, 0])
+    assert a["g"].tolist() == [0, 4]
+
+
 def test_cpus_after_gpus():
     import oracle as orc
     # one GPU each; CPU levels 1, 2, 4 for the job; values [job][level][g-1]

@@ -105,6 +105,13 @@ def test_the_job_to_shrink_is_one_of_this_node():
     assert parts == [{0: 1}, {}, {1: 1}] and moves == 1       # node 0: 0.7 stays; node 1: 0.2 goes
 
 
+def test_a_job_that_keeps_what_it_holds_is_not_asked():
+    import oracle as orc
+    # the flat job fills node 0 and must not be touched (state 2): the newcomer takes the two GPUs of node 1 and stops
+    a, parts, _, moves = nodes_loop(orc, [FLAT, STEEP], (2, 2, 99, 1e6), [{0: 2}, {}], state=[2, 0])
+    assert parts == [{0: 2}, {1: 2}] and moves == 2
+
+
 def test_a_shrunk_job_gives_this_node_first_then_its_last_parts():
     import oracle as orc
     # job 0 runs on 4 GPUs over three nodes and has plans for 1 and 4 only: it can only give three at once (0.3 lost)

@@ -56,25 +56,29 @@ def test_frozen_round_without_states_is_the_plain_greedy(orc):
     assert np.array_equal(a, r["assign"]) and total == r["total"] and gap == r["min_gap"]
 
 
-def lone_job(orc, work, arrival, delta=50.0, dt=60.0, n_ticks=40):
+def lone_job(orc, work, arrival, delta=50.0, dt=60.0, n_ticks=40, policy="greedy"):
     curve = [2.0, 3.5, 6.0, 8.0]
     _, (tb, grid, bt, bp, ct, ref) = tiny_round(orc, [curve], [0], [-1], [0], G=4)
     return orc.simulator.simulate(ref, tb, grid, workloads.Cluster(4, 100, 1e9), bt, bp, ct, [arrival], [work], [delta], dt,
-                                  n_ticks)
+                                  n_ticks, policy=policy)
 
 
-def test_lone_job_finishes_at_the_closed_form_time(orc):
-    # arrives at 130 s: first seen by the tick at 180 s; 4 GPUs give 6 samples/s
-    out = lone_job(orc, work=6.0 * 1000.0, arrival=130.0)
+@pytest.mark.parametrize("policy", ["greedy", "loop"])
+def test_lone_job_finishes_at_the_closed_form_time(orc, policy):
+    import functools
+    lone = functools.partial(lone_job, policy=policy)
+    # arrives at 130 s: first seen by the tick at 180 s; 4 GPUs give 6 samples/s (the loop gets there in three steps
+    # of one round: 1, 2, 4 GPUs)
+    out = lone(orc, work=6.0 * 1000.0, arrival=130.0)
     assert out["finish"][0] == pytest.approx(180.0 + 1000.0, rel=1e-15)
     assert out["n_reconf"][0] == 0 and out["progress"][0] == 6000.0
     assert out["held"][0] == 60.0 * 17                       # ticks at 180 ... 1140 s
     assert out["gpus_in_use"].tolist()[:3] == [0, 0, 0] and set(out["gpus_in_use"][3:20]) == {4} and out["gpus_in_use"][20] == 0
     # arrival exactly on a tick counts for that tick; work that ends exactly with a tick
-    out = lone_job(orc, work=6.0 * 120.0, arrival=120.0)
+    out = lone(orc, work=6.0 * 120.0, arrival=120.0)
     assert out["finish"][0] == 240.0
     # never finishing inside the horizon
-    out = lone_job(orc, work=1e9, arrival=0.0)
+    out = lone(orc, work=1e9, arrival=0.0)
     assert out["finish"][0] == -1.0 and out["progress"][0] == pytest.approx(6.0 * 60.0 * 40)
 
 
@@ -135,3 +139,60 @@ def test_simulation_conserves_what_it_should(orc):
     # a stricter gate can only reduce reconfigurations to zero; with no gate none is frozen
     assert orc.simulator.simulate(*args, gate=1.0)["n_reconf"].sum() == 0
     assert orc.simulator.simulate(*args, gate=-np.inf)["frozen"].sum() == 0
+
+
+def test_the_loop_as_the_policy_of_the_simulation(orc):
+    """Algorithm 1's loop every tick instead of the from-scratch greedy: running jobs keep what they hold unless a job
+    with a higher slope takes it, and a job the gate freezes is not asked at all."""
+    a_curve, b_curve = [1.0, 1.8, 2.4, 2.8], [1.5, 3.0, 5.0, 5.5]
+    _, (tb, grid, bt, bp, ct, ref) = tiny_round(orc, [a_curve, b_curve], [0, 0], [-1, -1], [0, 0], G=8)
+
+    def run(gate, delta_a=30.0, policy="loop"):
+        return orc.simulator.simulate(ref, tb, grid, workloads.Cluster(8, 100, 1e9), bt, bp, ct, [0.0, 300.0], [1e9, 1e9],
+                                      [delta_a, 10.0], 60.0, 60, gate=gate, trace=True, policy=policy)
+    # A alone climbs to 8 GPUs; B arrives at 300 s.  Its first GPU is worth 1.5 and makes A give four (0.4 lost), the
+    # next three are free by then; the step to 8 (0.125 per GPU) is not worth A's 0.3 per GPU: 4 + 4
+    out = run(-np.inf)
+    g_a, g_b = [int(h["g"][0]) for h in out["history"]], [int(h["g"][1]) for h in out["history"]]
+    assert g_a[:5] == [8] * 5 and g_a[5:] == [4] * 55 and g_b[:5] == [0] * 5 and g_b[5:] == [4] * 55
+    assert out["n_reconf"].tolist() == [1, 0]
+    # with the gate A is frozen until T > 1000 s (the tick with k = 17), and a frozen job gives nothing
+    out = run(0.97)
+    g_a, g_b = [int(h["g"][0]) for h in out["history"]], [int(h["g"][1]) for h in out["history"]]
+    assert g_a[:17] == [8] * 17 and g_a[17:] == [4] * 43 and g_b[:17] == [0] * 17 and g_b[17:] == [4] * 43
+    assert out["frozen"][:17].tolist() == [0] + [1] * 16
+    assert out["progress"][0] == pytest.approx(2.8 * 60 * 17 + 2.4 * 30 + 2.4 * 60 * (60 - 18))
+    # where the two policies part: B's first GPU would cost A more than it brings (A gives four at once and loses 2.0,
+    # B gains 1.5), so the loop leaves A alone for good, while a round from scratch shares the cluster
+    _, (tb2, grid2, bt2, bp2, ct2, ref2) = tiny_round(orc, [[1.0, 2.0, 4.0, 6.0], b_curve], [0, 0], [-1, -1], [0, 0], G=8)
+    args = (ref2, tb2, grid2, workloads.Cluster(8, 100, 1e9), bt2, bp2, ct2, [0.0, 300.0], [1e9, 1e9], [30.0, 10.0], 60.0, 20)
+    loop = orc.simulator.simulate(*args, gate=-np.inf, trace=True, policy="loop")
+    scratch = orc.simulator.simulate(*args, gate=-np.inf, trace=True)
+    assert [int(h["g"][1]) for h in loop["history"]] == [0] * 20
+    assert [int(h["g"][1]) for h in scratch["history"]][5:] == [4] * 15
+
+
+def test_simulation_with_the_loop_conserves_what_it_should(orc):
+    wl = workloads.paper_scale()
+    r = orc.schedule_round(wl, n_threads=4)
+    tr = workloads.trace(wl.n_jobs, horizon_s=2 * 3600.0)
+    work = workloads.job_lengths_s(tr.u_duration) * wl.coef[:, 16] * 4
+    args = (wl.coef[:, 16], r["table"], wl.grid, wl.cluster, r["best_thr"], r["best_plan"], r["curve_thr"], tr.arrival, work,
+            tr.delta, 60.0, 300)
+    out = orc.simulator.simulate(*args, trace=True, policy="loop")
+    fin = out["finish"] >= 0
+    assert 10 < fin.sum() < wl.n_jobs
+    assert np.all(out["gpus_in_use"] <= wl.cluster.G)
+    assert np.all(out["finish"][fin] > tr.arrival[fin]) and np.all(out["progress"][fin] == work[fin])
+    assert np.all(out["progress"][~fin] < work[~fin])
+    for k, h in enumerate(out["history"]):
+        t = 60.0 * k
+        assert np.all(h["g"][tr.arrival > t] == 0)
+        assert np.all(h["g"][fin & (out["finish"] <= t)] == 0)
+    assert orc.simulator.simulate(*args, gate=1.0, policy="loop")["n_reconf"].sum() == 0
+    assert orc.simulator.simulate(*args, gate=-np.inf, policy="loop")["frozen"].sum() == 0
+    # running jobs keep what they hold: fewer reconfigurations than rounds from scratch make on the same trace
+    scratch = orc.simulator.simulate(*args, gate=-np.inf)
+    loop = orc.simulator.simulate(*args, gate=-np.inf, policy="loop")
+    print("reconfigurations without a gate: from scratch", int(scratch["n_reconf"].sum()), "loop", int(loop["n_reconf"].sum()))
+    assert loop["n_reconf"].sum() < scratch["n_reconf"].sum()
