@@ -524,15 +524,28 @@ def sim_bench(rk, ctx, dev, reps):
         torch.cuda.synchronize()
         if i:
             wall.append((time.perf_counter() - t0) * 1e3)
-    fin = res.finish.cpu().numpy()[:J]
-    done = fin >= 0
-    ms = float(np.median(wall))
-    return {"entry": "rk_job_curves once + rk_simulate", "jobs": J, "gpus": int(wl.cluster.G), "ticks": n_ticks,
-            "tick_s": 60.0, "gate": 0.97, "curves_ms": a.elapsed_time(b), "simulate_ms": ms, "ms_per_tick": ms / n_ticks,
-            "ticks_per_s": n_ticks / (ms * 1e-3), "jobs_finished": int(done.sum()),
-            "mean_jct_s": float(np.mean((fin - tr.arrival)[done])) if done.any() else None,
-            "reconfigurations": int(res.n_reconf.cpu().numpy()[:J].sum()),
-            "mean_gpus_in_use": float(res.gpus_in_use.cpu().numpy()[:n_ticks].mean())}
+    def summary(ms):
+        fin = res.finish.cpu().numpy()[:J]
+        done = fin >= 0
+        return {"simulate_ms": ms, "ms_per_tick": ms / n_ticks, "ticks_per_s": n_ticks / (ms * 1e-3),
+                "jobs_finished": int(done.sum()),
+                "mean_jct_s": float(np.mean((fin - tr.arrival)[done])) if done.any() else None,
+                "reconfigurations": int(res.n_reconf.cpu().numpy()[:J].sum()),
+                "mean_gpus_in_use": float(res.gpus_in_use.cpu().numpy()[:n_ticks].mean())}
+    out = {"entry": "rk_job_curves once + rk_simulate", "jobs": J, "gpus": int(wl.cluster.G), "ticks": n_ticks,
+           "tick_s": 60.0, "gate": 0.97, "curves_ms": a.elapsed_time(b), **summary(float(np.median(wall)))}
+    # the same trace with Algorithm 1's Schedule loop as the round of every tick (running jobs keep what they hold)
+    wall = []
+    for i in range(reps + 1):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rk.rk_simulate(ctx, jobs.ref_thr, table.c, grid, cluster, bt, bp, ct, arrival, work_d, delta, 60.0, n_ticks, 0.97, res,
+                       policy=1)
+        torch.cuda.synchronize()
+        if i:
+            wall.append((time.perf_counter() - t0) * 1e3)
+    out["schedule_loop_policy"] = summary(float(np.median(wall)))
+    return out
 
 
 def main():
