@@ -479,14 +479,26 @@ typedef struct {
     const double *delta;        /* checkpoint-resume cost of one reconfiguration, seconds */
 } rk_trace;
 
+/* Nodes of the cluster, all alike. */
+#define RK_MAX_NODES 4096u
+typedef struct {
+    uint32_t n_nodes;           /* 1..RK_MAX_NODES */
+    uint32_t gpus_per_node;     /* 1..65535 */
+    uint32_t cpus_per_node;     /* 0..65535 */
+    float mem_per_node_gb;      /* GiB of host memory */
+} rk_nodes;
+
 typedef struct {
     double dt;                  /* tick length, seconds, > 0 */
     uint32_t n_ticks;
     uint32_t policy;            /* the round of every tick: 0 the greedy from scratch (as rk_allocate) with the
                                    frozen jobs charged first; 1 Algorithm 1's Schedule loop from what the jobs
                                    hold (as rk_reschedule: running jobs keep it unless a job with a higher
-                                   slope takes it; frozen jobs in state 2) */
+                                   slope takes it; frozen jobs in state 2); 2 the same loop over nodes */
     double gate;                /* threshold of the reconfiguration rule (the paper uses 0.97) */
+    const rk_nodes *nodes;      /* [host] policy 2 only (otherwise not read): the loop searches node by node (as
+                                   rk_reschedule_nodes) from the placement the last tick left; the grid's CPU
+                                   levels must be per GPU */
 } rk_sim_options;
 
 /* Results, all [device]; per job: finish (seconds, -1 if unfinished), n_reconf,
@@ -528,15 +540,6 @@ int32_t rk_simulate(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *tabl
                     const rk_alloc_grid *grid, const rk_cluster *cluster,
                     const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
                     const rk_trace *trace, const rk_sim_options *options, const rk_sim_result *result);
-
-/* Nodes of the cluster, all alike. */
-#define RK_MAX_NODES 4096u
-typedef struct {
-    uint32_t n_nodes;           /* 1..RK_MAX_NODES */
-    uint32_t gpus_per_node;     /* 1..65535 */
-    uint32_t cpus_per_node;     /* 0..65535 */
-    float mem_per_node_gb;      /* GiB of host memory */
-} rk_nodes;
 
 /* One part of a job's placement: g GPUs, c CPUs and mem_gb GiB on a node. */
 typedef struct { uint32_t node, g, c; float mem_gb; } rk_place_entry;

@@ -16,7 +16,9 @@ Every tick of length dt, at time t = k*dt:
      jobs keep their GPUs and CPUs.  policy "greedy": the from-scratch greedy
      with the frozen jobs charged first; policy "loop": Algorithm 1's Schedule
      loop from what the jobs hold (running jobs keep it unless a job with a
-     higher slope takes it; the policy is triggered every tick);
+     higher slope takes it; the policy is triggered every tick); policy
+     "nodes": the same loop with ScheduleJob searching node by node, from the
+     placement the last tick left (nodes = (n, GPUs, CPUs, GiB per node));
   4. a running job whose (GPUs, CPUs, plan) changed while it keeps running is
      reconfigured: N += 1 and delta seconds of checkpoint-resume are owed;
      starting from or stopping at zero GPUs is free;
@@ -34,7 +36,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import frozen_round, reschedule
+from . import PLACE_DTYPE, frozen_round, reschedule, reschedule_nodes
 
 
 def level_of(grid, c, g):
@@ -46,7 +48,7 @@ def level_of(grid, c, g):
 
 
 def simulate(ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, arrival, work, delta, dt, n_ticks,
-             gate=0.97, trace=False, policy="greedy"):
+             gate=0.97, trace=False, policy="greedy", nodes=None):
     J = table.n_jobs
     arrival, work, delta = (np.asarray(a, np.float64) for a in (arrival, work, delta))
     dt, gate = float(dt), float(gate)
@@ -62,7 +64,8 @@ def simulate(ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, arri
     gpus_in_use = np.zeros(n_ticks, np.uint32)
     totals = np.zeros(n_ticks, np.float64)
     frozen_count = np.zeros(n_ticks, np.uint32)
-    history = []
+    history, placements = [], []
+    where = (np.zeros(J + 1, np.uint32), np.zeros(0, PLACE_DTYPE))       # nobody is anywhere yet
     for k in range(n_ticks):
         t = float(k) * dt
         active = (arrival <= t) & ~done
@@ -71,7 +74,13 @@ def simulate(ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, arri
             may_move = held - (n_reconf.astype(np.float64) + 1.0) * delta > gate * held
         frozen = running & ~may_move
         state = np.where(~active, 1, np.where(frozen, 2, 0)).astype(np.uint8)
-        if policy == "loop":
+        if policy == "nodes":
+            res = reschedule_nodes(ref_thr, table, grid, *nodes, best_thr, best_plan, curve_thr, seg_prev, lvl_prev, where,
+                                   state=state)
+            assert res is not None, "what the jobs hold and where they are have come apart"
+            assign, p_off, p_ent, total, _ = res
+            where = (p_off, p_ent)
+        elif policy == "loop":
             assign, total, _ = reschedule(ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, seg_prev, lvl_prev,
                                           state=state)
         else:
@@ -105,8 +114,10 @@ def simulate(ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, arri
                 g_prev[j], c_prev[j], plan_prev[j], seg_prev[j], lvl_prev[j] = 0, 0, 0xFFFFFFFF, -1, 0
         if trace:
             history.append(assign.copy())
+            placements.append(where)
     out = dict(finish=finish, n_reconf=n_reconf, progress=progress, held=held, gpus_in_use=gpus_in_use, totals=totals,
                frozen=frozen_count)
     if trace:
         out["history"] = history
+        out["placements"] = placements
     return out

@@ -88,7 +88,8 @@ class rk_trace(C.Structure):
 
 
 class rk_sim_options(C.Structure):
-    _fields_ = [("dt", C.c_double), ("n_ticks", C.c_uint32), ("policy", C.c_uint32), ("gate", C.c_double)]
+    _fields_ = [("dt", C.c_double), ("n_ticks", C.c_uint32), ("policy", C.c_uint32), ("gate", C.c_double),
+                ("nodes", C.c_void_p)]
 
 
 class rk_sim_result(C.Structure):
@@ -463,10 +464,12 @@ class SimResult:
 
 
 def rk_simulate(ctx, ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, arrival, work, delta, dt, n_ticks,
-                gate, result: SimResult, policy=0):
-    """arrival, work, delta: float64 device tensors.  policy 0: greedy round every tick, 1: Algorithm 1's loop."""
+                gate, result: SimResult, policy=0, nodes=None):
+    """arrival, work, delta: float64 device tensors.  policy 0: greedy round every tick, 1: Algorithm 1's loop,
+    2: that loop over the nodes (nodes: rk_nodes)."""
     tr = rk_trace(arrival.data_ptr(), work.data_ptr(), delta.data_ptr())
-    opt = rk_sim_options(float(dt), int(n_ticks), int(policy), float(gate))
+    opt = rk_sim_options(float(dt), int(n_ticks), int(policy), float(gate),
+                         None if nodes is None else C.cast(C.pointer(nodes), C.c_void_p))
     _check(ctx, load_library().rk_simulate(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.byref(cluster),
                                            _ptr(best_thr), _ptr(best_plan), _ptr(curve_thr), C.byref(tr), C.byref(opt),
                                            C.byref(result.c)))

@@ -50,6 +50,7 @@ enum {
     SL_RS_F32, SL_RS_U32, SL_RS_U64,                     // the Schedule loop: cached slopes; order, marks and saved states; CPU needs
     SL_EVAL_PARTIAL,                                     // evaluation with best plan: keys of the segments that span tiles
     SL_PLACE_KEEP,                                       // placement: which jobs keep their earlier parts
+    SL_SIM_PLACES,                                       // simulation over nodes: where the jobs are, where they go
     SL_ND_NODES, SL_ND_U32, SL_ND_F32, SL_ND_U64,        // the Schedule loop over nodes: node tables and their copy; per-job words
     SL_COUNT
 };
@@ -155,3 +156,11 @@ int32_t rk_launch_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_plan_ta
                              const rk_cluster *cluster, const float *best_thr, const uint32_t *best_plan,
                              const float *curve_thr, const rk_job_state *jobs_state, rk_assign *assign, float *total,
                              uint32_t *stats);
+// ... and over its nodes (arguments as rk_reschedule_nodes, already validated, device current; entries holds at least
+// n_nodes * gpus_per_node records)
+int32_t rk_launch_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                                   const rk_alloc_grid *grid, const rk_nodes *nodes, const float *best_thr,
+                                   const uint32_t *best_plan, const float *curve_thr, const rk_job_state *jobs_state,
+                                   const uint32_t *prev_off, const rk_place_entry *prev_entries, uint64_t n_prev_entries,
+                                   rk_assign *assign, uint32_t *place_off, rk_place_entry *entries, float *total,
+                                   uint32_t *stats);

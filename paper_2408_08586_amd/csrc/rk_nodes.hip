@@ -813,6 +813,19 @@ extern "C" int32_t rk_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const 
     if (cap_entries < gpus && J > 0) return rk_fail(ctx, RK_ERR_CAPACITY, "entries: %llu records, %llu may be needed", (unsigned long long)cap_entries, (unsigned long long)gpus);
     if (J > 0 && !entries) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
     RK_HIP(ctx, hipSetDevice(ctx->device));
+    return rk_launch_reschedule_nodes(ctx, ref_thr, table, grid, nodes, best_thr, best_plan, curve_thr, jobs_state, prev_off,
+                                      prev_entries, n_prev_entries, assign, place_off, entries, total, stats);
+}
+
+int32_t rk_launch_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                                   const rk_alloc_grid *grid, const rk_nodes *nodes, const float *best_thr,
+                                   const uint32_t *best_plan, const float *curve_thr, const rk_job_state *jobs_state,
+                                   const uint32_t *prev_off, const rk_place_entry *prev_entries, uint64_t n_prev_entries,
+                                   rk_assign *assign, uint32_t *place_off, rk_place_entry *entries, float *total,
+                                   uint32_t *stats) {
+    const uint32_t J = table->n_jobs;
+    const uint64_t gpus = (uint64_t)nodes->n_nodes * nodes->gpus_per_node;
+    int32_t rc;
     const size_t n = J ? J : 1, N = nodes->n_nodes;
     const size_t nodes_words = 3 * N + 2 * (size_t)gpus;
     uint32_t *w_nodes, *w_jobs;

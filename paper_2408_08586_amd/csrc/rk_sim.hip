@@ -44,6 +44,9 @@ struct SimArgs {
     double *held;               // result arrays or scratch when the caller passes none
     double *progress, *finish;
     uint32_t *n_reconf;
+    // the search over nodes only: where the jobs are (left by the last tick) and where this tick puts them
+    uint32_t *at_off, *now_off;
+    rk_place_entry *at_ent, *now_ent;
 };
 
 __global__ __launch_bounds__(SIM_THREADS) void k_sim_init(SimArgs A) {
@@ -53,6 +56,14 @@ __global__ __launch_bounds__(SIM_THREADS) void k_sim_init(SimArgs A) {
     A.S.owed[j] = 0.0; A.S.done[j] = 0;
     A.held[j] = 0.0; A.progress[j] = 0.0; A.finish[j] = -1.0; A.n_reconf[j] = 0;
     if (j == 0) *A.tick = 0xFFFFFFFFu;                    // the first k_sim_begin makes it 0
+    if (A.at_off) { A.at_off[j] = 0u; if (j == 0) A.at_off[A.n_jobs] = 0u; }   // nobody is anywhere yet
+}
+
+// the placement this tick made is where the jobs are when the next tick begins
+__global__ void k_sim_keep_placement(SimArgs A) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i <= A.n_jobs) A.at_off[i] = A.now_off[i];
+    if (i < A.now_off[A.n_jobs]) A.at_ent[i] = A.now_ent[i];
 }
 
 __global__ __launch_bounds__(SIM_THREADS) void k_sim_begin(SimArgs A) {
@@ -185,7 +196,20 @@ extern "C" int32_t rk_simulate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
         return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
     if (!(options->dt > 0.0)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "dt must be positive");
     if (options->gate != options->gate) return rk_fail(ctx, RK_ERR_INVALID_ARG, "gate is NaN");
-    if (options->policy > 1u) return rk_fail(ctx, RK_ERR_INVALID_ARG, "policy must be 0 (greedy round) or 1 (Schedule loop)");
+    if (options->policy > 2u)
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "policy must be 0 (greedy round), 1 (Schedule loop) or 2 (Schedule loop over nodes)");
+    const rk_nodes *nodes = options->policy == 2u ? options->nodes : nullptr;
+    uint64_t cap_parts = 0;
+    if (options->policy == 2u) {
+        if (!nodes) return rk_fail(ctx, RK_ERR_INVALID_ARG, "policy 2 needs the nodes");
+        if (nodes->n_nodes == 0 || nodes->n_nodes > RK_MAX_NODES || nodes->gpus_per_node == 0 ||
+            nodes->gpus_per_node > 65535u || nodes->cpus_per_node > 65535u || !(nodes->mem_per_node_gb >= 0.f))
+            return rk_fail(ctx, RK_ERR_INVALID_ARG, "nodes: 1..%u nodes of 1..65535 GPUs, at most 65535 CPUs, memory >= 0", RK_MAX_NODES);
+        if (grid->cpu_mode != 1u)
+            return rk_fail(ctx, RK_ERR_UNSUPPORTED, "the search over nodes needs CPU levels per GPU (cpu_mode 1)");
+        cap_parts = (uint64_t)nodes->n_nodes * nodes->gpus_per_node;
+        if (cap_parts > (1u << 20)) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 2^20 GPUs on the nodes");
+    }
     if (!(cluster->host_mem_gb >= 0.f)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "host_mem_gb negative or NaN");
     if (J > RK_MAX_JOBS_PER_ROUND)
         return rk_fail(ctx, RK_ERR_UNSUPPORTED, "%u jobs, the allocation kernels take up to %u", J, RK_MAX_JOBS_PER_ROUND);
@@ -219,6 +243,15 @@ extern "C" int32_t rk_simulate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
     A.n_reconf = result->n_reconf ? result->n_reconf : s_nrec;
     A.assign = assign;
 
+    A.at_off = A.now_off = nullptr; A.at_ent = A.now_ent = nullptr;
+    if (nodes) {                                               // two placements: where the jobs are, where they go
+        char *pl;
+        const size_t off_bytes = (((size_t)J + 1) * 4 + 255) & ~(size_t)255;
+        const size_t ent_bytes = ((size_t)cap_parts * sizeof(rk_place_entry) + 255) & ~(size_t)255;
+        if ((rc = rk_scratch(ctx, SL_SIM_PLACES, 2 * (off_bytes + ent_bytes), (void **)&pl))) return rc;
+        A.at_off = (uint32_t *)pl; A.now_off = (uint32_t *)(pl + off_bytes);
+        A.at_ent = (rk_place_entry *)(pl + 2 * off_bytes); A.now_ent = (rk_place_entry *)(pl + 2 * off_bytes + ent_bytes);
+    }
     A.tick = reinterpret_cast<uint32_t *>(A.F.cap0 + 4);       // inside the 256-byte capacity block
     A.tick_total = reinterpret_cast<float *>(A.F.cap0 + 5);
 
@@ -237,7 +270,11 @@ extern "C" int32_t rk_simulate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
         RK_CHECK_LAUNCH(ctx, "k_sim_begin");
         ctx->stream = s;                                       // the allocation enqueues on the context's stream
         int32_t r;
-        if (options->policy == 1u) {                           // Algorithm 1's loop from what the jobs hold
+        if (options->policy == 2u) {                           // ... searching node by node, from where the jobs are
+            const rk_job_state held = {A.F.state, A.S.seg, A.S.lvl, nullptr, nullptr};
+            r = rk_launch_reschedule_nodes(ctx, ref_thr, table, grid, nodes, best_thr, best_plan, curve_thr, &held, A.at_off,
+                                           A.at_ent, cap_parts, assign, A.now_off, A.now_ent, A.tick_total, nullptr);
+        } else if (options->policy == 1u) {                    // Algorithm 1's loop from what the jobs hold
             const rk_job_state held = {A.F.state, A.S.seg, A.S.lvl, nullptr, nullptr};
             r = rk_launch_reschedule(ctx, ref_thr, table, grid, cluster, best_thr, best_plan, curve_thr, &held, assign,
                                      A.tick_total, nullptr);
@@ -250,6 +287,11 @@ extern "C" int32_t rk_simulate(rk_ctx *ctx, const float *ref_thr, const rk_plan_
         if (r) return r;
         k_sim_commit<<<(J + COMMIT_THREADS - 1) / COMMIT_THREADS, COMMIT_THREADS, 0, s>>>(A);
         RK_CHECK_LAUNCH(ctx, "k_sim_commit");
+        if (nodes) {
+            const uint64_t most = cap_parts > J + 1 ? cap_parts : J + 1;
+            k_sim_keep_placement<<<(uint32_t)((most + 255) / 256), 256, 0, s>>>(A);
+            RK_CHECK_LAUNCH(ctx, "k_sim_keep_placement");
+        }
         return RK_OK;
     };
 

@@ -17,7 +17,7 @@ def gpu():
     return DeviceRun
 
 
-def run_on_gpu(run, r, arrival, work, delta, dt, n_ticks, gate, cluster=None, curves=None, policy=0):
+def run_on_gpu(run, r, arrival, work, delta, dt, n_ticks, gate, cluster=None, curves=None, policy=0, nodes=None):
     import paper_2408_08586_amd as rk
     torch = run.torch
     J = run.wl.n_jobs
@@ -26,7 +26,8 @@ def run_on_gpu(run, r, arrival, work, delta, dt, n_ticks, gate, cluster=None, cu
     bt, bp, ct = curves if curves is not None else (run.dev_f32(r["best_thr"]), run.dev_u32(r["best_plan"]),
                                                     run.dev_f32(r["curve_thr"]))
     rk.rk_simulate(run.ctx, run.jobs.ref_thr, run.table.c, run.grid, run.cluster if cluster is None else cluster, bt, bp, ct,
-                   f64(arrival), f64(work), f64(delta), dt, n_ticks, gate, res, policy=policy)
+                   f64(arrival), f64(work), f64(delta), dt, n_ticks, gate, res, policy=policy,
+                   nodes=None if nodes is None else rk.rk_nodes(*nodes))
     rk.rk_sync(run.ctx)
     return dict(finish=res.finish.cpu().numpy()[:J], n_reconf=res.n_reconf.cpu().numpy()[:J].view(np.uint32),
                 progress=res.progress.cpu().numpy()[:J], held=res.held.cpu().numpy()[:J],
@@ -92,6 +93,45 @@ def test_simulation_with_the_loop_as_its_policy(gpu, orc, name, hours, dt, n_tic
                                    tr.arrival, work, tr.delta, dt, n_ticks))
     same(b, orc.simulator.simulate(wl.coef[:, 16], r["table"], wl.grid, wl.cluster, r["best_thr"], r["best_plan"], r["curve_thr"],
                                    tr.arrival, work, tr.delta, dt, n_ticks, policy="loop"))
+    run.close()
+
+
+@pytest.mark.parametrize("name", ["large", "trace_scale"])
+def test_simulation_over_nodes(gpu, orc, name):
+    """The loop with ScheduleJob searching node by node as the round of every tick: where the jobs are is carried from
+    tick to tick on the device as in the oracle's simulation."""
+    if name == "large":
+        wl, nodes, hours, dt, n_ticks, scale = workloads.large(), (128, 8, 128, 2048.0), 4.0, 120.0, 100, 2.0
+    else:                                                    # the trace experiment's shape with CPUs per GPU
+        base = workloads.trace_scale()
+        grid = workloads.Grid(np.array([1, 2, 4, 8, 16], np.uint32), 1, np.array([64.0], np.float32), 0)
+        wl = workloads.Workload("trace_scale_per_gpu", base.coef, base.ints, base.bounds, grid, base.env,
+                                workloads.Cluster(64, 8 * 128, 8 * 512.0))
+        nodes, hours, dt, n_ticks, scale = (8, 8, 128, 512.0), 12.0, 60.0, 360, 4.0
+    r = orc.schedule_round(wl, n_threads=16)
+    tr = workloads.trace(wl.n_jobs, horizon_s=hours * 3600.0)
+    work = workloads.job_lengths_s(tr.u_duration) * wl.coef[:, 16] * scale
+    run = gpu(wl)
+    run.enumerate()
+    for gate in (0.97, -np.inf):
+        want = orc.simulator.simulate(wl.coef[:, 16], r["table"], wl.grid, wl.cluster, r["best_thr"], r["best_plan"],
+                                      r["curve_thr"], tr.arrival, work, tr.delta, dt, n_ticks, gate=gate, policy="nodes",
+                                      nodes=nodes)
+        got = run_on_gpu(run, r, tr.arrival, work, tr.delta, dt, n_ticks, gate, policy=2, nodes=nodes)
+        same(got, want)
+        if gate == 0.97:
+            fin = want["finish"] >= 0
+            print(f"{name}, over nodes: {int(fin.sum())}/{wl.n_jobs} jobs finish, {int(want['n_reconf'].sum())} reconfigurations, "
+                  f"{int(want['frozen'].sum())} frozen job-ticks, mean GPUs in use {want['gpus_in_use'].mean():.1f}")
+            assert fin.sum() > 0
+    # the other policies still run on this context afterwards
+    same(run_on_gpu(run, r, tr.arrival, work, tr.delta, dt, 20, 0.97, policy=1),
+         orc.simulator.simulate(wl.coef[:, 16], r["table"], wl.grid, wl.cluster, r["best_thr"], r["best_plan"], r["curve_thr"],
+                                tr.arrival, work, tr.delta, dt, 20, policy="loop"))
+    import paper_2408_08586_amd as rk
+    with pytest.raises(rk.RkError) as e:
+        run_on_gpu(run, r, tr.arrival, work, tr.delta, dt, 5, 0.97, policy=2)            # no nodes
+    assert e.value.code == rk.RK_ERR_INVALID_ARG
     run.close()
 
 

@@ -196,3 +196,40 @@ def test_simulation_with_the_loop_conserves_what_it_should(orc):
     loop = orc.simulator.simulate(*args, gate=-np.inf, policy="loop")
     print("reconfigurations without a gate: from scratch", int(scratch["n_reconf"].sum()), "loop", int(loop["n_reconf"].sum()))
     assert loop["n_reconf"].sum() < scratch["n_reconf"].sum()
+
+
+def test_simulation_over_nodes(orc):
+    """The loop with ScheduleJob searching node by node as the round of every tick, from the placement the last tick
+    left: one node that holds the whole cluster gives the trajectories of the loop over totals; on real nodes no node
+    ever holds more than it has and every job's parts add up to what it holds."""
+    wl = workloads.large()
+    r = orc.schedule_round(wl, n_threads=8)
+    tr = workloads.trace(wl.n_jobs, horizon_s=2 * 3600.0)
+    work = workloads.job_lengths_s(tr.u_duration) * wl.coef[:, 16] * 2.0
+    args = (wl.coef[:, 16], r["table"], wl.grid, wl.cluster, r["best_thr"], r["best_plan"], r["curve_thr"], tr.arrival, work,
+            tr.delta, 120.0, 40)
+    loop = orc.simulator.simulate(*args, policy="loop")
+    one = orc.simulator.simulate(*args, policy="nodes", nodes=(1, wl.cluster.G, wl.cluster.C, wl.cluster.host_mem_gb))
+    for k in ("finish", "n_reconf", "progress", "held", "gpus_in_use", "frozen"):
+        assert np.array_equal(loop[k], one[k]), k
+    assert np.allclose(loop["totals"], one["totals"], rtol=1e-12)
+    nodes = (128, 8, 128, 2048.0)
+    out = orc.simulator.simulate(*args, policy="nodes", nodes=nodes, trace=True)
+    fin = out["finish"] >= 0
+    assert fin.sum() > 100 and out["n_reconf"].sum() > 0 and out["frozen"].sum() > 0
+    levels = np.asarray(wl.grid.cpu_levels)
+    spread = 0
+    for k, (h, (off, ent)) in enumerate(zip(out["history"], out["placements"])):
+        used_g, used_c = np.zeros(nodes[0], np.int64), np.zeros(nodes[0], np.int64)
+        np.add.at(used_g, ent["node"], ent["g"])
+        np.add.at(used_c, ent["node"], ent["c"])
+        assert used_g.max(initial=0) <= nodes[1] and used_c.max(initial=0) <= nodes[2]
+        per_job = np.add.reduceat(np.concatenate([ent["g"], [0]]), np.minimum(off[:-1], len(ent)))
+        per_job[np.diff(off.astype(np.int64)) == 0] = 0
+        assert np.array_equal(per_job, h["g"])
+        spread += int((np.diff(off.astype(np.int64)) > 1).sum())
+        t = 120.0 * k
+        assert np.all(h["g"][tr.arrival > t] == 0)
+    assert spread > 0
+    print(f"over nodes: {int(fin.sum())} jobs finish, {int(out['n_reconf'].sum())} reconfigurations "
+          f"(loop over totals: {int((loop['finish'] >= 0).sum())}, {int(loop['n_reconf'].sum())})")
