@@ -545,6 +545,30 @@ def sim_bench(rk, ctx, dev, reps):
         if i:
             wall.append((time.perf_counter() - t0) * 1e3)
     out["schedule_loop_policy"] = summary(float(np.median(wall)))
+    # the loop searching node by node needs CPU levels per GPU: the same jobs and trace on 8 nodes of 8 GPUs, 128 CPUs
+    # and 512 GiB with CPU ratios {1, 2, 4, 8, 16} per GPU, under the loop over totals and under the loop over nodes
+    wl2 = workloads.Workload("trace_scale_per_gpu", wl.coef, wl.ints, wl.bounds,
+                             workloads.Grid(np.array([1, 2, 4, 8, 16], np.uint32), 1, np.array([64.0], np.float32), 0),
+                             wl.env, workloads.Cluster(64, 8 * 128, 8 * 512.0))
+    grid2, cluster2 = rk.make_grid(wl2.grid), rk.make_cluster(wl2.cluster)
+    n2 = table.n_segments(len(wl2.grid.cpu_levels) * len(wl2.grid.mem_levels_gb))
+    f32 = lambda: torch.empty(n2 + 4, dtype=torch.float32, device=dev)
+    i32 = lambda: torch.empty(n2 + 4, dtype=torch.int32, device=dev)
+    bt, bp, ct, cp, cg = f32(), i32(), f32(), i32(), i32()
+    rk.rk_job_curves(ctx, jobs, table.c, grid2, env, 0, J, bt, bp, ct, cp, cg)
+    nodes = rk.rk_nodes(8, 8, 128, 512.0)
+    out["per_gpu_cpu_levels"] = {"nodes": 8, "gpus_per_node": 8, "cpus_per_node": 128, "mem_per_node_gb": 512.0}
+    for key, policy in (("schedule_loop_policy", 1), ("schedule_loop_over_nodes_policy", 2)):
+        wall = []
+        for i in range(reps + 1):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            rk.rk_simulate(ctx, jobs.ref_thr, table.c, grid2, cluster2, bt, bp, ct, arrival, work_d, delta, 60.0, n_ticks, 0.97,
+                           res, policy=policy, nodes=nodes if policy == 2 else None)
+            torch.cuda.synchronize()
+            if i:
+                wall.append((time.perf_counter() - t0) * 1e3)
+        out["per_gpu_cpu_levels"][key] = summary(float(np.median(wall)))
     return out
 
 
