@@ -325,6 +325,24 @@ int32_t rk_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *ta
                       const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
                       const rk_job_state *jobs_state, rk_assign *assign, float *total, uint32_t *stats);
 
+/* Many independent rounds of that loop over the same jobs and curves at once, a
+ * workgroup per round (what-if questions: other capacities, other states of the
+ * jobs; Sec. 5.2: the curves do not depend on the cluster's state).
+ *   clusters     [host] n_rounds entries: capacity of round r
+ *   jobs_state   arrays [device]; state_stride 0: every round starts from the same
+ *                state (n_jobs entries per array); state_stride n_jobs: round r
+ *                reads entries [r * n_jobs, (r + 1) * n_jobs) of every array given
+ *   assign       [device] n_rounds * n_jobs records, round r at r * n_jobs
+ *   totals       [device] n_rounds floats
+ *   stats        [device] 4 * n_rounds words or NULL
+ * Every round's result is what rk_reschedule gives for its cluster and state.
+ * Limits: n_rounds <= 65535, n_rounds * n_jobs <= 2^26. */
+int32_t rk_reschedule_rounds(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                             const rk_alloc_grid *grid, uint32_t n_rounds, const rk_cluster *clusters,
+                             const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                             const rk_job_state *jobs_state, uint32_t state_stride, rk_assign *assign,
+                             float *totals, uint32_t *stats_or_null);
+
 /* One scheduling round end to end: enumerate -> evaluate -> best plan ->
  * curves -> greedy allocation, all on the device.  Waits once for the plan
  * counts. assign [device] n_jobs records, total [device] one float. */

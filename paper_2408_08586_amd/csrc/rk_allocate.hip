@@ -1435,13 +1435,41 @@ struct RsArgs {
     uint32_t *keep_ci;
     float *keep_ds;              // the two give-slopes of a job before a step touched it
     uint32_t *stats;             // may be null: steps committed, jobs on the full path, shrinks applied, steps taken back
+    // several independent rounds over the same jobs (a workgroup per round): round r works on the slice [r * n_jobs, ...)
+    // of every per-job array above, reads the state arrays from r * state_stride on and its cluster from d_clusters[r]
+    uint32_t state_stride;
+    const rk_cluster *d_clusters;    // null: the single round's G and C above
 };
+
+// The arguments of round r: every per-job array moved to the round's slice.
+__device__ __forceinline__ RsArgs rs_round(const RsArgs &B, uint32_t r) {
+    RsArgs A = B;
+    const size_t at = (size_t)r * (B.n_jobs ? B.n_jobs : 1u), from = (size_t)r * B.state_stride;
+    A.st.gi += at; A.st.g += at; A.st.ci += at;
+    if (B.state) A.state += from;
+    A.cur_seg += from; A.cur_c += from;
+    if (B.floor_seg) A.floor_seg += from;
+    if (B.floor_c) A.floor_c += from;
+    A.ds_g += at; A.ds_c += at; A.sg += at; A.sc += at; A.ug += at; A.uc += at; A.udg += at; A.udc_g += at; A.udc_c += at;
+    A.order += at; A.touched += at; A.stamp += at; A.first += at; A.keep_gi += at; A.keep_ci += at; A.keep_ds += 2 * at;
+    if (B.stats) A.stats += 4 * (size_t)r;
+    if (B.d_clusters) { A.G = B.d_clusters[r].G; A.C = B.d_clusters[r].C; }
+    return A;
+}
+
+// rounds that share their jobs: where every round's slots begin, and the job of every slot
+__global__ void k_rs_meta(uint32_t n_rounds, uint32_t n_jobs, uint32_t *round_off, uint32_t *jmap) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i <= n_rounds) round_off[i] = (uint32_t)(i * n_jobs);
+    if (i < (size_t)n_rounds * n_jobs) jmap[i] = (uint32_t)(i % n_jobs);
+}
 
 // Every job on its own, any number of workgroups: what it holds, whether it comes first (a floor it is below), its
 // cached slopes and steps.
-__global__ void k_rs_prepare(RsArgs A) {
+__global__ void k_rs_prepare(RsArgs B) {
     const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= A.n_jobs) return;
+    if (j >= B.n_jobs) return;
+    const RsArgs A = rs_round(B, blockIdx.y);
     int32_t gi = -1;
     uint32_t ci = 0;
     if (rs_holds(A, j) && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < rs_ns(A, j) && A.cur_c[j] < A.X.grid.n_cpu) {
@@ -1454,7 +1482,8 @@ __global__ void k_rs_prepare(RsArgs A) {
     rs_refresh(A, j);
 }
 
-__global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs A) {
+__global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
+    const RsArgs A = rs_round(B, blockIdx.x);
     __shared__ RsStep sh_step;
     __shared__ unsigned long long sh_free[2], sh_avail[2], sh_held[2][RS_THREADS / 64];
     __shared__ float sh_lost, sh_wmin[RS_THREADS / 64];
@@ -1912,57 +1941,114 @@ extern "C" int32_t rk_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_pla
                                 stats);
 }
 
-int32_t rk_launch_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table, const rk_alloc_grid *grid,
-                             const rk_cluster *cluster, const float *best_thr, const uint32_t *best_plan,
-                             const float *curve_thr, const rk_job_state *jobs_state, rk_assign *assign, float *total,
-                             uint32_t *stats) {
+// n_rounds independent rounds over the same jobs (clusters [host] n_rounds entries; round r reads the state arrays from
+// r * state_stride on and writes assign[r * n_jobs ...], totals[r], stats[4 r ...]); one round: the plain loop
+static int32_t launch_reschedule_rounds(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                                        const rk_alloc_grid *grid, uint32_t n_rounds, const rk_cluster *clusters,
+                                        const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                                        const rk_job_state *jobs_state, uint32_t state_stride, rk_assign *assign,
+                                        float *totals, uint32_t *stats) {
     const uint32_t J = table->n_jobs;
     int32_t rc;
     Arena arena = {nullptr, 0, 0};
-    const size_t n = J ? J : 1;
+    const size_t n = J ? J : 1, all = n * n_rounds;
     RsArgs A;
     JobState &st = A.st;
     st = JobState{};
     st.blocks_per_round = (J + JOB_THREADS - 1) / JOB_THREADS;
     if (st.blocks_per_round == 0) st.blocks_per_round = 1;
-    if ((rc = scratch_typed(ctx, arena, SL_ST_GI, n, &st.gi))) return rc;
-    if ((rc = scratch_typed(ctx, arena, SL_ST_G, n, &st.g))) return rc;
-    if ((rc = scratch_typed(ctx, arena, SL_ST_CI, n, &st.ci))) return rc;
-    if ((rc = scratch_typed(ctx, arena, SL_ST_PARTIAL, (size_t)st.blocks_per_round * 2, &st.partial))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_GI, all, &st.gi))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_G, all, &st.g))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_CI, all, &st.ci))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_ST_PARTIAL, (size_t)st.blocks_per_round * 2 * n_rounds, &st.partial))) return rc;
     float *f32;
     uint32_t *u32;
     unsigned long long *u64;
-    if ((rc = scratch_typed(ctx, arena, SL_RS_F32, n * 8, &f32))) return rc;
-    if ((rc = scratch_typed(ctx, arena, SL_RS_U32, n * 7, &u32))) return rc;
-    if ((rc = scratch_typed(ctx, arena, SL_RS_U64, n * 2, &u64))) return rc;
-    A.ds_g = f32; A.ds_c = f32 + n; A.sg = f32 + 2 * n; A.sc = f32 + 3 * n; A.ug = f32 + 4 * n; A.uc = f32 + 5 * n;
-    A.keep_ds = f32 + 6 * n;
-    A.order = u32; A.touched = u32 + n; A.stamp = u32 + 2 * n; A.first = u32 + 3 * n;
-    A.keep_gi = reinterpret_cast<int32_t *>(u32 + 4 * n); A.keep_ci = u32 + 5 * n; A.udg = u32 + 6 * n;
-    A.udc_g = u64; A.udc_c = u64 + n;
+    if ((rc = scratch_typed(ctx, arena, SL_RS_F32, all * 8, &f32))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_RS_U32, all * 7, &u32))) return rc;
+    if ((rc = scratch_typed(ctx, arena, SL_RS_U64, all * 2, &u64))) return rc;
+    A.ds_g = f32; A.ds_c = f32 + all; A.sg = f32 + 2 * all; A.sc = f32 + 3 * all; A.ug = f32 + 4 * all; A.uc = f32 + 5 * all;
+    A.keep_ds = f32 + 6 * all;
+    A.order = u32; A.touched = u32 + all; A.stamp = u32 + 2 * all; A.first = u32 + 3 * all;
+    A.keep_gi = reinterpret_cast<int32_t *>(u32 + 4 * all); A.keep_ci = u32 + 5 * all; A.udg = u32 + 6 * all;
+    A.udc_g = u64; A.udc_c = u64 + all;
     Ctx &X = A.X;
     X.ref_thr = ref_thr; X.tb = table_dev(table); X.grid = grid_dev(grid); X.jb = 0; X.jmap = nullptr;
     X.best_thr = best_thr; X.best_plan = best_plan; X.curve_thr = curve_thr;
-    X.R.round_off = nullptr; X.R.clusters = nullptr; X.R.n_rounds = 1; X.R.inline_one = 1u;
-    X.R.off0 = 0; X.R.off1 = J; X.R.cl = *cluster;
-    A.n_jobs = J; A.G = cluster->G; A.C = cluster->C;
+    X.R.round_off = nullptr; X.R.clusters = nullptr; X.R.n_rounds = n_rounds; X.R.inline_one = 1u;
+    X.R.off0 = 0; X.R.off1 = J; X.R.cl = clusters[0];
+    A.n_jobs = J; A.G = clusters[0].G; A.C = clusters[0].C;
     A.state = jobs_state->state; A.cur_seg = jobs_state->cur_seg; A.cur_c = jobs_state->cur_c;
     A.floor_seg = jobs_state->floor_seg; A.floor_c = jobs_state->floor_c;
     A.stats = stats;
+    A.state_stride = state_stride; A.d_clusters = nullptr;
     hipStream_t s = ctx->stream;
+    if (n_rounds > 1) {                                        // the rounds' slots, the job of every slot, the clusters
+        const size_t off_bytes = (((size_t)n_rounds + 1) * 4 + 15) & ~(size_t)15;
+        char *d_meta;
+        uint32_t *d_jmap;
+        if ((rc = rk_scratch(ctx, SL_ROUND_META, off_bytes + (size_t)n_rounds * sizeof(rk_cluster), (void **)&d_meta))) return rc;
+        if ((rc = rk_scratch(ctx, SL_JMAP, all * 4, (void **)&d_jmap))) return rc;
+        RK_HIP(ctx, hipMemcpyAsync(d_meta + off_bytes, clusters, (size_t)n_rounds * sizeof(rk_cluster), hipMemcpyHostToDevice, s));
+        const size_t most = all > (size_t)n_rounds + 1 ? all : (size_t)n_rounds + 1;
+        k_rs_meta<<<(uint32_t)((most + 255) / 256), 256, 0, s>>>(n_rounds, J, reinterpret_cast<uint32_t *>(d_meta), d_jmap);
+        RK_CHECK_LAUNCH(ctx, "k_rs_meta");
+        X.R.round_off = reinterpret_cast<const uint32_t *>(d_meta);
+        X.R.clusters = reinterpret_cast<const rk_cluster *>(d_meta + off_bytes);
+        X.R.inline_one = 0u;
+        X.jmap = d_jmap;
+        A.d_clusters = X.R.clusters;
+    }
     if (J > 0) {
-        k_rs_prepare<<<(J + 255) / 256, 256, 0, s>>>(A);
+        k_rs_prepare<<<dim3((J + 255) / 256, n_rounds), 256, 0, s>>>(A);
         RK_CHECK_LAUNCH(ctx, "k_rs_prepare");
     }
-    k_reschedule<<<1, RS_THREADS, 0, s>>>(A);
+    k_reschedule<<<n_rounds, RS_THREADS, 0, s>>>(A);
     RK_CHECK_LAUNCH(ctx, "k_reschedule");
     if (J > 0) {
-        k_mem_wish<<<dim3(st.blocks_per_round, 1), JOB_THREADS, 0, s>>>(X, st, assign);
+        k_mem_wish<<<dim3(st.blocks_per_round, n_rounds), JOB_THREADS, 0, s>>>(X, st, assign);
         RK_CHECK_LAUNCH(ctx, "k_mem_wish");
     }
-    k_mem_finish<<<1, 64, 0, s>>>(X, st, assign, total);
+    k_mem_finish<<<n_rounds, 64, 0, s>>>(X, st, assign, totals);
     RK_CHECK_LAUNCH(ctx, "k_mem_finish");
     return RK_OK;
+}
+
+int32_t rk_launch_reschedule(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table, const rk_alloc_grid *grid,
+                             const rk_cluster *cluster, const float *best_thr, const uint32_t *best_plan,
+                             const float *curve_thr, const rk_job_state *jobs_state, rk_assign *assign, float *total,
+                             uint32_t *stats) {
+    return launch_reschedule_rounds(ctx, ref_thr, table, grid, 1, cluster, best_thr, best_plan, curve_thr, jobs_state, 0, assign,
+                                    total, stats);
+}
+
+extern "C" int32_t rk_reschedule_rounds(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                                        const rk_alloc_grid *grid, uint32_t n_rounds, const rk_cluster *clusters,
+                                        const float *best_thr, const uint32_t *best_plan, const float *curve_thr,
+                                        const rk_job_state *jobs_state, uint32_t state_stride, rk_assign *assign,
+                                        float *totals, uint32_t *stats) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if ((rc = rk_check_table(ctx, table, 0, table ? table->n_jobs : 0))) return rc;
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    if (!clusters || !totals || !jobs_state) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (n_rounds == 0) return RK_OK;
+    const uint32_t J = table->n_jobs;
+    if (J > 0 && (!ref_thr || !assign || !jobs_state->cur_seg || !jobs_state->cur_c ||
+                  (table->n_segs > 0 && (!best_thr || !best_plan || !curve_thr))))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (state_stride != 0 && state_stride != J)
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "state_stride must be 0 (one state for all rounds) or n_jobs (one per round)");
+    for (uint32_t r = 0; r < n_rounds; ++r)
+        if (!(clusters[r].host_mem_gb >= 0.f)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "host_mem_gb negative or NaN");
+    if (table->max_segs_per_job > 32767u) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 32767 segments per job");
+    if (J > RK_MAX_JOBS_PER_ROUND)
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "%u jobs, the allocation kernels take up to %u", J, RK_MAX_JOBS_PER_ROUND);
+    if ((uint64_t)n_rounds * (J ? J : 1) > (1ull << 26) || n_rounds > 65535u)
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "rounds x jobs above 2^26, or more than 65535 rounds");
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    return launch_reschedule_rounds(ctx, ref_thr, table, grid, n_rounds, clusters, best_thr, best_plan, curve_thr, jobs_state,
+                                    state_stride, assign, totals, stats);
 }
 
 static int32_t allocate_one_round(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,

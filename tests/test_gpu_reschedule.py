@@ -207,6 +207,53 @@ def test_generated_rounds_from_a_running_state(gpu, orc, name):
     run.close()
 
 
+def test_many_rounds_at_once(gpu, orc):
+    """rk_reschedule_rounds: what-if rounds over the same jobs, a workgroup each - other capacities from one state,
+    and other states (jobs that left, other floors) round by round; every round is the oracle's loop for its inputs."""
+    import torch
+    import paper_2408_08586_amd as rk
+    for seed, (J, n_rounds, per_round) in enumerate([(40, 7, False), (300, 64, True), (1500, 33, True), (1, 3, False)]):
+        rng = np.random.default_rng(98000 + seed)
+        wl, tb, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state = random_round(rng, orc, J, int(rng.integers(2, 17)))
+        base = wl.cluster
+        clusters = [workloads.Cluster(int(base.G * u), int(base.C * u), base.host_mem_gb)
+                    for u in rng.uniform(0.5, 1.5, n_rounds)]
+        if per_round:                                        # every round its own state: some jobs have left, floors differ
+            seg = np.tile(cur_seg, (n_rounds, 1))
+            seg[rng.uniform(size=seg.shape) < 0.1] = -1
+            fl = np.tile(floor_seg, (n_rounds, 1))
+            fl[rng.uniform(size=fl.shape) < 0.2] = -1
+            lv, fc, stt = np.tile(cur_c, (n_rounds, 1)), np.tile(floor_c, (n_rounds, 1)), np.tile(state, (n_rounds, 1))
+        else:
+            seg, fl, lv, fc, stt = cur_seg[None], floor_seg[None], cur_c[None], floor_c[None], state[None]
+        run = gpu(wl)
+        run.enumerate()
+        dev = run.device
+        i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32).reshape(-1)).to(dev)
+        u8 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint8).reshape(-1)).to(dev)
+        assign = rk.new_assign(n_rounds * J, dev)
+        totals = run.f32(n_rounds)
+        stats = torch.zeros(4 * n_rounds, dtype=torch.int32, device=dev)
+        rk.rk_reschedule_rounds(run.ctx, run.jobs.ref_thr, run.table.c, run.grid, [rk.make_cluster(c) for c in clusters],
+                                run.dev_f32(bt), run.dev_u32(bp), run.dev_f32(ct), i32(seg), run.dev_u32(lv.reshape(-1)), assign,
+                                totals, state_stride=J if per_round else 0, state=u8(stt), floor_seg=i32(fl),
+                                floor_c=run.dev_u32(fc.reshape(-1)), stats=stats)
+        rk.rk_sync(run.ctx)
+        got_a = rk.assign_to_numpy(assign).reshape(n_rounds, J)
+        got_t, got_s = totals.cpu().numpy()[:n_rounds], stats.cpu().numpy().reshape(n_rounds, 4)
+        n_moves = 0
+        for r in range(n_rounds):
+            k = r if per_round else 0
+            want = orc.reschedule(wl.coef[:, 16], tb, wl.grid, clusters[r], bt, bp, ct, seg[k], lv[k], fl[k], fc[k], state=stt[k])
+            same((got_a[r], float(got_t[r]), int(got_s[r, 0])), want)
+            n_moves += want[2]
+        # one round through the same entry point is rk_reschedule
+        one = on_gpu(run, bt, bp, ct, clusters[0], seg[0], lv[0], fl[0], fc[0], stt[0])
+        assert np.array_equal(one[0], got_a[0]) and one[2] == got_s[0, 0]
+        print(f"{n_rounds} rounds of {J} jobs: {n_moves} steps committed")
+        run.close()
+
+
 def test_argument_errors(gpu, orc):
     import paper_2408_08586_amd as rk
     wl = workloads.tiny()
