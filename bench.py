@@ -302,6 +302,28 @@ def algorithm1_bench(rk, ctx, dev, wl, jobs, table, grid, env, best_thr, best_pl
             "jobs_running_before": int((cur_seg >= 0).sum()), "steps_committed": int(moves[0].item()), "jobs_on_the_full_path": int(moves[1].item()),
             "shrinks_applied": int(moves[2].item()), "steps_taken_back": int(moves[3].item()),
             "jobs_running_after": int((res["g"] > 0).sum()), "ms": float(np.median(ms))}
+    # what-if: the same state under 64 other capacities (0.75 to 1.25 of the cluster), all rounds in one call
+    n_what = 64
+    what = [rk.make_cluster(type(wl.cluster)(max(held, int(wl.cluster.G * u)), int(wl.cluster.C * u), wl.cluster.host_mem_gb))
+            for u in np.linspace(0.75, 1.25, n_what)]
+    outs, totals = rk.new_assign(J * n_what, dev), torch.zeros(n_what, dtype=torch.float32, device=dev)
+    st64 = torch.zeros(4 * n_what, dtype=torch.int32, device=dev)
+    ms64 = []
+    for i in range(reps + 2):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        rk.rk_reschedule_rounds(ctx, jobs.ref_thr, table.c, grid, what, best_thr, best_plan, curve_thr, d_seg, d_c, outs, totals,
+                                stats=st64)
+        b.record()
+        torch.cuda.synchronize()
+        if i >= 2:
+            ms64.append(a.elapsed_time(b))
+    info["what_if_rounds"] = {"entry": "rk_reschedule_rounds (a workgroup per round)", "rounds": n_what, "jobs": J,
+                              "capacities": "0.75 to 1.25 of the cluster's GPUs and CPUs, from the same state",
+                              "steps_committed_min_max": [int(st64.cpu().numpy()[0::4].min()), int(st64.cpu().numpy()[0::4].max())],
+                              "ms": float(np.median(ms64)), "ms_per_round": float(np.median(ms64)) / n_what,
+                              "rounds_per_s": n_what / (float(np.median(ms64)) * 1e-3)}
+    del outs
     gpn, n_nodes = 8, max(1, wl.cluster.G // 8)
     cap = n_nodes * gpn
     placed = rk.new_assign(J, dev)

@@ -1415,8 +1415,7 @@ __global__ __launch_bounds__(FLOOR_THREADS) void k_floors(Ctx X, JobState st, Sl
 // carry them.
 constexpr int RS_THREADS = 1024;
 
-struct RsArgs {
-    Ctx X;
+struct RsRound {                 // what a round of the loop works on
     JobState st;                 // gi, g, ci: the state the loop works on (and the memory step reads)
     uint32_t n_jobs;
     unsigned long long G, C;
@@ -1435,16 +1434,29 @@ struct RsArgs {
     uint32_t *keep_ci;
     float *keep_ds;              // the two give-slopes of a job before a step touched it
     uint32_t *stats;             // may be null: steps committed, jobs on the full path, shrinks applied, steps taken back
-    // several independent rounds over the same jobs (a workgroup per round): round r works on the slice [r * n_jobs, ...)
-    // of every per-job array above, reads the state arrays from r * state_stride on and its cluster from d_clusters[r]
-    uint32_t state_stride;
-    const rk_cluster *d_clusters;    // null: the single round's G and C above
 };
 
-// The arguments of round r: every per-job array moved to the round's slice.
-__device__ __forceinline__ RsArgs rs_round(const RsArgs &B, uint32_t r) {
-    RsArgs A = B;
-    const size_t at = (size_t)r * (B.n_jobs ? B.n_jobs : 1u), from = (size_t)r * B.state_stride;
+struct RsArgs {                  // the kernels' argument
+    Ctx X;
+    RsRound r;
+    // several independent rounds over the same jobs (a workgroup per round): round k works on the slice [k * n_jobs, ...)
+    // of every per-job array of r, reads the state arrays from k * state_stride on and its cluster from d_clusters[k]
+    uint32_t state_stride;
+    const rk_cluster *d_clusters;    // null: the single round's G and C
+};
+
+// What the code of a round sees: its own slice of the per-job arrays, and the table, grid and curves where the kernel
+// arguments hold them (a copy of the grid's level arrays would live in scratch memory).
+struct RsView : RsRound {
+    const Ctx &X;
+    __device__ RsView(const RsRound &r, const Ctx &x) : RsRound(r), X(x) {}
+};
+
+// The view of round k: every per-job array moved to the round's slice.
+__device__ __forceinline__ RsView rs_round(const RsArgs &K, uint32_t r) {
+    RsView A(K.r, K.X);
+    const RsRound &B = K.r;
+    const size_t at = (size_t)r * (B.n_jobs ? B.n_jobs : 1u), from = (size_t)r * K.state_stride;
     A.st.gi += at; A.st.g += at; A.st.ci += at;
     if (B.state) A.state += from;
     A.cur_seg += from; A.cur_c += from;
@@ -1453,7 +1465,7 @@ __device__ __forceinline__ RsArgs rs_round(const RsArgs &B, uint32_t r) {
     A.ds_g += at; A.ds_c += at; A.sg += at; A.sc += at; A.ug += at; A.uc += at; A.udg += at; A.udc_g += at; A.udc_c += at;
     A.order += at; A.touched += at; A.stamp += at; A.first += at; A.keep_gi += at; A.keep_ci += at; A.keep_ds += 2 * at;
     if (B.stats) A.stats += 4 * (size_t)r;
-    if (B.d_clusters) { A.G = B.d_clusters[r].G; A.C = B.d_clusters[r].C; }
+    if (K.d_clusters) { A.G = K.d_clusters[r].G; A.C = K.d_clusters[r].C; }
     return A;
 }
 
@@ -1468,8 +1480,8 @@ __global__ void k_rs_meta(uint32_t n_rounds, uint32_t n_jobs, uint32_t *round_of
 // cached slopes and steps.
 __global__ void k_rs_prepare(RsArgs B) {
     const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= B.n_jobs) return;
-    const RsArgs A = rs_round(B, blockIdx.y);
+    if (j >= B.r.n_jobs) return;
+    const RsView A = rs_round(B, blockIdx.y);
     int32_t gi = -1;
     uint32_t ci = 0;
     if (rs_holds(A, j) && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < rs_ns(A, j) && A.cur_c[j] < A.X.grid.n_cpu) {
@@ -1483,7 +1495,7 @@ __global__ void k_rs_prepare(RsArgs B) {
 }
 
 __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
-    const RsArgs A = rs_round(B, blockIdx.x);
+    const RsView A = rs_round(B, blockIdx.x);
     __shared__ RsStep sh_step;
     __shared__ unsigned long long sh_free[2], sh_avail[2], sh_held[2][RS_THREADS / 64];
     __shared__ float sh_lost, sh_wmin[RS_THREADS / 64];
@@ -1952,7 +1964,8 @@ static int32_t launch_reschedule_rounds(rk_ctx *ctx, const float *ref_thr, const
     int32_t rc;
     Arena arena = {nullptr, 0, 0};
     const size_t n = J ? J : 1, all = n * n_rounds;
-    RsArgs A;
+    RsArgs K;
+    RsRound &A = K.r;
     JobState &st = A.st;
     st = JobState{};
     st.blocks_per_round = (J + JOB_THREADS - 1) / JOB_THREADS;
@@ -1972,7 +1985,7 @@ static int32_t launch_reschedule_rounds(rk_ctx *ctx, const float *ref_thr, const
     A.order = u32; A.touched = u32 + all; A.stamp = u32 + 2 * all; A.first = u32 + 3 * all;
     A.keep_gi = reinterpret_cast<int32_t *>(u32 + 4 * all); A.keep_ci = u32 + 5 * all; A.udg = u32 + 6 * all;
     A.udc_g = u64; A.udc_c = u64 + all;
-    Ctx &X = A.X;
+    Ctx &X = K.X;
     X.ref_thr = ref_thr; X.tb = table_dev(table); X.grid = grid_dev(grid); X.jb = 0; X.jmap = nullptr;
     X.best_thr = best_thr; X.best_plan = best_plan; X.curve_thr = curve_thr;
     X.R.round_off = nullptr; X.R.clusters = nullptr; X.R.n_rounds = n_rounds; X.R.inline_one = 1u;
@@ -1981,7 +1994,7 @@ static int32_t launch_reschedule_rounds(rk_ctx *ctx, const float *ref_thr, const
     A.state = jobs_state->state; A.cur_seg = jobs_state->cur_seg; A.cur_c = jobs_state->cur_c;
     A.floor_seg = jobs_state->floor_seg; A.floor_c = jobs_state->floor_c;
     A.stats = stats;
-    A.state_stride = state_stride; A.d_clusters = nullptr;
+    K.state_stride = state_stride; K.d_clusters = nullptr;
     hipStream_t s = ctx->stream;
     if (n_rounds > 1) {                                        // the rounds' slots, the job of every slot, the clusters
         const size_t off_bytes = (((size_t)n_rounds + 1) * 4 + 15) & ~(size_t)15;
@@ -1997,13 +2010,13 @@ static int32_t launch_reschedule_rounds(rk_ctx *ctx, const float *ref_thr, const
         X.R.clusters = reinterpret_cast<const rk_cluster *>(d_meta + off_bytes);
         X.R.inline_one = 0u;
         X.jmap = d_jmap;
-        A.d_clusters = X.R.clusters;
+        K.d_clusters = X.R.clusters;
     }
     if (J > 0) {
-        k_rs_prepare<<<dim3((J + 255) / 256, n_rounds), 256, 0, s>>>(A);
+        k_rs_prepare<<<dim3((J + 255) / 256, n_rounds), 256, 0, s>>>(K);
         RK_CHECK_LAUNCH(ctx, "k_rs_prepare");
     }
-    k_reschedule<<<n_rounds, RS_THREADS, 0, s>>>(A);
+    k_reschedule<<<n_rounds, RS_THREADS, 0, s>>>(K);
     RK_CHECK_LAUNCH(ctx, "k_reschedule");
     if (J > 0) {
         k_mem_wish<<<dim3(st.blocks_per_round, n_rounds), JOB_THREADS, 0, s>>>(X, st, assign);
