@@ -390,6 +390,16 @@ def algorithm1_bench(rk, ctx, dev, wl, jobs, table, grid, env, best_thr, best_pl
             if i >= 2:
                 ms_plan.append(a.elapsed_time(b))
         p_n = rk.assign_to_numpy(placed)
+        # the whole round in one call from the job descriptors (enumeration, curves, the loop, the plans); host time
+        lat = []
+        for i in range(reps + 2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            rk.rk_schedule_round_nodes(ctx, jobs, rk.make_bounds(wl.bounds), grid, env, nodes, d_seg_n, d_c, out, placed, off, ent,
+                                       cap, total, prev_off=off0, prev_entries=ent0, n_prev_entries=r0.n_entries)
+            torch.cuda.synchronize()
+            if i >= 2:
+                lat.append((time.perf_counter() - t0) * 1e3)
         st5 = stats.cpu().numpy()
         info["over_nodes"] = {"entry": "rk_reschedule_nodes (one workgroup; the job to shrink is one of the node under search)",
                               "nodes": n_nodes, "gpus_per_node": gpn, "cpus_per_node": int(nodes.cpus_per_node),
@@ -400,7 +410,9 @@ def algorithm1_bench(rk, ctx, dev, wl, jobs, table, grid, env, best_thr, best_pl
                               "ms": float(np.median(ms)),
                               "best_plan_placed": {"entry": "rk_best_plan_placed (k_replan + k_place_total)",
                                                    "plans_changed_by_the_split": int(((p_n["plan"] != res_n["plan"]) & (res_n["g"] > 0)).sum()),
-                                                   "total": float(total[0].item()), "ms": float(np.median(ms_plan))}}
+                                                   "total": float(total[0].item()), "ms": float(np.median(ms_plan))},
+                              "round_from_descriptors": {"entry": "rk_schedule_round_nodes (host-synchronous)",
+                                                         "ms": float(np.median(lat))}}
     return info
 
 

@@ -720,6 +720,22 @@ int32_t rk_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const rk_plan_tab
                             rk_assign *assign, uint32_t *place_off, rk_place_entry *entries,
                             uint64_t cap_entries, float *total, uint32_t *stats_or_null);
 
+/* A whole round of Algorithm 1 on nodes from the job descriptors, in one call
+ * (Sec. 5.2, Algorithm 1: Schedule over the jobs, ScheduleJob over the nodes,
+ * GetBestPlan for the placement found, memory last): the plan table and the
+ * curves of all jobs (as rk_schedule_round computes them, in the context's
+ * buffers), rk_reschedule_nodes from what the jobs hold and where they are,
+ * then rk_best_plan_placed on the placement that leaves.  Arguments as for
+ * these two; assign receives the loop's records (plans of the packed
+ * placement), placed the records with the plans of the actual splits, total
+ * the sum of thr / ref_thr over placed. */
+int32_t rk_schedule_round_nodes(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                                const rk_alloc_grid *grid, const rk_env *env, const rk_nodes *nodes,
+                                const rk_job_state *jobs_state, const uint32_t *prev_off_or_null,
+                                const rk_place_entry *prev_entries_or_null, uint64_t n_prev_entries,
+                                rk_assign *assign, rk_assign *placed, uint32_t *place_off, rk_place_entry *entries,
+                                uint64_t cap_entries, float *total, uint32_t *stats_or_null);
+
 /* ---- measurement helper (no part of the method) --------------------------- */
 
 /* Streams a buffer and nothing else, for the benchmark's roofline context:

@@ -26,7 +26,7 @@ FIT_FIELDS = ("k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_con
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
            "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
            "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared", "rk_place", "rk_allocate_static", "rk_place_plans",
-           "rk_schedule_round_placed", "rk_reschedule", "rk_probe_stream", "rk_eval_best_plan", "rk_reschedule_nodes", "rk_best_plan_placed", "rk_reschedule_rounds")
+           "rk_schedule_round_placed", "rk_reschedule", "rk_probe_stream", "rk_eval_best_plan", "rk_reschedule_nodes", "rk_best_plan_placed", "rk_reschedule_rounds", "rk_schedule_round_nodes")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -329,6 +329,17 @@ def rk_reschedule_rounds(ctx, ref_thr, table, grid, clusters, best_thr, best_pla
     _check(ctx, load_library().rk_reschedule_rounds(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.c_uint32(n_rounds), arr,
                                                     _ptr(best_thr), _ptr(best_plan), _ptr(curve_thr), C.byref(js),
                                                     C.c_uint32(state_stride), _ptr(assign), _ptr(totals), _ptr(stats)))
+
+
+def rk_schedule_round_nodes(ctx, jobs: Jobs, bounds, grid, env, nodes, cur_seg, cur_c, assign, placed, place_off, entries,
+                            cap_entries, total, prev_off=None, prev_entries=None, n_prev_entries=0, state=None, floor_seg=None,
+                            floor_c=None, stats=None):
+    """A whole round of Algorithm 1 on nodes from the job descriptors (device tensors for the state and the results)."""
+    js = rk_job_state(_ptr(state), _ptr(cur_seg), _ptr(cur_c), _ptr(floor_seg), _ptr(floor_c))
+    _check(ctx, load_library().rk_schedule_round_nodes(ctx, C.byref(jobs.c), C.byref(bounds), C.byref(grid), C.byref(env),
+                                                       C.byref(nodes), C.byref(js), _ptr(prev_off), _ptr(prev_entries),
+                                                       C.c_uint64(n_prev_entries), _ptr(assign), _ptr(placed), _ptr(place_off),
+                                                       _ptr(entries), C.c_uint64(cap_entries), _ptr(total), _ptr(stats)))
 
 
 def rk_reschedule_nodes(ctx, ref_thr, table, grid, nodes: "rk_nodes", best_thr, best_plan, curve_thr, cur_seg, cur_c, assign,

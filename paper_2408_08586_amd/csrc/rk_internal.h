@@ -164,3 +164,7 @@ int32_t rk_launch_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const rk_p
                                    const uint32_t *prev_off, const rk_place_entry *prev_entries, uint64_t n_prev_entries,
                                    rk_assign *assign, uint32_t *place_off, rk_place_entry *entries, float *total,
                                    uint32_t *stats);
+// GetBestPlan(j, placement) for a given placement (arguments as rk_best_plan_placed, already validated, device current)
+int32_t rk_launch_best_plan_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table, const rk_alloc_grid *grid,
+                                   const rk_env *env, const rk_assign *assign, const uint32_t *place_off,
+                                   const rk_place_entry *entries, rk_assign *placed, float *total);

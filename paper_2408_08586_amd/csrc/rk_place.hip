@@ -768,6 +768,13 @@ extern "C" int32_t rk_best_plan_placed(rk_ctx *ctx, const rk_jobs *jobs, const r
     if (n_jobs > 0 && (!placed || !assign || !entries || !jobs->ref_thr)) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
     if (placed == assign) return rk_fail(ctx, RK_ERR_INVALID_ARG, "placed must not be the records it is chosen from");
     RK_HIP(ctx, hipSetDevice(ctx->device));
+    return rk_launch_best_plan_placed(ctx, jobs, table, grid, env, assign, place_off, entries, placed, total);
+}
+
+int32_t rk_launch_best_plan_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *table, const rk_alloc_grid *grid,
+                                   const rk_env *env, const rk_assign *assign, const uint32_t *place_off,
+                                   const rk_place_entry *entries, rk_assign *placed, float *total) {
+    const uint32_t n_jobs = table->n_jobs;
     if (n_jobs > 0) {
         ReplanArgs R;
         R.jobs = job_dev(jobs); R.tb = table_dev(table); R.grid = grid_dev(grid); R.env = *env;

@@ -10,8 +10,10 @@ namespace {
 // what a round leaves in the context's buffers for a step that follows it
 struct RoundKeep {
     rk_plan_table tb;
-    float *best_thr;
+    float *best_thr, *curve_thr;
+    uint32_t *best_plan;
     int32_t *min_seg;        // null without service levels
+    bool curves_only;        // set by the caller: stop after the curves, no allocation
 };
 
 // sla == NULL: every job is best-effort.  round_jobs != NULL: the rounds are made of slots, slot i
@@ -96,7 +98,10 @@ int32_t schedule_rounds(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *
     if ((rc = rk_scratch(ctx, SL_CURVE_G, n_out * 4, (void **)&curve_g))) return rc;
 
     if ((rc = rk_launch_fused(ctx, jobs, &tb, grid, env, 0, J, best_thr, best_plan, curve_thr, curve_plan, curve_g))) return rc;
-    if (keep) { keep->tb = tb; keep->best_thr = best_thr; keep->min_seg = nullptr; }
+    if (keep) {
+        keep->tb = tb; keep->best_thr = best_thr; keep->best_plan = best_plan; keep->curve_thr = curve_thr; keep->min_seg = nullptr;
+        if (keep->curves_only) return RK_OK;
+    }
     SlaDev S = {};
     if (sla && J > 0) {
         int32_t *min_seg;
@@ -173,10 +178,50 @@ int32_t rk_schedule_round_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan
     const rk_cluster cluster = {(uint32_t)G, (uint32_t)Cc, (float)nodes->n_nodes * nodes->mem_per_node_gb};
     const uint32_t off[2] = {0u, jobs->n_jobs};
     RoundKeep keep;
+    keep.curves_only = false;
     if ((rc = schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, nullptr, &cluster, jobs->n_jobs > 0 ? sla : nullptr, assign,
                               total, &keep))) return rc;
     return rk_launch_place_plans(ctx, jobs, &keep.tb, grid, env, nodes, keep.best_thr, assign, keep.min_seg, nullptr, nullptr,
                                  placed, place_off, entries, cap_entries, status, total, result);
+}
+
+int32_t rk_schedule_round_nodes(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_bounds *bounds,
+                                const rk_alloc_grid *grid, const rk_env *env, const rk_nodes *nodes,
+                                const rk_job_state *jobs_state, const uint32_t *prev_off,
+                                const rk_place_entry *prev_entries, uint64_t n_prev_entries, rk_assign *assign,
+                                rk_assign *placed, uint32_t *place_off, rk_place_entry *entries, uint64_t cap_entries,
+                                float *total, uint32_t *stats) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    if (!jobs || !nodes || !total || !jobs_state || !place_off) return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    const uint32_t J = jobs->n_jobs;
+    if (J > 0 && (!assign || !placed || !entries || !jobs_state->cur_seg || !jobs_state->cur_c))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    if (placed == assign && J > 0) return rk_fail(ctx, RK_ERR_INVALID_ARG, "placed must not be assign");
+    if ((prev_off == nullptr) != (prev_entries == nullptr))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "the earlier placement needs both its offsets and its entries");
+    if (nodes->n_nodes == 0 || nodes->n_nodes > RK_MAX_NODES || nodes->gpus_per_node == 0 ||
+        nodes->gpus_per_node > 65535u || nodes->cpus_per_node > 65535u || !(nodes->mem_per_node_gb >= 0.f))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "nodes: 1..%u nodes of 1..65535 GPUs, at most 65535 CPUs, memory >= 0", RK_MAX_NODES);
+    int32_t rc;
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    if (grid->cpu_mode != 1u)
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "the search over nodes needs CPU levels per GPU (cpu_mode 1)");
+    const uint64_t gpus = (uint64_t)nodes->n_nodes * nodes->gpus_per_node;
+    if (gpus > (1u << 20)) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than 2^20 GPUs on the nodes");
+    if (J > RK_MAX_JOBS_PER_ROUND)
+        return rk_fail(ctx, RK_ERR_UNSUPPORTED, "%u jobs, the allocation kernels take up to %u", J, RK_MAX_JOBS_PER_ROUND);
+    if (cap_entries < gpus && J > 0)
+        return rk_fail(ctx, RK_ERR_CAPACITY, "entries: %llu records, %llu may be needed", (unsigned long long)cap_entries, (unsigned long long)gpus);
+    // plan table and curves of all jobs in the context's buffers, then the loop over the nodes, then the plans for the splits
+    const rk_cluster whole = {(uint32_t)gpus, 0u, 0.f};
+    const uint32_t off[2] = {0u, J};
+    RoundKeep keep;
+    keep.curves_only = true;
+    if ((rc = schedule_rounds(ctx, jobs, bounds, grid, env, 1, off, nullptr, &whole, nullptr, assign, total, &keep))) return rc;
+    if ((rc = rk_launch_reschedule_nodes(ctx, jobs->ref_thr, &keep.tb, grid, nodes, keep.best_thr, keep.best_plan, keep.curve_thr,
+                                         jobs_state, prev_off, prev_entries, n_prev_entries, assign, place_off, entries, total,
+                                         stats))) return rc;
+    return rk_launch_best_plan_placed(ctx, jobs, &keep.tb, grid, env, assign, place_off, entries, placed, total);
 }
 
 }  // extern "C"

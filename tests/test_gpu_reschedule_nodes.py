@@ -248,6 +248,22 @@ def test_generated_rounds_from_a_running_state(gpu, orc, name):
     on = (a["g"] > 0)
     res = SimpleNamespace(n_entries=len(ent), n_placed=int(on.sum()), n_failed=0)
     compare(orc, wl, tb, w_placed, (rk.assign_to_numpy(placed), off, ent, on.astype(np.uint32), float(total2[0].item()), res))
+    # the whole round in one call, from the job descriptors: the same records, placement and plans
+    a1, p1, total1 = rk.new_assign(J, dev), rk.new_assign(J, dev), run.f32(1)
+    off1 = torch.full((J + 1,), -1, dtype=torch.int32, device=dev)
+    ent1 = rk.new_place_entries(n_nodes * gpn, dev)
+    st1 = torch.full((5,), -1, dtype=torch.int32, device=dev)
+    i32 = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
+    rk.rk_schedule_round_nodes(run.ctx, run.jobs, rk.make_bounds(wl.bounds), run.grid, run.env, rk.rk_nodes(*nodes), i32(cur_seg),
+                               run.dev_u32(cur_c), a1, p1, off1, ent1, n_nodes * gpn, total1,
+                               prev_off=torch.from_numpy(off0.view(np.int32).copy()).to(dev),
+                               prev_entries=torch.from_numpy((ent0 if ent0.size else np.zeros(1, rk.PLACE_DTYPE)).view(np.uint8).copy()).to(dev),
+                               n_prev_entries=len(ent0), state=torch.from_numpy(state).to(dev), floor_seg=i32(floor_seg),
+                               floor_c=run.dev_u32(floor_c), stats=st1)
+    rk.rk_sync(run.ctx)
+    assert np.array_equal(rk.assign_to_numpy(a1), a) and np.array_equal(rk.u32(off1), off)
+    assert np.array_equal(rk.place_entries_to_numpy(ent1, int(off[J])), ent) and st1.cpu().numpy().tolist() == stats.tolist()
+    assert np.array_equal(rk.assign_to_numpy(p1), rk.assign_to_numpy(placed)) and float(total1[0].item()) == float(total2[0].item())
     changed = int(((rk.assign_to_numpy(placed)["plan"] != a["plan"]) & on).sum())
     print(f"{name}: the actual splits change the plan of {changed} of {int(on.sum())} jobs ({n_band} inside the tie band)", flush=True)
     run.close()
