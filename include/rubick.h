@@ -662,6 +662,29 @@ int32_t rk_schedule_round_placed(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan
                                  uint32_t *place_off, rk_place_entry *entries, uint64_t cap_entries,
                                  uint32_t *status, float *total, rk_place_result *result);
 
+/* Who is privileged when Schedule runs from a running state (Sec. 5.2: the
+ * guaranteed jobs whose demands are within their tenant's remaining quota are
+ * scheduled first; the quota usage of a job is its minimum demand): turns the
+ * service levels into the floors and states rk_reschedule, rk_reschedule_rounds
+ * and rk_reschedule_nodes take.  Over all jobs of the table.
+ *  - A guaranteed job that holds something (held: state, cur_seg, cur_c) keeps
+ *    taking part; its minimum demand (min_seg, min_c as rk_min_res gives them;
+ *    none when min_seg is no index of its list or its tenant is unknown) is its
+ *    floor and is charged to its tenant's quota before any queued job is looked
+ *    at; a quota does not go below zero.
+ *  - Queued guaranteed jobs, in job order: a job whose minimum demand (GPUs,
+ *    CPUs) fits what is left of its tenant's quota gets it as its floor - the
+ *    loop then serves it first - and charges the quota; a job that does not
+ *    fit, or has no minimum demand, waits: state 1.
+ *  - Best-effort jobs have no floor.  A job whose given state says it takes no
+ *    part keeps that state and charges nothing.
+ *   sla        guaranteed, tenant, n_tenants, quota_g, quota_c are read
+ *   floor_seg, floor_c, state_out   [device] n_jobs entries each (state_out
+ *              must not be the array held->state points to) */
+int32_t rk_privileged(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_grid *grid, const rk_sla *sla,
+                      const int32_t *min_seg, const uint32_t *min_c, const rk_job_state *held, int32_t *floor_seg,
+                      uint32_t *floor_c, uint8_t *state_out);
+
 /* Algorithm 1's Schedule with ScheduleJob searching the cluster node by node
  * (Sec. 5.2, Algorithm 1: "for n in cluster.nodes", GetLowestSlopeOverMinJob(n,
  * resType), and the paragraph on shrinking).  State, order of the jobs, steps,

@@ -425,4 +425,20 @@ def reschedule_nodes(ref_thr, table, grid, n_nodes, gpus_per_node, cpus_per_node
     return assign, place_off, entries[:int(place_off[J])].copy(), total.value, moves.value
 
 
+def privileged(table, grid, guaranteed, tenant, min_seg, min_c, quota_g, quota_c, cur_seg, cur_c, state=None):
+    """Floors and states for the Schedule loops from the service levels -> (floor_seg, floor_c, state)."""
+    gh = _GridHolder(grid)
+    J = table.n_jobs
+    u32 = lambda a: np.ascontiguousarray(a, dtype=np.uint32)
+    guaranteed, tenant, min_c, quota_g, quota_c, cur_c = (u32(a) for a in (guaranteed, tenant, min_c, quota_g, quota_c, cur_c))
+    min_seg, cur_seg = np.ascontiguousarray(min_seg, dtype=np.int32), np.ascontiguousarray(cur_seg, dtype=np.int32)
+    state = None if state is None else np.ascontiguousarray(state, dtype=np.uint8)
+    floor_seg, floor_c, out = np.zeros(J, np.int32), np.zeros(J, np.uint32), np.zeros(J, np.uint8)
+    rc = lib().ork_privileged(C.c_uint32(J), C.byref(table.c), C.byref(gh.c), _p(guaranteed), _p(tenant), _p(min_seg), _p(min_c),
+                              C.c_uint32(quota_g.size), _p(quota_g), _p(quota_c), _p(state), _p(cur_seg), _p(cur_c),
+                              _p(floor_seg), _p(floor_c), _p(out))
+    assert rc == 0
+    return floor_seg, floor_c, out
+
+
 from . import simulator  # noqa: E402

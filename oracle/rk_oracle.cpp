@@ -1259,6 +1259,57 @@ int ork_reschedule_nodes_f32(uint32_t n_jobs, const float *ref_thr, const ork_ta
     return 0;
 }
 
+/* Who is privileged when Schedule runs from a running state (Sec. 5.2, "Scheduling algorithm design": the guaranteed
+ * jobs whose demands are within their tenant's remaining quota are scheduled first; the quota usage of a job is its
+ * minimum demand): the floors and states the loop takes.
+ *   - A guaranteed job that holds something keeps taking part; its minimum demand (min_seg, min_c as ork_min_res_f32
+ *     gives them; none when min_seg is not an index of its list or its tenant is unknown) is its floor and is charged
+ *     to its tenant's quota before any queued job is looked at (a quota cannot go below zero).
+ *   - Queued guaranteed jobs, in job order: a job whose minimum demand (GPUs, CPUs) fits what is left of its tenant's
+ *     quota gets it as its floor - the loop then serves it first - and charges the quota; a job that does not fit, or
+ *     has no minimum demand, waits: state 1.
+ *   - Best-effort jobs have no floor.  A job whose state says it takes no part keeps that state and charges nothing.
+ * PARITY UNPINNED as a reading; pinned by hand cases and, from an empty cluster, by the privileged phase of the
+ * allocation from scratch (ork_policy_f32) when capacity is plentiful. */
+int ork_privileged(uint32_t n_jobs, const ork_table *tb, const ork_grid *grid, const uint32_t *guaranteed,
+                   const uint32_t *tenant, const int32_t *min_seg, const uint32_t *min_c, uint32_t n_tenants,
+                   const uint32_t *quota_g, const uint32_t *quota_c, const uint8_t *state_in, const int32_t *cur_seg,
+                   const uint32_t *cur_c, int32_t *floor_seg, uint32_t *floor_c, uint8_t *state_out) {
+    std::vector<uint64_t> qg(quota_g, quota_g + n_tenants), qc(quota_c, quota_c + n_tenants);
+    auto ns_of = [&](uint32_t j) { return (int64_t)(tb->seg_off[j + 1] - tb->seg_off[j]); };
+    auto has_min = [&](uint32_t j) { return min_seg[j] >= 0 && min_seg[j] < ns_of(j) && tenant[j] < n_tenants; };
+    auto demand = [&](uint32_t j, uint64_t &g, uint64_t &c) {
+        g = tb->seg_g[tb->seg_off[j] + min_seg[j]];
+        c = cpus_of(grid, std::min(min_c[j], grid->n_cpu - 1), (uint32_t)g);
+    };
+    auto holds = [&](uint32_t j) {
+        const bool in = !state_in || state_in[j] == 0 || state_in[j] == 2;
+        return in && cur_seg[j] >= 0 && cur_seg[j] < ns_of(j) && cur_c[j] < grid->n_cpu;
+    };
+    for (uint32_t j = 0; j < n_jobs; ++j) {
+        floor_seg[j] = -1; floor_c[j] = 0;
+        state_out[j] = state_in ? state_in[j] : 0;
+        if (!guaranteed[j] || !holds(j) || !has_min(j)) continue;
+        uint64_t g, c;
+        demand(j, g, c);
+        floor_seg[j] = min_seg[j]; floor_c[j] = std::min(min_c[j], grid->n_cpu - 1);
+        qg[tenant[j]] -= std::min(qg[tenant[j]], g);
+        qc[tenant[j]] -= std::min(qc[tenant[j]], c);
+    }
+    for (uint32_t j = 0; j < n_jobs; ++j) {
+        if (!guaranteed[j] || holds(j) || state_out[j] != 0) continue;
+        uint64_t g = 0, c = 0;
+        if (has_min(j)) demand(j, g, c);
+        if (has_min(j) && g <= qg[tenant[j]] && c <= qc[tenant[j]]) {
+            floor_seg[j] = min_seg[j]; floor_c[j] = std::min(min_c[j], grid->n_cpu - 1);
+            qg[tenant[j]] -= g; qc[tenant[j]] -= c;
+        } else {
+            state_out[j] = 1;
+        }
+    }
+    return 0;
+}
+
 }  // extern "C"
 
 namespace {

@@ -213,6 +213,15 @@ int ork_reschedule_nodes_f32(uint32_t n_jobs, const float *ref_thr, const ork_ta
                              const ork_place_entry *prev_entries, ork_assign *assign, uint32_t *place_off,
                              ork_place_entry *entries, double *total, uint32_t *n_moves);
 
+/* Floors and states for the Schedule loops from the service levels: running
+ * guaranteed jobs keep their minimum demand as floor and charge their tenant's
+ * quota first; queued guaranteed jobs get theirs in job order while the quota
+ * lasts, the others wait (state 1). */
+int ork_privileged(uint32_t n_jobs, const ork_table *table, const ork_grid *grid, const uint32_t *guaranteed,
+                   const uint32_t *tenant, const int32_t *min_seg, const uint32_t *min_c, uint32_t n_tenants,
+                   const uint32_t *quota_g, const uint32_t *quota_c, const uint8_t *state_in, const int32_t *cur_seg,
+                   const uint32_t *cur_c, int32_t *floor_seg, uint32_t *floor_c, uint8_t *state_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,6 +50,7 @@ enum {
     SL_RS_F32, SL_RS_U32, SL_RS_U64,                     // the Schedule loop: cached slopes; order, marks and saved states; CPU needs
     SL_EVAL_PARTIAL,                                     // evaluation with best plan: keys of the segments that span tiles
     SL_PLACE_KEEP,                                       // placement: which jobs keep their earlier parts
+    SL_PRIV_LIST,                                        // privileged jobs of the loop: the queued guaranteed jobs
     SL_SIM_PLACES,                                       // simulation over nodes: where the jobs are, where they go
     SL_ND_NODES, SL_ND_U32, SL_ND_F32, SL_ND_U64,        // the Schedule loop over nodes: node tables and their copy; per-job words
     SL_COUNT

@@ -113,6 +113,112 @@ __global__ __launch_bounds__(POINT_THREADS) void k_eval_points(JobDev jobs, Tabl
     if (WITH_FEAS) feas[i] = (uint8_t)why;
 }
 
+
+// ------------------------------------------------------------------ who is privileged when the loop runs
+// Floors and states for Algorithm 1's Schedule loops from the service levels (paper Sec. 5.2: the guaranteed jobs whose
+// demands are within their tenant's remaining quota are scheduled first; a job's quota usage is its minimum demand).
+// One workgroup.  Running guaranteed jobs are charged first, all at once (a quota that cannot go below zero ends at
+// max(0, quota - sum) whatever the order); the queued ones are gathered in job order and every tenant's thread then
+// walks the list for its own jobs, which is the only part that has an order.
+constexpr int PRIV_THREADS = 1024;
+
+struct PrivArgs {
+    TableDev tb;
+    GridDev grid;
+    uint32_t n_jobs, n_tenants;
+    const uint32_t *guaranteed, *tenant, *quota_g, *quota_c;
+    const int32_t *min_seg;
+    const uint32_t *min_c;
+    const uint8_t *state_in;     // may be null
+    const int32_t *cur_seg;
+    const uint32_t *cur_c;
+    int32_t *floor_seg;
+    uint32_t *floor_c;
+    uint8_t *state_out;
+    uint32_t *list;              // queued guaranteed jobs in job order: job, tenant (n_tenants: none), GPUs, CPUs
+};
+
+__global__ __launch_bounds__(PRIV_THREADS) void k_privileged(PrivArgs A) {
+    __shared__ unsigned long long qg[RK_MAX_TENANTS], qc[RK_MAX_TENANTS];
+    __shared__ uint32_t sh_scan[PRIV_THREADS / 64], sh_n;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, J = A.n_jobs, T = A.n_tenants;
+    if (tid < T) { qg[tid] = 0ull; qc[tid] = 0ull; }
+    if (tid == 0) sh_n = 0u;
+    __syncthreads();
+    auto ns_of = [&](uint32_t j) { return A.tb.seg_off[j + 1] - A.tb.seg_off[j]; };
+    auto has_min = [&](uint32_t j) { return A.min_seg[j] >= 0 && (uint32_t)A.min_seg[j] < ns_of(j) && A.tenant[j] < T; };
+    auto level_of = [&](uint32_t j) { return A.min_c[j] < A.grid.n_cpu ? A.min_c[j] : A.grid.n_cpu - 1u; };
+    auto holds = [&](uint32_t j) {
+        const bool in = !A.state_in || A.state_in[j] == 0 || A.state_in[j] == 2;
+        return in && A.cur_seg[j] >= 0 && (uint32_t)A.cur_seg[j] < ns_of(j) && A.cur_c[j] < A.grid.n_cpu;
+    };
+    // the running guaranteed jobs: their floors, and what they use of their tenants' quotas
+    for (uint32_t base = 0; base < J; base += PRIV_THREADS) {
+        const uint32_t j = base + tid;
+        bool queued = false;
+        uint32_t tn = T, g = 0, c = 0;
+        if (j < J) {
+            int32_t fs = -1;
+            uint32_t fc = 0;
+            const uint8_t st = A.state_in ? A.state_in[j] : (uint8_t)0;
+            if (A.guaranteed[j]) {
+                const bool with_min = has_min(j);
+                if (with_min) {
+                    g = A.tb.seg_g[A.tb.seg_off[j] + (uint32_t)A.min_seg[j]];
+                    c = cpus_of(A.grid, level_of(j), g);
+                    tn = A.tenant[j];
+                }
+                if (holds(j)) {
+                    if (with_min) {
+                        fs = A.min_seg[j]; fc = level_of(j);
+                        atomicAdd(&qg[tn], (unsigned long long)g);
+                        atomicAdd(&qc[tn], (unsigned long long)c);
+                    }
+                } else if (st == 0) {
+                    queued = true;
+                }
+            }
+            A.floor_seg[j] = fs; A.floor_c[j] = fc; A.state_out[j] = st;
+        }
+        // the queued ones of this batch go to the list, in job order
+        uint32_t inc = queued ? 1u : 0u;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t o = __shfl_up(inc, off, 64);
+            if ((int)lane >= off) inc += o;
+        }
+        if (lane == 63) sh_scan[wave] = inc;
+        __syncthreads();
+        uint32_t before = sh_n, all = 0;
+        for (uint32_t w = 0; w < PRIV_THREADS / 64; ++w) { if (w < wave) before += sh_scan[w]; all += sh_scan[w]; }
+        if (queued) {
+            uint32_t *e = A.list + 4 * (size_t)(before + inc - 1u);
+            e[0] = j; e[1] = tn; e[2] = g; e[3] = c;
+        }
+        __syncthreads();
+        if (tid == 0) sh_n += all;
+        __syncthreads();
+    }
+    const uint32_t n_queued = sh_n;
+    if (tid < T) {
+        const unsigned long long ug = qg[tid], uc = qc[tid], hg = A.quota_g[tid], hc = A.quota_c[tid];
+        unsigned long long left_g = hg > ug ? hg - ug : 0ull, left_c = hc > uc ? hc - uc : 0ull;
+        for (uint32_t i = 0; i < n_queued; ++i) {
+            if (A.list[4 * (size_t)i + 1] != tid) continue;
+            const uint32_t j = A.list[4 * (size_t)i], g = A.list[4 * (size_t)i + 2], c = A.list[4 * (size_t)i + 3];
+            if (g <= left_g && c <= left_c) {
+                A.floor_seg[j] = A.min_seg[j]; A.floor_c[j] = level_of(j);
+                left_g -= g; left_c -= c;
+            } else {
+                A.state_out[j] = 1;
+            }
+        }
+    }
+    // queued guaranteed jobs without a minimum demand or with an unknown tenant wait
+    for (uint32_t i = tid; i < n_queued; i += PRIV_THREADS)
+        if (A.list[4 * (size_t)i + 1] >= T) A.state_out[A.list[4 * (size_t)i]] = 1;
+}
+
 }  // namespace
 
 int32_t rk_launch_min_res(rk_ctx *ctx, const TableDev &tb, const rk_alloc_grid *grid, uint32_t jb, uint32_t je,
@@ -166,6 +272,33 @@ int32_t rk_eval_points(rk_ctx *ctx, const rk_jobs *jobs, const rk_plan_table *ta
                                                                        jobs->n_jobs, table->option_mask, n_points, pt_job,
                                                                        pt_plan, pt_c, pt_m, thr, nullptr);
     RK_CHECK_LAUNCH(ctx, "k_eval_points");
+    return RK_OK;
+}
+
+int32_t rk_privileged(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_grid *grid, const rk_sla *sla,
+                      const int32_t *min_seg, const uint32_t *min_c, const rk_job_state *held, int32_t *floor_seg,
+                      uint32_t *floor_c, uint8_t *state_out) {
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    int32_t rc;
+    if ((rc = rk_check_table(ctx, table, 0, table ? table->n_jobs : 0))) return rc;
+    if ((rc = rk_check_grid(ctx, grid))) return rc;
+    const uint32_t J = table->n_jobs;
+    if (J == 0) return RK_OK;
+    if (!sla || !sla->guaranteed || !sla->tenant || (sla->n_tenants > 0 && (!sla->quota_g || !sla->quota_c)))
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "sla: guaranteed, tenant or quota array is null");
+    if (sla->n_tenants > RK_MAX_TENANTS) return rk_fail(ctx, RK_ERR_UNSUPPORTED, "more than %u tenants", RK_MAX_TENANTS);
+    if (!min_seg || !min_c || !held || !held->cur_seg || !held->cur_c || !floor_seg || !floor_c || !state_out)
+        return rk_fail(ctx, RK_ERR_INVALID_ARG, "null argument");
+    RK_HIP(ctx, hipSetDevice(ctx->device));
+    PrivArgs A;
+    A.tb = table_dev(table); A.grid = grid_dev(grid); A.n_jobs = J; A.n_tenants = sla->n_tenants;
+    A.guaranteed = sla->guaranteed; A.tenant = sla->tenant; A.quota_g = sla->quota_g; A.quota_c = sla->quota_c;
+    A.min_seg = min_seg; A.min_c = min_c;
+    A.state_in = held->state; A.cur_seg = held->cur_seg; A.cur_c = held->cur_c;
+    A.floor_seg = floor_seg; A.floor_c = floor_c; A.state_out = state_out;
+    if ((rc = rk_scratch(ctx, SL_PRIV_LIST, (size_t)J * 16, (void **)&A.list))) return rc;
+    k_privileged<<<1, PRIV_THREADS, 0, ctx->stream>>>(A);
+    RK_CHECK_LAUNCH(ctx, "k_privileged");
     return RK_OK;
 }
 

@@ -406,3 +406,51 @@ def test_sla_argument_errors(gpu, orc):
     rk.rk_min_res(run.ctx, run.table.c, run.grid, 3, 3, bt, no_request, ms, mc, mc)
     rk.rk_eval_points(run.ctx, run.jobs, run.table.c, run.grid, run.env, None, None, None, None, run.f32(0)[:0])
     run.close()
+
+
+def test_privileged_jobs_for_the_loop(gpu, orc):
+    """rk_privileged against the oracle on drawn service levels and states: floors and states bit for bit; then the loop
+    from them on both sides (service levels -> minimum demands -> who is privileged -> Algorithm 1's loop)."""
+    import torch
+    import paper_2408_08586_amd as rk
+    from test_gpu_reschedule import random_round, on_gpu as loop_on_gpu, same as same_round
+    n_wait = n_floor = 0
+    for seed in range(120):
+        rng = np.random.default_rng(61000 + seed)
+        big = seed % 10 == 9
+        wl, tb, bt, bp, ct, cur_seg, cur_c, _, _, state = random_round(rng, orc, 3000 if big else None, 12 if big else None)
+        J = wl.n_jobs
+        T = int(rng.choice([1, 3, 17, 256]))
+        guaranteed = (rng.uniform(size=J) < 0.5).astype(np.uint32)
+        tenant = rng.integers(0, T + 2, J).astype(np.uint32)                 # a few unknown tenants
+        ns = np.diff(tb.seg_off)
+        min_seg = np.where(rng.uniform(size=J) < 0.85, rng.integers(0, np.maximum(ns, 1)), -1).astype(np.int32)
+        min_seg[rng.uniform(size=J) < 0.03] = 10 ** 6                        # not an index of the job's list
+        min_c = rng.integers(0, len(wl.grid.cpu_levels) + 1, J).astype(np.uint32)        # one level beyond the grid: clamped
+        scale = max(1, J // max(T, 1))
+        quota_g = rng.integers(0, 4 * scale + 2, T).astype(np.uint32)
+        quota_c = rng.integers(0, 16 * scale + 2, T).astype(np.uint32)
+        use_state = seed % 3 != 0
+        st_in = state if use_state else None
+        want = orc.privileged(tb, wl.grid, guaranteed, tenant, min_seg, min_c, quota_g, quota_c, cur_seg, cur_c, state=st_in)
+        run = gpu(wl)
+        run.enumerate()
+        dev = run.device
+        sla = rk.Sla(guaranteed, tenant, quota_g, quota_c, device=dev)
+        i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+        fs, fc = torch.full((J,), -7, dtype=torch.int32, device=dev), torch.full((J,), -7, dtype=torch.int32, device=dev)
+        so = torch.full((J,), 77, dtype=torch.uint8, device=dev)
+        rk.rk_privileged(run.ctx, run.table.c, run.grid, sla, i32(min_seg), run.dev_u32(min_c), i32(cur_seg), run.dev_u32(cur_c),
+                         fs, fc, so, state=None if st_in is None else torch.from_numpy(st_in).to(dev))
+        rk.rk_sync(run.ctx)
+        g_fs, g_fc, g_so = fs.cpu().numpy(), fc.cpu().numpy().view(np.uint32), so.cpu().numpy()
+        assert np.array_equal(g_fs, want[0]) and np.array_equal(g_fc, want[1]) and np.array_equal(g_so, want[2]), seed
+        n_wait += int(((want[2] == 1) & ((st_in if st_in is not None else 0) == 0)).sum())
+        n_floor += int((want[0] >= 0).sum())
+        if seed % 4 == 0:                                                    # ... and the loop from these floors and states
+            w_round = orc.reschedule(wl.coef[:, 16], tb, wl.grid, wl.cluster, bt, bp, ct, cur_seg, cur_c, want[0], want[1],
+                                     state=want[2])
+            same_round(loop_on_gpu(run, bt, bp, ct, wl.cluster, cur_seg, cur_c, g_fs, g_fc, g_so), w_round)
+        run.close()
+    print(f"120 cases: {n_floor} floors granted, {n_wait} jobs wait")
+    assert n_floor > 500 and n_wait > 500

@@ -186,3 +186,65 @@ def test_policy_invariants_on_generated_workload(orc):
     for t in range(4):
         js = [j for j in np.flatnonzero(guaranteed) if tenant[j] == t and a["g"][j] > 0]
         assert sum(int(tb.seg_g[tb.seg_off[j] + seg[j]]) for j in js) <= quota_g[t]
+
+
+def privileged_case(orc, guaranteed, tenant, min_g, min_c, quota_g, quota_c, hold, state=None, levels=(1, 2), mode=0):
+    """min_g[j], hold[j]: GPUs (0 = none) out of the counts 1, 2, 4, 8."""
+    J = len(guaranteed)
+    tb = orc.enumerate_plans(np.tile(np.array([[8, 8, 1]], np.uint32), (J, 1)), workloads.Bounds(g_max=8))
+    grid = workloads.Grid(np.array(levels, np.uint32), mode, np.array([1.0], np.float32), 0)
+    seg = lambda g: [1, 2, 4, 8].index(g) if g else -1
+    return orc.privileged(tb, grid, guaranteed, tenant, [seg(g) for g in min_g], min_c, quota_g, quota_c,
+                          [seg(g) for g in hold], np.zeros(J, np.uint32), state=state)
+
+
+def test_privileged_jobs_for_the_loop(orc):
+    # three queued guaranteed jobs of one tenant with 4-GPU minima and a quota of 10 GPUs: the first two get their floor
+    # (the loop will serve them first), the third waits
+    fs, fc, st = privileged_case(orc, [1, 1, 1], [0, 0, 0], [4, 4, 4], [0, 0, 0], [10], [100], [0, 0, 0])
+    assert fs.tolist() == [2, 2, -1] and st.tolist() == [0, 0, 1]
+    # a running guaranteed job is charged first, whatever its index: job 2 runs, so only one queued job fits beside it
+    fs, fc, st = privileged_case(orc, [1, 1, 1], [0, 0, 0], [4, 4, 4], [0, 0, 0], [10], [100], [0, 0, 8])
+    assert fs.tolist() == [2, -1, 2] and st.tolist() == [0, 1, 0]
+    # ... and keeps taking part even when the quota would not admit it today (its floor stays, nothing is left)
+    fs, fc, st = privileged_case(orc, [1, 1], [0, 0], [4, 4], [0, 0], [3], [100], [8, 0])
+    assert fs.tolist() == [2, -1] and st.tolist() == [0, 1]
+    # tenants have separate quotas; the CPU quota binds as well (level 1 = 2 CPUs per job here)
+    fs, fc, st = privileged_case(orc, [1, 1], [0, 1], [4, 4], [0, 0], [5, 5], [100, 100], [0, 0])
+    assert st.tolist() == [0, 0]
+    fs, fc, st = privileged_case(orc, [1, 1], [0, 0], [2, 2], [1, 1], [100], [3], [0, 0])
+    assert fs.tolist() == [1, -1] and fc.tolist() == [1, 0] and st.tolist() == [0, 1]
+    # with CPUs per GPU the demand is level * GPUs: 2 GPUs at 2 per GPU need 4
+    fs, fc, st = privileged_case(orc, [1], [0], [2], [1], [100], [3], [0], mode=1)
+    assert st.tolist() == [1]
+    # no minimum demand, or an unknown tenant: a queued job waits, a running one goes on without a floor
+    fs, fc, st = privileged_case(orc, [1, 1, 1, 1], [0, 9, 0, 9], [0, 4, 0, 4], [0] * 4, [100], [100], [0, 0, 4, 4])
+    assert fs.tolist() == [-1] * 4 and st.tolist() == [1, 1, 0, 0]
+    # best-effort jobs are left alone; states that are given are kept (a job that takes no part charges nothing,
+    # a job that keeps what it holds is charged like any running job)
+    fs, fc, st = privileged_case(orc, [0, 1, 1, 1], [0, 0, 0, 0], [4, 4, 4, 4], [0] * 4, [8], [100], [2, 4, 4, 0],
+                                 state=[0, 1, 2, 0])
+    assert fs.tolist() == [-1, -1, 2, 2] and st.tolist() == [0, 1, 2, 0]
+
+
+def test_privileged_from_an_empty_cluster_is_the_privileged_phase_of_the_allocation(orc):
+    """With nobody running and capacity to spare, the jobs that get a floor here are the jobs the allocation from scratch
+    grants their minimum (its privileged phase has the same quota rule, pinned above)."""
+    rng = np.random.default_rng(31)
+    for trial in range(200):
+        J, T = int(rng.integers(1, 12)), int(rng.integers(1, 4))
+        guaranteed = (rng.uniform(size=J) < 0.6).astype(np.uint32)
+        tenant = rng.integers(0, T + 1, J).astype(np.uint32)                # T = unknown tenant
+        min_g = [int(rng.choice([0, 1, 2, 4, 8])) for _ in range(J)]
+        min_c = rng.integers(0, 2, J).astype(np.uint32)
+        quota_g, quota_c = rng.integers(0, 20, T).astype(np.uint32), rng.integers(0, 12, T).astype(np.uint32)
+        fs, fc, st = privileged_case(orc, guaranteed, tenant, min_g, min_c, quota_g, quota_c, [0] * J)
+        c = [1.0, 2.0, 3.0, 4.0]
+        seg = [[1, 2, 4, 8].index(g) if g else -1 for g in min_g]
+        a, _, _ = floors_case(orc, [c] * J, guaranteed, tenant, seg, min_c, quota_g, quota_c, G=10 ** 5)
+        for j in range(J):
+            if guaranteed[j]:
+                assert (st[j] == 0) == (a["g"][j] > 0), (trial, j)                   # waits there, waits here
+                assert (fs[j] >= 0) == (a["g"][j] > 0)
+            else:
+                assert st[j] == 0 and fs[j] == -1
