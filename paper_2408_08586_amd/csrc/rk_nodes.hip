@@ -484,24 +484,19 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
         }
     };
 
-    // ---- privileged jobs (below their floor), in job order
-    for (uint32_t base = 0; base < J; base += ND_THREADS) {  // their list: 1,024 jobs at a time (tmp_off serves as the list)
+    // ---- privileged jobs (below their floor) come first, in job order: their list (tmp_off serves as the list)
+    uint32_t n_first = 0;
+    for (uint32_t base = 0; base < J; base += ND_THREADS) {
         const uint32_t j = base + tid;
         const bool is = j < J && A.first[j] != 0u;
         uint32_t all;
         const uint32_t at = block_scan(is ? 1u : 0u, all);
-        if (is) A.tmp_off[at] = j;
-        __syncthreads();
-        for (uint32_t k = 0; k < all; ++k) schedule_job(A.tmp_off[k]);
-        __syncthreads();
-    }
-    // ---- the others: their order is fixed once, by GPU slope, then CPU slope (both descending), then index
-    for (uint32_t j = tid; j < J; j += ND_THREADS) {
-        const bool in = rs_part(A, j) && !A.first[j];
-        A.sg[j] = in ? A.ug[j] : -1.f;                       // the cached slopes are current; -1: not in the list
-        A.sc[j] = in ? A.uc[j] : -1.f;
+        if (is) A.tmp_off[n_first + at] = j;
+        n_first += all;
     }
     __syncthreads();
+    // ---- then the others: their order is fixed once (when the privileged jobs are through), by GPU slope, then CPU
+    // slope (both descending), then index.
     // Most jobs find nothing to do when their turn comes, and whether that is so follows from values that change
     // only when a step is committed.  A GPU step does nothing when there is none, or when what the nodes can give
     // a job at its level (GPUs with their CPUs) is less than the step needs and no job anywhere has a slope below
@@ -513,8 +508,21 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
         return ga > gb || (ga == gb && (ca > cb || (ca == cb && a < b)));
     };
     float last_g = INF, last_c = INF;
-    uint32_t last_j = 0u, moves_seen = ND_NONE;
-    for (;;) {
+    uint32_t last_j = 0u, moves_seen = ND_NONE, k_first = 0;
+    bool others = false;
+    for (;;) {                                               // one job per turn; ScheduleJob appears once in the code
+        if (k_first < n_first) {
+            schedule_job(A.tmp_off[k_first++]);
+            continue;
+        }
+        if (!others) {
+            for (uint32_t j = tid; j < J; j += ND_THREADS) {
+                const bool in = rs_part(A, j) && !A.first[j];
+                A.sg[j] = in ? A.ug[j] : -1.f;               // the cached slopes are current; -1: not in the list
+                A.sc[j] = in ? A.uc[j] : -1.f;
+            }
+            others = true;
+        }
         __syncthreads();
         const bool fresh = sh_moves != moves_seen;          // a step was committed since the last look (or this is the first)
         moves_seen = sh_moves;
