@@ -324,6 +324,37 @@ def algorithm1_bench(rk, ctx, dev, wl, jobs, table, grid, env, best_thr, best_pl
                               "ms": float(np.median(ms64)), "ms_per_round": float(np.median(ms64)) / n_what,
                               "rounds_per_s": n_what / (float(np.median(ms64)) * 1e-3)}
     del outs
+    # service levels through the loop: 30 % guaranteed jobs of 6 tenants (quotas: half the cluster), minimum demands at
+    # half the drawn request; rk_privileged turns them into floors and states, the loop runs from these
+    import workloads
+    sl = workloads.sla_draws(wl, quota_share=0.5)
+    ns = (seg_off[1:] - seg_off[:-1])
+    min_seg = np.where(ns > 0, np.minimum((sl.u_seg * ns * 0.5).astype(np.int64), np.maximum(ns - 1, 0)), -1).astype(np.int32)
+    sla = rk.Sla(sl.guaranteed, sl.tenant, sl.quota_g, sl.quota_c, device=dev)
+    d_min = torch.from_numpy(min_seg).to(dev)
+    d_minc = torch.zeros(J, dtype=torch.int32, device=dev)
+    fl_s, fl_c = torch.zeros(J, dtype=torch.int32, device=dev), torch.zeros(J, dtype=torch.int32, device=dev)
+    st_o = torch.zeros(J, dtype=torch.uint8, device=dev)
+    ms_p, ms_l = [], []
+    for i in range(reps + 2):
+        a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        a.record()
+        rk.rk_privileged(ctx, table.c, grid, sla, d_min, d_minc, d_seg, d_c, fl_s, fl_c, st_o)
+        b.record()
+        rk.rk_reschedule(ctx, jobs.ref_thr, table.c, grid, small, best_thr, best_plan, curve_thr, d_seg, d_c, out, total,
+                         state=st_o, floor_seg=fl_s, floor_c=fl_c, n_moves=moves)
+        c.record()
+        torch.cuda.synchronize()
+        if i >= 2:
+            ms_p.append(a.elapsed_time(b)); ms_l.append(b.elapsed_time(c))
+    res_s = rk.assign_to_numpy(out)
+    gu = sl.guaranteed != 0
+    info["with_service_levels"] = {"entry": "rk_privileged, then rk_reschedule from its floors and states",
+                                   "guaranteed_jobs": int(gu.sum()), "floors_granted": int((fl_s.cpu().numpy() >= 0).sum()),
+                                   "jobs_that_wait": int((st_o.cpu().numpy() == 1).sum()),
+                                   "guaranteed_jobs_running_after": int((gu & (res_s["g"] > 0)).sum()),
+                                   "steps_committed": int(moves[0].item()), "privileged_ms": float(np.median(ms_p)),
+                                   "loop_ms": float(np.median(ms_l))}
     gpn, n_nodes = 8, max(1, wl.cluster.G // 8)
     cap = n_nodes * gpn
     placed = rk.new_assign(J, dev)

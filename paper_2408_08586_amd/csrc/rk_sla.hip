@@ -118,8 +118,9 @@ __global__ __launch_bounds__(POINT_THREADS) void k_eval_points(JobDev jobs, Tabl
 // Floors and states for Algorithm 1's Schedule loops from the service levels (paper Sec. 5.2: the guaranteed jobs whose
 // demands are within their tenant's remaining quota are scheduled first; a job's quota usage is its minimum demand).
 // One workgroup.  Running guaranteed jobs are charged first, all at once (a quota that cannot go below zero ends at
-// max(0, quota - sum) whatever the order); the queued ones are gathered in job order and every tenant's thread then
-// walks the list for its own jobs, which is the only part that has an order.
+// max(0, quota - sum) whatever the order); the queued ones are gathered in job order, their tenants in LDS.  A
+// wavefront per tenant then walks the list 64 entries at a time: a ballot finds the tenant's jobs among them, their
+// demands are already in the lanes' registers, and only the quota arithmetic of those jobs runs one after another.
 constexpr int PRIV_THREADS = 1024;
 
 struct PrivArgs {
@@ -141,6 +142,7 @@ struct PrivArgs {
 __global__ __launch_bounds__(PRIV_THREADS) void k_privileged(PrivArgs A) {
     __shared__ unsigned long long qg[RK_MAX_TENANTS], qc[RK_MAX_TENANTS];
     __shared__ uint32_t sh_scan[PRIV_THREADS / 64], sh_n;
+    __shared__ uint16_t sh_tenant[RK_MAX_JOBS_PER_ROUND];   // tenant of every list entry (n_tenants: none)
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, J = A.n_jobs, T = A.n_tenants;
     if (tid < T) { qg[tid] = 0ull; qc[tid] = 0ull; }
     if (tid == 0) sh_n = 0u;
@@ -194,23 +196,35 @@ __global__ __launch_bounds__(PRIV_THREADS) void k_privileged(PrivArgs A) {
         if (queued) {
             uint32_t *e = A.list + 4 * (size_t)(before + inc - 1u);
             e[0] = j; e[1] = tn; e[2] = g; e[3] = c;
+            sh_tenant[before + inc - 1u] = (uint16_t)tn;
         }
         __syncthreads();
         if (tid == 0) sh_n += all;
         __syncthreads();
     }
     const uint32_t n_queued = sh_n;
-    if (tid < T) {
-        const unsigned long long ug = qg[tid], uc = qc[tid], hg = A.quota_g[tid], hc = A.quota_c[tid];
-        unsigned long long left_g = hg > ug ? hg - ug : 0ull, left_c = hc > uc ? hc - uc : 0ull;
-        for (uint32_t i = 0; i < n_queued; ++i) {
-            if (A.list[4 * (size_t)i + 1] != tid) continue;
-            const uint32_t j = A.list[4 * (size_t)i], g = A.list[4 * (size_t)i + 2], c = A.list[4 * (size_t)i + 3];
-            if (g <= left_g && c <= left_c) {
-                A.floor_seg[j] = A.min_seg[j]; A.floor_c[j] = level_of(j);
-                left_g -= g; left_c -= c;
-            } else {
-                A.state_out[j] = 1;
+    for (uint32_t t = wave; t < T; t += PRIV_THREADS / 64) {
+        const unsigned long long ug = qg[t], uc = qc[t], hg = A.quota_g[t], hc = A.quota_c[t];
+        unsigned long long left_g = hg > ug ? hg - ug : 0ull, left_c = hc > uc ? hc - uc : 0ull;   // the same in all lanes
+        for (uint32_t base = 0; base < n_queued; base += 64u) {
+            const uint32_t i = base + lane;
+            const bool mine = i < n_queued && sh_tenant[i] == t;
+            unsigned long long todo = __ballot(mine);
+            if (!todo) continue;
+            uint32_t j = 0, g = 0, c = 0;
+            if (mine) { j = A.list[4 * (size_t)i]; g = A.list[4 * (size_t)i + 2]; c = A.list[4 * (size_t)i + 3]; }
+            bool granted = false;
+            while (todo) {                                   // this tenant's jobs among the 64, in job order
+                const int b = __ffsll((long long)todo) - 1;
+                todo &= todo - 1ull;
+                const uint32_t gb = __shfl(g, b, 64), cb = __shfl(c, b, 64);
+                const bool fits = gb <= left_g && cb <= left_c;
+                if (fits) { left_g -= gb; left_c -= cb; }
+                if ((int)lane == b) granted = fits;
+            }
+            if (mine) {
+                if (granted) { A.floor_seg[j] = A.min_seg[j]; A.floor_c[j] = level_of(j); }
+                else A.state_out[j] = 1;
             }
         }
     }
