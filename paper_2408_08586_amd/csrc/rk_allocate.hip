@@ -1548,9 +1548,15 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
                     const float *ds = res == 0 ? A.ds_g : A.ds_c;
                     float best = INF;
                     uint32_t who = 0xFFFFFFFFu;
-                    for (uint32_t v = tid; v < J; v += RS_THREADS) {
-                        const float s = ds[v];
-                        if (v != j && s < best) { best = s; who = v; }
+                    for (uint32_t v0 = tid; v0 < J; v0 += 4 * RS_THREADS) {      // four loads in flight
+                        float x[4];
+#pragma unroll
+                        for (uint32_t k = 0; k < 4; ++k) x[k] = v0 + k * RS_THREADS < J ? ds[v0 + k * RS_THREADS] : INF;
+#pragma unroll
+                        for (uint32_t k = 0; k < 4; ++k) {
+                            const uint32_t v = v0 + k * RS_THREADS;
+                            if (v != j && x[k] < best) { best = x[k]; who = v; }
+                        }
                     }
 #pragma unroll
                     for (int off = 32; off >= 1; off >>= 1) {
