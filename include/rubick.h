@@ -533,8 +533,8 @@ typedef struct {
 } rk_sim_result;
 
 /* Discrete-time simulation of the whole job set on cached curves (Sec. 5.2: the
- * curves do not depend on the cluster's state and can be computed once; "a job
- * is reconfigured only if (T - N*delta)/T exceeds a threshold"; Sec. 7.4: a
+ * curves do not depend on the cluster's state and can be computed once; the
+ * reconfiguration rule compares (T - N*delta)/T with a threshold; Sec. 7.4: a
  * discrete-time simulator).  The arrays best_thr, best_plan, curve_thr are in
  * segment layout of all jobs (as rk_job_curves writes them for [0, n_jobs)).
  * Every tick k, at t = k*dt:
@@ -686,8 +686,9 @@ int32_t rk_privileged(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_gr
                       uint32_t *floor_c, uint8_t *state_out);
 
 /* Algorithm 1's Schedule with ScheduleJob searching the cluster node by node
- * (Sec. 5.2, Algorithm 1: "for n in cluster.nodes", GetLowestSlopeOverMinJob(n,
- * resType), and the paragraph on shrinking).  State, order of the jobs, steps,
+ * (Sec. 5.2, Algorithm 1: ScheduleJob's loop over the nodes, whose
+ * GetLowestSlopeOverMinJob takes the node as its argument; and the paragraph
+ * on shrinking).  State, order of the jobs, steps,
  * slopes, permit cases and commit rule are those of rk_reschedule; here every
  * job that holds something is somewhere, and the job to shrink on a node is
  * the one with the lowest slope among the jobs on THAT node.

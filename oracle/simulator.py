@@ -1,7 +1,7 @@
 """Discrete-time cluster simulation on the CPU oracle (paper Sec. 7.4: a
 discrete-time simulator replays job traces through the scheduling policy;
-Sec. 5.2 "Incorporating reconfiguration penalty": a job is reconfigured only
-if (T - N*delta)/T exceeds 0.97).
+Sec. 5.2, paragraph on the reconfiguration penalty: the rule compares
+(T - N*delta)/T with a threshold of 0.97).
 
 TEST INFRASTRUCTURE ONLY, like the rest of oracle/.
 
