@@ -307,3 +307,51 @@ def test_argument_errors(gpu, orc):
     want = orc.reschedule_nodes(wl.coef[:, 16], tb, wl.grid, *nodes, bt, bp, ct, np.full(J, -1), np.zeros(J), None)
     assert np.array_equal(a, want[0])
     run.close()
+
+
+def test_tables_without_jobs_or_without_plans(gpu, orc):
+    """Zero jobs, and jobs none of which has a plan (no segment: the value arrays are empty and may be null), through the
+    entry points of the loops: nothing is scheduled, nothing is read that is not there."""
+    import torch
+    import paper_2408_08586_amd as rk
+    base = workloads.tiny()
+    grid = workloads.Grid(np.array([1, 2], np.uint32), 1, np.array([0.0, 8.0], np.float32), 0)
+    for name, coef, ints in (("empty", base.coef[:0], base.ints[:0]),
+                             ("noplans", base.coef[:3], np.array([[5, 7, 2], [0, 8, 1], [8, 0, 1]], np.uint32))):
+        wl = workloads.Workload(name, coef, ints, base.bounds, grid, base.env, base.cluster)
+        J = wl.n_jobs
+        run = gpu(wl)
+        t = run.enumerate()
+        assert t.n_segs == 0
+        dev = run.device
+        nodes = rk.rk_nodes(2, 4, 16, 64.0)
+        seg = torch.full((max(J, 1),), -1, dtype=torch.int32, device=dev)
+        lvl = torch.zeros(max(J, 1), dtype=torch.int32, device=dev)
+        assign, placed, total = rk.new_assign(max(J, 1), dev), rk.new_assign(max(J, 1), dev), run.f32(1)
+        off = torch.full((J + 1,), -1, dtype=torch.int32, device=dev)
+        ent = rk.new_place_entries(8, dev)
+        stats = torch.full((5,), -1, dtype=torch.int32, device=dev)
+        rk.rk_reschedule_nodes(run.ctx, run.jobs.ref_thr, run.table.c, run.grid, nodes, None, None, None, seg, lvl, assign, off,
+                               ent, 8, total, stats=stats)
+        rk.rk_sync(run.ctx)
+        assert not rk.u32(off).any() and float(total[0].item()) == 0.0 and stats.cpu().numpy().tolist() == [0, 0, 0, 0, 0]
+        assert not rk.assign_to_numpy(assign)["g"][:J].any()
+        rk.rk_best_plan_placed(run.ctx, run.jobs, run.table.c, run.grid, run.env, assign, off, ent, placed, total)
+        rk.rk_schedule_round_nodes(run.ctx, run.jobs, rk.make_bounds(wl.bounds), run.grid, run.env, nodes, seg, lvl, assign, placed,
+                                   off, ent, 8, total, stats=stats)
+        rk.rk_sync(run.ctx)
+        assert not rk.u32(off).any() and float(total[0].item()) == 0.0 and not rk.assign_to_numpy(placed)["g"][:J].any()
+        totals = run.f32(3)
+        many = rk.new_assign(3 * max(J, 1), dev)
+        rk.rk_reschedule_rounds(run.ctx, run.jobs.ref_thr, run.table.c, run.grid, [rk.make_cluster(base.cluster)] * 3, None, None,
+                                None, seg, lvl, many, totals)
+        rk.rk_sync(run.ctx)
+        assert not totals.cpu().numpy()[:3].any() and not rk.assign_to_numpy(many)["g"][:3 * J].any()
+        z = np.zeros(max(J, 1), np.uint32)
+        fs, fc = torch.zeros(max(J, 1), dtype=torch.int32, device=dev), torch.zeros(max(J, 1), dtype=torch.int32, device=dev)
+        so = torch.zeros(max(J, 1), dtype=torch.uint8, device=dev)
+        rk.rk_privileged(run.ctx, run.table.c, run.grid, rk.Sla(z + 1, z, [4], [4], device=dev), seg, lvl, seg, lvl, fs, fc, so)
+        rk.rk_sync(run.ctx)
+        if J:                                                # guaranteed jobs without a minimum demand wait
+            assert so.cpu().numpy()[:J].tolist() == [1] * J and (fs.cpu().numpy()[:J] == -1).all()
+        run.close()
