@@ -209,6 +209,9 @@ def test_privileged_jobs_for_the_loop(orc):
     # ... and keeps taking part even when the quota would not admit it today (its floor stays, nothing is left)
     fs, fc, st = privileged_case(orc, [1, 1], [0, 0], [4, 4], [0, 0], [3], [100], [8, 0])
     assert fs.tolist() == [2, -1] and st.tolist() == [0, 1]
+    # a running job's CPUs are charged too: its minimum at level 1 takes 2 of the tenant's 3 CPUs, the queued job needs 2
+    fs, fc, st = privileged_case(orc, [1, 1], [0, 0], [2, 2], [1, 1], [100], [3], [4, 0])
+    assert fs.tolist() == [1, -1] and st.tolist() == [0, 1]
     # tenants have separate quotas; the CPU quota binds as well (level 1 = 2 CPUs per job here)
     fs, fc, st = privileged_case(orc, [1, 1], [0, 1], [4, 4], [0, 0], [5, 5], [100, 100], [0, 0])
     assert st.tolist() == [0, 0]
