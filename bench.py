@@ -774,6 +774,22 @@ def main():
                 probe[k].append((x, y))
     torch.cuda.synchronize()
     probe_ms = {k: sum(x.elapsed_time(y) for x, y in v) / len(v) for k, v in probe.items()}
+    # the slope table of the curves (not part of the timed step: the allocation computes its steps itself)
+    n_sl = table.n_segments(n_rows)
+    sl_f = [torch.empty(n_sl + 4, dtype=torch.float32, device=dev) for _ in range(2)]
+    sl_i = [torch.empty(n_sl + 4, dtype=torch.int32, device=dev) for _ in range(2)]
+    sl_0 = (torch.empty(n_rows * J + 4, dtype=torch.float32, device=dev), torch.empty(n_rows * J + 4, dtype=torch.int32, device=dev))
+    slopes = []
+    for i in range(7):
+        x = mark()
+        rk.rk_curve_slopes(ctx, jobs.ref_thr, table.c, grid, 0, J, best_thr, curve_thr, sl_f[0][:n_sl], sl_i[0], sl_0[0], sl_0[1],
+                           sl_f[1], sl_i[1])
+        y = mark()
+        if i >= 2:
+            slopes.append((x, y))
+    torch.cuda.synchronize()
+    slopes_ms = sum(x.elapsed_time(y) for x, y in slopes) / len(slopes)
+    del sl_f, sl_i, sl_0
     if args.stream_calibration:
         # for profiles: the strided read, and k_eval with the feasibility output, which the timed steps do not ask for
         feas = torch.empty(max(chunk_cands) + 16, dtype=torch.uint8, device=dev)
@@ -888,6 +904,7 @@ def main():
         "kernels": {"timed_region_avg_launch_ms": hot_avg_ms,
                     "stage_pass": "separate pass after the timed region, events around every call",
                     "avg_launch_ms": avg_ms, "per_step_ms": per_step_ms,
+                    "curve_slopes_ms": slopes_ms,
                     "eval_best_candidates_per_s": n_cand / (hot_avg_ms["eval_best"] * n_chunks * 1e-3),
                     # kernels that only fill and only read the same buffer (4 bytes per candidate each way)
                     "plain_stream_ms": probe_ms,

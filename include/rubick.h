@@ -234,6 +234,29 @@ int32_t rk_curves(rk_ctx *ctx, const rk_plan_table *table, const rk_alloc_grid *
                   const float *best_thr, const uint32_t *best_plan,
                   float *curve_thr, uint32_t *curve_plan, uint32_t *curve_g, uint64_t cap_segs);
 
+/* The slope table of the curves (Sec. 5.2: a job's slope, per resource type, is
+ * the throughput change per unit of the resource; Fig. 6): the steps the
+ * allocation rules take, independent of the cluster.  For jobs [job_begin,
+ * job_end), arrays in segment layout ([job][CPU level][tier][GPU count]):
+ *   gpu_slope, gpu_next   from that GPU count to the larger count with the
+ *                         highest float32 slope ((v1 - v0) / ref_thr) / (g1 - g0)
+ *                         on the curve of the row, the smaller count among equal
+ *                         slopes; index of that count in the job's list, -1 and
+ *                         slope 0 when no larger count is better
+ *   cpu_slope, cpu_next   at that GPU count from the row's CPU level to the level
+ *                         with the highest ((best' - best) / ref_thr) / (CPUs' -
+ *                         CPUs), the lower level among equals; n_cpu and slope 0
+ *                         when no higher level is better
+ *   from0_slope, from0_next   per job and row ([job][CPU level][tier]): the first
+ *                         GPU step of a job that holds nothing
+ * best_thr, curve_thr as rk_best_plan / rk_curves (or rk_job_curves) write them
+ * for the same range.  cap_segs = capacity of the four segment-layout outputs. */
+int32_t rk_curve_slopes(rk_ctx *ctx, const float *ref_thr, const rk_plan_table *table,
+                        const rk_alloc_grid *grid, uint32_t job_begin, uint32_t job_end,
+                        const float *best_thr, const float *curve_thr, float *gpu_slope, int32_t *gpu_next,
+                        float *from0_slope, int32_t *from0_next, float *cpu_slope, uint32_t *cpu_next,
+                        uint64_t cap_segs);
+
 /* Evaluation + best plan + curves in one pass without materialising the
  * candidates; results are identical to rk_eval_candidates -> rk_best_plan ->
  * rk_curves.  best_thr / best_plan may be NULL. */

@@ -441,4 +441,22 @@ def privileged(table, grid, guaranteed, tenant, min_seg, min_c, quota_g, quota_c
     return floor_seg, floor_c, out
 
 
+def curve_slopes(ref_thr, table, grid, best_thr, curve_thr, jb=0, je=None):
+    """The slope table of the curves -> dict(gpu_slope, gpu_next, from0_slope, from0_next, cpu_slope, cpu_next)."""
+    je = table.n_jobs if je is None else je
+    gh = _GridHolder(grid)
+    f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    ref_thr, best_thr, curve_thr = f(ref_thr), f(best_thr), f(curve_thr)
+    rows = len(grid.cpu_levels) * len(grid.mem_levels_gb)
+    n = rows * int(table.seg_off[je] - table.seg_off[jb])
+    out = dict(gpu_slope=np.zeros(n, np.float32), gpu_next=np.zeros(n, np.int32),
+               from0_slope=np.zeros(rows * (je - jb), np.float32), from0_next=np.zeros(rows * (je - jb), np.int32),
+               cpu_slope=np.zeros(n, np.float32), cpu_next=np.zeros(n, np.uint32))
+    rc = lib().ork_curve_slopes(_p(ref_thr), C.byref(table.c), C.byref(gh.c), C.c_uint32(jb), C.c_uint32(je), _p(best_thr),
+                                _p(curve_thr), _p(out["gpu_slope"]), _p(out["gpu_next"]), _p(out["from0_slope"]),
+                                _p(out["from0_next"]), _p(out["cpu_slope"]), _p(out["cpu_next"]))
+    assert rc == 0
+    return out
+
+
 from . import simulator  # noqa: E402

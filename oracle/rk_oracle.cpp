@@ -1310,6 +1310,62 @@ int ork_privileged(uint32_t n_jobs, const ork_table *tb, const ork_grid *grid, c
     return 0;
 }
 
+/* Slopes of the resource sensitivity curves (Sec. 5.2: the slope of a job's curve, per resource type, is the
+ * throughput change per unit of the resource; Fig. 6).  A table of the steps the allocation rules take, for every
+ * row (CPU level, memory tier) and GPU count of a job, cluster-independent:
+ *   GPUs: from count s (or from nothing) to the larger count s' with the highest float32 slope
+ *         ((curve(s') - curve(s)) / ref_thr) / (g(s') - g(s)), the smaller count among equal slopes; none: 0, -1.
+ *   CPUs: at count s from level c to the level c' > c with the highest ((best(c') - best(c)) / ref_thr) / (CPUs(c') -
+ *         CPUs(c)), the lower level among equals; none: 0, n_cpu.
+ * Arrays in segment layout of jobs [jb, je) ([job][level][tier][count]); from0_* per job and row.
+ * Pinned: hand values, concave curves (the next count, slopes falling), and the steps of the Schedule loop for a lone
+ * job on a large empty cluster, which walk exactly this table. */
+int ork_curve_slopes(const float *ref_thr, const ork_table *tb, const ork_grid *grid, uint32_t jb, uint32_t je,
+                     const float *best_thr, const float *curve_thr, float *gpu_slope, int32_t *gpu_next,
+                     float *from0_slope, int32_t *from0_next, float *cpu_slope, uint32_t *cpu_next) {
+    const uint64_t rows = (uint64_t)grid->n_cpu * grid->n_mem;
+    for (uint32_t j = jb; j < je; ++j) {
+        const uint32_t s0 = tb->seg_off[j], ns = tb->seg_off[j + 1] - s0;
+        const uint64_t base = rows * (s0 - tb->seg_off[jb]);
+        for (uint32_t ci = 0; ci < grid->n_cpu; ++ci)
+            for (uint32_t mi = 0; mi < grid->n_mem; ++mi) {
+                const uint64_t row = base + ((uint64_t)ci * grid->n_mem + mi) * ns;
+                for (int64_t s = -1; s < (int64_t)ns; ++s) {
+                    const float cur = s < 0 ? 0.0f : curve_thr[row + s];
+                    const uint32_t g = s < 0 ? 0u : tb->seg_g[s0 + s];
+                    float top = 0.0f; int32_t nxt = -1;
+                    for (uint32_t t = (uint32_t)(s + 1); t < ns; ++t) {
+                        const float v = curve_thr[row + t];
+                        if (!(v > cur)) continue;
+                        float sl = (v - cur) / ref_thr[j];
+                        sl = sl / (float)(tb->seg_g[s0 + t] - g);
+                        if (sl > top) { top = sl; nxt = (int32_t)t; }
+                    }
+                    if (s < 0) {
+                        from0_slope[rows * (j - jb) + (uint64_t)ci * grid->n_mem + mi] = top;
+                        from0_next[rows * (j - jb) + (uint64_t)ci * grid->n_mem + mi] = nxt;
+                    } else {
+                        gpu_slope[row + s] = top; gpu_next[row + s] = nxt;
+                    }
+                }
+                for (uint32_t s = 0; s < ns; ++s) {
+                    const float cur = best_thr[row + s];
+                    const uint32_t g = tb->seg_g[s0 + s];
+                    float top = 0.0f; uint32_t nxt = grid->n_cpu;
+                    for (uint32_t c = ci + 1; c < grid->n_cpu; ++c) {
+                        const float v = best_thr[base + ((uint64_t)c * grid->n_mem + mi) * ns + s];
+                        if (!(v > cur)) continue;
+                        float sl = (v - cur) / ref_thr[j];
+                        sl = sl / (float)(cpus_of(grid, c, g) - cpus_of(grid, ci, g));
+                        if (sl > top) { top = sl; nxt = c; }
+                    }
+                    cpu_slope[row + s] = top; cpu_next[row + s] = nxt;
+                }
+            }
+    }
+    return 0;
+}
+
 }  // extern "C"
 
 namespace {

@@ -222,6 +222,13 @@ int ork_privileged(uint32_t n_jobs, const ork_table *table, const ork_grid *grid
                    const uint32_t *quota_g, const uint32_t *quota_c, const uint8_t *state_in, const int32_t *cur_seg,
                    const uint32_t *cur_c, int32_t *floor_seg, uint32_t *floor_c, uint8_t *state_out);
 
+/* The slope table of the curves: per row and GPU count the next GPU step (slope,
+ * target count or -1) and the next CPU step (slope, target level or n_cpu), and
+ * per row the first step from nothing.  Segment layout of jobs [jb, je). */
+int ork_curve_slopes(const float *ref_thr, const ork_table *table, const ork_grid *grid, uint32_t jb, uint32_t je,
+                     const float *best_thr, const float *curve_thr, float *gpu_slope, int32_t *gpu_next,
+                     float *from0_slope, int32_t *from0_next, float *cpu_slope, uint32_t *cpu_next);
+
 #ifdef __cplusplus
 }
 #endif

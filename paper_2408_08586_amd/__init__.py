@@ -26,7 +26,7 @@ FIT_FIELDS = ("k_bwd", "k_sync", "k_opt", "k_opt_off", "k_off", "k_swap", "k_con
 EXPORTS = ("rk_create", "rk_destroy", "rk_sync", "rk_last_error", "rk_enumerate_plans", "rk_eval_candidates",
            "rk_best_plan", "rk_curves", "rk_job_curves", "rk_allocate", "rk_schedule_round", "rk_schedule_rounds",
            "rk_eval_points", "rk_min_res", "rk_allocate_sla", "rk_schedule_round_sla", "rk_fit_models", "rk_simulate", "rk_schedule_rounds_shared", "rk_place", "rk_allocate_static", "rk_place_plans",
-           "rk_schedule_round_placed", "rk_reschedule", "rk_probe_stream", "rk_eval_best_plan", "rk_reschedule_nodes", "rk_best_plan_placed", "rk_reschedule_rounds", "rk_schedule_round_nodes", "rk_privileged")
+           "rk_schedule_round_placed", "rk_reschedule", "rk_probe_stream", "rk_eval_best_plan", "rk_reschedule_nodes", "rk_best_plan_placed", "rk_reschedule_rounds", "rk_schedule_round_nodes", "rk_privileged", "rk_curve_slopes")
 
 _JOB_F32 = ("P_bytes", "seq", "hidden", "elem_bytes", "t_fwd_sample", "k_bwd", "k_sync", "k_opt", "k_opt_off",
             "k_off", "k_swap", "k_const", "mem_state", "mem_act", "mem_act_gc", "mem_const", "ref_thr")
@@ -317,6 +317,15 @@ def rk_reschedule(ctx, ref_thr, table, grid, cluster: rk_cluster, best_thr, best
     _check(ctx, load_library().rk_reschedule(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.byref(cluster),
                                              _ptr(best_thr), _ptr(best_plan), _ptr(curve_thr), C.byref(js), _ptr(assign),
                                              _ptr(total), _ptr(n_moves)))
+
+
+def rk_curve_slopes(ctx, ref_thr, table, grid, job_begin, job_end, best_thr, curve_thr, gpu_slope, gpu_next, from0_slope,
+                    from0_next, cpu_slope, cpu_next):
+    """The slope table of the curves (device tensors; capacity = size of gpu_slope)."""
+    _check(ctx, load_library().rk_curve_slopes(ctx, _ptr(ref_thr), C.byref(table), C.byref(grid), C.c_uint32(job_begin),
+                                               C.c_uint32(job_end), _ptr(best_thr), _ptr(curve_thr), _ptr(gpu_slope),
+                                               _ptr(gpu_next), _ptr(from0_slope), _ptr(from0_next), _ptr(cpu_slope),
+                                               _ptr(cpu_next), C.c_uint64(gpu_slope.numel())))
 
 
 def rk_privileged(ctx, table, grid, sla: "Sla", min_seg, min_c, cur_seg, cur_c, floor_seg, floor_c, state_out, state=None):

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librubick.so")
-SOURCES = ["rk_ctx.hip", "rk_enumerate.hip", "rk_eval.hip", "rk_fused.hip", "rk_allocate.hip", "rk_sla.hip", "rk_fit.hip", "rk_sim.hip", "rk_place.hip", "rk_nodes.hip", "rk_round.hip", "rk_probe.hip"]
+SOURCES = ["rk_ctx.hip", "rk_enumerate.hip", "rk_eval.hip", "rk_fused.hip", "rk_allocate.hip", "rk_sla.hip", "rk_fit.hip", "rk_sim.hip", "rk_place.hip", "rk_nodes.hip", "rk_slopes.hip", "rk_round.hip", "rk_probe.hip"]
 
 # -ffp-contract=off and the correctly rounded divide keep the float32 memory
 # estimate bit-reproducible; packed FP32 instructions are disabled on purpose.
