@@ -130,35 +130,6 @@ __device__ __forceinline__ uint32_t round_index_of(const RoundArgs &R, uint32_t 
 }
 
 
-template <int CTRL>
-__device__ __forceinline__ unsigned long long dpp_u64(unsigned long long v) {
-    const uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
-    const uint32_t l2 = (uint32_t)__builtin_amdgcn_update_dpp((int)lo, (int)lo, CTRL, 0xF, 0xF, false);
-    const uint32_t h2 = (uint32_t)__builtin_amdgcn_update_dpp((int)hi, (int)hi, CTRL, 0xF, 0xF, false);
-    return ((unsigned long long)h2 << 32) | l2;
-}
-
-// Maximum over the wavefront, in every lane; all 64 lanes must be active.
-// Within each row of 16 lanes by data-parallel-primitive moves (neighbour,
-// neighbour pair, mirrored halves of 8, mirrored halves of 16), then the four
-// rows through scalar registers.
-__device__ __forceinline__ unsigned long long wave_max_u64_rows(unsigned long long v) {
-    unsigned long long o;
-    o = dpp_u64<0xB1>(v);  v = o > v ? o : v;                   // quad_perm [1,0,3,2]
-    o = dpp_u64<0x4E>(v);  v = o > v ? o : v;                   // quad_perm [2,3,0,1]
-    o = dpp_u64<0x141>(v); v = o > v ? o : v;                   // row_half_mirror
-    o = dpp_u64<0x140>(v); v = o > v ? o : v;                   // row_mirror
-    unsigned long long m = 0;
-#pragma unroll
-    for (int r = 0; r < 64; r += 16) {
-        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, r);
-        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), r);
-        const unsigned long long row = ((unsigned long long)hi << 32) | lo;
-        m = row > m ? row : m;
-    }
-    return m;
-}
-
 __device__ __forceinline__ double wave_sum_f64(double v) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -1495,14 +1466,28 @@ __global__ void k_rs_prepare(RsArgs B) {
 }
 
 __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
-    const RsView A = rs_round(B, blockIdx.x);
-    __shared__ RsStep sh_step;
+    // what every job loses per GPU / CPU it gives, [2][n_jobs]: read by all threads at every search for a job to
+    // shrink, so the round keeps them in LDS (k_rs_prepare left them in memory)
+    extern __shared__ float sh_ds[];
+    RsView A = rs_round(B, blockIdx.x);
+    for (uint32_t j = threadIdx.x; j < A.n_jobs; j += RS_THREADS) {
+        sh_ds[j] = A.ds_g[j];
+        sh_ds[A.n_jobs + j] = A.ds_c[j];
+    }
+    A.ds_g = sh_ds;
+    A.ds_c = sh_ds + A.n_jobs;
+    __shared__ RsStep sh_step, sh_next[2];
     __shared__ unsigned long long sh_free[2], sh_avail[2], sh_held[2][RS_THREADS / 64];
     __shared__ float sh_lost, sh_wmin[RS_THREADS / 64];
+    __shared__ unsigned long long sh_wlow[RS_THREADS / 64];
+    __shared__ uint32_t sh_below, sh_next_below;
     __shared__ uint32_t sh_widx[RS_THREADS / 64];
     __shared__ uint32_t sh_ok, sh_go, sh_touched, sh_epoch, sh_moves, sh_nb, sh_full, sh_shrinks, sh_undone;
     __shared__ RsMin sh_min[2], sh_wm[2][RS_THREADS / 64];
     __shared__ float sh_wc[RS_THREADS / 64];
+    constexpr uint32_t RS_LIST = 2048;                     // jobs with something to do, as the last look over all jobs found them
+    __shared__ uint32_t sh_listed, sh_list_j[RS_LIST];
+    __shared__ float sh_list_g[RS_LIST], sh_list_c[RS_LIST];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t J = A.n_jobs;
     const float INF = __int_as_float(0x7F800000);
@@ -1528,12 +1513,19 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
 
     // ScheduleJob(j); the same code path for all threads
     auto schedule_job = [&](uint32_t j) {
+        bool have_next = false;                            // sh_next holds the job's next steps (from the refresh after a commit)
         for (uint32_t res = 0; res < 2; ++res) {
             for (;;) {
                 if (wave == 0) {
-                    const RsStep st = res == 0 ? rs_up_gpu(A, j, lane, 64) : rs_up_cpu(A, j, lane, 64);
+                    const RsStep st = have_next ? sh_next[res] : (res == 0 ? rs_up_gpu(A, j, lane, 64) : rs_up_cpu(A, j, lane, 64));
+                    bool below = false;                     // below its floor: it takes at a loss
+                    if (res == 0) {
+                        if (have_next) below = sh_next_below != 0u;
+                        else { const int32_t fl = rs_fl_s(A, j); below = fl >= 0 && A.st.gi[j] < fl; }
+                    }
                     if (lane == 0) {
                         sh_step = st;
+                        sh_below = below ? 1u : 0u;
                         sh_avail[0] = sh_free[0]; sh_avail[1] = sh_free[1];
                         sh_lost = 0.f; sh_ok = 1u; sh_touched = 0u; sh_epoch += 1u;
                     }
@@ -1541,11 +1533,11 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
                 __syncthreads();
                 const RsStep st = sh_step;
                 if (!st.any) { __syncthreads(); break; }
-                const bool below_min = res == 0 && rs_fl_s(A, j) >= 0 && A.st.gi[j] < rs_fl_s(A, j);
+                const bool below_min = sh_below != 0u;
                 const unsigned long long need = res == 0 ? st.dg : st.dc;
                 while (sh_ok && sh_avail[res] < need) {
                     // the job with the lowest slope among those that can give (GetLowestSlopeOverMinJob); ties: lower index
-                    const float *ds = res == 0 ? A.ds_g : A.ds_c;
+                    const float *ds = sh_ds + res * J;
                     float best = INF;
                     uint32_t who = 0xFFFFFFFFu;
                     for (uint32_t v0 = tid; v0 < J; v0 += 4 * RS_THREADS) {      // four loads in flight
@@ -1553,43 +1545,48 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
 #pragma unroll
                         for (uint32_t k = 0; k < 4; ++k) x[k] = v0 + k * RS_THREADS < J ? ds[v0 + k * RS_THREADS] : INF;
 #pragma unroll
-                        for (uint32_t k = 0; k < 4; ++k) {
+                        for (uint32_t k = 0; k < 4; ++k) {                        // ascending: the lower job stays among equal slopes
                             const uint32_t v = v0 + k * RS_THREADS;
                             if (v != j && x[k] < best) { best = x[k]; who = v; }
                         }
                     }
-#pragma unroll
-                    for (int off = 32; off >= 1; off >>= 1) {
-                        const float ob = __shfl_xor(best, off, 64);
-                        const uint32_t ow = __shfl_xor(who, off, 64);
-                        if (ob < best || (ob == best && ow < who)) { best = ob; who = ow; }
-                    }
-                    if (lane == 0) { sh_wmin[wave] = best; sh_widx[wave] = who; }
-                    __syncthreads();
-                    if (tid == 0) {
-                        float b2 = INF;
-                        uint32_t w2 = 0xFFFFFFFFu;
-                        for (uint32_t w = 0; w < RS_THREADS / 64; ++w)
-                            if (sh_wmin[w] < b2 || (sh_wmin[w] == b2 && sh_widx[w] < w2)) { b2 = sh_wmin[w]; w2 = sh_widx[w]; }
-                        if (w2 == 0xFFFFFFFFu || !(b2 < INF) || !(below_min || st.slope > b2)) {
-                            sh_ok = 0u;
+                    // (slope, job) as one key, the slope as a word that orders like it
+                    unsigned long long low = who == 0xFFFFFFFFu ? ~0ull : ((unsigned long long)rs_ordered(best) << 32) | who;
+                    low = wave_min_u64_rows(low);
+                    if (lane == 0) sh_wlow[wave] = low;
+                    rs_lds_barrier();
+                    if (wave == 0) {                           // the first wavefront takes the decision and the step down
+                        const unsigned long long k2 = wave_min_u64_rows(lane < RS_THREADS / 64 ? sh_wlow[lane] : ~0ull);
+                        const uint32_t w2 = (uint32_t)k2;
+                        const float b2 = rs_unordered((uint32_t)(k2 >> 32));
+                        // what the step down reads first, asked for together
+                        const bool some = k2 != ~0ull;
+                        const uint32_t stamp2 = some ? A.stamp[w2] : 0u;
+                        const int32_t gi0 = some ? A.st.gi[w2] : -1;
+                        const uint32_t ci0 = some ? A.st.ci[w2] : 0u;
+                        const uint32_t so2 = some ? A.X.tb.seg_off[w2] : 0u, ns2 = some ? A.X.tb.seg_off[w2 + 1] - so2 : 0u;
+                        if (!some || !(below_min || st.slope > b2)) {
+                            if (lane == 0) sh_ok = 0u;
                         } else {
-                            const RsGive gv = res == 0 ? rs_down_gpu(A, w2) : rs_down_cpu(A, w2);
-                            if (A.stamp[w2] != sh_epoch) {          // first time this job gives in this step: remember its state
-                                A.stamp[w2] = sh_epoch;
-                                A.keep_gi[w2] = A.st.gi[w2]; A.keep_ci[w2] = A.st.ci[w2];
-                                A.keep_ds[2 * w2] = A.ds_g[w2]; A.keep_ds[2 * w2 + 1] = A.ds_c[w2];
-                                A.touched[sh_touched++] = w2;
+                            const RsShrunk sk = rs_shrink_wave(A, w2, so2, ns2, res, gi0, ci0, lane);
+                            if (lane == 0) {
+                                if (stamp2 != sh_epoch) {           // first time this job gives in this step: remember its state
+                                    A.stamp[w2] = sh_epoch;
+                                    A.keep_gi[w2] = gi0; A.keep_ci[w2] = ci0;
+                                    A.keep_ds[2 * w2] = A.ds_g[w2]; A.keep_ds[2 * w2 + 1] = A.ds_c[w2];
+                                    A.touched[sh_touched++] = w2;
+                                }
+                                sh_avail[0] += sk.gv.dg; sh_avail[1] += sk.gv.dc;
+                                sh_lost = sh_lost + sk.gv.loss;
+                                A.st.gi[w2] = sk.gi; A.st.ci[w2] = sk.ci;
+                                A.ds_g[w2] = sk.ds_g; A.ds_c[w2] = sk.ds_c;   // (its own next steps are brought up to date on commit)
+                                sh_shrinks += 1u;
                             }
-                            sh_avail[0] += gv.dg; sh_avail[1] += gv.dc;
-                            sh_lost = sh_lost + gv.loss;
-                            if (res == 0) { A.st.gi[w2] = gv.tgt; if (gv.tgt < 0) A.st.ci[w2] = 0u; }
-                            else A.st.ci[w2] -= 1u;
-                            rs_refresh_give(A, w2);             // (its own next steps are brought up to date on commit)
-                            sh_shrinks += 1u;
                         }
                     }
-                    __syncthreads();
+                    // (what the first wavefront wrote to memory, the state of the job that gave, is read again by itself only,
+                    // until the barrier that follows the loop)
+                    rs_lds_barrier();
                 }
                 if (tid == 0) {
                     bool ok = sh_ok != 0u;
@@ -1613,8 +1610,10 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
                 __syncthreads();
                 const uint32_t go = sh_go;
                 if (go) {                                       // the jobs whose state changed: all their cached values
-                    const uint32_t n_changed = sh_touched + 1u;      // a wavefront per job
-                    for (uint32_t i = wave; i < n_changed; i += RS_THREADS / 64) rs_refresh_lanes(A, i < sh_touched ? A.touched[i] : j, lane, 64);
+                    const uint32_t n_touched = sh_touched;           // a wavefront per job
+                    for (uint32_t i = wave; i < n_touched + 1u; i += RS_THREADS / 64)
+                        rs_refresh_wave(A, i < n_touched ? A.touched[i] : j, lane, sh_next, &sh_next_below, i >= n_touched);
+                    have_next = true;
                 }
                 __syncthreads();
                 if (!go) break;
@@ -1670,7 +1669,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
         __syncthreads();
         if (fresh) {                                      // otherwise the lowest slopes are what they were
             for (uint32_t res = 0; res < 2; ++res) {
-                const float *ds = res == 0 ? A.ds_g : A.ds_c;
+                const float *ds = sh_ds + res * J;
                 RsMin m = {INF, INF, 0xFFFFFFFFu};
                 for (uint32_t v0 = tid; v0 < J; v0 += 4 * RS_THREADS) {      // four loads in flight
                     float x[4];
@@ -1696,34 +1695,51 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
                 for (uint32_t w = 1; w < RS_THREADS / 64; ++w) m = rs_min_merge(m, sh_wm[tid][w]);
                 sh_min[tid] = m;
             }
+            if (tid == 2) sh_listed = 0u;
         }
         __syncthreads();
         const unsigned long long free_g = sh_free[0], free_c = sh_free[1];
         const RsMin mg = sh_min[0], mc = sh_min[1];
         float best_g = -1.f, best_c = -1.f;                // -1: none found
         uint32_t best_j = 0xFFFFFFFFu;
-        for (uint32_t j0 = tid; j0 < J; j0 += 4 * RS_THREADS) {      // four jobs' values in flight
-            float kg[4], kc[4], ug[4], uc[4];
-            uint32_t dg[4];
-            unsigned long long dcg[4], dcc[4];
+        // A look after a committed step goes over all jobs and lists those that have something to do; until the next
+        // committed step the later looks go over that list only (if it held them all): nothing they depend on changes.
+        if (fresh || sh_listed > RS_LIST) {
+            for (uint32_t j0 = tid; j0 < J; j0 += 4 * RS_THREADS) {      // four jobs' values in flight
+                float kg[4], kc[4], ug[4], uc[4];
+                uint32_t dg[4];
+                unsigned long long dcg[4], dcc[4];
 #pragma unroll
-            for (uint32_t k = 0; k < 4; ++k) {
-                const uint32_t j = j0 + k * RS_THREADS;
-                const bool in = j < J;
-                kg[k] = in ? A.sg[j] : -1.f; kc[k] = in ? A.sc[j] : -1.f;
-                ug[k] = in ? A.ug[j] : 0.f; uc[k] = in ? A.uc[j] : 0.f;
-                dg[k] = in ? A.udg[j] : 0u; dcg[k] = in ? A.udc_g[j] : 0ull; dcc[k] = in ? A.udc_c[j] : 0ull;
+                for (uint32_t k = 0; k < 4; ++k) {
+                    const uint32_t j = j0 + k * RS_THREADS;
+                    const bool in = j < J;
+                    kg[k] = in ? A.sg[j] : -1.f; kc[k] = in ? A.sc[j] : -1.f;
+                    ug[k] = in ? A.ug[j] : 0.f; uc[k] = in ? A.uc[j] : 0.f;
+                    dg[k] = in ? A.udg[j] : 0u; dcg[k] = in ? A.udc_g[j] : 0ull; dcc[k] = in ? A.udc_c[j] : 0ull;
+                }
+#pragma unroll
+                for (uint32_t k = 0; k < 4; ++k) {
+                    const uint32_t j = j0 + k * RS_THREADS;
+                    if (kg[k] < 0.f || !comes_before(last_g, last_c, last_j, kg[k], kc[k], j)) continue;   // not in the list, or served
+                    const float lowest_g = j == mg.i1 ? mg.m2 : mg.m1, lowest_c = j == mc.i1 ? mc.m2 : mc.m1;
+                    // GPU step: none; or GPUs are short and nobody may be shrunk for it; or the GPUs are there and its CPUs are not
+                    const bool gpu_idle = !(ug[k] > 0.f) || (free_g < dg[k] ? !(ug[k] > lowest_g) : free_c < dcg[k]);
+                    const bool cpu_idle = !(uc[k] > 0.f) || (free_c < dcc[k] && !(uc[k] > lowest_c));
+                    if (gpu_idle && cpu_idle) continue;
+                    if (fresh) {
+                        const uint32_t at = atomicAdd(&sh_listed, 1u);
+                        if (at < RS_LIST) { sh_list_j[at] = j; sh_list_g[at] = kg[k]; sh_list_c[at] = kc[k]; }
+                    }
+                    if (best_j == 0xFFFFFFFFu || comes_before(kg[k], kc[k], j, best_g, best_c, best_j)) { best_g = kg[k]; best_c = kc[k]; best_j = j; }
+                }
             }
-#pragma unroll
-            for (uint32_t k = 0; k < 4; ++k) {
-                const uint32_t j = j0 + k * RS_THREADS;
-                if (kg[k] < 0.f || !comes_before(last_g, last_c, last_j, kg[k], kc[k], j)) continue;   // not in the list, or served
-                const float lowest_g = j == mg.i1 ? mg.m2 : mg.m1, lowest_c = j == mc.i1 ? mc.m2 : mc.m1;
-                // GPU step: none; or GPUs are short and nobody may be shrunk for it; or the GPUs are there and its CPUs are not
-                const bool gpu_idle = !(ug[k] > 0.f) || (free_g < dg[k] ? !(ug[k] > lowest_g) : free_c < dcg[k]);
-                const bool cpu_idle = !(uc[k] > 0.f) || (free_c < dcc[k] && !(uc[k] > lowest_c));
-                if (gpu_idle && cpu_idle) continue;
-                if (best_j == 0xFFFFFFFFu || comes_before(kg[k], kc[k], j, best_g, best_c, best_j)) { best_g = kg[k]; best_c = kc[k]; best_j = j; }
+        } else {
+            const uint32_t listed = sh_listed;
+            for (uint32_t i = tid; i < listed; i += RS_THREADS) {
+                const uint32_t j = sh_list_j[i];
+                const float kg = sh_list_g[i], kc = sh_list_c[i];
+                if (!comes_before(last_g, last_c, last_j, kg, kc, j)) continue;                            // served
+                if (best_j == 0xFFFFFFFFu || comes_before(kg, kc, j, best_g, best_c, best_j)) { best_g = kg; best_c = kc; best_j = j; }
             }
         }
 #pragma unroll
@@ -2022,7 +2038,13 @@ static int32_t launch_reschedule_rounds(rk_ctx *ctx, const float *ref_thr, const
         k_rs_prepare<<<dim3((J + 255) / 256, n_rounds), 256, 0, s>>>(K);
         RK_CHECK_LAUNCH(ctx, "k_rs_prepare");
     }
-    k_reschedule<<<n_rounds, RS_THREADS, 0, s>>>(K);
+    const size_t lds = (size_t)2 * (J ? J : 1u) * sizeof(float);                // at most 96 KiB
+    if (lds > 64 * 1024 && !ctx->loop_lds_raised) {
+        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_reschedule),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 2 * RK_MAX_JOBS_PER_ROUND * sizeof(float)));
+        ctx->loop_lds_raised = true;
+    }
+    k_reschedule<<<n_rounds, RS_THREADS, lds, s>>>(K);
     RK_CHECK_LAUNCH(ctx, "k_reschedule");
     if (J > 0) {
         k_mem_wish<<<dim3(st.blocks_per_round, n_rounds), JOB_THREADS, 0, s>>>(X, st, assign);
