@@ -161,6 +161,77 @@ def test_larger_drawn_rounds(gpu, orc):
     assert n_moves > 3000
 
 
+def many_amounts_round(rng, orc, J):
+    """A round whose jobs have 174 GPU counts each (the divisors of a global batch of 720,720 up to 4,096 GPUs, data
+    parallel only): drawn values on some of them, a random present state with floors and jobs that take no part."""
+    bounds = workloads.Bounds(g_max=4096, tp_max=1)
+    ints = np.tile(np.array([[1, 720720, 1]], np.uint32), (J, 1))
+    tb = orc.enumerate_plans(ints, bounds)
+    ns = int(tb.seg_off[1])
+    assert ns == 174 and np.all(np.diff(tb.seg_off) == ns)
+    seg_g = np.asarray(tb.seg_g[:ns], dtype=np.int64)
+    n_cpu, n_mem = int(rng.integers(1, 5)), int(rng.integers(1, 4))
+    grid = workloads.Grid(np.sort(rng.choice(np.arange(1, 9), n_cpu, replace=False)).astype(np.uint32), int(rng.integers(0, 2)),
+                          np.sort(rng.choice(np.array([0, 4, 16, 64], np.float32), n_mem, replace=False)).astype(np.float32),
+                          int(rng.integers(0, 2)))
+    bt = np.zeros((J, n_cpu, n_mem, ns), np.float32)
+    for j in range(J):
+        valid = np.unique(np.concatenate([[0], rng.choice(np.arange(ns), int(rng.integers(3, 60)))]))
+        base = np.zeros(ns)
+        base[valid] = np.cumsum(np.sort(rng.uniform(0.2, 2.0, len(valid)))[::-1] * rng.uniform(0.5, 1.5, len(valid)))
+        base = np.round(base * 16) / 16
+        for c in range(n_cpu):
+            for m in range(n_mem):
+                v = base * (1 + 0.25 * c * rng.uniform(0, 1)) * (1.0 if m == n_mem - 1 else rng.choice([0.0, 0.8, 1.0]))
+                bt[j, c, m] = np.round(v * 16) / 16
+        bt[j] = np.maximum.accumulate(np.maximum.accumulate(bt[j], axis=0), axis=1)
+    flat = bt.reshape(-1)
+    bp = rng.integers(0, 1000, flat.size).astype(np.uint32)
+    bp[flat == 0] = orc.NO_PLAN
+    ct, _, _ = orc.curves(tb, grid, flat, bp)
+    ref = rng.uniform(0.5, 2.0, J).astype(np.float32)
+    G = int(rng.integers(64, 4097))
+    cl = workloads.Cluster(G, int(rng.integers(G, 12 * G)), float(rng.choice([0.0, 16.0, 200.0, 1e6])))
+    cur_seg, cur_c = np.full(J, -1, np.int32), np.zeros(J, np.uint32)
+    floor_seg, floor_c = np.full(J, -1, np.int32), np.zeros(J, np.uint32)
+    left = G
+    for j in rng.permutation(J).tolist():
+        ok = np.flatnonzero(bt[j, 0, n_mem - 1] > 0)
+        if rng.uniform() < 0.3:
+            floor_seg[j], floor_c[j] = int(rng.choice(ok[:max(1, len(ok) // 3)])), int(rng.integers(0, n_cpu))
+        if rng.uniform() < 0.6:
+            fit = ok[(seg_g[ok] <= left // 2) & (ok >= floor_seg[j])]
+            if fit.size:
+                cur_seg[j], cur_c[j] = int(rng.choice(fit)), int(rng.integers(0, n_cpu))
+                left -= int(seg_g[cur_seg[j]])
+    state = (rng.uniform(size=J) < 0.1).astype(np.uint8)
+    state[rng.uniform(size=J) < 0.1] = 2
+    coef = np.tile(workloads.tiny().coef[:1], (J, 1))
+    coef[:, 16] = ref
+    wl = workloads.Workload("many amounts", coef, ints, bounds, grid, workloads.Env(), cl)
+    return wl, tb, flat, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state
+
+
+def test_jobs_with_more_amounts_than_a_wavefront_has_lanes(gpu, orc):
+    """174 GPU counts per job: the steps of such a job are searched 64 amounts at a time, not from one register row."""
+    n_moves = n_shrunk = 0
+    for seed in range(40):
+        rng = np.random.default_rng(98000 + seed)
+        wl, tb, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state = many_amounts_round(rng, orc, int(rng.integers(3, 30)))
+        want = orc.reschedule(wl.coef[:, 16], tb, wl.grid, wl.cluster, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state=state)
+        run = gpu(wl)
+        run.enumerate()
+        assert np.array_equal(run.table_numpy()["seg_g"], tb.seg_g)
+        got = on_gpu(run, bt, bp, ct, wl.cluster, cur_seg, cur_c, floor_seg, floor_c, state)
+        run.close()
+        same(got, want)
+        n_moves += want[2]
+        held = np.where(cur_seg >= 0, np.asarray(tb.seg_g[:174])[np.maximum(cur_seg, 0)], 0)
+        n_shrunk += int(np.sum((want[0]["g"] < held) & (state == 0)))
+    print(f"40 rounds, {n_moves} steps committed, {n_shrunk} jobs hold less afterwards")
+    assert n_moves > 150 and n_shrunk > 20
+
+
 @pytest.mark.parametrize("name", ["paper_scale", "what_if", "stress"])
 def test_generated_rounds_from_a_running_state(gpu, orc, name):
     """The state a from-scratch round leaves, then the cluster loses a tenth of its GPUs and CPUs, a tenth of the

@@ -137,6 +137,42 @@ def test_larger_drawn_rounds(gpu, orc):
     assert n_moves > 1000
 
 
+def test_jobs_with_more_amounts_than_a_wavefront_has_lanes(gpu, orc):
+    """174 GPU counts per job (see the same test of the loop over totals), on nodes of 8 GPUs."""
+    from test_gpu_reschedule import many_amounts_round
+    n_moves = n_spread = 0
+    for seed in range(25):
+        rng = np.random.default_rng(83000 + seed)
+        wl, tb, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state = many_amounts_round(rng, orc, int(rng.integers(3, 30)))
+        grid = workloads.Grid(wl.grid.cpu_levels, 1, wl.grid.mem_levels_gb, wl.grid.mem_mode)
+        ct, _, _ = orc.curves(tb, grid, bt, bp)
+        wl = workloads.Workload("many amounts", wl.coef, wl.ints, wl.bounds, grid, wl.env, wl.cluster)
+        seg_g = np.asarray(tb.seg_g[:174], dtype=np.int64)
+        gpn, top = 8, int(grid.cpu_levels[-1])
+        n_nodes = -(-wl.cluster.G // gpn)
+        cpn = gpn * top if seed % 2 else int(rng.integers(gpn, gpn * top + 1))
+        mem = float(rng.choice([8.0, 64.0, 1e6]))
+        free_g, free_c = [gpn] * n_nodes, [cpn] * n_nodes
+        off, ent = [0], []
+        cur_seg[(state != 0) & (state != 2)] = -1
+        for j in range(wl.n_jobs):
+            if cur_seg[j] >= 0:
+                parts = first_fit(free_g, free_c, int(seg_g[cur_seg[j]]), int(grid.cpu_levels[cur_c[j]]))
+                if parts is None:
+                    cur_seg[j] = -1
+                else:
+                    ent += [(n, k, int(grid.cpu_levels[cur_c[j]]) * k, 0.0) for n, k in sorted(parts.items())]
+            off.append(len(ent))
+        prev = (np.array(off, np.uint32), np.array(ent, orc.PLACE_DTYPE) if ent else np.zeros(0, orc.PLACE_DTYPE))
+        print("seed", 83000 + seed, "jobs", wl.n_jobs, "nodes", n_nodes, flush=True)
+        want = run_both(gpu, orc, (wl, tb, bt, bp, ct, (n_nodes, gpn, cpn, mem), cur_seg, cur_c, prev, floor_seg, floor_c, state))
+        assert want is not None
+        n_moves += want[4]
+        n_spread += int(np.any(np.diff(want[1].astype(np.int64)) > 1))
+    print(f"25 rounds, {n_moves} steps committed, {n_spread} rounds with a job on several nodes")
+    assert n_moves > 100 and n_spread > 15
+
+
 def test_shapes_at_the_limits(gpu, orc):
     """The most nodes the library takes (four per thread of the kernel), nodes of more GPUs than a wavefront has lanes,
     the most jobs a round may have, and the smallest cluster there is."""
