@@ -1380,10 +1380,12 @@ __global__ __launch_bounds__(FLOOR_THREADS) void k_floors(Ctx X, JobState st, Sl
 // the taker is below its floor, and the step is committed when all was found and (unless the taker is below its
 // floor) the taker gains more than the others lose; otherwise everything is put back.
 //
-// One workgroup: the rule is sequential.  What is parallel is the search for a job's next step (a wavefront over
-// its amounts), the search for the job to shrink (all threads over cached slopes) and the order of the jobs (a
-// rank sort).  Control flow is the same for all threads; the first thread takes the decisions, LDS and barriers
-// carry them.
+// One workgroup: the rule is sequential.  What is parallel is the search for a job's next step and the step down of
+// the job that gives (a wavefront over its amounts, the job's rows in its registers), the search for the job to
+// shrink (all threads over the cached give-slopes, which the round keeps in LDS) and the look for the next job that
+// has something to do (all threads; no sort).  Control flow is the same for all threads; the first wavefront takes
+// the decisions, LDS and barriers carry them.  A phase between two barriers costs its longest chain of dependent
+// loads plus its instructions on one wavefront, so the phases ask for what they read in as few rounds as they can.
 constexpr int RS_THREADS = 1024;
 
 struct RsRound {                 // what a round of the loop works on
