@@ -161,6 +161,20 @@ def test_larger_drawn_rounds(gpu, orc):
     assert n_moves > 3000
 
 
+def test_the_largest_round(gpu, orc):
+    """12,288 jobs, the most a round takes: every thread of the kernel owns twelve, the give-slopes fill 96 KiB of LDS."""
+    rng = np.random.default_rng(96500)
+    wl, tb, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state = random_round(rng, orc, 12288, 3)
+    want = orc.reschedule(wl.coef[:, 16], tb, wl.grid, wl.cluster, bt, bp, ct, cur_seg, cur_c, floor_seg, floor_c, state=state)
+    run = gpu(wl)
+    run.enumerate()
+    got = on_gpu(run, bt, bp, ct, wl.cluster, cur_seg, cur_c, floor_seg, floor_c, state)
+    run.close()
+    same(got, want)
+    print(f"12,288 jobs, {want[2]} steps committed")
+    assert want[2] > 500
+
+
 def many_amounts_round(rng, orc, J):
     """A round whose jobs have 174 GPU counts each (the divisors of a global batch of 720,720 up to 4,096 GPUs, data
     parallel only): drawn values on some of them, a random present state with floors and jobs that take no part."""
