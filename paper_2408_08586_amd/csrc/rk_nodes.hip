@@ -127,6 +127,25 @@ __device__ __forceinline__ float nd_lowest_on(const NdArgs &A, uint32_t n, uint3
     return best;
 }
 
+// The same for a whole wavefront, a resident per lane (64 at a time): the residents' slopes are asked for together.
+__device__ __forceinline__ float nd_lowest_on_wave(const NdArgs &A, uint32_t n, uint32_t j, const float *ds, uint32_t &who,
+                                                   uint32_t lane) {
+    const float INF = __int_as_float(0x7F800000);
+    const uint32_t c = A.cnt[n];
+    const uint32_t *rj = A.res_job + (size_t)n * A.gpn;
+    unsigned long long low = ~0ull;                          // (slope as a word that orders like it, job)
+    for (uint32_t b = 0; b < c; b += 64u) {
+        const uint32_t i = b + lane;
+        const uint32_t v = i < c ? rj[i] : j;
+        const float s = v != j ? ds[v] : INF;
+        const unsigned long long key = ((unsigned long long)rs_ordered(s) << 32) | v;
+        if (s < INF && key < low) low = key;
+    }
+    low = wave_min_u64_rows(low);
+    who = low == ~0ull ? ND_NONE : (uint32_t)low;
+    return low == ~0ull ? INF : rs_unordered((uint32_t)(low >> 32));
+}
+
 // All cached values of job v from its present state: what it gives (rs_refresh_give) and its next steps in full, so
 // that ScheduleJob need not search them again.  `lanes` threads share the search (1, or the 64 of a wavefront).
 __device__ __forceinline__ void nd_refresh(const NdArgs &A, uint32_t v, uint32_t lane, uint32_t lanes) {
@@ -136,6 +155,26 @@ __device__ __forceinline__ void nd_refresh(const NdArgs &A, uint32_t v, uint32_t
     A.ds_g[v] = a.any ? a.slope : __int_as_float(0x7F800000);
     A.ds_c[v] = b.any ? b.slope : __int_as_float(0x7F800000);
     A.ug[v] = ug.any ? ug.slope : 0.f; A.udg[v] = (uint32_t)ug.dg; A.udc_g[v] = ug.dc;   // (a step that exists has its slope here)
+    A.uc[v] = uc.any ? uc.slope : 0.f; A.udc_c[v] = uc.dc;
+    A.gain_g[v] = ug.gain; A.gain_c[v] = uc.gain; A.tgt_g[v] = ug.tgt; A.lvl_g[v] = ug.lvl; A.lvl_c[v] = uc.lvl;
+    A.any[v] = (ug.any ? 1u : 0u) | (uc.any ? 2u : 0u);
+}
+// nd_refresh for a whole wavefront: a job of at most 64 amounts that is not below its floor has its rows loaded at
+// once, an amount per lane, and every step comes from the registers (rs_rows)
+__device__ __forceinline__ void nd_refresh_wave(const NdArgs &A, uint32_t v, uint32_t lane) {
+    const int32_t gi = A.st.gi[v];
+    const uint32_t ci = A.st.ci[v];
+    const int32_t fl = rs_fl_s(A, v);
+    const uint32_t so = A.X.tb.seg_off[v], ns = A.X.tb.seg_off[v + 1] - so;
+    if (ns > 64u || (fl >= 0 && gi < fl)) { nd_refresh(A, v, lane, 64); return; }
+    const RsRows R = rs_rows(A, v, so, ns, gi, ci, lane);
+    const RsGive a = rs_down_gpu_rows(A, R, R.curve, gi, ci, lane);
+    const RsGive b = rs_down_cpu_rows(A, R, gi, ci, rs_lane_f(R.best, gi), rs_lane_f(R.best_lo, gi));
+    const RsStep ug = rs_up_gpu_rows(A, R, gi, ci, lane), uc = rs_up_cpu_rows(A, R, gi, ci, lane);
+    if (lane != 0) return;
+    A.ds_g[v] = a.any ? a.slope : __int_as_float(0x7F800000);
+    A.ds_c[v] = b.any ? b.slope : __int_as_float(0x7F800000);
+    A.ug[v] = ug.any ? ug.slope : 0.f; A.udg[v] = (uint32_t)ug.dg; A.udc_g[v] = ug.dc;
     A.uc[v] = uc.any ? uc.slope : 0.f; A.udc_c[v] = uc.dc;
     A.gain_g[v] = ug.gain; A.gain_c[v] = uc.gain; A.tgt_g[v] = ug.tgt; A.lvl_g[v] = ug.lvl; A.lvl_c[v] = uc.lvl;
     A.any[v] = (ug.any ? 1u : 0u) | (uc.any ? 2u : 0u);
@@ -334,23 +373,73 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
                 const uint32_t f = sh_vnode;
                 if (f != ND_NONE) {                          // node f: the job still lacks GPUs and somebody may be shrunk
                     for (;;) {
-                        if (tid == 0) {
-                            uint32_t who;
-                            const float low = nd_lowest_on(A, f, j, A.ds_g, who);
-                            if (who == ND_NONE || !(below_min || st.slope > low)) {
-                                sh_v = ND_NONE;
+                        if (wave == 0) {                     // the first wavefront: a resident of node f per lane
+                            const uint32_t c = A.cnt[f];
+                            const size_t base = (size_t)f * A.gpn;
+                            if (c > 64u) {                       // more residents than lanes: the first lane asks them one by one
+                                if (lane == 0) {
+                                    uint32_t who;
+                                    const float low = nd_lowest_on(A, f, j, A.ds_g, who);
+                                    if (who == ND_NONE || !(below_min || st.slope > low)) {
+                                        sh_v = ND_NONE;
+                                    } else {
+                                        const RsGive gv = rs_down_gpu(A, who);
+                                        remember(who);
+                                        const uint32_t per_v = nd_cpl(A, A.st.ci[who]);
+                                        const uint32_t here_has = nd_part(A, f, who);
+                                        const uint32_t here = (uint32_t)gv.dg < here_has ? (uint32_t)gv.dg : here_has;
+                                        nd_drop(A, f, who, here, per_v);
+                                        sh_rest = (uint32_t)gv.dg - here; sh_per_v = per_v; sh_v = who;
+                                        sh_lost = sh_lost + gv.loss;
+                                        A.st.gi[who] = gv.tgt; if (gv.tgt < 0) A.st.ci[who] = 0u;
+                                        rs_refresh_give(A, who);
+                                        sh_shrinks += 1u;
+                                    }
+                                }
                             } else {
-                                const RsGive gv = rs_down_gpu(A, who);
-                                remember(who);
-                                const uint32_t per_v = nd_cpl(A, A.st.ci[who]);
-                                const uint32_t here_has = nd_part(A, f, who);
-                                const uint32_t here = (uint32_t)gv.dg < here_has ? (uint32_t)gv.dg : here_has;
-                                nd_drop(A, f, who, here, per_v);
-                                sh_rest = (uint32_t)gv.dg - here; sh_per_v = per_v; sh_v = who;
-                                sh_lost = sh_lost + gv.loss;
-                                A.st.gi[who] = gv.tgt; if (gv.tgt < 0) A.st.ci[who] = 0u;
-                                rs_refresh_give(A, who);
-                                sh_shrinks += 1u;
+                                // the node's list and what it has free, asked for together; then the residents' slopes
+                                const uint32_t free_g = A.free_g[f], free_c = A.free_c[f];
+                                const uint32_t rv = lane < c ? A.res_job[base + lane] : j;
+                                const uint32_t rk = lane < c ? A.res_k[base + lane] : 0u;
+                                const float sl = rv != j ? A.ds_g[rv] : INF;
+                                unsigned long long key = ~0ull;      // (slope as a word that orders like it, job): lower job among equals
+                                if (sl < INF) key = ((unsigned long long)rs_ordered(sl) << 32) | rv;
+                                key = wave_min_u64_rows(key);
+                                const uint32_t who = (uint32_t)key;
+                                const float low = rs_unordered((uint32_t)(key >> 32));
+                                if (key == ~0ull || !(below_min || st.slope > low)) {
+                                    if (lane == 0) sh_v = ND_NONE;
+                                } else {
+                                    // the job's state and what remembering it reads, together
+                                    const int32_t gi0 = A.st.gi[who];
+                                    const uint32_t ci0 = A.st.ci[who];
+                                    const uint32_t so = A.X.tb.seg_off[who], ns = A.X.tb.seg_off[who + 1] - so;
+                                    const uint32_t stamp = A.stamp[who];
+                                    const float ds_c0 = A.ds_c[who];
+                                    const uint32_t slot = (uint32_t)__ffsll((long long)__ballot(lane < c && rv == who)) - 1u;
+                                    const uint32_t here_has = wave_lane_u32(rk, slot);
+                                    const float ds_g0 = __uint_as_float(wave_lane_u32(__float_as_uint(sl), slot));
+                                    const uint32_t last_v = wave_lane_u32(rv, c - 1u), last_k = wave_lane_u32(rk, c - 1u);
+                                    const RsShrunk sk = rs_shrink_wave(A, who, so, ns, 0, gi0, ci0, lane);
+                                    if (lane == 0) {
+                                        if (stamp != sh_epoch) {     // (remember)
+                                            A.stamp[who] = sh_epoch;
+                                            A.keep_gi[who] = gi0; A.keep_ci[who] = ci0;
+                                            A.keep_ds[2 * who] = ds_g0; A.keep_ds[2 * who + 1] = ds_c0;
+                                            A.touched[sh_touched++] = who;
+                                        }
+                                        const uint32_t per_v = nd_cpl(A, ci0);
+                                        const uint32_t here = (uint32_t)sk.gv.dg < here_has ? (uint32_t)sk.gv.dg : here_has;
+                                        A.free_g[f] = free_g + here; A.free_c[f] = free_c + here * per_v;      // (nd_drop)
+                                        if (here_has - here) A.res_k[base + slot] = here_has - here;
+                                        else { A.res_job[base + slot] = last_v; A.res_k[base + slot] = last_k; A.cnt[f] = c - 1u; }
+                                        sh_rest = (uint32_t)sk.gv.dg - here; sh_per_v = per_v; sh_v = who;
+                                        sh_lost = sh_lost + sk.gv.loss;
+                                        A.st.gi[who] = sk.gi; A.st.ci[who] = sk.ci;
+                                        A.ds_g[who] = sk.ds_g; A.ds_c[who] = sk.ds_c;
+                                        sh_shrinks += 1u;
+                                    }
+                                }
                             }
                         }
                         __syncthreads();
@@ -402,7 +491,7 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
             const uint32_t go = sh_go;
             if (go) {
                 const uint32_t n_changed = sh_touched + 1u;      // a wavefront per job whose state changed
-                for (uint32_t i = wave; i < n_changed; i += ND_WAVES) nd_refresh(A, i < sh_touched ? A.touched[i] : j, lane, 64);
+                for (uint32_t i = wave; i < n_changed; i += ND_WAVES) nd_refresh_wave(A, i < sh_touched ? A.touched[i] : j, lane);
             } else {
                 restore_nodes();
             }
@@ -437,21 +526,27 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
             for (uint32_t p = 0; p < np && found; ++p) {
                 const uint32_t n = A.plist[2 * p], need = more * A.plist[2 * p + 1];
                 for (;;) {
-                    if (tid == 0) {
-                        if (A.free_c[n] >= need) { A.free_c[n] -= need; sh_flag = 0u; }
+                    if (wave == 0) {                         // the first wavefront: its lanes share the job's step down
+                        const uint32_t free_here = A.free_c[n];
+                        if (free_here >= need) { if (lane == 0) { A.free_c[n] = free_here - need; sh_flag = 0u; } }
                         else {
                             uint32_t who;
-                            const float low = nd_lowest_on(A, n, j, A.ds_c, who);
-                            if (who == ND_NONE || !(st.slope > low)) { sh_ok = 0u; sh_flag = 0u; }
+                            const float low = nd_lowest_on_wave(A, n, j, A.ds_c, who, lane);
+                            if (who == ND_NONE || !(st.slope > low)) { if (lane == 0) { sh_ok = 0u; sh_flag = 0u; } }
                             else {
-                                const RsGive gv = rs_down_cpu(A, who);
-                                remember(who);
-                                sh_per_v = nd_cpl(A, A.st.ci[who]) - nd_cpl(A, A.st.ci[who] - 1u);
-                                sh_v = who; sh_flag = 1u;
-                                sh_lost = sh_lost + gv.loss;
-                                A.st.ci[who] -= 1u;
-                                rs_refresh_give(A, who);
-                                sh_shrinks += 1u;
+                                const int32_t gi0 = A.st.gi[who];
+                                const uint32_t ci0 = A.st.ci[who];
+                                const uint32_t so = A.X.tb.seg_off[who], ns = A.X.tb.seg_off[who + 1] - so;
+                                const RsShrunk sk = rs_shrink_wave(A, who, so, ns, 1, gi0, ci0, lane);
+                                if (lane == 0) {
+                                    remember(who);
+                                    sh_per_v = nd_cpl(A, ci0) - nd_cpl(A, ci0 - 1u);
+                                    sh_v = who; sh_flag = 1u;
+                                    sh_lost = sh_lost + sk.gv.loss;
+                                    A.st.ci[who] = sk.ci;
+                                    A.ds_g[who] = sk.ds_g; A.ds_c[who] = sk.ds_c;
+                                    sh_shrinks += 1u;
+                                }
                             }
                         }
                     }
@@ -475,7 +570,7 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
             const uint32_t go = sh_go;
             if (go) {
                 const uint32_t n_changed = sh_touched + 1u;      // a wavefront per job whose state changed
-                for (uint32_t i = wave; i < n_changed; i += ND_WAVES) nd_refresh(A, i < sh_touched ? A.touched[i] : j, lane, 64);
+                for (uint32_t i = wave; i < n_changed; i += ND_WAVES) nd_refresh_wave(A, i < sh_touched ? A.touched[i] : j, lane);
             } else {
                 restore_nodes();
             }
