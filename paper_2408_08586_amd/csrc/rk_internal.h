@@ -26,6 +26,7 @@ struct rk_ctx {
     hipEvent_t sim_ev[2];                   // ... ordered after and before the context's stream with these
     bool fused_lds_raised;                  // fused kernel: its dynamic LDS limit has been raised for this context
     bool loop_lds_raised;                   // the Schedule loop over totals: likewise
+    bool nodes_lds_raised;                  // the Schedule loop over nodes: likewise
     unsigned char *static_scratch;          // this device's copy of the static scratch array (rk_allocate_static)
     bool place_lds_raised;                  // placement kernel: its dynamic LDS limit has been raised for this context
 };

@@ -39,8 +39,7 @@ struct NdCurves {
 };
 struct NdHold { int32_t *gi; uint32_t *ci; };
 
-struct NdArgs {
-    NdCurves X;
+struct NdBody {
     NdHold st;                       // what every job holds: index of its GPU count (-1 nothing), CPU level
     unsigned long long G;            // GPUs of the cluster
     uint32_t n_jobs, n_nodes, gpn, cpn;
@@ -74,6 +73,13 @@ struct NdArgs {
     uint32_t *stats;                 // may be null
     uint32_t *flags;                 // one word: non-zero when some job's parts are no placement
 };
+// What the device code sees: the body by value (registers), the table, grid and curves where the kernel arguments
+// hold them (a copy of the grid's level arrays would live in scratch memory).
+struct NdArgs : NdBody {
+    const NdCurves &X;
+    __device__ NdArgs(const NdBody &b, const NdCurves &x) : NdBody(b), X(x) {}
+};
+struct NdKernArgs { NdCurves X; NdBody b; };       // the kernels' argument
 
 __device__ __forceinline__ uint32_t nd_cpl(const NdArgs &A, uint32_t lvl) { return A.X.grid.cpu_levels[lvl]; }
 
@@ -193,7 +199,8 @@ __device__ __forceinline__ RsStep nd_cached_step(const NdArgs &A, uint32_t j, ui
 }
 
 // The nodes, all free and empty.
-__global__ void k_nd_init(NdArgs A) {
+__global__ void k_nd_init(NdKernArgs K) {
+    const NdArgs A(K.b, K.X);
     const uint32_t n = blockIdx.x * blockDim.x + threadIdx.x;
     if (n < A.n_nodes) { A.free_g[n] = A.gpn; A.free_c[n] = A.cpn; A.cnt[n] = 0u; }
     if (n == 0) A.flags[0] = 0u;
@@ -201,7 +208,8 @@ __global__ void k_nd_init(NdArgs A) {
 
 // Every job on its own, any number of workgroups: what it holds, whether it comes first, its parts booked on the
 // nodes (atomics; a node that ends up holding more than it has is seen by the main kernel), its cached slopes.
-__global__ void k_nd_prepare(NdArgs A) {
+__global__ void k_nd_prepare(NdKernArgs K) {
+    const NdArgs A(K.b, K.X);
     const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= A.n_jobs) return;
     const uint32_t N = A.n_nodes;
@@ -245,7 +253,17 @@ __global__ void k_nd_prepare(NdArgs A) {
     nd_refresh(A, j, 0, 1);
 }
 
-__global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
+__global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdKernArgs K) {
+    // what every job loses per GPU / CPU it gives, [2][n_jobs]: read at every look at a node's residents and at every
+    // look for the next job, so the kernel keeps them in LDS (k_nd_prepare left them in memory)
+    extern __shared__ float sh_ds[];
+    NdArgs A(K.b, K.X);
+    for (uint32_t j = threadIdx.x; j < A.n_jobs; j += ND_THREADS) {
+        sh_ds[j] = K.b.ds_g[j];
+        sh_ds[A.n_jobs + j] = K.b.ds_c[j];
+    }
+    A.ds_g = sh_ds;
+    A.ds_c = sh_ds + A.n_jobs;
     __shared__ RsStep sh_step;
     __shared__ float sh_lost, sh_wmin[ND_WAVES], sh_wc[ND_WAVES];
     __shared__ uint32_t sh_widx[ND_WAVES], sh_scan[ND_WAVES];
@@ -294,8 +312,21 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
         }
         return;
     }
-    auto keep_nodes = [&]() { for (uint32_t i = tid; i < A.nodes_words; i += ND_THREADS) A.keep_nodes[i] = A.free_g[i]; };
-    auto restore_nodes = [&]() { for (uint32_t i = tid; i < A.nodes_words; i += ND_THREADS) A.free_g[i] = A.keep_nodes[i]; };
+    // the node tables and their copy, four words at a time, two pieces in flight (nodes_words is a multiple of four)
+    auto copy_nodes = [&](uint32_t *to, const uint32_t *from) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(from);
+        uint4 *dst = reinterpret_cast<uint4 *>(to);
+        const uint32_t n4 = A.nodes_words / 4u;
+        for (uint32_t i = tid; i < n4; i += 2 * ND_THREADS) {
+            const uint4 a = src[i];
+            const bool two = i + ND_THREADS < n4;
+            const uint4 b = two ? src[i + ND_THREADS] : a;
+            dst[i] = a;
+            if (two) dst[i + ND_THREADS] = b;
+        }
+    };
+    auto keep_nodes = [&]() { copy_nodes(A.keep_nodes, A.free_g); };
+    auto restore_nodes = [&]() { copy_nodes(A.free_g, A.keep_nodes); };
     // first thread: remember job v as it is before this step changes it
     auto remember = [&](uint32_t v) {
         if (A.stamp[v] == sh_epoch) return;
@@ -626,7 +657,7 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdArgs A) {
             if (tid < RK_MAX_CPU_LEVELS) sh_take[tid] = 0ull;
             if (tid == 0) sh_free_c = 0ull;
             for (uint32_t res = 0; res < 2; ++res) {
-                const float *ds = res == 0 ? A.ds_g : A.ds_c;
+                const float *ds = sh_ds + res * J;
                 RsMin m = {INF, INF, ND_NONE};
                 for (uint32_t v0 = tid; v0 < J; v0 += 4 * ND_THREADS) {      // four loads in flight
                     float x[4];
@@ -930,7 +961,7 @@ int32_t rk_launch_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const rk_p
     const uint64_t gpus = (uint64_t)nodes->n_nodes * nodes->gpus_per_node;
     int32_t rc;
     const size_t n = J ? J : 1, N = nodes->n_nodes;
-    const size_t nodes_words = 3 * N + 2 * (size_t)gpus;
+    const size_t nodes_words = (3 * N + 2 * (size_t)gpus + 3) & ~(size_t)3;      // whole 16-byte pieces: the copy moves four words at a time
     uint32_t *w_nodes, *w_jobs;
     float *f_jobs;
     unsigned long long *u64;
@@ -938,9 +969,10 @@ int32_t rk_launch_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const rk_p
     if ((rc = rk_scratch(ctx, SL_ND_U32, (15 * n + 2) * sizeof(uint32_t), (void **)&w_jobs))) return rc;
     if ((rc = rk_scratch(ctx, SL_ND_F32, 10 * n * sizeof(float), (void **)&f_jobs))) return rc;
     if ((rc = rk_scratch(ctx, SL_ND_U64, 2 * n * sizeof(unsigned long long), (void **)&u64))) return rc;
-    NdArgs A;
-    A.X.ref_thr = ref_thr; A.X.tb = table_dev(table); A.X.grid = grid_dev(grid);
-    A.X.best_thr = best_thr; A.X.best_plan = best_plan; A.X.curve_thr = curve_thr;
+    NdKernArgs K;
+    NdBody &A = K.b;
+    K.X.ref_thr = ref_thr; K.X.tb = table_dev(table); K.X.grid = grid_dev(grid);
+    K.X.best_thr = best_thr; K.X.best_plan = best_plan; K.X.curve_thr = curve_thr;
     A.G = gpus;
     A.n_jobs = J; A.n_nodes = nodes->n_nodes; A.gpn = nodes->gpus_per_node; A.cpn = nodes->cpus_per_node;
     A.mem_gb = nodes->mem_per_node_gb;
@@ -962,13 +994,19 @@ int32_t rk_launch_reschedule_nodes(rk_ctx *ctx, const float *ref_thr, const rk_p
     A.sc = f_jobs + 5 * n; A.keep_ds = f_jobs + 6 * n; A.gain_g = f_jobs + 8 * n; A.gain_c = f_jobs + 9 * n;
     A.udc_g = u64; A.udc_c = u64 + n;
     A.assign = assign; A.place_off = place_off; A.entries = entries; A.total = total; A.stats = stats;
-    k_nd_init<<<(uint32_t)((N + 255) / 256), 256, 0, ctx->stream>>>(A);
+    k_nd_init<<<(uint32_t)((N + 255) / 256), 256, 0, ctx->stream>>>(K);
     RK_CHECK_LAUNCH(ctx, "k_nd_init");
     if (J > 0) {
-        k_nd_prepare<<<(J + 255) / 256, 256, 0, ctx->stream>>>(A);
+        k_nd_prepare<<<(J + 255) / 256, 256, 0, ctx->stream>>>(K);
         RK_CHECK_LAUNCH(ctx, "k_nd_prepare");
     }
-    k_reschedule_nodes<<<1, ND_THREADS, 0, ctx->stream>>>(A);
+    const size_t lds = (size_t)2 * n * sizeof(float);                           // at most 96 KiB
+    if (lds > 64 * 1024 && !ctx->nodes_lds_raised) {
+        RK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_reschedule_nodes),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 2 * RK_MAX_JOBS_PER_ROUND * sizeof(float)));
+        ctx->nodes_lds_raised = true;
+    }
+    k_reschedule_nodes<<<1, ND_THREADS, lds, ctx->stream>>>(K);
     RK_CHECK_LAUNCH(ctx, "k_reschedule_nodes");
     return RK_OK;
 }
