@@ -1480,13 +1480,14 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
     A.ds_c = sh_ds + A.n_jobs;
     __shared__ RsStep sh_step, sh_next[2];
     __shared__ unsigned long long sh_free[2], sh_avail[2], sh_held[2][RS_THREADS / 64];
-    __shared__ float sh_lost, sh_wmin[RS_THREADS / 64];
+    __shared__ float sh_lost;
+    __shared__ unsigned long long sh_pick_key[RS_THREADS / 64 + 1];
+    __shared__ uint32_t sh_pick_j[RS_THREADS / 64 + 1];
     __shared__ unsigned long long sh_wlow[RS_THREADS / 64];
     __shared__ uint32_t sh_below, sh_next_below;
     __shared__ uint32_t sh_widx[RS_THREADS / 64];
     __shared__ uint32_t sh_ok, sh_go, sh_touched, sh_epoch, sh_moves, sh_nb, sh_full, sh_shrinks, sh_undone;
     __shared__ RsMin sh_min[2], sh_wm[2][RS_THREADS / 64];
-    __shared__ float sh_wc[RS_THREADS / 64];
     constexpr uint32_t RS_LIST = 2048;                     // jobs with something to do, as the last look over all jobs found them
     __shared__ uint32_t sh_listed, sh_list_j[RS_LIST];
     __shared__ float sh_list_g[RS_LIST], sh_list_c[RS_LIST];
@@ -1744,24 +1745,10 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
                 if (best_j == 0xFFFFFFFFu || comes_before(kg, kc, j, best_g, best_c, best_j)) { best_g = kg; best_c = kc; best_j = j; }
             }
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const float og = __shfl_xor(best_g, off, 64), oc = __shfl_xor(best_c, off, 64);
-            const uint32_t oj = __shfl_xor(best_j, off, 64);
-            if (oj != 0xFFFFFFFFu && (best_j == 0xFFFFFFFFu || comes_before(og, oc, oj, best_g, best_c, best_j))) {
-                best_g = og; best_c = oc; best_j = oj;
-            }
+        {                                                    // the first of the threads' candidates in the order
+            const RsPick pick = rs_pick_first<RS_THREADS / 64>(best_g, best_c, best_j, lane, wave, sh_pick_key, sh_pick_j);
+            best_g = pick.g; best_c = pick.c; best_j = pick.j;
         }
-        if (lane == 0) { sh_wmin[wave] = best_g; sh_wc[wave] = best_c; sh_widx[wave] = best_j; }
-        __syncthreads();
-        best_g = sh_wmin[0]; best_c = sh_wc[0]; best_j = sh_widx[0];
-        for (uint32_t w = 1; w < RS_THREADS / 64; ++w) {
-            const uint32_t oj = sh_widx[w];
-            if (oj != 0xFFFFFFFFu && (best_j == 0xFFFFFFFFu || comes_before(sh_wmin[w], sh_wc[w], oj, best_g, best_c, best_j))) {
-                best_g = sh_wmin[w]; best_c = sh_wc[w]; best_j = oj;
-            }
-        }
-        __syncthreads();
         if (best_j == 0xFFFFFFFFu) break;
         if (tid == 0) sh_full += 1u;
         schedule_job(best_j);

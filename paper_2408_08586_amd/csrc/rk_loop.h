@@ -448,6 +448,56 @@ __device__ __forceinline__ uint32_t rs_ordered(float x) {
 }
 __device__ __forceinline__ float rs_unordered(uint32_t u) { return __uint_as_float((u & 0x80000000u) ? (u & 0x7FFFFFFFu) : ~u); }
 
+// Minimum of a word over the wavefront, in every lane; all 64 lanes must be active (as wave_max_u64_rows).
+template <int CTRL>
+__device__ __forceinline__ uint32_t rs_dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+}
+__device__ __forceinline__ uint32_t wave_min_u32_rows(uint32_t v) {
+    uint32_t o;
+    o = rs_dpp_u32<0xB1>(v);  v = o < v ? o : v;                // quad_perm [1,0,3,2]
+    o = rs_dpp_u32<0x4E>(v);  v = o < v ? o : v;                // quad_perm [2,3,0,1]
+    o = rs_dpp_u32<0x141>(v); v = o < v ? o : v;                // row_half_mirror
+    o = rs_dpp_u32<0x140>(v); v = o < v ? o : v;                // row_mirror
+    uint32_t m = 0xFFFFFFFFu;
+#pragma unroll
+    for (int r = 0; r < 64; r += 16) {
+        const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)v, r);
+        m = row < m ? row : m;
+    }
+    return m;
+}
+
+// The job that comes first in the loops' order (GPU slope, then CPU slope, both descending, then the lower index)
+// among the candidates of a workgroup's threads (j == 0xFFFFFFFF: a thread without one; slopes are not negative).
+// All threads call and all get the result.  The slopes travel as one key of two words that order like them, the
+// wavefronts reduce by DPP, the first one reduces their results; sh_key and sh_j hold WAVES + 1 entries.
+struct RsPick { float g, c; uint32_t j; };
+template <int WAVES>
+__device__ __forceinline__ RsPick rs_pick_first(float g, float c, uint32_t j, uint32_t lane, uint32_t wave,
+                                                unsigned long long *sh_key, uint32_t *sh_j) {
+    const uint32_t NONE = 0xFFFFFFFFu;
+    const unsigned long long key = j == NONE ? 0ull : ((unsigned long long)rs_ordered(g) << 32) | rs_ordered(c);
+    const unsigned long long top = wave_max_u64_rows(key);
+    const uint32_t first = wave_min_u32_rows(j != NONE && key == top ? j : NONE);
+    if (lane == 0) { sh_key[wave] = top; sh_j[wave] = first; }
+    rs_lds_barrier();
+    if (wave == 0) {
+        const unsigned long long k2 = lane < WAVES ? sh_key[lane] : 0ull;
+        const uint32_t j2 = lane < WAVES ? sh_j[lane] : NONE;
+        const unsigned long long t2 = wave_max_u64_rows(k2);
+        const uint32_t f2 = wave_min_u32_rows(j2 != NONE && k2 == t2 ? j2 : NONE);
+        if (lane == 0) { sh_key[WAVES] = t2; sh_j[WAVES] = f2; }
+    }
+    rs_lds_barrier();
+    RsPick out;
+    const unsigned long long t = sh_key[WAVES];
+    out.j = sh_j[WAVES];
+    out.g = rs_unordered((uint32_t)(t >> 32));
+    out.c = rs_unordered((uint32_t)t);
+    return out;
+}
+
 // the two lowest values of ds over all jobs and the job of the lowest (lower index among equal values)
 struct RsMin { float m1, m2; uint32_t i1; };
 __device__ __forceinline__ RsMin rs_min_merge(const RsMin &a, const RsMin &b) {

@@ -265,7 +265,9 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdKernArgs K) {
     A.ds_g = sh_ds;
     A.ds_c = sh_ds + A.n_jobs;
     __shared__ RsStep sh_step;
-    __shared__ float sh_lost, sh_wmin[ND_WAVES], sh_wc[ND_WAVES];
+    __shared__ float sh_lost;
+    __shared__ unsigned long long sh_pick_key[ND_WAVES + 1];
+    __shared__ uint32_t sh_pick_j[ND_WAVES + 1];
     __shared__ uint32_t sh_widx[ND_WAVES], sh_scan[ND_WAVES];
     __shared__ uint32_t sh_lack, sh_ok, sh_go, sh_touched, sh_epoch, sh_moves, sh_full, sh_shrinks, sh_undone;
     __shared__ uint32_t sh_vnode, sh_next, sh_v, sh_rest, sh_per_v, sh_flag, sh_np, sh_bad, sh_fit, sh_done, sh_ask;
@@ -730,24 +732,10 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdKernArgs K) {
                 if (best_j == ND_NONE || comes_before(kg[k], kc[k], j, best_g, best_c, best_j)) { best_g = kg[k]; best_c = kc[k]; best_j = j; }
             }
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const float og = __shfl_xor(best_g, off, 64), oc = __shfl_xor(best_c, off, 64);
-            const uint32_t oj = __shfl_xor(best_j, off, 64);
-            if (oj != ND_NONE && (best_j == ND_NONE || comes_before(og, oc, oj, best_g, best_c, best_j))) {
-                best_g = og; best_c = oc; best_j = oj;
-            }
+        {                                                    // the first of the threads' candidates in the order
+            const RsPick pick = rs_pick_first<ND_WAVES>(best_g, best_c, best_j, lane, wave, sh_pick_key, sh_pick_j);
+            best_g = pick.g; best_c = pick.c; best_j = pick.j;
         }
-        if (lane == 0) { sh_wmin[wave] = best_g; sh_wc[wave] = best_c; sh_widx[wave] = best_j; }
-        __syncthreads();
-        best_g = sh_wmin[0]; best_c = sh_wc[0]; best_j = sh_widx[0];
-        for (uint32_t w = 1; w < ND_WAVES; ++w) {
-            const uint32_t oj = sh_widx[w];
-            if (oj != ND_NONE && (best_j == ND_NONE || comes_before(sh_wmin[w], sh_wc[w], oj, best_g, best_c, best_j))) {
-                best_g = sh_wmin[w]; best_c = sh_wc[w]; best_j = oj;
-            }
-        }
-        __syncthreads();
         if (best_j == ND_NONE) break;
         if (tid == 0) sh_full += 1u;
         schedule_job(best_j);
