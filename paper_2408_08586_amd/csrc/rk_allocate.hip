@@ -1516,16 +1516,15 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
 
     // ScheduleJob(j); the same code path for all threads
     auto schedule_job = [&](uint32_t j) {
-        bool have_next = false;                            // sh_next holds the job's next steps (from the refresh after a commit)
+        // The job's next steps (GPUs, CPUs) and whether it is below its floor are kept in LDS: found here for the job as
+        // it is (its cached values are written again, unchanged), and again by the refresh after every committed step.
+        if (wave == 0) rs_refresh_wave(A, j, lane, sh_next, &sh_next_below, true);
+        rs_lds_barrier();
         for (uint32_t res = 0; res < 2; ++res) {
             for (;;) {
                 if (wave == 0) {
-                    const RsStep st = have_next ? sh_next[res] : (res == 0 ? rs_up_gpu(A, j, lane, 64) : rs_up_cpu(A, j, lane, 64));
-                    bool below = false;                     // below its floor: it takes at a loss
-                    if (res == 0) {
-                        if (have_next) below = sh_next_below != 0u;
-                        else { const int32_t fl = rs_fl_s(A, j); below = fl >= 0 && A.st.gi[j] < fl; }
-                    }
+                    const RsStep st = sh_next[res];
+                    const bool below = res == 0 && sh_next_below != 0u;     // below its floor: it takes at a loss
                     if (lane == 0) {
                         sh_step = st;
                         sh_below = below ? 1u : 0u;
@@ -1616,7 +1615,6 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
                     const uint32_t n_touched = sh_touched;           // a wavefront per job
                     for (uint32_t i = wave; i < n_touched + 1u; i += RS_THREADS / 64)
                         rs_refresh_wave(A, i < n_touched ? A.touched[i] : j, lane, sh_next, &sh_next_below, i >= n_touched);
-                    have_next = true;
                 }
                 __syncthreads();
                 if (!go) break;
