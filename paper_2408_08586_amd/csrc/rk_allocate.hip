@@ -1487,7 +1487,9 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
     __shared__ uint32_t sh_below, sh_next_below;
     __shared__ uint32_t sh_widx[RS_THREADS / 64];
     __shared__ uint32_t sh_ok, sh_go, sh_touched, sh_epoch, sh_moves, sh_nb, sh_full, sh_shrinks, sh_undone;
-    __shared__ RsMin sh_min[2], sh_wm[2][RS_THREADS / 64];
+    __shared__ RsMin sh_min[2];
+    __shared__ unsigned long long sh_two_k[2 * (RS_THREADS / 64 + 1)];
+    __shared__ uint32_t sh_two_s[2 * (RS_THREADS / 64 + 1)];
     constexpr uint32_t RS_LIST = 2048;                     // jobs with something to do, as the last look over all jobs found them
     __shared__ uint32_t sh_listed, sh_list_j[RS_LIST];
     __shared__ float sh_list_g[RS_LIST], sh_list_c[RS_LIST];
@@ -1669,33 +1671,9 @@ __global__ __launch_bounds__(RS_THREADS) void k_reschedule(RsArgs B) {
         moves_seen = sh_moves;
         __syncthreads();
         if (fresh) {                                      // otherwise the lowest slopes are what they were
-            for (uint32_t res = 0; res < 2; ++res) {
-                const float *ds = sh_ds + res * J;
-                RsMin m = {INF, INF, 0xFFFFFFFFu};
-                for (uint32_t v0 = tid; v0 < J; v0 += 4 * RS_THREADS) {      // four loads in flight
-                    float x[4];
-#pragma unroll
-                    for (uint32_t k = 0; k < 4; ++k) x[k] = v0 + k * RS_THREADS < J ? ds[v0 + k * RS_THREADS] : INF;
-#pragma unroll
-                    for (uint32_t k = 0; k < 4; ++k) {
-                        const RsMin one = {x[k], INF, v0 + k * RS_THREADS};
-                        m = rs_min_merge(m, one);
-                    }
-                }
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) {
-                    RsMin o;
-                    o.m1 = __shfl_xor(m.m1, off, 64); o.m2 = __shfl_xor(m.m2, off, 64); o.i1 = __shfl_xor(m.i1, off, 64);
-                    m = rs_min_merge(m, o);
-                }
-                if (lane == 0) sh_wm[res][wave] = m;
-            }
-            __syncthreads();
-            if (tid < 2) {
-                RsMin m = sh_wm[tid][0];
-                for (uint32_t w = 1; w < RS_THREADS / 64; ++w) m = rs_min_merge(m, sh_wm[tid][w]);
-                sh_min[tid] = m;
-            }
+            RsMin two[2];
+            rs_two_lowest<RS_THREADS / 64, RS_THREADS>(sh_ds, J, tid, lane, wave, sh_two_k, sh_two_s, two);
+            if (tid == 0) { sh_min[0] = two[0]; sh_min[1] = two[1]; }
             if (tid == 2) sh_listed = 0u;
         }
         __syncthreads();

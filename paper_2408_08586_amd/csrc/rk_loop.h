@@ -498,13 +498,71 @@ __device__ __forceinline__ RsPick rs_pick_first(float g, float c, uint32_t j, ui
     return out;
 }
 
-// the two lowest values of ds over all jobs and the job of the lowest (lower index among equal values)
+// The two lowest give-slopes over all jobs, per resource, and the job of the lowest (the lower index among equal
+// values; none: 0xFFFFFFFF with both values infinite).  ds holds the slopes [2][n_jobs] (LDS).  All THREADS threads of
+// the workgroup call and all get the result in out[0] (GPUs) and out[1] (CPUs).  Every thread keeps the two lowest
+// of its own jobs; the lowest goes through a DPP minimum of packed keys (slope as a word that orders like it, job),
+// the second lowest is the minimum of what the threads hold once the lowest's owner puts its own second in.
+// sh_k and sh_s hold 2 * (WAVES + 1) entries each.
 struct RsMin { float m1, m2; uint32_t i1; };
-__device__ __forceinline__ RsMin rs_min_merge(const RsMin &a, const RsMin &b) {
-    RsMin r;
-    const bool a_first = a.m1 < b.m1 || (a.m1 == b.m1 && a.i1 <= b.i1);
-    const RsMin &lo = a_first ? a : b, &hi = a_first ? b : a;
-    r.m1 = lo.m1; r.i1 = lo.i1;
-    r.m2 = lo.m2 < hi.m1 ? lo.m2 : hi.m1;
-    return r;
+template <int WAVES, int THREADS>
+__device__ __forceinline__ void rs_two_lowest(const float *ds, uint32_t n_jobs, uint32_t tid, uint32_t lane, uint32_t wave,
+                                              unsigned long long *sh_k, uint32_t *sh_s, RsMin (&out)[2]) {
+    const float INF = __int_as_float(0x7F800000);
+    const uint32_t NONE = 0xFFFFFFFFu;
+    float a[2] = {INF, INF}, b[2] = {INF, INF};
+    uint32_t ia[2] = {NONE, NONE};
+    for (uint32_t v0 = tid; v0 < n_jobs; v0 += 4 * THREADS) {            // four loads per resource in flight
+        float x[2][4];
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) {
+            const uint32_t v = v0 + k * THREADS;
+            x[0][k] = v < n_jobs ? ds[v] : INF;
+            x[1][k] = v < n_jobs ? ds[n_jobs + v] : INF;
+        }
+#pragma unroll
+        for (uint32_t r = 0; r < 2; ++r)
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {                           // ascending jobs: the lower one stays among equals
+                const float y = x[r][k];
+                if (y < a[r]) { b[r] = a[r]; a[r] = y; ia[r] = v0 + k * THREADS; }
+                else if (y < b[r]) b[r] = y;
+            }
+    }
+#pragma unroll
+    for (uint32_t r = 0; r < 2; ++r) {
+        const unsigned long long key = ia[r] == NONE ? ~0ull : ((unsigned long long)rs_ordered(a[r]) << 32) | ia[r];
+        const unsigned long long w = wave_min_u64_rows(key);
+        if (lane == 0) sh_k[r * (WAVES + 1) + wave] = w;
+    }
+    rs_lds_barrier();
+    if (wave == 0) {
+#pragma unroll
+        for (uint32_t r = 0; r < 2; ++r) {
+            const unsigned long long w = wave_min_u64_rows(lane < WAVES ? sh_k[r * (WAVES + 1) + lane] : ~0ull);
+            if (lane == 0) sh_k[r * (WAVES + 1) + WAVES] = w;
+        }
+    }
+    rs_lds_barrier();
+#pragma unroll
+    for (uint32_t r = 0; r < 2; ++r) {
+        const unsigned long long low = sh_k[r * (WAVES + 1) + WAVES];
+        out[r].i1 = low == ~0ull ? NONE : (uint32_t)low;
+        out[r].m1 = low == ~0ull ? INF : rs_unordered((uint32_t)(low >> 32));
+        // what this thread holds beside the lowest: its own lowest, or its second when the lowest is its own
+        const float mine = (ia[r] != NONE && ia[r] == out[r].i1) ? b[r] : a[r];
+        const uint32_t w = wave_min_u32_rows(rs_ordered(mine));
+        if (lane == 0) sh_s[r * (WAVES + 1) + wave] = w;
+    }
+    rs_lds_barrier();
+    if (wave == 0) {
+#pragma unroll
+        for (uint32_t r = 0; r < 2; ++r) {
+            const uint32_t w = wave_min_u32_rows(lane < WAVES ? sh_s[r * (WAVES + 1) + lane] : rs_ordered(INF));
+            if (lane == 0) sh_s[r * (WAVES + 1) + WAVES] = w;
+        }
+    }
+    rs_lds_barrier();
+#pragma unroll
+    for (uint32_t r = 0; r < 2; ++r) out[r].m2 = rs_unordered(sh_s[r * (WAVES + 1) + WAVES]);
 }

@@ -272,7 +272,9 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdKernArgs K) {
     __shared__ uint32_t sh_lack, sh_ok, sh_go, sh_touched, sh_epoch, sh_moves, sh_full, sh_shrinks, sh_undone;
     __shared__ uint32_t sh_vnode, sh_next, sh_v, sh_rest, sh_per_v, sh_flag, sh_np, sh_bad, sh_fit, sh_done, sh_ask;
     __shared__ unsigned long long sh_take[RK_MAX_CPU_LEVELS], sh_free_c;
-    __shared__ RsMin sh_min[2], sh_wm[2][ND_WAVES];
+    __shared__ RsMin sh_min[2];
+    __shared__ unsigned long long sh_two_k[2 * (ND_WAVES + 1)];
+    __shared__ uint32_t sh_two_s[2 * (ND_WAVES + 1)];
     __shared__ double sh_sum[ND_WAVES];
     __shared__ float sh_mem[RK_MAX_NODES];                  // memory of the nodes: sums of wishes, then what is left
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -658,32 +660,10 @@ __global__ __launch_bounds__(ND_THREADS) void k_reschedule_nodes(NdKernArgs K) {
         if (fresh) {
             if (tid < RK_MAX_CPU_LEVELS) sh_take[tid] = 0ull;
             if (tid == 0) sh_free_c = 0ull;
-            for (uint32_t res = 0; res < 2; ++res) {
-                const float *ds = sh_ds + res * J;
-                RsMin m = {INF, INF, ND_NONE};
-                for (uint32_t v0 = tid; v0 < J; v0 += 4 * ND_THREADS) {      // four loads in flight
-                    float x[4];
-#pragma unroll
-                    for (uint32_t k = 0; k < 4; ++k) x[k] = v0 + k * ND_THREADS < J ? ds[v0 + k * ND_THREADS] : INF;
-#pragma unroll
-                    for (uint32_t k = 0; k < 4; ++k) {
-                        const RsMin one = {x[k], INF, v0 + k * ND_THREADS};
-                        m = rs_min_merge(m, one);
-                    }
-                }
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) {
-                    RsMin o;
-                    o.m1 = __shfl_xor(m.m1, off, 64); o.m2 = __shfl_xor(m.m2, off, 64); o.i1 = __shfl_xor(m.i1, off, 64);
-                    m = rs_min_merge(m, o);
-                }
-                if (lane == 0) sh_wm[res][wave] = m;
-            }
-            __syncthreads();
-            if (tid < 2) {
-                RsMin m = sh_wm[tid][0];
-                for (uint32_t w = 1; w < ND_WAVES; ++w) m = rs_min_merge(m, sh_wm[tid][w]);
-                sh_min[tid] = m;
+            {
+                RsMin two[2];
+                rs_two_lowest<ND_WAVES, ND_THREADS>(sh_ds, J, tid, lane, wave, sh_two_k, sh_two_s, two);
+                if (tid == 0) { sh_min[0] = two[0]; sh_min[1] = two[1]; }
             }
             {                                                    // what the nodes can give at every CPU level
                 unsigned long long fc = 0;
