@@ -140,10 +140,25 @@ __device__ __forceinline__ void residual(const Run &R, const double (&x)[NP], do
     J[TH_CONST] = w * G[TH_CONST];
 }
 
+// Sum over the group of W lanes, the same bits in every lane (both partners of every step add the same two values).
+// Inside a row of 16 lanes the partners are reached by data-parallel-primitive moves (neighbour, neighbour pair,
+// mirrored halves of 8, mirrored halves of 16), beyond it by shuffles; all 64 lanes must be active.
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const uint32_t lo = (uint32_t)b, hi = (uint32_t)(b >> 32);
+    const uint32_t l2 = (uint32_t)__builtin_amdgcn_update_dpp((int)lo, (int)lo, CTRL, 0xF, 0xF, false);
+    const uint32_t h2 = (uint32_t)__builtin_amdgcn_update_dpp((int)hi, (int)hi, CTRL, 0xF, 0xF, false);
+    return __longlong_as_double((long long)(((unsigned long long)h2 << 32) | l2));
+}
 template <int W>
 __device__ __forceinline__ double group_sum(double v) {
+    if (W >= 2) v += dpp_f64<0xB1>(v);                      // quad_perm [1,0,3,2]
+    if (W >= 4) v += dpp_f64<0x4E>(v);                      // quad_perm [2,3,0,1]
+    if (W >= 8) v += dpp_f64<0x141>(v);                     // row_half_mirror
+    if (W >= 16) v += dpp_f64<0x140>(v);                    // row_mirror
 #pragma unroll
-    for (int off = W / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, W);
+    for (int off = 16; off < W; off <<= 1) v += __shfl_xor(v, off, 64);
     return v;
 }
 
@@ -300,8 +315,13 @@ __global__ __launch_bounds__(FIT_THREADS) void k_fit(FitArgs A) {
                 moved = fmax(moved, fabs(de[i]) * sqrt(fmax(D[i], 0.0)));
             }
             const bool small = ok && moved <= XTOL * scale;
-            Normal trial;
-            evaluate(xn, trial);                              // every lane of the wavefront, finished groups too
+            // the trial point: residual and derivatives of the lane's run, and the group's error there (every lane of the
+            // wavefront, finished groups too); its normal equations replace the current ones below, where it is accepted
+            double res_t = 0.0, J_t[NP];
+#pragma unroll
+            for (int i = 0; i < NP; ++i) J_t[i] = 0.0;
+            if (has_run) residual(R, xn, res_t, J_t);
+            const double F_t = group_sum<W>(res_t * res_t);
             double pred = 0.0;
 #pragma unroll
             for (int i = 0; i < NP; ++i) {
@@ -311,20 +331,31 @@ __global__ __launch_bounds__(FIT_THREADS) void k_fit(FitArgs A) {
                 pred -= de[i] * (2.0 * cur.g[i] + Ad);
             }
             const bool go = active && !converged && !small;
-            const bool accept = go && ok && trial.F < cur.F && pred > 0.0;
+            const bool accept = go && ok && F_t < cur.F && pred > 0.0;
             if (accept) {
-                const double rho = (cur.F - trial.F) / pred, q = 2.0 * rho - 1.0;
+                const double rho = (cur.F - F_t) / pred, q = 2.0 * rho - 1.0;
                 lam = fmax(lam * fmax(1.0 / 3.0, 1.0 - q * q * q), 1e-15);
                 nu = 2.0;
 #pragma unroll
                 for (int i = 0; i < NP; ++i) x[i] = xn[i];
-                cur = trial;
             } else if (go) {
                 lam *= nu;
                 nu *= 2.0;
                 if (lam > 1e20) active = false;
             }
             if (converged || small) active = false;
+            // (the sums run in every lane; a group keeps its own where it did not accept)
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+#pragma unroll
+                for (int j = i; j < NP; ++j) {
+                    const double a = group_sum<W>(J_t[i] * J_t[j]);
+                    cur.A[tri(i, j)] = accept ? a : cur.A[tri(i, j)];
+                }
+                const double g = group_sum<W>(J_t[i] * res_t);
+                cur.g[i] = accept ? g : cur.g[i];
+            }
+            cur.F = accept ? F_t : cur.F;
         }
         if (enabled && cur.F < best_F) {
             best_F = cur.F;
